@@ -1,0 +1,176 @@
+"""CPU oracle of the Lynx MoE decode layer -- TEST INFRASTRUCTURE, not the product.
+
+Thin ctypes wrapper around ``lynx_oracle.c`` (plain C, fp64).  Only the tests, the smoke check and
+the benchmark's ``cpu_baseline`` leg may import this package; the HIP path never does, and this
+package never imports the HIP path.  What each function computes, and which passage of the paper
+(arXiv 2411.08982) it follows, is stated in the C file.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from ctypes import POINTER, c_double, c_float, c_int, c_int32, c_uint16, c_uint64
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "lynx_oracle.c")
+_LIB = os.path.join(_HERE, "liblynx_oracle.so")
+
+OK = 0
+ERR_INVALID_ARG = -1
+ERR_UNSUPPORTED = -2
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (no fast-math, no FMA contraction).  Returns the library path."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-ffp-contract=off", "-fno-fast-math", "-Wall", "-shared",
+               "-fPIC", _SRC, "-o", _LIB, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        u16p, f32p, f64p, i32p, u64p = (POINTER(c_uint16), POINTER(c_float), POINTER(c_double), POINTER(c_int32),
+                                        POINTER(c_uint64))
+        lib.orc_num_threads.restype = c_int
+        lib.orc_route.argtypes = [u16p, f32p, f32p, c_int, c_int, c_int, c_int, f32p, i32p, f64p, f64p]
+        lib.orc_affinity_bin.argtypes = [f32p, i32p, c_int, c_int, c_int, c_float, c_int, c_int, i32p, f64p, i32p,
+                                         i32p, i32p, i32p, i32p, u64p, i32p]
+        lib.orc_permute.argtypes = [i32p, c_int, c_int, c_int, i32p, i32p, i32p, i32p]
+        lib.orc_moe_ffn.argtypes = [u16p, u16p, u16p, u16p, u16p, u16p, u16p, c_int, c_int, i32p, f64p, c_int, c_int,
+                                    c_int, c_int, c_int, f64p]
+        for f in (lib.orc_route, lib.orc_affinity_bin, lib.orc_permute, lib.orc_moe_ffn):
+            f.restype = c_int
+        _lib = lib
+    return _lib
+
+
+class OracleError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        super().__init__(f"{where} returned {code}")
+        self.code = code
+
+
+def _p(a, ctype):
+    if a is None:
+        return ctypes.cast(None, POINTER(ctype))
+    return a.ctypes.data_as(POINTER(ctype))
+
+
+def _arr(a, dtype):
+    a = np.ascontiguousarray(a, dtype=dtype)
+    return a
+
+
+def num_threads() -> int:
+    return int(_load().orc_num_threads())
+
+
+def route(x_bf16, Wr, bias, k):
+    """x_bf16 [T,H] uint16 (bf16 bits), Wr [N,H] f32, bias [N] f32 or None.
+    Returns dict(logits f32 [T,N], idx i32 [T,k], gate f64 [T,k], psum f64 [T])."""
+    x = _arr(x_bf16, np.uint16)
+    Wr = _arr(Wr, np.float32)
+    T, H = x.shape
+    N = Wr.shape[0]
+    assert Wr.shape[1] == H
+    b = None if bias is None else _arr(bias, np.float32)
+    logits = np.zeros((T, N), np.float32)
+    idx = np.zeros((T, k), np.int32)
+    gate = np.zeros((T, k), np.float64)
+    psum = np.zeros((T,), np.float64)
+    rc = _load().orc_route(_p(x, c_uint16), _p(Wr, c_float), _p(b, c_float), T, H, N, k, _p(logits, c_float),
+                           _p(idx, c_int32), _p(gate, c_double), _p(psum, c_double))
+    if rc != OK:
+        raise OracleError(rc, "orc_route")
+    return dict(logits=logits, idx=idx, gate=gate, psum=psum)
+
+
+def affinity_bin(logits, topk_idx, alpha, beta, enable=1):
+    """logits [T,N] f32, topk_idx [T,k] i32.  Returns dict with new_idx, new_gate (f64), cnt_before,
+    cnt_after, bin_hist [N,beta], num_active [2], and the diagnostics q [T,N], score [N] (uint64),
+    active [N] (0/1)."""
+    z = _arr(logits, np.float32)
+    idx = _arr(topk_idx, np.int32)
+    T, N = z.shape
+    k = idx.shape[1]
+    assert idx.shape[0] == T
+    nb = max(int(beta), 1)
+    new_idx = np.zeros((T, k), np.int32)
+    new_gate = np.zeros((T, k), np.float64)
+    cnt_before = np.zeros((N,), np.int32)
+    cnt_after = np.zeros((N,), np.int32)
+    bin_hist = np.zeros((N, nb), np.int32)
+    num_active = np.zeros((2,), np.int32)
+    q = np.zeros((T, N), np.int32)
+    score = np.zeros((N,), np.uint64)
+    active = np.zeros((N,), np.int32)
+    rc = _load().orc_affinity_bin(_p(z, c_float), _p(idx, c_int32), T, N, k, float(alpha), int(beta), int(enable),
+                                  _p(new_idx, c_int32), _p(new_gate, c_double), _p(cnt_before, c_int32),
+                                  _p(cnt_after, c_int32), _p(bin_hist, c_int32), _p(num_active, c_int32),
+                                  _p(q, c_int32), _p(score, c_uint64), _p(active, c_int32))
+    if rc != OK:
+        raise OracleError(rc, "orc_affinity_bin")
+    return dict(new_idx=new_idx, new_gate=new_gate, cnt_before=cnt_before, cnt_after=cnt_after, bin_hist=bin_hist,
+                num_active=num_active, q=q, score=score, active=active)
+
+
+def permute(idx, N):
+    """idx [T,k] i32.  Returns dict(offsets [N+1], perm [T*k], active [N], num_active [1])."""
+    idx = _arr(idx, np.int32)
+    T, k = idx.shape
+    offsets = np.zeros((N + 1,), np.int32)
+    perm = np.zeros((T * k,), np.int32)
+    active = np.zeros((N,), np.int32)
+    num_active = np.zeros((1,), np.int32)
+    rc = _load().orc_permute(_p(idx, c_int32), T, N, k, _p(offsets, c_int32), _p(perm, c_int32), _p(active, c_int32),
+                             _p(num_active, c_int32))
+    if rc != OK:
+        raise OracleError(rc, "orc_permute")
+    return dict(offsets=offsets, perm=perm, active=active, num_active=num_active)
+
+
+def moe_ffn(x_bf16, Wg, Wu, Wd, idx, gate, Sg=None, Su=None, Sd=None):
+    """x_bf16 [T,H]; Wg, Wu [N,F,H]; Wd [N,H,F]; optional shared Sg, Su [S,Fs,H], Sd [S,H,Fs] (all uint16
+    bf16 bits); idx [T,k] i32; gate [T,k] f64.  Returns y [T,H] f64."""
+    x = _arr(x_bf16, np.uint16)
+    Wg, Wu, Wd = _arr(Wg, np.uint16), _arr(Wu, np.uint16), _arr(Wd, np.uint16)
+    idx = _arr(idx, np.int32)
+    gate = _arr(gate, np.float64)
+    T, H = x.shape
+    N, F, H2 = Wg.shape
+    assert H2 == H and Wu.shape == (N, F, H) and Wd.shape == (N, H, F)
+    k = idx.shape[1]
+    assert idx.shape == (T, k) and gate.shape == (T, k)
+    if Sg is not None and len(Sg) > 0:
+        Sg, Su, Sd = _arr(Sg, np.uint16), _arr(Su, np.uint16), _arr(Sd, np.uint16)
+        S, Fs, _ = Sg.shape
+        assert Su.shape == (S, Fs, H) and Sd.shape == (S, H, Fs)
+    else:
+        Sg = Su = Sd = None
+        S, Fs = 0, 0
+    y = np.zeros((T, H), np.float64)
+    rc = _load().orc_moe_ffn(_p(x, c_uint16), _p(Wg, c_uint16), _p(Wu, c_uint16), _p(Wd, c_uint16), _p(Sg, c_uint16),
+                             _p(Su, c_uint16), _p(Sd, c_uint16), S, Fs, _p(idx, c_int32), _p(gate, c_double), T, H, F,
+                             N, k, _p(y, c_double))
+    if rc != OK:
+        raise OracleError(rc, "orc_moe_ffn")
+    return y
+
+
+def moe_layer(x_bf16, Wr, bias, Wg, Wu, Wd, k, alpha, beta, enable=1, Sg=None, Su=None, Sd=None):
+    """The whole decode step: route -> affinity_bin -> permute -> FFN + combine."""
+    r = route(x_bf16, Wr, bias, k)
+    a = affinity_bin(r["logits"], r["idx"], alpha, beta, enable)
+    p = permute(a["new_idx"], Wr.shape[0])
+    y = moe_ffn(x_bf16, Wg, Wu, Wd, a["new_idx"], a["new_gate"], Sg, Su, Sd)
+    return dict(route=r, bin=a, permute=p, y=y)

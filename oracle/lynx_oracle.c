@@ -1,0 +1,400 @@
+/*
+ * lynx_oracle.c -- TEST INFRASTRUCTURE, NOT THE PRODUCT.
+ *
+ * A plain, slow, obviously-correct CPU statement of what one batched MoE-layer decode step of
+ * Lynx (arXiv 2411.08982) computes: router logits, softmax and top-k (Sec. 2.1), AffinityBinning
+ * (Sec. 3.2.1), batch-wide expert scoring (Sec. 3.3.1), expert remapping (Sec. 3.4), token
+ * assignment / compaction / renormalisation (Sec. 4), and the grouped SwiGLU expert FFN with the
+ * gate-weighted combine that the remapper dispatches.
+ *
+ * Only tests, the smoke check and the benchmark's cpu_baseline leg may call this file.  It shares
+ * no code with the HIP path.  Floating point is fp64 except where a floating-point value decides
+ * an integer (top-k comparisons and the bin index): those are taken in fp32, the precision of the
+ * router logits, with exactly one rounded subtract and one rounded multiply.
+ *
+ * Where the paper gives prose only (it prints no formula for the pruning rule and no values for
+ * alpha and beta) the reading implemented here is written out step by step at each function.
+ *
+ * Pins (tests/test_oracle_*.py): library fp64 matmul / softmax / stable argsort for the plain
+ * steps; hand-worked 4x4 example; invariants the paper states (k distinct experts per token,
+ * remap onto already-active experts, top-1 of a confident token kept, invoked count never rises);
+ * closed-form special cases; exhaustive subset search on tiny batches.
+ * Parity unpinned against the paper: the values of alpha and beta (the paper prints none).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define ORC_OK 0
+#define ORC_ERR_INVALID_ARG (-1)
+#define ORC_ERR_UNSUPPORTED (-2)
+
+#define ORC_MAX_BETA 6
+
+static double bf16_to_f64(uint16_t b)
+{
+    uint32_t u = (uint32_t)b << 16;
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return (double)f;
+}
+
+int orc_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* k largest entries of z among the allowed experts, in descending order; equal values go to the
+ * lower expert index.  allowed == NULL means every expert.  Returns how many were found. */
+static int topk_select(const float *z, const uint8_t *allowed, int N, int k, int32_t *out)
+{
+    uint8_t *taken = (uint8_t *)calloc((size_t)N, 1);
+    int found = 0;
+    for (int j = 0; j < k; ++j) {
+        int best = -1;
+        for (int e = 0; e < N; ++e) {
+            if (taken[e] || (allowed && !allowed[e])) continue;
+            if (best < 0 || z[e] > z[best]) best = e; /* strict: ties keep the lower index */
+        }
+        if (best < 0) break;
+        taken[best] = 1;
+        out[found++] = best;
+    }
+    free(taken);
+    return found;
+}
+
+/* Gates of a selection: softmax over the k selected logits only (Sec. 4, "renormalizes weights"). */
+static void gates_of_selection(const float *z, const int32_t *sel, int k, double *gate)
+{
+    double zmax = (double)z[sel[0]];
+    for (int j = 1; j < k; ++j)
+        if ((double)z[sel[j]] > zmax) zmax = (double)z[sel[j]];
+    double den = 0.0;
+    for (int j = 0; j < k; ++j) den += exp((double)z[sel[j]] - zmax);
+    for (int j = 0; j < k; ++j) gate[j] = exp((double)z[sel[j]] - zmax) / den;
+}
+
+/*
+ * Router (Sec. 2.1): z[t,e] = sum_h x[t,h] * Wr[e,h] + bias[e], accumulated in fp64 and rounded
+ * once to fp32; p = softmax(z); the k experts of largest z per token (descending, ties to the
+ * lower index); psum = sum of the selected softmax probabilities; gates = the selected
+ * probabilities renormalised to sum 1.
+ */
+int orc_route(const uint16_t *x_bf16, const float *Wr, const float *bias, int T, int H, int N, int k,
+              float *logits, int32_t *topk_idx, double *topk_gate, double *topk_psum)
+{
+    if (T < 0 || H <= 0 || N <= 0 || k <= 0) return ORC_ERR_INVALID_ARG;
+    if (k > N) return ORC_ERR_UNSUPPORTED;
+    for (int t = 0; t < T; ++t) {
+        float *z = logits + (size_t)t * N;
+        for (int e = 0; e < N; ++e) {
+            double acc = 0.0;
+            for (int h = 0; h < H; ++h)
+                acc += bf16_to_f64(x_bf16[(size_t)t * H + h]) * (double)Wr[(size_t)e * H + h];
+            if (bias) acc += (double)bias[e];
+            z[e] = (float)acc;
+        }
+        int32_t *sel = topk_idx + (size_t)t * k;
+        topk_select(z, NULL, N, k, sel);
+        double zmax = (double)z[sel[0]], den = 0.0, num = 0.0;
+        for (int e = 0; e < N; ++e) den += exp((double)z[e] - zmax);
+        for (int j = 0; j < k; ++j) num += exp((double)z[sel[j]] - zmax);
+        topk_psum[t] = num / den;
+        gates_of_selection(z, sel, k, topk_gate + (size_t)t * k);
+    }
+    return ORC_OK;
+}
+
+/*
+ * AffinityBinning + adaptive expert scorer + expert remapper (Secs. 3.2.1, 3.3.1, 3.4, 4).
+ *
+ * Bins (Sec. 3.2.1).  The affinity of expert e for token t is log(p_e / p_top1) = z_e - z_max.
+ * With d = z_max - z_e >= 0 taken as one fp32 subtract, the bin magnitude is
+ *     q[t,e] = min(floor(alpha * d), beta)          (one fp32 multiply, then floor)
+ * so the paper's bin value is -q; bin 0 holds the top-1; bin width is 1/alpha; q = beta means
+ * "deeper than the beta allowed bins" and carries no weight.
+ *
+ * Score (Sec. 3.3.1).  Every (token, expert) pair with q < beta votes B^(-q) for the expert, where
+ * the base B is the batch size T.  With Hst[e][j] = #{t : q[t,e] = j} the score is
+ * sum_j Hst[e][j] * T^(-j); it is held exactly as the integer S[e] = sum_j Hst[e][j] * T^(beta-1-j).
+ *
+ * Active set.  U = experts some token selected.  Token by token, slot by slot in rank order, the
+ * token nominates the highest-scoring expert of U that sits in a bin at least as good as the
+ * slot's own pick and that the token has not nominated yet (equal scores: lower index).  A slot
+ * whose own pick is out of range (q = beta) ends the token's nominations.  A = all nominations;
+ * if fewer than k experts were nominated, A is filled from U by descending score.
+ *
+ * Remap (Sec. 3.4, Sec. 4).  Each token takes its top-k among A by the original logits; gates are
+ * the softmax over the k selected original logits.
+ *
+ * enable = 0 (batch not memory-bound, Sec. 3.1.1 / 3.5) or T = 1 leaves the selection as it is.
+ *
+ * q_out [T,N], score_out [N], active_out [N] (0/1) are optional diagnostics (may be NULL).
+ */
+int orc_affinity_bin(const float *logits, const int32_t *topk_idx, int T, int N, int k, float alpha, int beta,
+                     int enable, int32_t *new_idx, double *new_gate, int32_t *cnt_before, int32_t *cnt_after,
+                     int32_t *bin_hist, int32_t *num_active, int32_t *q_out, uint64_t *score_out,
+                     int32_t *active_out)
+{
+    if (T < 0 || N <= 0 || k <= 0 || beta < 1 || !(alpha >= 0.0f) || isinf(alpha)) return ORC_ERR_INVALID_ARG;
+    if (k > N || beta > ORC_MAX_BETA) return ORC_ERR_UNSUPPORTED;
+    {
+        double lim = 1.0;
+        for (int j = 0; j < beta; ++j) lim *= (double)(T > 1 ? T : 1);
+        if (lim >= 4611686018427387904.0) return ORC_ERR_UNSUPPORTED; /* T^beta must stay below 2^62 */
+    }
+    for (int t = 0; t < T; ++t)
+        for (int j = 0; j < k; ++j) {
+            int32_t e = topk_idx[(size_t)t * k + j];
+            if (e < 0 || e >= N) return ORC_ERR_INVALID_ARG;
+            for (int i = 0; i < j; ++i)
+                if (topk_idx[(size_t)t * k + i] == e) return ORC_ERR_INVALID_ARG;
+        }
+
+    int32_t *q = (int32_t *)malloc(sizeof(int32_t) * (size_t)(T > 0 ? T : 1) * N);
+    uint64_t *score = (uint64_t *)calloc((size_t)N, sizeof(uint64_t));
+    uint8_t *inU = (uint8_t *)calloc((size_t)N, 1);
+    uint8_t *inA = (uint8_t *)calloc((size_t)N, 1);
+    uint8_t *used = (uint8_t *)calloc((size_t)N, 1);
+
+    /* bins */
+    for (int t = 0; t < T; ++t) {
+        const float *z = logits + (size_t)t * N;
+        float zmax = z[0];
+        for (int e = 1; e < N; ++e)
+            if (z[e] > zmax) zmax = z[e];
+        for (int e = 0; e < N; ++e) {
+            volatile float d = zmax - z[e];
+            volatile float scaled = alpha * d;
+            float qf = floorf(scaled);
+            q[(size_t)t * N + e] = (qf >= (float)beta) ? beta : (int32_t)qf;
+        }
+    }
+    /* histogram of bins per expert, votes of the original selection */
+    memset(bin_hist, 0, sizeof(int32_t) * (size_t)N * beta);
+    memset(cnt_before, 0, sizeof(int32_t) * (size_t)N);
+    memset(cnt_after, 0, sizeof(int32_t) * (size_t)N);
+    for (int t = 0; t < T; ++t)
+        for (int e = 0; e < N; ++e) {
+            int32_t b = q[(size_t)t * N + e];
+            if (b < beta) bin_hist[(size_t)e * beta + b] += 1;
+        }
+    for (int t = 0; t < T; ++t)
+        for (int j = 0; j < k; ++j) cnt_before[topk_idx[(size_t)t * k + j]] += 1;
+    int nU = 0;
+    for (int e = 0; e < N; ++e) {
+        inU[e] = cnt_before[e] > 0;
+        nU += inU[e];
+    }
+    /* score as a base-T integer with beta digits, most significant digit = bin 0 */
+    for (int e = 0; e < N; ++e) {
+        uint64_t s = 0;
+        for (int j = 0; j < beta; ++j) s = s * (uint64_t)T + (uint64_t)bin_hist[(size_t)e * beta + j];
+        score[e] = s;
+    }
+
+    if (!enable || T <= 1) {
+        for (int t = 0; t < T; ++t) {
+            for (int j = 0; j < k; ++j) new_idx[(size_t)t * k + j] = topk_idx[(size_t)t * k + j];
+            gates_of_selection(logits + (size_t)t * N, new_idx + (size_t)t * k, k, new_gate + (size_t)t * k);
+        }
+        for (int e = 0; e < N; ++e) {
+            cnt_after[e] = cnt_before[e];
+            inA[e] = inU[e];
+        }
+        num_active[0] = nU;
+        num_active[1] = nU;
+    } else {
+        /* nominations */
+        for (int t = 0; t < T; ++t) {
+            const int32_t *qt = q + (size_t)t * N;
+            memset(used, 0, (size_t)N);
+            for (int i = 0; i < k; ++i) {
+                int32_t qi = qt[topk_idx[(size_t)t * k + i]];
+                if (qi >= beta) break;
+                int best = -1;
+                for (int e = 0; e < N; ++e) {
+                    if (!inU[e] || used[e] || qt[e] > qi) continue;
+                    if (best < 0 || score[e] > score[best]) best = e;
+                }
+                /* never empty: the slot's own pick and the picks before it all qualify */
+                used[best] = 1;
+                inA[best] = 1;
+            }
+        }
+        /* fill to k */
+        int nA = 0;
+        for (int e = 0; e < N; ++e) nA += inA[e];
+        while (nA < k) {
+            int best = -1;
+            for (int e = 0; e < N; ++e) {
+                if (!inU[e] || inA[e]) continue;
+                if (best < 0 || score[e] > score[best]) best = e;
+            }
+            if (best < 0) break; /* cannot happen for T >= 1: |U| >= k */
+            inA[best] = 1;
+            ++nA;
+        }
+        /* remap */
+        for (int t = 0; t < T; ++t) {
+            const float *z = logits + (size_t)t * N;
+            int32_t *sel = new_idx + (size_t)t * k;
+            topk_select(z, inA, N, k, sel);
+            gates_of_selection(z, sel, k, new_gate + (size_t)t * k);
+            for (int j = 0; j < k; ++j) cnt_after[sel[j]] += 1;
+        }
+        int nAfter = 0;
+        for (int e = 0; e < N; ++e) nAfter += cnt_after[e] > 0;
+        num_active[0] = nU;
+        num_active[1] = nAfter;
+    }
+
+    if (q_out) memcpy(q_out, q, sizeof(int32_t) * (size_t)T * N);
+    if (score_out) memcpy(score_out, score, sizeof(uint64_t) * (size_t)N);
+    if (active_out)
+        for (int e = 0; e < N; ++e) active_out[e] = inA[e];
+    free(q);
+    free(score);
+    free(inU);
+    free(inA);
+    free(used);
+    return ORC_OK;
+}
+
+/*
+ * Token assignment (Sec. 4): per-expert pair counts, exclusive offsets by expert id, and the list
+ * of (token, slot) pairs t*k+slot grouped by expert, ascending in t then slot inside an expert.
+ * active_experts holds the invoked expert ids ascending; entries past num_active are -1.
+ */
+int orc_permute(const int32_t *idx, int T, int N, int k, int32_t *expert_offsets, int32_t *perm,
+                int32_t *active_experts, int32_t *num_active)
+{
+    if (T < 0 || N <= 0 || k <= 0) return ORC_ERR_INVALID_ARG;
+    for (int i = 0; i < T * k; ++i)
+        if (idx[i] < 0 || idx[i] >= N) return ORC_ERR_INVALID_ARG;
+    int32_t *count = (int32_t *)calloc((size_t)N, sizeof(int32_t));
+    for (int i = 0; i < T * k; ++i) count[idx[i]] += 1;
+    expert_offsets[0] = 0;
+    for (int e = 0; e < N; ++e) expert_offsets[e + 1] = expert_offsets[e] + count[e];
+    int na = 0;
+    for (int e = 0; e < N; ++e) {
+        active_experts[e] = -1;
+        if (count[e] > 0) active_experts[na++] = e;
+    }
+    num_active[0] = na;
+    memset(count, 0, sizeof(int32_t) * (size_t)N);
+    for (int i = 0; i < T * k; ++i) { /* i = t*k+slot ascending: stable */
+        int e = idx[i];
+        perm[expert_offsets[e] + count[e]] = i;
+        count[e] += 1;
+    }
+    free(count);
+    return ORC_OK;
+}
+
+/* One SwiGLU FFN applied to a list of tokens: out[i,:] = Wd * (silu(Wg x) .* (Wu x)).
+ * Wg, Wu are [F,H], Wd is [H,F], all bf16 row-major; xs is [T,H] fp64; out is [ntok,H] fp64. */
+static void swiglu_ffn(const uint16_t *Wg, const uint16_t *Wu, const uint16_t *Wd, int H, int F,
+                       const double *xs, const int32_t *tok, int ntok, double *out)
+{
+    double *hbuf = (double *)malloc(sizeof(double) * (size_t)ntok * F);
+#pragma omp parallel
+    {
+        double *row = (double *)malloc(sizeof(double) * (size_t)(H > F ? H : F) * 2);
+        double *rowg = row, *rowu = row + (H > F ? H : F);
+#pragma omp for schedule(static)
+        for (int f = 0; f < F; ++f) {
+            for (int h = 0; h < H; ++h) {
+                rowg[h] = bf16_to_f64(Wg[(size_t)f * H + h]);
+                rowu[h] = bf16_to_f64(Wu[(size_t)f * H + h]);
+            }
+            for (int i = 0; i < ntok; ++i) {
+                const double *x = xs + (size_t)tok[i] * H;
+                double a = 0.0, b = 0.0;
+                for (int h = 0; h < H; ++h) {
+                    a += rowg[h] * x[h];
+                    b += rowu[h] * x[h];
+                }
+                hbuf[(size_t)i * F + f] = (a / (1.0 + exp(-a))) * b;
+            }
+        }
+#pragma omp for schedule(static)
+        for (int r = 0; r < H; ++r) {
+            for (int f = 0; f < F; ++f) rowg[f] = bf16_to_f64(Wd[(size_t)r * F + f]);
+            for (int i = 0; i < ntok; ++i) {
+                const double *hv = hbuf + (size_t)i * F;
+                double o = 0.0;
+                for (int f = 0; f < F; ++f) o += rowg[f] * hv[f];
+                out[(size_t)i * H + r] = o;
+            }
+        }
+        free(row);
+    }
+    free(hbuf);
+}
+
+/*
+ * Grouped expert FFN and combine: y[t] = sum_j gate[t,j] * FFN_{idx[t,j]}(x[t]) + sum_s FFN_s(x[t]),
+ * shared experts entering with weight 1 (Sec. 3.3.1, last paragraph).  The intermediate vector is
+ * never rounded.  Routed weights: Wg, Wu [N,F,H], Wd [N,H,F]; shared: Sg, Su [n_shared,F_shared,H],
+ * Sd [n_shared,H,F_shared]; all bf16 row-major.  y is [T,H] fp64.
+ */
+int orc_moe_ffn(const uint16_t *x_bf16, const uint16_t *Wg, const uint16_t *Wu, const uint16_t *Wd,
+                const uint16_t *Sg, const uint16_t *Su, const uint16_t *Sd, int n_shared, int F_shared,
+                const int32_t *idx, const double *gate, int T, int H, int F, int N, int k, double *y)
+{
+    if (T < 0 || H <= 0 || F <= 0 || N <= 0 || k <= 0 || n_shared < 0) return ORC_ERR_INVALID_ARG;
+    if (n_shared > 0 && (F_shared <= 0 || !Sg || !Su || !Sd)) return ORC_ERR_INVALID_ARG;
+    for (int i = 0; i < T * k; ++i)
+        if (idx[i] < 0 || idx[i] >= N) return ORC_ERR_INVALID_ARG;
+    if (T == 0) return ORC_OK;
+    double *xs = (double *)malloc(sizeof(double) * (size_t)T * H);
+    for (size_t i = 0; i < (size_t)T * H; ++i) xs[i] = bf16_to_f64(x_bf16[i]);
+    for (size_t i = 0; i < (size_t)T * H; ++i) y[i] = 0.0;
+    int32_t *tok = (int32_t *)malloc(sizeof(int32_t) * (size_t)T);
+    int32_t *slot = (int32_t *)malloc(sizeof(int32_t) * (size_t)T);
+    double *out = (double *)malloc(sizeof(double) * (size_t)T * H);
+    /* per-pair expert outputs o[t,j,:], kept so that the combine sums slots in rank order */
+    double *o = (double *)calloc((size_t)T * k * H, sizeof(double));
+    for (int e = 0; e < N; ++e) {
+        int n = 0;
+        for (int t = 0; t < T; ++t)
+            for (int j = 0; j < k; ++j)
+                if (idx[(size_t)t * k + j] == e) {
+                    tok[n] = t;
+                    slot[n] = j;
+                    ++n;
+                }
+        if (n == 0) continue;
+        swiglu_ffn(Wg + (size_t)e * F * H, Wu + (size_t)e * F * H, Wd + (size_t)e * H * F, H, F, xs, tok, n, out);
+        for (int i = 0; i < n; ++i)
+            memcpy(o + ((size_t)tok[i] * k + slot[i]) * H, out + (size_t)i * H, sizeof(double) * (size_t)H);
+    }
+    for (int t = 0; t < T; ++t)
+        for (int j = 0; j < k; ++j) {
+            double g = gate[(size_t)t * k + j];
+            const double *oj = o + ((size_t)t * k + j) * H;
+            for (int h = 0; h < H; ++h) y[(size_t)t * H + h] += g * oj[h];
+        }
+    for (int t = 0; t < T; ++t) tok[t] = t;
+    for (int s = 0; s < n_shared; ++s) {
+        swiglu_ffn(Sg + (size_t)s * F_shared * H, Su + (size_t)s * F_shared * H, Sd + (size_t)s * H * F_shared, H,
+                   F_shared, xs, tok, T, out);
+        for (size_t i = 0; i < (size_t)T * H; ++i) y[i] += out[i];
+    }
+    free(o);
+    free(out);
+    free(slot);
+    free(tok);
+    free(xs);
+    return ORC_OK;
+}
