@@ -1,0 +1,136 @@
+/*
+ * lynx.h -- C ABI of the MI355X (gfx950) implementation of the batched MoE-layer decode step of
+ * Lynx (arXiv 2411.08982): router logits, softmax and top-k (Sec. 2.1); AffinityBinning, batch-wide
+ * expert scoring and remapping (Secs. 3.2.1, 3.3.1, 3.4); token assignment and weight
+ * renormalisation (Sec. 4); grouped SwiGLU expert FFN over the experts still invoked, and the
+ * gate-weighted combine (the "expert computation kernel" the remapper dispatches, Sec. 3.4).
+ *
+ * Conventions
+ *  - Every pointer is a DEVICE pointer owned by the caller unless it says "host".  The library
+ *    allocates nothing and keeps no state between calls.
+ *  - Every call only enqueues kernels on `stream` (a hipStream_t passed as void*; NULL = the null
+ *    stream).  No call synchronises with the host or reads device results on the host, so a sequence
+ *    of calls can be captured into a hipGraph.
+ *  - All matrices are dense row-major unless a packed layout is named.  bf16 values travel as
+ *    uint16_t bit patterns.  T = decode tokens in the batch, H = hidden size, F = expert FFN width,
+ *    N = routed experts, k = experts per token.
+ *  - Return value: LYNX_OK, or a negative error; lynx_last_error() gives a host string for the last
+ *    error of the calling thread.  On error nothing has been enqueued.
+ *  - Inputs are assumed finite.  Indices outside [0,N) in caller-provided index arrays never cause an
+ *    out-of-bounds access: such pairs are skipped.
+ *  - Limits: T <= LYNX_MAX_T, N <= LYNX_MAX_N, k <= LYNX_MAX_K, beta <= LYNX_MAX_BETA,
+ *    H % 32 == 0, F % 32 == 0, F_shared % 32 == 0.
+ */
+#ifndef LYNX_H
+#define LYNX_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LYNX_OK 0
+#define LYNX_ERR_INVALID_ARG (-1) /* null pointer, negative size, alpha < 0 or not finite, beta < 1 */
+#define LYNX_ERR_UNSUPPORTED (-2) /* a documented limit is exceeded (k > N, beta > 6, T^beta >= 2^62, ...) */
+#define LYNX_ERR_HIP (-3)         /* a HIP runtime call failed */
+
+#define LYNX_MAX_T 1024
+#define LYNX_MAX_N 256
+#define LYNX_MAX_K 16
+#define LYNX_MAX_BETA 6
+
+/* Host string describing the last error on this thread ("" if none). */
+const char *lynx_last_error(void);
+
+/* Bytes of device workspace that lynx_affinity_bin and lynx_moe_ffn need for these sizes
+ * (one buffer of this size serves both; contents need not be preserved between calls). */
+size_t lynx_workspace_bytes(int T, int H, int F, int N, int k, int n_shared, int F_shared);
+
+/*
+ * Router (Sec. 2.1): z[t,e] = sum_h x[t,h] * Wr[e,h] + bias[e] in fp32; p = softmax(z); the k
+ * experts of largest z per token, descending, equal logits to the lower expert index.
+ *   x_bf16 [T,H] bf16, Wr [N,H] fp32, bias [N] fp32 or NULL.
+ *   logits [T,N] fp32 out; topk_idx [T,k] int32 out; topk_gate [T,k] fp32 out = selected
+ *   probabilities renormalised to sum 1; topk_psum [T] fp32 out = sum of the selected probabilities.
+ */
+int lynx_route(const uint16_t *x_bf16, const float *Wr, const float *bias, int T, int H, int N, int k,
+               float *logits, int32_t *topk_idx, float *topk_gate, float *topk_psum, void *stream);
+
+/*
+ * AffinityBinning, batch-wide scoring, active-set selection, remapping (Secs. 3.2.1, 3.3.1, 3.4, 4).
+ *   Bin magnitude q[t,e] = min(floor(alpha * (max_e' z[t,e'] - z[t,e])), beta), one fp32 subtract
+ *   and one fp32 multiply (the paper's bin value is -q; bin width 1/alpha; beta allowed bins).
+ *   bin_hist[e][j] = #{t : q[t,e] = j}, j < beta.  Score of expert e = sum_j bin_hist[e][j] * T^(-j)
+ *   (batch size as the base, bin value as the exponent), compared exactly as a base-T integer.
+ *   Each token, slot by slot in rank order, nominates the best-scoring expert among those the batch
+ *   already invokes that lies in a bin at least as good as the slot's own pick (and that the token
+ *   has not nominated yet; equal scores to the lower index); a slot whose own pick is out of range
+ *   (q = beta) ends the token's nominations.  The active set is the union of the nominations, filled
+ *   by descending score up to k experts if smaller.  Every token then takes its top-k by original
+ *   logit within the active set; gates are the softmax over the k selected original logits.
+ *   enable = 0 (batch not memory-bound, Sec. 3.1.1) or T = 1 keeps topk_idx as it is.
+ *
+ *   logits [T,N] fp32, topk_idx [T,k] int32 (k distinct experts per row, descending logit).
+ *   new_idx [T,k] int32 out, new_gate [T,k] fp32 out, cnt_before [N], cnt_after [N] int32 out (pairs
+ *   per expert before / after), bin_hist [N,beta] int32 out, num_active [2] int32 out (experts invoked
+ *   before, after).  workspace: lynx_workspace_bytes() bytes.
+ */
+int lynx_affinity_bin(const float *logits, const int32_t *topk_idx, int T, int N, int k, float alpha, int beta,
+                      int enable, int32_t *new_idx, float *new_gate, int32_t *cnt_before, int32_t *cnt_after,
+                      int32_t *bin_hist, int32_t *num_active, void *workspace, void *stream);
+
+/*
+ * Token assignment (Sec. 4): expert_offsets [N+1] int32 out = exclusive prefix of pairs per expert;
+ * perm [T*k] int32 out = pair ids t*k+slot grouped by expert ascending, ascending inside an expert;
+ * active_experts [N] int32 out = invoked expert ids ascending, -1 past num_active; num_active [1] out.
+ * idx [T,k] int32 must hold k distinct experts per row.
+ */
+int lynx_permute(const int32_t *idx, int T, int N, int k, int32_t *expert_offsets, int32_t *perm,
+                 int32_t *active_experts, int32_t *num_active, void *stream);
+
+/*
+ * One-time re-layout of expert weights into the streaming layout lynx_moe_ffn reads (same byte
+ * count as the row-major weights).  Input: Wg, Wu [E,F,H], Wd [E,H,F] bf16 row-major.  Output:
+ *   Wgu_packed [E][F/16][H/32][2][64][8] bf16: tile (rt,kt), matrix m (0 = gate, 1 = up), entry
+ *     (lane l, i) = W_m[rt*16 + l%16][kt*32 + (l/16)*8 + i];
+ *   Wd_packed  [E][H/16][F/32][64][8] bf16: entry (lane l, i) = Wd[rt*16 + l%16][kt*32 + (l/16)*8 + i].
+ * Each 16-row tile is then one contiguous run, read with 1 KiB wave-wide loads.
+ */
+int lynx_pack_weights(const uint16_t *Wg, const uint16_t *Wu, const uint16_t *Wd, int E, int H, int F,
+                      uint16_t *Wgu_packed, uint16_t *Wd_packed, void *stream);
+
+/*
+ * Grouped SwiGLU expert FFN over the invoked experts and gate-weighted combine:
+ *   y[t] = sum_j gate[t,j] * Wd[e] (silu(Wg[e] x_t) .* (Wu[e] x_t)),  e = idx[t,j],
+ *          + sum_s Sd[s] (silu(Sg[s] x_t) .* (Su[s] x_t))            (shared experts, weight 1,
+ *                                                                      Sec. 3.3.1 last paragraph)
+ * bf16 operands, fp32 accumulation; the intermediate vector is rounded to bf16 between the two
+ * projections.  Each invoked expert's weights are read once per call; experts with no pair are not
+ * touched.  Weights in the packed layout of lynx_pack_weights (Sgu/Sd: packed with E = n_shared,
+ * F = F_shared; NULL when n_shared = 0).  expert_offsets / perm / active_experts / num_active as
+ * written by lynx_permute for the same idx.  y [T,H] fp32 out, overwritten.
+ */
+int lynx_moe_ffn(const uint16_t *x_bf16, const uint16_t *Wgu_packed, const uint16_t *Wd_packed,
+                 const uint16_t *Sgu_packed, const uint16_t *Sd_packed, int n_shared, int F_shared,
+                 const int32_t *idx, const float *gate, const int32_t *expert_offsets, const int32_t *perm,
+                 const int32_t *active_experts, const int32_t *num_active, int T, int H, int F, int N, int k,
+                 float *y, void *workspace, void *stream);
+
+/*
+ * The whole decode step of one MoE layer: lynx_route, lynx_affinity_bin, lynx_permute, lynx_moe_ffn
+ * chained on `stream` with the argument meanings above.  All intermediate arrays are outputs.
+ */
+int lynx_moe_layer(const uint16_t *x_bf16, const float *Wr, const float *bias, const uint16_t *Wgu_packed,
+                   const uint16_t *Wd_packed, const uint16_t *Sgu_packed, const uint16_t *Sd_packed, int n_shared,
+                   int F_shared, int T, int H, int F, int N, int k, float alpha, int beta, int enable, float *logits,
+                   int32_t *topk_idx, float *topk_gate, float *topk_psum, int32_t *new_idx, float *new_gate,
+                   int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist, int32_t *num_active,
+                   int32_t *expert_offsets, int32_t *perm, int32_t *active_experts, int32_t *num_active_perm, float *y,
+                   void *workspace, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LYNX_H */

@@ -43,12 +43,13 @@ def _load():
                                         POINTER(c_uint64))
         lib.orc_num_threads.restype = c_int
         lib.orc_route.argtypes = [u16p, f32p, f32p, c_int, c_int, c_int, c_int, f32p, i32p, f64p, f64p]
+        lib.orc_topk.argtypes = [f32p, c_int, c_int, c_int, i32p, f64p, f64p]
         lib.orc_affinity_bin.argtypes = [f32p, i32p, c_int, c_int, c_int, c_float, c_int, c_int, i32p, f64p, i32p,
                                          i32p, i32p, i32p, i32p, u64p, i32p]
         lib.orc_permute.argtypes = [i32p, c_int, c_int, c_int, i32p, i32p, i32p, i32p]
         lib.orc_moe_ffn.argtypes = [u16p, u16p, u16p, u16p, u16p, u16p, u16p, c_int, c_int, i32p, f64p, c_int, c_int,
                                     c_int, c_int, c_int, f64p]
-        for f in (lib.orc_route, lib.orc_affinity_bin, lib.orc_permute, lib.orc_moe_ffn):
+        for f in (lib.orc_route, lib.orc_topk, lib.orc_affinity_bin, lib.orc_permute, lib.orc_moe_ffn):
             f.restype = c_int
         _lib = lib
     return _lib
@@ -93,6 +94,19 @@ def route(x_bf16, Wr, bias, k):
     if rc != OK:
         raise OracleError(rc, "orc_route")
     return dict(logits=logits, idx=idx, gate=gate, psum=psum)
+
+
+def topk(logits, k):
+    """Softmax + top-k from given fp32 logits [T,N].  Returns dict(idx, gate f64, psum f64)."""
+    z = _arr(logits, np.float32)
+    T, N = z.shape
+    idx = np.zeros((T, k), np.int32)
+    gate = np.zeros((T, k), np.float64)
+    psum = np.zeros((T,), np.float64)
+    rc = _load().orc_topk(_p(z, c_float), T, N, k, _p(idx, c_int32), _p(gate, c_double), _p(psum, c_double))
+    if rc != OK:
+        raise OracleError(rc, "orc_topk")
+    return dict(idx=idx, gate=gate, psum=psum)
 
 
 def affinity_bin(logits, topk_idx, alpha, beta, enable=1):

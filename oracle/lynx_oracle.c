@@ -83,6 +83,28 @@ static void gates_of_selection(const float *z, const int32_t *sel, int k, double
     for (int j = 0; j < k; ++j) gate[j] = exp((double)z[sel[j]] - zmax) / den;
 }
 
+/* Softmax + top-k of one token's logits (Sec. 2.1): selection, renormalised gates, selected mass. */
+static void select_and_weigh(const float *z, int N, int k, int32_t *sel, double *gate, double *psum)
+{
+    topk_select(z, NULL, N, k, sel);
+    double zmax = (double)z[sel[0]], den = 0.0, num = 0.0;
+    for (int e = 0; e < N; ++e) den += exp((double)z[e] - zmax);
+    for (int j = 0; j < k; ++j) num += exp((double)z[sel[j]] - zmax);
+    *psum = num / den;
+    gates_of_selection(z, sel, k, gate);
+}
+
+/* Softmax + top-k from given fp32 logits [T,N] (the second half of orc_route on its own). */
+int orc_topk(const float *logits, int T, int N, int k, int32_t *topk_idx, double *topk_gate, double *topk_psum)
+{
+    if (T < 0 || N <= 0 || k <= 0) return ORC_ERR_INVALID_ARG;
+    if (k > N) return ORC_ERR_UNSUPPORTED;
+    for (int t = 0; t < T; ++t)
+        select_and_weigh(logits + (size_t)t * N, N, k, topk_idx + (size_t)t * k, topk_gate + (size_t)t * k,
+                         topk_psum + t);
+    return ORC_OK;
+}
+
 /*
  * Router (Sec. 2.1): z[t,e] = sum_h x[t,h] * Wr[e,h] + bias[e], accumulated in fp64 and rounded
  * once to fp32; p = softmax(z); the k experts of largest z per token (descending, ties to the
@@ -103,13 +125,7 @@ int orc_route(const uint16_t *x_bf16, const float *Wr, const float *bias, int T,
             if (bias) acc += (double)bias[e];
             z[e] = (float)acc;
         }
-        int32_t *sel = topk_idx + (size_t)t * k;
-        topk_select(z, NULL, N, k, sel);
-        double zmax = (double)z[sel[0]], den = 0.0, num = 0.0;
-        for (int e = 0; e < N; ++e) den += exp((double)z[e] - zmax);
-        for (int j = 0; j < k; ++j) num += exp((double)z[sel[j]] - zmax);
-        topk_psum[t] = num / den;
-        gates_of_selection(z, sel, k, topk_gate + (size_t)t * k);
+        select_and_weigh(z, N, k, topk_idx + (size_t)t * k, topk_gate + (size_t)t * k, topk_psum + t);
     }
     return ORC_OK;
 }

@@ -1,0 +1,197 @@
+"""ctypes binding of liblynx.so: argument marshalling only.
+
+Every function takes torch tensors that already live on the GPU (torch is used for device memory and
+streams, nothing else), checks dtype / contiguity / device, and passes raw device pointers and the
+current HIP stream to the C ABI declared in include/lynx.h.  No step of the path runs in Python or
+torch, and there is no CPU fallback: a missing library is an error.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from ctypes import c_float, c_int, c_size_t, c_void_p
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblynx.so")
+
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_HIP = 0, -1, -2, -3
+MAX_T, MAX_N, MAX_K, MAX_BETA = 1024, 256, 16, 6
+
+SYMBOLS = ["lynx_last_error", "lynx_workspace_bytes", "lynx_route", "lynx_affinity_bin", "lynx_permute",
+           "lynx_pack_weights", "lynx_moe_ffn", "lynx_moe_layer"]
+
+
+class LynxError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"liblynx error {code}: {msg}")
+        self.code = code
+
+
+_lib = None
+
+
+def lib():
+    """Loads liblynx.so (built in-tree by paper_2411_08982_amd.build); raises if it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(f"{LIB_PATH} is not built: run `python -m paper_2411_08982_amd.build` "
+                                    "(there is no fallback path)")
+        L = ctypes.CDLL(LIB_PATH)
+        P, I, F = c_void_p, c_int, c_float
+        L.lynx_last_error.restype = ctypes.c_char_p
+        L.lynx_last_error.argtypes = []
+        L.lynx_workspace_bytes.restype = c_size_t
+        L.lynx_workspace_bytes.argtypes = [I] * 7
+        L.lynx_route.argtypes = [P, P, P, I, I, I, I, P, P, P, P, P]
+        L.lynx_affinity_bin.argtypes = [P, P, I, I, I, F, I, I, P, P, P, P, P, P, P, P]
+        L.lynx_permute.argtypes = [P, I, I, I, P, P, P, P, P]
+        L.lynx_pack_weights.argtypes = [P, P, P, I, I, I, P, P, P]
+        L.lynx_moe_ffn.argtypes = [P, P, P, P, P, I, I, P, P, P, P, P, P, I, I, I, I, I, P, P, P]
+        L.lynx_moe_layer.argtypes = [P, P, P, P, P, P, P, I, I, I, I, I, I, I, F, I, I] + [P] * 17
+        for name in SYMBOLS[2:]:
+            getattr(L, name).restype = c_int
+        _lib = L
+    return _lib
+
+
+def _check(rc: int):
+    if rc != OK:
+        raise LynxError(rc, lib().lynx_last_error().decode())
+
+
+def _ptr(t, dtype, what):
+    if t is None:
+        return None
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError(f"{what}: expected a CUDA/HIP tensor")
+    if t.dtype != dtype:
+        raise TypeError(f"{what}: expected {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{what}: must be contiguous")
+    return t.data_ptr()
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+BF16, F32, I32 = torch.bfloat16, torch.float32, torch.int32
+
+
+def workspace_bytes(T, H, F, N, k, n_shared=0, F_shared=0) -> int:
+    return int(lib().lynx_workspace_bytes(T, H, F, N, k, n_shared, F_shared))
+
+
+def new_workspace(T, H, F, N, k, n_shared=0, F_shared=0, device="cuda"):
+    return torch.empty(max(workspace_bytes(T, H, F, N, k, n_shared, F_shared), 256), dtype=torch.uint8, device=device)
+
+
+def lynx_route(x, Wr, bias, k, out=None):
+    """x [T,H] bf16, Wr [N,H] f32, bias [N] f32 or None -> dict(logits, idx, gate, psum)."""
+    T, H = x.shape
+    N = Wr.shape[0]
+    dev = x.device
+    o = out or dict(logits=torch.empty((T, N), dtype=F32, device=dev), idx=torch.empty((T, k), dtype=I32, device=dev),
+                    gate=torch.empty((T, k), dtype=F32, device=dev), psum=torch.empty((T,), dtype=F32, device=dev))
+    _check(lib().lynx_route(_ptr(x, BF16, "x"), _ptr(Wr, F32, "Wr"), _ptr(bias, F32, "bias"), T, H, N, k,
+                            _ptr(o["logits"], F32, "logits"), _ptr(o["idx"], I32, "idx"), _ptr(o["gate"], F32, "gate"),
+                            _ptr(o["psum"], F32, "psum"), _stream()))
+    return o
+
+
+def lynx_affinity_bin(logits, topk_idx, alpha, beta, enable=1, workspace=None, out=None):
+    """logits [T,N] f32, topk_idx [T,k] i32 -> dict(new_idx, new_gate, cnt_before, cnt_after, bin_hist, num_active)."""
+    T, N = logits.shape
+    k = topk_idx.shape[1]
+    dev = logits.device
+    nb = max(int(beta), 1)
+    o = out or dict(new_idx=torch.empty((T, k), dtype=I32, device=dev), new_gate=torch.empty((T, k), dtype=F32, device=dev),
+                    cnt_before=torch.empty((N,), dtype=I32, device=dev), cnt_after=torch.empty((N,), dtype=I32, device=dev),
+                    bin_hist=torch.empty((N, nb), dtype=I32, device=dev), num_active=torch.empty((2,), dtype=I32, device=dev))
+    ws = None if workspace is None else workspace.data_ptr()
+    _check(lib().lynx_affinity_bin(_ptr(logits, F32, "logits"), _ptr(topk_idx, I32, "topk_idx"), T, N, k, float(alpha),
+                                   int(beta), int(enable), _ptr(o["new_idx"], I32, "new_idx"),
+                                   _ptr(o["new_gate"], F32, "new_gate"), _ptr(o["cnt_before"], I32, "cnt_before"),
+                                   _ptr(o["cnt_after"], I32, "cnt_after"), _ptr(o["bin_hist"], I32, "bin_hist"),
+                                   _ptr(o["num_active"], I32, "num_active"), ws, _stream()))
+    return o
+
+
+def lynx_permute(idx, N, out=None):
+    """idx [T,k] i32 -> dict(offsets [N+1], perm [T*k], active [N], num_active [1])."""
+    T, k = idx.shape
+    dev = idx.device
+    o = out or dict(offsets=torch.empty((N + 1,), dtype=I32, device=dev), perm=torch.empty((T * k,), dtype=I32, device=dev),
+                    active=torch.empty((N,), dtype=I32, device=dev), num_active=torch.empty((1,), dtype=I32, device=dev))
+    _check(lib().lynx_permute(_ptr(idx, I32, "idx"), T, N, k, _ptr(o["offsets"], I32, "offsets"),
+                              _ptr(o["perm"], I32, "perm"), _ptr(o["active"], I32, "active"),
+                              _ptr(o["num_active"], I32, "num_active"), _stream()))
+    return o
+
+
+def lynx_pack_weights(Wg, Wu, Wd):
+    """Wg, Wu [E,F,H], Wd [E,H,F] bf16 row-major -> (Wgu_packed, Wd_packed) in the streaming layout."""
+    E, F, H = Wg.shape
+    if Wu.shape != (E, F, H) or Wd.shape != (E, H, F):
+        raise ValueError("weight shapes do not match")
+    Wgu = torch.empty((E, F // 16, H // 32, 2, 64, 8), dtype=BF16, device=Wg.device)
+    Wdp = torch.empty((E, H // 16, F // 32, 64, 8), dtype=BF16, device=Wg.device)
+    _check(lib().lynx_pack_weights(_ptr(Wg, BF16, "Wg"), _ptr(Wu, BF16, "Wu"), _ptr(Wd, BF16, "Wd"), E, H, F,
+                                   _ptr(Wgu, BF16, "Wgu"), _ptr(Wdp, BF16, "Wdp"), _stream()))
+    return Wgu, Wdp
+
+
+def lynx_moe_ffn(x, Wgu, Wdp, idx, gate, perm_out, N, F, Sgu=None, Sdp=None, n_shared=0, F_shared=0, workspace=None,
+                 y=None):
+    """x [T,H] bf16, packed weights, idx/gate [T,k], perm_out = result of lynx_permute -> y [T,H] f32."""
+    T, H = x.shape
+    k = idx.shape[1]
+    if workspace is None:
+        workspace = new_workspace(T, H, F, N, k, n_shared, F_shared, x.device)
+    need = workspace_bytes(T, H, F, N, k, n_shared, F_shared)
+    if workspace.numel() * workspace.element_size() < need:
+        raise ValueError(f"workspace too small: {workspace.numel()} < {need}")
+    if y is None:
+        y = torch.empty((T, H), dtype=F32, device=x.device)
+    _check(lib().lynx_moe_ffn(_ptr(x, BF16, "x"), _ptr(Wgu, BF16, "Wgu"), _ptr(Wdp, BF16, "Wdp"), _ptr(Sgu, BF16, "Sgu"),
+                              _ptr(Sdp, BF16, "Sdp"), n_shared, F_shared, _ptr(idx, I32, "idx"), _ptr(gate, F32, "gate"),
+                              _ptr(perm_out["offsets"], I32, "offsets"), _ptr(perm_out["perm"], I32, "perm"),
+                              _ptr(perm_out["active"], I32, "active"), _ptr(perm_out["num_active"], I32, "num_active"),
+                              T, H, F, N, k, _ptr(y, F32, "y"), workspace.data_ptr(), _stream()))
+    return y
+
+
+class LayerBuffers:
+    """All outputs and scratch of lynx_moe_layer for fixed sizes, allocated once."""
+
+    def __init__(self, T, H, F, N, k, beta, n_shared=0, F_shared=0, device="cuda"):
+        e = lambda shape, dt: torch.empty(shape, dtype=dt, device=device)
+        self.sizes = (T, H, F, N, k, n_shared, F_shared)
+        self.beta = beta
+        self.logits, self.topk_idx, self.topk_gate, self.topk_psum = e((T, N), F32), e((T, k), I32), e((T, k), F32), e((T,), F32)
+        self.new_idx, self.new_gate = e((T, k), I32), e((T, k), F32)
+        self.cnt_before, self.cnt_after, self.bin_hist, self.num_active = e((N,), I32), e((N,), I32), e((N, beta), I32), e((2,), I32)
+        self.offsets, self.perm, self.active, self.num_active_perm = e((N + 1,), I32), e((max(T * k, 1),), I32), e((N,), I32), e((1,), I32)
+        self.y = e((T, H), F32)
+        self.workspace = new_workspace(T, H, F, N, k, n_shared, F_shared, device)
+
+
+def lynx_moe_layer(x, Wr, bias, Wgu, Wdp, F, k, alpha, beta, enable=1, Sgu=None, Sdp=None, n_shared=0, F_shared=0,
+                   buffers: LayerBuffers | None = None):
+    """route -> affinity_bin -> permute -> FFN + combine on the current stream.  Returns the LayerBuffers."""
+    T, H = x.shape
+    N = Wr.shape[0]
+    b = buffers or LayerBuffers(T, H, F, N, k, beta, n_shared, F_shared, x.device)
+    if b.sizes != (T, H, F, N, k, n_shared, F_shared) or b.beta != beta:
+        raise ValueError("buffers were allocated for other sizes")
+    _check(lib().lynx_moe_layer(
+        _ptr(x, BF16, "x"), _ptr(Wr, F32, "Wr"), _ptr(bias, F32, "bias"), _ptr(Wgu, BF16, "Wgu"), _ptr(Wdp, BF16, "Wdp"),
+        _ptr(Sgu, BF16, "Sgu"), _ptr(Sdp, BF16, "Sdp"), n_shared, F_shared, T, H, F, N, k, float(alpha), int(beta),
+        int(enable), b.logits.data_ptr(), b.topk_idx.data_ptr(), b.topk_gate.data_ptr(), b.topk_psum.data_ptr(),
+        b.new_idx.data_ptr(), b.new_gate.data_ptr(), b.cnt_before.data_ptr(), b.cnt_after.data_ptr(),
+        b.bin_hist.data_ptr(), b.num_active.data_ptr(), b.offsets.data_ptr(), b.perm.data_ptr(), b.active.data_ptr(),
+        b.num_active_perm.data_ptr(), b.y.data_ptr(), b.workspace.data_ptr(), _stream()))
+    return b

@@ -1,0 +1,37 @@
+"""Helpers of the GPU parity tests: numpy <-> device tensor marshalling and the comparison rules."""
+import numpy as np
+import torch
+
+
+def to_bf16_dev(bits: np.ndarray):
+    """uint16 bf16 bit patterns -> torch.bfloat16 tensor on the GPU (bit-preserving)."""
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
+
+
+def bf16_bits(t) -> np.ndarray:
+    """torch.bfloat16 tensor (any device) -> uint16 bit patterns on the host."""
+    return t.detach().contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def dev(a: np.ndarray):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t) -> np.ndarray:
+    return t.detach().cpu().numpy()
+
+
+def row_rel_err(y, y_ref):
+    """Per token row: max_h |y - y_ref| / max_h |y_ref| (the layer-output tolerance is stated on this)."""
+    y = np.asarray(y, np.float64)
+    y_ref = np.asarray(y_ref, np.float64)
+    den = np.abs(y_ref).max(axis=1)
+    den = np.where(den == 0, 1.0, den)
+    return np.abs(y - y_ref).max(axis=1) / den
+
+
+def pack_reference(W: np.ndarray) -> np.ndarray:
+    """Row-major [E,R,K] -> [E,R/16,K/32,64,8]: entry (lane l, i) = W[rt*16 + l%16][kt*32 + (l//16)*8 + i]."""
+    E, R, K = W.shape
+    t = W.reshape(E, R // 16, 16, K // 32, 4, 8)       # e, rt, r, kt, g, i
+    return np.ascontiguousarray(t.transpose(0, 1, 3, 4, 2, 5)).reshape(E, R // 16, K // 32, 64, 8)   # lane = g*16 + r

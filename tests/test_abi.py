@@ -1,0 +1,77 @@
+"""The C-ABI library loads and exports every symbol that include/lynx.h declares; argument checks
+that return before any kernel launch behave as documented.  No GPU is needed."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2411_08982_amd as L
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "lynx.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(lynx_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = L.lib()
+    names = _declared()
+    assert set(names) == set(L.SYMBOLS) and len(names) == 8
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_header_limits_match_binding():
+    text = open(os.path.join(ROOT, "include", "lynx.h")).read()
+    vals = {m[0]: int(m[1]) for m in re.findall(r"#define (LYNX_MAX_[A-Z]+) (\d+)", text)}
+    from paper_2411_08982_amd import binding as B
+    assert (vals["LYNX_MAX_T"], vals["LYNX_MAX_N"], vals["LYNX_MAX_K"], vals["LYNX_MAX_BETA"]) == (
+        B.MAX_T, B.MAX_N, B.MAX_K, B.MAX_BETA)
+
+
+def test_workspace_bytes_monotone_and_nonnegative():
+    a = L.workspace_bytes(16, 512, 1024, 8, 2)
+    b = L.workspace_bytes(32, 512, 1024, 8, 2)
+    c = L.workspace_bytes(32, 512, 1024, 8, 2, 1, 2048)
+    assert 0 < a < b < c
+    assert L.workspace_bytes(-1, 512, 1024, 8, 2) == 0
+    # h scratch (bf16) + per-pair outputs (fp32) must fit
+    assert a >= 16 * 2 * 1024 * 2 + 16 * 2 * 512 * 4
+
+
+def test_argument_errors_are_reported_before_any_launch():
+    lib = L.lib()
+    one = ctypes.c_void_p(256)   # never dereferenced: every call below must fail on its size checks
+    rc = lib.lynx_route(one, one, None, 4, 64, 4, 8, one, one, one, one, None)           # k > N
+    assert rc == -2 and b"lynx_route" in lib.lynx_last_error()
+    assert lib.lynx_route(one, one, None, 4, 48, 4, 2, one, one, one, one, None) == -2    # H % 32
+    assert lib.lynx_route(one, one, None, -1, 64, 4, 2, one, one, one, one, None) == -1
+    assert lib.lynx_route(None, one, None, 4, 64, 4, 2, one, one, one, one, None) == -1
+    assert lib.lynx_route(one, one, None, 2000, 64, 4, 2, one, one, one, one, None) == -2  # T > LYNX_MAX_T
+    ab = lambda T, N, k, alpha, beta: lib.lynx_affinity_bin(one, one, T, N, k, ctypes.c_float(alpha), beta, 1, one, one,
+                                                             one, one, one, one, None, None)
+    assert ab(4, 8, 2, 1.0, 0) == -1
+    assert ab(4, 8, 2, -1.0, 2) == -1
+    assert ab(4, 8, 2, float("nan"), 2) == -1
+    assert ab(4, 8, 2, float("inf"), 2) == -1
+    assert ab(4, 8, 2, 1.0, 7) == -2
+    assert ab(4, 300, 2, 1.0, 2) == -2
+    assert lib.lynx_permute(one, 4, 8, 9, one, one, one, one, None) == -2
+    assert lib.lynx_permute(one, 4, 0, 1, one, one, one, one, None) == -1
+    assert lib.lynx_pack_weights(one, one, one, 2, 48, 64, one, one, None) == -2
+    rc = lib.lynx_moe_ffn(one, one, one, None, None, 1, 64, one, one, one, one, one, one, 4, 64, 64, 4, 2, one, one, None)
+    assert rc == -1 and b"shared" in lib.lynx_last_error()
+    assert lib.lynx_moe_ffn(one, one, one, None, None, 0, 0, one, one, one, one, one, one, 4, 64, 72, 4, 2, one, one,
+                            None) == -2
+
+
+def test_missing_library_is_an_error(monkeypatch, tmp_path):
+    from paper_2411_08982_amd import binding as B
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(FileNotFoundError):
+        B.lib()

@@ -1,0 +1,283 @@
+"""GPU parity: every C-ABI entry point of liblynx against the CPU oracle on the same seeded inputs.
+
+Bars: integer outputs (indices, counts, offsets, permutation, histogram) bit-exact given identical
+fp32 logits; router logits within 1e-5; gates within 1e-5; layer outputs within 1e-2 per token row
+(max_h |y - y_ref| / max_h |y_ref|; bf16 operands, fp32 accumulation, bf16 intermediate vector).
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads as wl
+from gpu_util import bf16_bits, dev, host, pack_reference, row_rel_err, to_bf16_dev
+
+pytestmark = pytest.mark.gpu
+
+Y_TOL = 1e-2
+LOGIT_TOL = 1e-5
+GATE_TOL = 1e-5
+
+
+@pytest.fixture(scope="module")
+def L():
+    import paper_2411_08982_amd as lib
+    lib.lib()   # fails loudly if liblynx.so is not built
+    assert torch.cuda.is_available()
+    return lib
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+# ------------------------------------------------------------------------------------------------ route
+
+@pytest.mark.parametrize("T,H,N,k,bias", [(16, 512, 8, 2, True), (1, 4096, 8, 2, True), (33, 2048, 60, 4, True),
+                                          (64, 2048, 64, 6, False), (128, 2048, 128, 8, True), (5, 32, 256, 16, True),
+                                          (3, 64, 4, 4, True)])
+def test_route(L, T, H, N, k, bias):
+    _say(f"route T={T} H={H} N={N} k={k}")
+    rng = np.random.default_rng(T * 7 + N)
+    x = wl.f32_to_bf16_bits(rng.standard_normal((T, H)).astype(np.float32))
+    Wr = (rng.standard_normal((N, H)) / np.sqrt(H)).astype(np.float32)
+    b = wl.zipf_bias(N, 1.0, 0.5, rng) if bias else None
+    ref = oracle.route(x, Wr, b, k)
+    out = L.lynx_route(to_bf16_dev(x), dev(Wr), None if b is None else dev(b), k)
+    torch.cuda.synchronize()
+    z = host(out["logits"])
+    assert np.all(np.abs(z - ref["logits"]) <= LOGIT_TOL * np.maximum(1.0, np.abs(ref["logits"])))
+    # selection, gates and selected mass are judged on the GPU's own fp32 logits (identical logits on both sides)
+    ref2 = oracle.topk(z, k)
+    assert np.array_equal(host(out["idx"]), ref2["idx"])
+    np.testing.assert_allclose(host(out["gate"]), ref2["gate"], rtol=GATE_TOL, atol=1e-7)
+    np.testing.assert_allclose(host(out["psum"]), ref2["psum"], rtol=GATE_TOL, atol=1e-7)
+
+
+def test_route_ties_go_to_lower_index(L):
+    H = N = 32
+    rng = np.random.default_rng(1)
+    Wr = rng.integers(-2, 3, size=(N, H)).astype(np.float32)      # exact small-integer logits, many ties
+    x = wl.f32_to_bf16_bits(np.eye(H, dtype=np.float32))
+    out = L.lynx_route(to_bf16_dev(x), dev(Wr), None, 5)
+    torch.cuda.synchronize()
+    ref = oracle.route(x, Wr, None, 5)
+    assert np.array_equal(host(out["logits"]), ref["logits"])
+    assert np.array_equal(host(out["idx"]), ref["idx"])
+
+
+# ------------------------------------------------------------------------------------------------ affinity_bin
+
+BIN_CASES = [(16, 8, 2, 1.1, 0.0), (8, 8, 2, 1.1, 0.0), (32, 60, 4, 1.0, 0.0), (64, 64, 6, 0.9, 0.05),
+             (128, 128, 8, 1.0, 0.0), (512, 128, 8, 1.0, 0.0), (256, 64, 6, 0.9, 0.05), (5, 6, 3, 1.0, 0.2),
+             (2, 4, 2, 1.0, 0.0), (1, 8, 2, 1.0, 0.0), (33, 17, 5, 1.0, 0.1), (1024, 256, 16, 1.0, 0.0),
+             (7, 200, 16, 1.0, 0.0), (40, 10, 10, 1.0, 0.0)]
+
+
+def _check_bin(L, z, k, alpha, beta, enable):
+    idx = oracle.topk(z, k)["idx"]
+    ref = oracle.affinity_bin(z, idx, alpha, beta, enable)
+    out = L.lynx_affinity_bin(dev(z), dev(idx), alpha, beta, enable)
+    torch.cuda.synchronize()
+    for key in ("new_idx", "cnt_before", "cnt_after", "bin_hist", "num_active"):
+        assert np.array_equal(host(out[key]), ref[key]), key
+    np.testing.assert_allclose(host(out["new_gate"]), ref["new_gate"], rtol=GATE_TOL, atol=1e-7)
+    return ref
+
+
+@pytest.mark.parametrize("T,N,k,s,tail", BIN_CASES)
+def test_affinity_bin(L, T, N, k, s, tail):
+    for alpha, beta in [(2.0, 2), (4.0, 1), (1.0, 3), (0.5, 6), (0.0, 2), (1.0e6, 1)]:
+        if T ** beta >= 2 ** 62:
+            continue
+        for seed, quantum in [(0, None), (1, 0.25)]:               # quantised logits: exact ties and bin-boundary hits
+            _say(f"affinity_bin T={T} N={N} k={k} alpha={alpha} beta={beta} seed={seed} quantum={quantum}")
+            z = wl.make_logits(T, N, seed=seed * 100 + T, zipf_s=s, tail_frac=tail, quantum=quantum)
+            ref = _check_bin(L, z, k, alpha, beta, 1)
+            if T > 1 and alpha > 0:
+                assert ref["num_active"][1] <= ref["num_active"][0]
+    z = wl.make_logits(T, N, seed=3, zipf_s=s, tail_frac=tail)
+    _check_bin(L, z, k, 2.0, 2, 0)                                   # bypass
+
+
+def test_affinity_bin_worked_example(L, golden_w1):
+    z = np.array(golden_w1["logits"], np.float32)
+    idx = np.array(golden_w1["topk_idx"], np.int32)
+    out = L.lynx_affinity_bin(dev(z), dev(idx), 1.0, 2, 1)
+    torch.cuda.synchronize()
+    assert host(out["new_idx"]).tolist() == [[int(v) for v in r] for r in golden_w1["new_idx"]]
+    assert host(out["cnt_after"]).tolist() == [int(v) for v in golden_w1["cnt_after"][0]]
+    assert host(out["num_active"]).tolist() == [4, 2]
+    np.testing.assert_allclose(host(out["new_gate"]), np.array(golden_w1["gate_after"]), atol=6e-6)
+
+
+def test_affinity_bin_is_deterministic(L):
+    z = wl.make_logits(256, 128, seed=9, tail_frac=0.05)
+    idx = dev(oracle.topk(z, 8)["idx"])
+    zd = dev(z)
+    first = {k_: host(v).copy() for k_, v in L.lynx_affinity_bin(zd, idx, 2.0, 2, 1).items()}
+    for _ in range(5):
+        again = L.lynx_affinity_bin(zd, idx, 2.0, 2, 1)
+        torch.cuda.synchronize()
+        for key, v in first.items():
+            assert np.array_equal(host(again[key]), v), key
+
+
+# ------------------------------------------------------------------------------------------------ permute
+
+@pytest.mark.parametrize("T,N,k,seed", [(1, 4, 2, 0), (16, 8, 2, 1), (37, 60, 4, 2), (128, 128, 8, 3), (512, 128, 8, 4),
+                                        (1024, 256, 16, 5), (100, 8, 8, 6), (65, 3, 1, 7)])
+def test_permute(L, T, N, k, seed):
+    _say(f"permute T={T} N={N} k={k}")
+    rng = np.random.default_rng(seed)
+    hot = max(k, N // 3)                                             # leave some experts empty
+    idx = np.stack([rng.permutation(hot)[:k] for _ in range(T)]).astype(np.int32)
+    ref = oracle.permute(idx, N)
+    out = L.lynx_permute(dev(idx), N)
+    torch.cuda.synchronize()
+    for key in ("offsets", "perm", "active", "num_active"):
+        assert np.array_equal(host(out[key]), ref[key]), key
+
+
+# ------------------------------------------------------------------------------------------------ pack + FFN
+
+def test_pack_weights_layout(L):
+    rng = np.random.default_rng(0)
+    E, F, H = 3, 96, 64
+    Wg, Wu = (rng.integers(0, 65536, size=(E, F, H)).astype(np.uint16) for _ in range(2))
+    Wd = rng.integers(0, 65536, size=(E, H, F)).astype(np.uint16)
+    Wgu, Wdp = L.lynx_pack_weights(to_bf16_dev(Wg), to_bf16_dev(Wu), to_bf16_dev(Wd))
+    torch.cuda.synchronize()
+    gu_ref = np.stack([pack_reference(Wg), pack_reference(Wu)], axis=3)          # [E, F/16, H/32, 2, 64, 8]
+    assert np.array_equal(bf16_bits(Wgu), gu_ref)
+    assert np.array_equal(bf16_bits(Wdp), pack_reference(Wd))
+
+
+def _ffn_case(L, T, H, F, N, k, S, Fs, seed, hot=None, std=0.05):
+    rng = np.random.default_rng(seed)
+    x = wl.f32_to_bf16_bits(rng.standard_normal((T, H)).astype(np.float32))
+    Wg, Wu, Wd = wl.bf16_normal(rng, (N, F, H), std), wl.bf16_normal(rng, (N, F, H), std), wl.bf16_normal(rng, (N, H, F), std)
+    Sg = Su = Sd = None
+    if S:
+        Sg, Su, Sd = (wl.bf16_normal(rng, (S, Fs, H), std), wl.bf16_normal(rng, (S, Fs, H), std),
+                      wl.bf16_normal(rng, (S, H, Fs), std))
+    hot = hot or N
+    idx = np.stack([rng.permutation(hot)[:k] for _ in range(T)]).astype(np.int32)
+    gate = rng.random((T, k)).astype(np.float32) + 0.1
+    gate /= gate.sum(1, keepdims=True)
+    y_ref = oracle.moe_ffn(x, Wg, Wu, Wd, idx, gate.astype(np.float64), Sg, Su, Sd)
+    Wgu, Wdp = L.lynx_pack_weights(to_bf16_dev(Wg), to_bf16_dev(Wu), to_bf16_dev(Wd))
+    Sgu = Sdp = None
+    if S:
+        Sgu, Sdp = L.lynx_pack_weights(to_bf16_dev(Sg), to_bf16_dev(Su), to_bf16_dev(Sd))
+    idx_d = dev(idx)
+    p = L.lynx_permute(idx_d, N)
+    y = L.lynx_moe_ffn(to_bf16_dev(x), Wgu, Wdp, idx_d, dev(gate), p, N, F, Sgu, Sdp, S, Fs)
+    torch.cuda.synchronize()
+    err = row_rel_err(host(y), y_ref)
+    assert np.all(np.isfinite(host(y)))
+    assert err.max() <= Y_TOL, f"max row error {err.max():.3e}"
+    return err.max()
+
+
+FFN_CASES = [
+    # T,   H,   F,  N, k, S, Fs, hot     what it covers
+    (16, 512, 1024, 8, 2, 0, 0, None),   # the tiny configuration's shapes
+    (1, 256, 320, 4, 2, 0, 0, None),     # single token; F/64 ragged (5 row tiles per workgroup column)
+    (40, 256, 352, 4, 2, 0, 0, 2),       # 40 tokens on each of 2 experts (3 token tiles); K = 352: ragged last chunk
+    (100, 128, 224, 6, 3, 1, 160, 3),    # 100 tokens per expert (8 token tiles) + one shared expert
+    (300, 128, 96, 4, 2, 2, 64, 2),      # 300 tokens per expert: more than one 128-token block; two shared experts
+    (7, 64, 32, 3, 3, 0, 0, None),       # k = N, smallest allowed F
+    (64, 2048, 768, 16, 8, 0, 0, None),  # Qwen3-like row / column sizes
+]
+
+
+@pytest.mark.parametrize("T,H,F,N,k,S,Fs,hot", FFN_CASES)
+def test_moe_ffn(L, T, H, F, N, k, S, Fs, hot):
+    _say(f"moe_ffn T={T} H={H} F={F} N={N} k={k} shared={S}x{Fs} hot={hot}")
+    e = _ffn_case(L, T, H, F, N, k, S, Fs, seed=T + F, hot=hot)
+    _say(f"  max row rel err {e:.3e}")
+
+
+def test_moe_ffn_skips_invalid_pairs_without_fault(L):
+    # an index outside [0,N) is documented as "pair skipped": the call must stay in bounds and finite
+    rng = np.random.default_rng(4)
+    T, H, F, N, k = 8, 64, 64, 4, 2
+    x = wl.f32_to_bf16_bits(rng.standard_normal((T, H)).astype(np.float32))
+    Wg, Wu, Wd = wl.bf16_normal(rng, (N, F, H), 0.05), wl.bf16_normal(rng, (N, F, H), 0.05), wl.bf16_normal(rng, (N, H, F), 0.05)
+    idx = np.stack([rng.permutation(N)[:k] for _ in range(T)]).astype(np.int32)
+    gate = np.full((T, k), 0.5, np.float32)
+    bad = idx.copy()
+    bad[2, 1] = -1
+    bad[5, 0] = N + 3
+    Wgu, Wdp = L.lynx_pack_weights(to_bf16_dev(Wg), to_bf16_dev(Wu), to_bf16_dev(Wd))
+    p = L.lynx_permute(dev(bad), N)
+    y = host(L.lynx_moe_ffn(to_bf16_dev(x), Wgu, Wdp, dev(bad), dev(gate), p, N, F))
+    torch.cuda.synchronize()
+    assert np.all(np.isfinite(y))
+    g2 = gate.astype(np.float64).copy()
+    g2[2, 1] = 0.0
+    g2[5, 0] = 0.0
+    good = np.where((bad < 0) | (bad >= N), 0, bad)                     # zero gate: the stand-in expert does not matter
+    y_ref = oracle.moe_ffn(x, Wg, Wu, Wd, good.astype(np.int32), g2)
+    assert row_rel_err(y, y_ref).max() <= Y_TOL
+
+
+# ------------------------------------------------------------------------------------------------ whole layer
+
+def _layer_case(L, cfg, T, alpha, beta, enable, data=None):
+    d = data or wl.make_layer(cfg, T)
+    x, Wr, bias = to_bf16_dev(d["x"]), dev(d["Wr"]), dev(d["bias"])
+    Wgu, Wdp = L.lynx_pack_weights(to_bf16_dev(d["Wg"]), to_bf16_dev(d["Wu"]), to_bf16_dev(d["Wd"]))
+    Sgu = Sdp = None
+    if cfg.n_shared:
+        Sgu, Sdp = L.lynx_pack_weights(to_bf16_dev(d["Sg"]), to_bf16_dev(d["Su"]), to_bf16_dev(d["Sd"]))
+    b = L.lynx_moe_layer(x, Wr, bias, Wgu, Wdp, cfg.F, cfg.k, alpha, beta, enable, Sgu, Sdp, cfg.n_shared, cfg.F_shared)
+    torch.cuda.synchronize()
+    # router: logits against the oracle's own; everything downstream on the GPU's logits (identical on both sides)
+    r = oracle.route(d["x"], d["Wr"], d["bias"], cfg.k)
+    z = host(b.logits)
+    assert np.all(np.abs(z - r["logits"]) <= LOGIT_TOL * np.maximum(1.0, np.abs(r["logits"])))
+    tk = oracle.topk(z, cfg.k)
+    assert np.array_equal(host(b.topk_idx), tk["idx"])
+    a = oracle.affinity_bin(z, tk["idx"], alpha, beta, enable)
+    for key, got in (("new_idx", b.new_idx), ("cnt_before", b.cnt_before), ("cnt_after", b.cnt_after),
+                     ("bin_hist", b.bin_hist), ("num_active", b.num_active)):
+        assert np.array_equal(host(got), a[key]), key
+    np.testing.assert_allclose(host(b.new_gate), a["new_gate"], rtol=GATE_TOL, atol=1e-7)
+    p = oracle.permute(a["new_idx"], cfg.N)
+    for key, got in (("offsets", b.offsets), ("perm", b.perm), ("active", b.active), ("num_active", b.num_active_perm)):
+        assert np.array_equal(host(got), p[key]), key
+    y_ref = oracle.moe_ffn(d["x"], d["Wg"], d["Wu"], d["Wd"], a["new_idx"], a["new_gate"], d["Sg"], d["Su"], d["Sd"])
+    err = row_rel_err(host(b.y), y_ref)
+    assert err.max() <= Y_TOL, f"max row error {err.max():.3e}"
+    return a["num_active"], err.max()
+
+
+@pytest.mark.parametrize("preset,enable", [("moderate", 1), ("aggressive", 1), ("moderate", 0)])
+def test_layer_tiny_config(L, preset, enable):
+    cfg = wl.CONFIGS["tiny"]
+    alpha, beta = wl.PRESETS[preset]
+    na, err = _layer_case(L, cfg, 16, alpha, beta, enable)
+    _say(f"tiny layer {preset} enable={enable}: invoked {na.tolist()}, max row err {err:.3e}")
+
+
+@pytest.mark.parametrize("name,T", [("qwen15moe", 8), ("dsv2lite", 16)])
+def test_layer_small_shared_expert_configs(L, name, T):
+    # real row/column sizes of the shared-expert families with the expert count cut down so the oracle finishes in seconds
+    import dataclasses
+    cfg = dataclasses.replace(wl.CONFIGS[name], N=12)
+    alpha, beta = wl.PRESETS["aggressive"]
+    na, err = _layer_case(L, cfg, T, alpha, beta, 1)
+    _say(f"{name}-shaped (N=12) layer T={T}: invoked {na.tolist()}, max row err {err:.3e}")
+
+
+def test_layer_zero_tokens(L):
+    cfg = wl.CONFIGS["tiny"]
+    d = wl.make_layer(cfg, 0)
+    Wgu, Wdp = L.lynx_pack_weights(to_bf16_dev(d["Wg"]), to_bf16_dev(d["Wu"]), to_bf16_dev(d["Wd"]))
+    x = torch.empty((0, cfg.H), dtype=torch.bfloat16, device="cuda")
+    b = L.lynx_moe_layer(x, dev(d["Wr"]), dev(d["bias"]), Wgu, Wdp, cfg.F, cfg.k, 2.0, 2, 1)
+    torch.cuda.synchronize()
+    assert host(b.num_active).tolist() == [0, 0] and host(b.num_active_perm).tolist() == [0]
+    assert np.all(host(b.offsets) == 0) and np.all(host(b.active) == -1)
