@@ -1,0 +1,223 @@
+#!/usr/bin/env python3
+"""Benchmark of the Lynx MoE decode layer on one MI355X.
+
+A step = one pass of the whole hot path (lynx_route -> lynx_affinity_bin -> lynx_permute ->
+lynx_moe_ffn) over one decode batch of a synthetic Mixtral-8x7B-shaped layer (hidden 4096, FFN 14336,
+8 experts, top-2, bf16 weights), inputs already resident in HBM.  Prints ONE JSON line: the headline
+us/batch, the HBM roofline of the dominant kernel (gate/up weight stream) measured with HIP events
+around that kernel inside the timed steps, a sweep over the configuration's batch sizes with the
+remap off / on, and the CPU oracle timed on the host cores as a reported baseline.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config mixtral] [--tokens 8] [--preset aggressive]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", default="mixtral", choices=["tiny", "mixtral", "qwen15moe", "dsv2lite", "qwen3"])
+    ap.add_argument("--tokens", type=int, default=8)
+    ap.add_argument("--preset", default="aggressive", choices=["moderate", "aggressive", "off"])
+    ap.add_argument("--no-sweep", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sweep-iters", type=int, default=10)
+    return ap.parse_args()
+
+
+def expert_bytes(cfg, n_routed):
+    """Algorithmic expert-weight bytes of one layer pass: gate/up part and down part."""
+    gu = n_routed * 2 * cfg.H * cfg.F * 2 + cfg.n_shared * 2 * cfg.H * cfg.F_shared * 2
+    dn = n_routed * cfg.H * cfg.F * 2 + cfg.n_shared * cfg.H * cfg.F_shared * 2
+    return gu, dn
+
+
+class Layer:
+    """Device-resident inputs and packed weights of one synthetic layer, plus per-T buffers."""
+
+    def __init__(self, cfg, T_gen, keep_row_major=False):
+        import torch
+
+        import paper_2411_08982_amd as L
+        import workloads as wl
+        self.L, self.cfg, self.torch, self.wl = L, cfg, torch, wl
+        d = wl.make_layer_device(cfg, T_gen, "cuda")
+        self.Wr, self.bias = d["Wr"], d["bias"]
+        self.Wgu, self.Wdp = L.lynx_pack_weights(d["Wg"], d["Wu"], d["Wd"])
+        self.Sgu = self.Sdp = None
+        if cfg.n_shared:
+            self.Sgu, self.Sdp = L.lynx_pack_weights(d["Sg"], d["Su"], d["Sd"])
+        torch.cuda.synchronize()
+        self.row_major = {k: d[k] for k in ("Wg", "Wu", "Wd", "Sg", "Su", "Sd")} if keep_row_major else None
+        self.x = {T_gen: d["x"]}
+        self.buf = {}
+
+    def tokens(self, T):
+        if T not in self.x:
+            import numpy as np
+            xb = self.wl.make_tokens(self.cfg, T, self.Wr.cpu().numpy(), self.bias.cpu().numpy())
+            self.x[T] = self.torch.from_numpy(xb.view(np.int16)).cuda().view(self.torch.bfloat16)
+        return self.x[T]
+
+    def buffers(self, T, beta):
+        key = (T, beta)
+        if key not in self.buf:
+            c = self.cfg
+            self.buf[key] = self.L.LayerBuffers(T, c.H, c.F, c.N, c.k, beta, c.n_shared, c.F_shared)
+        return self.buf[key]
+
+    def step(self, T, alpha, beta, enable, events=None):
+        """The four C-ABI calls of one decode step on the current stream."""
+        L, c = self.L, self.cfg
+        b = self.buffers(T, beta)
+        x = self.tokens(T)
+        r = dict(logits=b.logits, idx=b.topk_idx, gate=b.topk_gate, psum=b.topk_psum)
+        L.lynx_route(x, self.Wr, self.bias, c.k, out=r)
+        a = dict(new_idx=b.new_idx, new_gate=b.new_gate, cnt_before=b.cnt_before, cnt_after=b.cnt_after,
+                 bin_hist=b.bin_hist, num_active=b.num_active)
+        L.lynx_affinity_bin(b.logits, b.topk_idx, alpha, beta, enable, workspace=b.workspace, out=a)
+        p = dict(offsets=b.offsets, perm=b.perm, active=b.active, num_active=b.num_active_perm)
+        L.lynx_permute(b.new_idx, c.N, out=p)
+        L.lynx_moe_ffn(x, self.Wgu, self.Wdp, b.new_idx, b.new_gate, p, c.N, c.F, self.Sgu, self.Sdp, c.n_shared,
+                       c.F_shared, workspace=b.workspace, y=b.y, stage_events=events)
+        return b
+
+
+def preset_args(wl, preset):
+    if preset == "off":
+        return 2.0, 2, 0
+    a, b = wl.PRESETS[preset]
+    return a, b, 1
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print(f"bench.py: this build runs on one GPU only (no collectives, no sharding); --gpus {args.gpus} is not "
+              "supported. Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+    import torch
+
+    import workloads as wl
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    cfg = wl.CONFIGS[args.config]
+    T = args.tokens
+    alpha, beta, enable = preset_args(wl, args.preset)
+    layer = Layer(cfg, T, keep_row_major=not args.no_cpu_baseline)
+
+    K, W = args.steps, args.warmup
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(K)]
+    for evs in events:           # a first record creates the underlying hipEvent_t handles
+        for e in evs:
+            e.record()
+    for _ in range(W):
+        layer.step(T, alpha, beta, enable)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(K):
+        b = layer.step(T, alpha, beta, enable, events[i])
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt * 1e3 / K
+    gu_ms = sum(e[0].elapsed_time(e[1]) for e in events) / K
+    dn_ms = sum(e[1].elapsed_time(e[2]) for e in events) / K
+    cb_ms = sum(e[2].elapsed_time(e[3]) for e in events) / K
+    n_before, n_after = (int(v) for v in b.num_active.cpu().tolist())
+    gu_bytes, dn_bytes = expert_bytes(cfg, n_after)
+    gu_gbps = gu_bytes / (gu_ms * 1e-3) / 1e9
+    ffn_gbps = (gu_bytes + dn_bytes) / ((gu_ms + dn_ms) * 1e-3) / 1e9
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get(f"{args.config}_T{T}_{args.preset}")
+        except Exception:
+            traffic = None
+
+    out = {
+        "metric": "MoE-layer decode us/batch",
+        "value": round(ms_per_step * 1e3, 2),
+        "unit": "us/batch",
+        "n_gpus": 1,
+        "steps": K,
+        "warmup": W,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"{cfg.name}-shaped MoE layer: hidden {cfg.H}, FFN {cfg.F}, {cfg.N} experts top-{cfg.k}, "
+                               f"{cfg.n_shared} shared, bf16 weights, {T} decode tokens, remap {args.preset}",
+                   "tokens": T, "alpha": alpha, "beta": beta, "remap": bool(enable)},
+        "tokens_per_s": round(T / (ms_per_step * 1e-3), 1),
+        "experts_invoked": {"before": n_before, "after": n_after},
+        "expert_weight_hbm_GBps": round(ffn_gbps, 1),
+        "stage_us": {"gate_up": round(gu_ms * 1e3, 2), "down": round(dn_ms * 1e3, 2), "combine": round(cb_ms * 1e3, 2),
+                     "route_bin_permute_and_gaps": round((ms_per_step - gu_ms - dn_ms - cb_ms) * 1e3, 2)},
+        "roofline": {"bound": "hbm", "kernel": "expert_gemm_kernel<true> (gate/up weight stream)",
+                     "achieved": round(gu_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(gu_gbps / HBM_PEAK_GBPS, 4), "traffic": traffic,
+                     "bytes_per_launch": gu_bytes, "avg_launch_us": round(gu_ms * 1e3, 2)},
+    }
+
+    if not args.no_sweep:
+        sweep = []
+        for Ts in cfg.batches:
+            for preset in ("off", "moderate", "aggressive"):
+                a_, b_, en_ = preset_args(wl, preset)
+                for _ in range(3):
+                    layer.step(Ts, a_, b_, en_)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                torch.cuda.synchronize()
+                e0.record()
+                for _ in range(args.sweep_iters):
+                    bb = layer.step(Ts, a_, b_, en_)
+                e1.record()
+                torch.cuda.synchronize()
+                us = e0.elapsed_time(e1) * 1e3 / args.sweep_iters
+                nb, na = (int(v) for v in bb.num_active.cpu().tolist())
+                g, d_ = expert_bytes(cfg, na)
+                sweep.append({"tokens": Ts, "remap": preset, "us": round(us, 1), "invoked_before": nb, "invoked_after": na,
+                              "expert_weight_GBps": round((g + d_) / (us * 1e-6) / 1e9, 1),
+                              "hbm_frac": round((g + d_) / (us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4)})
+        out["sweep"] = sweep
+
+    if not args.no_cpu_baseline:
+        import numpy as np
+
+        import oracle
+        bits = lambda t: None if t is None else t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+        rm = {k_: bits(v) for k_, v in layer.row_major.items()}
+        xh = bits(layer.tokens(T))
+        Wr, bias = layer.Wr.cpu().numpy(), layer.bias.cpu().numpy()
+        t0 = time.perf_counter()
+        o = oracle.moe_layer(xh, Wr, bias, rm["Wg"], rm["Wu"], rm["Wd"], cfg.k, alpha, beta, enable, rm["Sg"], rm["Su"],
+                             rm["Sd"])
+        cpu_s = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round(cpu_s * 1e6, 1), "unit": "us/batch", "cores": oracle.num_threads(),
+                               "kind": "oracle",
+                               "sample": f"one full layer pass of the same workload ({T} tokens, all invoked experts), "
+                                         "1 repetition, plain C fp64 oracle with an OpenMP split over weight rows",
+                               "experts_invoked": [int(v) for v in o["bin"]["num_active"]]}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

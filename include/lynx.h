@@ -119,6 +119,18 @@ int lynx_moe_ffn(const uint16_t *x_bf16, const uint16_t *Wgu_packed, const uint1
                  float *y, void *workspace, void *stream);
 
 /*
+ * lynx_moe_ffn with stage timing for measurement (roofline of the weight-streaming kernels): the same
+ * work, and additionally records the caller's events on `stream`.  stage_events: HOST array of four
+ * hipEvent_t (entries may be NULL) recorded before the gate/up kernel, after it, after the down kernel,
+ * and after the combine.  stage_events == NULL is exactly lynx_moe_ffn.
+ */
+int lynx_moe_ffn_timed(const uint16_t *x_bf16, const uint16_t *Wgu_packed, const uint16_t *Wd_packed,
+                       const uint16_t *Sgu_packed, const uint16_t *Sd_packed, int n_shared, int F_shared,
+                       const int32_t *idx, const float *gate, const int32_t *expert_offsets, const int32_t *perm,
+                       const int32_t *active_experts, const int32_t *num_active, int T, int H, int F, int N, int k,
+                       float *y, void *workspace, void *stream, void *const *stage_events);
+
+/*
  * The whole decode step of one MoE layer: lynx_route, lynx_affinity_bin, lynx_permute, lynx_moe_ffn
  * chained on `stream` with the argument meanings above.  All intermediate arrays are outputs.
  */

@@ -20,7 +20,7 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_HIP = 0, -1, -2, -3
 MAX_T, MAX_N, MAX_K, MAX_BETA = 1024, 256, 16, 6
 
 SYMBOLS = ["lynx_last_error", "lynx_workspace_bytes", "lynx_route", "lynx_affinity_bin", "lynx_permute",
-           "lynx_pack_weights", "lynx_moe_ffn", "lynx_moe_layer"]
+           "lynx_pack_weights", "lynx_moe_ffn", "lynx_moe_ffn_timed", "lynx_moe_layer"]
 
 
 class LynxError(RuntimeError):
@@ -50,6 +50,7 @@ def lib():
         L.lynx_permute.argtypes = [P, I, I, I, P, P, P, P, P]
         L.lynx_pack_weights.argtypes = [P, P, P, I, I, I, P, P, P]
         L.lynx_moe_ffn.argtypes = [P, P, P, P, P, I, I, P, P, P, P, P, P, I, I, I, I, I, P, P, P]
+        L.lynx_moe_ffn_timed.argtypes = L.lynx_moe_ffn.argtypes + [ctypes.POINTER(c_void_p)]
         L.lynx_moe_layer.argtypes = [P, P, P, P, P, P, P, I, I, I, I, I, I, I, F, I, I] + [P] * 17
         for name in SYMBOLS[2:]:
             getattr(L, name).restype = c_int
@@ -145,8 +146,10 @@ def lynx_pack_weights(Wg, Wu, Wd):
 
 
 def lynx_moe_ffn(x, Wgu, Wdp, idx, gate, perm_out, N, F, Sgu=None, Sdp=None, n_shared=0, F_shared=0, workspace=None,
-                 y=None):
-    """x [T,H] bf16, packed weights, idx/gate [T,k], perm_out = result of lynx_permute -> y [T,H] f32."""
+                 y=None, stage_events=None):
+    """x [T,H] bf16, packed weights, idx/gate [T,k], perm_out = result of lynx_permute -> y [T,H] f32.
+    stage_events: optional list of four torch.cuda.Event(enable_timing=True) that have been recorded at
+    least once (so that their handles exist); they are re-recorded at the stage boundaries."""
     T, H = x.shape
     k = idx.shape[1]
     if workspace is None:
@@ -156,11 +159,16 @@ def lynx_moe_ffn(x, Wgu, Wdp, idx, gate, perm_out, N, F, Sgu=None, Sdp=None, n_s
         raise ValueError(f"workspace too small: {workspace.numel()} < {need}")
     if y is None:
         y = torch.empty((T, H), dtype=F32, device=x.device)
-    _check(lib().lynx_moe_ffn(_ptr(x, BF16, "x"), _ptr(Wgu, BF16, "Wgu"), _ptr(Wdp, BF16, "Wdp"), _ptr(Sgu, BF16, "Sgu"),
-                              _ptr(Sdp, BF16, "Sdp"), n_shared, F_shared, _ptr(idx, I32, "idx"), _ptr(gate, F32, "gate"),
-                              _ptr(perm_out["offsets"], I32, "offsets"), _ptr(perm_out["perm"], I32, "perm"),
-                              _ptr(perm_out["active"], I32, "active"), _ptr(perm_out["num_active"], I32, "num_active"),
-                              T, H, F, N, k, _ptr(y, F32, "y"), workspace.data_ptr(), _stream()))
+    args = (_ptr(x, BF16, "x"), _ptr(Wgu, BF16, "Wgu"), _ptr(Wdp, BF16, "Wdp"), _ptr(Sgu, BF16, "Sgu"),
+            _ptr(Sdp, BF16, "Sdp"), n_shared, F_shared, _ptr(idx, I32, "idx"), _ptr(gate, F32, "gate"),
+            _ptr(perm_out["offsets"], I32, "offsets"), _ptr(perm_out["perm"], I32, "perm"),
+            _ptr(perm_out["active"], I32, "active"), _ptr(perm_out["num_active"], I32, "num_active"),
+            T, H, F, N, k, _ptr(y, F32, "y"), workspace.data_ptr(), _stream())
+    if stage_events is None:
+        _check(lib().lynx_moe_ffn(*args))
+    else:
+        ev = (c_void_p * 4)(*[e.cuda_event for e in stage_events])
+        _check(lib().lynx_moe_ffn_timed(*args, ev))
     return y
 
 

@@ -5,14 +5,19 @@
 // of experts the batch activates), so the kernels are organised around the weight stream:
 //   * weights are pre-packed so that a wave reads a 16-row x 32-column bf16 tile as one contiguous
 //     1 KiB load (16 bytes per lane) that IS the A operand of v_mfma_f32_16x16x32_bf16;
-//   * a wave owns 16 output rows and walks the whole contraction dimension, keeping a ring of
+//   * a wave owns 16 output rows and walks (a slice of) the contraction dimension with a ring of
 //     prefetched tiles in registers, so each weight byte is fetched from HBM once per call;
-//   * the (few) tokens of the expert are the B operand: staged through LDS in K-chunks, double
-//     buffered, shared by the four waves of the workgroup;
-//   * a workgroup = (invoked expert, 64 output rows).  The grid is fixed (N experts + shared experts);
-//     workgroups whose rank is past the device-side num_active leave at once, so nothing is read
-//     back to the host.
-// Two launches (gate/up with the SiLU-multiply epilogue, then down) and a small combine.
+//   * the tokens of the expert are the B operand.  Experts with few tokens (<= 16, the usual decode
+//     case) read the token columns straight from global memory in MFMA layout ("direct" kernel: no
+//     LDS, no barrier in the loop); experts with many tokens stage the token tile through LDS, shared
+//     by four row tiles ("staged" kernel);
+//   * the grid is fixed (N experts + shared experts, times row tiles); a workgroup whose rank is past
+//     the device-side num_active, or whose expert belongs to the other kernel, leaves at once, so
+//     nothing is read back to the host.
+// Launches: direct gate/up (+ staged gate/up if the batch can have an expert with > 16 tokens), the
+// same for down, and a small combine.
+#include <stdlib.h>
+
 #include "lynx_common.h"
 
 namespace lynx {
@@ -22,11 +27,11 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kFfnThreads = 256;
 constexpr int kFfnWaves = kFfnThreads / kWave;
-constexpr int kRowsPerWG = 16 * kFfnWaves;   // output rows per workgroup
-constexpr int kNTMax = 8;                    // token tiles (of 16) held in accumulators at once
-constexpr int kTokBlock = 16 * kNTMax;
 constexpr int kPF = 8;                       // weight tiles in flight per wave and matrix
-constexpr int kStageBytes = 2 * 18432;       // two LDS buffers for the token tile
+constexpr int kDirectMaxTokens = 16;         // experts with more tokens go to the staged kernel
+constexpr int kStagedNT = 8;                 // token tiles (of 16) per pass of the staged kernel
+constexpr int kTokBlock = 16 * kStagedNT;
+constexpr int kStageBytes = 2 * 18432;       // two LDS buffers for the staged token tile
 
 struct GemmParams {
     const uint16_t *W_routed;   // packed routed weights (gate/up interleaved, or down)
@@ -42,6 +47,88 @@ struct GemmParams {
     long long shared_h_base;    // element offset of the shared experts' h rows in the h scratch
 };
 
+// What a workgroup works on, resolved from blockIdx and the device-side routing tables.
+struct WorkItem {
+    const uint4 *W;      // packed weights of the expert
+    const uint16_t *B;   // B-operand rows
+    void *out;
+    int R, K, tile, Te, off, shared_s;
+    bool valid;
+};
+
+template <bool DUAL>
+__device__ __forceinline__ WorkItem resolve_work(const GemmParams &p)
+{
+    WorkItem w;
+    w.valid = false;
+    w.off = 0;
+    w.shared_s = -1;
+    w.B = p.B;
+    w.out = p.out;
+    const int b = blockIdx.x;
+    const int P = p.T * p.k;
+    const uint16_t *Wbase;
+    if (b < p.routed_blocks) {
+        const int rank = b / p.tiles_r;
+        w.tile = b % p.tiles_r;
+        const int na = min(*p.num_active, p.N);
+        if (rank >= na) return w;
+        const int e = p.active[rank];
+        if (e < 0 || e >= p.N) return w;
+        w.off = p.offsets[e];
+        w.Te = p.offsets[e + 1] - w.off;
+        if (w.off < 0 || w.Te <= 0 || w.off + w.Te > P) return w;
+        w.R = p.R;
+        w.K = p.K;
+        Wbase = p.W_routed + (size_t)e * ((size_t)w.R * w.K * (DUAL ? 2 : 1));
+    } else {
+        const int bs = b - p.routed_blocks;
+        w.shared_s = bs / p.tiles_s;
+        w.tile = bs % p.tiles_s;
+        if (w.shared_s >= p.n_shared || p.T <= 0) return w;
+        w.Te = p.T;
+        w.R = p.Rs;
+        w.K = p.Ks;
+        Wbase = p.W_shared + (size_t)w.shared_s * ((size_t)w.R * w.K * (DUAL ? 2 : 1));
+        // shared experts keep their h rows in their own region of the scratch
+        const size_t hbase = (size_t)p.shared_h_base + (size_t)w.shared_s * p.T * (DUAL ? w.R : w.K);
+        if (DUAL)
+            w.out = reinterpret_cast<uint16_t *>(p.out) + hbase;
+        else
+            w.B = p.B + hbase;
+    }
+    w.W = reinterpret_cast<const uint4 *>(Wbase);
+    w.valid = true;
+    return w;
+}
+
+// B row (element offset) and output row of the i-th token of the work item; -1 = none.
+template <bool DUAL>
+__device__ __forceinline__ void token_rows(const GemmParams &p, const WorkItem &w, int i, int &ro, int &orow)
+{
+    ro = -1;
+    orow = -1;
+    if (i >= w.Te) return;
+    const int P = p.T * p.k;
+    if (w.shared_s < 0) {
+        const int pv = p.perm[w.off + i];
+        if (pv < 0 || pv >= P) return;
+        if (DUAL) {   // B row = x[token], out row = sorted position in h
+            ro = (pv / p.k) * w.K;
+            orow = w.off + i;
+        } else {      // B row = h[sorted position], out row = pair id in o
+            ro = (w.off + i) * w.K;
+            orow = pv;
+        }
+    } else if (DUAL) {   // shared: every token
+        ro = i * w.K;
+        orow = i;
+    } else {
+        ro = i * w.K;
+        orow = P + w.shared_s * p.T + i;
+    }
+}
+
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
 {
     uint32_t u = __float_as_uint(f);
@@ -50,221 +137,309 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
 }
 
 __device__ __forceinline__ float silu_mul(float g, float u) { return (g / (1.0f + __expf(-g))) * u; }
+__device__ __forceinline__ uint4 zero4() { return make_uint4(0u, 0u, 0u, 0u); }
+__device__ __forceinline__ uint4 sel4(bool keep, uint4 v) { return keep ? v : zero4(); }
 
-// One pass over the contraction dimension for NT token tiles.  KS = k-steps (of 32 columns) per LDS
-// chunk.  Wt points at this wave's row tile (uint4 units), or the wave is idle (rows past R).
-template <bool DUAL, int NT, int KS>
-__device__ __forceinline__ void stream_rows(const uint4 *__restrict__ Wt, bool wave_active, int KT, int K,
-                                            const uint16_t *__restrict__ B, const int *rowoff, char *stage,
-                                            f32x4 (&accg)[NT], f32x4 (&accu)[NT])
+template <int NT>
+__device__ __forceinline__ void clear_acc(f32x4 (&accg)[NT], f32x4 (&accu)[NT])
 {
-    constexpr int ROWB = KS * 64 + 16;           // LDS bytes per token row (+16: conflict-free 16-byte reads)
-    constexpr int BUFB = NT * 16 * ROWB;
-    static_assert(2 * BUFB <= kStageBytes, "token tile does not fit the LDS stage");
-    constexpr int PIECES = NT * 16 * KS * 4;     // 16-byte pieces per chunk
-    constexpr int PPT = (PIECES + kFfnThreads - 1) / kFfnThreads;
-    constexpr int U = KS > kPF ? KS : kPF;
-    constexpr int WSTEP = DUAL ? 2 * kWave : kWave;   // uint4 per k-step
-
-    const int tid = threadIdx.x, lane = lane_id();
-    const int nchunks = (KT + KS - 1) / KS;
-    uint4 xr[PPT];
-
-    auto load_x = [&](int c) {
-#pragma unroll
-        for (int i = 0; i < PPT; ++i) {
-            const int q = tid + kFfnThreads * i;
-            uint4 val = make_uint4(0u, 0u, 0u, 0u);
-            if (q < PIECES) {
-                const int row = q / (KS * 4), pc = q % (KS * 4);
-                const int col = c * KS * 32 + pc * 8;
-                const int ro = rowoff[row];
-                if (ro >= 0 && col < K) val = *reinterpret_cast<const uint4 *>(B + (size_t)ro + col);
-            }
-            xr[i] = val;
-        }
-    };
-    auto store_x = [&](int c) {
-        char *buf = stage + (c & 1) * BUFB;
-#pragma unroll
-        for (int i = 0; i < PPT; ++i) {
-            const int q = tid + kFfnThreads * i;
-            if (q < PIECES) {
-                const int row = q / (KS * 4), pc = q % (KS * 4);
-                *reinterpret_cast<uint4 *>(buf + row * ROWB + pc * 16) = xr[i];
-            }
-        }
-    };
-
-    uint4 wg[kPF], wu[kPF];
-#pragma unroll
-    for (int j = 0; j < kPF; ++j) {
-        wg[j] = make_uint4(0u, 0u, 0u, 0u);
-        wu[j] = make_uint4(0u, 0u, 0u, 0u);
-        if (wave_active && j < KT) {
-            wg[j] = Wt[(size_t)j * WSTEP + lane];
-            if (DUAL) wu[j] = Wt[(size_t)j * WSTEP + kWave + lane];
-        }
-    }
-    load_x(0);
-    store_x(0);
-    __syncthreads();
-
-    const int brow = (lane & 15) * ROWB + (lane >> 4) * 16;   // this lane's B-fragment offset inside a token tile
-    for (int s0 = 0; s0 < KT; s0 += U) {
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int s = s0 + u;
-            if (s < KT) {
-                const int c = s / KS;
-                if (u % KS == 0 && c + 1 < nchunks) load_x(c + 1);
-                if (wave_active) {
-                    const bf16x8 ag = __builtin_bit_cast(bf16x8, wg[u % kPF]);
-                    const bf16x8 au = __builtin_bit_cast(bf16x8, wu[u % kPF]);
-                    if (s + kPF < KT) {
-                        wg[u % kPF] = Wt[(size_t)(s + kPF) * WSTEP + lane];
-                        if (DUAL) wu[u % kPF] = Wt[(size_t)(s + kPF) * WSTEP + kWave + lane];
-                    }
-                    const char *buf = stage + (c & 1) * BUFB + brow + (u % KS) * 64;
-#pragma unroll
-                    for (int nt = 0; nt < NT; ++nt) {
-                        const bf16x8 b = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(buf + nt * 16 * ROWB));
-                        accg[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ag, b, accg[nt], 0, 0, 0);
-                        if (DUAL) accu[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(au, b, accu[nt], 0, 0, 0);
-                    }
-                }
-                if (u % KS == KS - 1 || s == KT - 1) {
-                    if (c + 1 < nchunks) store_x(c + 1);
-                    __syncthreads();
-                }
-            }
-        }
-    }
-}
-
-// Handles one block of up to 16*NT tokens of the workgroup's expert: stream, then epilogue.
-template <bool DUAL, int NT, int KS>
-__device__ __forceinline__ void expert_block(const uint4 *Wt, bool wave_active, int R, int K, const uint16_t *B,
-                                             void *out, int row0, const int *rowoff, const int *outrow, char *stage)
-{
-    f32x4 accg[NT], accu[NT];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
         accg[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
         accu[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
-    stream_rows<DUAL, NT, KS>(Wt, wave_active, K / 32, K, B, rowoff, stage, accg, accu);
-    if (!wave_active) return;
-    // D fragment: lane holds token column (lane & 15), output rows 4*(lane >> 4) .. +3 of the wave's 16
-    const int lane = lane_id();
-    const int r = row0 + 4 * (lane >> 4);
+}
+
+// D fragment of v_mfma_f32_16x16x32: lane holds token column (lane & 15) and output rows
+// 4*(lane >> 4) .. +3 of the wave's 16.  gate/up: h = silu(g) * u rounded to bf16; down: fp32.
+template <bool DUAL, int NT>
+__device__ __forceinline__ void epilogue(const f32x4 (&accg)[NT], const f32x4 (&accu)[NT], void *out, int R, int row0,
+                                         const int (&orow)[NT])
+{
+    const int r = row0 + 4 * (lane_id() >> 4);
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
-        const int orow = outrow[nt * 16 + (lane & 15)];
-        if (orow < 0) continue;
+        if (orow[nt] < 0) continue;
         if (DUAL) {
             uint2 pk;
             pk.x = (uint32_t)f32_to_bf16_rne(silu_mul(accg[nt][0], accu[nt][0])) |
                    ((uint32_t)f32_to_bf16_rne(silu_mul(accg[nt][1], accu[nt][1])) << 16);
             pk.y = (uint32_t)f32_to_bf16_rne(silu_mul(accg[nt][2], accu[nt][2])) |
                    ((uint32_t)f32_to_bf16_rne(silu_mul(accg[nt][3], accu[nt][3])) << 16);
-            *reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(out) + (size_t)orow * R + r) = pk;
+            *reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(out) + (size_t)orow[nt] * R + r) = pk;
         } else {
-            *reinterpret_cast<float4 *>(reinterpret_cast<float *>(out) + (size_t)orow * R + r) =
+            *reinterpret_cast<float4 *>(reinterpret_cast<float *>(out) + (size_t)orow[nt] * R + r) =
                 make_float4(accg[nt][0], accg[nt][1], accg[nt][2], accg[nt][3]);
         }
     }
 }
 
-template <bool DUAL>
-__global__ __launch_bounds__(kFfnThreads, 2) void expert_gemm_kernel(GemmParams p)
+// ---------------------------------------------------------------------------------------------------
+// Weight streaming.  Both kernels keep a ring of kPF prefetched 1 KiB weight tiles per wave and matrix
+// in registers.  The loop bodies are branch-free on purpose: loads past the end are clamped to the last
+// tile (re-reading it from cache) and their MFMA operand is zeroed, so that the compiler can count the
+// outstanding loads and wait for exactly the oldest one instead of draining the queue.
+// ---------------------------------------------------------------------------------------------------
+
+// Direct: Wt = first weight tile of this wave (uint4 units); n = k-steps of this wave (>= 1);
+// brow[nt] = this lane's B pointer at the wave's first column (4 uint4 = 32 columns per step).
+// The address passes through an empty asm so that the compiler treats every ring load as a distinct,
+// unmovable-by-value-numbering load: otherwise it merges the prefetch for the next turn of the ring
+// with the loads of that turn and issues them only when they are needed.
+__device__ __forceinline__ uint4 ring_load(const uint4 *__restrict__ base, int index)
 {
-    __shared__ __attribute__((aligned(16))) char stage[kStageBytes];
-    __shared__ int rowoff[kTokBlock];   // element offset of each token's B row, -1 = padding (zeros)
-    __shared__ int outrow[kTokBlock];   // output row of each token, -1 = none
+    asm volatile("" : "+v"(index));
+    return base[index];
+}
 
-    const int b = blockIdx.x;
-    const int tid = threadIdx.x;
-    const int P = p.T * p.k;
-    int R, K, tile, Te, off = 0, shared_s = -1;
-    const uint16_t *Wexp;
-    if (b < p.routed_blocks) {
-        const int rank = b / p.tiles_r;
-        tile = b % p.tiles_r;
-        const int na = min(*p.num_active, p.N);
-        if (rank >= na) return;
-        const int e = p.active[rank];
-        if (e < 0 || e >= p.N) return;
-        off = p.offsets[e];
-        Te = p.offsets[e + 1] - off;
-        if (off < 0 || Te <= 0 || off + Te > P) return;
-        R = p.R;
-        K = p.K;
-        Wexp = p.W_routed + (size_t)e * ((size_t)R * K * (DUAL ? 2 : 1));
-    } else {
-        const int bs = b - p.routed_blocks;
-        shared_s = bs / p.tiles_s;
-        tile = bs % p.tiles_s;
-        if (shared_s >= p.n_shared || p.T <= 0) return;
-        Te = p.T;
-        R = p.Rs;
-        K = p.Ks;
-        Wexp = p.W_shared + (size_t)shared_s * ((size_t)R * K * (DUAL ? 2 : 1));
+template <bool DUAL, int NT>
+__device__ __forceinline__ void stream_direct(const uint4 *__restrict__ Wt, int n, const uint4 *const (&brow)[NT],
+                                              f32x4 (&accg)[NT], f32x4 (&accu)[NT])
+{
+    constexpr int WSTEP = DUAL ? 2 * kWave : kWave;
+    const uint4 *Wl = Wt + lane_id();
+    const int last = n - 1;
+    uint4 wg[kPF], wu[kPF], bb[kPF][NT];
+#pragma unroll
+    for (int j = 0; j < kPF; ++j) {
+        const int s = min(j, last);
+        wg[j] = ring_load(Wl, s * WSTEP);
+        wu[j] = DUAL ? ring_load(Wl, s * WSTEP + kWave) : zero4();
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) bb[j][nt] = ring_load(brow[nt], s * 4);
     }
-    const int KT = K / 32;
-    const int rt = tile * kFfnWaves + wave_id();   // 16-row tile of this wave
-    const bool wave_active = rt * 16 < R;
-    const uint4 *Wt = reinterpret_cast<const uint4 *>(Wexp) + (size_t)rt * KT * (DUAL ? 2 * kWave : kWave);
-    const int row0 = rt * 16;
+    for (int s0 = 0; s0 < n; s0 += kPF) {
+#pragma unroll
+        for (int u = 0; u < kPF; ++u) {
+            const int s = s0 + u;
+            const bool live = s < n;
+            // consume slot u ...
+            const bf16x8 ag = __builtin_bit_cast(bf16x8, sel4(live, wg[u]));
+            const bf16x8 au = __builtin_bit_cast(bf16x8, sel4(live, wu[u]));
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                const bf16x8 b = __builtin_bit_cast(bf16x8, bb[u][nt]);
+                accg[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ag, b, accg[nt], 0, 0, 0);
+                if (DUAL) accu[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(au, b, accu[nt], 0, 0, 0);
+            }
+            // ... then refill it (the scheduling fences keep the refill behind the last read of the slot,
+            // so that it can land in the same registers and the ring needs no copies)
+            __builtin_amdgcn_sched_barrier(0);
+            const int sn = min(s + kPF, last);
+            wg[u] = ring_load(Wl, sn * WSTEP);
+            if (DUAL) wu[u] = ring_load(Wl, sn * WSTEP + kWave);
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) bb[u][nt] = ring_load(brow[nt], sn * 4);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+}
 
-    for (int i0 = 0; i0 < Te; i0 += kTokBlock) {
-        const int nb = min(Te - i0, kTokBlock);
-        __syncthreads();   // previous block's epilogue has read outrow
-        if (tid < kTokBlock) {
-            int ro = -1, orow = -1;
-            const int i = i0 + tid;
-            if (tid < nb) {
-                if (shared_s < 0) {
-                    const int pv = p.perm[off + i];
-                    if (pv >= 0 && pv < P) {
-                        if (DUAL) {   // B row = x[token], out row = sorted position in h
-                            ro = (pv / p.k) * K;
-                            orow = off + i;
-                        } else {      // B row = h[sorted position], out row = pair id in o
-                            ro = (off + i) * K;
-                            orow = pv;
-                        }
-                    }
-                } else if (DUAL) {    // shared: every token, h rows after the routed ones
-                    ro = i * K;
-                    orow = i;
-                } else {
-                    ro = i * K;
-                    orow = P + shared_s * p.T + i;
+// One expert with <= 16*NT tokens: the four waves are RW row tiles x KW slices of K; the slices are
+// summed through LDS at the end.
+template <bool DUAL, int NT, int KW>
+__device__ __forceinline__ void expert_direct(const GemmParams &p, const WorkItem &w, float *red)
+{
+    constexpr int RW = kFfnWaves / KW;
+    constexpr int WSTEP = DUAL ? 2 * kWave : kWave;
+    constexpr int NACC = NT * (DUAL ? 2 : 1);
+    const int lane = lane_id(), wv = wave_id();
+    const int rw = wv / KW, kw = wv % KW;
+    const int KT = w.K / 32;
+    const int rt = w.tile * RW + rw;
+    const bool rows_ok = rt * 16 < w.R;
+    const int per = (KT + KW - 1) / KW;
+    const int kb = kw * per;
+    const int n = min(KT, kb + per) - kb;
+
+    int orow[NT];
+    const uint4 *brow[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        int ro;
+        token_rows<DUAL>(p, w, nt * 16 + (lane & 15), ro, orow[nt]);
+        ro = max(ro, 0);   // columns without a token read row 0; their results are never stored
+        brow[nt] = reinterpret_cast<const uint4 *>(w.B + (size_t)ro + (size_t)kb * 32 + (lane >> 4) * 8);
+    }
+    f32x4 accg[NT], accu[NT];
+    clear_acc<NT>(accg, accu);
+    if (rows_ok && n > 0) stream_direct<DUAL, NT>(w.W + ((size_t)rt * KT + kb) * WSTEP, n, brow, accg, accu);
+    if (KW > 1) {
+        f32x4 *r4 = reinterpret_cast<f32x4 *>(red);   // [rw][kw-1][NACC][lane]
+        if (kw > 0) {
+            f32x4 *dst = r4 + ((size_t)(rw * (KW - 1) + (kw - 1)) * NACC) * kWave + lane;
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                dst[(size_t)nt * kWave] = accg[nt];
+                if (DUAL) dst[(size_t)(NT + nt) * kWave] = accu[nt];
+            }
+        }
+        __syncthreads();
+        if (kw == 0) {
+#pragma unroll
+            for (int j = 1; j < KW; ++j) {
+                const f32x4 *src = r4 + ((size_t)(rw * (KW - 1) + (j - 1)) * NACC) * kWave + lane;
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) {
+                    accg[nt] += src[(size_t)nt * kWave];
+                    if (DUAL) accu[nt] += src[(size_t)(NT + nt) * kWave];
                 }
             }
+        }
+    }
+    if (kw == 0 && rows_ok) epilogue<DUAL, NT>(accg, accu, w.out, w.R, rt * 16, orow);
+}
+
+// Grid: (routed expert rank, tile of 16*RW rows) + (shared expert, tile), RW = 4 / KW.
+template <bool DUAL, int KW>
+__global__ __launch_bounds__(kFfnThreads, 2) void expert_direct_kernel(GemmParams p)
+{
+    __shared__ __attribute__((aligned(16))) float red[(KW > 1) ? (KW - 1) * (kFfnWaves / KW) * 2 * 4 * kWave : 4];
+    const WorkItem w = resolve_work<DUAL>(p);
+    if (!w.valid || w.Te > kDirectMaxTokens) return;
+    expert_direct<DUAL, 1, KW>(p, w, red);
+}
+
+// Staged: the token tile is staged through LDS in chunks of KS k-steps, double buffered and shared by
+// the four waves, which own four consecutive 16-row tiles and walk all of K.
+template <bool DUAL, int NT, int KS>
+__device__ __forceinline__ void stream_staged(const uint4 *__restrict__ Wt, bool wave_active, int KT, int K,
+                                              const uint16_t *__restrict__ B, const int *rowoff, char *stage,
+                                              f32x4 (&accg)[NT], f32x4 (&accu)[NT])
+{
+    constexpr int ROWB = KS * 64 + 16;           // LDS bytes per token row (+16: conflict-free 16-byte reads)
+    constexpr int BUFB = NT * 16 * ROWB;
+    static_assert(2 * BUFB <= kStageBytes, "token tile does not fit the LDS stage");
+    constexpr int PIECES = NT * 16 * KS * 4;     // 16-byte pieces per chunk
+    static_assert(PIECES % kFfnThreads == 0, "pieces must divide evenly over the workgroup");
+    constexpr int PPT = PIECES / kFfnThreads;
+    static_assert(kPF % KS == 0, "a ring turn must hold whole chunks");
+    constexpr int WSTEP = DUAL ? 2 * kWave : kWave;
+
+    const int tid = threadIdx.x, lane = lane_id();
+    const int last = KT - 1;
+    const int lastc = (KT + KS - 1) / KS - 1;
+
+    // this thread's staging pieces: (token row, 16-byte piece inside the chunk)
+    int xoff[PPT];    // element offset of the piece in chunk 0 (rows without a token read row 0, zeroed below)
+    bool xok[PPT];
+#pragma unroll
+    for (int i = 0; i < PPT; ++i) {
+        const int q = tid + kFfnThreads * i;
+        const int row = q / (KS * 4), pc = q % (KS * 4);
+        const int ro = rowoff[row];
+        xok[i] = ro >= 0;
+        xoff[i] = max(ro, 0) + pc * 8;
+    }
+    const int pc0 = (tid % (KS * 4)) * 8;   // column of every piece of this thread inside a chunk (256 % (KS*4) == 0)
+    uint4 xr[PPT];
+    auto load_x = [&](int c) {   // chunk c; columns past K read as zero
+        const int col = c * KS * 32;
+        const bool inside = col + pc0 < K;
+        const int ccol = inside ? col : 0;
+#pragma unroll
+        for (int i = 0; i < PPT; ++i)
+            xr[i] = sel4(inside && xok[i], *reinterpret_cast<const uint4 *>(B + (size_t)xoff[i] + ccol));
+    };
+    auto store_x = [&](int c) {
+        char *buf = stage + (c & 1) * BUFB;
+#pragma unroll
+        for (int i = 0; i < PPT; ++i) {
+            const int q = tid + kFfnThreads * i;
+            *reinterpret_cast<uint4 *>(buf + (q / (KS * 4)) * ROWB + (q % (KS * 4)) * 16) = xr[i];
+        }
+    };
+
+    const uint4 *Wl = Wt + lane;
+    uint4 wg[kPF], wu[kPF];
+#pragma unroll
+    for (int j = 0; j < kPF; ++j) {
+        const int s = min(j, last);
+        wg[j] = ring_load(Wl, s * WSTEP);
+        wu[j] = DUAL ? ring_load(Wl, s * WSTEP + kWave) : zero4();
+    }
+    load_x(0);
+    store_x(0);
+    __syncthreads();
+
+    const int brow = (lane & 15) * ROWB + (lane >> 4) * 16;   // this lane's B-fragment offset inside a token tile
+    for (int s0 = 0; s0 < KT; s0 += kPF) {
+#pragma unroll
+        for (int u = 0; u < kPF; ++u) {
+            const int s = s0 + u;
+            const int c = s / KS;
+            if (u % KS == 0) {
+                load_x(min(c + 1, lastc));
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            const bool live = wave_active && s < KT;
+            const bf16x8 ag = __builtin_bit_cast(bf16x8, sel4(live, wg[u]));
+            const bf16x8 au = __builtin_bit_cast(bf16x8, sel4(live, wu[u]));
+            const char *buf = stage + (c & 1) * BUFB + brow + (u % KS) * 64;
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                const bf16x8 b = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(buf + nt * 16 * ROWB));
+                accg[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ag, b, accg[nt], 0, 0, 0);
+                if (DUAL) accu[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(au, b, accu[nt], 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            const int sn = min(s + kPF, last);
+            wg[u] = ring_load(Wl, sn * WSTEP);
+            if (DUAL) wu[u] = ring_load(Wl, sn * WSTEP + kWave);
+            __builtin_amdgcn_sched_barrier(0);
+            if (u % KS == KS - 1) {
+                store_x(c + 1);
+                __syncthreads();
+            }
+        }
+    }
+}
+
+template <bool DUAL, int NT, int KS>
+__device__ __forceinline__ void expert_staged(const WorkItem &w, const int *rowoff, const int *outrow, char *stage)
+{
+    constexpr int WSTEP = DUAL ? 2 * kWave : kWave;
+    const int KT = w.K / 32;
+    const int rt = w.tile * kFfnWaves + wave_id();
+    const bool wave_active = rt * 16 < w.R;
+    const int rtc = wave_active ? rt : 0;   // idle waves read tile 0 (in bounds) and contribute nothing
+    f32x4 accg[NT], accu[NT];
+    clear_acc<NT>(accg, accu);
+    stream_staged<DUAL, NT, KS>(w.W + (size_t)rtc * KT * WSTEP, wave_active, KT, w.K, w.B, rowoff, stage, accg, accu);
+    if (!wave_active) return;
+    int orow[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) orow[nt] = outrow[nt * 16 + (lane_id() & 15)];
+    epilogue<DUAL, NT>(accg, accu, w.out, w.R, rt * 16, orow);
+}
+
+// Grid: (routed expert rank, tile of 64 rows) + (shared expert, tile).  Only experts with more than
+// kDirectMaxTokens tokens; up to 128 tokens per pass over the weights.
+template <bool DUAL>
+__global__ __launch_bounds__(kFfnThreads, 2) void expert_staged_kernel(GemmParams p)
+{
+    __shared__ __attribute__((aligned(16))) char stage[kStageBytes];
+    __shared__ int rowoff[kTokBlock];   // element offset of each token's B row, -1 = none
+    __shared__ int outrow[kTokBlock];   // output row of each token, -1 = none
+    const WorkItem w = resolve_work<DUAL>(p);
+    if (!w.valid || w.Te <= kDirectMaxTokens) return;
+    const int tid = threadIdx.x;
+    for (int i0 = 0; i0 < w.Te; i0 += kTokBlock) {
+        const int nb = min(w.Te - i0, kTokBlock);
+        __syncthreads();   // the previous pass has read rowoff / outrow and the stage
+        if (tid < kTokBlock) {
+            int ro, orow;
+            token_rows<DUAL>(p, w, tid < nb ? i0 + tid : w.Te, ro, orow);
             rowoff[tid] = ro;
             outrow[tid] = orow;
         }
         __syncthreads();
-        // shared experts keep their h rows in their own region of the scratch
-        const uint16_t *B = p.B;
-        void *out = p.out;
-        if (shared_s >= 0) {
-            const size_t hbase = (size_t)p.shared_h_base + (size_t)shared_s * p.T * (DUAL ? R : K);
-            if (DUAL)
-                out = reinterpret_cast<uint16_t *>(p.out) + hbase;
-            else
-                B = p.B + hbase;
-        }
-        if (nb <= 16)
-            expert_block<DUAL, 1, 16>(Wt, wave_active, R, K, B, out, row0, rowoff, outrow, stage);
-        else if (nb <= 32)
-            expert_block<DUAL, 2, 8>(Wt, wave_active, R, K, B, out, row0, rowoff, outrow, stage);
+        if (nb <= 32)
+            expert_staged<DUAL, 2, 8>(w, rowoff, outrow, stage);
         else if (nb <= 64)
-            expert_block<DUAL, 4, 4>(Wt, wave_active, R, K, B, out, row0, rowoff, outrow, stage);
+            expert_staged<DUAL, 4, 4>(w, rowoff, outrow, stage);
         else
-            expert_block<DUAL, 8, 2>(Wt, wave_active, R, K, B, out, row0, rowoff, outrow, stage);
+            expert_staged<DUAL, 8, 2>(w, rowoff, outrow, stage);
     }
 }
 
@@ -317,6 +492,61 @@ __global__ __launch_bounds__(256) void pack_kernel(const uint16_t *__restrict__ 
     *reinterpret_cast<uint4 *>(out + q * 8) = *reinterpret_cast<const uint4 *>(src);
 }
 
+// How many of a workgroup's four waves split the contraction dimension (the rest split rows).  Long
+// per-wave streams amortise the fill and drain of the prefetch ring, so K is only split when the
+// batch cannot invoke enough experts to give every CU several waves otherwise.
+static int pick_k_waves(int R, int K, bool dual, int max_experts, const char *env_override)
+{
+    if (const char *v = getenv(env_override)) {
+        const int kw = atoi(v);
+        if (kw == 1 || kw == 2 || kw == 4) return kw;
+    }
+    const long waves = (long)max_experts * (R / 16);                      // waves if K is not split
+    const long tile_bytes = (long)16 * K * 2 * (dual ? 2 : 1);            // weight bytes behind one 16-row tile
+    int kw = waves >= 2048 ? 1 : waves >= 1024 ? 2 : 4;
+    while (kw > 1 && tile_bytes / kw < 32 * 1024) kw >>= 1;               // keep at least 32 KiB per wave
+    return kw;
+}
+
+static void set_tiles(GemmParams &p, int rows_per_wg)
+{
+    p.tiles_r = (p.R + rows_per_wg - 1) / rows_per_wg;
+    p.tiles_s = p.n_shared ? (p.Rs + rows_per_wg - 1) / rows_per_wg : 0;
+    p.routed_blocks = p.N * p.tiles_r;
+}
+
+template <bool DUAL>
+static void launch_direct_kw(const GemmParams &p, int kw, hipStream_t st)
+{
+    const dim3 grid(p.routed_blocks + p.n_shared * p.tiles_s), block(kFfnThreads);
+    if (kw == 4)
+        hipLaunchKernelGGL((expert_direct_kernel<DUAL, 4>), grid, block, 0, st, p);
+    else if (kw == 2)
+        hipLaunchKernelGGL((expert_direct_kernel<DUAL, 2>), grid, block, 0, st, p);
+    else
+        hipLaunchKernelGGL((expert_direct_kernel<DUAL, 1>), grid, block, 0, st, p);
+}
+
+// One projection (gate/up or down) over all experts: the direct kernel, and the staged kernel when
+// some expert of this batch could hold more than kDirectMaxTokens tokens.
+template <bool DUAL>
+static int launch_projection(GemmParams p, const char *env_override, hipStream_t st, const char *what)
+{
+    const int max_experts = (int)min((long)p.N, (long)p.T * p.k) + p.n_shared;
+    const int kw = pick_k_waves(p.R, p.K, DUAL, max_experts, env_override);
+    set_tiles(p, 16 * (kFfnWaves / kw));
+    launch_direct_kw<DUAL>(p, kw, st);
+    int rc = check_launch(what);
+    if (rc != LYNX_OK) return rc;
+    if (p.T > kDirectMaxTokens) {
+        set_tiles(p, 16 * kFfnWaves);
+        hipLaunchKernelGGL((expert_staged_kernel<DUAL>), dim3(p.routed_blocks + p.n_shared * p.tiles_s),
+                           dim3(kFfnThreads), 0, st, p);
+        rc = check_launch(what);
+    }
+    return rc;
+}
+
 static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 struct Workspace {
@@ -363,13 +593,19 @@ extern "C" int lynx_pack_weights(const uint16_t *Wg, const uint16_t *Wu, const u
     return check_launch("lynx_pack_weights(down)");
 }
 
-extern "C" int lynx_moe_ffn(const uint16_t *x_bf16, const uint16_t *Wgu_packed, const uint16_t *Wd_packed,
-                            const uint16_t *Sgu_packed, const uint16_t *Sd_packed, int n_shared, int F_shared,
-                            const int32_t *idx, const float *gate, const int32_t *expert_offsets, const int32_t *perm,
-                            const int32_t *active_experts, const int32_t *num_active, int T, int H, int F, int N, int k,
-                            float *y, void *workspace, void *stream)
+extern "C" int lynx_moe_ffn_timed(const uint16_t *x_bf16, const uint16_t *Wgu_packed, const uint16_t *Wd_packed,
+                                  const uint16_t *Sgu_packed, const uint16_t *Sd_packed, int n_shared, int F_shared,
+                                  const int32_t *idx, const float *gate, const int32_t *expert_offsets,
+                                  const int32_t *perm, const int32_t *active_experts, const int32_t *num_active, int T,
+                                  int H, int F, int N, int k, float *y, void *workspace, void *stream,
+                                  void *const *stage_events)
 {
     using namespace lynx;
+    auto mark = [&](int i) -> int {
+        if (!stage_events || !stage_events[i]) return LYNX_OK;
+        const hipError_t err = hipEventRecord((hipEvent_t)stage_events[i], (hipStream_t)stream);
+        return err == hipSuccess ? LYNX_OK : fail(LYNX_ERR_HIP, "lynx_moe_ffn_timed: hipEventRecord: %s", hipGetErrorString(err));
+    };
     if (T < 0 || H <= 0 || F <= 0 || N <= 0 || k <= 0 || n_shared < 0)
         return fail(LYNX_ERR_INVALID_ARG, "lynx_moe_ffn: bad size");
     if (n_shared > 0 && (F_shared <= 0 || !Sgu_packed || !Sd_packed))
@@ -410,11 +646,11 @@ extern "C" int lynx_moe_ffn(const uint16_t *x_bf16, const uint16_t *Wgu_packed, 
     p.K = H;
     p.Rs = F_shared;
     p.Ks = H;
-    p.tiles_r = (F + kRowsPerWG - 1) / kRowsPerWG;
-    p.tiles_s = n_shared ? (F_shared + kRowsPerWG - 1) / kRowsPerWG : 0;
-    p.routed_blocks = N * p.tiles_r;
-    hipLaunchKernelGGL(expert_gemm_kernel<true>, dim3(p.routed_blocks + n_shared * p.tiles_s), dim3(kFfnThreads), 0, st, p);
-    int rc = check_launch("lynx_moe_ffn(gate/up)");
+    int rc = mark(0);
+    if (rc != LYNX_OK) return rc;
+    rc = launch_projection<true>(p, "LYNX_FFN_KW_GU", st, "lynx_moe_ffn(gate/up)");
+    if (rc != LYNX_OK) return rc;
+    rc = mark(1);
     if (rc != LYNX_OK) return rc;
 
     // down: rows = H, contraction = F
@@ -426,14 +662,25 @@ extern "C" int lynx_moe_ffn(const uint16_t *x_bf16, const uint16_t *Wgu_packed, 
     p.K = F;
     p.Rs = H;
     p.Ks = F_shared;
-    p.tiles_r = (H + kRowsPerWG - 1) / kRowsPerWG;
-    p.tiles_s = n_shared ? p.tiles_r : 0;
-    p.routed_blocks = N * p.tiles_r;
-    hipLaunchKernelGGL(expert_gemm_kernel<false>, dim3(p.routed_blocks + n_shared * p.tiles_s), dim3(kFfnThreads), 0, st, p);
-    rc = check_launch("lynx_moe_ffn(down)");
+    rc = launch_projection<false>(p, "LYNX_FFN_KW_DN", st, "lynx_moe_ffn(down)");
+    if (rc != LYNX_OK) return rc;
+    rc = mark(2);
     if (rc != LYNX_OK) return rc;
 
     hipLaunchKernelGGL(combine_kernel, dim3((H / 4 + 255) / 256, T), dim3(256), 0, st, obuf, idx, gate, T, H, N, k,
                        n_shared, y);
-    return check_launch("lynx_moe_ffn(combine)");
+    rc = check_launch("lynx_moe_ffn(combine)");
+    if (rc != LYNX_OK) return rc;
+    return mark(3);
+}
+
+extern "C" int lynx_moe_ffn(const uint16_t *x_bf16, const uint16_t *Wgu_packed, const uint16_t *Wd_packed,
+                            const uint16_t *Sgu_packed, const uint16_t *Sd_packed, int n_shared, int F_shared,
+                            const int32_t *idx, const float *gate, const int32_t *expert_offsets, const int32_t *perm,
+                            const int32_t *active_experts, const int32_t *num_active, int T, int H, int F, int N, int k,
+                            float *y, void *workspace, void *stream)
+{
+    return lynx_moe_ffn_timed(x_bf16, Wgu_packed, Wd_packed, Sgu_packed, Sd_packed, n_shared, F_shared, idx, gate,
+                              expert_offsets, perm, active_experts, num_active, T, H, F, N, k, y, workspace, stream,
+                              nullptr);
 }
