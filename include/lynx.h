@@ -44,8 +44,9 @@ extern "C" {
 /* Host string describing the last error on this thread ("" if none). */
 const char *lynx_last_error(void);
 
-/* Bytes of device workspace that lynx_affinity_bin and lynx_moe_ffn need for these sizes
- * (one buffer of this size serves both; contents need not be preserved between calls). */
+/* Bytes of device workspace that lynx_affinity_bin, lynx_moe_ffn and lynx_moe_layer need for these
+ * sizes (one buffer serves all; contents need not be preserved between calls; calls that share a
+ * workspace must not overlap in time).  lynx_affinity_bin alone uses only the first 64 KiB. */
 size_t lynx_workspace_bytes(int T, int H, int F, int N, int k, int n_shared, int F_shared);
 
 /*
@@ -75,7 +76,7 @@ int lynx_route(const uint16_t *x_bf16, const float *Wr, const float *bias, int T
  *   logits [T,N] fp32, topk_idx [T,k] int32 (k distinct experts per row, descending logit).
  *   new_idx [T,k] int32 out, new_gate [T,k] fp32 out, cnt_before [N], cnt_after [N] int32 out (pairs
  *   per expert before / after), bin_hist [N,beta] int32 out, num_active [2] int32 out (experts invoked
- *   before, after).  workspace: lynx_workspace_bytes() bytes.
+ *   before, after).  workspace: lynx_workspace_bytes() bytes (the first 64 KiB are used).
  */
 int lynx_affinity_bin(const float *logits, const int32_t *topk_idx, int T, int N, int k, float alpha, int beta,
                       int enable, int32_t *new_idx, float *new_gate, int32_t *cnt_before, int32_t *cnt_after,
@@ -131,8 +132,10 @@ int lynx_moe_ffn_timed(const uint16_t *x_bf16, const uint16_t *Wgu_packed, const
                        float *y, void *workspace, void *stream, void *const *stage_events);
 
 /*
- * The whole decode step of one MoE layer: lynx_route, lynx_affinity_bin, lynx_permute, lynx_moe_ffn
- * chained on `stream` with the argument meanings above.  All intermediate arrays are outputs.
+ * The whole decode step of one MoE layer: the work of lynx_route, lynx_affinity_bin, lynx_permute and
+ * lynx_moe_ffn chained on `stream` with the argument meanings above and identical results (the routing
+ * side is issued as four fused launches).  All intermediate arrays are outputs.  stage_events: as in
+ * lynx_moe_ffn_timed, or NULL.
  */
 int lynx_moe_layer(const uint16_t *x_bf16, const float *Wr, const float *bias, const uint16_t *Wgu_packed,
                    const uint16_t *Wd_packed, const uint16_t *Sgu_packed, const uint16_t *Sd_packed, int n_shared,
@@ -140,7 +143,7 @@ int lynx_moe_layer(const uint16_t *x_bf16, const float *Wr, const float *bias, c
                    int32_t *topk_idx, float *topk_gate, float *topk_psum, int32_t *new_idx, float *new_gate,
                    int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist, int32_t *num_active,
                    int32_t *expert_offsets, int32_t *perm, int32_t *active_experts, int32_t *num_active_perm, float *y,
-                   void *workspace, void *stream);
+                   void *workspace, void *stream, void *const *stage_events);
 
 #ifdef __cplusplus
 }

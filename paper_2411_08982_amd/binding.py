@@ -51,7 +51,7 @@ def lib():
         L.lynx_pack_weights.argtypes = [P, P, P, I, I, I, P, P, P]
         L.lynx_moe_ffn.argtypes = [P, P, P, P, P, I, I, P, P, P, P, P, P, I, I, I, I, I, P, P, P]
         L.lynx_moe_ffn_timed.argtypes = L.lynx_moe_ffn.argtypes + [ctypes.POINTER(c_void_p)]
-        L.lynx_moe_layer.argtypes = [P, P, P, P, P, P, P, I, I, I, I, I, I, I, F, I, I] + [P] * 17
+        L.lynx_moe_layer.argtypes = [P, P, P, P, P, P, P, I, I, I, I, I, I, I, F, I, I] + [P] * 17 + [ctypes.POINTER(c_void_p)]
         for name in SYMBOLS[2:]:
             getattr(L, name).restype = c_int
         _lib = L
@@ -112,7 +112,9 @@ def lynx_affinity_bin(logits, topk_idx, alpha, beta, enable=1, workspace=None, o
     o = out or dict(new_idx=torch.empty((T, k), dtype=I32, device=dev), new_gate=torch.empty((T, k), dtype=F32, device=dev),
                     cnt_before=torch.empty((N,), dtype=I32, device=dev), cnt_after=torch.empty((N,), dtype=I32, device=dev),
                     bin_hist=torch.empty((N, nb), dtype=I32, device=dev), num_active=torch.empty((2,), dtype=I32, device=dev))
-    ws = None if workspace is None else workspace.data_ptr()
+    if workspace is None:
+        workspace = torch.empty(65536, dtype=torch.uint8, device=dev)
+    ws = workspace.data_ptr()
     _check(lib().lynx_affinity_bin(_ptr(logits, F32, "logits"), _ptr(topk_idx, I32, "topk_idx"), T, N, k, float(alpha),
                                    int(beta), int(enable), _ptr(o["new_idx"], I32, "new_idx"),
                                    _ptr(o["new_gate"], F32, "new_gate"), _ptr(o["cnt_before"], I32, "cnt_before"),
@@ -188,7 +190,7 @@ class LayerBuffers:
 
 
 def lynx_moe_layer(x, Wr, bias, Wgu, Wdp, F, k, alpha, beta, enable=1, Sgu=None, Sdp=None, n_shared=0, F_shared=0,
-                   buffers: LayerBuffers | None = None):
+                   buffers: LayerBuffers | None = None, stage_events=None):
     """route -> affinity_bin -> permute -> FFN + combine on the current stream.  Returns the LayerBuffers."""
     T, H = x.shape
     N = Wr.shape[0]
@@ -201,5 +203,6 @@ def lynx_moe_layer(x, Wr, bias, Wgu, Wdp, F, k, alpha, beta, enable=1, Sgu=None,
         int(enable), b.logits.data_ptr(), b.topk_idx.data_ptr(), b.topk_gate.data_ptr(), b.topk_psum.data_ptr(),
         b.new_idx.data_ptr(), b.new_gate.data_ptr(), b.cnt_before.data_ptr(), b.cnt_after.data_ptr(),
         b.bin_hist.data_ptr(), b.num_active.data_ptr(), b.offsets.data_ptr(), b.perm.data_ptr(), b.active.data_ptr(),
-        b.num_active_perm.data_ptr(), b.y.data_ptr(), b.workspace.data_ptr(), _stream()))
+        b.num_active_perm.data_ptr(), b.y.data_ptr(), b.workspace.data_ptr(), _stream(),
+        None if stage_events is None else (c_void_p * 4)(*[e.cuda_event for e in stage_events])))
     return b

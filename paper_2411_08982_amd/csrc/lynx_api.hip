@@ -28,6 +28,16 @@ int check_launch(const char *what)
 
 extern "C" const char *lynx_last_error(void) { return lynx::g_last_error; }
 
+namespace lynx {
+int routing_fused(const uint16_t *x, const float *Wr, const float *bias, int T, int H, int N, int k, float alpha,
+                  int beta, int enable, float *logits, int32_t *topk_idx, float *topk_gate, float *topk_psum,
+                  int32_t *new_idx, float *new_gate, int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist,
+                  int32_t *num_active, int32_t *expert_offsets, int32_t *perm, int32_t *active_experts,
+                  int32_t *num_active_perm, void *workspace, hipStream_t st);
+}
+
+// The fused path issues the routing side in four launches (logits; top-k + bins; nominations; remap +
+// token assignment) instead of the seven of the separate calls; results are identical.
 extern "C" int lynx_moe_layer(const uint16_t *x_bf16, const float *Wr, const float *bias, const uint16_t *Wgu_packed,
                               const uint16_t *Wd_packed, const uint16_t *Sgu_packed, const uint16_t *Sd_packed,
                               int n_shared, int F_shared, int T, int H, int F, int N, int k, float alpha, int beta,
@@ -35,15 +45,45 @@ extern "C" int lynx_moe_layer(const uint16_t *x_bf16, const float *Wr, const flo
                               int32_t *new_idx, float *new_gate, int32_t *cnt_before, int32_t *cnt_after,
                               int32_t *bin_hist, int32_t *num_active, int32_t *expert_offsets, int32_t *perm,
                               int32_t *active_experts, int32_t *num_active_perm, float *y, void *workspace,
-                              void *stream)
+                              void *stream, void *const *stage_events)
 {
-    int rc = lynx_route(x_bf16, Wr, bias, T, H, N, k, logits, topk_idx, topk_gate, topk_psum, stream);
-    if (rc != LYNX_OK) return rc;
-    rc = lynx_affinity_bin(logits, topk_idx, T, N, k, alpha, beta, enable, new_idx, new_gate, cnt_before, cnt_after,
-                           bin_hist, num_active, workspace, stream);
-    if (rc != LYNX_OK) return rc;
-    rc = lynx_permute(new_idx, T, N, k, expert_offsets, perm, active_experts, num_active_perm, stream);
-    if (rc != LYNX_OK) return rc;
-    return lynx_moe_ffn(x_bf16, Wgu_packed, Wd_packed, Sgu_packed, Sd_packed, n_shared, F_shared, new_idx, new_gate,
-                        expert_offsets, perm, active_experts, num_active_perm, T, H, F, N, k, y, workspace, stream);
+    using namespace lynx;
+    int rc;
+    if (T <= 0 || !workspace) {
+        // no tokens (or a missing workspace, which the separate calls report): take the separate calls
+        rc = lynx_route(x_bf16, Wr, bias, T, H, N, k, logits, topk_idx, topk_gate, topk_psum, stream);
+        if (rc != LYNX_OK) return rc;
+        rc = lynx_affinity_bin(logits, topk_idx, T, N, k, alpha, beta, enable, new_idx, new_gate, cnt_before, cnt_after,
+                               bin_hist, num_active, workspace, stream);
+        if (rc != LYNX_OK) return rc;
+        rc = lynx_permute(new_idx, T, N, k, expert_offsets, perm, active_experts, num_active_perm, stream);
+        if (rc != LYNX_OK) return rc;
+    } else {
+        // same argument checks as the separate calls, before anything is enqueued
+        if (H <= 0 || N <= 0 || k <= 0) return fail(LYNX_ERR_INVALID_ARG, "lynx_moe_layer: negative or zero size");
+        if (k > N || N > LYNX_MAX_N || k > LYNX_MAX_K || T > LYNX_MAX_T || (H % 32) != 0 || beta > LYNX_MAX_BETA)
+            return fail(LYNX_ERR_UNSUPPORTED, "lynx_moe_layer: need k<=N<=%d, k<=%d, T<=%d, beta<=%d, H%%32==0", LYNX_MAX_N,
+                        LYNX_MAX_K, LYNX_MAX_T, LYNX_MAX_BETA);
+        if (beta < 1 || !(alpha >= 0.0f) || alpha > 3.0e38f)
+            return fail(LYNX_ERR_INVALID_ARG, "lynx_moe_layer: alpha must be finite and >= 0, beta >= 1");
+        double lim = 1.0;
+        for (int j = 0; j < beta; ++j) lim *= (double)T;
+        if (lim >= 4611686018427387904.0) return fail(LYNX_ERR_UNSUPPORTED, "lynx_moe_layer: T^beta must stay below 2^62");
+        if (!x_bf16 || !Wr || !logits || !topk_idx || !topk_gate || !topk_psum || !new_idx || !new_gate || !cnt_before ||
+            !cnt_after || !bin_hist || !num_active || !expert_offsets || !perm || !active_experts || !num_active_perm)
+            return fail(LYNX_ERR_INVALID_ARG, "lynx_moe_layer: null pointer");
+        // the FFN's own checks, repeated here so that an error leaves nothing enqueued
+        if (F <= 0 || n_shared < 0 || !Wgu_packed || !Wd_packed || !y ||
+            (n_shared > 0 && (F_shared <= 0 || !Sgu_packed || !Sd_packed)))
+            return fail(LYNX_ERR_INVALID_ARG, "lynx_moe_layer: bad FFN size or null weight / output pointer");
+        if ((F % 32) != 0 || (n_shared > 0 && (F_shared % 32) != 0))
+            return fail(LYNX_ERR_UNSUPPORTED, "lynx_moe_layer: F and F_shared must be multiples of 32");
+        rc = routing_fused(x_bf16, Wr, bias, T, H, N, k, alpha, beta, enable, logits, topk_idx, topk_gate, topk_psum,
+                           new_idx, new_gate, cnt_before, cnt_after, bin_hist, num_active, expert_offsets, perm,
+                           active_experts, num_active_perm, workspace, (hipStream_t)stream);
+        if (rc != LYNX_OK) return rc;
+    }
+    return lynx_moe_ffn_timed(x_bf16, Wgu_packed, Wd_packed, Sgu_packed, Sd_packed, n_shared, F_shared, new_idx, new_gate,
+                              expert_offsets, perm, active_experts, num_active_perm, T, H, F, N, k, y, workspace, stream,
+                              stage_events);
 }

@@ -19,19 +19,36 @@ constexpr int kSlots = LYNX_MAX_N / kWave;  // expert slots per lane when a wave
 __device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & (kWave - 1)); }
 __device__ __forceinline__ int wave_id() { return (int)(threadIdx.x >> 6); }
 
+// Wave-wide reductions on the DPP data path (row shifts inside each row of 16 lanes, then the two row
+// broadcasts): no LDS crossbar round trips.  After the sequence lane 63 holds the result; it is read back
+// as a wave-uniform value.  Lanes that a step does not write keep their own value (max) or add zero (sum).
+#define LYNX_DPP_STEP_MAX(ctrl, rmask)                                                                          \
+    v = fmaxf(v, __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(v), __float_as_int(v), ctrl, rmask, 0xf, false)))
+#define LYNX_DPP_STEP_SUM(ctrl, rmask) \
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), ctrl, rmask, 0xf, false))
+
 __device__ __forceinline__ float wave_max(float v)
 {
-#pragma unroll
-    for (int m = kWave / 2; m > 0; m >>= 1) v = fmaxf(v, __shfl_xor(v, m, kWave));
-    return v;
+    LYNX_DPP_STEP_MAX(0x111, 0xf);   // row_shr:1
+    LYNX_DPP_STEP_MAX(0x112, 0xf);   // row_shr:2
+    LYNX_DPP_STEP_MAX(0x114, 0xf);   // row_shr:4
+    LYNX_DPP_STEP_MAX(0x118, 0xf);   // row_shr:8   -> lane 15 of every row holds the row's maximum
+    LYNX_DPP_STEP_MAX(0x142, 0xa);   // row_bcast:15 into rows 1 and 3
+    LYNX_DPP_STEP_MAX(0x143, 0xc);   // row_bcast:31 into rows 2 and 3 -> lane 63 holds the wave's maximum
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 
-// Butterfly sum: every lane ends with the same value, summed in a fixed order.
+// Fixed summation order (a prefix tree inside rows, then rows 0+1, 2+3, then halves): every lane gets the
+// same value, and it does not depend on scheduling.
 __device__ __forceinline__ float wave_sum(float v)
 {
-#pragma unroll
-    for (int m = kWave / 2; m > 0; m >>= 1) v += __shfl_xor(v, m, kWave);
-    return v;
+    LYNX_DPP_STEP_SUM(0x111, 0xf);
+    LYNX_DPP_STEP_SUM(0x112, 0xf);
+    LYNX_DPP_STEP_SUM(0x114, 0xf);
+    LYNX_DPP_STEP_SUM(0x118, 0xf);
+    LYNX_DPP_STEP_SUM(0x142, 0xa);
+    LYNX_DPP_STEP_SUM(0x143, 0xc);
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 
 // Bin magnitude of one (token, expert) pair: min(floor(alpha * (zmax - z)), beta), with exactly one
@@ -46,30 +63,67 @@ __device__ __forceinline__ int bin_of(float zmax, float z, float alpha, int beta
 // The wave holds one token's logits: lane l, slot i <-> expert l + 64*i.  Picks the k largest among
 // the candidate slots (bit i of `cand`), descending, equal values to the lower expert index, and calls
 // emit(j, expert, value) on every lane with the j-th winner (expert = INT_MAX when none is left).
+// Per pick: one DPP max reduction, then the lowest-indexed holder of that maximum by ballot + find-first
+// (slot 0 holds the lower experts, so the first slot with a match wins).  Values are finite.
 template <typename Emit>
 __device__ __forceinline__ void wave_topk(const float (&v)[kSlots], unsigned cand, int k, Emit &&emit)
 {
     const int lane = lane_id();
     for (int j = 0; j < k; ++j) {
-        float bv = -INFINITY;
-        int be = INT_MAX;
+        float m = -INFINITY;
 #pragma unroll
         for (int i = 0; i < kSlots; ++i)
-            if (((cand >> i) & 1u) && (be == INT_MAX || v[i] > bv)) {
-                bv = v[i];
-                be = lane + kWave * i;
-            }
+            if ((cand >> i) & 1u) m = fmaxf(m, v[i]);
+        const float best = wave_max(m);
+        int e = INT_MAX;
 #pragma unroll
-        for (int m = kWave / 2; m > 0; m >>= 1) {
-            float ov = __shfl_xor(bv, m, kWave);
-            int oe = __shfl_xor(be, m, kWave);
-            bool take = (oe != INT_MAX) && (be == INT_MAX || ov > bv || (ov == bv && oe < be));
-            bv = take ? ov : bv;
-            be = take ? oe : be;
+        for (int i = 0; i < kSlots; ++i) {
+            const unsigned long long b = __ballot(((cand >> i) & 1u) && v[i] == best);
+            if (e == INT_MAX && b != 0ull) e = __ffsll((long long)b) - 1 + kWave * i;
         }
-        if (be != INT_MAX && (be & (kWave - 1)) == lane) cand &= ~(1u << (be >> 6));
-        emit(j, be, bv);
+        if (e != INT_MAX && (e & (kWave - 1)) == lane) cand &= ~(1u << (e >> 6));
+        emit(j, e, best);
     }
+}
+
+// ---- workspace layout (one caller-provided buffer serves every call) -----------------------------------
+// [ routing scratch | h: bf16 intermediate vectors | o: fp32 per-pair outputs ]
+// Routing scratch (int32 words): tickets of the "last workgroup finishes the batch-level step" pattern,
+// the experts in score order, the active-set flags and the per-expert token bit sets of the permutation.
+constexpr int kWsTickets = 0;                              // 16 words
+constexpr int kWsOrder = 16;                               // LYNX_MAX_N words
+constexpr int kWsActive = kWsOrder + LYNX_MAX_N;           // LYNX_MAX_N words
+constexpr int kWsMember = kWsActive + LYNX_MAX_N;          // LYNX_MAX_N * LYNX_MAX_T/32 words
+constexpr int kWsRoutingWords = kWsMember + LYNX_MAX_N * (LYNX_MAX_T / 32);
+constexpr size_t kWsRoutingBytes = 65536;
+static_assert((size_t)kWsRoutingWords * 4 <= kWsRoutingBytes, "routing scratch does not fit its reservation");
+
+struct Workspace {
+    size_t h_elems, o_elems, h_off, o_off, routing_off, total;
+};
+
+inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+// o holds one fp32 row per (token, slot) pair and per (shared expert, K split, token).
+inline Workspace workspace_layout(int T, int H, int F, int k, int n_shared, int F_shared, int shared_splits)
+{
+    Workspace w;
+    w.h_elems = (size_t)T * k * F + (size_t)n_shared * T * F_shared;
+    w.o_elems = ((size_t)T * k + (size_t)n_shared * shared_splits * T) * H;
+    w.routing_off = 0;
+    w.h_off = kWsRoutingBytes;
+    w.o_off = w.h_off + align256(w.h_elems * 2);
+    w.total = w.o_off + align256(w.o_elems * 4);
+    return w;
+}
+
+// Number of K slices a shared expert's down projection is cut into, so that a shared expert that is
+// several times wider than a routed one still spreads over the chip (each slice owns its output rows).
+inline int shared_down_splits(int F, int n_shared, int F_shared)
+{
+    if (n_shared <= 0 || F_shared <= F) return 1;
+    int s = (F_shared + F - 1) / F;
+    return s > 8 ? 8 : s;
 }
 
 }  // namespace lynx

@@ -8,14 +8,13 @@
 //   * a wave owns 16 output rows and walks (a slice of) the contraction dimension with a ring of
 //     prefetched tiles in registers, so each weight byte is fetched from HBM once per call;
 //   * the tokens of the expert are the B operand.  Experts with few tokens (<= 16, the usual decode
-//     case) read the token columns straight from global memory in MFMA layout ("direct" kernel: no
+//     case) read the token columns straight from global memory in MFMA layout ("direct" path: no
 //     LDS, no barrier in the loop); experts with many tokens stage the token tile through LDS, shared
-//     by four row tiles ("staged" kernel);
-//   * the grid is fixed (N experts + shared experts, times row tiles); a workgroup whose rank is past
-//     the device-side num_active, or whose expert belongs to the other kernel, leaves at once, so
-//     nothing is read back to the host.
-// Launches: direct gate/up (+ staged gate/up if the batch can have an expert with > 16 tokens), the
-// same for down, and a small combine.
+//     by four row tiles ("staged" path);
+//   * the grid is fixed (most experts the batch can invoke + shared experts, times row tiles); a
+//     workgroup whose rank is past the device-side num_active leaves at once, so nothing is read back
+//     to the host.
+// Launches: gate/up (with the SiLU-multiply epilogue), down, and a small combine.
 #include <stdlib.h>
 
 #include "lynx_common.h"
@@ -44,6 +43,7 @@ struct GemmParams {
     int Rs, Ks;                 // shared
     int tiles_r, tiles_s;       // workgroups per routed / shared expert
     int routed_blocks;
+    int shared_splits;          // K slices per shared expert (down projection only; each slice has its own output rows)
     long long shared_h_base;    // element offset of the shared experts' h rows in the h scratch
 };
 
@@ -53,6 +53,8 @@ struct WorkItem {
     const uint16_t *B;   // B-operand rows
     void *out;
     int R, K, tile, Te, off, shared_s;
+    int kbeg, ksteps;    // slice of the contraction dimension this work item covers, in k-steps of 32 columns
+    int out_base;        // shared experts: first output row of this work item
     bool valid;
 };
 
@@ -80,15 +82,24 @@ __device__ __forceinline__ WorkItem resolve_work(const GemmParams &p)
         if (w.off < 0 || w.Te <= 0 || w.off + w.Te > P) return w;
         w.R = p.R;
         w.K = p.K;
+        w.kbeg = 0;
+        w.ksteps = w.K / 32;
+        w.out_base = 0;
         Wbase = p.W_routed + (size_t)e * ((size_t)w.R * w.K * (DUAL ? 2 : 1));
     } else {
         const int bs = b - p.routed_blocks;
-        w.shared_s = bs / p.tiles_s;
+        const int v = bs / p.tiles_s;   // (shared expert, K slice)
+        w.shared_s = v / p.shared_splits;
         w.tile = bs % p.tiles_s;
         if (w.shared_s >= p.n_shared || p.T <= 0) return w;
         w.Te = p.T;
         w.R = p.Rs;
         w.K = p.Ks;
+        const int per = (w.K / 32 + p.shared_splits - 1) / p.shared_splits;
+        w.kbeg = (v % p.shared_splits) * per;
+        w.ksteps = min(w.K / 32, w.kbeg + per) - w.kbeg;
+        if (w.ksteps <= 0) return w;
+        w.out_base = P + v * p.T;
         Wbase = p.W_shared + (size_t)w.shared_s * ((size_t)w.R * w.K * (DUAL ? 2 : 1));
         // shared experts keep their h rows in their own region of the scratch
         const size_t hbase = (size_t)p.shared_h_base + (size_t)w.shared_s * p.T * (DUAL ? w.R : w.K);
@@ -125,7 +136,7 @@ __device__ __forceinline__ void token_rows(const GemmParams &p, const WorkItem &
         orow = i;
     } else {
         ro = i * w.K;
-        orow = P + w.shared_s * p.T + i;
+        orow = w.out_base + i;
     }
 }
 
@@ -248,9 +259,9 @@ __device__ __forceinline__ void expert_direct(const GemmParams &p, const WorkIte
     const int KT = w.K / 32;
     const int rt = w.tile * RW + rw;
     const bool rows_ok = rt * 16 < w.R;
-    const int per = (KT + KW - 1) / KW;
-    const int kb = kw * per;
-    const int n = min(KT, kb + per) - kb;
+    const int per = (w.ksteps + KW - 1) / KW;
+    const int kb = w.kbeg + kw * per;
+    const int n = min(w.kbeg + w.ksteps, kb + per) - kb;
 
     int orow[NT];
     const uint4 *brow[NT];
@@ -290,22 +301,12 @@ __device__ __forceinline__ void expert_direct(const GemmParams &p, const WorkIte
     if (kw == 0 && rows_ok) epilogue<DUAL, NT>(accg, accu, w.out, w.R, rt * 16, orow);
 }
 
-// Grid: (routed expert rank, tile of 16*RW rows) + (shared expert, tile), RW = 4 / KW.
-template <bool DUAL, int KW>
-__global__ __launch_bounds__(kFfnThreads, 2) void expert_direct_kernel(GemmParams p)
-{
-    __shared__ __attribute__((aligned(16))) float red[(KW > 1) ? (KW - 1) * (kFfnWaves / KW) * 2 * 4 * kWave : 4];
-    const WorkItem w = resolve_work<DUAL>(p);
-    if (!w.valid || w.Te > kDirectMaxTokens) return;
-    expert_direct<DUAL, 1, KW>(p, w, red);
-}
-
 // Staged: the token tile is staged through LDS in chunks of KS k-steps, double buffered and shared by
 // the four waves, which own four consecutive 16-row tiles and walk all of K.
 template <bool DUAL, int NT, int KS>
 __device__ __forceinline__ void stream_staged(const uint4 *__restrict__ Wt, bool wave_active, int KT, int K,
                                               const uint16_t *__restrict__ B, const int *rowoff, char *stage,
-                                              f32x4 (&accg)[NT], f32x4 (&accu)[NT])
+                                              f32x4 (&accg)[NT], f32x4 (&accu)[NT])   // KT steps from Wt; B columns [0, K)
 {
     constexpr int ROWB = KS * 64 + 16;           // LDS bytes per token row (+16: conflict-free 16-byte reads)
     constexpr int BUFB = NT * 16 * ROWB;
@@ -405,7 +406,8 @@ __device__ __forceinline__ void expert_staged(const WorkItem &w, const int *rowo
     const int rtc = wave_active ? rt : 0;   // idle waves read tile 0 (in bounds) and contribute nothing
     f32x4 accg[NT], accu[NT];
     clear_acc<NT>(accg, accu);
-    stream_staged<DUAL, NT, KS>(w.W + (size_t)rtc * KT * WSTEP, wave_active, KT, w.K, w.B, rowoff, stage, accg, accu);
+    stream_staged<DUAL, NT, KS>(w.W + ((size_t)rtc * KT + w.kbeg) * WSTEP, wave_active, w.ksteps, w.ksteps * 32,
+                                w.B + (size_t)w.kbeg * 32, rowoff, stage, accg, accu);
     if (!wave_active) return;
     int orow[NT];
 #pragma unroll
@@ -413,16 +415,25 @@ __device__ __forceinline__ void expert_staged(const WorkItem &w, const int *rowo
     epilogue<DUAL, NT>(accg, accu, w.out, w.R, rt * 16, orow);
 }
 
-// Grid: (routed expert rank, tile of 64 rows) + (shared expert, tile).  Only experts with more than
-// kDirectMaxTokens tokens; up to 128 tokens per pass over the weights.
-template <bool DUAL>
-__global__ __launch_bounds__(kFfnThreads, 2) void expert_staged_kernel(GemmParams p)
+// One launch per projection.  Grid: (routed expert rank, tile of 16*RW rows) + (shared expert, K slice,
+// tile), RW = 4 / KW.  An expert with at most kDirectMaxTokens tokens takes the direct path with the
+// workgroup's four waves as RW row tiles x KW slices of K.  A larger expert takes the staged path, in which
+// a workgroup covers 64 rows: of every KW consecutive workgroups one does the work, in passes of up to 128
+// tokens, and the others leave.
+template <bool DUAL, int KW>
+__global__ __launch_bounds__(kFfnThreads, 2) void expert_kernel(GemmParams p)
 {
-    __shared__ __attribute__((aligned(16))) char stage[kStageBytes];
-    __shared__ int rowoff[kTokBlock];   // element offset of each token's B row, -1 = none
-    __shared__ int outrow[kTokBlock];   // output row of each token, -1 = none
-    const WorkItem w = resolve_work<DUAL>(p);
-    if (!w.valid || w.Te <= kDirectMaxTokens) return;
+    __shared__ __attribute__((aligned(16))) char stage[kStageBytes];   // staged token tile, or the K-slice partial sums
+    __shared__ int rowoff[kTokBlock];   // staged path: element offset of each token's B row, -1 = none
+    __shared__ int outrow[kTokBlock];   // staged path: output row of each token, -1 = none
+    WorkItem w = resolve_work<DUAL>(p);
+    if (!w.valid) return;
+    if (w.Te <= kDirectMaxTokens) {
+        expert_direct<DUAL, 1, KW>(p, w, reinterpret_cast<float *>(stage));
+        return;
+    }
+    if ((w.tile % KW) != 0) return;
+    w.tile /= KW;
     const int tid = threadIdx.x;
     for (int i0 = 0; i0 < w.Te; i0 += kTokBlock) {
         const int nb = min(w.Te - i0, kTokBlock);
@@ -512,57 +523,26 @@ static void set_tiles(GemmParams &p, int rows_per_wg)
 {
     p.tiles_r = (p.R + rows_per_wg - 1) / rows_per_wg;
     p.tiles_s = p.n_shared ? (p.Rs + rows_per_wg - 1) / rows_per_wg : 0;
-    p.routed_blocks = p.N * p.tiles_r;
+    p.routed_blocks = (int)min((long)p.N, (long)p.T * p.k) * p.tiles_r;   // at most min(N, T*k) experts are invoked
 }
 
-template <bool DUAL>
-static void launch_direct_kw(const GemmParams &p, int kw, hipStream_t st)
-{
-    const dim3 grid(p.routed_blocks + p.n_shared * p.tiles_s), block(kFfnThreads);
-    if (kw == 4)
-        hipLaunchKernelGGL((expert_direct_kernel<DUAL, 4>), grid, block, 0, st, p);
-    else if (kw == 2)
-        hipLaunchKernelGGL((expert_direct_kernel<DUAL, 2>), grid, block, 0, st, p);
-    else
-        hipLaunchKernelGGL((expert_direct_kernel<DUAL, 1>), grid, block, 0, st, p);
-}
+static unsigned grid_blocks(const GemmParams &p) { return (unsigned)(p.routed_blocks + p.n_shared * p.shared_splits * p.tiles_s); }
 
-// One projection (gate/up or down) over all experts: the direct kernel, and the staged kernel when
-// some expert of this batch could hold more than kDirectMaxTokens tokens.
+// One projection (gate/up or down) over all invoked and shared experts.
 template <bool DUAL>
 static int launch_projection(GemmParams p, const char *env_override, hipStream_t st, const char *what)
 {
     const int max_experts = (int)min((long)p.N, (long)p.T * p.k) + p.n_shared;
     const int kw = pick_k_waves(p.R, p.K, DUAL, max_experts, env_override);
     set_tiles(p, 16 * (kFfnWaves / kw));
-    launch_direct_kw<DUAL>(p, kw, st);
-    int rc = check_launch(what);
-    if (rc != LYNX_OK) return rc;
-    if (p.T > kDirectMaxTokens) {
-        set_tiles(p, 16 * kFfnWaves);
-        hipLaunchKernelGGL((expert_staged_kernel<DUAL>), dim3(p.routed_blocks + p.n_shared * p.tiles_s),
-                           dim3(kFfnThreads), 0, st, p);
-        rc = check_launch(what);
-    }
-    return rc;
-}
-
-static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
-
-struct Workspace {
-    size_t h_elems, o_elems, h_off, o_off, total;
-};
-
-static Workspace workspace_layout(int T, int H, int F, int N, int k, int n_shared, int F_shared)
-{
-    (void)N;
-    Workspace w;
-    w.h_elems = (size_t)T * k * F + (size_t)n_shared * T * F_shared;
-    w.o_elems = ((size_t)T * k + (size_t)n_shared * T) * H;
-    w.h_off = 0;
-    w.o_off = align256(w.h_elems * 2);
-    w.total = w.o_off + align256(w.o_elems * 4) + 65536;
-    return w;
+    const dim3 grid(grid_blocks(p)), block(kFfnThreads);
+    if (kw == 4)
+        hipLaunchKernelGGL((expert_kernel<DUAL, 4>), grid, block, 0, st, p);
+    else if (kw == 2)
+        hipLaunchKernelGGL((expert_kernel<DUAL, 2>), grid, block, 0, st, p);
+    else
+        hipLaunchKernelGGL((expert_kernel<DUAL, 1>), grid, block, 0, st, p);
+    return check_launch(what);
 }
 
 }  // namespace lynx
@@ -570,7 +550,9 @@ static Workspace workspace_layout(int T, int H, int F, int N, int k, int n_share
 extern "C" size_t lynx_workspace_bytes(int T, int H, int F, int N, int k, int n_shared, int F_shared)
 {
     if (T < 0 || H < 0 || F < 0 || N < 0 || k < 0 || n_shared < 0 || F_shared < 0) return 0;
-    return lynx::workspace_layout(T, H, F, N, k, n_shared, F_shared).total;
+    (void)N;
+    if (n_shared == 0) F_shared = 0;
+    return lynx::workspace_layout(T, H, F, k, n_shared, F_shared, lynx::shared_down_splits(F, n_shared, F_shared)).total;
 }
 
 extern "C" int lynx_pack_weights(const uint16_t *Wg, const uint16_t *Wu, const uint16_t *Wd, int E, int H, int F,
@@ -619,7 +601,8 @@ extern "C" int lynx_moe_ffn_timed(const uint16_t *x_bf16, const uint16_t *Wgu_pa
         !num_active || !y || !workspace)
         return fail(LYNX_ERR_INVALID_ARG, "lynx_moe_ffn: null pointer");
     if (n_shared == 0) F_shared = 0;
-    const Workspace ws = workspace_layout(T, H, F, N, k, n_shared, F_shared);
+    const int splits = shared_down_splits(F, n_shared, F_shared);
+    const Workspace ws = workspace_layout(T, H, F, k, n_shared, F_shared, splits);
     if (ws.h_elems >= 0x7fffffffull || ws.o_elems >= 0x7fffffffull * 4)
         return fail(LYNX_ERR_UNSUPPORTED, "lynx_moe_ffn: scratch index would overflow 32 bits");
     uint16_t *hbuf = reinterpret_cast<uint16_t *>(reinterpret_cast<char *>(workspace) + ws.h_off);
@@ -635,6 +618,7 @@ extern "C" int lynx_moe_ffn_timed(const uint16_t *x_bf16, const uint16_t *Wgu_pa
     p.N = N;
     p.k = k;
     p.n_shared = n_shared;
+    p.shared_splits = 1;
     p.shared_h_base = (long long)T * k * F;
 
     // gate/up: rows = F, contraction = H
@@ -662,13 +646,14 @@ extern "C" int lynx_moe_ffn_timed(const uint16_t *x_bf16, const uint16_t *Wgu_pa
     p.K = F;
     p.Rs = H;
     p.Ks = F_shared;
+    p.shared_splits = splits;
     rc = launch_projection<false>(p, "LYNX_FFN_KW_DN", st, "lynx_moe_ffn(down)");
     if (rc != LYNX_OK) return rc;
     rc = mark(2);
     if (rc != LYNX_OK) return rc;
 
     hipLaunchKernelGGL(combine_kernel, dim3((H / 4 + 255) / 256, T), dim3(256), 0, st, obuf, idx, gate, T, H, N, k,
-                       n_shared, y);
+                       n_shared * splits, y);
     rc = check_launch("lynx_moe_ffn(combine)");
     if (rc != LYNX_OK) return rc;
     return mark(3);

@@ -1,0 +1,85 @@
+// Token assignment from per-expert token bit sets (paper Sec. 4, "assigns tokens"), shared by the
+// stand-alone lynx_permute kernel and by the last workgroup of the fused remap kernel.
+//
+// A token holds k distinct experts, so an expert sees a token at most once: the membership of the batch
+// in each expert is a T-bit set.  Pair counts are popcounts, and the stable position of pair (t, slot)
+// inside its expert is the popcount of the bits below t.  No sort, no ordered atomics.
+#pragma once
+
+#include "lynx_common.h"
+
+namespace lynx {
+
+struct PermuteShared {
+    unsigned member[LYNX_MAX_N * (LYNX_MAX_T / 32)];   // member[e*W + w] bit b: token 32*w+b uses expert e
+    int count[LYNX_MAX_N];
+    int offs[LYNX_MAX_N + 1];
+    int arank[LYNX_MAX_N + 1];
+};
+
+// Every thread of the workgroup calls this with sh.member filled (and visible: barrier before).
+// perm must have been pre-filled with -1 where invalid indices can occur.
+template <int THREADS>
+__device__ __forceinline__ void permute_from_bitsets(PermuteShared &sh, const int32_t *__restrict__ idx, int T, int N,
+                                                     int k, int32_t *__restrict__ expert_offsets,
+                                                     int32_t *__restrict__ perm, int32_t *__restrict__ active_experts,
+                                                     int32_t *__restrict__ num_active)
+{
+    const int tid = threadIdx.x;
+    const int W = (T + 31) / 32;
+    const int P = T * k;
+    if (tid < N) {
+        int c = 0;
+        for (int w = 0; w < W; ++w) c += __popc(sh.member[tid * W + w]);
+        sh.count[tid] = c;
+    }
+    __syncthreads();
+    // exclusive prefixes over experts: pair offsets and rank among the invoked experts
+    if (tid < kWave) {
+        int carry_o = 0, carry_a = 0;
+        for (int base = 0; base < N; base += kWave) {
+            const int e = base + tid;
+            const int c = (e < N) ? sh.count[e] : 0;
+            const int a = c > 0 ? 1 : 0;
+            int so = c, sa = a;
+#pragma unroll
+            for (int d = 1; d < kWave; d <<= 1) {
+                const int uo = __shfl_up(so, d, kWave), ua = __shfl_up(sa, d, kWave);
+                if (tid >= d) {
+                    so += uo;
+                    sa += ua;
+                }
+            }
+            if (e < N) {
+                sh.offs[e] = carry_o + so - c;
+                sh.arank[e] = carry_a + sa - a;
+            }
+            carry_o += __shfl(so, kWave - 1, kWave);
+            carry_a += __shfl(sa, kWave - 1, kWave);
+        }
+        if (tid == 0) {
+            sh.offs[N] = carry_o;
+            sh.arank[N] = carry_a;
+        }
+    }
+    __syncthreads();
+    for (int p = tid; p < P; p += THREADS) {
+        const int e = idx[p];
+        if (e < 0 || e >= N) continue;
+        const int t = p / k;
+        int pos = sh.offs[e];
+        const int wt = t >> 5;
+        for (int w = 0; w < wt; ++w) pos += __popc(sh.member[e * W + w]);
+        pos += __popc(sh.member[e * W + wt] & ((1u << (t & 31)) - 1u));
+        perm[pos] = p;   // pos < offs[N] <= P by construction
+    }
+    for (int e = tid; e <= N; e += THREADS) expert_offsets[e] = sh.offs[e];
+    const int na = sh.arank[N];
+    for (int e = tid; e < N; e += THREADS) {
+        if (sh.count[e] > 0) active_experts[sh.arank[e]] = e;
+        if (e >= na) active_experts[e] = -1;
+    }
+    if (tid == 0) num_active[0] = na;
+}
+
+}  // namespace lynx

@@ -1,0 +1,753 @@
+// Routing side of the Lynx decode step: router logits, softmax and top-k (paper Sec. 2.1),
+// AffinityBinning (Sec. 3.2.1), batch-wide expert scoring and active-set selection (Sec. 3.3.1),
+// remapping with gate renormalisation (Secs. 3.4, 4) and, in the fused whole-layer path, the token
+// assignment (Sec. 4).
+//
+// These steps are latency-bound (microseconds).  On a chip with one L2 per XCD every dependent launch
+// costs a few microseconds of its own (first loads miss, last stores are written back), so the layout
+// minimises dependent launches and dependent memory round trips inside them:
+//   logits_kernel         (token tile x expert group)  fp32 dot products: the router row is prefetched
+//                         into registers while the 4 tokens are staged in LDS; lanes split H; transposing
+//                         butterfly reduction.  Always its own launch (it needs the whole chip).
+//   T <= 64:  routing_small_kernel  ONE workgroup does everything else with all state in LDS: top-k,
+//                         bins + histogram, scores + score order, nominations, fill, remap, gates, counts
+//                         and (fused path) the token assignment.  Two launches for the whole routing side.
+//   T  > 64:  token_kernel -> nominate_kernel -> remap_kernel, one wave per token over many workgroups, one
+//                         launch per batch-level dependency (finished histogram; finished active set).
+//                         Scores/order and the fill are recomputed by every workgroup in its prologue
+//                         instead of costing a launch; the last workgroup of remap_kernel (atomic ticket
+//                         after a fence: nobody waits, nothing can hang) assigns the tokens.
+// Nomination: with the experts laid out across the lanes in score order, "the best-scoring expert that
+// qualifies" is a ballot followed by find-first-set.  All decisions are integer (bins from one fp32
+// subtract and one fp32 multiply, scores as base-T integers, ties to the lower expert index), so results
+// do not depend on the order in which waves or workgroups run.
+#include "lynx_permute_core.h"
+
+namespace lynx {
+
+constexpr int kRouteTT = 4;        // tokens per logits workgroup
+constexpr int kRouteHC = 4096;     // hidden columns staged in LDS per pass
+constexpr int kTokThreads = 256;   // multi-workgroup token kernels: 4 waves = 4 tokens per workgroup (one per SIMD)
+constexpr int kTokWaves = kTokThreads / kWave;
+constexpr int kSmallThreads = 1024;   // single-workgroup path: 16 waves = 16 tokens
+constexpr int kSmallWaves = kSmallThreads / kWave;
+
+struct ZeroList {
+    int32_t *ptr[7];
+    int count[7];
+    int n;
+};
+
+__device__ __forceinline__ void zero_slices(const ZeroList &z, int wg, int nwg, int tid, int nthreads)
+{
+    for (int a = 0; a < z.n; ++a)
+        for (int i = wg * nthreads + tid; i < z.count[a]; i += nwg * nthreads) z.ptr[a][i] = 0;
+}
+
+__global__ __launch_bounds__(256) void zero_kernel(ZeroList z)
+{
+    zero_slices(z, blockIdx.x, gridDim.x, threadIdx.x, blockDim.x);
+}
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// logits[t,e] = sum_h x[t,h] * Wr[e,h] + bias[e].  Grid (ceil(T/4), ceil(N/4)); wave w owns expert
+// 4*blockIdx.y + w for the workgroup's 4 tokens.  Also clears the scratch of the kernels that follow.
+__global__ __launch_bounds__(256) void logits_kernel(const uint16_t *__restrict__ x, const float *__restrict__ Wr,
+                                                     const float *__restrict__ bias, int T, int H, int N,
+                                                     float *__restrict__ logits, ZeroList z)
+{
+    __shared__ __attribute__((aligned(16))) uint16_t xs[kRouteTT * kRouteHC];
+    const int tid = threadIdx.x, lane = lane_id(), wave = wave_id();
+    zero_slices(z, blockIdx.y * gridDim.x + blockIdx.x, gridDim.x * gridDim.y, tid, 256);
+    const int t0 = blockIdx.x * kRouteTT;
+    const int ntok = min(kRouteTT, T - t0);
+    const int e = blockIdx.y * 4 + wave;
+    const int ec = min(e, N - 1);   // surplus waves redo the last expert and drop the result
+    float acc[kRouteTT];
+#pragma unroll
+    for (int tt = 0; tt < kRouteTT; ++tt) acc[tt] = 0.f;
+
+    constexpr int kIter = kRouteHC / (kWave * 8);   // 8 column groups of 512 per pass
+    for (int h0 = 0; h0 < H; h0 += kRouteHC) {
+        const int hc = min(kRouteHC, H - h0);
+        const int ppr = hc / 8;   // 16-byte pieces per token row
+        // the router row of this pass goes to registers first, so that it is in flight while x is staged
+        const float *w = Wr + (size_t)ec * H + h0;
+        float4 w0[kIter], w1[kIter];
+#pragma unroll
+        for (int i = 0; i < kIter; ++i) {
+            const int h = lane * 8 + i * kWave * 8;
+            const int hcl = min(h, hc - 8);   // past the end: re-read the last piece, weight it with zero below
+            w0[i] = *reinterpret_cast<const float4 *>(w + hcl);
+            w1[i] = *reinterpret_cast<const float4 *>(w + hcl + 4);
+            if (h >= hc) {
+                w0[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+                w1[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+        }
+        if (h0 > 0) __syncthreads();
+        for (int q = tid; q < kRouteTT * ppr; q += 256) {
+            const int tt = q / ppr, pc = q % ppr;
+            uint4 v = make_uint4(0u, 0u, 0u, 0u);
+            if (tt < ntok) v = *reinterpret_cast<const uint4 *>(x + (size_t)(t0 + tt) * H + h0 + pc * 8);
+            *reinterpret_cast<uint4 *>(xs + tt * kRouteHC + pc * 8) = v;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < kIter; ++i) {
+            const int h = min(lane * 8 + i * kWave * 8, hc - 8);
+#pragma unroll
+            for (int tt = 0; tt < kRouteTT; ++tt) {
+                const uint4 xv = *reinterpret_cast<const uint4 *>(xs + tt * kRouteHC + h);
+                float a = acc[tt];
+                a = fmaf(bf16_lo(xv.x), w0[i].x, a);
+                a = fmaf(bf16_hi(xv.x), w0[i].y, a);
+                a = fmaf(bf16_lo(xv.y), w0[i].z, a);
+                a = fmaf(bf16_hi(xv.y), w0[i].w, a);
+                a = fmaf(bf16_lo(xv.z), w1[i].x, a);
+                a = fmaf(bf16_hi(xv.z), w1[i].y, a);
+                a = fmaf(bf16_lo(xv.w), w1[i].z, a);
+                a = fmaf(bf16_hi(xv.w), w1[i].w, a);
+                acc[tt] = a;
+            }
+        }
+    }
+    // transposing butterfly: after two exchange steps each quarter of the wave owns one token's sum
+    const bool hi32 = (lane & 32) != 0;
+    float a0 = hi32 ? acc[2] : acc[0], a1 = hi32 ? acc[3] : acc[1];
+    const float s0 = hi32 ? acc[0] : acc[2], s1 = hi32 ? acc[1] : acc[3];
+    a0 += __shfl_xor(s0, 32, kWave);
+    a1 += __shfl_xor(s1, 32, kWave);
+    const bool hi16 = (lane & 16) != 0;
+    float keep = hi16 ? a1 : a0;
+    const float send = hi16 ? a0 : a1;
+    keep += __shfl_xor(send, 16, kWave);
+#pragma unroll
+    for (int m = 8; m > 0; m >>= 1) keep += __shfl_xor(keep, m, kWave);
+    const int tok = (hi32 ? 2 : 0) + (hi16 ? 1 : 0);
+    if ((lane & 15) == 0 && tok < ntok && e < N) {
+        float zv = keep;
+        if (bias) zv += bias[e];
+        logits[(size_t)(t0 + tok) * N + e] = zv;
+    }
+}
+
+// One wave holds one token's logits: lane l, slot i <-> expert l + 64*i.
+struct TokenLogits {
+    float v[kSlots];
+    unsigned have;   // bit i: slot i is a real expert
+};
+
+__device__ __forceinline__ TokenLogits load_token(const float *__restrict__ z, int N)
+{
+    TokenLogits t;
+    t.have = 0;
+    const int lane = lane_id();
+#pragma unroll
+    for (int i = 0; i < kSlots; ++i) {
+        const int e = lane + kWave * i;
+        t.v[i] = (e < N) ? z[e] : -INFINITY;
+        t.have |= (e < N) ? (1u << i) : 0u;
+    }
+    return t;
+}
+
+__device__ __forceinline__ float token_max(const TokenLogits &t)
+{
+    float m = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < kSlots; ++i) m = fmaxf(m, t.v[i]);
+    return wave_max(m);
+}
+
+// Gates of a selection held one per lane (lane j < k: expert mye, logit myz): softmax over the selected
+// logits (paper Sec. 4, "renormalizes weights").  Returns this lane's gate; num = sum of the numerators.
+__device__ __forceinline__ float selection_gate(int k, int mye, float myz, float &num, float &zref)
+{
+    zref = wave_max(myz);
+    const float mynum = (lane_id() < k && mye >= 0) ? expf(myz - zref) : 0.f;
+    num = wave_sum(mynum);
+    return mynum / num;
+}
+
+// ---- per-token steps (one wave per token), shared by the single-workgroup and the multi-workgroup paths ----
+
+// Softmax + top-k (Sec. 2.1): lane j < k returns the j-th pick in mye; writes idx / gate / psum.
+__device__ __forceinline__ int token_topk(const TokenLogits &tl, int t, int k, int32_t *__restrict__ topk_idx,
+                                          float *__restrict__ topk_gate, float *__restrict__ topk_psum)
+{
+    const int lane = lane_id();
+    int mye = -1;
+    float myz = -INFINITY;
+    wave_topk(tl.v, tl.have, k, [&](int j, int e, float z) {
+        if (lane == j) {
+            mye = (e == INT_MAX) ? -1 : e;
+            myz = z;
+        }
+    });
+    float num, zref;
+    const float g = selection_gate(k, mye, myz, num, zref);
+    float part = 0.f;
+#pragma unroll
+    for (int i = 0; i < kSlots; ++i)
+        if ((tl.have >> i) & 1u) part += expf(tl.v[i] - zref);
+    const float den = wave_sum(part);
+    if (lane < k) {
+        topk_idx[(size_t)t * k + lane] = mye;
+        topk_gate[(size_t)t * k + lane] = g;
+    }
+    if (lane == 0) topk_psum[t] = num / den;
+    return mye;
+}
+
+// Bins of every expert for this token into the (LDS) histogram, and the token's pairs per expert.
+__device__ __forceinline__ void token_bins(const TokenLogits &tl, int k, int mye, float alpha, int beta, int *hist,
+                                           int *cntb)
+{
+    const int lane = lane_id();
+    const float zmax = token_max(tl);
+#pragma unroll
+    for (int i = 0; i < kSlots; ++i)
+        if ((tl.have >> i) & 1u) {
+            const int q = bin_of(zmax, tl.v[i], alpha, beta);
+            if (q >= 0 && q < beta) atomicAdd(&hist[(lane + kWave * i) * beta + q], 1);
+        }
+    if (lane < k && mye >= 0) atomicAdd(&cntb[mye], 1);
+}
+
+// Nominations of one token (Sec. 3.3.1 under the stated reading).  order[r] = expert with the r-th best
+// score, inU[e] = the batch invokes e, sel = the token's own picks in rank order; sets inA[e] = 1.
+__device__ __forceinline__ void token_nominate(const float *__restrict__ z, int N, int k, float alpha, int beta,
+                                               const int *order, const int *inU, const int32_t *sel, int *inA)
+{
+    const int lane = lane_id();
+    const float zmax = token_max(load_token(z, N));
+    int er[kSlots], qr[kSlots];
+    unsigned avail = 0;   // bit i: the expert at score rank lane+64*i is invoked by the batch and not used yet
+#pragma unroll
+    for (int i = 0; i < kSlots; ++i) {
+        const int r = lane + kWave * i;
+        er[i] = (r < N) ? order[r] : 0;
+        qr[i] = (r < N) ? bin_of(zmax, z[er[i]], alpha, beta) : INT_MAX;
+        if (r < N && inU[er[i]]) avail |= 1u << i;
+    }
+    // bins of the token's own picks, one per lane, fetched together (no dependent load inside the slot loop)
+    int myq = beta;
+    if (lane < k) {
+        const int es = sel[lane];
+        if (es >= 0 && es < N) myq = bin_of(zmax, z[es], alpha, beta);
+    }
+    for (int s = 0; s < k; ++s) {
+        const int qs = __builtin_amdgcn_readlane(myq, s);
+        if (qs >= beta) break;   // out of range (or no valid pick): this and all later picks constrain nothing
+        bool found = false;
+#pragma unroll
+        for (int i = 0; i < kSlots; ++i) {
+            if (found) continue;
+            const bool ok = ((avail >> i) & 1u) && qr[i] <= qs;
+            const unsigned long long b = __ballot(ok);
+            if (b != 0ull) {
+                found = true;
+                if (lane == __ffsll((long long)b) - 1) {
+                    avail &= ~(1u << i);
+                    inA[er[i]] = 1;
+                }
+            }
+        }
+    }
+}
+
+// Fill of the active set up to k from the invoked experts in score order (one wave; inA / inU in LDS).
+// Returns the number of invoked experts |U|.
+__device__ __forceinline__ int wave_fill_active(int N, int k, const int *order, const int *inU, int *inA, bool do_fill)
+{
+    const int lane = lane_id();
+    int nA = 0, nU = 0;
+    for (int base = 0; base < N; base += kWave) {
+        const int e = base + lane;
+        nA += __popcll(__ballot(e < N && inA[e] != 0));
+        nU += __popcll(__ballot(e < N && inU[e] != 0));
+    }
+    int need = do_fill ? k - nA : 0;
+    for (int base = 0; base < N && need > 0; base += kWave) {
+        const int r = base + lane;
+        const int e = (r < N) ? order[r] : 0;
+        const bool c = r < N && inU[e] && !inA[e];
+        const unsigned long long b = __ballot(c);
+        if (c && __popcll(b & ((1ull << lane) - 1ull)) < need) inA[e] = 1;
+        need -= __popcll(b);
+    }
+    return nU;
+}
+
+// Selection of one token inside the active set (or its unchanged selection when bypassed) and its gates
+// (Secs. 3.4, 4).  Lane j < k returns the j-th expert; writes new_idx / new_gate.
+__device__ __forceinline__ int token_remap(const float *__restrict__ z, int t, int N, int k, bool bypass, const int *inA,
+                                           const int32_t *sel, int32_t *__restrict__ new_idx,
+                                           float *__restrict__ new_gate)
+{
+    const int lane = lane_id();
+    int mye = -1;
+    float myz = -INFINITY;
+    if (bypass) {
+        if (lane < k) {
+            mye = sel[lane];
+            if (mye < 0 || mye >= N) mye = -1;
+            if (mye >= 0) myz = z[mye];
+        }
+    } else {
+        const TokenLogits tl = load_token(z, N);
+        unsigned cand = 0;
+#pragma unroll
+        for (int i = 0; i < kSlots; ++i)
+            if (((tl.have >> i) & 1u) && inA[lane + kWave * i]) cand |= 1u << i;
+        wave_topk(tl.v, cand, k, [&](int j, int e, float zz) {
+            if (lane == j) {
+                mye = (e == INT_MAX) ? -1 : e;
+                myz = zz;
+            }
+        });
+    }
+    float num, zref;
+    const float g = selection_gate(k, mye, myz, num, zref);
+    if (lane < k) {
+        new_idx[(size_t)t * k + lane] = mye;
+        new_gate[(size_t)t * k + lane] = g;
+    }
+    return mye;
+}
+
+// Scores as base-T integers (most significant digit = bin 0) from a histogram, and the score order:
+// order[r] = expert with the r-th best score, equal scores to the lower index.  Threads tid < N take part;
+// the caller puts barriers around it.
+__device__ __forceinline__ void score_of(int tid, int N, int T, int beta, const int *hist, unsigned long long *score)
+{
+    if (tid < N) {
+        unsigned long long s = 0;
+        for (int j = 0; j < beta; ++j) s = s * (unsigned long long)T + (unsigned long long)hist[tid * beta + j];
+        score[tid] = s;
+    }
+}
+__device__ __forceinline__ void rank_of(int tid, int N, const unsigned long long *score, int *order)
+{
+    if (tid < N) {
+        const unsigned long long s = score[tid];
+        int r = 0;
+        for (int e = 0; e < N; ++e) {
+            const unsigned long long o = score[e];
+            r += (o > s || (o == s && e < tid)) ? 1 : 0;
+        }
+        order[r] = tid;
+    }
+}
+
+// True on every thread of the workgroup that takes the ticket last (all others have finished and fenced).
+__device__ __forceinline__ bool last_workgroup(int32_t *ticket, int *flag_lds)
+{
+    __threadfence();
+    __syncthreads();
+    if (threadIdx.x == 0) *flag_lds = (atomicAdd(ticket, 1) == (int)gridDim.x - 1) ? 1 : 0;
+    __syncthreads();
+    const bool last = *flag_lds != 0;
+    if (last) __threadfence();
+    return last;
+}
+
+// ---- small batches (T <= kSmallT): everything after the logits in ONE workgroup, all state in LDS -----------
+
+constexpr int kSmallT = 16;
+
+struct SmallShared {
+    PermuteShared perm;
+    int hist[LYNX_MAX_N * LYNX_MAX_BETA];
+    unsigned long long score[LYNX_MAX_N];
+    int cntb[LYNX_MAX_N], cnta[LYNX_MAX_N], order[LYNX_MAX_N], inU[LYNX_MAX_N], inA[LYNX_MAX_N];
+    int32_t sel[kSmallT * LYNX_MAX_K];      // the tokens' own picks
+    int32_t newsel[kSmallT * LYNX_MAX_K];   // the remapped picks
+    int n_before, n_after;
+};
+
+template <bool DO_TOPK, bool DO_PERMUTE>
+__global__ __launch_bounds__(kSmallThreads) void routing_small_kernel(
+    const float *__restrict__ logits, int T, int N, int k, float alpha, int beta, int bypass,
+    int32_t *__restrict__ topk_idx, float *__restrict__ topk_gate, float *__restrict__ topk_psum,
+    int32_t *__restrict__ new_idx, float *__restrict__ new_gate, int32_t *__restrict__ cnt_before,
+    int32_t *__restrict__ cnt_after, int32_t *__restrict__ bin_hist, int32_t *__restrict__ num_active,
+    int32_t *__restrict__ expert_offsets, int32_t *__restrict__ perm, int32_t *__restrict__ active_experts,
+    int32_t *__restrict__ num_active_perm)
+{
+    __shared__ SmallShared sh;
+    const int tid = threadIdx.x, lane = lane_id(), wave = wave_id();
+    const int W = (T + 31) / 32;
+    for (int i = tid; i < N * beta; i += kSmallThreads) sh.hist[i] = 0;
+    for (int i = tid; i < N; i += kSmallThreads) {
+        sh.cntb[i] = 0;
+        sh.cnta[i] = 0;
+        sh.inA[i] = 0;
+    }
+    if (DO_PERMUTE) {
+        for (int i = tid; i < N * W; i += kSmallThreads) sh.perm.member[i] = 0u;
+        for (int p = tid; p < T * k; p += kSmallThreads) perm[p] = -1;
+    }
+    if (tid == 0) sh.n_after = 0;
+    __syncthreads();
+    // top-k (or the given picks), bins, histogram
+    for (int t = wave; t < T; t += kSmallWaves) {
+        const TokenLogits tl = load_token(logits + (size_t)t * N, N);
+        int mye = -1;
+        if (DO_TOPK) {
+            mye = token_topk(tl, t, k, topk_idx, topk_gate, topk_psum);
+        } else if (lane < k) {
+            mye = topk_idx[(size_t)t * k + lane];
+            if (mye < 0 || mye >= N) mye = -1;
+        }
+        if (lane < k) sh.sel[t * k + lane] = mye;
+        token_bins(tl, k, mye, alpha, beta, sh.hist, sh.cntb);
+    }
+    __syncthreads();
+    score_of(tid, N, T, beta, sh.hist, sh.score);
+    if (tid < N) sh.inU[tid] = sh.cntb[tid] > 0;
+    __syncthreads();
+    rank_of(tid, N, sh.score, sh.order);
+    __syncthreads();
+    if (!bypass) {
+        for (int t = wave; t < T; t += kSmallWaves)
+            token_nominate(logits + (size_t)t * N, N, k, alpha, beta, sh.order, sh.inU, sh.sel + t * k, sh.inA);
+        __syncthreads();
+    }
+    if (wave == 0) {
+        const int nU = wave_fill_active(N, k, sh.order, sh.inU, sh.inA, !bypass);
+        if (lane == 0) sh.n_before = nU;
+    }
+    __syncthreads();
+    for (int t = wave; t < T; t += kSmallWaves) {
+        const int mye = token_remap(logits + (size_t)t * N, t, N, k, bypass != 0, sh.inA, sh.sel + t * k, new_idx, new_gate);
+        if (lane < k) {
+            sh.newsel[t * k + lane] = mye;
+            if (mye >= 0) {
+                atomicAdd(&sh.cnta[mye], 1);
+                if (DO_PERMUTE) atomicOr(&sh.perm.member[mye * W + (t >> 5)], 1u << (t & 31));
+            }
+        }
+    }
+    __syncthreads();
+    for (int i = tid; i < N * beta; i += kSmallThreads) bin_hist[i] = sh.hist[i];
+    for (int i = tid; i < N; i += kSmallThreads) {
+        cnt_before[i] = sh.cntb[i];
+        cnt_after[i] = sh.cnta[i];
+        if (sh.cnta[i] > 0) atomicAdd(&sh.n_after, 1);
+    }
+    __syncthreads();
+    if (tid == 0) {
+        num_active[0] = sh.n_before;
+        num_active[1] = sh.n_after;
+    }
+    if constexpr (DO_PERMUTE)
+        permute_from_bitsets<kSmallThreads>(sh.perm, sh.newsel, T, N, k, expert_offsets, perm, active_experts,
+                                          num_active_perm);
+}
+
+// ---- large batches: one wave per token over many workgroups, one launch per batch-level dependency ----------
+
+// Softmax + top-k (DO_TOPK) and/or bins + histogram + pairs per expert (DO_BINS, accumulated with atomics
+// into the zeroed outputs).
+template <bool DO_TOPK, bool DO_BINS>
+__global__ __launch_bounds__(kTokThreads) void token_kernel(const float *__restrict__ logits, int T, int N, int k,
+                                                            float alpha, int beta, int32_t *__restrict__ topk_idx,
+                                                            float *__restrict__ topk_gate,
+                                                            float *__restrict__ topk_psum,
+                                                            int32_t *__restrict__ bin_hist,
+                                                            int32_t *__restrict__ cnt_before)
+{
+    __shared__ int hist[DO_BINS ? LYNX_MAX_N * LYNX_MAX_BETA : 1];
+    __shared__ int cntb[DO_BINS ? LYNX_MAX_N : 1];
+    const int tid = threadIdx.x, lane = lane_id(), wave = wave_id();
+    if (DO_BINS) {
+        for (int i = tid; i < N * beta; i += kTokThreads) hist[i] = 0;
+        for (int i = tid; i < N; i += kTokThreads) cntb[i] = 0;
+        __syncthreads();
+    }
+    const int t = blockIdx.x * kTokWaves + wave;
+    if (t < T) {
+        const TokenLogits tl = load_token(logits + (size_t)t * N, N);
+        int mye = -1;
+        if (DO_TOPK) {
+            mye = token_topk(tl, t, k, topk_idx, topk_gate, topk_psum);
+        } else if (lane < k) {
+            mye = topk_idx[(size_t)t * k + lane];
+            if (mye < 0 || mye >= N) mye = -1;
+        }
+        if (DO_BINS) token_bins(tl, k, mye, alpha, beta, hist, cntb);
+    }
+    if (!DO_BINS) return;
+    __syncthreads();
+    for (int i = tid; i < N * beta; i += kTokThreads)
+        if (hist[i]) atomicAdd(&bin_hist[i], hist[i]);
+    for (int i = tid; i < N; i += kTokThreads)
+        if (cntb[i]) atomicAdd(&cnt_before[i], cntb[i]);
+}
+
+// Every workgroup first turns the finished histogram into scores and the score order (cheap, and it saves a
+// launch), then nominates for its tokens.  Workgroup 0 also publishes the order for the remap kernel.
+__global__ __launch_bounds__(kTokThreads) void nominate_kernel(const float *__restrict__ logits,
+                                                               const int32_t *__restrict__ topk_idx,
+                                                               const int32_t *__restrict__ bin_hist,
+                                                               const int32_t *__restrict__ cnt_before, int T, int N,
+                                                               int k, float alpha, int beta, int32_t *__restrict__ ws)
+{
+    __shared__ unsigned long long score[LYNX_MAX_N];
+    __shared__ int order[LYNX_MAX_N], inU[LYNX_MAX_N], inA[LYNX_MAX_N];
+    const int tid = threadIdx.x, wave = wave_id();
+    score_of(tid, N, T, beta, bin_hist, score);
+    if (tid < N) {
+        inU[tid] = cnt_before[tid] > 0;
+        inA[tid] = 0;
+    }
+    __syncthreads();
+    rank_of(tid, N, score, order);
+    __syncthreads();
+    if (blockIdx.x == 0 && tid < N) ws[kWsOrder + tid] = order[tid];
+    const int t = blockIdx.x * kTokWaves + wave;
+    if (t < T) token_nominate(logits + (size_t)t * N, N, k, alpha, beta, order, inU, topk_idx + (size_t)t * k, inA);
+    __syncthreads();
+    if (tid < N && inA[tid]) ws[kWsActive + tid] = 1;
+}
+
+template <bool DO_PERMUTE>
+struct RemapShared {
+    int inA[LYNX_MAX_N], inU[LYNX_MAX_N], order[LYNX_MAX_N], cnta[LYNX_MAX_N];
+    int flag, n_after;
+};
+template <>
+struct RemapShared<true> {
+    PermuteShared perm;
+    int inA[LYNX_MAX_N], inU[LYNX_MAX_N], order[LYNX_MAX_N], cnta[LYNX_MAX_N];
+    int flag, n_after;
+};
+
+// Every workgroup first completes the active set (fill up to k) from the finished nominations, then selects
+// inside it for its tokens.  The last workgroup to finish counts the invoked experts and, with DO_PERMUTE,
+// assigns the tokens (offsets, permutation, invoked-expert list) from the token bit sets.
+template <bool DO_PERMUTE>
+__global__ __launch_bounds__(kTokThreads) void remap_kernel(const float *__restrict__ logits,
+                                                            const int32_t *__restrict__ topk_idx,
+                                                            const int32_t *__restrict__ cnt_before, int T, int N, int k,
+                                                            int bypass, int32_t *__restrict__ ws,
+                                                            int32_t *__restrict__ new_idx, float *__restrict__ new_gate,
+                                                            int32_t *__restrict__ cnt_after,
+                                                            int32_t *__restrict__ num_active,
+                                                            int32_t *__restrict__ expert_offsets,
+                                                            int32_t *__restrict__ perm,
+                                                            int32_t *__restrict__ active_experts,
+                                                            int32_t *__restrict__ num_active_perm)
+{
+    __shared__ RemapShared<DO_PERMUTE> sh;
+    const int tid = threadIdx.x, lane = lane_id(), wave = wave_id();
+    const int W = (T + 31) / 32;
+    if (tid < N) {
+        sh.inA[tid] = bypass ? 0 : ws[kWsActive + tid];
+        sh.inU[tid] = cnt_before[tid] > 0;
+        sh.order[tid] = bypass ? tid : ws[kWsOrder + tid];
+        sh.cnta[tid] = 0;
+    }
+    if (tid == 0) sh.n_after = 0;
+    if (DO_PERMUTE) {   // pairs whose expert is invalid stay unassigned
+        const int p0 = blockIdx.x * kTokWaves * k, p1 = min(T * k, p0 + kTokWaves * k);
+        for (int p = p0 + tid; p < p1; p += kTokThreads) perm[p] = -1;
+    }
+    __syncthreads();
+    if (wave == 0) {
+        const int nU = wave_fill_active(N, k, sh.order, sh.inU, sh.inA, !bypass);
+        if (blockIdx.x == 0 && lane == 0) num_active[0] = nU;
+    }
+    __syncthreads();
+    const int t = blockIdx.x * kTokWaves + wave;
+    if (t < T) {
+        const int mye = token_remap(logits + (size_t)t * N, t, N, k, bypass != 0, sh.inA, topk_idx + (size_t)t * k, new_idx,
+                                    new_gate);
+        if (lane < k && mye >= 0) {
+            atomicAdd(&sh.cnta[mye], 1);
+            if (DO_PERMUTE) atomicOr(reinterpret_cast<unsigned *>(ws + kWsMember) + mye * W + (t >> 5), 1u << (t & 31));
+        }
+    }
+    __syncthreads();
+    if (tid < N && sh.cnta[tid]) atomicAdd(&cnt_after[tid], sh.cnta[tid]);
+    if (!last_workgroup(ws + kWsTickets + 2, &sh.flag)) return;
+    if (tid < N && __atomic_load_n(&cnt_after[tid], __ATOMIC_RELAXED) > 0) atomicAdd(&sh.n_after, 1);
+    if constexpr (DO_PERMUTE) {
+        const unsigned *member = reinterpret_cast<const unsigned *>(ws + kWsMember);
+        for (int i = tid; i < N * W; i += kTokThreads) sh.perm.member[i] = __atomic_load_n(&member[i], __ATOMIC_RELAXED);
+    }
+    __syncthreads();
+    if (tid == 0) num_active[1] = sh.n_after;
+    if constexpr (DO_PERMUTE)
+        permute_from_bitsets<kTokThreads>(sh.perm, new_idx, T, N, k, expert_offsets, perm, active_experts,
+                                          num_active_perm);
+}
+
+static int check_routing_sizes(const char *who, int T, int N, int k)
+{
+    if (T < 0 || N <= 0 || k <= 0) return fail(LYNX_ERR_INVALID_ARG, "%s: negative or zero size (T=%d N=%d k=%d)", who, T, N, k);
+    if (k > N || N > LYNX_MAX_N || k > LYNX_MAX_K || T > LYNX_MAX_T)
+        return fail(LYNX_ERR_UNSUPPORTED, "%s: need k<=N<=%d, k<=%d, T<=%d (T=%d N=%d k=%d)", who, LYNX_MAX_N, LYNX_MAX_K,
+                    LYNX_MAX_T, T, N, k);
+    return LYNX_OK;
+}
+
+static int check_bin_params(const char *who, int T, float alpha, int beta)
+{
+    if (beta < 1 || !(alpha >= 0.0f) || alpha > 3.0e38f)
+        return fail(LYNX_ERR_INVALID_ARG, "%s: alpha must be finite and >= 0, beta >= 1 (alpha=%g beta=%d)", who,
+                    (double)alpha, beta);
+    if (beta > LYNX_MAX_BETA) return fail(LYNX_ERR_UNSUPPORTED, "%s: beta <= %d", who, LYNX_MAX_BETA);
+    double lim = 1.0;
+    for (int j = 0; j < beta; ++j) lim *= (double)(T > 1 ? T : 1);
+    if (lim >= 4611686018427387904.0)
+        return fail(LYNX_ERR_UNSUPPORTED, "%s: T^beta must stay below 2^62 (T=%d beta=%d)", who, T, beta);
+    return LYNX_OK;
+}
+
+static void add_zero(ZeroList &z, int32_t *p, int count)
+{
+    z.ptr[z.n] = p;
+    z.count[z.n] = count;
+    ++z.n;
+}
+
+static void launch_logits(const uint16_t *x, const float *Wr, const float *bias, int T, int H, int N, float *logits,
+                          const ZeroList &z, hipStream_t st)
+{
+    hipLaunchKernelGGL(logits_kernel, dim3((T + kRouteTT - 1) / kRouteTT, (N + 3) / 4), dim3(256), 0, st, x, Wr, bias, T,
+                       H, N, logits, z);
+}
+
+// Everything after the logits.  DO_TOPK: compute the top-k (else topk_idx is an input); DO_PERMUTE: also
+// assign the tokens.  clear_first: the multi-workgroup path accumulates into zeroed arrays; true = clear them
+// with a launch of their own, false = the caller already had them cleared (by the logits kernel).
+template <bool DO_TOPK, bool DO_PERMUTE>
+static int launch_after_logits(const char *who, const float *logits, int T, int N, int k, float alpha, int beta,
+                               int enable, int32_t *topk_idx, float *topk_gate, float *topk_psum, int32_t *new_idx,
+                               float *new_gate, int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist,
+                               int32_t *num_active, int32_t *expert_offsets, int32_t *perm, int32_t *active_experts,
+                               int32_t *num_active_perm, int32_t *ws, bool clear_first, hipStream_t st)
+{
+    const int bypass = (!enable || T <= 1) ? 1 : 0;
+    if (T <= kSmallT) {
+        hipLaunchKernelGGL((routing_small_kernel<DO_TOPK, DO_PERMUTE>), dim3(1), dim3(kSmallThreads), 0, st, logits, T, N, k,
+                           alpha, beta, bypass, topk_idx, topk_gate, topk_psum, new_idx, new_gate, cnt_before, cnt_after,
+                           bin_hist, num_active, expert_offsets, perm, active_experts, num_active_perm);
+        return check_launch(who);
+    }
+    int rc;
+    if (clear_first) {
+        ZeroList z;
+        z.n = 0;
+        add_zero(z, ws + kWsTickets, 16);
+        add_zero(z, ws + kWsActive, N);
+        if (DO_PERMUTE) add_zero(z, ws + kWsMember, N * ((T + 31) / 32));
+        add_zero(z, bin_hist, N * beta);
+        add_zero(z, cnt_before, N);
+        add_zero(z, cnt_after, N);
+        hipLaunchKernelGGL(zero_kernel, dim3(8), dim3(256), 0, st, z);
+        rc = check_launch(who);
+        if (rc != LYNX_OK) return rc;
+    }
+    const dim3 tgrid((T + kTokWaves - 1) / kTokWaves), tblock(kTokThreads);
+    hipLaunchKernelGGL((token_kernel<DO_TOPK, true>), tgrid, tblock, 0, st, logits, T, N, k, alpha, beta, topk_idx,
+                       topk_gate, topk_psum, bin_hist, cnt_before);
+    rc = check_launch(who);
+    if (rc != LYNX_OK) return rc;
+    if (!bypass) {
+        hipLaunchKernelGGL(nominate_kernel, tgrid, tblock, 0, st, logits, topk_idx, bin_hist, cnt_before, T, N, k, alpha,
+                           beta, ws);
+        rc = check_launch(who);
+        if (rc != LYNX_OK) return rc;
+    }
+    hipLaunchKernelGGL((remap_kernel<DO_PERMUTE>), tgrid, tblock, 0, st, logits, topk_idx, cnt_before, T, N, k, bypass, ws,
+                       new_idx, new_gate, cnt_after, num_active, expert_offsets, perm, active_experts, num_active_perm);
+    return check_launch(who);
+}
+
+// The whole routing side of lynx_moe_layer: two launches for T <= 64, four otherwise.  T >= 1, arguments checked.
+int routing_fused(const uint16_t *x, const float *Wr, const float *bias, int T, int H, int N, int k, float alpha,
+                  int beta, int enable, float *logits, int32_t *topk_idx, float *topk_gate, float *topk_psum,
+                  int32_t *new_idx, float *new_gate, int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist,
+                  int32_t *num_active, int32_t *expert_offsets, int32_t *perm, int32_t *active_experts,
+                  int32_t *num_active_perm, void *workspace, hipStream_t st)
+{
+    int32_t *ws = reinterpret_cast<int32_t *>(workspace);
+    ZeroList z;
+    z.n = 0;
+    if (T > kSmallT) {   // the logits kernel clears what the multi-workgroup kernels accumulate into
+        add_zero(z, ws + kWsTickets, 16);
+        add_zero(z, ws + kWsActive, N);
+        add_zero(z, ws + kWsMember, N * ((T + 31) / 32));
+        add_zero(z, bin_hist, N * beta);
+        add_zero(z, cnt_before, N);
+        add_zero(z, cnt_after, N);
+    }
+    launch_logits(x, Wr, bias, T, H, N, logits, z, st);
+    int rc = check_launch("lynx_moe_layer(logits)");
+    if (rc != LYNX_OK) return rc;
+    return launch_after_logits<true, true>("lynx_moe_layer(routing)", logits, T, N, k, alpha, beta, enable, topk_idx,
+                                           topk_gate, topk_psum, new_idx, new_gate, cnt_before, cnt_after, bin_hist,
+                                           num_active, expert_offsets, perm, active_experts, num_active_perm, ws, false, st);
+}
+
+}  // namespace lynx
+
+extern "C" int lynx_route(const uint16_t *x_bf16, const float *Wr, const float *bias, int T, int H, int N, int k,
+                          float *logits, int32_t *topk_idx, float *topk_gate, float *topk_psum, void *stream)
+{
+    using namespace lynx;
+    int rc = check_routing_sizes("lynx_route", T, N, k);
+    if (rc != LYNX_OK) return rc;
+    if (H <= 0) return fail(LYNX_ERR_INVALID_ARG, "lynx_route: H must be positive");
+    if ((H % 32) != 0) return fail(LYNX_ERR_UNSUPPORTED, "lynx_route: H must be a multiple of 32 (H=%d)", H);
+    if (T == 0) return LYNX_OK;
+    if (!x_bf16 || !Wr || !logits || !topk_idx || !topk_gate || !topk_psum)
+        return fail(LYNX_ERR_INVALID_ARG, "lynx_route: null pointer");
+    hipStream_t st = (hipStream_t)stream;
+    ZeroList z;
+    z.n = 0;
+    launch_logits(x_bf16, Wr, bias, T, H, N, logits, z, st);
+    rc = check_launch("lynx_route(logits)");
+    if (rc != LYNX_OK) return rc;
+    hipLaunchKernelGGL((token_kernel<true, false>), dim3((T + kTokWaves - 1) / kTokWaves), dim3(kTokThreads), 0, st,
+                       logits, T, N, k, 0.f, 1, topk_idx, topk_gate, topk_psum, nullptr, nullptr);
+    return check_launch("lynx_route(top-k)");
+}
+
+extern "C" int lynx_affinity_bin(const float *logits, const int32_t *topk_idx, int T, int N, int k, float alpha,
+                                 int beta, int enable, int32_t *new_idx, float *new_gate, int32_t *cnt_before,
+                                 int32_t *cnt_after, int32_t *bin_hist, int32_t *num_active, void *workspace,
+                                 void *stream)
+{
+    using namespace lynx;
+    int rc = check_routing_sizes("lynx_affinity_bin", T, N, k);
+    if (rc != LYNX_OK) return rc;
+    rc = check_bin_params("lynx_affinity_bin", T, alpha, beta);
+    if (rc != LYNX_OK) return rc;
+    if (!cnt_before || !cnt_after || !bin_hist || !num_active || !workspace)
+        return fail(LYNX_ERR_INVALID_ARG, "lynx_affinity_bin: null output or workspace pointer");
+    if (T > 0 && (!logits || !topk_idx || !new_idx || !new_gate))
+        return fail(LYNX_ERR_INVALID_ARG, "lynx_affinity_bin: null pointer");
+    hipStream_t st = (hipStream_t)stream;
+    int32_t *ws = reinterpret_cast<int32_t *>(workspace);
+    if (T == 0) {
+        ZeroList z;
+        z.n = 0;
+        add_zero(z, bin_hist, N * beta);
+        add_zero(z, cnt_before, N);
+        add_zero(z, cnt_after, N);
+        add_zero(z, num_active, 2);
+        hipLaunchKernelGGL(zero_kernel, dim3(1), dim3(256), 0, st, z);
+        return check_launch("lynx_affinity_bin(clear)");
+    }
+    return launch_after_logits<false, false>("lynx_affinity_bin", logits, T, N, k, alpha, beta, enable,
+                                             const_cast<int32_t *>(topk_idx), nullptr, nullptr, new_idx, new_gate,
+                                             cnt_before, cnt_after, bin_hist, num_active, nullptr, nullptr, nullptr,
+                                             nullptr, ws, true, st);
+}

@@ -272,6 +272,29 @@ def test_layer_small_shared_expert_configs(L, name, T):
     _say(f"{name}-shaped (N=12) layer T={T}: invoked {na.tolist()}, max row err {err:.3e}")
 
 
+@pytest.mark.parametrize("name,T,preset", [("tiny", 16, "moderate"), ("tiny", 1, "aggressive"), ("tiny", 37, "aggressive")])
+def test_fused_layer_equals_separate_calls(L, name, T, preset):
+    # lynx_moe_layer issues fused launches; every output must be bit-identical to the four separate calls
+    cfg = wl.CONFIGS[name]
+    alpha, beta = wl.PRESETS[preset]
+    d = wl.make_layer(cfg, T)
+    x, Wr, bias = to_bf16_dev(d["x"]), dev(d["Wr"]), dev(d["bias"])
+    Wgu, Wdp = L.lynx_pack_weights(to_bf16_dev(d["Wg"]), to_bf16_dev(d["Wu"]), to_bf16_dev(d["Wd"]))
+    b = L.lynx_moe_layer(x, Wr, bias, Wgu, Wdp, cfg.F, cfg.k, alpha, beta, 1)
+    r = L.lynx_route(x, Wr, bias, cfg.k)
+    a = L.lynx_affinity_bin(r["logits"], r["idx"], alpha, beta, 1)
+    p = L.lynx_permute(a["new_idx"], cfg.N)
+    y = L.lynx_moe_ffn(x, Wgu, Wdp, a["new_idx"], a["new_gate"], p, cfg.N, cfg.F)
+    torch.cuda.synchronize()
+    pairs = [(b.logits, r["logits"]), (b.topk_idx, r["idx"]), (b.topk_gate, r["gate"]), (b.topk_psum, r["psum"]),
+             (b.new_idx, a["new_idx"]), (b.new_gate, a["new_gate"]), (b.cnt_before, a["cnt_before"]),
+             (b.cnt_after, a["cnt_after"]), (b.bin_hist, a["bin_hist"]), (b.num_active, a["num_active"]),
+             (b.offsets, p["offsets"]), (b.perm, p["perm"]), (b.active, p["active"]), (b.num_active_perm, p["num_active"]),
+             (b.y, y)]
+    for i, (u, v) in enumerate(pairs):
+        assert torch.equal(u, v), i
+
+
 def test_layer_zero_tokens(L):
     cfg = wl.CONFIGS["tiny"]
     d = wl.make_layer(cfg, 0)
