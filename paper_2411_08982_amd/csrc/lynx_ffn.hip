@@ -28,7 +28,7 @@ constexpr int kFfnThreads = 256;
 constexpr int kFfnWaves = kFfnThreads / kWave;
 constexpr int kPF = 8;                       // weight tiles in flight per wave and matrix
 constexpr int kDirectMaxTokens = 16;         // experts with more tokens go to the staged kernel
-constexpr int kStagedNT = 8;                 // token tiles (of 16) per pass of the staged kernel
+constexpr int kStagedNT = 4;                 // token tiles (of 16) per pass of the staged path
 constexpr int kTokBlock = 16 * kStagedNT;
 constexpr int kStageBytes = 2 * 18432;       // two LDS buffers for the staged token tile
 
@@ -418,7 +418,7 @@ __device__ __forceinline__ void expert_staged(const WorkItem &w, const int *rowo
 // One launch per projection.  Grid: (routed expert rank, tile of 16*RW rows) + (shared expert, K slice,
 // tile), RW = 4 / KW.  An expert with at most kDirectMaxTokens tokens takes the direct path with the
 // workgroup's four waves as RW row tiles x KW slices of K.  A larger expert takes the staged path, in which
-// a workgroup covers 64 rows: of every KW consecutive workgroups one does the work, in passes of up to 128
+// a workgroup covers 64 rows: of every KW consecutive workgroups one does the work, in passes of up to 64
 // tokens, and the others leave.
 template <bool DUAL, int KW>
 __global__ __launch_bounds__(kFfnThreads, 2) void expert_kernel(GemmParams p)
@@ -447,10 +447,8 @@ __global__ __launch_bounds__(kFfnThreads, 2) void expert_kernel(GemmParams p)
         __syncthreads();
         if (nb <= 32)
             expert_staged<DUAL, 2, 8>(w, rowoff, outrow, stage);
-        else if (nb <= 64)
-            expert_staged<DUAL, 4, 4>(w, rowoff, outrow, stage);
         else
-            expert_staged<DUAL, 8, 2>(w, rowoff, outrow, stage);
+            expert_staged<DUAL, 4, 4>(w, rowoff, outrow, stage);
     }
 }
 
