@@ -1,0 +1,173 @@
+"""GPU parity at the full sizes of the benchmark configurations, through the same fused entry point
+(`lynx_moe_layer`) and launch configuration that bench.py times.
+
+Routing outputs are small, so they are compared in full: logits against the oracle's own router, and
+every integer output (indices, counts, histogram, offsets, permutation, invoked-expert list) bit-exact
+against the oracle fed with the GPU's fp32 logits.  The layer output is compared on sampled tokens,
+which the oracle computes one by one from the weights of just the experts those tokens use; properties
+that hold at any size (finite output, gates summing to 1, invoked experts not rising) are checked on
+the whole batch.  Inputs are synthetic (workloads.py); expert weights are drawn on the device.
+"""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads as wl
+from gpu_util import bf16_bits, dev, host, row_rel_err, to_bf16_dev
+
+pytestmark = pytest.mark.gpu
+
+Y_TOL = 1e-2
+LOGIT_TOL = 1e-5
+GATE_TOL = 1e-5
+
+
+@pytest.fixture(scope="module")
+def L():
+    import paper_2411_08982_amd as lib
+    lib.lib()
+    assert torch.cuda.is_available()
+    return lib
+
+
+class DeviceLayer:
+    def __init__(self, L, cfg, T):
+        d = wl.make_layer_device(cfg, T, "cuda")
+        self.cfg, self.d = cfg, d
+        self.Wgu, self.Wdp = L.lynx_pack_weights(d["Wg"], d["Wu"], d["Wd"])
+        self.Sgu = self.Sdp = None
+        if cfg.n_shared:
+            self.Sgu, self.Sdp = L.lynx_pack_weights(d["Sg"], d["Su"], d["Sd"])
+        torch.cuda.synchronize()
+
+    def tokens(self, T):
+        Wr, bias = host(self.d["Wr"]), host(self.d["bias"])
+        return wl.make_tokens(self.cfg, T, Wr, bias)
+
+
+_layers = {}
+
+
+def _layer(L, name):
+    if name not in _layers:
+        _layers.clear()          # one large layer resident at a time
+        torch.cuda.empty_cache()
+        cfg = wl.CONFIGS[name]
+        _layers[name] = DeviceLayer(L, cfg, cfg.batches[0])
+    return _layers[name]
+
+
+def _check_layer(L, lay, T, alpha, beta, enable, n_sample=5, seed=0):
+    cfg, d = lay.cfg, lay.d
+    xb = lay.tokens(T)
+    x = to_bf16_dev(xb)
+    b = L.lynx_moe_layer(x, d["Wr"], d["bias"], lay.Wgu, lay.Wdp, cfg.F, cfg.k, alpha, beta, enable, lay.Sgu, lay.Sdp,
+                         cfg.n_shared, cfg.F_shared)
+    torch.cuda.synchronize()
+    Wr, bias = host(d["Wr"]), host(d["bias"])
+    # routing, whole batch
+    r = oracle.route(xb, Wr, bias, cfg.k)
+    z = host(b.logits)
+    assert np.all(np.abs(z - r["logits"]) <= LOGIT_TOL * np.maximum(1.0, np.abs(r["logits"])))
+    tk = oracle.topk(z, cfg.k)
+    assert np.array_equal(host(b.topk_idx), tk["idx"])
+    np.testing.assert_allclose(host(b.topk_gate), tk["gate"], rtol=GATE_TOL, atol=1e-7)
+    np.testing.assert_allclose(host(b.topk_psum), tk["psum"], rtol=GATE_TOL, atol=1e-7)
+    a = oracle.affinity_bin(z, tk["idx"], alpha, beta, enable)
+    for key, got in (("new_idx", b.new_idx), ("cnt_before", b.cnt_before), ("cnt_after", b.cnt_after),
+                     ("bin_hist", b.bin_hist), ("num_active", b.num_active)):
+        assert np.array_equal(host(got), a[key]), key
+    g = host(b.new_gate)
+    np.testing.assert_allclose(g, a["new_gate"], rtol=GATE_TOL, atol=1e-7)
+    p = oracle.permute(a["new_idx"], cfg.N)
+    for key, got in (("offsets", b.offsets), ("perm", b.perm), ("active", b.active), ("num_active", b.num_active_perm)):
+        assert np.array_equal(host(got), p[key]), key
+    # properties on the whole batch
+    y = host(b.y)
+    assert np.all(np.isfinite(y))
+    np.testing.assert_allclose(g.sum(1), 1.0, rtol=1e-5)
+    assert a["num_active"][1] <= a["num_active"][0]
+    # sampled tokens against the oracle, with only the experts those tokens use copied to the host
+    rng = np.random.default_rng(seed)
+    toks = sorted(set([0, T - 1] + rng.choice(T, size=min(T, n_sample), replace=False).tolist()))
+    sel = a["new_idx"][toks]
+    used = np.unique(sel)
+    remap = {int(e): i for i, e in enumerate(used)}
+    sel_c = np.vectorize(remap.get)(sel).astype(np.int32)
+    ue = torch.from_numpy(used.astype(np.int64)).cuda()
+    Wg, Wu, Wd = (bf16_bits(d[k_].index_select(0, ue)) for k_ in ("Wg", "Wu", "Wd"))
+    Sg = Su = Sd = None
+    if cfg.n_shared:
+        Sg, Su, Sd = (bf16_bits(d[k_]) for k_ in ("Sg", "Su", "Sd"))
+    y_ref = oracle.moe_ffn(xb[toks], Wg, Wu, Wd, sel_c, a["new_gate"][toks], Sg, Su, Sd)
+    err = row_rel_err(y[toks], y_ref)
+    assert err.max() <= Y_TOL, f"max row error {err.max():.3e} on tokens {toks}"
+    return a["num_active"], err.max()
+
+
+FULL = [("mixtral", 8, "aggressive"), ("mixtral", 1, "aggressive"), ("mixtral", 32, "moderate"), ("mixtral", 128, "off"),
+        ("qwen15moe", 8, "aggressive"), ("qwen15moe", 64, "moderate"), ("qwen15moe", 256, "aggressive"),
+        ("dsv2lite", 16, "aggressive"), ("dsv2lite", 128, "moderate"), ("dsv2lite", 256, "aggressive"),
+        ("qwen3", 32, "aggressive"), ("qwen3", 128, "moderate"), ("qwen3", 512, "aggressive")]
+
+
+@pytest.mark.parametrize("name,T,preset", FULL)
+def test_full_size_layer(L, name, T, preset):
+    print(f"full-size layer {name} T={T} remap={preset}", flush=True)
+    lay = _layer(L, name)
+    if preset == "off":
+        alpha, beta, enable = 2.0, 2, 0
+    else:
+        (alpha, beta), enable = wl.PRESETS[preset], 1
+    na, err = _check_layer(L, lay, T, alpha, beta, enable)
+    print(f"  invoked {na.tolist()}, max sampled row err {err:.3e}", flush=True)
+
+
+def test_release_large_layers():
+    _layers.clear()
+    torch.cuda.empty_cache()
+
+
+# ---- limits and ragged sizes through the fused entry point, small H / F so that the oracle does the whole batch ----
+
+EDGE = [
+    # T,    N,   k,  H,  F, S, Fs
+    (1024, 256, 16, 64, 64, 0, 0),     # every documented maximum at once
+    (17, 20, 3, 96, 160, 1, 64),       # just past the single-workgroup routing path
+    (16, 20, 3, 96, 160, 0, 0),        # the largest batch of the single-workgroup routing path
+    (65, 9, 9, 64, 96, 2, 32),         # k = N: nothing to remap; 65 tokens on every expert (two staged passes)
+    (33, 128, 8, 32, 32, 0, 0),        # smallest H and F
+    (2, 5, 1, 64, 64, 0, 0),           # k = 1
+]
+
+
+@pytest.mark.parametrize("T,N,k,H,F,S,Fs", EDGE)
+def test_edge_sizes(L, T, N, k, H, F, S, Fs):
+    print(f"edge layer T={T} N={N} k={k} H={H} F={F} shared={S}x{Fs}", flush=True)
+    cfg = dataclasses.replace(wl.CONFIGS["tiny"], name="edge", H=H, F=F, N=N, k=k, n_shared=S, F_shared=Fs, seed=T + N)
+    d = wl.make_layer(cfg, T)
+    x, Wr, bias = to_bf16_dev(d["x"]), dev(d["Wr"]), dev(d["bias"])
+    Wgu, Wdp = L.lynx_pack_weights(to_bf16_dev(d["Wg"]), to_bf16_dev(d["Wu"]), to_bf16_dev(d["Wd"]))
+    Sgu = Sdp = None
+    if S:
+        Sgu, Sdp = L.lynx_pack_weights(to_bf16_dev(d["Sg"]), to_bf16_dev(d["Su"]), to_bf16_dev(d["Sd"]))
+    for alpha, beta in ((4.0, 1), (1.0, 3)):
+        b = L.lynx_moe_layer(x, Wr, bias, Wgu, Wdp, F, k, alpha, beta, 1, Sgu, Sdp, S, Fs)
+        torch.cuda.synchronize()
+        z = host(b.logits)
+        r = oracle.route(d["x"], d["Wr"], d["bias"], k)
+        assert np.all(np.abs(z - r["logits"]) <= LOGIT_TOL * np.maximum(1.0, np.abs(r["logits"])))
+        tk = oracle.topk(z, k)
+        a = oracle.affinity_bin(z, tk["idx"], alpha, beta, 1)
+        p = oracle.permute(a["new_idx"], N)
+        for key, got in (("new_idx", b.new_idx), ("cnt_after", b.cnt_after), ("bin_hist", b.bin_hist),
+                         ("num_active", b.num_active)):
+            assert np.array_equal(host(got), a[key]), key
+        for key, got in (("offsets", b.offsets), ("perm", b.perm), ("active", b.active)):
+            assert np.array_equal(host(got), p[key]), key
+        y_ref = oracle.moe_ffn(d["x"], d["Wg"], d["Wu"], d["Wd"], a["new_idx"], a["new_gate"], d["Sg"], d["Su"], d["Sd"])
+        err = row_rel_err(host(b.y), y_ref)
+        assert err.max() <= Y_TOL, f"max row error {err.max():.3e}"
