@@ -36,6 +36,9 @@ def parse():
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sweep-iters", type=int, default=10)
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="before the steps, run a plain 1 GiB read + 1 GiB write elementwise kernel three times: under "
+                         "rocprofv3 --pmc its FETCH_SIZE / WRITE_SIZE readings give the counters' scale")
     return ap.parse_args()
 
 
@@ -111,6 +114,13 @@ def main():
     alpha, beta, enable = preset_args(wl, args.preset)
     layer = Layer(cfg, T, keep_row_major=not args.no_cpu_baseline)
 
+    if args.pmc_calibration:
+        a = torch.ones(1 << 28, dtype=torch.float32, device="cuda")   # 1 GiB
+        c = torch.empty_like(a)
+        for _ in range(3):
+            torch.mul(a, 1.0, out=c)                                    # plain copy kernel: reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del a, c
     K, W = args.steps, args.warmup
     for _ in range(W):
         layer.step(T, alpha, beta, enable)
