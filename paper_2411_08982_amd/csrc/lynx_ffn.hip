@@ -203,19 +203,20 @@ __device__ __forceinline__ uint4 ring_load(const uint4 *__restrict__ base, int i
     return base[index];
 }
 
-template <bool DUAL, int NT>
-__device__ __forceinline__ void stream_direct(const uint4 *__restrict__ Wt, int n, const uint4 *const (&brow)[NT],
-                                              f32x4 (&accg)[NT], f32x4 (&accu)[NT])
+// Two weight streams share every B fragment: gate and up tiles (interleaved: second = 64, step = 128) or,
+// for the down projection, two consecutive row tiles (second = one row tile further, step = 64).
+template <int NT>
+__device__ __forceinline__ void stream_direct(const uint4 *__restrict__ Wt, int step, int second, int n,
+                                              const uint4 *const (&brow)[NT], f32x4 (&acc0)[NT], f32x4 (&acc1)[NT])
 {
-    constexpr int WSTEP = DUAL ? 2 * kWave : kWave;
     const uint4 *Wl = Wt + lane_id();
     const int last = n - 1;
-    uint4 wg[kPF], wu[kPF], bb[kPF][NT];
+    uint4 w0[kPF], w1[kPF], bb[kPF][NT];
 #pragma unroll
     for (int j = 0; j < kPF; ++j) {
         const int s = min(j, last);
-        wg[j] = ring_load(Wl, s * WSTEP);
-        wu[j] = DUAL ? ring_load(Wl, s * WSTEP + kWave) : zero4();
+        w0[j] = ring_load(Wl, s * step);
+        w1[j] = ring_load(Wl, s * step + second);
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) bb[j][nt] = ring_load(brow[nt], s * 4);
     }
@@ -225,20 +226,20 @@ __device__ __forceinline__ void stream_direct(const uint4 *__restrict__ Wt, int 
             const int s = s0 + u;
             const bool live = s < n;
             // consume slot u ...
-            const bf16x8 ag = __builtin_bit_cast(bf16x8, sel4(live, wg[u]));
-            const bf16x8 au = __builtin_bit_cast(bf16x8, sel4(live, wu[u]));
+            const bf16x8 a0 = __builtin_bit_cast(bf16x8, sel4(live, w0[u]));
+            const bf16x8 a1 = __builtin_bit_cast(bf16x8, sel4(live, w1[u]));
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
                 const bf16x8 b = __builtin_bit_cast(bf16x8, bb[u][nt]);
-                accg[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ag, b, accg[nt], 0, 0, 0);
-                if (DUAL) accu[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(au, b, accu[nt], 0, 0, 0);
+                acc0[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, b, acc0[nt], 0, 0, 0);
+                acc1[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, b, acc1[nt], 0, 0, 0);
             }
             // ... then refill it (the scheduling fences keep the refill behind the last read of the slot,
             // so that it can land in the same registers and the ring needs no copies)
             __builtin_amdgcn_sched_barrier(0);
             const int sn = min(s + kPF, last);
-            wg[u] = ring_load(Wl, sn * WSTEP);
-            if (DUAL) wu[u] = ring_load(Wl, sn * WSTEP + kWave);
+            w0[u] = ring_load(Wl, sn * step);
+            w1[u] = ring_load(Wl, sn * step + second);
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) bb[u][nt] = ring_load(brow[nt], sn * 4);
             __builtin_amdgcn_sched_barrier(0);
@@ -246,19 +247,20 @@ __device__ __forceinline__ void stream_direct(const uint4 *__restrict__ Wt, int 
     }
 }
 
-// One expert with <= 16*NT tokens: the four waves are RW row tiles x KW slices of K; the slices are
-// summed through LDS at the end.
+// One expert with <= 16*NT tokens: the four waves are RW row groups x KW slices of K; the slices are
+// summed through LDS at the end.  A row group is one 16-row tile of gate and up (gate/up) or two
+// consecutive 16-row tiles (down), so that every token fragment loaded feeds two MFMAs.
 template <bool DUAL, int NT, int KW>
 __device__ __forceinline__ void expert_direct(const GemmParams &p, const WorkItem &w, float *red)
 {
     constexpr int RW = kFfnWaves / KW;
-    constexpr int WSTEP = DUAL ? 2 * kWave : kWave;
-    constexpr int NACC = NT * (DUAL ? 2 : 1);
+    constexpr int NACC = NT * 2;
     const int lane = lane_id(), wv = wave_id();
     const int rw = wv / KW, kw = wv % KW;
     const int KT = w.K / 32;
-    const int rt = w.tile * RW + rw;
-    const bool rows_ok = rt * 16 < w.R;
+    const int grp = w.tile * RW + rw;                      // row group of this wave
+    const int rt = DUAL ? grp : 2 * grp;                   // its first 16-row tile
+    const bool rows_ok = rt * 16 < w.R;                    // (down: R/16 is even, so the second tile exists too)
     const int per = (w.ksteps + KW - 1) / KW;
     const int kb = w.kbeg + kw * per;
     const int n = min(w.kbeg + w.ksteps, kb + per) - kb;
@@ -272,17 +274,22 @@ __device__ __forceinline__ void expert_direct(const GemmParams &p, const WorkIte
         ro = max(ro, 0);   // columns without a token read row 0; their results are never stored
         brow[nt] = reinterpret_cast<const uint4 *>(w.B + (size_t)ro + (size_t)kb * 32 + (lane >> 4) * 8);
     }
-    f32x4 accg[NT], accu[NT];
-    clear_acc<NT>(accg, accu);
-    if (rows_ok && n > 0) stream_direct<DUAL, NT>(w.W + ((size_t)rt * KT + kb) * WSTEP, n, brow, accg, accu);
+    f32x4 acc0[NT], acc1[NT];
+    clear_acc<NT>(acc0, acc1);
+    if (rows_ok && n > 0) {
+        if (DUAL)
+            stream_direct<NT>(w.W + ((size_t)rt * KT + kb) * (2 * kWave), 2 * kWave, kWave, n, brow, acc0, acc1);
+        else
+            stream_direct<NT>(w.W + ((size_t)rt * KT + kb) * kWave, kWave, KT * kWave, n, brow, acc0, acc1);
+    }
     if (KW > 1) {
         f32x4 *r4 = reinterpret_cast<f32x4 *>(red);   // [rw][kw-1][NACC][lane]
         if (kw > 0) {
             f32x4 *dst = r4 + ((size_t)(rw * (KW - 1) + (kw - 1)) * NACC) * kWave + lane;
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
-                dst[(size_t)nt * kWave] = accg[nt];
-                if (DUAL) dst[(size_t)(NT + nt) * kWave] = accu[nt];
+                dst[(size_t)nt * kWave] = acc0[nt];
+                dst[(size_t)(NT + nt) * kWave] = acc1[nt];
             }
         }
         __syncthreads();
@@ -292,13 +299,20 @@ __device__ __forceinline__ void expert_direct(const GemmParams &p, const WorkIte
                 const f32x4 *src = r4 + ((size_t)(rw * (KW - 1) + (j - 1)) * NACC) * kWave + lane;
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt) {
-                    accg[nt] += src[(size_t)nt * kWave];
-                    if (DUAL) accu[nt] += src[(size_t)(NT + nt) * kWave];
+                    acc0[nt] += src[(size_t)nt * kWave];
+                    acc1[nt] += src[(size_t)(NT + nt) * kWave];
                 }
             }
         }
     }
-    if (kw == 0 && rows_ok) epilogue<DUAL, NT>(accg, accu, w.out, w.R, rt * 16, orow);
+    if (kw == 0 && rows_ok) {
+        if (DUAL) {
+            epilogue<true, NT>(acc0, acc1, w.out, w.R, rt * 16, orow);
+        } else {
+            epilogue<false, NT>(acc0, acc0, w.out, w.R, rt * 16, orow);
+            epilogue<false, NT>(acc1, acc1, w.out, w.R, rt * 16 + 16, orow);
+        }
+    }
 }
 
 // Staged: the token tile is staged through LDS in chunks of KS k-steps, double buffered and shared by
@@ -432,23 +446,31 @@ __global__ __launch_bounds__(kFfnThreads, 2) void expert_kernel(GemmParams p)
         expert_direct<DUAL, 1, KW>(p, w, reinterpret_cast<float *>(stage));
         return;
     }
-    if ((w.tile % KW) != 0) return;
-    w.tile /= KW;
+    // staged path: units of 64 rows.  A direct workgroup covers 16*RW rows (gate/up) or 32*RW rows (down).
+    constexpr int kRowsPerWG = 16 * (kFfnWaves / KW) * (DUAL ? 1 : 2);
+    constexpr int kUnits = kRowsPerWG >= 64 ? kRowsPerWG / 64 : 1;      // staged units this workgroup does
+    constexpr int kShare = kRowsPerWG >= 64 ? 1 : 64 / kRowsPerWG;      // workgroups that share one unit
+    if ((w.tile % kShare) != 0) return;
+    const int unit0 = (w.tile / kShare) * kUnits;
     const int tid = threadIdx.x;
-    for (int i0 = 0; i0 < w.Te; i0 += kTokBlock) {
-        const int nb = min(w.Te - i0, kTokBlock);
-        __syncthreads();   // the previous pass has read rowoff / outrow and the stage
-        if (tid < kTokBlock) {
-            int ro, orow;
-            token_rows<DUAL>(p, w, tid < nb ? i0 + tid : w.Te, ro, orow);
-            rowoff[tid] = ro;
-            outrow[tid] = orow;
+    for (int un = 0; un < kUnits; ++un) {
+        w.tile = unit0 + un;
+        if (w.tile * 64 >= w.R) break;
+        for (int i0 = 0; i0 < w.Te; i0 += kTokBlock) {
+            const int nb = min(w.Te - i0, kTokBlock);
+            __syncthreads();   // the previous pass has read rowoff / outrow and the stage
+            if (tid < kTokBlock) {
+                int ro, orow;
+                token_rows<DUAL>(p, w, tid < nb ? i0 + tid : w.Te, ro, orow);
+                rowoff[tid] = ro;
+                outrow[tid] = orow;
+            }
+            __syncthreads();
+            if (nb <= 32)
+                expert_staged<DUAL, 2, 8>(w, rowoff, outrow, stage);
+            else
+                expert_staged<DUAL, 4, 4>(w, rowoff, outrow, stage);
         }
-        __syncthreads();
-        if (nb <= 32)
-            expert_staged<DUAL, 2, 8>(w, rowoff, outrow, stage);
-        else
-            expert_staged<DUAL, 4, 4>(w, rowoff, outrow, stage);
     }
 }
 
@@ -504,16 +526,22 @@ __global__ __launch_bounds__(256) void pack_kernel(const uint16_t *__restrict__ 
 // How many of a workgroup's four waves split the contraction dimension (the rest split rows).  Long
 // per-wave streams amortise the fill and drain of the prefetch ring, so K is only split when the
 // batch cannot invoke enough experts to give every CU several waves otherwise.
-static int pick_k_waves(int R, int K, bool dual, int max_experts, const char *env_override)
+static int pick_k_waves(int K, bool dual, int T, int max_experts, const char *env_override)
 {
     if (const char *v = getenv(env_override)) {
         const int kw = atoi(v);
         if (kw == 1 || kw == 2 || kw == 4) return kw;
     }
-    const long waves = (long)max_experts * (R / 16);                      // waves if K is not split
-    const long tile_bytes = (long)16 * K * 2 * (dual ? 2 : 1);            // weight bytes behind one 16-row tile
-    int kw = waves >= 2048 ? 1 : waves >= 1024 ? 2 : 4;
-    while (kw > 1 && tile_bytes / kw < 32 * 1024) kw >>= 1;               // keep at least 32 KiB per wave
+    // With more than 16 tokens some expert may take the staged path, whose unit is 64 rows: the workgroup
+    // shape is then chosen so that a workgroup covers exactly 64 rows (workgroups that only exist to be told
+    // they have nothing to do are expensive).
+    if (T > kDirectMaxTokens) return dual ? 1 : 2;
+    // Measured: splitting K only pays when the batch can invoke so few experts that whole row groups would
+    // leave the chip with too few, too long workgroups (Mixtral-like shapes); with many small experts the
+    // short streams cost more than the finer granularity gains.
+    const long group_bytes = (long)16 * K * 2 * 2;                        // weight bytes behind one row group
+    int kw = max_experts <= 8 ? 4 : max_experts <= 16 ? 2 : 1;
+    while (kw > 1 && group_bytes / kw < 32 * 1024) kw >>= 1;              // keep at least 32 KiB per wave
     return kw;
 }
 
@@ -531,8 +559,8 @@ template <bool DUAL>
 static int launch_projection(GemmParams p, const char *env_override, hipStream_t st, const char *what)
 {
     const int max_experts = (int)min((long)p.N, (long)p.T * p.k) + p.n_shared;
-    const int kw = pick_k_waves(p.R, p.K, DUAL, max_experts, env_override);
-    set_tiles(p, 16 * (kFfnWaves / kw));
+    const int kw = pick_k_waves(p.K, DUAL, p.T, max_experts, env_override);
+    set_tiles(p, 16 * (kFfnWaves / kw) * (DUAL ? 1 : 2));
     const dim3 grid(grid_blocks(p)), block(kFfnThreads);
     if (kw == 4)
         hipLaunchKernelGGL((expert_kernel<DUAL, 4>), grid, block, 0, st, p);
