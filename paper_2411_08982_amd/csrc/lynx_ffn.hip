@@ -554,6 +554,26 @@ static void set_tiles(GemmParams &p, int rows_per_wg)
 
 static unsigned grid_blocks(const GemmParams &p) { return (unsigned)(p.routed_blocks + p.n_shared * p.shared_splits * p.tiles_s); }
 
+// Workgroups per CU.  The dispatcher fills a CU up to its occupancy limit before it moves on, so a grid
+// that is small compared with the chip (few invoked experts) would leave CUs idle while others hold three
+// workgroups.  A dynamic-LDS pad makes exactly kWgPerCu workgroups fit a CU, which spreads such grids.
+constexpr int kWgPerCu = 2;
+constexpr int kLdsPerCu = 160 * 1024;
+constexpr int kLdsTargetPerWg = 56 * 1024;
+
+template <bool DUAL, int KW>
+static int lds_pad()
+{
+    static_assert(kLdsTargetPerWg * (kWgPerCu + 1) > kLdsPerCu && kLdsTargetPerWg * kWgPerCu <= kLdsPerCu, "LDS pad");
+    static int pad = -1;   // per instantiation
+    if (pad < 0) {
+        hipFuncAttributes attr;
+        if (hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(&expert_kernel<DUAL, KW>)) != hipSuccess) return 0;
+        pad = max(0, kLdsTargetPerWg - (int)attr.sharedSizeBytes);
+    }
+    return pad;
+}
+
 // One projection (gate/up or down) over all invoked and shared experts.
 template <bool DUAL>
 static int launch_projection(GemmParams p, const char *env_override, hipStream_t st, const char *what)
@@ -562,12 +582,16 @@ static int launch_projection(GemmParams p, const char *env_override, hipStream_t
     const int kw = pick_k_waves(p.K, DUAL, p.T, max_experts, env_override);
     set_tiles(p, 16 * (kFfnWaves / kw) * (DUAL ? 1 : 2));
     const dim3 grid(grid_blocks(p)), block(kFfnThreads);
-    if (kw == 4)
-        hipLaunchKernelGGL((expert_kernel<DUAL, 4>), grid, block, 0, st, p);
-    else if (kw == 2)
-        hipLaunchKernelGGL((expert_kernel<DUAL, 2>), grid, block, 0, st, p);
-    else
-        hipLaunchKernelGGL((expert_kernel<DUAL, 1>), grid, block, 0, st, p);
+    if (kw == 4) {
+        const int pad = lds_pad<DUAL, 4>();
+        hipLaunchKernelGGL((expert_kernel<DUAL, 4>), grid, block, pad, st, p);
+    } else if (kw == 2) {
+        const int pad = lds_pad<DUAL, 2>();
+        hipLaunchKernelGGL((expert_kernel<DUAL, 2>), grid, block, pad, st, p);
+    } else {
+        const int pad = lds_pad<DUAL, 1>();
+        hipLaunchKernelGGL((expert_kernel<DUAL, 1>), grid, block, pad, st, p);
+    }
     return check_launch(what);
 }
 
