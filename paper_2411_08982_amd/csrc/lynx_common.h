@@ -14,7 +14,7 @@ int fail(int code, const char *fmt, ...);
 int check_launch(const char *what);
 
 constexpr int kWave = 64;
-constexpr int kSlots = LYNX_MAX_N / kWave;  // expert slots per lane when a wave holds one token's N logits
+constexpr int kSlots = LYNX_MAX_N / kWave;  // most expert slots per lane when a wave holds one token's N logits
 
 __device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & (kWave - 1)); }
 __device__ __forceinline__ int wave_id() { return (int)(threadIdx.x >> 6); }
@@ -65,19 +65,19 @@ __device__ __forceinline__ int bin_of(float zmax, float z, float alpha, int beta
 // emit(j, expert, value) on every lane with the j-th winner (expert = INT_MAX when none is left).
 // Per pick: one DPP max reduction, then the lowest-indexed holder of that maximum by ballot + find-first
 // (slot 0 holds the lower experts, so the first slot with a match wins).  Values are finite.
-template <typename Emit>
-__device__ __forceinline__ void wave_topk(const float (&v)[kSlots], unsigned cand, int k, Emit &&emit)
+template <int NS, typename Emit>
+__device__ __forceinline__ void wave_topk(const float (&v)[NS], unsigned cand, int k, Emit &&emit)
 {
     const int lane = lane_id();
     for (int j = 0; j < k; ++j) {
         float m = -INFINITY;
 #pragma unroll
-        for (int i = 0; i < kSlots; ++i)
+        for (int i = 0; i < NS; ++i)
             if ((cand >> i) & 1u) m = fmaxf(m, v[i]);
         const float best = wave_max(m);
         int e = INT_MAX;
 #pragma unroll
-        for (int i = 0; i < kSlots; ++i) {
+        for (int i = 0; i < NS; ++i) {
             const unsigned long long b = __ballot(((cand >> i) & 1u) && v[i] == best);
             if (e == INT_MAX && b != 0ull) e = __ffsll((long long)b) - 1 + kWave * i;
         }

@@ -10,17 +10,19 @@
 
 namespace lynx {
 
-struct PermuteShared {
-    unsigned member[LYNX_MAX_N * (LYNX_MAX_T / 32)];   // member[e*W + w] bit b: token 32*w+b uses expert e
+template <int MAXW>   // capacity in 32-token words per expert
+struct PermuteSharedT {
+    unsigned member[LYNX_MAX_N * MAXW];   // member[e*W + w] bit b: token 32*w+b uses expert e
     int count[LYNX_MAX_N];
     int offs[LYNX_MAX_N + 1];
     int arank[LYNX_MAX_N + 1];
 };
+typedef PermuteSharedT<LYNX_MAX_T / 32> PermuteShared;
 
 // Every thread of the workgroup calls this with sh.member filled (and visible: barrier before).
 // perm must have been pre-filled with -1 where invalid indices can occur.
-template <int THREADS>
-__device__ __forceinline__ void permute_from_bitsets(PermuteShared &sh, const int32_t *__restrict__ idx, int T, int N,
+template <int THREADS, typename Shared>
+__device__ __forceinline__ void permute_from_bitsets(Shared &sh, const int32_t *__restrict__ idx, int T, int N,
                                                      int k, int32_t *__restrict__ expert_offsets,
                                                      int32_t *__restrict__ perm, int32_t *__restrict__ active_experts,
                                                      int32_t *__restrict__ num_active)

@@ -135,18 +135,22 @@ __global__ __launch_bounds__(256) void logits_kernel(const uint16_t *__restrict_
 }
 
 // One wave holds one token's logits: lane l, slot i <-> expert l + 64*i.
+// NS = slots per lane = ceil(N / 64): the kernels are instantiated for 1, 2 and 4 so that a router with
+// few experts does not pay for empty slots.
+template <int NS>
 struct TokenLogits {
-    float v[kSlots];
+    float v[NS];
     unsigned have;   // bit i: slot i is a real expert
 };
 
-__device__ __forceinline__ TokenLogits load_token(const float *__restrict__ z, int N)
+template <int NS>
+__device__ __forceinline__ TokenLogits<NS> load_token(const float *__restrict__ z, int N)
 {
-    TokenLogits t;
+    TokenLogits<NS> t;
     t.have = 0;
     const int lane = lane_id();
 #pragma unroll
-    for (int i = 0; i < kSlots; ++i) {
+    for (int i = 0; i < NS; ++i) {
         const int e = lane + kWave * i;
         t.v[i] = (e < N) ? z[e] : -INFINITY;
         t.have |= (e < N) ? (1u << i) : 0u;
@@ -154,11 +158,12 @@ __device__ __forceinline__ TokenLogits load_token(const float *__restrict__ z, i
     return t;
 }
 
-__device__ __forceinline__ float token_max(const TokenLogits &t)
+template <int NS>
+__device__ __forceinline__ float token_max(const TokenLogits<NS> &t)
 {
     float m = -INFINITY;
 #pragma unroll
-    for (int i = 0; i < kSlots; ++i) m = fmaxf(m, t.v[i]);
+    for (int i = 0; i < NS; ++i) m = fmaxf(m, t.v[i]);
     return wave_max(m);
 }
 
@@ -175,7 +180,8 @@ __device__ __forceinline__ float selection_gate(int k, int mye, float myz, float
 // ---- per-token steps (one wave per token), shared by the single-workgroup and the multi-workgroup paths ----
 
 // Softmax + top-k (Sec. 2.1): lane j < k returns the j-th pick in mye; writes idx / gate / psum.
-__device__ __forceinline__ int token_topk(const TokenLogits &tl, int t, int k, int32_t *__restrict__ topk_idx,
+template <int NS>
+__device__ __forceinline__ int token_topk(const TokenLogits<NS> &tl, int t, int k, int32_t *__restrict__ topk_idx,
                                           float *__restrict__ topk_gate, float *__restrict__ topk_psum)
 {
     const int lane = lane_id();
@@ -191,7 +197,7 @@ __device__ __forceinline__ int token_topk(const TokenLogits &tl, int t, int k, i
     const float g = selection_gate(k, mye, myz, num, zref);
     float part = 0.f;
 #pragma unroll
-    for (int i = 0; i < kSlots; ++i)
+    for (int i = 0; i < NS; ++i)
         if ((tl.have >> i) & 1u) part += expf(tl.v[i] - zref);
     const float den = wave_sum(part);
     if (lane < k) {
@@ -203,13 +209,14 @@ __device__ __forceinline__ int token_topk(const TokenLogits &tl, int t, int k, i
 }
 
 // Bins of every expert for this token into the (LDS) histogram, and the token's pairs per expert.
-__device__ __forceinline__ void token_bins(const TokenLogits &tl, int k, int mye, float alpha, int beta, int *hist,
+template <int NS>
+__device__ __forceinline__ void token_bins(const TokenLogits<NS> &tl, int k, int mye, float alpha, int beta, int *hist,
                                            int *cntb)
 {
     const int lane = lane_id();
     const float zmax = token_max(tl);
 #pragma unroll
-    for (int i = 0; i < kSlots; ++i)
+    for (int i = 0; i < NS; ++i)
         if ((tl.have >> i) & 1u) {
             const int q = bin_of(zmax, tl.v[i], alpha, beta);
             if (q >= 0 && q < beta) atomicAdd(&hist[(lane + kWave * i) * beta + q], 1);
@@ -217,34 +224,51 @@ __device__ __forceinline__ void token_bins(const TokenLogits &tl, int k, int mye
     if (lane < k && mye >= 0) atomicAdd(&cntb[mye], 1);
 }
 
+// Value of expert e (wave-uniform or per-lane) out of a token's logits held across the lanes.
+template <int NS>
+__device__ __forceinline__ float logit_of(const TokenLogits<NS> &tl, int e)
+{
+    float r = 0.f;
+#pragma unroll
+    for (int i = 0; i < NS; ++i) {
+        const float c = __shfl(tl.v[i], e & (kWave - 1), kWave);
+        r = ((e >> 6) == i) ? c : r;
+    }
+    return r;
+}
+
 // Nominations of one token (Sec. 3.3.1 under the stated reading).  order[r] = expert with the r-th best
 // score, inU[e] = the batch invokes e, sel = the token's own picks in rank order; sets inA[e] = 1.
-__device__ __forceinline__ void token_nominate(const float *__restrict__ z, int N, int k, float alpha, int beta,
+// The logits stay in registers: the experts are brought into score order with lane permutations.
+template <int NS>
+__device__ __forceinline__ void token_nominate(const TokenLogits<NS> &tl, int N, int k, float alpha, int beta,
                                                const int *order, const int *inU, const int32_t *sel, int *inA)
 {
     const int lane = lane_id();
-    const float zmax = token_max(load_token(z, N));
-    int er[kSlots], qr[kSlots];
+    const float zmax = token_max(tl);
+    int er[NS], qr[NS];
     unsigned avail = 0;   // bit i: the expert at score rank lane+64*i is invoked by the batch and not used yet
 #pragma unroll
-    for (int i = 0; i < kSlots; ++i) {
+    for (int i = 0; i < NS; ++i) {
         const int r = lane + kWave * i;
         er[i] = (r < N) ? order[r] : 0;
-        qr[i] = (r < N) ? bin_of(zmax, z[er[i]], alpha, beta) : INT_MAX;
+        qr[i] = (r < N) ? bin_of(zmax, logit_of(tl, er[i]), alpha, beta) : INT_MAX;
         if (r < N && inU[er[i]]) avail |= 1u << i;
     }
-    // bins of the token's own picks, one per lane, fetched together (no dependent load inside the slot loop)
+    // bins of the token's own picks, one per lane
     int myq = beta;
-    if (lane < k) {
-        const int es = sel[lane];
-        if (es >= 0 && es < N) myq = bin_of(zmax, z[es], alpha, beta);
+    {
+        const int es = (lane < k) ? sel[lane] : -1;
+        const bool ok = es >= 0 && es < N;
+        const float zs = logit_of(tl, ok ? es : 0);
+        if (ok) myq = bin_of(zmax, zs, alpha, beta);
     }
     for (int s = 0; s < k; ++s) {
         const int qs = __builtin_amdgcn_readlane(myq, s);
         if (qs >= beta) break;   // out of range (or no valid pick): this and all later picks constrain nothing
         bool found = false;
 #pragma unroll
-        for (int i = 0; i < kSlots; ++i) {
+        for (int i = 0; i < NS; ++i) {
             if (found) continue;
             const bool ok = ((avail >> i) & 1u) && qr[i] <= qs;
             const unsigned long long b = __ballot(ok);
@@ -284,7 +308,8 @@ __device__ __forceinline__ int wave_fill_active(int N, int k, const int *order, 
 
 // Selection of one token inside the active set (or its unchanged selection when bypassed) and its gates
 // (Secs. 3.4, 4).  Lane j < k returns the j-th expert; writes new_idx / new_gate.
-__device__ __forceinline__ int token_remap(const float *__restrict__ z, int t, int N, int k, bool bypass, const int *inA,
+template <int NS>
+__device__ __forceinline__ int token_remap(const TokenLogits<NS> &tl, int t, int N, int k, bool bypass, const int *inA,
                                            const int32_t *sel, int32_t *__restrict__ new_idx,
                                            float *__restrict__ new_gate)
 {
@@ -292,16 +317,17 @@ __device__ __forceinline__ int token_remap(const float *__restrict__ z, int t, i
     int mye = -1;
     float myz = -INFINITY;
     if (bypass) {
-        if (lane < k) {
-            mye = sel[lane];
-            if (mye < 0 || mye >= N) mye = -1;
-            if (mye >= 0) myz = z[mye];
+        const int es = (lane < k) ? sel[lane] : -1;
+        const bool ok = es >= 0 && es < N;
+        const float zs = logit_of(tl, ok ? es : 0);
+        if (ok) {
+            mye = es;
+            myz = zs;
         }
     } else {
-        const TokenLogits tl = load_token(z, N);
         unsigned cand = 0;
 #pragma unroll
-        for (int i = 0; i < kSlots; ++i)
+        for (int i = 0; i < NS; ++i)
             if (((tl.have >> i) & 1u) && inA[lane + kWave * i]) cand |= 1u << i;
         wave_topk(tl.v, cand, k, [&](int j, int e, float zz) {
             if (lane == j) {
@@ -357,10 +383,10 @@ __device__ __forceinline__ bool last_workgroup(int32_t *ticket, int *flag_lds)
 
 // ---- small batches (T <= kSmallT): everything after the logits in ONE workgroup, all state in LDS -----------
 
-constexpr int kSmallT = 16;
+constexpr int kSmallT = 16;   // one token per wave; beyond that one CU's ALUs are the bottleneck (measured)
 
 struct SmallShared {
-    PermuteShared perm;
+    PermuteSharedT<1> perm;
     int hist[LYNX_MAX_N * LYNX_MAX_BETA];
     unsigned long long score[LYNX_MAX_N];
     int cntb[LYNX_MAX_N], cnta[LYNX_MAX_N], order[LYNX_MAX_N], inU[LYNX_MAX_N], inA[LYNX_MAX_N];
@@ -368,8 +394,10 @@ struct SmallShared {
     int32_t newsel[kSmallT * LYNX_MAX_K];   // the remapped picks
     int n_before, n_after;
 };
+static_assert(kSmallT <= kSmallWaves && kSmallT <= 32, "one wave per token, one 32-token word per expert");
 
-template <bool DO_TOPK, bool DO_PERMUTE>
+// One workgroup, wave t owns token t and keeps its logits in registers from the first step to the last.
+template <int NS, bool DO_TOPK, bool DO_PERMUTE>
 __global__ __launch_bounds__(kSmallThreads) void routing_small_kernel(
     const float *__restrict__ logits, int T, int N, int k, float alpha, int beta, int bypass,
     int32_t *__restrict__ topk_idx, float *__restrict__ topk_gate, float *__restrict__ topk_psum,
@@ -379,29 +407,30 @@ __global__ __launch_bounds__(kSmallThreads) void routing_small_kernel(
     int32_t *__restrict__ num_active_perm)
 {
     __shared__ SmallShared sh;
-    const int tid = threadIdx.x, lane = lane_id(), wave = wave_id();
-    const int W = (T + 31) / 32;
+    const int tid = threadIdx.x, lane = lane_id(), t = wave_id();
+    const bool has_token = t < T;
+    // the token's logits (and, if given, its picks) are requested first; everything below overlaps the loads
+    TokenLogits<NS> tl = load_token<NS>(logits + (size_t)(has_token ? t : 0) * N, N);
+    int given = -1;
+    if (!DO_TOPK && has_token && lane < k) given = topk_idx[(size_t)t * k + lane];
     for (int i = tid; i < N * beta; i += kSmallThreads) sh.hist[i] = 0;
     for (int i = tid; i < N; i += kSmallThreads) {
         sh.cntb[i] = 0;
         sh.cnta[i] = 0;
         sh.inA[i] = 0;
+        if (DO_PERMUTE) sh.perm.member[i] = 0u;
     }
-    if (DO_PERMUTE) {
-        for (int i = tid; i < N * W; i += kSmallThreads) sh.perm.member[i] = 0u;
+    if (DO_PERMUTE)
         for (int p = tid; p < T * k; p += kSmallThreads) perm[p] = -1;
-    }
     if (tid == 0) sh.n_after = 0;
     __syncthreads();
     // top-k (or the given picks), bins, histogram
-    for (int t = wave; t < T; t += kSmallWaves) {
-        const TokenLogits tl = load_token(logits + (size_t)t * N, N);
+    if (has_token) {
         int mye = -1;
         if (DO_TOPK) {
             mye = token_topk(tl, t, k, topk_idx, topk_gate, topk_psum);
         } else if (lane < k) {
-            mye = topk_idx[(size_t)t * k + lane];
-            if (mye < 0 || mye >= N) mye = -1;
+            mye = (given < 0 || given >= N) ? -1 : given;
         }
         if (lane < k) sh.sel[t * k + lane] = mye;
         token_bins(tl, k, mye, alpha, beta, sh.hist, sh.cntb);
@@ -413,22 +442,21 @@ __global__ __launch_bounds__(kSmallThreads) void routing_small_kernel(
     rank_of(tid, N, sh.score, sh.order);
     __syncthreads();
     if (!bypass) {
-        for (int t = wave; t < T; t += kSmallWaves)
-            token_nominate(logits + (size_t)t * N, N, k, alpha, beta, sh.order, sh.inU, sh.sel + t * k, sh.inA);
+        if (has_token) token_nominate(tl, N, k, alpha, beta, sh.order, sh.inU, sh.sel + t * k, sh.inA);
         __syncthreads();
     }
-    if (wave == 0) {
+    if (t == 0) {
         const int nU = wave_fill_active(N, k, sh.order, sh.inU, sh.inA, !bypass);
         if (lane == 0) sh.n_before = nU;
     }
     __syncthreads();
-    for (int t = wave; t < T; t += kSmallWaves) {
-        const int mye = token_remap(logits + (size_t)t * N, t, N, k, bypass != 0, sh.inA, sh.sel + t * k, new_idx, new_gate);
+    if (has_token) {
+        const int mye = token_remap(tl, t, N, k, bypass != 0, sh.inA, sh.sel + t * k, new_idx, new_gate);
         if (lane < k) {
             sh.newsel[t * k + lane] = mye;
             if (mye >= 0) {
                 atomicAdd(&sh.cnta[mye], 1);
-                if (DO_PERMUTE) atomicOr(&sh.perm.member[mye * W + (t >> 5)], 1u << (t & 31));
+                if (DO_PERMUTE) atomicOr(&sh.perm.member[mye], 1u << t);
             }
         }
     }
@@ -446,14 +474,14 @@ __global__ __launch_bounds__(kSmallThreads) void routing_small_kernel(
     }
     if constexpr (DO_PERMUTE)
         permute_from_bitsets<kSmallThreads>(sh.perm, sh.newsel, T, N, k, expert_offsets, perm, active_experts,
-                                          num_active_perm);
+                                            num_active_perm);
 }
 
 // ---- large batches: one wave per token over many workgroups, one launch per batch-level dependency ----------
 
 // Softmax + top-k (DO_TOPK) and/or bins + histogram + pairs per expert (DO_BINS, accumulated with atomics
 // into the zeroed outputs).
-template <bool DO_TOPK, bool DO_BINS>
+template <int NS, bool DO_TOPK, bool DO_BINS>
 __global__ __launch_bounds__(kTokThreads) void token_kernel(const float *__restrict__ logits, int T, int N, int k,
                                                             float alpha, int beta, int32_t *__restrict__ topk_idx,
                                                             float *__restrict__ topk_gate,
@@ -471,7 +499,7 @@ __global__ __launch_bounds__(kTokThreads) void token_kernel(const float *__restr
     }
     const int t = blockIdx.x * kTokWaves + wave;
     if (t < T) {
-        const TokenLogits tl = load_token(logits + (size_t)t * N, N);
+        const TokenLogits<NS> tl = load_token<NS>(logits + (size_t)t * N, N);
         int mye = -1;
         if (DO_TOPK) {
             mye = token_topk(tl, t, k, topk_idx, topk_gate, topk_psum);
@@ -491,6 +519,7 @@ __global__ __launch_bounds__(kTokThreads) void token_kernel(const float *__restr
 
 // Every workgroup first turns the finished histogram into scores and the score order (cheap, and it saves a
 // launch), then nominates for its tokens.  Workgroup 0 also publishes the order for the remap kernel.
+template <int NS>
 __global__ __launch_bounds__(kTokThreads) void nominate_kernel(const float *__restrict__ logits,
                                                                const int32_t *__restrict__ topk_idx,
                                                                const int32_t *__restrict__ bin_hist,
@@ -499,7 +528,12 @@ __global__ __launch_bounds__(kTokThreads) void nominate_kernel(const float *__re
 {
     __shared__ unsigned long long score[LYNX_MAX_N];
     __shared__ int order[LYNX_MAX_N], inU[LYNX_MAX_N], inA[LYNX_MAX_N];
-    const int tid = threadIdx.x, wave = wave_id();
+    __shared__ int32_t sel[kTokWaves * LYNX_MAX_K];
+    const int tid = threadIdx.x, lane = lane_id(), wave = wave_id();
+    const int t = blockIdx.x * kTokWaves + wave;
+    // the token's logits and picks are requested first; the score prologue overlaps the loads
+    const TokenLogits<NS> tl = load_token<NS>(logits + (size_t)(t < T ? t : 0) * N, N);
+    if (lane < k) sel[wave * k + lane] = (t < T) ? topk_idx[(size_t)t * k + lane] : -1;
     score_of(tid, N, T, beta, bin_hist, score);
     if (tid < N) {
         inU[tid] = cnt_before[tid] > 0;
@@ -509,8 +543,7 @@ __global__ __launch_bounds__(kTokThreads) void nominate_kernel(const float *__re
     rank_of(tid, N, score, order);
     __syncthreads();
     if (blockIdx.x == 0 && tid < N) ws[kWsOrder + tid] = order[tid];
-    const int t = blockIdx.x * kTokWaves + wave;
-    if (t < T) token_nominate(logits + (size_t)t * N, N, k, alpha, beta, order, inU, topk_idx + (size_t)t * k, inA);
+    if (t < T) token_nominate(tl, N, k, alpha, beta, order, inU, sel + wave * k, inA);
     __syncthreads();
     if (tid < N && inA[tid]) ws[kWsActive + tid] = 1;
 }
@@ -530,7 +563,7 @@ struct RemapShared<true> {
 // Every workgroup first completes the active set (fill up to k) from the finished nominations, then selects
 // inside it for its tokens.  The last workgroup to finish counts the invoked experts and, with DO_PERMUTE,
 // assigns the tokens (offsets, permutation, invoked-expert list) from the token bit sets.
-template <bool DO_PERMUTE>
+template <int NS, bool DO_PERMUTE>
 __global__ __launch_bounds__(kTokThreads) void remap_kernel(const float *__restrict__ logits,
                                                             const int32_t *__restrict__ topk_idx,
                                                             const int32_t *__restrict__ cnt_before, int T, int N, int k,
@@ -544,8 +577,13 @@ __global__ __launch_bounds__(kTokThreads) void remap_kernel(const float *__restr
                                                             int32_t *__restrict__ num_active_perm)
 {
     __shared__ RemapShared<DO_PERMUTE> sh;
+    __shared__ int32_t sel[kTokWaves * LYNX_MAX_K];
     const int tid = threadIdx.x, lane = lane_id(), wave = wave_id();
     const int W = (T + 31) / 32;
+    const int t = blockIdx.x * kTokWaves + wave;
+    // the token's logits and picks are requested first; the prologue overlaps the loads
+    const TokenLogits<NS> tl = load_token<NS>(logits + (size_t)(t < T ? t : 0) * N, N);
+    if (lane < k) sel[wave * k + lane] = (t < T) ? topk_idx[(size_t)t * k + lane] : -1;
     if (tid < N) {
         sh.inA[tid] = bypass ? 0 : ws[kWsActive + tid];
         sh.inU[tid] = cnt_before[tid] > 0;
@@ -563,10 +601,8 @@ __global__ __launch_bounds__(kTokThreads) void remap_kernel(const float *__restr
         if (blockIdx.x == 0 && lane == 0) num_active[0] = nU;
     }
     __syncthreads();
-    const int t = blockIdx.x * kTokWaves + wave;
     if (t < T) {
-        const int mye = token_remap(logits + (size_t)t * N, t, N, k, bypass != 0, sh.inA, topk_idx + (size_t)t * k, new_idx,
-                                    new_gate);
+        const int mye = token_remap(tl, t, N, k, bypass != 0, sh.inA, sel + wave * k, new_idx, new_gate);
         if (lane < k && mye >= 0) {
             atomicAdd(&sh.cnta[mye], 1);
             if (DO_PERMUTE) atomicOr(reinterpret_cast<unsigned *>(ws + kWsMember) + mye * W + (t >> 5), 1u << (t & 31));
@@ -626,8 +662,8 @@ static void launch_logits(const uint16_t *x, const float *Wr, const float *bias,
 // Everything after the logits.  DO_TOPK: compute the top-k (else topk_idx is an input); DO_PERMUTE: also
 // assign the tokens.  clear_first: the multi-workgroup path accumulates into zeroed arrays; true = clear them
 // with a launch of their own, false = the caller already had them cleared (by the logits kernel).
-template <bool DO_TOPK, bool DO_PERMUTE>
-static int launch_after_logits(const char *who, const float *logits, int T, int N, int k, float alpha, int beta,
+template <int NS, bool DO_TOPK, bool DO_PERMUTE>
+static int launch_after_logits_ns(const char *who, const float *logits, int T, int N, int k, float alpha, int beta,
                                int enable, int32_t *topk_idx, float *topk_gate, float *topk_psum, int32_t *new_idx,
                                float *new_gate, int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist,
                                int32_t *num_active, int32_t *expert_offsets, int32_t *perm, int32_t *active_experts,
@@ -635,7 +671,7 @@ static int launch_after_logits(const char *who, const float *logits, int T, int 
 {
     const int bypass = (!enable || T <= 1) ? 1 : 0;
     if (T <= kSmallT) {
-        hipLaunchKernelGGL((routing_small_kernel<DO_TOPK, DO_PERMUTE>), dim3(1), dim3(kSmallThreads), 0, st, logits, T, N, k,
+        hipLaunchKernelGGL((routing_small_kernel<NS, DO_TOPK, DO_PERMUTE>), dim3(1), dim3(kSmallThreads), 0, st, logits, T, N, k,
                            alpha, beta, bypass, topk_idx, topk_gate, topk_psum, new_idx, new_gate, cnt_before, cnt_after,
                            bin_hist, num_active, expert_offsets, perm, active_experts, num_active_perm);
         return check_launch(who);
@@ -655,19 +691,35 @@ static int launch_after_logits(const char *who, const float *logits, int T, int 
         if (rc != LYNX_OK) return rc;
     }
     const dim3 tgrid((T + kTokWaves - 1) / kTokWaves), tblock(kTokThreads);
-    hipLaunchKernelGGL((token_kernel<DO_TOPK, true>), tgrid, tblock, 0, st, logits, T, N, k, alpha, beta, topk_idx,
+    hipLaunchKernelGGL((token_kernel<NS, DO_TOPK, true>), tgrid, tblock, 0, st, logits, T, N, k, alpha, beta, topk_idx,
                        topk_gate, topk_psum, bin_hist, cnt_before);
     rc = check_launch(who);
     if (rc != LYNX_OK) return rc;
     if (!bypass) {
-        hipLaunchKernelGGL(nominate_kernel, tgrid, tblock, 0, st, logits, topk_idx, bin_hist, cnt_before, T, N, k, alpha,
+        hipLaunchKernelGGL((nominate_kernel<NS>), tgrid, tblock, 0, st, logits, topk_idx, bin_hist, cnt_before, T, N, k, alpha,
                            beta, ws);
         rc = check_launch(who);
         if (rc != LYNX_OK) return rc;
     }
-    hipLaunchKernelGGL((remap_kernel<DO_PERMUTE>), tgrid, tblock, 0, st, logits, topk_idx, cnt_before, T, N, k, bypass, ws,
+    hipLaunchKernelGGL((remap_kernel<NS, DO_PERMUTE>), tgrid, tblock, 0, st, logits, topk_idx, cnt_before, T, N, k, bypass, ws,
                        new_idx, new_gate, cnt_after, num_active, expert_offsets, perm, active_experts, num_active_perm);
     return check_launch(who);
+}
+
+template <bool DO_TOPK, bool DO_PERMUTE>
+static int launch_after_logits(const char *who, const float *logits, int T, int N, int k, float alpha, int beta,
+                               int enable, int32_t *topk_idx, float *topk_gate, float *topk_psum, int32_t *new_idx,
+                               float *new_gate, int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist,
+                               int32_t *num_active, int32_t *expert_offsets, int32_t *perm, int32_t *active_experts,
+                               int32_t *num_active_perm, int32_t *ws, bool clear_first, hipStream_t st)
+{
+#define LYNX_ROUTING_ARGS                                                                                             \
+    who, logits, T, N, k, alpha, beta, enable, topk_idx, topk_gate, topk_psum, new_idx, new_gate, cnt_before, cnt_after, \
+        bin_hist, num_active, expert_offsets, perm, active_experts, num_active_perm, ws, clear_first, st
+    if (N <= kWave) return launch_after_logits_ns<1, DO_TOPK, DO_PERMUTE>(LYNX_ROUTING_ARGS);
+    if (N <= 2 * kWave) return launch_after_logits_ns<2, DO_TOPK, DO_PERMUTE>(LYNX_ROUTING_ARGS);
+    return launch_after_logits_ns<4, DO_TOPK, DO_PERMUTE>(LYNX_ROUTING_ARGS);
+#undef LYNX_ROUTING_ARGS
 }
 
 // The whole routing side of lynx_moe_layer: two launches for T <= 64, four otherwise.  T >= 1, arguments checked.
@@ -715,8 +767,16 @@ extern "C" int lynx_route(const uint16_t *x_bf16, const float *Wr, const float *
     launch_logits(x_bf16, Wr, bias, T, H, N, logits, z, st);
     rc = check_launch("lynx_route(logits)");
     if (rc != LYNX_OK) return rc;
-    hipLaunchKernelGGL((token_kernel<true, false>), dim3((T + kTokWaves - 1) / kTokWaves), dim3(kTokThreads), 0, st,
-                       logits, T, N, k, 0.f, 1, topk_idx, topk_gate, topk_psum, nullptr, nullptr);
+    const dim3 tgrid((T + kTokWaves - 1) / kTokWaves), tblock(kTokThreads);
+    if (N <= kWave)
+        hipLaunchKernelGGL((token_kernel<1, true, false>), tgrid, tblock, 0, st, logits, T, N, k, 0.f, 1, topk_idx,
+                           topk_gate, topk_psum, nullptr, nullptr);
+    else if (N <= 2 * kWave)
+        hipLaunchKernelGGL((token_kernel<2, true, false>), tgrid, tblock, 0, st, logits, T, N, k, 0.f, 1, topk_idx,
+                           topk_gate, topk_psum, nullptr, nullptr);
+    else
+        hipLaunchKernelGGL((token_kernel<4, true, false>), tgrid, tblock, 0, st, logits, T, N, k, 0.f, 1, topk_idx,
+                           topk_gate, topk_psum, nullptr, nullptr);
     return check_launch("lynx_route(top-k)");
 }
 
