@@ -8,6 +8,10 @@ us/batch, the HBM roofline of the dominant kernel (gate/up weight stream) measur
 around that kernel inside the timed steps, a sweep over the configuration's batch sizes with the
 remap off / on, and the CPU oracle timed on the host cores as a reported baseline.
 
+Successive steps cycle over several resident copies of the layer's expert weights (distinct buffers, same
+router and tokens), as the layers of a model would: a step that re-read the very buffers of the step before
+would find a small configuration's experts in the 256 MB last-level cache and report a rate above HBM's.
+
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config mixtral] [--tokens 8] [--preset aggressive]
 """
 from __future__ import annotations
@@ -36,6 +40,8 @@ def parse():
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sweep-iters", type=int, default=10)
+    ap.add_argument("--layers", type=int, default=0,
+                    help="resident copies of the expert weights that successive steps cycle over (0 = enough for 4 GiB)")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="before the steps, run a plain 1 GiB read + 1 GiB write elementwise kernel three times: under "
                          "rocprofv3 --pmc its FETCH_SIZE / WRITE_SIZE readings give the counters' scale")
@@ -52,21 +58,27 @@ def expert_bytes(cfg, n_routed):
 class Layer:
     """Device-resident inputs and packed weights of one synthetic layer, plus per-T buffers."""
 
-    def __init__(self, cfg, T_gen, keep_row_major=False):
+    def __init__(self, cfg, T_gen, keep_row_major=False, n_layers=1):
         import torch
 
         import paper_2411_08982_amd as L
         import workloads as wl
         self.L, self.cfg, self.torch, self.wl = L, cfg, torch, wl
-        d = wl.make_layer_device(cfg, T_gen, "cuda")
-        self.Wr, self.bias = d["Wr"], d["bias"]
-        self.Wgu, self.Wdp = L.lynx_pack_weights(d["Wg"], d["Wu"], d["Wd"])
-        self.Sgu = self.Sdp = None
-        if cfg.n_shared:
-            self.Sgu, self.Sdp = L.lynx_pack_weights(d["Sg"], d["Su"], d["Sd"])
-        torch.cuda.synchronize()
-        self.row_major = {k: d[k] for k in ("Wg", "Wu", "Wd", "Sg", "Su", "Sd")} if keep_row_major else None
-        self.x = {T_gen: d["x"]}
+        self.weights = []          # per resident layer: packed routed gate/up, down, shared gate/up, down
+        self.calls = 0
+        for l in range(n_layers):
+            d = wl.make_layer_device(cfg, T_gen if l == 0 else 1, "cuda", layer=l)
+            Wgu, Wdp = L.lynx_pack_weights(d["Wg"], d["Wu"], d["Wd"])
+            Sgu = Sdp = None
+            if cfg.n_shared:
+                Sgu, Sdp = L.lynx_pack_weights(d["Sg"], d["Su"], d["Sd"])
+            torch.cuda.synchronize()
+            self.weights.append((Wgu, Wdp, Sgu, Sdp))
+            if l == 0:             # router, tokens and the oracle's row-major weights are those of layer 0
+                self.Wr, self.bias = d["Wr"], d["bias"]
+                self.row_major = {k: d[k] for k in ("Wg", "Wu", "Wd", "Sg", "Su", "Sd")} if keep_row_major else None
+                self.x = {T_gen: d["x"]}
+            del d
         self.buf = {}
 
     def tokens(self, T):
@@ -83,11 +95,16 @@ class Layer:
             self.buf[key] = self.L.LayerBuffers(T, c.H, c.F, c.N, c.k, beta, c.n_shared, c.F_shared)
         return self.buf[key]
 
-    def step(self, T, alpha, beta, enable, events=None):
-        """One decode step (the whole hot path) through the fused C-ABI entry point, on the current stream."""
+    def step(self, T, alpha, beta, enable, events=None, layer=None):
+        """One decode step (the whole hot path) through the fused C-ABI entry point, on the current stream.
+        Successive calls take the resident layers' expert weights in turn."""
         c = self.cfg
-        return self.L.lynx_moe_layer(self.tokens(T), self.Wr, self.bias, self.Wgu, self.Wdp, c.F, c.k, alpha, beta, enable,
-                                     self.Sgu, self.Sdp, c.n_shared, c.F_shared, buffers=self.buffers(T, beta),
+        if layer is None:
+            layer = self.calls % len(self.weights)
+            self.calls += 1
+        Wgu, Wdp, Sgu, Sdp = self.weights[layer]
+        return self.L.lynx_moe_layer(self.tokens(T), self.Wr, self.bias, Wgu, Wdp, c.F, c.k, alpha, beta, enable,
+                                     Sgu, Sdp, c.n_shared, c.F_shared, buffers=self.buffers(T, beta),
                                      stage_events=events)
 
 
@@ -112,7 +129,9 @@ def main():
     cfg = wl.CONFIGS[args.config]
     T = args.tokens
     alpha, beta, enable = preset_args(wl, args.preset)
-    layer = Layer(cfg, T, keep_row_major=not args.no_cpu_baseline)
+    routed_bytes = 3 * cfg.N * cfg.H * cfg.F * 2
+    n_layers = args.layers if args.layers > 0 else max(1, min(8, -(-(4 << 30) // routed_bytes)))
+    layer = Layer(cfg, T, keep_row_major=not args.no_cpu_baseline, n_layers=n_layers)
 
     if args.pmc_calibration:
         a = torch.ones(1 << 28, dtype=torch.float32, device="cuda")   # 1 GiB
@@ -173,13 +192,13 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{cfg.name}-shaped MoE layer: hidden {cfg.H}, FFN {cfg.F}, {cfg.N} experts top-{cfg.k}, "
                                f"{cfg.n_shared} shared, bf16 weights, {T} decode tokens, remap {args.preset}",
-                   "tokens": T, "alpha": alpha, "beta": beta, "remap": bool(enable)},
+                   "tokens": T, "alpha": alpha, "beta": beta, "remap": bool(enable), "resident_layers": n_layers},
         "tokens_per_s": round(T / (ms_per_step * 1e-3), 1),
         "experts_invoked": {"before": n_before, "after": n_after},
         "expert_weight_hbm_GBps": round(ffn_gbps, 1),
         "stage_us": {"gate_up": round(gu_ms * 1e3, 2), "down": round(dn_ms * 1e3, 2), "combine": round(cb_ms * 1e3, 2),
                      "routing_and_rest": round((ms_per_step - gu_ms - dn_ms - cb_ms) * 1e3, 2)},
-        "roofline": {"bound": "hbm", "kernel": "expert_direct_kernel<true> (gate/up weight stream)",
+        "roofline": {"bound": "hbm", "kernel": "expert_kernel<true, KW> (gate/up weight stream)",
                      "achieved": round(gu_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(gu_gbps / HBM_PEAK_GBPS, 4), "traffic": traffic,
                      "bytes_per_launch": gu_bytes, "avg_launch_us": round(gu_ms * 1e3, 2)},

@@ -15,7 +15,6 @@
 //     workgroup whose rank is past the device-side num_active leaves at once, so nothing is read back
 //     to the host.
 // Launches: gate/up (with the SiLU-multiply epilogue), down, and a small combine.
-#include <stdlib.h>
 
 #include "lynx_common.h"
 
@@ -26,7 +25,11 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kFfnThreads = 256;
 constexpr int kFfnWaves = kFfnThreads / kWave;
-constexpr int kPF = 8;                       // weight tiles in flight per wave and matrix
+constexpr int kPF = 8;                       // staged path: weight tiles in flight per wave and matrix
+#ifndef LYNX_PFD
+#define LYNX_PFD 8
+#endif
+constexpr int kPFD = LYNX_PFD;               // direct path: the same
 constexpr int kDirectMaxTokens = 16;         // experts with more tokens go to the staged kernel
 constexpr int kStagedNT = 4;                 // token tiles (of 16) per pass of the staged path
 constexpr int kTokBlock = 16 * kStagedNT;
@@ -52,34 +55,34 @@ struct WorkItem {
     const uint4 *W;      // packed weights of the expert
     const uint16_t *B;   // B-operand rows
     void *out;
-    int R, K, tile, Te, off, shared_s;
+    int R, K, tile, Te, off, shared_s, e;
     int kbeg, ksteps;    // slice of the contraction dimension this work item covers, in k-steps of 32 columns
     int out_base;        // shared experts: first output row of this work item
     bool valid;
 };
 
+// First half: which expert, from blockIdx and the invoked-expert list (one round trip to memory).  Everything
+// the weight stream needs is known after it, so the weight prefetch can start before the token tables are read.
 template <bool DUAL>
-__device__ __forceinline__ WorkItem resolve_work(const GemmParams &p)
+__device__ __forceinline__ WorkItem resolve_expert(const GemmParams &p)
 {
     WorkItem w;
     w.valid = false;
     w.off = 0;
+    w.Te = 0;
+    w.e = -1;
     w.shared_s = -1;
     w.B = p.B;
     w.out = p.out;
     const int b = blockIdx.x;
-    const int P = p.T * p.k;
     const uint16_t *Wbase;
     if (b < p.routed_blocks) {
         const int rank = b / p.tiles_r;
         w.tile = b % p.tiles_r;
+        const int e = p.active[rank];           // rank < min(N, T*k) <= N: inside the list
         const int na = min(*p.num_active, p.N);
-        if (rank >= na) return w;
-        const int e = p.active[rank];
-        if (e < 0 || e >= p.N) return w;
-        w.off = p.offsets[e];
-        w.Te = p.offsets[e + 1] - w.off;
-        if (w.off < 0 || w.Te <= 0 || w.off + w.Te > P) return w;
+        if (rank >= na || e < 0 || e >= p.N) return w;
+        w.e = e;
         w.R = p.R;
         w.K = p.K;
         w.kbeg = 0;
@@ -99,7 +102,7 @@ __device__ __forceinline__ WorkItem resolve_work(const GemmParams &p)
         w.kbeg = (v % p.shared_splits) * per;
         w.ksteps = min(w.K / 32, w.kbeg + per) - w.kbeg;
         if (w.ksteps <= 0) return w;
-        w.out_base = P + v * p.T;
+        w.out_base = p.T * p.k + v * p.T;
         Wbase = p.W_shared + (size_t)w.shared_s * ((size_t)w.R * w.K * (DUAL ? 2 : 1));
         // shared experts keep their h rows in their own region of the scratch
         const size_t hbase = (size_t)p.shared_h_base + (size_t)w.shared_s * p.T * (DUAL ? w.R : w.K);
@@ -113,6 +116,15 @@ __device__ __forceinline__ WorkItem resolve_work(const GemmParams &p)
     return w;
 }
 
+// Second half: the routed expert's token range (a second round trip).
+__device__ __forceinline__ void resolve_tokens(const GemmParams &p, WorkItem &w)
+{
+    if (w.shared_s >= 0) return;
+    w.off = p.offsets[w.e];
+    w.Te = p.offsets[w.e + 1] - w.off;
+    if (w.off < 0 || w.Te <= 0 || w.off + w.Te > p.T * p.k) w.valid = false;
+}
+
 // B row (element offset) and output row of the i-th token of the work item; -1 = none.
 template <bool DUAL>
 __device__ __forceinline__ void token_rows(const GemmParams &p, const WorkItem &w, int i, int &ro, int &orow)
@@ -123,13 +135,14 @@ __device__ __forceinline__ void token_rows(const GemmParams &p, const WorkItem &
     const int P = p.T * p.k;
     if (w.shared_s < 0) {
         const int pv = p.perm[w.off + i];
-        if (pv < 0 || pv >= P) return;
+        const bool ok = pv >= 0 && pv < P;
         if (DUAL) {   // B row = x[token], out row = sorted position in h
+            if (!ok) return;
             ro = (pv / p.k) * w.K;
             orow = w.off + i;
-        } else {      // B row = h[sorted position], out row = pair id in o
+        } else {      // B row = h[sorted position] (known without the permutation), out row = pair id in o
             ro = (w.off + i) * w.K;
-            orow = pv;
+            orow = ok ? pv : -1;
         }
     } else if (DUAL) {   // shared: every token
         ro = i * w.K;
@@ -203,31 +216,88 @@ __device__ __forceinline__ uint4 ring_load(const uint4 *__restrict__ base, int i
     return base[index];
 }
 
+// The same for expert weights, as a non-temporal load: a weight byte is read once per launch, and a stream
+// that does not allocate in the caches on its way runs measurably closer to the HBM rate.
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 ring_load_weights(const uint4 *__restrict__ base, int index)
+{
+    asm volatile("" : "+v"(index));
+    const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(base) + index);
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 // Two weight streams share every B fragment: gate and up tiles (interleaved: second = 64, step = 128) or,
 // for the down projection, two consecutive row tiles (second = one row tile further, step = 64).
-template <int NT>
-__device__ __forceinline__ void stream_direct(const uint4 *__restrict__ Wt, int step, int second, int n,
-                                              const uint4 *const (&brow)[NT], f32x4 (&acc0)[NT], f32x4 (&acc1)[NT])
+struct WeightRing {
+    uint4 w0[kPFD], w1[kPFD];
+};
+
+// Where a wave of the direct path streams from: needs the expert, not its tokens.
+struct DirectPlan {
+    const uint4 *Wl;     // this lane's piece of the wave's first weight tile
+    int step, second;    // uint4 strides: next k-step, second stream
+    int kb, n;           // first k-step and k-steps of this wave
+    int rt;              // first 16-row tile
+    bool rows_ok;
+};
+
+template <bool DUAL, int KW>
+__device__ __forceinline__ DirectPlan plan_direct(const WorkItem &w)
 {
-    const uint4 *Wl = Wt + lane_id();
-    const int last = n - 1;
-    uint4 w0[kPF], w1[kPF], bb[kPF][NT];
+    constexpr int RW = kFfnWaves / KW;
+    const int wv = wave_id();
+    const int rw = wv / KW, kw = wv % KW;
+    const int KT = w.K / 32;
+    DirectPlan d;
+    const int grp = w.tile * RW + rw;                  // row group of this wave
+    d.rt = DUAL ? grp : 2 * grp;
+    d.rows_ok = d.rt * 16 < w.R;                       // (down: R/16 is even, so the second tile exists too)
+    const int per = (w.ksteps + KW - 1) / KW;
+    d.kb = w.kbeg + kw * per;
+    d.n = min(w.kbeg + w.ksteps, d.kb + per) - d.kb;
+    const int rtc = d.rows_ok ? d.rt : 0;              // waves past the last row read tile 0 and store nothing
+    const int kbc = d.n > 0 ? d.kb : 0;
+    d.step = DUAL ? 2 * kWave : kWave;
+    d.second = DUAL ? kWave : KT * kWave;
+    d.Wl = w.W + ((size_t)rtc * KT + kbc) * d.step + lane_id();
+    return d;
+}
+
+__device__ __forceinline__ void prefetch_weights(const DirectPlan &d, WeightRing &r)
+{
+    const int last = max(d.n, 1) - 1;
 #pragma unroll
-    for (int j = 0; j < kPF; ++j) {
+    for (int j = 0; j < kPFD; ++j) {
         const int s = min(j, last);
-        w0[j] = ring_load(Wl, s * step);
-        w1[j] = ring_load(Wl, s * step + second);
+        r.w0[j] = ring_load_weights(d.Wl, s * d.step);
+        r.w1[j] = ring_load_weights(d.Wl, s * d.step + d.second);
+    }
+}
+
+// The ring arrives with its first turn of weight tiles already requested (prefetch_weights).
+template <int NT>
+__device__ __forceinline__ void stream_direct(const DirectPlan &d, WeightRing &r, const uint4 *const (&brow)[NT],
+                                              f32x4 (&acc0)[NT], f32x4 (&acc1)[NT])
+{
+    const uint4 *Wl = d.Wl;
+    const int step = d.step, second = d.second;
+    const int n = d.rows_ok ? d.n : 0;     // k-steps whose products count
+    const int last = max(d.n, 1) - 1;
+    uint4 bb[kPFD][NT];
+#pragma unroll
+    for (int j = 0; j < kPFD; ++j) {
+        const int s = min(j, last);
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) bb[j][nt] = ring_load(brow[nt], s * 4);
     }
-    for (int s0 = 0; s0 < n; s0 += kPF) {
+    for (int s0 = 0; s0 < n; s0 += kPFD) {
 #pragma unroll
-        for (int u = 0; u < kPF; ++u) {
+        for (int u = 0; u < kPFD; ++u) {
             const int s = s0 + u;
             const bool live = s < n;
             // consume slot u ...
-            const bf16x8 a0 = __builtin_bit_cast(bf16x8, sel4(live, w0[u]));
-            const bf16x8 a1 = __builtin_bit_cast(bf16x8, sel4(live, w1[u]));
+            const bf16x8 a0 = __builtin_bit_cast(bf16x8, sel4(live, r.w0[u]));
+            const bf16x8 a1 = __builtin_bit_cast(bf16x8, sel4(live, r.w1[u]));
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
                 const bf16x8 b = __builtin_bit_cast(bf16x8, bb[u][nt]);
@@ -237,9 +307,9 @@ __device__ __forceinline__ void stream_direct(const uint4 *__restrict__ Wt, int 
             // ... then refill it (the scheduling fences keep the refill behind the last read of the slot,
             // so that it can land in the same registers and the ring needs no copies)
             __builtin_amdgcn_sched_barrier(0);
-            const int sn = min(s + kPF, last);
-            w0[u] = ring_load(Wl, sn * step);
-            w1[u] = ring_load(Wl, sn * step + second);
+            const int sn = min(s + kPFD, last);
+            r.w0[u] = ring_load_weights(Wl, sn * step);
+            r.w1[u] = ring_load_weights(Wl, sn * step + second);
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) bb[u][nt] = ring_load(brow[nt], sn * 4);
             __builtin_amdgcn_sched_barrier(0);
@@ -251,19 +321,15 @@ __device__ __forceinline__ void stream_direct(const uint4 *__restrict__ Wt, int 
 // summed through LDS at the end.  A row group is one 16-row tile of gate and up (gate/up) or two
 // consecutive 16-row tiles (down), so that every token fragment loaded feeds two MFMAs.
 template <bool DUAL, int NT, int KW>
-__device__ __forceinline__ void expert_direct(const GemmParams &p, const WorkItem &w, float *red)
+__device__ __forceinline__ void expert_direct(const GemmParams &p, const WorkItem &w, const DirectPlan &d, WeightRing &ring,
+                                              float *red)
 {
-    constexpr int RW = kFfnWaves / KW;
     constexpr int NACC = NT * 2;
     const int lane = lane_id(), wv = wave_id();
     const int rw = wv / KW, kw = wv % KW;
-    const int KT = w.K / 32;
-    const int grp = w.tile * RW + rw;                      // row group of this wave
-    const int rt = DUAL ? grp : 2 * grp;                   // its first 16-row tile
-    const bool rows_ok = rt * 16 < w.R;                    // (down: R/16 is even, so the second tile exists too)
-    const int per = (w.ksteps + KW - 1) / KW;
-    const int kb = w.kbeg + kw * per;
-    const int n = min(w.kbeg + w.ksteps, kb + per) - kb;
+    const int rt = d.rt;
+    const bool rows_ok = d.rows_ok;
+    const int kbc = d.n > 0 ? d.kb : 0;
 
     int orow[NT];
     const uint4 *brow[NT];
@@ -272,16 +338,11 @@ __device__ __forceinline__ void expert_direct(const GemmParams &p, const WorkIte
         int ro;
         token_rows<DUAL>(p, w, nt * 16 + (lane & 15), ro, orow[nt]);
         ro = max(ro, 0);   // columns without a token read row 0; their results are never stored
-        brow[nt] = reinterpret_cast<const uint4 *>(w.B + (size_t)ro + (size_t)kb * 32 + (lane >> 4) * 8);
+        brow[nt] = reinterpret_cast<const uint4 *>(w.B + (size_t)ro + (size_t)kbc * 32 + (lane >> 4) * 8);
     }
     f32x4 acc0[NT], acc1[NT];
     clear_acc<NT>(acc0, acc1);
-    if (rows_ok && n > 0) {
-        if (DUAL)
-            stream_direct<NT>(w.W + ((size_t)rt * KT + kb) * (2 * kWave), 2 * kWave, kWave, n, brow, acc0, acc1);
-        else
-            stream_direct<NT>(w.W + ((size_t)rt * KT + kb) * kWave, kWave, KT * kWave, n, brow, acc0, acc1);
-    }
+    stream_direct<NT>(d, ring, brow, acc0, acc1);
     if (KW > 1) {
         f32x4 *r4 = reinterpret_cast<f32x4 *>(red);   // [rw][kw-1][NACC][lane]
         if (kw > 0) {
@@ -370,8 +431,8 @@ __device__ __forceinline__ void stream_staged(const uint4 *__restrict__ Wt, bool
 #pragma unroll
     for (int j = 0; j < kPF; ++j) {
         const int s = min(j, last);
-        wg[j] = ring_load(Wl, s * WSTEP);
-        wu[j] = DUAL ? ring_load(Wl, s * WSTEP + kWave) : zero4();
+        wg[j] = ring_load_weights(Wl, s * WSTEP);
+        wu[j] = DUAL ? ring_load_weights(Wl, s * WSTEP + kWave) : zero4();
     }
     load_x(0);
     store_x(0);
@@ -399,8 +460,8 @@ __device__ __forceinline__ void stream_staged(const uint4 *__restrict__ Wt, bool
             }
             __builtin_amdgcn_sched_barrier(0);
             const int sn = min(s + kPF, last);
-            wg[u] = ring_load(Wl, sn * WSTEP);
-            if (DUAL) wu[u] = ring_load(Wl, sn * WSTEP + kWave);
+            wg[u] = ring_load_weights(Wl, sn * WSTEP);
+            if (DUAL) wu[u] = ring_load_weights(Wl, sn * WSTEP + kWave);
             __builtin_amdgcn_sched_barrier(0);
             if (u % KS == KS - 1) {
                 store_x(c + 1);
@@ -440,20 +501,31 @@ __global__ __launch_bounds__(kFfnThreads, 2) void expert_kernel(GemmParams p)
     __shared__ __attribute__((aligned(16))) char stage[kStageBytes];   // staged token tile, or the K-slice partial sums
     __shared__ int rowoff[kTokBlock];   // staged path: element offset of each token's B row, -1 = none
     __shared__ int outrow[kTokBlock];   // staged path: output row of each token, -1 = none
-    WorkItem w = resolve_work<DUAL>(p);
+    WorkItem w = resolve_expert<DUAL>(p);
+    if (!w.valid) return;
+    // The weight stream of the direct path starts before the token tables are read (their loads depend on
+    // each other: offsets, then the permutation, then the token rows).
+    const DirectPlan plan = plan_direct<DUAL, KW>(w);
+    WeightRing ring;
+    prefetch_weights(plan, ring);
+    resolve_tokens(p, w);
     if (!w.valid) return;
     if (w.Te <= kDirectMaxTokens) {
-        expert_direct<DUAL, 1, KW>(p, w, reinterpret_cast<float *>(stage));
+        expert_direct<DUAL, 1, KW>(p, w, plan, ring, reinterpret_cast<float *>(stage));
         return;
     }
     // staged path: units of 64 rows.  A direct workgroup covers 16*RW rows (gate/up) or 32*RW rows (down).
     constexpr int kRowsPerWG = 16 * (kFfnWaves / KW) * (DUAL ? 1 : 2);
     constexpr int kUnits = kRowsPerWG >= 64 ? kRowsPerWG / 64 : 1;      // staged units this workgroup does
     constexpr int kShare = kRowsPerWG >= 64 ? 1 : 64 / kRowsPerWG;      // workgroups that share one unit
-    if ((w.tile % kShare) != 0) return;
-    const int unit0 = (w.tile / kShare) * kUnits;
+    // (shared experts see every token, so the host knows that they are staged and gives them one workgroup
+    // per unit)
+    const bool shared = w.shared_s >= 0;
+    if (!shared && (w.tile % kShare) != 0) return;
+    const int unit0 = shared ? w.tile : (w.tile / kShare) * kUnits;
+    const int units = shared ? 1 : kUnits;
     const int tid = threadIdx.x;
-    for (int un = 0; un < kUnits; ++un) {
+    for (int un = 0; un < units; ++un) {
         w.tile = unit0 + un;
         if (w.tile * 64 >= w.R) break;
         for (int i0 = 0; i0 < w.Te; i0 += kTokBlock) {
@@ -526,12 +598,8 @@ __global__ __launch_bounds__(256) void pack_kernel(const uint16_t *__restrict__ 
 // How many of a workgroup's four waves split the contraction dimension (the rest split rows).  Long
 // per-wave streams amortise the fill and drain of the prefetch ring, so K is only split when the
 // batch cannot invoke enough experts to give every CU several waves otherwise.
-static int pick_k_waves(int K, bool dual, int T, int max_experts, const char *env_override)
+static int pick_k_waves(int K, bool dual, int T, int max_experts)
 {
-    if (const char *v = getenv(env_override)) {
-        const int kw = atoi(v);
-        if (kw == 1 || kw == 2 || kw == 4) return kw;
-    }
     // With more than 16 tokens some expert may take the staged path, whose unit is 64 rows: the workgroup
     // shape is then chosen so that a workgroup covers exactly 64 rows (workgroups that only exist to be told
     // they have nothing to do are expensive).
@@ -548,7 +616,9 @@ static int pick_k_waves(int K, bool dual, int T, int max_experts, const char *en
 static void set_tiles(GemmParams &p, int rows_per_wg)
 {
     p.tiles_r = (p.R + rows_per_wg - 1) / rows_per_wg;
-    p.tiles_s = p.n_shared ? (p.Rs + rows_per_wg - 1) / rows_per_wg : 0;
+    // shared experts process all T tokens: staged (units of 64 rows, one per workgroup) when T is past the direct limit
+    const int rows_shared = p.T > kDirectMaxTokens ? 64 : rows_per_wg;
+    p.tiles_s = p.n_shared ? (p.Rs + rows_shared - 1) / rows_shared : 0;
     p.routed_blocks = (int)min((long)p.N, (long)p.T * p.k) * p.tiles_r;   // at most min(N, T*k) experts are invoked
 }
 
@@ -576,10 +646,10 @@ static int lds_pad()
 
 // One projection (gate/up or down) over all invoked and shared experts.
 template <bool DUAL>
-static int launch_projection(GemmParams p, const char *env_override, hipStream_t st, const char *what)
+static int launch_projection(GemmParams p, hipStream_t st, const char *what)
 {
     const int max_experts = (int)min((long)p.N, (long)p.T * p.k) + p.n_shared;
-    const int kw = pick_k_waves(p.K, DUAL, p.T, max_experts, env_override);
+    const int kw = pick_k_waves(p.K, DUAL, p.T, max_experts);
     set_tiles(p, 16 * (kFfnWaves / kw) * (DUAL ? 1 : 2));
     const dim3 grid(grid_blocks(p)), block(kFfnThreads);
     if (kw == 4) {
@@ -682,7 +752,7 @@ extern "C" int lynx_moe_ffn_timed(const uint16_t *x_bf16, const uint16_t *Wgu_pa
     p.Ks = H;
     int rc = mark(0);
     if (rc != LYNX_OK) return rc;
-    rc = launch_projection<true>(p, "LYNX_FFN_KW_GU", st, "lynx_moe_ffn(gate/up)");
+    rc = launch_projection<true>(p, st, "lynx_moe_ffn(gate/up)");
     if (rc != LYNX_OK) return rc;
     rc = mark(1);
     if (rc != LYNX_OK) return rc;
@@ -697,7 +767,7 @@ extern "C" int lynx_moe_ffn_timed(const uint16_t *x_bf16, const uint16_t *Wgu_pa
     p.Rs = H;
     p.Ks = F_shared;
     p.shared_splits = splits;
-    rc = launch_projection<false>(p, "LYNX_FFN_KW_DN", st, "lynx_moe_ffn(down)");
+    rc = launch_projection<false>(p, st, "lynx_moe_ffn(down)");
     if (rc != LYNX_OK) return rc;
     rc = mark(2);
     if (rc != LYNX_OK) return rc;
