@@ -9,10 +9,10 @@
 //   logits_kernel         (token tile x expert group)  fp32 dot products: the router row is prefetched
 //                         into registers while the 4 tokens are staged in LDS; lanes split H; transposing
 //                         butterfly reduction.  Always its own launch (it needs the whole chip).
-//   T <= 64:  routing_small_kernel  ONE workgroup does everything else with all state in LDS: top-k,
+//   T <= 16:  routing_small_kernel  ONE workgroup does everything else with all state in LDS: top-k,
 //                         bins + histogram, scores + score order, nominations, fill, remap, gates, counts
 //                         and (fused path) the token assignment.  Two launches for the whole routing side.
-//   T  > 64:  token_kernel -> nominate_kernel -> remap_kernel, one wave per token over many workgroups, one
+//   T  > 16:  token_kernel -> nominate_kernel -> remap_kernel, one wave per token over many workgroups, one
 //                         launch per batch-level dependency (finished histogram; finished active set).
 //                         Scores/order and the fill are recomputed by every workgroup in its prologue
 //                         instead of costing a launch; the last workgroup of remap_kernel (atomic ticket
@@ -722,7 +722,7 @@ static int launch_after_logits(const char *who, const float *logits, int T, int 
 #undef LYNX_ROUTING_ARGS
 }
 
-// The whole routing side of lynx_moe_layer: two launches for T <= 64, four otherwise.  T >= 1, arguments checked.
+// The whole routing side of lynx_moe_layer: two launches for T <= kSmallT, four otherwise.  T >= 1, arguments checked.
 int routing_fused(const uint16_t *x, const float *Wr, const float *bias, int T, int H, int N, int k, float alpha,
                   int beta, int enable, float *logits, int32_t *topk_idx, float *topk_gate, float *topk_psum,
                   int32_t *new_idx, float *new_gate, int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist,
