@@ -42,6 +42,9 @@ def parse():
     ap.add_argument("--sweep-iters", type=int, default=10)
     ap.add_argument("--layers", type=int, default=0,
                     help="resident copies of the expert weights that successive steps cycle over (0 = enough for 4 GiB)")
+    ap.add_argument("--stack", type=int, default=0,
+                    help="time a chained stack of this many layers (own router and weights each, x <- bf16(x + y) between "
+                         "them) as a whole, eagerly and as one HIP graph, instead of the single-layer benchmark")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="before the steps, run a plain 1 GiB read + 1 GiB write elementwise kernel three times: under "
                          "rocprofv3 --pmc its FETCH_SIZE / WRITE_SIZE readings give the counters' scale")
@@ -115,6 +118,95 @@ def preset_args(wl, preset):
     return a, b, 1
 
 
+def run_stack(args, cfg, wl, torch):
+    """A stack of layers on one stream with a true dependency from each layer to the next, timed as a whole."""
+    import numpy as np
+
+    import paper_2411_08982_amd as L
+    T, n_layers = args.tokens, args.stack
+    alpha, beta, enable = preset_args(wl, args.preset)
+    layers, bufs = [], []
+    x0 = None
+    for l in range(n_layers):
+        d = wl.make_layer_device(cfg, T if l == 0 else 1, "cuda", layer=l)
+        Wgu, Wdp = L.lynx_pack_weights(d["Wg"], d["Wu"], d["Wd"])
+        Sgu = Sdp = None
+        if cfg.n_shared:
+            Sgu, Sdp = L.lynx_pack_weights(d["Sg"], d["Su"], d["Sd"])
+        torch.cuda.synchronize()
+        layers.append((d["Wr"], d["bias"], Wgu, Wdp, Sgu, Sdp))
+        bufs.append(L.LayerBuffers(T, cfg.H, cfg.F, cfg.N, cfg.k, beta, cfg.n_shared, cfg.F_shared))
+        if l == 0:
+            x0 = d["x"]
+        del d
+    xs = [x0] + [torch.empty_like(x0) for _ in range(n_layers)]
+
+    def chain(en):
+        for l, (Wr, bias, Wgu, Wdp, Sgu, Sdp) in enumerate(layers):
+            b = L.lynx_moe_layer(xs[l], Wr, bias, Wgu, Wdp, cfg.F, cfg.k, alpha, beta, en, Sgu, Sdp, cfg.n_shared,
+                                 cfg.F_shared, buffers=bufs[l])
+            L.lynx_residual_add(xs[l], b.y, out=xs[l + 1])
+
+    def timed(fn, reps):
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for a, b in evs:
+            a.record()
+            fn()
+            b.record()
+        torch.cuda.synchronize()
+        us = sorted(a.elapsed_time(b) * 1e3 for a, b in evs)
+        return us[len(us) // 2], us[0]
+
+    res = {}
+    for name, en in (("off", 0), (args.preset, enable)):
+        if name in res:
+            continue
+        for _ in range(max(1, args.warmup)):
+            chain(en)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            chain(en)
+        torch.cuda.synchronize()
+        wall_us = (time.perf_counter() - t0) * 1e6 / args.steps
+        eager_med, eager_min = timed(lambda: chain(en), args.steps)
+        na = np.array([b.num_active.cpu().numpy() for b in bufs])
+        routed = float(na[:, 1].sum()) * 3 * cfg.H * cfg.F * 2 + n_layers * cfg.n_shared * 3 * cfg.H * cfg.F_shared * 2
+        # the same chain as one HIP graph (the library enqueues kernels only: no allocation, memset or host read)
+        g = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            chain(en)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        with torch.cuda.graph(g, stream=side):
+            chain(en)
+        for _ in range(2):
+            g.replay()
+        graph_med, graph_min = timed(g.replay, args.steps)
+        res[name] = {"us_wall_eager": round(wall_us, 1), "us_eager_median": round(eager_med, 1), "us_eager_min": round(eager_min, 1),
+                     "us_graph_median": round(graph_med, 1), "us_graph_min": round(graph_min, 1),
+                     "invoked_before_mean": round(float(na[:, 0].mean()), 2), "invoked_after_mean": round(float(na[:, 1].mean()), 2),
+                     "expert_weight_GBps_graph": round(routed / (graph_med * 1e-6) / 1e9, 1)}
+        del g
+    best = res[args.preset]
+    out = {"metric": f"MoE-stack decode us/batch ({n_layers} chained layers)", "value": best["us_graph_median"], "unit": "us/batch",
+           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(best["us_graph_median"] * 1e-3, 5),
+           "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": f"{n_layers} chained {cfg.name}-shaped MoE layers (own router and expert weights each): hidden "
+                                  f"{cfg.H}, FFN {cfg.F}, {cfg.N} experts top-{cfg.k}, {cfg.n_shared} shared, bf16 weights, {T} "
+                                  f"decode tokens, remap {args.preset}; x <- bf16(x + y) between layers",
+                      "tokens": T, "alpha": alpha, "beta": beta, "layers": n_layers},
+           "us_per_layer": round(best["us_graph_median"] / n_layers, 2),
+           "tokens_per_s": round(T / (best["us_graph_median"] * 1e-6), 1),
+           "stack": res,
+           "roofline": {"bound": "hbm", "kernel": "whole stack (all kernels of all layers)", "achieved": best["expert_weight_GBps_graph"],
+                        "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(best["expert_weight_GBps_graph"] / HBM_PEAK_GBPS, 4),
+                        "traffic": None}}
+    print(json.dumps(out))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -127,6 +219,9 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     cfg = wl.CONFIGS[args.config]
+    if args.stack > 0:
+        run_stack(args, cfg, wl, torch)
+        return
     T = args.tokens
     alpha, beta, enable = preset_args(wl, args.preset)
     routed_bytes = 3 * cfg.N * cfg.H * cfg.F * 2
@@ -169,6 +264,22 @@ def main():
     gu_gbps = gu_bytes / (gu_ms * 1e-3) / 1e9
     ffn_gbps = (gu_bytes + dn_bytes) / ((gu_ms + dn_ms) * 1e-3) / 1e9
 
+    # The practical ceiling beside it: a plain read-only streaming kernel over 2 GiB, same load width and hint.
+    probe = torch.zeros(1 << 29, dtype=torch.int32, device="cuda")
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    plain = {}
+    for name, nt in (("non_temporal", True), ("default", False)):
+        for _ in range(2):
+            layer.L.lynx_read_probe(probe, sink, nt)
+        p0, p1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        p0.record()
+        for _ in range(5):
+            layer.L.lynx_read_probe(probe, sink, nt)
+        p1.record()
+        torch.cuda.synchronize()
+        plain[name] = round(5 * probe.numel() * 4 / (p0.elapsed_time(p1) * 1e-3) / 1e9, 1)
+    del probe
+
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
@@ -201,7 +312,8 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "expert_kernel<true, KW> (gate/up weight stream)",
                      "achieved": round(gu_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(gu_gbps / HBM_PEAK_GBPS, 4), "traffic": traffic,
-                     "bytes_per_launch": gu_bytes, "avg_launch_us": round(gu_ms * 1e3, 2)},
+                     "bytes_per_launch": gu_bytes, "avg_launch_us": round(gu_ms * 1e3, 2),
+                     "plain_read_GBps": plain},
     }
 
     if not args.no_sweep:

@@ -134,7 +134,7 @@ int lynx_moe_ffn_timed(const uint16_t *x_bf16, const uint16_t *Wgu_packed, const
 /*
  * The whole decode step of one MoE layer: the work of lynx_route, lynx_affinity_bin, lynx_permute and
  * lynx_moe_ffn chained on `stream` with the argument meanings above and identical results (the routing
- * side is issued as four fused launches).  All intermediate arrays are outputs.  stage_events: as in
+ * side is issued as two launches up to 16 tokens and four beyond).  All intermediate arrays are outputs.  stage_events: as in
  * lynx_moe_ffn_timed, or NULL.
  */
 int lynx_moe_layer(const uint16_t *x_bf16, const float *Wr, const float *bias, const uint16_t *Wgu_packed,
@@ -144,6 +144,24 @@ int lynx_moe_layer(const uint16_t *x_bf16, const float *Wr, const float *bias, c
                    int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist, int32_t *num_active,
                    int32_t *expert_offsets, int32_t *perm, int32_t *active_experts, int32_t *num_active_perm, float *y,
                    void *workspace, void *stream, void *const *stage_events);
+
+/*
+ * Measurement aid, not a step of the method: the residual update that chains MoE layers into a stack (the
+ * benchmark times a stack of layers as a whole, each layer's input depending on the layer before):
+ * x_next[i] = bf16(float(x[i]) + y[i]) for i < n, one fp32 addition rounded to nearest even.  x_bf16 [n] and
+ * x_next_bf16 [n] bf16, y [n] fp32, all DEVICE; n even; x_next may be x itself.  n == 0 is a no-op.
+ */
+int lynx_residual_add(const uint16_t *x_bf16, const float *y, size_t n, uint16_t *x_next_bf16, void *stream);
+
+/*
+ * Measurement aid, not a step of the method: enqueues a plain read-only streaming kernel over
+ * buf[0, bytes) (DEVICE memory, 16-byte aligned, bytes a multiple of 16; nothing is modified).  Timed by the
+ * caller over a buffer much larger than the caches it gives the read bandwidth the chip delivers in
+ * practice, which the benchmark prints beside the rate of the expert-weight stream.  non_temporal != 0:
+ * the loads carry the same non-temporal hint as the weight stream.  sink: one DEVICE uint32_t (kept only so
+ * that the loads have a use; practically never written).  bytes == 0 is a no-op.
+ */
+int lynx_read_probe(const void *buf, size_t bytes, int non_temporal, uint32_t *sink, void *stream);
 
 #ifdef __cplusplus
 }

@@ -4,7 +4,7 @@ The product is liblynx.so (hand-written HIP, C ABI in include/lynx.h); this pack
 Python binding.  Build with `python -m paper_2411_08982_amd.build`.
 """
 from .binding import (LIB_PATH, SYMBOLS, LayerBuffers, LynxError, lib, lynx_affinity_bin, lynx_moe_ffn, lynx_moe_layer,
-                      lynx_pack_weights, lynx_permute, lynx_route, new_workspace, workspace_bytes)
+                      lynx_pack_weights, lynx_permute, lynx_read_probe, lynx_residual_add, lynx_route, new_workspace, workspace_bytes)
 
 __all__ = ["LIB_PATH", "SYMBOLS", "LayerBuffers", "LynxError", "lib", "lynx_affinity_bin", "lynx_moe_ffn",
-           "lynx_moe_layer", "lynx_pack_weights", "lynx_permute", "lynx_route", "new_workspace", "workspace_bytes"]
+           "lynx_moe_layer", "lynx_pack_weights", "lynx_permute", "lynx_read_probe", "lynx_residual_add", "lynx_route", "new_workspace", "workspace_bytes"]

@@ -20,7 +20,7 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_HIP = 0, -1, -2, -3
 MAX_T, MAX_N, MAX_K, MAX_BETA = 1024, 256, 16, 6
 
 SYMBOLS = ["lynx_last_error", "lynx_workspace_bytes", "lynx_route", "lynx_affinity_bin", "lynx_permute",
-           "lynx_pack_weights", "lynx_moe_ffn", "lynx_moe_ffn_timed", "lynx_moe_layer"]
+           "lynx_pack_weights", "lynx_moe_ffn", "lynx_moe_ffn_timed", "lynx_moe_layer", "lynx_residual_add", "lynx_read_probe"]
 
 
 class LynxError(RuntimeError):
@@ -52,6 +52,8 @@ def lib():
         L.lynx_moe_ffn.argtypes = [P, P, P, P, P, I, I, P, P, P, P, P, P, I, I, I, I, I, P, P, P]
         L.lynx_moe_ffn_timed.argtypes = L.lynx_moe_ffn.argtypes + [ctypes.POINTER(c_void_p)]
         L.lynx_moe_layer.argtypes = [P, P, P, P, P, P, P, I, I, I, I, I, I, I, F, I, I] + [P] * 17 + [ctypes.POINTER(c_void_p)]
+        L.lynx_read_probe.argtypes = [P, c_size_t, I, P, P]
+        L.lynx_residual_add.argtypes = [P, P, c_size_t, P, P]
         for name in SYMBOLS[2:]:
             getattr(L, name).restype = c_int
         _lib = L
@@ -206,3 +208,19 @@ def lynx_moe_layer(x, Wr, bias, Wgu, Wdp, F, k, alpha, beta, enable=1, Sgu=None,
         b.num_active_perm.data_ptr(), b.y.data_ptr(), b.workspace.data_ptr(), _stream(),
         None if stage_events is None else (c_void_p * 4)(*[e.cuda_event for e in stage_events])))
     return b
+
+
+def lynx_read_probe(buf, sink, non_temporal=True):
+    """Enqueues the plain read-only streaming kernel over `buf` (any contiguous device tensor whose byte size is a
+    multiple of 16); `sink` is a one-element int32/uint32 device tensor.  The caller times it."""
+    assert buf.is_cuda and buf.is_contiguous() and sink.is_cuda and sink.numel() >= 1 and sink.element_size() == 4
+    _check(lib().lynx_read_probe(buf.data_ptr(), buf.numel() * buf.element_size(), int(bool(non_temporal)), sink.data_ptr(),
+                                 _stream()))
+
+
+def lynx_residual_add(x, y, out=None):
+    """out = bf16(x + y) (x, out bf16; y fp32, same shape), the update that chains layers of a stack."""
+    out = torch.empty_like(x) if out is None else out
+    assert x.shape == y.shape == out.shape
+    _check(lib().lynx_residual_add(_ptr(x, BF16, "x"), _ptr(y, F32, "y"), x.numel(), _ptr(out, BF16, "out"), _stream()))
+    return out

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblynx.so")
-SOURCES = ["lynx_api.hip", "lynx_routing.hip", "lynx_permute.hip", "lynx_ffn.hip"]
+SOURCES = ["lynx_api.hip", "lynx_routing.hip", "lynx_permute.hip", "lynx_ffn.hip", "lynx_probe.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off", "-fno-fast-math",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-function"]

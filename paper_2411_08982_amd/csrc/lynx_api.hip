@@ -36,8 +36,9 @@ int routing_fused(const uint16_t *x, const float *Wr, const float *bias, int T, 
                   int32_t *num_active_perm, void *workspace, hipStream_t st);
 }
 
-// The fused path issues the routing side in four launches (logits; top-k + bins; nominations; remap +
-// token assignment) instead of the seven of the separate calls; results are identical.
+// The fused path issues the routing side in two launches up to 16 tokens (logits; everything else in one
+// workgroup) and in four beyond (logits; top-k + bins; nominations; remap + token assignment) instead of the
+// launches of the separate calls; results are identical.
 extern "C" int lynx_moe_layer(const uint16_t *x_bf16, const float *Wr, const float *bias, const uint16_t *Wgu_packed,
                               const uint16_t *Wd_packed, const uint16_t *Sgu_packed, const uint16_t *Sd_packed,
                               int n_shared, int F_shared, int T, int H, int F, int N, int k, float alpha, int beta,

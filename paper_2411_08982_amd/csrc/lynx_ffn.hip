@@ -31,9 +31,10 @@ constexpr int kPF = 8;                       // staged path: weight tiles in fli
 #endif
 constexpr int kPFD = LYNX_PFD;               // direct path: the same
 constexpr int kDirectMaxTokens = 16;         // experts with more tokens go to the staged kernel
-constexpr int kStagedNT = 4;                 // token tiles (of 16) per pass of the staged path
-constexpr int kTokBlock = 16 * kStagedNT;
+constexpr int kTokBlock = 64;                // tokens per pass of the staged path (batches of up to 64 tokens)
+constexpr int kTokBlockBig = 128;            // the same in the kernels launched for larger batches
 constexpr int kStageBytes = 2 * 18432;       // two LDS buffers for the staged token tile
+constexpr int kStageBytesBig = 2 * 128 * (4 * 64 + 16);   // the same in the large-batch kernels (128 tokens x 4 k-steps)
 
 struct GemmParams {
     const uint16_t *W_routed;   // packed routed weights (gate/up interleaved, or down)
@@ -44,8 +45,11 @@ struct GemmParams {
     int T, N, k, n_shared;
     int R, K;                   // routed: output rows, contraction length
     int Rs, Ks;                 // shared
-    int tiles_r, tiles_s;       // workgroups per routed / shared expert
-    int routed_blocks;
+    int tiles_r, tiles_s;       // row tiles (workgroups) per routed expert / per shared work item
+    int tiles_s_stride;         // tiles_s rounded up so that the token blocks of one shared row tile share an XCD
+    int shared_tblocks;         // token blocks that a shared expert's tokens are divided into (1 = not divided)
+    int tok_block;              // tokens per block: one pass of the staged path
+    int routed_blocks, shared_blocks;   // grid = shared blocks first (the longest workgroups), then routed
     int shared_splits;          // K slices per shared expert (down projection only; each slice has its own output rows)
     long long shared_h_base;    // element offset of the shared experts' h rows in the h scratch
 };
@@ -56,6 +60,7 @@ struct WorkItem {
     const uint16_t *B;   // B-operand rows
     void *out;
     int R, K, tile, Te, off, shared_s, e;
+    int tok0;            // shared experts: first token of this work item's token block
     int kbeg, ksteps;    // slice of the contraction dimension this work item covers, in k-steps of 32 columns
     int out_base;        // shared experts: first output row of this work item
     bool valid;
@@ -72,13 +77,15 @@ __device__ __forceinline__ WorkItem resolve_expert(const GemmParams &p)
     w.Te = 0;
     w.e = -1;
     w.shared_s = -1;
+    w.tok0 = 0;
     w.B = p.B;
     w.out = p.out;
     const int b = blockIdx.x;
     const uint16_t *Wbase;
-    if (b < p.routed_blocks) {
-        const int rank = b / p.tiles_r;
-        w.tile = b % p.tiles_r;
+    if (b >= p.shared_blocks) {
+        const int br = b - p.shared_blocks;
+        const int rank = br / p.tiles_r;
+        w.tile = br % p.tiles_r;
         const int e = p.active[rank];           // rank < min(N, T*k) <= N: inside the list
         const int na = min(*p.num_active, p.N);
         if (rank >= na || e < 0 || e >= p.N) return w;
@@ -90,12 +97,16 @@ __device__ __forceinline__ WorkItem resolve_expert(const GemmParams &p)
         w.out_base = 0;
         Wbase = p.W_routed + (size_t)e * ((size_t)w.R * w.K * (DUAL ? 2 : 1));
     } else {
-        const int bs = b - p.routed_blocks;
-        const int v = bs / p.tiles_s;   // (shared expert, K slice)
+        // b = ((shared expert, K slice) * token blocks + token block) * stride + row tile.  Workgroups go to the
+        // XCDs round-robin and the stride is a multiple of 8, so the token blocks of one row tile read their
+        // common weights through one L2.
+        w.tile = b % p.tiles_s_stride;
+        const int vt = b / p.tiles_s_stride;
+        const int v = vt / p.shared_tblocks;   // (shared expert, K slice)
+        w.tok0 = (vt % p.shared_tblocks) * p.tok_block;
         w.shared_s = v / p.shared_splits;
-        w.tile = bs % p.tiles_s;
-        if (w.shared_s >= p.n_shared || p.T <= 0) return w;
-        w.Te = p.T;
+        if (w.tile >= p.tiles_s || w.shared_s >= p.n_shared || w.tok0 >= p.T) return w;
+        w.Te = p.shared_tblocks > 1 ? min(p.T, w.tok0 + p.tok_block) : p.T;   // tokens [tok0, Te)
         w.R = p.Rs;
         w.K = p.Ks;
         const int per = (w.K / 32 + p.shared_splits - 1) / p.shared_splits;
@@ -385,7 +396,7 @@ __device__ __forceinline__ void stream_staged(const uint4 *__restrict__ Wt, bool
 {
     constexpr int ROWB = KS * 64 + 16;           // LDS bytes per token row (+16: conflict-free 16-byte reads)
     constexpr int BUFB = NT * 16 * ROWB;
-    static_assert(2 * BUFB <= kStageBytes, "token tile does not fit the LDS stage");
+    static_assert(2 * BUFB <= (NT > 4 ? kStageBytesBig : kStageBytes), "token tile does not fit the LDS stage");
     constexpr int PIECES = NT * 16 * KS * 4;     // 16-byte pieces per chunk
     static_assert(PIECES % kFfnThreads == 0, "pieces must divide evenly over the workgroup");
     constexpr int PPT = PIECES / kFfnThreads;
@@ -495,22 +506,26 @@ __device__ __forceinline__ void expert_staged(const WorkItem &w, const int *rowo
 // workgroup's four waves as RW row tiles x KW slices of K.  A larger expert takes the staged path, in which
 // a workgroup covers 64 rows: of every KW consecutive workgroups one does the work, in passes of up to 64
 // tokens, and the others leave.
-template <bool DUAL, int KW>
+template <bool DUAL, int KW, bool BIG>
 __global__ __launch_bounds__(kFfnThreads, 2) void expert_kernel(GemmParams p)
 {
-    __shared__ __attribute__((aligned(16))) char stage[kStageBytes];   // staged token tile, or the K-slice partial sums
-    __shared__ int rowoff[kTokBlock];   // staged path: element offset of each token's B row, -1 = none
-    __shared__ int outrow[kTokBlock];   // staged path: output row of each token, -1 = none
+    // staged token tile, or the K-slice partial sums
+    __shared__ __attribute__((aligned(16))) char stage[BIG ? kStageBytesBig : kStageBytes];
+    constexpr int TB = BIG ? kTokBlockBig : kTokBlock;   // tokens per pass
+    __shared__ int rowoff[TB];   // staged path: element offset of each token's B row, -1 = none
+    __shared__ int outrow[TB];   // staged path: output row of each token, -1 = none
     WorkItem w = resolve_expert<DUAL>(p);
     if (!w.valid) return;
     // The weight stream of the direct path starts before the token tables are read (their loads depend on
     // each other: offsets, then the permutation, then the token rows).
+    // (Not in the large-batch kernels: their staged path needs the registers, and few of their experts are direct.)
     const DirectPlan plan = plan_direct<DUAL, KW>(w);
     WeightRing ring;
-    prefetch_weights(plan, ring);
+    if (!BIG) prefetch_weights(plan, ring);
     resolve_tokens(p, w);
     if (!w.valid) return;
     if (w.Te <= kDirectMaxTokens) {
+        if (BIG) prefetch_weights(plan, ring);
         expert_direct<DUAL, 1, KW>(p, w, plan, ring, reinterpret_cast<float *>(stage));
         return;
     }
@@ -528,10 +543,10 @@ __global__ __launch_bounds__(kFfnThreads, 2) void expert_kernel(GemmParams p)
     for (int un = 0; un < units; ++un) {
         w.tile = unit0 + un;
         if (w.tile * 64 >= w.R) break;
-        for (int i0 = 0; i0 < w.Te; i0 += kTokBlock) {
-            const int nb = min(w.Te - i0, kTokBlock);
+        for (int i0 = w.tok0; i0 < w.Te; i0 += TB) {
+            const int nb = min(w.Te - i0, TB);
             __syncthreads();   // the previous pass has read rowoff / outrow and the stage
-            if (tid < kTokBlock) {
+            if (tid < TB) {
                 int ro, orow;
                 token_rows<DUAL>(p, w, tid < nb ? i0 + tid : w.Te, ro, orow);
                 rowoff[tid] = ro;
@@ -540,8 +555,10 @@ __global__ __launch_bounds__(kFfnThreads, 2) void expert_kernel(GemmParams p)
             __syncthreads();
             if (nb <= 32)
                 expert_staged<DUAL, 2, 8>(w, rowoff, outrow, stage);
-            else
+            else if (!BIG || nb <= 64)
                 expert_staged<DUAL, 4, 4>(w, rowoff, outrow, stage);
+            else
+                expert_staged<DUAL, 8, 4>(w, rowoff, outrow, stage);
         }
     }
 }
@@ -600,13 +617,16 @@ __global__ __launch_bounds__(256) void pack_kernel(const uint16_t *__restrict__ 
 // batch cannot invoke enough experts to give every CU several waves otherwise.
 static int pick_k_waves(int K, bool dual, int T, int max_experts)
 {
-    // With more than 16 tokens some expert may take the staged path, whose unit is 64 rows: the workgroup
-    // shape is then chosen so that a workgroup covers exactly 64 rows (workgroups that only exist to be told
-    // they have nothing to do are expensive).
-    if (T > kDirectMaxTokens) return dual ? 1 : 2;
-    // Measured: splitting K only pays when the batch can invoke so few experts that whole row groups would
-    // leave the chip with too few, too long workgroups (Mixtral-like shapes); with many small experts the
-    // short streams cost more than the finer granularity gains.
+    // Gate/up: a wave streams a whole row tile of both matrices (2 * K * 32 bytes, contiguous); measured best
+    // at every expert count.  It also makes a workgroup exactly one 64-row unit of the staged path.
+    if (dual) return 1;
+    // Down, more than 16 tokens: some expert may take the staged path, whose unit is 64 rows; two row groups
+    // of 32 rows per workgroup cover exactly one (workgroups that only exist to be told they have nothing to
+    // do are expensive).
+    if (T > kDirectMaxTokens) return 2;
+    // Down, direct path only.  Measured: splitting K pays when the batch can invoke so few experts that
+    // whole row groups would leave the chip with too few, too long workgroups (Mixtral-like shapes); with
+    // many small experts the short streams cost more than the finer granularity gains.
     const long group_bytes = (long)16 * K * 2 * 2;                        // weight bytes behind one row group
     int kw = max_experts <= 8 ? 4 : max_experts <= 16 ? 2 : 1;
     while (kw > 1 && group_bytes / kw < 32 * 1024) kw >>= 1;              // keep at least 32 KiB per wave
@@ -619,10 +639,16 @@ static void set_tiles(GemmParams &p, int rows_per_wg)
     // shared experts process all T tokens: staged (units of 64 rows, one per workgroup) when T is past the direct limit
     const int rows_shared = p.T > kDirectMaxTokens ? 64 : rows_per_wg;
     p.tiles_s = p.n_shared ? (p.Rs + rows_shared - 1) / rows_shared : 0;
+    // ... and then a workgroup with all T tokens would make one pass per 64 tokens over the same weights and be by
+    // far the longest of the launch: the passes go to workgroups of their own instead.
+    p.tok_block = p.T > kTokBlock ? kTokBlockBig : kTokBlock;
+    p.shared_tblocks = p.T > kDirectMaxTokens ? (p.T + p.tok_block - 1) / p.tok_block : 1;
+    p.tiles_s_stride = p.shared_tblocks > 1 ? (p.tiles_s + 7) / 8 * 8 : p.tiles_s;
+    p.shared_blocks = p.n_shared * p.shared_splits * p.shared_tblocks * p.tiles_s_stride;
     p.routed_blocks = (int)min((long)p.N, (long)p.T * p.k) * p.tiles_r;   // at most min(N, T*k) experts are invoked
 }
 
-static unsigned grid_blocks(const GemmParams &p) { return (unsigned)(p.routed_blocks + p.n_shared * p.shared_splits * p.tiles_s); }
+static unsigned grid_blocks(const GemmParams &p) { return (unsigned)(p.shared_blocks + p.routed_blocks); }
 
 // Workgroups per CU.  The dispatcher fills a CU up to its occupancy limit before it moves on, so a grid
 // that is small compared with the chip (few invoked experts) would leave CUs idle while others hold three
@@ -631,38 +657,42 @@ constexpr int kWgPerCu = 2;
 constexpr int kLdsPerCu = 160 * 1024;
 constexpr int kLdsTargetPerWg = 56 * 1024;
 
-template <bool DUAL, int KW>
-static int lds_pad()
+template <bool DUAL, int KW, bool BIG>
+static int launch_padded(const GemmParams &p, hipStream_t st)
 {
     static_assert(kLdsTargetPerWg * (kWgPerCu + 1) > kLdsPerCu && kLdsTargetPerWg * kWgPerCu <= kLdsPerCu, "LDS pad");
     static int pad = -1;   // per instantiation
     if (pad < 0) {
         hipFuncAttributes attr;
-        if (hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(&expert_kernel<DUAL, KW>)) != hipSuccess) return 0;
+        if (hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(&expert_kernel<DUAL, KW, BIG>)) != hipSuccess)
+            return fail(LYNX_ERR_HIP, "lynx_moe_ffn: hipFuncGetAttributes failed");
         pad = max(0, kLdsTargetPerWg - (int)attr.sharedSizeBytes);
     }
-    return pad;
+    hipLaunchKernelGGL((expert_kernel<DUAL, KW, BIG>), dim3(grid_blocks(p)), dim3(kFfnThreads), pad, st, p);
+    return LYNX_OK;
 }
 
-// One projection (gate/up or down) over all invoked and shared experts.
+// One projection (gate/up or down) over all invoked and shared experts.  Batches of more than 64 tokens take
+// the kernels whose staged path makes passes of up to 128 tokens.
 template <bool DUAL>
 static int launch_projection(GemmParams p, hipStream_t st, const char *what)
 {
     const int max_experts = (int)min((long)p.N, (long)p.T * p.k) + p.n_shared;
     const int kw = pick_k_waves(p.K, DUAL, p.T, max_experts);
     set_tiles(p, 16 * (kFfnWaves / kw) * (DUAL ? 1 : 2));
-    const dim3 grid(grid_blocks(p)), block(kFfnThreads);
-    if (kw == 4) {
-        const int pad = lds_pad<DUAL, 4>();
-        hipLaunchKernelGGL((expert_kernel<DUAL, 4>), grid, block, pad, st, p);
-    } else if (kw == 2) {
-        const int pad = lds_pad<DUAL, 2>();
-        hipLaunchKernelGGL((expert_kernel<DUAL, 2>), grid, block, pad, st, p);
-    } else {
-        const int pad = lds_pad<DUAL, 1>();
-        hipLaunchKernelGGL((expert_kernel<DUAL, 1>), grid, block, pad, st, p);
-    }
-    return check_launch(what);
+    const bool big = p.T > kTokBlock;
+    int rc;
+    if (DUAL)
+        rc = big ? launch_padded<true, 1, true>(p, st) : launch_padded<true, 1, false>(p, st);
+    else if (big)
+        rc = launch_padded<false, 2, true>(p, st);
+    else if (kw == 4)
+        rc = launch_padded<false, 4, false>(p, st);
+    else if (kw == 2)
+        rc = launch_padded<false, 2, false>(p, st);
+    else
+        rc = launch_padded<false, 1, false>(p, st);
+    return rc != LYNX_OK ? rc : check_launch(what);
 }
 
 }  // namespace lynx

@@ -20,7 +20,7 @@ def _declared():
 def test_library_exports_every_declared_symbol():
     lib = L.lib()
     names = _declared()
-    assert set(names) == set(L.SYMBOLS) and len(names) == 9
+    assert set(names) == set(L.SYMBOLS) and len(names) == 11
     for n in names:
         assert getattr(lib, n) is not None
 
@@ -67,6 +67,11 @@ def test_argument_errors_are_reported_before_any_launch():
     assert rc == -1 and b"shared" in lib.lynx_last_error()
     assert lib.lynx_moe_ffn(one, one, one, None, None, 0, 0, one, one, one, one, one, one, 4, 64, 72, 4, 2, one, one,
                             None) == -2
+    assert lib.lynx_residual_add(one, one, 3, one, None) == -1       # odd length
+    assert lib.lynx_residual_add(one, None, 4, one, None) == -1
+    assert lib.lynx_read_probe(None, 32, 1, one, None) == -1
+    assert lib.lynx_read_probe(one, 24, 1, one, None) == -1          # size not a multiple of 16
+    assert lib.lynx_read_probe(one, 0, 1, one, None) == 0            # nothing to read
 
 
 def test_missing_library_is_an_error(monkeypatch, tmp_path):

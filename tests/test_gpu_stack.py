@@ -1,0 +1,145 @@
+"""GPU tests of a chained stack of MoE layers, x_{l+1} = bf16(x_l + y_l), as the benchmark times it.
+
+Parity is checked per layer with the GPU's own layer input fed to the oracle (a comparison along the chain
+would turn legitimate bf16 differences into different routing further down).  The stack is also captured
+into a HIP graph: every replay, with eager work and synchronisations in between, must reproduce the eager
+result bit for bit (the kernels use no floating-point atomics, so the result does not depend on timing).
+"""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads as wl
+from gpu_util import bf16_bits, dev, host, row_rel_err, to_bf16_dev
+
+pytestmark = pytest.mark.gpu
+
+Y_TOL = 1e-2
+
+
+@pytest.fixture(scope="module")
+def L():
+    import paper_2411_08982_amd as lib
+    lib.lib()
+    assert torch.cuda.is_available()
+    return lib
+
+
+class Stack:
+    """`n_layers` small layers with their own routers and expert weights, resident on the GPU."""
+
+    def __init__(self, L, cfg, T, n_layers, alpha, beta):
+        self.L, self.cfg, self.T, self.alpha, self.beta = L, cfg, T, alpha, beta
+        self.host_layers = [wl.make_layer(cfg, T, layer=l) for l in range(n_layers)]
+        self.dev_layers = []
+        for d in self.host_layers:
+            Wgu, Wdp = L.lynx_pack_weights(to_bf16_dev(d["Wg"]), to_bf16_dev(d["Wu"]), to_bf16_dev(d["Wd"]))
+            Sgu = Sdp = None
+            if cfg.n_shared:
+                Sgu, Sdp = L.lynx_pack_weights(to_bf16_dev(d["Sg"]), to_bf16_dev(d["Su"]), to_bf16_dev(d["Sd"]))
+            self.dev_layers.append((dev(d["Wr"]), dev(d["bias"]), Wgu, Wdp, Sgu, Sdp))
+        self.x0 = to_bf16_dev(self.host_layers[0]["x"])
+        # every layer has its own outputs (kept for the checks) and its own input buffer
+        self.buf = [L.LayerBuffers(T, cfg.H, cfg.F, cfg.N, cfg.k, beta, cfg.n_shared, cfg.F_shared) for _ in range(n_layers)]
+        self.x = [self.x0] + [torch.empty_like(self.x0) for _ in range(n_layers)]
+        torch.cuda.synchronize()
+
+    def run(self):
+        """Enqueues the whole chain on the current stream; allocates nothing."""
+        c = self.cfg
+        for l, (Wr, bias, Wgu, Wdp, Sgu, Sdp) in enumerate(self.dev_layers):
+            b = self.L.lynx_moe_layer(self.x[l], Wr, bias, Wgu, Wdp, c.F, c.k, self.alpha, self.beta, 1, Sgu, Sdp,
+                                      c.n_shared, c.F_shared, buffers=self.buf[l])
+            self.L.lynx_residual_add(self.x[l], b.y, out=self.x[l + 1])
+
+    def snapshot(self):
+        torch.cuda.synchronize()
+        out = [bf16_bits(x) for x in self.x]
+        for b in self.buf:
+            out += [host(b.y), host(b.new_idx), host(b.perm), host(b.num_active)]
+        return out
+
+
+def test_residual_add_is_one_rounded_fp32_addition(L):
+    rng = np.random.default_rng(5)
+    for shape in ((3, 64), (1, 2), (37, 4096)):
+        xb = wl.f32_to_bf16_bits(rng.standard_normal(shape).astype(np.float32) * 3)
+        y = (rng.standard_normal(shape) * np.exp(rng.uniform(-8, 3, shape))).astype(np.float32)
+        want = wl.f32_to_bf16_bits(wl.bf16_bits_to_f32(xb) + y)          # numpy fp32 add, then round to nearest even
+        x = to_bf16_dev(xb)
+        got = L.lynx_residual_add(x, dev(y))
+        torch.cuda.synchronize()
+        assert np.array_equal(bf16_bits(got), want)
+        L.lynx_residual_add(x, dev(y), out=x)                            # in place
+        torch.cuda.synchronize()
+        assert np.array_equal(bf16_bits(x), want)
+
+
+@pytest.mark.parametrize("T,shared", [(8, 0), (24, 1)])
+def test_stack_parity_layer_by_layer(L, T, shared):
+    print(f"stack of 4 layers, T={T}, shared={shared}", flush=True)
+    cfg = dataclasses.replace(wl.CONFIGS["tiny"], name="stack", H=256, F=384, N=24, k=3, n_shared=shared,
+                              F_shared=128 if shared else 0, seed=11)
+    alpha, beta = 2.0, 2
+    st = Stack(L, cfg, T, 4, alpha, beta)
+    st.run()
+    torch.cuda.synchronize()
+    remapped = 0
+    for l, d in enumerate(st.host_layers):
+        xb = bf16_bits(st.x[l])                     # the GPU's own input of this layer
+        b = st.buf[l]
+        z = host(b.logits)
+        r = oracle.route(xb, d["Wr"], d["bias"], cfg.k)
+        assert np.all(np.abs(z - r["logits"]) <= 1e-5 * np.maximum(1.0, np.abs(r["logits"])))
+        tk = oracle.topk(z, cfg.k)
+        a = oracle.affinity_bin(z, tk["idx"], alpha, beta, 1)
+        assert np.array_equal(host(b.new_idx), a["new_idx"])
+        assert np.array_equal(host(b.num_active), a["num_active"])
+        p = oracle.permute(a["new_idx"], cfg.N)
+        assert np.array_equal(host(b.perm), p["perm"]) and np.array_equal(host(b.offsets), p["offsets"])
+        y_ref = oracle.moe_ffn(xb, d["Wg"], d["Wu"], d["Wd"], a["new_idx"], a["new_gate"], d.get("Sg"), d.get("Su"),
+                               d.get("Sd"))
+        y = host(b.y)
+        assert row_rel_err(y, y_ref).max() <= Y_TOL
+        assert np.array_equal(bf16_bits(st.x[l + 1]), wl.f32_to_bf16_bits(wl.bf16_bits_to_f32(xb) + y))
+        remapped += int(a["num_active"][0] - a["num_active"][1])
+    print(f"  experts saved over the stack: {remapped}", flush=True)
+
+
+@pytest.mark.parametrize("T", [8, 40])
+def test_graph_replays_reproduce_the_eager_stack(L, T):
+    print(f"graph capture of a 3-layer stack, T={T}", flush=True)
+    cfg = dataclasses.replace(wl.CONFIGS["tiny"], name="graph", H=256, F=384, N=24, k=3, n_shared=1, F_shared=128, seed=12)
+    st = Stack(L, cfg, T, 3, 4.0, 1)
+    st.run()
+    eager = st.snapshot()
+    other = to_bf16_dev(wl.make_tokens(cfg, T, st.host_layers[0]["Wr"], st.host_layers[0]["bias"], seed=99))
+    first = st.x0.clone()
+    st.x0.copy_(other)
+    st.run()
+    eager_other = st.snapshot()
+    assert not np.array_equal(eager[-4], eager_other[-4])       # the second input really gives another result
+
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        st.run()                                                # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    with torch.cuda.graph(g, stream=side):
+        st.run()
+    for rep, (inp, want) in enumerate([(first, eager), (other, eager_other), (first, eager), (first, eager)]):
+        for x in st.x[1:]:
+            x.zero_()                                           # eager work between the replays
+        for b in st.buf:
+            b.y.fill_(float("nan"))
+        st.x0.copy_(inp)
+        torch.cuda.synchronize()
+        g.replay()
+        got = st.snapshot()
+        for i, (u, v) in enumerate(zip(got, want)):
+            assert np.array_equal(u, v), f"replay {rep}: array {i} differs from the eager run"
