@@ -86,6 +86,26 @@ __device__ __forceinline__ void wave_topk(const float (&v)[NS], unsigned cand, i
     }
 }
 
+// ---- data handed from one workgroup to another inside a launch ---------------------------------------------
+// Every XCD has its own L2, and a device-wide fence (write back / invalidate that L2) costs microseconds per
+// workgroup.  Instead, the few words that another workgroup of the same launch will read are written with
+// device-coherent stores or atomics (they go through to the point where all XCDs meet) and read with
+// device-coherent loads; the writer waits for its stores to complete before it takes its ticket.
+__device__ __forceinline__ void store_coherent(int32_t *p, int32_t v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ int32_t load_coherent(const int32_t *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ unsigned load_coherent(const unsigned *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// All memory operations this wave has issued are complete (vmcnt, expcnt, lgkmcnt = 0).
+__device__ __forceinline__ void wait_memory_complete() { __builtin_amdgcn_s_waitcnt(0); }
+
 // ---- workspace layout (one caller-provided buffer serves every call) -----------------------------------
 // [ routing scratch | h: bf16 intermediate vectors | o: fp32 per-pair outputs ]
 // Routing scratch (int32 words): tickets of the "last workgroup finishes the batch-level step" pattern,

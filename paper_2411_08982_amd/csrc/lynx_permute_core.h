@@ -66,7 +66,7 @@ __device__ __forceinline__ void permute_from_bitsets(Shared &sh, const int32_t *
     }
     __syncthreads();
     for (int p = tid; p < P; p += THREADS) {
-        const int e = idx[p];
+        const int e = load_coherent(idx + p);   // in the fused kernel another workgroup of this launch wrote it
         if (e < 0 || e >= N) continue;
         const int t = p / k;
         int pos = sh.offs[e];

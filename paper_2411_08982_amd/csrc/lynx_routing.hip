@@ -339,7 +339,7 @@ __device__ __forceinline__ int token_remap(const TokenLogits<NS> &tl, int t, int
     float num, zref;
     const float g = selection_gate(k, mye, myz, num, zref);
     if (lane < k) {
-        new_idx[(size_t)t * k + lane] = mye;
+        store_coherent(&new_idx[(size_t)t * k + lane], mye);   // read by the workgroup that assigns the tokens
         new_gate[(size_t)t * k + lane] = g;
     }
     return mye;
@@ -369,16 +369,16 @@ __device__ __forceinline__ void rank_of(int tid, int N, const unsigned long long
     }
 }
 
-// True on every thread of the workgroup that takes the ticket last (all others have finished and fenced).
+// True on every thread of the workgroup that takes the ticket last.  Nobody waits for anybody.  What the
+// last workgroup reads of the others' results must have been written with atomics or store_coherent and must
+// be read with load_coherent: there is no device-wide fence here (see lynx_common.h).
 __device__ __forceinline__ bool last_workgroup(int32_t *ticket, int *flag_lds)
 {
-    __threadfence();
+    wait_memory_complete();
     __syncthreads();
     if (threadIdx.x == 0) *flag_lds = (atomicAdd(ticket, 1) == (int)gridDim.x - 1) ? 1 : 0;
     __syncthreads();
-    const bool last = *flag_lds != 0;
-    if (last) __threadfence();
-    return last;
+    return *flag_lds != 0;
 }
 
 // ---- small batches (T <= kSmallT): everything after the logits in ONE workgroup, all state in LDS -----------
@@ -593,7 +593,7 @@ __global__ __launch_bounds__(kTokThreads) void remap_kernel(const float *__restr
     if (tid == 0) sh.n_after = 0;
     if (DO_PERMUTE) {   // pairs whose expert is invalid stay unassigned
         const int p0 = blockIdx.x * kTokWaves * k, p1 = min(T * k, p0 + kTokWaves * k);
-        for (int p = p0 + tid; p < p1; p += kTokThreads) perm[p] = -1;
+        for (int p = p0 + tid; p < p1; p += kTokThreads) store_coherent(&perm[p], -1);   // overwritten by the last workgroup
     }
     __syncthreads();
     if (wave == 0) {
@@ -611,10 +611,10 @@ __global__ __launch_bounds__(kTokThreads) void remap_kernel(const float *__restr
     __syncthreads();
     if (tid < N && sh.cnta[tid]) atomicAdd(&cnt_after[tid], sh.cnta[tid]);
     if (!last_workgroup(ws + kWsTickets + 2, &sh.flag)) return;
-    if (tid < N && __atomic_load_n(&cnt_after[tid], __ATOMIC_RELAXED) > 0) atomicAdd(&sh.n_after, 1);
+    if (tid < N && load_coherent(&cnt_after[tid]) > 0) atomicAdd(&sh.n_after, 1);
     if constexpr (DO_PERMUTE) {
         const unsigned *member = reinterpret_cast<const unsigned *>(ws + kWsMember);
-        for (int i = tid; i < N * W; i += kTokThreads) sh.perm.member[i] = __atomic_load_n(&member[i], __ATOMIC_RELAXED);
+        for (int i = tid; i < N * W; i += kTokThreads) sh.perm.member[i] = load_coherent(&member[i]);
     }
     __syncthreads();
     if (tid == 0) num_active[1] = sh.n_after;
