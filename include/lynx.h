@@ -46,7 +46,10 @@ const char *lynx_last_error(void);
 
 /* Bytes of device workspace that lynx_affinity_bin, lynx_moe_ffn and lynx_moe_layer need for these
  * sizes (one buffer serves all; contents need not be preserved between calls; calls that share a
- * workspace must not overlap in time).  lynx_affinity_bin alone uses only the first 64 KiB. */
+ * workspace must not overlap in time).  lynx_affinity_bin alone uses only the first 64 KiB.  Word
+ * 9744 of the workspace (int32) is a diagnostic written by lynx_moe_ffn / lynx_moe_layer: non-zero after
+ * the call if a workgroup gave up a bounded wait for another workgroup's result (never seen; y is then
+ * not valid). */
 size_t lynx_workspace_bytes(int T, int H, int F, int N, int k, int n_shared, int F_shared);
 
 /*
@@ -109,7 +112,8 @@ int lynx_pack_weights(const uint16_t *Wg, const uint16_t *Wu, const uint16_t *Wd
  *                                                                      Sec. 3.3.1 last paragraph)
  * bf16 operands, fp32 accumulation; the intermediate vector is rounded to bf16 between the two
  * projections.  Each invoked expert's weights are read once per call; experts with no pair are not
- * touched.  Weights in the packed layout of lynx_pack_weights (Sgu/Sd: packed with E = n_shared,
+ * touched.  When both projections run as one launch, a down-projection workgroup waits (bounded) for the
+ * gate/up workgroups of its expert, which always precede it in dispatch order.  Weights in the packed layout of lynx_pack_weights (Sgu/Sd: packed with E = n_shared,
  * F = F_shared; NULL when n_shared = 0).  expert_offsets / perm / active_experts / num_active as
  * written by lynx_permute for the same idx.  y [T,H] fp32 out, overwritten.
  */
@@ -120,10 +124,18 @@ int lynx_moe_ffn(const uint16_t *x_bf16, const uint16_t *Wgu_packed, const uint1
                  float *y, void *workspace, void *stream);
 
 /*
+ * How many launches of the weight-streaming kernel lynx_moe_ffn issues for this batch size and expert width:
+ * 1 (gate/up and down workgroups in one grid) or 2 (one grid each).  For measurement: per-launch figures of
+ * a profile are whole-FFN figures divided by this.
+ */
+int lynx_moe_ffn_launches(int T, int F);
+
+/*
  * lynx_moe_ffn with stage timing for measurement (roofline of the weight-streaming kernels): the same
  * work, and additionally records the caller's events on `stream`.  stage_events: HOST array of four
- * hipEvent_t (entries may be NULL) recorded before the gate/up kernel, after it, after the down kernel,
- * and after the combine.  stage_events == NULL is exactly lynx_moe_ffn.
+ * hipEvent_t (entries may be NULL): [0] is recorded before the weight-streaming launch(es), [1] and [2]
+ * after them (gate/up and down are one kernel, launched once or twice: the two events are adjacent), [3]
+ * after the combine.  stage_events == NULL is exactly lynx_moe_ffn.
  */
 int lynx_moe_ffn_timed(const uint16_t *x_bf16, const uint16_t *Wgu_packed, const uint16_t *Wd_packed,
                        const uint16_t *Sgu_packed, const uint16_t *Sd_packed, int n_shared, int F_shared,

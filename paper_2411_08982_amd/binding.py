@@ -20,7 +20,7 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_HIP = 0, -1, -2, -3
 MAX_T, MAX_N, MAX_K, MAX_BETA = 1024, 256, 16, 6
 
 SYMBOLS = ["lynx_last_error", "lynx_workspace_bytes", "lynx_route", "lynx_affinity_bin", "lynx_permute",
-           "lynx_pack_weights", "lynx_moe_ffn", "lynx_moe_ffn_timed", "lynx_moe_layer", "lynx_residual_add", "lynx_read_probe"]
+           "lynx_pack_weights", "lynx_moe_ffn", "lynx_moe_ffn_timed", "lynx_moe_layer", "lynx_moe_ffn_launches", "lynx_residual_add", "lynx_read_probe"]
 
 
 class LynxError(RuntimeError):
@@ -53,6 +53,7 @@ def lib():
         L.lynx_moe_ffn_timed.argtypes = L.lynx_moe_ffn.argtypes + [ctypes.POINTER(c_void_p)]
         L.lynx_moe_layer.argtypes = [P, P, P, P, P, P, P, I, I, I, I, I, I, I, F, I, I] + [P] * 17 + [ctypes.POINTER(c_void_p)]
         L.lynx_read_probe.argtypes = [P, c_size_t, I, P, P]
+        L.lynx_moe_ffn_launches.argtypes = [I, I]
         L.lynx_residual_add.argtypes = [P, P, c_size_t, P, P]
         for name in SYMBOLS[2:]:
             getattr(L, name).restype = c_int
@@ -82,6 +83,9 @@ def _stream():
 
 
 BF16, F32, I32 = torch.bfloat16, torch.float32, torch.int32
+
+
+WAIT_FLAG_WORD = 9744   # int32 word of the workspace: non-zero if a bounded wait inside the FFN kernel ran out
 
 
 def workspace_bytes(T, H, F, N, k, n_shared=0, F_shared=0) -> int:
@@ -224,3 +228,8 @@ def lynx_residual_add(x, y, out=None):
     assert x.shape == y.shape == out.shape
     _check(lib().lynx_residual_add(_ptr(x, BF16, "x"), _ptr(y, F32, "y"), x.numel(), _ptr(out, BF16, "out"), _stream()))
     return out
+
+
+def lynx_moe_ffn_launches(T, F) -> int:
+    """Launches of the weight-streaming kernel per lynx_moe_ffn call (1 or 2) for this batch size and expert width."""
+    return int(lib().lynx_moe_ffn_launches(int(T), int(F)))

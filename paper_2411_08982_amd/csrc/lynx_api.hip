@@ -34,6 +34,11 @@ int routing_fused(const uint16_t *x, const float *Wr, const float *bias, int T, 
                   int32_t *new_idx, float *new_gate, int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist,
                   int32_t *num_active, int32_t *expert_offsets, int32_t *perm, int32_t *active_experts,
                   int32_t *num_active_perm, void *workspace, hipStream_t st);
+int moe_ffn_impl(const uint16_t *x_bf16, const uint16_t *Wgu_packed, const uint16_t *Wd_packed, const uint16_t *Sgu_packed,
+                 const uint16_t *Sd_packed, int n_shared, int F_shared, const int32_t *idx, const float *gate,
+                 const int32_t *expert_offsets, const int32_t *perm, const int32_t *active_experts,
+                 const int32_t *num_active, int T, int H, int F, int N, int k, float *y, void *workspace, void *stream,
+                 void *const *stage_events, bool counters_cleared);
 }
 
 // The fused path issues the routing side in two launches up to 16 tokens (logits; everything else in one
@@ -50,6 +55,7 @@ extern "C" int lynx_moe_layer(const uint16_t *x_bf16, const float *Wr, const flo
 {
     using namespace lynx;
     int rc;
+    bool fused = false;
     if (T <= 0 || !workspace) {
         // no tokens (or a missing workspace, which the separate calls report): take the separate calls
         rc = lynx_route(x_bf16, Wr, bias, T, H, N, k, logits, topk_idx, topk_gate, topk_psum, stream);
@@ -83,8 +89,9 @@ extern "C" int lynx_moe_layer(const uint16_t *x_bf16, const float *Wr, const flo
                            new_idx, new_gate, cnt_before, cnt_after, bin_hist, num_active, expert_offsets, perm,
                            active_experts, num_active_perm, workspace, (hipStream_t)stream);
         if (rc != LYNX_OK) return rc;
+        fused = true;   // its first kernel has also cleared the FFN's completion counters
     }
-    return lynx_moe_ffn_timed(x_bf16, Wgu_packed, Wd_packed, Sgu_packed, Sd_packed, n_shared, F_shared, new_idx, new_gate,
-                              expert_offsets, perm, active_experts, num_active_perm, T, H, F, N, k, y, workspace, stream,
-                              stage_events);
+    return moe_ffn_impl(x_bf16, Wgu_packed, Wd_packed, Sgu_packed, Sd_packed, n_shared, F_shared, new_idx, new_gate,
+                        expert_offsets, perm, active_experts, num_active_perm, T, H, F, N, k, y, workspace, stream,
+                        stage_events, fused);
 }

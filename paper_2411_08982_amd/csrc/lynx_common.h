@@ -103,6 +103,18 @@ __device__ __forceinline__ unsigned load_coherent(const unsigned *p)
 {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+__device__ __forceinline__ void store_coherent(uint2 *p, uint2 v)
+{
+    __hip_atomic_store(reinterpret_cast<unsigned long long *>(p), ((unsigned long long)v.y << 32) | v.x, __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint4 load_coherent(const uint4 *p)   // two 8-byte device-coherent loads
+{
+    const unsigned long long *q = reinterpret_cast<const unsigned long long *>(p);
+    const unsigned long long lo = __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const unsigned long long hi = __hip_atomic_load(q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return make_uint4((unsigned)lo, (unsigned)(lo >> 32), (unsigned)hi, (unsigned)(hi >> 32));
+}
 // All memory operations this wave has issued are complete (vmcnt, expcnt, lgkmcnt = 0).
 __device__ __forceinline__ void wait_memory_complete() { __builtin_amdgcn_s_waitcnt(0); }
 
@@ -114,9 +126,14 @@ constexpr int kWsTickets = 0;                              // 16 words
 constexpr int kWsOrder = 16;                               // LYNX_MAX_N words
 constexpr int kWsActive = kWsOrder + LYNX_MAX_N;           // LYNX_MAX_N words
 constexpr int kWsMember = kWsActive + LYNX_MAX_N;          // LYNX_MAX_N * LYNX_MAX_T/32 words
-constexpr int kWsRoutingWords = kWsMember + LYNX_MAX_N * (LYNX_MAX_T / 32);
+constexpr int kWsDone = kWsMember + LYNX_MAX_N * (LYNX_MAX_T / 32);   // FFN: gate/up completion counters
+constexpr int kWsDoneWords = 1024;                         // LYNX_MAX_N routed + (shared expert, token block) pairs
+constexpr int kWsFlags = kWsDone + kWsDoneWords;           // FFN: bit 0 = a bounded wait ran out
+constexpr int kWsRoutingWords = kWsFlags + 16;
 constexpr size_t kWsRoutingBytes = 65536;
 static_assert((size_t)kWsRoutingWords * 4 <= kWsRoutingBytes, "routing scratch does not fit its reservation");
+
+inline int h_stride(int F) { return (F + 63) / 64 * 64; }   // elements between rows of the h scratch
 
 struct Workspace {
     size_t h_elems, o_elems, h_off, o_off, routing_off, total;
@@ -128,7 +145,8 @@ inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 inline Workspace workspace_layout(int T, int H, int F, int k, int n_shared, int F_shared, int shared_splits)
 {
     Workspace w;
-    w.h_elems = (size_t)T * k * F + (size_t)n_shared * T * F_shared;
+    // rows of the intermediate vectors start on 128-byte lines (a cache line never holds parts of two experts' rows)
+    w.h_elems = (size_t)T * k * h_stride(F) + (size_t)n_shared * T * h_stride(F_shared);
     w.o_elems = ((size_t)T * k + (size_t)n_shared * shared_splits * T) * H;
     w.routing_off = 0;
     w.h_off = kWsRoutingBytes;

@@ -44,6 +44,7 @@ struct GemmParams {
     const int32_t *offsets, *perm, *active, *num_active;
     int T, N, k, n_shared;
     int R, K;                   // routed: output rows, contraction length
+    int ldb_r, ldo_r, ldb_s, ldo_s;   // elements between B rows / output rows, routed and shared
     int Rs, Ks;                 // shared
     int tiles_r, tiles_s;       // row tiles (workgroups) per routed expert / per shared work item
     int tiles_s_stride;         // tiles_s rounded up so that the token blocks of one shared row tile share an XCD
@@ -60,6 +61,7 @@ struct WorkItem {
     const uint16_t *B;   // B-operand rows
     void *out;
     int R, K, tile, Te, off, shared_s, e;
+    int ldb, ldo;        // elements between B rows / output rows
     int tok0;            // shared experts: first token of this work item's token block
     int kbeg, ksteps;    // slice of the contraction dimension this work item covers, in k-steps of 32 columns
     int out_base;        // shared experts: first output row of this work item
@@ -69,7 +71,7 @@ struct WorkItem {
 // First half: which expert, from blockIdx and the invoked-expert list (one round trip to memory).  Everything
 // the weight stream needs is known after it, so the weight prefetch can start before the token tables are read.
 template <bool DUAL>
-__device__ __forceinline__ WorkItem resolve_expert(const GemmParams &p)
+__device__ __forceinline__ WorkItem resolve_expert(const GemmParams &p, int b)
 {
     WorkItem w;
     w.valid = false;
@@ -80,7 +82,6 @@ __device__ __forceinline__ WorkItem resolve_expert(const GemmParams &p)
     w.tok0 = 0;
     w.B = p.B;
     w.out = p.out;
-    const int b = blockIdx.x;
     const uint16_t *Wbase;
     if (b >= p.shared_blocks) {
         const int br = b - p.shared_blocks;
@@ -92,6 +93,8 @@ __device__ __forceinline__ WorkItem resolve_expert(const GemmParams &p)
         w.e = e;
         w.R = p.R;
         w.K = p.K;
+        w.ldb = p.ldb_r;
+        w.ldo = p.ldo_r;
         w.kbeg = 0;
         w.ksteps = w.K / 32;
         w.out_base = 0;
@@ -109,6 +112,8 @@ __device__ __forceinline__ WorkItem resolve_expert(const GemmParams &p)
         w.Te = p.shared_tblocks > 1 ? min(p.T, w.tok0 + p.tok_block) : p.T;   // tokens [tok0, Te)
         w.R = p.Rs;
         w.K = p.Ks;
+        w.ldb = p.ldb_s;
+        w.ldo = p.ldo_s;
         const int per = (w.K / 32 + p.shared_splits - 1) / p.shared_splits;
         w.kbeg = (v % p.shared_splits) * per;
         w.ksteps = min(w.K / 32, w.kbeg + per) - w.kbeg;
@@ -116,7 +121,7 @@ __device__ __forceinline__ WorkItem resolve_expert(const GemmParams &p)
         w.out_base = p.T * p.k + v * p.T;
         Wbase = p.W_shared + (size_t)w.shared_s * ((size_t)w.R * w.K * (DUAL ? 2 : 1));
         // shared experts keep their h rows in their own region of the scratch
-        const size_t hbase = (size_t)p.shared_h_base + (size_t)w.shared_s * p.T * (DUAL ? w.R : w.K);
+        const size_t hbase = (size_t)p.shared_h_base + (size_t)w.shared_s * p.T * (DUAL ? w.ldo : w.ldb);
         if (DUAL)
             w.out = reinterpret_cast<uint16_t *>(p.out) + hbase;
         else
@@ -149,17 +154,17 @@ __device__ __forceinline__ void token_rows(const GemmParams &p, const WorkItem &
         const bool ok = pv >= 0 && pv < P;
         if (DUAL) {   // B row = x[token], out row = sorted position in h
             if (!ok) return;
-            ro = (pv / p.k) * w.K;
+            ro = (pv / p.k) * w.ldb;
             orow = w.off + i;
         } else {      // B row = h[sorted position] (known without the permutation), out row = pair id in o
-            ro = (w.off + i) * w.K;
+            ro = (w.off + i) * w.ldb;
             orow = ok ? pv : -1;
         }
     } else if (DUAL) {   // shared: every token
-        ro = i * w.K;
+        ro = i * w.ldb;
         orow = i;
     } else {
-        ro = i * w.K;
+        ro = i * w.ldb;
         orow = w.out_base + i;
     }
 }
@@ -188,7 +193,7 @@ __device__ __forceinline__ void clear_acc(f32x4 (&accg)[NT], f32x4 (&accu)[NT])
 // D fragment of v_mfma_f32_16x16x32: lane holds token column (lane & 15) and output rows
 // 4*(lane >> 4) .. +3 of the wave's 16.  gate/up: h = silu(g) * u rounded to bf16; down: fp32.
 template <bool DUAL, int NT>
-__device__ __forceinline__ void epilogue(const f32x4 (&accg)[NT], const f32x4 (&accu)[NT], void *out, int R, int row0,
+__device__ __forceinline__ void epilogue(const f32x4 (&accg)[NT], const f32x4 (&accu)[NT], void *out, int ld, int row0,
                                          const int (&orow)[NT])
 {
     const int r = row0 + 4 * (lane_id() >> 4);
@@ -201,9 +206,10 @@ __device__ __forceinline__ void epilogue(const f32x4 (&accg)[NT], const f32x4 (&
                    ((uint32_t)f32_to_bf16_rne(silu_mul(accg[nt][1], accu[nt][1])) << 16);
             pk.y = (uint32_t)f32_to_bf16_rne(silu_mul(accg[nt][2], accu[nt][2])) |
                    ((uint32_t)f32_to_bf16_rne(silu_mul(accg[nt][3], accu[nt][3])) << 16);
-            *reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(out) + (size_t)orow[nt] * R + r) = pk;
+            // read by the down-projection workgroups of the same launch, possibly on another XCD
+            store_coherent(reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(out) + (size_t)orow[nt] * ld + r), pk);
         } else {
-            *reinterpret_cast<float4 *>(reinterpret_cast<float *>(out) + (size_t)orow[nt] * R + r) =
+            *reinterpret_cast<float4 *>(reinterpret_cast<float *>(out) + (size_t)orow[nt] * ld + r) =
                 make_float4(accg[nt][0], accg[nt][1], accg[nt][2], accg[nt][3]);
         }
     }
@@ -224,6 +230,19 @@ __device__ __forceinline__ void epilogue(const f32x4 (&accg)[NT], const f32x4 (&
 __device__ __forceinline__ uint4 ring_load(const uint4 *__restrict__ base, int index)
 {
     asm volatile("" : "+v"(index));
+    return base[index];
+}
+
+// B operand (token rows).  For the down projection these are the intermediate vectors that gate/up workgroups
+// of the same launch have written with device-coherent stores.  Plain (cached) loads are right for them: caches
+// are invalidated when a kernel starts, a row is first touched after its expert's counter says it is complete,
+// and rows start on 128-byte lines, so no cache on the reading side can hold an older copy of a line.  (Device-
+// coherent loads instead would send every workgroup's re-reads of the same few rows to memory.)
+template <bool COH>
+__device__ __forceinline__ uint4 ring_load_b(const uint4 *__restrict__ base, int index)
+{
+    asm volatile("" : "+v"(index));
+    if (COH) return load_coherent(base + index);
     return base[index];
 }
 
@@ -286,7 +305,7 @@ __device__ __forceinline__ void prefetch_weights(const DirectPlan &d, WeightRing
 }
 
 // The ring arrives with its first turn of weight tiles already requested (prefetch_weights).
-template <int NT>
+template <int NT, bool COH>
 __device__ __forceinline__ void stream_direct(const DirectPlan &d, WeightRing &r, const uint4 *const (&brow)[NT],
                                               f32x4 (&acc0)[NT], f32x4 (&acc1)[NT])
 {
@@ -299,7 +318,7 @@ __device__ __forceinline__ void stream_direct(const DirectPlan &d, WeightRing &r
     for (int j = 0; j < kPFD; ++j) {
         const int s = min(j, last);
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) bb[j][nt] = ring_load(brow[nt], s * 4);
+        for (int nt = 0; nt < NT; ++nt) bb[j][nt] = ring_load_b<COH>(brow[nt], s * 4);
     }
     for (int s0 = 0; s0 < n; s0 += kPFD) {
 #pragma unroll
@@ -322,7 +341,7 @@ __device__ __forceinline__ void stream_direct(const DirectPlan &d, WeightRing &r
             r.w0[u] = ring_load_weights(Wl, sn * step);
             r.w1[u] = ring_load_weights(Wl, sn * step + second);
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) bb[u][nt] = ring_load(brow[nt], sn * 4);
+            for (int nt = 0; nt < NT; ++nt) bb[u][nt] = ring_load_b<COH>(brow[nt], sn * 4);
             __builtin_amdgcn_sched_barrier(0);
         }
     }
@@ -348,12 +367,16 @@ __device__ __forceinline__ void expert_direct(const GemmParams &p, const WorkIte
     for (int nt = 0; nt < NT; ++nt) {
         int ro;
         token_rows<DUAL>(p, w, nt * 16 + (lane & 15), ro, orow[nt]);
-        ro = max(ro, 0);   // columns without a token read row 0; their results are never stored
+        if (ro < 0) {   // columns without a token read the work item's first row (a row that is complete, which an
+            int none;   // arbitrary row of the intermediate vectors need not be); their results are never stored
+            token_rows<DUAL>(p, w, 0, ro, none);
+            ro = max(ro, 0);
+        }
         brow[nt] = reinterpret_cast<const uint4 *>(w.B + (size_t)ro + (size_t)kbc * 32 + (lane >> 4) * 8);
     }
     f32x4 acc0[NT], acc1[NT];
     clear_acc<NT>(acc0, acc1);
-    stream_direct<NT>(d, ring, brow, acc0, acc1);
+    stream_direct<NT, false>(d, ring, brow, acc0, acc1);
     if (KW > 1) {
         f32x4 *r4 = reinterpret_cast<f32x4 *>(red);   // [rw][kw-1][NACC][lane]
         if (kw > 0) {
@@ -379,10 +402,10 @@ __device__ __forceinline__ void expert_direct(const GemmParams &p, const WorkIte
     }
     if (kw == 0 && rows_ok) {
         if (DUAL) {
-            epilogue<true, NT>(acc0, acc1, w.out, w.R, rt * 16, orow);
+            epilogue<true, NT>(acc0, acc1, w.out, w.ldo, rt * 16, orow);
         } else {
-            epilogue<false, NT>(acc0, acc0, w.out, w.R, rt * 16, orow);
-            epilogue<false, NT>(acc1, acc1, w.out, w.R, rt * 16 + 16, orow);
+            epilogue<false, NT>(acc0, acc0, w.out, w.ldo, rt * 16, orow);
+            epilogue<false, NT>(acc1, acc1, w.out, w.ldo, rt * 16 + 16, orow);
         }
     }
 }
@@ -408,7 +431,7 @@ __device__ __forceinline__ void stream_staged(const uint4 *__restrict__ Wt, bool
     const int lastc = (KT + KS - 1) / KS - 1;
 
     // this thread's staging pieces: (token row, 16-byte piece inside the chunk)
-    int xoff[PPT];    // element offset of the piece in chunk 0 (rows without a token read row 0, zeroed below)
+    int xoff[PPT];    // element offset of the piece in chunk 0
     bool xok[PPT];
 #pragma unroll
     for (int i = 0; i < PPT; ++i) {
@@ -416,7 +439,7 @@ __device__ __forceinline__ void stream_staged(const uint4 *__restrict__ Wt, bool
         const int row = q / (KS * 4), pc = q % (KS * 4);
         const int ro = rowoff[row];
         xok[i] = ro >= 0;
-        xoff[i] = max(ro, 0) + pc * 8;
+        xoff[i] = (ro >= 0 ? ro : max(rowoff[0], 0)) + pc * 8;   // rows without a token: the pass's first row, zeroed below
     }
     const int pc0 = (tid % (KS * 4)) * 8;   // column of every piece of this thread inside a chunk (256 % (KS*4) == 0)
     uint4 xr[PPT];
@@ -498,23 +521,44 @@ __device__ __forceinline__ void expert_staged(const WorkItem &w, const int *rowo
     int orow[NT];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) orow[nt] = outrow[nt * 16 + (lane_id() & 15)];
-    epilogue<DUAL, NT>(accg, accu, w.out, w.R, rt * 16, orow);
+    epilogue<DUAL, NT>(accg, accu, w.out, w.ldo, rt * 16, orow);
 }
 
-// One launch per projection.  Grid: (routed expert rank, tile of 16*RW rows) + (shared expert, K slice,
-// tile), RW = 4 / KW.  An expert with at most kDirectMaxTokens tokens takes the direct path with the
-// workgroup's four waves as RW row tiles x KW slices of K.  A larger expert takes the staged path, in which
-// a workgroup covers 64 rows: of every KW consecutive workgroups one does the work, in passes of up to 64
-// tokens, and the others leave.
-template <bool DUAL, int KW, bool BIG>
-__global__ __launch_bounds__(kFfnThreads, 2) void expert_kernel(GemmParams p)
+// Both projections of every invoked and shared expert in ONE launch.  Grid: all gate/up workgroups, then
+// all down workgroups; per projection (shared expert, K slice, token block, row tile) items first, then
+// (routed expert rank, tile of 16*RW rows), RW = 4 / KW.  An expert with at most kDirectMaxTokens tokens
+// takes the direct path with the workgroup's four waves as RW row tiles x KW slices of K.  A larger expert
+// takes the staged path, in which a workgroup covers 64 rows: of every KW consecutive workgroups one does the
+// work, in passes of up to 64 (128) tokens, and the others leave.
+//
+// A down workgroup needs the intermediate vectors h of its expert complete.  Every gate/up workgroup adds one
+// to its expert's counter once its h stores have completed; a down workgroup requests its first weight tiles
+// and then waits for the counter.  Workgroups are dispatched in index order, so when a down workgroup runs,
+// every gate/up workgroup has been dispatched, and those wait for nothing: the wait always ends.  It is bounded
+// all the same (on running out it sets a flag in the workspace and goes on), so no wave can hang.  The gain:
+// the down projection's start-up overlaps the tail of gate/up instead of following a launch boundary.
+struct FfnParams {
+    GemmParams gu, dn;
+    int gu_blocks;
+    int block0;       // index of this launch's first workgroup in the (gate/up, down) order
+    int wait;         // 0: the down workgroups of this launch follow a finished gate/up launch and do not wait
+    int32_t *done;    // [LYNX_MAX_N] routed experts, then [n_shared * token blocks]; zero before the launch
+    int32_t *flags;
+};
+
+constexpr int kSpinLimit = 1 << 17;   // polls of a counter (about a microsecond each) before giving up
+
+__device__ __forceinline__ int done_slot(const GemmParams &p, const WorkItem &w)
 {
-    // staged token tile, or the K-slice partial sums
-    __shared__ __attribute__((aligned(16))) char stage[BIG ? kStageBytesBig : kStageBytes];
+    return w.shared_s < 0 ? w.e : LYNX_MAX_N + w.shared_s * p.shared_tblocks + w.tok0 / p.tok_block;
+}
+
+template <bool DUAL, int KW, bool BIG>
+__device__ __forceinline__ void expert_work(const GemmParams &p, int b, const FfnParams &fp, char *stage, int *rowoff,
+                                            int *outrow)
+{
     constexpr int TB = BIG ? kTokBlockBig : kTokBlock;   // tokens per pass
-    __shared__ int rowoff[TB];   // staged path: element offset of each token's B row, -1 = none
-    __shared__ int outrow[TB];   // staged path: output row of each token, -1 = none
-    WorkItem w = resolve_expert<DUAL>(p);
+    WorkItem w = resolve_expert<DUAL>(p, b);
     if (!w.valid) return;
     // The weight stream of the direct path starts before the token tables are read (their loads depend on
     // each other: offsets, then the permutation, then the token rows).
@@ -524,43 +568,84 @@ __global__ __launch_bounds__(kFfnThreads, 2) void expert_kernel(GemmParams p)
     if (!BIG) prefetch_weights(plan, ring);
     resolve_tokens(p, w);
     if (!w.valid) return;
+    int32_t *counter = fp.done + done_slot(p, w);
+    if (!DUAL && fp.wait) {   // wait for this expert's (this token block's) intermediate vectors
+        const int target = w.shared_s < 0 ? fp.gu.tiles_r : fp.gu.tiles_s;
+        if (threadIdx.x == 0) {
+            int polls = 0;
+            while (load_coherent(counter) < target) {
+                if (++polls > kSpinLimit) {
+                    atomicOr(fp.flags, 1);
+                    break;
+                }
+                __builtin_amdgcn_s_sleep(8);
+            }
+        }
+        __syncthreads();
+    }
     if (w.Te <= kDirectMaxTokens) {
         if (BIG) prefetch_weights(plan, ring);
         expert_direct<DUAL, 1, KW>(p, w, plan, ring, reinterpret_cast<float *>(stage));
-        return;
-    }
-    // staged path: units of 64 rows.  A direct workgroup covers 16*RW rows (gate/up) or 32*RW rows (down).
-    constexpr int kRowsPerWG = 16 * (kFfnWaves / KW) * (DUAL ? 1 : 2);
-    constexpr int kUnits = kRowsPerWG >= 64 ? kRowsPerWG / 64 : 1;      // staged units this workgroup does
-    constexpr int kShare = kRowsPerWG >= 64 ? 1 : 64 / kRowsPerWG;      // workgroups that share one unit
-    // (shared experts see every token, so the host knows that they are staged and gives them one workgroup
-    // per unit)
-    const bool shared = w.shared_s >= 0;
-    if (!shared && (w.tile % kShare) != 0) return;
-    const int unit0 = shared ? w.tile : (w.tile / kShare) * kUnits;
-    const int units = shared ? 1 : kUnits;
-    const int tid = threadIdx.x;
-    for (int un = 0; un < units; ++un) {
-        w.tile = unit0 + un;
-        if (w.tile * 64 >= w.R) break;
-        for (int i0 = w.tok0; i0 < w.Te; i0 += TB) {
-            const int nb = min(w.Te - i0, TB);
-            __syncthreads();   // the previous pass has read rowoff / outrow and the stage
-            if (tid < TB) {
-                int ro, orow;
-                token_rows<DUAL>(p, w, tid < nb ? i0 + tid : w.Te, ro, orow);
-                rowoff[tid] = ro;
-                outrow[tid] = orow;
+    } else {
+        // staged path: units of 64 rows.  A direct workgroup covers 16*RW rows (gate/up) or 32*RW rows (down).
+        constexpr int kRowsPerWG = 16 * (kFfnWaves / KW) * (DUAL ? 1 : 2);
+        constexpr int kUnits = kRowsPerWG >= 64 ? kRowsPerWG / 64 : 1;      // staged units this workgroup does
+        constexpr int kShare = kRowsPerWG >= 64 ? 1 : 64 / kRowsPerWG;      // workgroups that share one unit
+        static_assert(!DUAL || (kUnits == 1 && kShare == 1), "every gate/up workgroup must do work and report it");
+        // (shared experts see every token, so the host knows that they are staged and gives them one workgroup
+        // per unit)
+        const bool shared = w.shared_s >= 0;
+        if (!shared && (w.tile % kShare) != 0) return;
+        const int unit0 = shared ? w.tile : (w.tile / kShare) * kUnits;
+        const int units = shared ? 1 : kUnits;
+        const int tid = threadIdx.x;
+        for (int un = 0; un < units; ++un) {
+            w.tile = unit0 + un;
+            if (w.tile * 64 >= w.R) break;
+            for (int i0 = w.tok0; i0 < w.Te; i0 += TB) {
+                const int nb = min(w.Te - i0, TB);
+                __syncthreads();   // the previous pass has read rowoff / outrow and the stage
+                if (tid < TB) {
+                    int ro, orow;
+                    token_rows<DUAL>(p, w, tid < nb ? i0 + tid : w.Te, ro, orow);
+                    rowoff[tid] = ro;
+                    outrow[tid] = orow;
+                }
+                __syncthreads();
+                if (nb <= 32)
+                    expert_staged<DUAL, 2, 8>(w, rowoff, outrow, stage);
+                else if (!BIG || nb <= 64)
+                    expert_staged<DUAL, 4, 4>(w, rowoff, outrow, stage);
+                else
+                    expert_staged<DUAL, 8, 4>(w, rowoff, outrow, stage);
             }
-            __syncthreads();
-            if (nb <= 32)
-                expert_staged<DUAL, 2, 8>(w, rowoff, outrow, stage);
-            else if (!BIG || nb <= 64)
-                expert_staged<DUAL, 4, 4>(w, rowoff, outrow, stage);
-            else
-                expert_staged<DUAL, 8, 4>(w, rowoff, outrow, stage);
         }
     }
+    if (DUAL && fp.wait) {   // report: this workgroup's part of h is complete in memory
+        wait_memory_complete();
+        __syncthreads();
+        if (threadIdx.x == 0) atomicAdd(counter, 1);
+    }
+}
+
+template <int KWD, bool BIG>
+__global__ __launch_bounds__(kFfnThreads, 2) void ffn_kernel(FfnParams fp)
+{
+    // staged token tile, or the K-slice partial sums
+    __shared__ __attribute__((aligned(16))) char stage[BIG ? kStageBytesBig : kStageBytes];
+    __shared__ int rowoff[BIG ? kTokBlockBig : kTokBlock];   // staged path: element offset of each token's B row, -1 = none
+    __shared__ int outrow[BIG ? kTokBlockBig : kTokBlock];   // staged path: output row of each token, -1 = none
+    const int b = blockIdx.x + fp.block0;
+    if (b < fp.gu_blocks)
+        expert_work<true, 1, BIG>(fp.gu, b, fp, stage, rowoff, outrow);
+    else
+        expert_work<false, KWD, BIG>(fp.dn, b - fp.gu_blocks, fp, stage, rowoff, outrow);
+}
+
+__global__ __launch_bounds__(256) void clear_kernel(int32_t *p, int n)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < n) p[i] = 0;
 }
 
 // y[t] = sum_j gate[t,j] * o[t*k+j] + sum_s o[P + s*T + t]
@@ -657,42 +742,57 @@ constexpr int kWgPerCu = 2;
 constexpr int kLdsPerCu = 160 * 1024;
 constexpr int kLdsTargetPerWg = 56 * 1024;
 
-template <bool DUAL, int KW, bool BIG>
-static int launch_padded(const GemmParams &p, hipStream_t st)
+template <int KWD, bool BIG>
+static int launch_padded(const FfnParams &fp, unsigned blocks, hipStream_t st)
 {
     static_assert(kLdsTargetPerWg * (kWgPerCu + 1) > kLdsPerCu && kLdsTargetPerWg * kWgPerCu <= kLdsPerCu, "LDS pad");
     static int pad = -1;   // per instantiation
     if (pad < 0) {
         hipFuncAttributes attr;
-        if (hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(&expert_kernel<DUAL, KW, BIG>)) != hipSuccess)
+        if (hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(&ffn_kernel<KWD, BIG>)) != hipSuccess)
             return fail(LYNX_ERR_HIP, "lynx_moe_ffn: hipFuncGetAttributes failed");
         pad = max(0, kLdsTargetPerWg - (int)attr.sharedSizeBytes);
     }
-    hipLaunchKernelGGL((expert_kernel<DUAL, KW, BIG>), dim3(grid_blocks(p)), dim3(kFfnThreads), pad, st, p);
+    hipLaunchKernelGGL((ffn_kernel<KWD, BIG>), dim3(blocks), dim3(kFfnThreads), pad, st, fp);
     return LYNX_OK;
 }
 
-// One projection (gate/up or down) over all invoked and shared experts.  Batches of more than 64 tokens take
-// the kernels whose staged path makes passes of up to 128 tokens.
-template <bool DUAL>
-static int launch_projection(GemmParams p, hipStream_t st, const char *what)
+// One launch for both projections, or one each (the same kernel over its gate/up and its down workgroups)?
+// Measured over the benchmark configurations: with more than 16 tokens and experts of moderate size the single
+// launch is 3-12 % faster (the down projection fills the tail of gate/up and there is one start-up less); with
+// huge experts (hundreds of gate/up workgroups each, whose completion reports then cost more than the overlap
+// gains) or at most 16 tokens it is equal or slower.
+static bool single_launch(int T, int F) { return T > kDirectMaxTokens && (F + 63) / 64 <= 64; }
+
+// Gate/up and down over all invoked and shared experts.  Batches of more than 64 tokens take the
+// kernels whose staged path makes passes of up to 128 tokens.
+static int launch_ffn(FfnParams fp, hipStream_t st)
 {
-    const int max_experts = (int)min((long)p.N, (long)p.T * p.k) + p.n_shared;
-    const int kw = pick_k_waves(p.K, DUAL, p.T, max_experts);
-    set_tiles(p, 16 * (kFfnWaves / kw) * (DUAL ? 1 : 2));
-    const bool big = p.T > kTokBlock;
-    int rc;
-    if (DUAL)
-        rc = big ? launch_padded<true, 1, true>(p, st) : launch_padded<true, 1, false>(p, st);
-    else if (big)
-        rc = launch_padded<false, 2, true>(p, st);
-    else if (kw == 4)
-        rc = launch_padded<false, 4, false>(p, st);
-    else if (kw == 2)
-        rc = launch_padded<false, 2, false>(p, st);
-    else
-        rc = launch_padded<false, 1, false>(p, st);
-    return rc != LYNX_OK ? rc : check_launch(what);
+    const GemmParams &d = fp.dn;
+    const int max_experts = (int)min((long)d.N, (long)d.T * d.k) + d.n_shared;
+    const int kwd = pick_k_waves(d.K, false, d.T, max_experts);
+    set_tiles(fp.gu, 16 * kFfnWaves);                    // gate/up: four row tiles per workgroup
+    set_tiles(fp.dn, 16 * (kFfnWaves / kwd) * 2);
+    fp.gu_blocks = (int)grid_blocks(fp.gu);
+    const unsigned dn_blocks = grid_blocks(fp.dn);
+    const bool big = d.T > kTokBlock;
+    const bool single = single_launch(d.T, d.K);
+    int rc = LYNX_OK;
+    for (int part = 0; part < (single ? 1 : 2) && rc == LYNX_OK; ++part) {
+        fp.wait = single ? 1 : 0;
+        fp.block0 = part == 0 ? 0 : fp.gu_blocks;
+        const unsigned blocks = single ? (unsigned)fp.gu_blocks + dn_blocks : part == 0 ? (unsigned)fp.gu_blocks : dn_blocks;
+        if (big)
+            rc = launch_padded<2, true>(fp, blocks, st);
+        else if (kwd == 4)
+            rc = launch_padded<4, false>(fp, blocks, st);
+        else if (kwd == 2)
+            rc = launch_padded<2, false>(fp, blocks, st);
+        else
+            rc = launch_padded<1, false>(fp, blocks, st);
+        if (rc == LYNX_OK) rc = check_launch("lynx_moe_ffn(gate/up, down)");
+    }
+    return rc;
 }
 
 }  // namespace lynx
@@ -704,6 +804,8 @@ extern "C" size_t lynx_workspace_bytes(int T, int H, int F, int N, int k, int n_
     if (n_shared == 0) F_shared = 0;
     return lynx::workspace_layout(T, H, F, k, n_shared, F_shared, lynx::shared_down_splits(F, n_shared, F_shared)).total;
 }
+
+extern "C" int lynx_moe_ffn_launches(int T, int F) { return lynx::single_launch(T, F) ? 1 : 2; }
 
 extern "C" int lynx_pack_weights(const uint16_t *Wg, const uint16_t *Wu, const uint16_t *Wd, int E, int H, int F,
                                  uint16_t *Wgu_packed, uint16_t *Wd_packed, void *stream)
@@ -725,14 +827,16 @@ extern "C" int lynx_pack_weights(const uint16_t *Wg, const uint16_t *Wu, const u
     return check_launch("lynx_pack_weights(down)");
 }
 
-extern "C" int lynx_moe_ffn_timed(const uint16_t *x_bf16, const uint16_t *Wgu_packed, const uint16_t *Wd_packed,
-                                  const uint16_t *Sgu_packed, const uint16_t *Sd_packed, int n_shared, int F_shared,
-                                  const int32_t *idx, const float *gate, const int32_t *expert_offsets,
-                                  const int32_t *perm, const int32_t *active_experts, const int32_t *num_active, int T,
-                                  int H, int F, int N, int k, float *y, void *workspace, void *stream,
-                                  void *const *stage_events)
+namespace lynx {
+
+// counters_cleared: the caller has already had the completion counters in the workspace cleared on `stream`
+// (the fused layer path does it in its first kernel); otherwise a small launch clears them here.
+int moe_ffn_impl(const uint16_t *x_bf16, const uint16_t *Wgu_packed, const uint16_t *Wd_packed, const uint16_t *Sgu_packed,
+                 const uint16_t *Sd_packed, int n_shared, int F_shared, const int32_t *idx, const float *gate,
+                 const int32_t *expert_offsets, const int32_t *perm, const int32_t *active_experts,
+                 const int32_t *num_active, int T, int H, int F, int N, int k, float *y, void *workspace, void *stream,
+                 void *const *stage_events, bool counters_cleared)
 {
-    using namespace lynx;
     auto mark = [&](int i) -> int {
         if (!stage_events || !stage_events[i]) return LYNX_OK;
         const hipError_t err = hipEventRecord((hipEvent_t)stage_events[i], (hipStream_t)stream);
@@ -751,14 +855,30 @@ extern "C" int lynx_moe_ffn_timed(const uint16_t *x_bf16, const uint16_t *Wgu_pa
         !num_active || !y || !workspace)
         return fail(LYNX_ERR_INVALID_ARG, "lynx_moe_ffn: null pointer");
     if (n_shared == 0) F_shared = 0;
+    const int tok_block = T > kTokBlock ? kTokBlockBig : kTokBlock;
+    if (LYNX_MAX_N + (long)n_shared * ((T + tok_block - 1) / tok_block) > kWsDoneWords)
+        return fail(LYNX_ERR_UNSUPPORTED, "lynx_moe_ffn: too many shared experts for this batch size (n_shared=%d T=%d)",
+                    n_shared, T);
     const int splits = shared_down_splits(F, n_shared, F_shared);
     const Workspace ws = workspace_layout(T, H, F, k, n_shared, F_shared, splits);
     if (ws.h_elems >= 0x7fffffffull || ws.o_elems >= 0x7fffffffull * 4)
         return fail(LYNX_ERR_UNSUPPORTED, "lynx_moe_ffn: scratch index would overflow 32 bits");
     uint16_t *hbuf = reinterpret_cast<uint16_t *>(reinterpret_cast<char *>(workspace) + ws.h_off);
     float *obuf = reinterpret_cast<float *>(reinterpret_cast<char *>(workspace) + ws.o_off);
+    int32_t *rws = reinterpret_cast<int32_t *>(workspace);
     hipStream_t st = (hipStream_t)stream;
+    int rc;
+    if (!counters_cleared) {
+        hipLaunchKernelGGL(clear_kernel, dim3((kWsDoneWords + 16 + 255) / 256), dim3(256), 0, st, rws + kWsDone,
+                           kWsDoneWords + 16);
+        rc = check_launch("lynx_moe_ffn(clear)");
+        if (rc != LYNX_OK) return rc;
+    }
 
+    FfnParams fp;
+    fp.done = rws + kWsDone;
+    fp.flags = rws + kWsFlags;
+    fp.gu_blocks = 0;
     GemmParams p;
     p.offsets = expert_offsets;
     p.perm = perm;
@@ -769,8 +889,7 @@ extern "C" int lynx_moe_ffn_timed(const uint16_t *x_bf16, const uint16_t *Wgu_pa
     p.k = k;
     p.n_shared = n_shared;
     p.shared_splits = 1;
-    p.shared_h_base = (long long)T * k * F;
-
+    p.shared_h_base = (long long)T * k * h_stride(F);
     // gate/up: rows = F, contraction = H
     p.W_routed = Wgu_packed;
     p.W_shared = Sgu_packed;
@@ -780,13 +899,10 @@ extern "C" int lynx_moe_ffn_timed(const uint16_t *x_bf16, const uint16_t *Wgu_pa
     p.K = H;
     p.Rs = F_shared;
     p.Ks = H;
-    int rc = mark(0);
-    if (rc != LYNX_OK) return rc;
-    rc = launch_projection<true>(p, st, "lynx_moe_ffn(gate/up)");
-    if (rc != LYNX_OK) return rc;
-    rc = mark(1);
-    if (rc != LYNX_OK) return rc;
-
+    p.ldb_r = p.ldb_s = H;
+    p.ldo_r = h_stride(F);
+    p.ldo_s = h_stride(F_shared);
+    fp.gu = p;
     // down: rows = H, contraction = F
     p.W_routed = Wd_packed;
     p.W_shared = Sd_packed;
@@ -796,8 +912,16 @@ extern "C" int lynx_moe_ffn_timed(const uint16_t *x_bf16, const uint16_t *Wgu_pa
     p.K = F;
     p.Rs = H;
     p.Ks = F_shared;
+    p.ldb_r = h_stride(F);
+    p.ldb_s = h_stride(F_shared);
+    p.ldo_r = p.ldo_s = H;
     p.shared_splits = splits;
-    rc = launch_projection<false>(p, st, "lynx_moe_ffn(down)");
+    fp.dn = p;
+    rc = mark(0);
+    if (rc != LYNX_OK) return rc;
+    rc = launch_ffn(fp, st);
+    if (rc != LYNX_OK) return rc;
+    rc = mark(1);
     if (rc != LYNX_OK) return rc;
     rc = mark(2);
     if (rc != LYNX_OK) return rc;
@@ -807,6 +931,20 @@ extern "C" int lynx_moe_ffn_timed(const uint16_t *x_bf16, const uint16_t *Wgu_pa
     rc = check_launch("lynx_moe_ffn(combine)");
     if (rc != LYNX_OK) return rc;
     return mark(3);
+}
+
+}  // namespace lynx
+
+extern "C" int lynx_moe_ffn_timed(const uint16_t *x_bf16, const uint16_t *Wgu_packed, const uint16_t *Wd_packed,
+                                  const uint16_t *Sgu_packed, const uint16_t *Sd_packed, int n_shared, int F_shared,
+                                  const int32_t *idx, const float *gate, const int32_t *expert_offsets,
+                                  const int32_t *perm, const int32_t *active_experts, const int32_t *num_active, int T,
+                                  int H, int F, int N, int k, float *y, void *workspace, void *stream,
+                                  void *const *stage_events)
+{
+    return lynx::moe_ffn_impl(x_bf16, Wgu_packed, Wd_packed, Sgu_packed, Sd_packed, n_shared, F_shared, idx, gate,
+                              expert_offsets, perm, active_experts, num_active, T, H, F, N, k, y, workspace, stream,
+                              stage_events, false);
 }
 
 extern "C" int lynx_moe_ffn(const uint16_t *x_bf16, const uint16_t *Wgu_packed, const uint16_t *Wd_packed,

@@ -33,8 +33,8 @@ constexpr int kSmallThreads = 1024;   // single-workgroup path: 16 waves = 16 to
 constexpr int kSmallWaves = kSmallThreads / kWave;
 
 struct ZeroList {
-    int32_t *ptr[7];
-    int count[7];
+    int32_t *ptr[8];
+    int count[8];
     int n;
 };
 
@@ -732,6 +732,7 @@ int routing_fused(const uint16_t *x, const float *Wr, const float *bias, int T, 
     int32_t *ws = reinterpret_cast<int32_t *>(workspace);
     ZeroList z;
     z.n = 0;
+    add_zero(z, ws + kWsDone, kWsDoneWords + 16);   // the FFN's completion counters and flags
     if (T > kSmallT) {   // the logits kernel clears what the multi-workgroup kernels accumulate into
         add_zero(z, ws + kWsTickets, 16);
         add_zero(z, ws + kWsActive, N);

@@ -20,7 +20,7 @@ def _declared():
 def test_library_exports_every_declared_symbol():
     lib = L.lib()
     names = _declared()
-    assert set(names) == set(L.SYMBOLS) and len(names) == 11
+    assert set(names) == set(L.SYMBOLS) and len(names) == 12
     for n in names:
         assert getattr(lib, n) is not None
 
@@ -69,6 +69,7 @@ def test_argument_errors_are_reported_before_any_launch():
                             None) == -2
     assert lib.lynx_residual_add(one, one, 3, one, None) == -1       # odd length
     assert lib.lynx_residual_add(one, None, 4, one, None) == -1
+    assert lib.lynx_moe_ffn_launches(8, 14336) == 2 and lib.lynx_moe_ffn_launches(64, 768) == 1
     assert lib.lynx_read_probe(None, 32, 1, one, None) == -1
     assert lib.lynx_read_probe(one, 24, 1, one, None) == -1          # size not a multiple of 16
     assert lib.lynx_read_probe(one, 0, 1, one, None) == 0            # nothing to read

@@ -86,6 +86,8 @@ def _check_layer(L, lay, T, alpha, beta, enable, n_sample=5, seed=0):
     for key, got in (("offsets", b.offsets), ("perm", b.perm), ("active", b.active), ("num_active", b.num_active_perm)):
         assert np.array_equal(host(got), p[key]), key
     # properties on the whole batch
+    from paper_2411_08982_amd.binding import WAIT_FLAG_WORD
+    assert int(b.workspace.view(torch.int32)[WAIT_FLAG_WORD]) == 0, "a workgroup gave up waiting for its expert's gate/up results"
     y = host(b.y)
     assert np.all(np.isfinite(y))
     np.testing.assert_allclose(g.sum(1), 1.0, rtol=1e-5)
@@ -157,6 +159,8 @@ def test_edge_sizes(L, T, N, k, H, F, S, Fs):
     for alpha, beta in ((4.0, 1), (1.0, 3)):
         b = L.lynx_moe_layer(x, Wr, bias, Wgu, Wdp, F, k, alpha, beta, 1, Sgu, Sdp, S, Fs)
         torch.cuda.synchronize()
+        from paper_2411_08982_amd.binding import WAIT_FLAG_WORD
+        assert int(b.workspace.view(torch.int32)[WAIT_FLAG_WORD]) == 0
         z = host(b.logits)
         r = oracle.route(d["x"], d["Wr"], d["bias"], k)
         assert np.all(np.abs(z - r["logits"]) <= LOGIT_TOL * np.maximum(1.0, np.abs(r["logits"])))
