@@ -65,15 +65,27 @@ __device__ __forceinline__ void permute_from_bitsets(Shared &sh, const int32_t *
         }
     }
     __syncthreads();
-    for (int p = tid; p < P; p += THREADS) {
-        const int e = load_coherent(idx + p);   // in the fused kernel another workgroup of this launch wrote it
-        if (e < 0 || e >= N) continue;
-        const int t = p / k;
-        int pos = sh.offs[e];
-        const int wt = t >> 5;
-        for (int w = 0; w < wt; ++w) pos += __popc(sh.member[e * W + w]);
-        pos += __popc(sh.member[e * W + wt] & ((1u << (t & 31)) - 1u));
-        perm[pos] = p;   // pos < offs[N] <= P by construction
+    // (the indices are read with device-coherent loads: in the fused kernel another workgroup of this launch
+    // wrote them; such loads go to memory, so several are requested before the first is used)
+    constexpr int kBatch = 8;
+    for (int p0 = tid; p0 < P; p0 += THREADS * kBatch) {
+        int ev[kBatch];
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+            const int p = p0 + u * THREADS;
+            ev[u] = p < P ? load_coherent(idx + p) : -1;
+        }
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+            const int p = p0 + u * THREADS, e = ev[u];
+            if (e < 0 || e >= N) continue;
+            const int t = p / k;
+            int pos = sh.offs[e];
+            const int wt = t >> 5;
+            for (int w = 0; w < wt; ++w) pos += __popc(sh.member[e * W + w]);
+            pos += __popc(sh.member[e * W + wt] & ((1u << (t & 31)) - 1u));
+            perm[pos] = p;   // pos < offs[N] <= P by construction
+        }
     }
     for (int e = tid; e <= N; e += THREADS) expert_offsets[e] = sh.offs[e];
     const int na = sh.arank[N];

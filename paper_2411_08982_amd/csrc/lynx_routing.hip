@@ -31,6 +31,7 @@ constexpr int kTokThreads = 256;   // multi-workgroup token kernels: 4 waves = 4
 constexpr int kTokWaves = kTokThreads / kWave;
 constexpr int kSmallThreads = 1024;   // single-workgroup path: 16 waves = 16 tokens
 constexpr int kSmallWaves = kSmallThreads / kWave;
+constexpr int kLogitsMfmaMinT = 128;   // larger batches compute the logits on the fp32 matrix cores (measured crossover)
 
 struct ZeroList {
     int32_t *ptr[8];
@@ -131,6 +132,85 @@ __global__ __launch_bounds__(256) void logits_kernel(const uint16_t *__restrict_
         float zv = keep;
         if (bias) zv += bias[e];
         logits[(size_t)(t0 + tok) * N + e] = zv;
+    }
+}
+
+// The same for larger batches on the fp32 matrix cores: one workgroup per 16 tokens x 16 experts, its four
+// waves split H and are summed in a fixed order through LDS.  v_mfma_f32_16x16x4_f32 takes fp32 operands
+// (x is exact in fp32) and accumulates in fp32.  A = x (lane l: token l%16, k group l/16), B = Wr (lane l:
+// expert l%16, k group l/16), D: lane l holds expert l%16 for tokens 4*(l/16) .. +3.  A k-step is 32 columns:
+// a lane loads the 8 consecutive columns of its k group (16 bytes of x, 32 bytes of Wr) and the j-th of its
+// 8 values goes into the j-th of 8 MFMAs (any assignment of columns to MFMAs is right as long as A and B
+// agree).  Against the 4 x 4 output tiles of logits_kernel this reads 4 times less through L2; its lanes read 16
+// rows at once, which costs latency, so it only pays for large batches (about 10 us at any size; logits_kernel:
+// 6 us at 32 tokens, 26 us at 512).
+typedef float logits_f32x4 __attribute__((ext_vector_type(4)));
+constexpr int kLogitsRing = 4;    // k-steps in flight per wave
+constexpr int kLogitsWaves = 4;   // waves of a workgroup, splitting H
+
+struct LogitsStep {
+    uint4 xv;
+    float4 w0, w1;
+};
+
+__device__ __forceinline__ LogitsStep logits_load(const uint16_t *__restrict__ xrow, const float *__restrict__ wrow, int step)
+{
+    asm volatile("" : "+v"(step));   // keeps the prefetch ring: see the weight ring of the expert kernels
+    LogitsStep r;
+    r.xv = *reinterpret_cast<const uint4 *>(xrow + step * 32);
+    r.w0 = *reinterpret_cast<const float4 *>(wrow + step * 32);
+    r.w1 = *reinterpret_cast<const float4 *>(wrow + step * 32 + 4);
+    return r;
+}
+
+__global__ __launch_bounds__(kLogitsWaves * kWave) void logits_mfma_kernel(const uint16_t *__restrict__ x, const float *__restrict__ Wr,
+                                                          const float *__restrict__ bias, int T, int H, int N,
+                                                          float *__restrict__ logits, ZeroList z)
+{
+    __shared__ logits_f32x4 part[kLogitsWaves - 1][kWave];
+    const int tid = threadIdx.x, lane = lane_id(), wave = wave_id();
+    zero_slices(z, blockIdx.y * gridDim.x + blockIdx.x, gridDim.x * gridDim.y, tid, kLogitsWaves * kWave);
+    const int t0 = blockIdx.x * 16, e0 = blockIdx.y * 16;
+    const int KT = H / 32;                                   // k-steps; wave w takes [kb, kb + n)
+    const int per = (KT + kLogitsWaves - 1) / kLogitsWaves;
+    const int kb = min(wave * per, KT), n = min(KT, kb + per) - kb;
+    const int kbc = n > 0 ? kb : 0, last = max(n, 1) - 1;
+    // rows past the end re-read the last row; their results are not stored
+    const uint16_t *xrow = x + (size_t)min(t0 + (lane & 15), T - 1) * H + kbc * 32 + (lane >> 4) * 8;
+    const float *wrow = Wr + (size_t)min(e0 + (lane & 15), N - 1) * H + kbc * 32 + (lane >> 4) * 8;
+    logits_f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    LogitsStep ring[kLogitsRing];
+#pragma unroll
+    for (int j = 0; j < kLogitsRing; ++j) ring[j] = logits_load(xrow, wrow, min(j, last));
+    for (int s0 = 0; s0 < n; s0 += kLogitsRing) {
+#pragma unroll
+        for (int u = 0; u < kLogitsRing; ++u) {
+            const int s = s0 + u;
+            const bool live = s < n;
+            const LogitsStep c = ring[u];
+            const float a[8] = {bf16_lo(c.xv.x), bf16_hi(c.xv.x), bf16_lo(c.xv.y), bf16_hi(c.xv.y),
+                                bf16_lo(c.xv.z), bf16_hi(c.xv.z), bf16_lo(c.xv.w), bf16_hi(c.xv.w)};
+            const float b[8] = {c.w0.x, c.w0.y, c.w0.z, c.w0.w, c.w1.x, c.w1.y, c.w1.z, c.w1.w};
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(live ? a[j] : 0.f, b[j], acc, 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            ring[u] = logits_load(xrow, wrow, min(s + kLogitsRing, last));
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    if (wave > 0) part[wave - 1][lane] = acc;
+    __syncthreads();
+    if (wave != 0) return;
+#pragma unroll
+    for (int w = 0; w < kLogitsWaves - 1; ++w) acc += part[w][lane];   // fixed order
+    const int e = e0 + (lane & 15);
+    if (e >= N) return;
+    const float bv = bias ? bias[e] : 0.f;
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+        const int t = t0 + 4 * (lane >> 4) + v;
+        if (t < T) logits[(size_t)t * N + e] = acc[v] + bv;
     }
 }
 
@@ -614,7 +694,20 @@ __global__ __launch_bounds__(kTokThreads) void remap_kernel(const float *__restr
     if (tid < N && load_coherent(&cnt_after[tid]) > 0) atomicAdd(&sh.n_after, 1);
     if constexpr (DO_PERMUTE) {
         const unsigned *member = reinterpret_cast<const unsigned *>(ws + kWsMember);
-        for (int i = tid; i < N * W; i += kTokThreads) sh.perm.member[i] = load_coherent(&member[i]);
+        constexpr int kBatch = 8;   // device-coherent loads go to memory: request several before using the first
+        for (int i0 = tid; i0 < N * W; i0 += kTokThreads * kBatch) {
+            unsigned mv[kBatch];
+#pragma unroll
+            for (int u = 0; u < kBatch; ++u) {
+                const int i = i0 + u * kTokThreads;
+                mv[u] = i < N * W ? load_coherent(&member[i]) : 0u;
+            }
+#pragma unroll
+            for (int u = 0; u < kBatch; ++u) {
+                const int i = i0 + u * kTokThreads;
+                if (i < N * W) sh.perm.member[i] = mv[u];
+            }
+        }
     }
     __syncthreads();
     if (tid == 0) num_active[1] = sh.n_after;
@@ -655,8 +748,12 @@ static void add_zero(ZeroList &z, int32_t *p, int count)
 static void launch_logits(const uint16_t *x, const float *Wr, const float *bias, int T, int H, int N, float *logits,
                           const ZeroList &z, hipStream_t st)
 {
-    hipLaunchKernelGGL(logits_kernel, dim3((T + kRouteTT - 1) / kRouteTT, (N + 3) / 4), dim3(256), 0, st, x, Wr, bias, T,
-                       H, N, logits, z);
+    if (T > kLogitsMfmaMinT)
+        hipLaunchKernelGGL(logits_mfma_kernel, dim3((T + 15) / 16, (N + 15) / 16), dim3(kLogitsWaves * kWave), 0, st, x, Wr, bias, T, H, N,
+                           logits, z);
+    else
+        hipLaunchKernelGGL(logits_kernel, dim3((T + kRouteTT - 1) / kRouteTT, (N + 3) / 4), dim3(256), 0, st, x, Wr, bias,
+                           T, H, N, logits, z);
 }
 
 // Everything after the logits.  DO_TOPK: compute the top-k (else topk_idx is an input); DO_PERMUTE: also
