@@ -13,6 +13,7 @@ namespace lynx {
 template <int MAXW>   // capacity in 32-token words per expert
 struct PermuteSharedT {
     unsigned member[LYNX_MAX_N * MAXW];   // member[e*W + w] bit b: token 32*w+b uses expert e
+    uint16_t before[LYNX_MAX_N * MAXW];   // before[e*W + w] = tokens of expert e in the words below w
     int count[LYNX_MAX_N];
     int offs[LYNX_MAX_N + 1];
     int arank[LYNX_MAX_N + 1];
@@ -32,7 +33,10 @@ __device__ __forceinline__ void permute_from_bitsets(Shared &sh, const int32_t *
     const int P = T * k;
     if (tid < N) {
         int c = 0;
-        for (int w = 0; w < W; ++w) c += __popc(sh.member[tid * W + w]);
+        for (int w = 0; w < W; ++w) {
+            sh.before[tid * W + w] = (uint16_t)c;
+            c += __popc(sh.member[tid * W + w]);
+        }
         sh.count[tid] = c;
     }
     __syncthreads();
@@ -80,10 +84,8 @@ __device__ __forceinline__ void permute_from_bitsets(Shared &sh, const int32_t *
             const int p = p0 + u * THREADS, e = ev[u];
             if (e < 0 || e >= N) continue;
             const int t = p / k;
-            int pos = sh.offs[e];
             const int wt = t >> 5;
-            for (int w = 0; w < wt; ++w) pos += __popc(sh.member[e * W + w]);
-            pos += __popc(sh.member[e * W + wt] & ((1u << (t & 31)) - 1u));
+            const int pos = sh.offs[e] + sh.before[e * W + wt] + __popc(sh.member[e * W + wt] & ((1u << (t & 31)) - 1u));
             perm[pos] = p;   // pos < offs[N] <= P by construction
         }
     }
