@@ -46,10 +46,13 @@ def _load():
         lib.orc_topk.argtypes = [f32p, c_int, c_int, c_int, i32p, f64p, f64p]
         lib.orc_affinity_bin.argtypes = [f32p, i32p, c_int, c_int, c_int, c_float, c_int, c_int, i32p, f64p, i32p,
                                          i32p, i32p, i32p, i32p, u64p, i32p]
+        lib.orc_affinity_bin_biased.argtypes = [f32p, i32p, c_int, c_int, c_int, c_float, c_int, c_float, c_int, i32p,
+                                                f64p, i32p, i32p, i32p, i32p, f32p]
         lib.orc_permute.argtypes = [i32p, c_int, c_int, c_int, i32p, i32p, i32p, i32p]
         lib.orc_moe_ffn.argtypes = [u16p, u16p, u16p, u16p, u16p, u16p, u16p, c_int, c_int, i32p, f64p, c_int, c_int,
                                     c_int, c_int, c_int, f64p]
-        for f in (lib.orc_route, lib.orc_topk, lib.orc_affinity_bin, lib.orc_permute, lib.orc_moe_ffn):
+        for f in (lib.orc_route, lib.orc_topk, lib.orc_affinity_bin, lib.orc_affinity_bin_biased, lib.orc_permute,
+                  lib.orc_moe_ffn):
             f.restype = c_int
         _lib = lib
     return _lib
@@ -136,6 +139,32 @@ def affinity_bin(logits, topk_idx, alpha, beta, enable=1):
         raise OracleError(rc, "orc_affinity_bin")
     return dict(new_idx=new_idx, new_gate=new_gate, cnt_before=cnt_before, cnt_after=cnt_after, bin_hist=bin_hist,
                 num_active=num_active, q=q, score=score, active=active)
+
+
+def affinity_bin_biased(logits, topk_idx, alpha, beta, gamma, enable=1):
+    """Score-biased selection (the variant of Sec. 3.3.1 that adds the batch score to the logits).  Returns dict
+    with new_idx, new_gate (f64), cnt_before, cnt_after, bin_hist [N,beta], num_active [2], bias [N] (f32)."""
+    z = _arr(logits, np.float32)
+    idx = _arr(topk_idx, np.int32)
+    T, N = z.shape
+    k = idx.shape[1]
+    assert idx.shape[0] == T
+    nb = max(int(beta), 1)
+    new_idx = np.zeros((T, k), np.int32)
+    new_gate = np.zeros((T, k), np.float64)
+    cnt_before = np.zeros((N,), np.int32)
+    cnt_after = np.zeros((N,), np.int32)
+    bin_hist = np.zeros((N, nb), np.int32)
+    num_active = np.zeros((2,), np.int32)
+    bias = np.zeros((N,), np.float32)
+    rc = _load().orc_affinity_bin_biased(_p(z, c_float), _p(idx, c_int32), T, N, k, float(alpha), int(beta), float(gamma),
+                                         int(enable), _p(new_idx, c_int32), _p(new_gate, c_double),
+                                         _p(cnt_before, c_int32), _p(cnt_after, c_int32), _p(bin_hist, c_int32),
+                                         _p(num_active, c_int32), _p(bias, c_float))
+    if rc != OK:
+        raise OracleError(rc, "orc_affinity_bin_biased")
+    return dict(new_idx=new_idx, new_gate=new_gate, cnt_before=cnt_before, cnt_after=cnt_after, bin_hist=bin_hist,
+                num_active=num_active, bias=bias)
 
 
 def permute(idx, N):

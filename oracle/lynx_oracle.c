@@ -287,6 +287,94 @@ int orc_affinity_bin(const float *logits, const int32_t *topk_idx, int T, int N,
 }
 
 /*
+ * Score-biased selection, the literal reading of Sec. 3.3.1 ("a weighted score is added to its router logit
+ * based on how frequently other tokens in the batch preferred it"), as a variant of orc_affinity_bin:
+ * bins, histogram and base-T scores exactly as there; then, instead of nominations and an active set,
+ *   s_e    = score_e / T^beta                 in [0, 1] (fp64 division, rounded once to fp32),
+ *   z'[t,e] = z[t,e] + gamma * s_e            (one fp32 multiply, one fp32 add),
+ * and every token keeps its top-ranked expert (Sec. 3.3.1: high-confidence tokens are always mapped to their
+ * top-ranked expert) and takes for its other k-1 slots the experts of largest z' among those the batch already
+ * invokes (Sec. 1: redirected to experts the batch is already activating), equal z' to the lower index.
+ * Gates: softmax over the selected ORIGINAL logits.  gamma = 0 reproduces the unchanged selection.
+ * bias_out [N] (optional) receives gamma * s_e.
+ */
+int orc_affinity_bin_biased(const float *logits, const int32_t *topk_idx, int T, int N, int k, float alpha, int beta,
+                            float gamma, int enable, int32_t *new_idx, double *new_gate, int32_t *cnt_before,
+                            int32_t *cnt_after, int32_t *bin_hist, int32_t *num_active, float *bias_out)
+{
+    if (T < 0 || N <= 0 || k <= 0 || beta < 1 || !(alpha >= 0.0f) || isinf(alpha) || !(gamma >= 0.0f) || isinf(gamma))
+        return ORC_ERR_INVALID_ARG;
+    if (k > N || beta > ORC_MAX_BETA) return ORC_ERR_UNSUPPORTED;
+    double tpow = 1.0; /* T^beta, by repeated multiplication */
+    for (int j = 0; j < beta; ++j) tpow *= (double)(T > 1 ? T : 1);
+    if (tpow >= 4611686018427387904.0) return ORC_ERR_UNSUPPORTED;
+    for (int t = 0; t < T; ++t)
+        for (int j = 0; j < k; ++j) {
+            int32_t e = topk_idx[(size_t)t * k + j];
+            if (e < 0 || e >= N) return ORC_ERR_INVALID_ARG;
+            for (int i = 0; i < j; ++i)
+                if (topk_idx[(size_t)t * k + i] == e) return ORC_ERR_INVALID_ARG;
+        }
+    uint8_t *allowed = (uint8_t *)calloc((size_t)N, 1);
+    float *bias = (float *)calloc((size_t)N, sizeof(float));
+    float *zb = (float *)malloc(sizeof(float) * (size_t)N);
+
+    memset(bin_hist, 0, sizeof(int32_t) * (size_t)N * beta);
+    memset(cnt_before, 0, sizeof(int32_t) * (size_t)N);
+    memset(cnt_after, 0, sizeof(int32_t) * (size_t)N);
+    for (int t = 0; t < T; ++t) {
+        const float *z = logits + (size_t)t * N;
+        float zmax = z[0];
+        for (int e = 1; e < N; ++e)
+            if (z[e] > zmax) zmax = z[e];
+        for (int e = 0; e < N; ++e) {
+            volatile float d = zmax - z[e];
+            volatile float scaled = alpha * d;
+            float qf = floorf(scaled);
+            if (qf < (float)beta) bin_hist[(size_t)e * beta + (int32_t)qf] += 1;
+        }
+        for (int j = 0; j < k; ++j) cnt_before[topk_idx[(size_t)t * k + j]] += 1;
+    }
+    int nU = 0;
+    for (int e = 0; e < N; ++e) nU += cnt_before[e] > 0;
+    for (int e = 0; e < N; ++e) {
+        uint64_t sc = 0;
+        for (int j = 0; j < beta; ++j) sc = sc * (uint64_t)T + (uint64_t)bin_hist[(size_t)e * beta + j];
+        volatile float se = (float)((double)sc / tpow);
+        volatile float b = gamma * se;
+        bias[e] = b;
+    }
+    const int bypass = !enable || T <= 1;
+    for (int t = 0; t < T; ++t) {
+        const float *z = logits + (size_t)t * N;
+        int32_t *sel = new_idx + (size_t)t * k;
+        if (bypass) {
+            for (int j = 0; j < k; ++j) sel[j] = topk_idx[(size_t)t * k + j];
+        } else {
+            const int32_t top = topk_idx[(size_t)t * k];
+            sel[0] = top;
+            for (int e = 0; e < N; ++e) {
+                allowed[e] = cnt_before[e] > 0 && e != top;
+                volatile float v = z[e] + bias[e];
+                zb[e] = v;
+            }
+            if (k > 1) topk_select(zb, allowed, N, k - 1, sel + 1);
+        }
+        gates_of_selection(z, sel, k, new_gate + (size_t)t * k);
+        for (int j = 0; j < k; ++j) cnt_after[sel[j]] += 1;
+    }
+    int nAfter = 0;
+    for (int e = 0; e < N; ++e) nAfter += cnt_after[e] > 0;
+    num_active[0] = nU;
+    num_active[1] = nAfter;
+    if (bias_out) memcpy(bias_out, bias, sizeof(float) * (size_t)N);
+    free(allowed);
+    free(bias);
+    free(zb);
+    return ORC_OK;
+}
+
+/*
  * Token assignment (Sec. 4): per-expert pair counts, exclusive offsets by expert id, and the list
  * of (token, slot) pairs t*k+slot grouped by expert, ascending in t then slot inside an expert.
  * active_experts holds the invoked expert ids ascending; entries past num_active are -1.
