@@ -42,6 +42,8 @@ def parse():
     ap.add_argument("--sweep-iters", type=int, default=10)
     ap.add_argument("--layers", type=int, default=0,
                     help="resident copies of the expert weights that successive steps cycle over (0 = enough for 4 GiB)")
+    ap.add_argument("--biased-gamma", type=float, default=4.0,
+                    help="bias strength of the score-biased selection variant in the sweep (0 = leave it out)")
     ap.add_argument("--stack", type=int, default=0,
                     help="time a chained stack of this many layers (own router and weights each, x <- bf16(x + y) between "
                          "them) as a whole, eagerly and as one HIP graph, instead of the single-layer benchmark")
@@ -341,6 +343,41 @@ def main():
                               "expert_weight_GBps": round((g + d_) / (us * 1e-6) / 1e9, 1),
                               "hbm_frac": round((g + d_) / (us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4)})
         out["sweep"] = sweep
+        if args.biased_gamma > 0:
+            # the score-biased selection variant (logit + gamma * normalised batch score), through the separate calls
+            # lynx_route -> lynx_affinity_bin_biased -> lynx_permute -> lynx_moe_ffn (more launches than the fused layer)
+            L = layer.L
+            a_, b_ = wl.PRESETS["moderate"]
+            var = []
+            for Ts in cfg.batches:
+                x = layer.tokens(Ts)
+                r = L.lynx_route(x, layer.Wr, layer.bias, cfg.k)
+                ab = L.lynx_affinity_bin_biased(r["logits"], r["idx"], a_, b_, args.biased_gamma, 1)
+                pm = L.lynx_permute(ab["new_idx"], cfg.N)
+                ws = L.new_workspace(Ts, cfg.H, cfg.F, cfg.N, cfg.k, cfg.n_shared, cfg.F_shared)
+                y = torch.empty((Ts, cfg.H), dtype=torch.float32, device="cuda")
+
+                def step_biased(i):
+                    Wgu, Wdp, Sgu, Sdp = layer.weights[i % len(layer.weights)]
+                    L.lynx_route(x, layer.Wr, layer.bias, cfg.k, out=r)
+                    L.lynx_affinity_bin_biased(r["logits"], r["idx"], a_, b_, args.biased_gamma, 1, workspace=ws, out=ab)
+                    L.lynx_permute(ab["new_idx"], cfg.N, out=pm)
+                    L.lynx_moe_ffn(x, Wgu, Wdp, ab["new_idx"], ab["new_gate"], pm, cfg.N, cfg.F, Sgu, Sdp, cfg.n_shared,
+                                   cfg.F_shared, workspace=ws, y=y)
+                for i in range(3):
+                    step_biased(i)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                torch.cuda.synchronize()
+                e0.record()
+                for i in range(args.sweep_iters):
+                    step_biased(i)
+                e1.record()
+                torch.cuda.synchronize()
+                us = e0.elapsed_time(e1) * 1e3 / args.sweep_iters
+                nb, na = (int(v) for v in ab["num_active"].cpu().tolist())
+                var.append({"tokens": Ts, "gamma": args.biased_gamma, "alpha": a_, "beta": b_, "us": round(us, 1),
+                            "invoked_before": nb, "invoked_after": na})
+            out["sweep_score_biased_variant"] = var
 
     if not args.no_cpu_baseline:
         import numpy as np

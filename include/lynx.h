@@ -86,6 +86,20 @@ int lynx_affinity_bin(const float *logits, const int32_t *topk_idx, int T, int N
                       int32_t *bin_hist, int32_t *num_active, void *workspace, void *stream);
 
 /*
+ * Score-biased selection: the variant of the adaptive expert scorer that takes Sec. 3.3.1's sentence "a
+ * weighted score is added to its router logit" literally.  Bins, histogram and base-T scores exactly as in
+ * lynx_affinity_bin; then bias[e] = gamma * score[e] / T^beta (score / T^beta in [0,1]: one fp64 division
+ * rounded to fp32, one fp32 multiply), and every token keeps its top-ranked expert (Sec. 3.3.1) and fills
+ * its other k-1 slots with the experts of largest logit + bias (one fp32 addition) among those the batch
+ * already invokes (Sec. 1), equal values to the lower index.  Gates: softmax over the selected ORIGINAL
+ * logits.  gamma >= 0, finite; gamma = 0 or enable = 0 or T <= 1 leaves the selection unchanged.  Other
+ * arguments, outputs and the workspace as in lynx_affinity_bin; composes with lynx_permute and lynx_moe_ffn.
+ */
+int lynx_affinity_bin_biased(const float *logits, const int32_t *topk_idx, int T, int N, int k, float alpha, int beta,
+                             float gamma, int enable, int32_t *new_idx, float *new_gate, int32_t *cnt_before,
+                             int32_t *cnt_after, int32_t *bin_hist, int32_t *num_active, void *workspace, void *stream);
+
+/*
  * Token assignment (Sec. 4): expert_offsets [N+1] int32 out = exclusive prefix of pairs per expert;
  * perm [T*k] int32 out = pair ids t*k+slot grouped by expert ascending, ascending inside an expert;
  * active_experts [N] int32 out = invoked expert ids ascending, -1 past num_active; num_active [1] out.

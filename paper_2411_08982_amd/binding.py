@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "liblynx.so")
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_HIP = 0, -1, -2, -3
 MAX_T, MAX_N, MAX_K, MAX_BETA = 1024, 256, 16, 6
 
-SYMBOLS = ["lynx_last_error", "lynx_workspace_bytes", "lynx_route", "lynx_affinity_bin", "lynx_permute",
+SYMBOLS = ["lynx_last_error", "lynx_workspace_bytes", "lynx_route", "lynx_affinity_bin", "lynx_affinity_bin_biased", "lynx_permute",
            "lynx_pack_weights", "lynx_moe_ffn", "lynx_moe_ffn_timed", "lynx_moe_layer", "lynx_moe_ffn_launches", "lynx_residual_add", "lynx_read_probe"]
 
 
@@ -47,6 +47,7 @@ def lib():
         L.lynx_workspace_bytes.argtypes = [I] * 7
         L.lynx_route.argtypes = [P, P, P, I, I, I, I, P, P, P, P, P]
         L.lynx_affinity_bin.argtypes = [P, P, I, I, I, F, I, I, P, P, P, P, P, P, P, P]
+        L.lynx_affinity_bin_biased.argtypes = [P, P, I, I, I, F, I, F, I, P, P, P, P, P, P, P, P]
         L.lynx_permute.argtypes = [P, I, I, I, P, P, P, P, P]
         L.lynx_pack_weights.argtypes = [P, P, P, I, I, I, P, P, P]
         L.lynx_moe_ffn.argtypes = [P, P, P, P, P, I, I, P, P, P, P, P, P, I, I, I, I, I, P, P, P]
@@ -126,6 +127,26 @@ def lynx_affinity_bin(logits, topk_idx, alpha, beta, enable=1, workspace=None, o
                                    _ptr(o["new_gate"], F32, "new_gate"), _ptr(o["cnt_before"], I32, "cnt_before"),
                                    _ptr(o["cnt_after"], I32, "cnt_after"), _ptr(o["bin_hist"], I32, "bin_hist"),
                                    _ptr(o["num_active"], I32, "num_active"), ws, _stream()))
+    return o
+
+
+def lynx_affinity_bin_biased(logits, topk_idx, alpha, beta, gamma, enable=1, workspace=None, out=None):
+    """Score-biased selection variant; arguments and result as lynx_affinity_bin plus the bias strength gamma."""
+    T, N = logits.shape
+    k = topk_idx.shape[1]
+    dev = logits.device
+    nb = max(int(beta), 1)
+    o = out or dict(new_idx=torch.empty((T, k), dtype=I32, device=dev), new_gate=torch.empty((T, k), dtype=F32, device=dev),
+                    cnt_before=torch.empty((N,), dtype=I32, device=dev), cnt_after=torch.empty((N,), dtype=I32, device=dev),
+                    bin_hist=torch.empty((N, nb), dtype=I32, device=dev), num_active=torch.empty((2,), dtype=I32, device=dev))
+    if workspace is None:
+        workspace = torch.empty(65536, dtype=torch.uint8, device=dev)
+    _check(lib().lynx_affinity_bin_biased(_ptr(logits, F32, "logits"), _ptr(topk_idx, I32, "topk_idx"), T, N, k,
+                                          float(alpha), int(beta), float(gamma), int(enable),
+                                          _ptr(o["new_idx"], I32, "new_idx"), _ptr(o["new_gate"], F32, "new_gate"),
+                                          _ptr(o["cnt_before"], I32, "cnt_before"), _ptr(o["cnt_after"], I32, "cnt_after"),
+                                          _ptr(o["bin_hist"], I32, "bin_hist"), _ptr(o["num_active"], I32, "num_active"),
+                                          workspace.data_ptr(), _stream()))
     return o
 
 

@@ -716,6 +716,92 @@ __global__ __launch_bounds__(kTokThreads) void remap_kernel(const float *__restr
                                           num_active_perm);
 }
 
+// ---- score-biased selection (the variant of Sec. 3.3.1 that adds the batch score to the logits) ------------------
+
+// Every workgroup first turns the finished histogram into the bias gamma * score / T^beta (one fp64 division
+// rounded to fp32, one fp32 multiply), then every wave selects for its token: the top-ranked expert stays, the
+// other k-1 slots go to the invoked experts of largest logit + bias; gates from the original logits.  The last
+// workgroup to finish counts the invoked experts before and after.
+template <int NS>
+__global__ __launch_bounds__(kTokThreads) void biased_remap_kernel(const float *__restrict__ logits,
+                                                                   const int32_t *__restrict__ topk_idx,
+                                                                   const int32_t *__restrict__ cnt_before,
+                                                                   const int32_t *__restrict__ bin_hist, int T, int N,
+                                                                   int k, int beta, float gamma, double tpow, int bypass,
+                                                                   int32_t *__restrict__ ws, int32_t *__restrict__ new_idx,
+                                                                   float *__restrict__ new_gate,
+                                                                   int32_t *__restrict__ cnt_after,
+                                                                   int32_t *__restrict__ num_active)
+{
+    __shared__ float bias[LYNX_MAX_N];
+    __shared__ int inU[LYNX_MAX_N];
+    __shared__ int cnta[LYNX_MAX_N];
+    __shared__ int counts[2];
+    __shared__ int flag;
+    const int tid = threadIdx.x, lane = lane_id(), wave = wave_id();
+    const int t = blockIdx.x * kTokWaves + wave;
+    const TokenLogits<NS> tl = load_token<NS>(logits + (size_t)(t < T ? t : 0) * N, N);
+    if (tid < N) {
+        unsigned long long sc = 0;
+        for (int j = 0; j < beta; ++j) sc = sc * (unsigned long long)T + (unsigned long long)bin_hist[tid * beta + j];
+        const float se = __double2float_rn(__ddiv_rn((double)sc, tpow));
+        bias[tid] = __fmul_rn(gamma, se);
+        inU[tid] = cnt_before[tid] > 0;
+        cnta[tid] = 0;
+    }
+    if (tid < 2) counts[tid] = 0;
+    __syncthreads();
+    if (t < T) {
+        int mye = -1;
+        float myz = -INFINITY;
+        const int es = (lane < k) ? topk_idx[(size_t)t * k + lane] : -1;   // the token's own picks, rank order
+        const bool ok = es >= 0 && es < N;
+        const float zs = logit_of(tl, ok ? es : 0);
+        if (bypass) {
+            if (ok) {
+                mye = es;
+                myz = zs;
+            }
+        } else {
+            const int top = __shfl(ok ? es : -1, 0, kWave);
+            if (lane == 0 && ok) {
+                mye = es;
+                myz = zs;
+            }
+            float zb[NS];
+            unsigned cand = 0;
+#pragma unroll
+            for (int i = 0; i < NS; ++i) {
+                const int e = lane + kWave * i;
+                const bool have = (tl.have >> i) & 1u;
+                zb[i] = have ? __fadd_rn(tl.v[i], bias[e]) : -INFINITY;
+                if (have && inU[e] && e != top) cand |= 1u << i;
+            }
+            wave_topk(zb, cand, k - 1, [&](int j, int e, float) {
+                if (lane == j + 1) mye = (e == INT_MAX) ? -1 : e;
+            });
+            const float zo = logit_of(tl, mye >= 0 ? mye : 0);   // gates come from the original logits
+            if (lane > 0 && mye >= 0) myz = zo;
+        }
+        float num, zref;
+        const float g = selection_gate(k, mye, myz, num, zref);
+        if (lane < k) {
+            new_idx[(size_t)t * k + lane] = mye;
+            new_gate[(size_t)t * k + lane] = g;
+            if (mye >= 0) atomicAdd(&cnta[mye], 1);
+        }
+    }
+    __syncthreads();
+    if (tid < N && cnta[tid]) atomicAdd(&cnt_after[tid], cnta[tid]);
+    if (!last_workgroup(ws + kWsTickets + 3, &flag)) return;
+    if (tid < N) {
+        if (inU[tid]) atomicAdd(&counts[0], 1);
+        if (load_coherent(&cnt_after[tid]) > 0) atomicAdd(&counts[1], 1);
+    }
+    __syncthreads();
+    if (tid < 2) num_active[tid] = counts[tid];
+}
+
 static int check_routing_sizes(const char *who, int T, int N, int k)
 {
     if (T < 0 || N <= 0 || k <= 0) return fail(LYNX_ERR_INVALID_ARG, "%s: negative or zero size (T=%d N=%d k=%d)", who, T, N, k);
@@ -847,6 +933,57 @@ int routing_fused(const uint16_t *x, const float *Wr, const float *bias, int T, 
 }
 
 }  // namespace lynx
+
+extern "C" int lynx_affinity_bin_biased(const float *logits, const int32_t *topk_idx, int T, int N, int k, float alpha,
+                                        int beta, float gamma, int enable, int32_t *new_idx, float *new_gate,
+                                        int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist,
+                                        int32_t *num_active, void *workspace, void *stream)
+{
+    using namespace lynx;
+    int rc = check_routing_sizes("lynx_affinity_bin_biased", T, N, k);
+    if (rc != LYNX_OK) return rc;
+    rc = check_bin_params("lynx_affinity_bin_biased", T, alpha, beta);
+    if (rc != LYNX_OK) return rc;
+    if (!(gamma >= 0.0f) || gamma > 3.0e38f)
+        return fail(LYNX_ERR_INVALID_ARG, "lynx_affinity_bin_biased: gamma must be finite and >= 0 (gamma=%g)", (double)gamma);
+    if (!cnt_before || !cnt_after || !bin_hist || !num_active || !workspace)
+        return fail(LYNX_ERR_INVALID_ARG, "lynx_affinity_bin_biased: null output or workspace pointer");
+    if (T > 0 && (!logits || !topk_idx || !new_idx || !new_gate))
+        return fail(LYNX_ERR_INVALID_ARG, "lynx_affinity_bin_biased: null pointer");
+    hipStream_t st = (hipStream_t)stream;
+    int32_t *ws = reinterpret_cast<int32_t *>(workspace);
+    ZeroList z;
+    z.n = 0;
+    add_zero(z, ws + kWsTickets, 16);
+    add_zero(z, bin_hist, N * beta);
+    add_zero(z, cnt_before, N);
+    add_zero(z, cnt_after, N);
+    add_zero(z, num_active, 2);
+    hipLaunchKernelGGL(zero_kernel, dim3(4), dim3(256), 0, st, z);
+    rc = check_launch("lynx_affinity_bin_biased(clear)");
+    if (rc != LYNX_OK || T == 0) return rc;
+    double tpow = 1.0;   // T^beta by repeated multiplication (below 2^62: checked above)
+    for (int j = 0; j < beta; ++j) tpow *= (double)(T > 1 ? T : 1);
+    const int bypass = (!enable || T <= 1) ? 1 : 0;
+    const dim3 tgrid((T + kTokWaves - 1) / kTokWaves), tblock(kTokThreads);
+#define LYNX_BIASED(NS)                                                                                                 \
+    do {                                                                                                                \
+        hipLaunchKernelGGL((token_kernel<NS, false, true>), tgrid, tblock, 0, st, logits, T, N, k, alpha, beta,         \
+                           const_cast<int32_t *>(topk_idx), nullptr, nullptr, bin_hist, cnt_before);                    \
+        rc = check_launch("lynx_affinity_bin_biased(bins)");                                                            \
+        if (rc != LYNX_OK) return rc;                                                                                   \
+        hipLaunchKernelGGL((biased_remap_kernel<NS>), tgrid, tblock, 0, st, logits, topk_idx, cnt_before, bin_hist, T,  \
+                           N, k, beta, gamma, tpow, bypass, ws, new_idx, new_gate, cnt_after, num_active);              \
+    } while (0)
+    if (N <= kWave)
+        LYNX_BIASED(1);
+    else if (N <= 2 * kWave)
+        LYNX_BIASED(2);
+    else
+        LYNX_BIASED(4);
+#undef LYNX_BIASED
+    return check_launch("lynx_affinity_bin_biased(select)");
+}
 
 extern "C" int lynx_route(const uint16_t *x_bf16, const float *Wr, const float *bias, int T, int H, int N, int k,
                           float *logits, int32_t *topk_idx, float *topk_gate, float *topk_psum, void *stream)

@@ -20,7 +20,7 @@ def _declared():
 def test_library_exports_every_declared_symbol():
     lib = L.lib()
     names = _declared()
-    assert set(names) == set(L.SYMBOLS) and len(names) == 12
+    assert set(names) == set(L.SYMBOLS) and len(names) == 13
     for n in names:
         assert getattr(lib, n) is not None
 
@@ -60,6 +60,9 @@ def test_argument_errors_are_reported_before_any_launch():
     assert ab(4, 8, 2, float("inf"), 2) == -1
     assert ab(4, 8, 2, 1.0, 7) == -2
     assert ab(4, 300, 2, 1.0, 2) == -2
+    abb = lambda gamma: lib.lynx_affinity_bin_biased(one, one, 4, 8, 2, ctypes.c_float(2.0), 2, ctypes.c_float(gamma), 1,
+                                                     one, one, one, one, one, one, None, None)
+    assert abb(-1.0) == -1 and abb(float("nan")) == -1 and abb(float("inf")) == -1
     assert lib.lynx_permute(one, 4, 8, 9, one, one, one, one, None) == -2
     assert lib.lynx_permute(one, 4, 0, 1, one, one, one, one, None) == -1
     assert lib.lynx_pack_weights(one, one, one, 2, 48, 64, one, one, None) == -2

@@ -123,6 +123,49 @@ def test_affinity_bin_is_deterministic(L):
             assert np.array_equal(host(again[key]), v), key
 
 
+@pytest.mark.parametrize("T,N,k,s,tail", BIN_CASES)
+def test_affinity_bin_biased(L, T, N, k, s, tail):
+    """Score-biased selection variant: every integer output bit-exact, gates within tolerance."""
+    for alpha, beta, gamma in [(2.0, 2, 1.0), (4.0, 1, 0.5), (1.0, 3, 4.0), (0.5, 6, 0.0), (2.0, 2, 1.0e6)]:
+        if T ** beta >= 2 ** 62:
+            continue
+        for seed, quantum in [(0, None), (1, 0.25)]:               # quantised logits: exact ties in logit + bias
+            _say(f"affinity_bin_biased T={T} N={N} k={k} alpha={alpha} beta={beta} gamma={gamma} seed={seed} q={quantum}")
+            z = wl.make_logits(T, N, seed=seed * 100 + T, zipf_s=s, tail_frac=tail, quantum=quantum)
+            idx = oracle.topk(z, k)["idx"]
+            ref = oracle.affinity_bin_biased(z, idx, alpha, beta, gamma, 1)
+            out = L.lynx_affinity_bin_biased(dev(z), dev(idx), alpha, beta, gamma, 1)
+            torch.cuda.synchronize()
+            for key in ("new_idx", "cnt_before", "cnt_after", "bin_hist", "num_active"):
+                assert np.array_equal(host(out[key]), ref[key]), key
+            np.testing.assert_allclose(host(out["new_gate"]), ref["new_gate"], rtol=GATE_TOL, atol=1e-7)
+    z = wl.make_logits(T, N, seed=3, zipf_s=s, tail_frac=tail)
+    idx = oracle.topk(z, k)["idx"]
+    out = L.lynx_affinity_bin_biased(dev(z), dev(idx), 2.0, 2, 3.0, 0)   # bypass
+    torch.cuda.synchronize()
+    assert np.array_equal(host(out["new_idx"]), idx)
+
+
+def test_biased_selection_through_the_ffn(L):
+    """The variant composes with lynx_permute and lynx_moe_ffn: whole layer against the oracle."""
+    cfg = wl.CONFIGS["tiny"]
+    T = 40
+    d = wl.make_layer(cfg, T)
+    x, Wr, bias = to_bf16_dev(d["x"]), dev(d["Wr"]), dev(d["bias"])
+    r = L.lynx_route(x, Wr, bias, cfg.k)
+    a = L.lynx_affinity_bin_biased(r["logits"], r["idx"], 2.0, 2, 2.0, 1)
+    p = L.lynx_permute(a["new_idx"], cfg.N)
+    Wgu, Wdp = L.lynx_pack_weights(to_bf16_dev(d["Wg"]), to_bf16_dev(d["Wu"]), to_bf16_dev(d["Wd"]))
+    y = L.lynx_moe_ffn(x, Wgu, Wdp, a["new_idx"], a["new_gate"], p, cfg.N, cfg.F)
+    torch.cuda.synchronize()
+    z = host(r["logits"])
+    ra = oracle.affinity_bin_biased(z, oracle.topk(z, cfg.k)["idx"], 2.0, 2, 2.0, 1)
+    assert np.array_equal(host(a["new_idx"]), ra["new_idx"])
+    assert ra["num_active"][1] <= ra["num_active"][0]
+    y_ref = oracle.moe_ffn(d["x"], d["Wg"], d["Wu"], d["Wd"], ra["new_idx"], ra["new_gate"])
+    assert row_rel_err(host(y), y_ref).max() <= Y_TOL
+
+
 # ------------------------------------------------------------------------------------------------ permute
 
 @pytest.mark.parametrize("T,N,k,seed", [(1, 4, 2, 0), (16, 8, 2, 1), (37, 60, 4, 2), (128, 128, 8, 3), (512, 128, 8, 4),
