@@ -51,6 +51,16 @@ def _load():
         lib.orc_permute.argtypes = [i32p, c_int, c_int, c_int, i32p, i32p, i32p, i32p]
         lib.orc_moe_ffn.argtypes = [u16p, u16p, u16p, u16p, u16p, u16p, u16p, c_int, c_int, i32p, f64p, c_int, c_int,
                                     c_int, c_int, c_int, f64p]
+        u8p = POINTER(ctypes.c_uint8)
+        lib.orc_e4m3_decode.argtypes = [ctypes.c_uint8]
+        lib.orc_e4m3_decode.restype = c_double
+        lib.orc_e4m3_encode.argtypes = [c_float]
+        lib.orc_e4m3_encode.restype = ctypes.c_uint8
+        lib.orc_quantize_rows_e4m3.argtypes = [u16p, ctypes.c_long, c_int, u8p, f32p]
+        lib.orc_quantize_rows_e4m3.restype = c_int
+        lib.orc_moe_ffn_q8.argtypes = [u16p, u8p, u8p, u8p, f32p, f32p, f32p, u8p, u8p, u8p, f32p, f32p, f32p, c_int, c_int,
+                                       i32p, f64p, c_int, c_int, c_int, c_int, c_int, f64p]
+        lib.orc_moe_ffn_q8.restype = c_int
         for f in (lib.orc_route, lib.orc_topk, lib.orc_affinity_bin, lib.orc_affinity_bin_biased, lib.orc_permute,
                   lib.orc_moe_ffn):
             f.restype = c_int
@@ -217,3 +227,57 @@ def moe_layer(x_bf16, Wr, bias, Wg, Wu, Wd, k, alpha, beta, enable=1, Sg=None, S
     p = permute(a["new_idx"], Wr.shape[0])
     y = moe_ffn(x_bf16, Wg, Wu, Wd, a["new_idx"], a["new_gate"], Sg, Su, Sd)
     return dict(route=r, bin=a, permute=p, y=y)
+
+
+# ---- expert weights in FP8 E4M3, weight-only ------------------------------------------------------------------------
+
+def e4m3_decode(codes):
+    """uint8 codes (any shape) -> float64 values (NaN for the two NaN codes)."""
+    c = np.ascontiguousarray(codes, dtype=np.uint8)
+    lib = _load()
+    return np.array([lib.orc_e4m3_decode(int(v)) for v in c.ravel()], np.float64).reshape(c.shape)
+
+
+def e4m3_encode(values):
+    """float32 values (any shape) -> nearest E4M3 codes (ties to even, saturating at +-448)."""
+    v = np.ascontiguousarray(values, dtype=np.float32)
+    lib = _load()
+    return np.array([lib.orc_e4m3_encode(float(x)) for x in v.ravel()], np.uint8).reshape(v.shape)
+
+
+def quantize_rows_e4m3(W_bf16):
+    """bf16 bits [..., K] -> (codes uint8 [..., K], scales float32 [...]): one scale per row, scale = amax / 448."""
+    W = _arr(W_bf16, np.uint16)
+    K = W.shape[-1]
+    rows = W.size // K
+    codes = np.zeros(W.shape, np.uint8)
+    scales = np.zeros(W.shape[:-1], np.float32)
+    rc = _load().orc_quantize_rows_e4m3(_p(W, c_uint16), rows, K, codes.ctypes.data_as(POINTER(ctypes.c_uint8)),
+                                        _p(scales, c_float))
+    if rc != OK:
+        raise OracleError(rc, "orc_quantize_rows_e4m3")
+    return codes, scales
+
+
+def moe_ffn_q8(x_bf16, Qg, Qu, Qd, sg, su, sd, idx, gate, SQg=None, SQu=None, SQd=None, ssg=None, ssu=None, ssd=None):
+    """moe_ffn with E4M3 weights: codes Qg, Qu [N,F,H], Qd [N,H,F] and scales sg, su [N,F], sd [N,H] (shared likewise)."""
+    x = _arr(x_bf16, np.uint16)
+    T, H = x.shape
+    N, F, _ = Qg.shape
+    idx = _arr(idx, np.int32)
+    k = idx.shape[1]
+    gate = _arr(gate, np.float64)
+    u8 = lambda a: None if a is None else np.ascontiguousarray(a, dtype=np.uint8)
+    f32 = lambda a: None if a is None else np.ascontiguousarray(a, dtype=np.float32)
+    Qg, Qu, Qd, SQg, SQu, SQd = (u8(a) for a in (Qg, Qu, Qd, SQg, SQu, SQd))
+    sg, su, sd, ssg, ssu, ssd = (f32(a) for a in (sg, su, sd, ssg, ssu, ssd))
+    n_shared, F_shared = (0, 0) if SQg is None else (SQg.shape[0], SQg.shape[1])
+    pu8 = lambda a: None if a is None else a.ctypes.data_as(POINTER(ctypes.c_uint8))
+    pf = lambda a: None if a is None else _p(a, c_float)
+    y = np.zeros((T, H), np.float64)
+    rc = _load().orc_moe_ffn_q8(_p(x, c_uint16), pu8(Qg), pu8(Qu), pu8(Qd), pf(sg), pf(su), pf(sd), pu8(SQg), pu8(SQu),
+                                pu8(SQd), pf(ssg), pf(ssu), pf(ssd), n_shared, F_shared, _p(idx, c_int32),
+                                _p(gate, c_double), T, H, F, N, k, _p(y, c_double))
+    if rc != OK:
+        raise OracleError(rc, "orc_moe_ffn_q8")
+    return y

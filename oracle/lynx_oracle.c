@@ -502,3 +502,168 @@ int orc_moe_ffn(const uint16_t *x_bf16, const uint16_t *Wg, const uint16_t *Wu, 
     free(xs);
     return ORC_OK;
 }
+
+/* ------------------------------------------------------------------------------------------------------------
+ * Expert weights in 8-bit floating point, weight-only (activations stay bf16): a widening beyond the paper's
+ * bf16 runs (its Sec. 5 shows the method is additive to weight quantisation).  Format: OCP FP8 E4M3 (1 sign,
+ * 4 exponent bits with bias 7, 3 mantissa bits, subnormals, no infinities, S.1111.111 = NaN, largest finite
+ * value 448), one fp32 scale per weight-matrix row.
+ * ------------------------------------------------------------------------------------------------------------ */
+
+/* Value of an E4M3 code. */
+double orc_e4m3_decode(uint8_t c)
+{
+    const int sgn = c >> 7, e = (c >> 3) & 15, m = c & 7;
+    double v;
+    if (e == 15 && m == 7) return NAN;
+    if (e == 0)
+        v = ldexp((double)m, -9); /* subnormal: m/8 * 2^-6 */
+    else
+        v = ldexp(1.0 + (double)m / 8.0, e - 7);
+    return sgn ? -v : v;
+}
+
+/* Nearest E4M3 code of v, ties to the even code, magnitudes of 448 and above to +-448, NaN to NaN. */
+uint8_t orc_e4m3_encode(float v)
+{
+    const uint8_t sgn = signbit(v) ? 0x80 : 0x00;
+    if (isnan(v)) return (uint8_t)(sgn | 0x7f);
+    const double a = fabs((double)v);
+    if (a >= 448.0) return (uint8_t)(sgn | 0x7e);
+    int code;
+    if (a < ldexp(1.0, -6)) {
+        code = (int)rint(ldexp(a, 9)); /* multiples of 2^-9; 8 is the smallest normal */
+    } else {
+        int e;
+        const double fr = frexp(a, &e); /* a = fr * 2^e, fr in [0.5, 1) */
+        const int ex = e - 1;           /* a = (2 fr) * 2^ex, 2 fr in [1, 2) */
+        int q = (int)rint((2.0 * fr - 1.0) * 8.0);
+        code = ((ex + 7) << 3) + q;     /* q = 8 carries into the exponent */
+    }
+    if (code > 0x7e) code = 0x7e;
+    return (uint8_t)(sgn | code);
+}
+
+/*
+ * Row-wise quantisation of bf16 weights W [rows, K]: scale = amax / 448 (one fp32 division; 1 for an all-zero
+ * row), code = encode(w / scale) (one fp32 division).  The dequantised weight is decode(code) * scale.
+ */
+int orc_quantize_rows_e4m3(const uint16_t *W_bf16, long rows, int K, uint8_t *codes, float *scales)
+{
+    if (rows < 0 || K <= 0) return ORC_ERR_INVALID_ARG;
+    for (long r = 0; r < rows; ++r) {
+        const uint16_t *w = W_bf16 + (size_t)r * K;
+        float amax = 0.0f;
+        for (int i = 0; i < K; ++i) {
+            const float a = fabsf((float)bf16_to_f64(w[i]));
+            if (a > amax) amax = a;
+        }
+        volatile float sc = amax / 448.0f;
+        if (amax == 0.0f) sc = 1.0f;
+        scales[r] = sc;
+        for (int i = 0; i < K; ++i) {
+            volatile float q = (float)bf16_to_f64(w[i]) / sc;
+            codes[(size_t)r * K + i] = orc_e4m3_encode(q);
+        }
+    }
+    return ORC_OK;
+}
+
+/* swiglu_ffn with quantised weights: rows of codes with one scale each. */
+static void swiglu_ffn_q8(const uint8_t *Qg, const uint8_t *Qu, const uint8_t *Qd, const float *sg, const float *su,
+                          const float *sd, int H, int F, const double *xs, const int32_t *tok, int ntok, double *out)
+{
+    double *hbuf = (double *)malloc(sizeof(double) * (size_t)ntok * F);
+#pragma omp parallel
+    {
+        double *row = (double *)malloc(sizeof(double) * (size_t)(H > F ? H : F) * 2);
+        double *rowg = row, *rowu = row + (H > F ? H : F);
+#pragma omp for schedule(static)
+        for (int f = 0; f < F; ++f) {
+            for (int h = 0; h < H; ++h) {
+                rowg[h] = orc_e4m3_decode(Qg[(size_t)f * H + h]);
+                rowu[h] = orc_e4m3_decode(Qu[(size_t)f * H + h]);
+            }
+            for (int i = 0; i < ntok; ++i) {
+                const double *x = xs + (size_t)tok[i] * H;
+                double a = 0.0, b = 0.0;
+                for (int h = 0; h < H; ++h) {
+                    a += rowg[h] * x[h];
+                    b += rowu[h] * x[h];
+                }
+                a *= (double)sg[f];
+                b *= (double)su[f];
+                hbuf[(size_t)i * F + f] = (a / (1.0 + exp(-a))) * b;
+            }
+        }
+#pragma omp for schedule(static)
+        for (int r = 0; r < H; ++r) {
+            for (int f = 0; f < F; ++f) rowg[f] = orc_e4m3_decode(Qd[(size_t)r * F + f]);
+            for (int i = 0; i < ntok; ++i) {
+                const double *hv = hbuf + (size_t)i * F;
+                double o = 0.0;
+                for (int f = 0; f < F; ++f) o += rowg[f] * hv[f];
+                out[(size_t)i * H + r] = o * (double)sd[r];
+            }
+        }
+        free(row);
+    }
+    free(hbuf);
+}
+
+/*
+ * orc_moe_ffn with E4M3 weights: Qg, Qu [N,F,H], Qd [N,H,F] codes; sg, su [N,F], sd [N,H] scales; shared
+ * experts likewise (SQ*, ss*).  Everything else as orc_moe_ffn.
+ */
+int orc_moe_ffn_q8(const uint16_t *x_bf16, const uint8_t *Qg, const uint8_t *Qu, const uint8_t *Qd, const float *sg,
+                   const float *su, const float *sd, const uint8_t *SQg, const uint8_t *SQu, const uint8_t *SQd,
+                   const float *ssg, const float *ssu, const float *ssd, int n_shared, int F_shared, const int32_t *idx,
+                   const double *gate, int T, int H, int F, int N, int k, double *y)
+{
+    if (T < 0 || H <= 0 || F <= 0 || N <= 0 || k <= 0 || n_shared < 0) return ORC_ERR_INVALID_ARG;
+    if (n_shared > 0 && (F_shared <= 0 || !SQg || !SQu || !SQd || !ssg || !ssu || !ssd)) return ORC_ERR_INVALID_ARG;
+    for (int i = 0; i < T * k; ++i)
+        if (idx[i] < 0 || idx[i] >= N) return ORC_ERR_INVALID_ARG;
+    if (T == 0) return ORC_OK;
+    double *xs = (double *)malloc(sizeof(double) * (size_t)T * H);
+    for (size_t i = 0; i < (size_t)T * H; ++i) xs[i] = bf16_to_f64(x_bf16[i]);
+    for (size_t i = 0; i < (size_t)T * H; ++i) y[i] = 0.0;
+    int32_t *tok = (int32_t *)malloc(sizeof(int32_t) * (size_t)T);
+    int32_t *slot = (int32_t *)malloc(sizeof(int32_t) * (size_t)T);
+    double *out = (double *)malloc(sizeof(double) * (size_t)T * H);
+    double *o = (double *)calloc((size_t)T * k * H, sizeof(double));
+    for (int e = 0; e < N; ++e) {
+        int n = 0;
+        for (int t = 0; t < T; ++t)
+            for (int j = 0; j < k; ++j)
+                if (idx[(size_t)t * k + j] == e) {
+                    tok[n] = t;
+                    slot[n] = j;
+                    ++n;
+                }
+        if (n == 0) continue;
+        swiglu_ffn_q8(Qg + (size_t)e * F * H, Qu + (size_t)e * F * H, Qd + (size_t)e * H * F, sg + (size_t)e * F,
+                      su + (size_t)e * F, sd + (size_t)e * H, H, F, xs, tok, n, out);
+        for (int i = 0; i < n; ++i)
+            memcpy(o + ((size_t)tok[i] * k + slot[i]) * H, out + (size_t)i * H, sizeof(double) * (size_t)H);
+    }
+    for (int t = 0; t < T; ++t)
+        for (int j = 0; j < k; ++j) {
+            double g = gate[(size_t)t * k + j];
+            const double *oj = o + ((size_t)t * k + j) * H;
+            for (int h = 0; h < H; ++h) y[(size_t)t * H + h] += g * oj[h];
+        }
+    for (int t = 0; t < T; ++t) tok[t] = t;
+    for (int s = 0; s < n_shared; ++s) {
+        swiglu_ffn_q8(SQg + (size_t)s * F_shared * H, SQu + (size_t)s * F_shared * H, SQd + (size_t)s * H * F_shared,
+                      ssg + (size_t)s * F_shared, ssu + (size_t)s * F_shared, ssd + (size_t)s * H, H, F_shared, xs, tok,
+                      T, out);
+        for (size_t i = 0; i < (size_t)T * H; ++i) y[i] += out[i];
+    }
+    free(o);
+    free(out);
+    free(slot);
+    free(tok);
+    free(xs);
+    return ORC_OK;
+}
