@@ -39,6 +39,7 @@ def parse():
     ap.add_argument("--preset", default="aggressive", choices=["moderate", "aggressive", "off"])
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-fp8", action="store_true", help="skip the FP8-weight variant of the same workload")
     ap.add_argument("--sweep-iters", type=int, default=10)
     ap.add_argument("--layers", type=int, default=0,
                     help="resident copies of the expert weights that successive steps cycle over (0 = enough for 4 GiB)")
@@ -378,6 +379,44 @@ def main():
                 var.append({"tokens": Ts, "gamma": args.biased_gamma, "alpha": a_, "beta": b_, "us": round(us, 1),
                             "invoked_before": nb, "invoked_after": na})
             out["sweep_score_biased_variant"] = var
+
+    if not args.no_fp8:
+        # The same workload with the expert weights in FP8 E4M3 (weight-only, row scales): a widening beyond the
+        # bf16 metric above, reported beside it and never as `value`.
+        L = layer.L
+        import workloads as wl2
+        q8 = []
+        for l in range(n_layers):
+            d = wl2.make_layer_device(cfg, 1, "cuda", layer=l)
+            q = L.lynx_quantize_weights_fp8(d["Wg"], d["Wu"], d["Wd"])
+            sh = L.lynx_quantize_weights_fp8(d["Sg"], d["Su"], d["Sd"]) if cfg.n_shared else None
+            torch.cuda.synchronize()
+            q8.append((q, sh))
+            del d
+        buf = layer.buffers(T, beta)
+
+        def step8(i, events=None):
+            q, sh = q8[i % n_layers]
+            return L.lynx_moe_layer_fp8(layer.tokens(T), layer.Wr, layer.bias, q, cfg.F, cfg.k, alpha, beta, enable, sh,
+                                        cfg.n_shared, cfg.F_shared, buffers=buf, stage_events=events)
+        for i in range(W):
+            step8(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(K):
+            step8(i)
+        torch.cuda.synchronize()
+        us8 = (time.perf_counter() - t0) * 1e6 / K
+        for i in range(K):
+            step8(i, events[i][:4])
+        torch.cuda.synchronize()
+        ffn8_ms = sum(e[0].elapsed_time(e[1]) for e in events) / K
+        out["fp8_weights"] = {"us_per_batch": round(us8, 2), "expert_ffn_us": round(ffn8_ms * 1e3, 2),
+                              "weight_bytes": ffn_bytes // 2, "expert_weight_GBps": round(ffn_bytes / 2 / (ffn8_ms * 1e-3) / 1e9, 1),
+                              "hbm_frac": round(ffn_bytes / 2 / (ffn8_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                              "speedup_vs_bf16": round(ms_per_step * 1e3 / us8, 3),
+                              "format": "OCP FP8 E4M3 codes + one fp32 scale per weight row; activations bf16"}
+        del q8
 
     if not args.no_cpu_baseline:
         import numpy as np

@@ -172,6 +172,43 @@ int lynx_moe_layer(const uint16_t *x_bf16, const float *Wr, const float *bias, c
                    void *workspace, void *stream, void *const *stage_events);
 
 /*
+ * Expert weights in 8-bit floating point, weight-only (a widening beyond the paper's bf16 runs; its Sec. 5 shows
+ * the method is additive to weight quantisation): halves the bytes the decode step is bound by.  Format: OCP FP8
+ * E4M3 (largest value 448), one fp32 scale per weight-matrix row: scale = amax(row) / 448 (1 for an all-zero
+ * row), code = nearest E4M3 value of w / scale (ties to even; both divisions correctly rounded fp32).
+ * lynx_quantize_weights_fp8 quantises row-major bf16 weights (as for lynx_pack_weights; H and F multiples of
+ * 64) straight into the streaming layout:
+ *   Wgu_q [E][F/16][H/64][2][64][16] bytes, Wd_q [E][H/16][F/64][64][16] bytes (a 1 KiB tile = 16 rows x 64
+ *   columns: lane l = row l%16, columns (l/16)*16 .. +15), scales_gu [E][2][F] (gate rows, then up rows),
+ *   scales_d [E][H].  All DEVICE.
+ */
+int lynx_quantize_weights_fp8(const uint16_t *Wg, const uint16_t *Wu, const uint16_t *Wd, int E, int H, int F,
+                              uint8_t *Wgu_q, uint8_t *Wd_q, float *scales_gu, float *scales_d, void *stream);
+
+/*
+ * lynx_moe_ffn_timed with FP8 weights: the codes are converted to bf16 in registers (exact), multiplied on the
+ * matrix cores as in the bf16 path, and the accumulated sums are multiplied by the row scales; activations and
+ * the intermediate vector stay bf16.  Shared experts quantised likewise (NULL when n_shared = 0).
+ * stage_events may be NULL.  H, F, F_shared multiples of 64.
+ */
+int lynx_moe_ffn_fp8(const uint16_t *x_bf16, const uint8_t *Wgu_q, const uint8_t *Wd_q, const float *scales_gu,
+                     const float *scales_d, const uint8_t *Sgu_q, const uint8_t *Sd_q, const float *shared_scales_gu,
+                     const float *shared_scales_d, int n_shared, int F_shared, const int32_t *idx, const float *gate,
+                     const int32_t *expert_offsets, const int32_t *perm, const int32_t *active_experts,
+                     const int32_t *num_active, int T, int H, int F, int N, int k, float *y, void *workspace,
+                     void *stream, void *const *stage_events);
+
+/* lynx_moe_layer with FP8 expert weights (routing unchanged). */
+int lynx_moe_layer_fp8(const uint16_t *x_bf16, const float *Wr, const float *bias, const uint8_t *Wgu_q,
+                       const uint8_t *Wd_q, const float *scales_gu, const float *scales_d, const uint8_t *Sgu_q,
+                       const uint8_t *Sd_q, const float *shared_scales_gu, const float *shared_scales_d, int n_shared,
+                       int F_shared, int T, int H, int F, int N, int k, float alpha, int beta, int enable, float *logits,
+                       int32_t *topk_idx, float *topk_gate, float *topk_psum, int32_t *new_idx, float *new_gate,
+                       int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist, int32_t *num_active,
+                       int32_t *expert_offsets, int32_t *perm, int32_t *active_experts, int32_t *num_active_perm,
+                       float *y, void *workspace, void *stream, void *const *stage_events);
+
+/*
  * Measurement aid, not a step of the method: the residual update that chains MoE layers into a stack (the
  * benchmark times a stack of layers as a whole, each layer's input depending on the layer before):
  * x_next[i] = bf16(float(x[i]) + y[i]) for i < n, one fp32 addition rounded to nearest even.  x_bf16 [n] and

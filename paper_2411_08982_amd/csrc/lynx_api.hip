@@ -38,22 +38,21 @@ int moe_ffn_impl(const uint16_t *x_bf16, const uint16_t *Wgu_packed, const uint1
                  const uint16_t *Sd_packed, int n_shared, int F_shared, const int32_t *idx, const float *gate,
                  const int32_t *expert_offsets, const int32_t *perm, const int32_t *active_experts,
                  const int32_t *num_active, int T, int H, int F, int N, int k, float *y, void *workspace, void *stream,
-                 void *const *stage_events, bool counters_cleared);
+                 void *const *stage_events, bool counters_cleared, const FfnScales *q8);
 }
 
 // The fused path issues the routing side in two launches up to 16 tokens (logits; everything else in one
 // workgroup) and in four beyond (logits; top-k + bins; nominations; remap + token assignment) instead of the
 // launches of the separate calls; results are identical.
-extern "C" int lynx_moe_layer(const uint16_t *x_bf16, const float *Wr, const float *bias, const uint16_t *Wgu_packed,
-                              const uint16_t *Wd_packed, const uint16_t *Sgu_packed, const uint16_t *Sd_packed,
-                              int n_shared, int F_shared, int T, int H, int F, int N, int k, float alpha, int beta,
-                              int enable, float *logits, int32_t *topk_idx, float *topk_gate, float *topk_psum,
-                              int32_t *new_idx, float *new_gate, int32_t *cnt_before, int32_t *cnt_after,
-                              int32_t *bin_hist, int32_t *num_active, int32_t *expert_offsets, int32_t *perm,
-                              int32_t *active_experts, int32_t *num_active_perm, float *y, void *workspace,
-                              void *stream, void *const *stage_events)
+namespace lynx {
+static int moe_layer_impl(const uint16_t *x_bf16, const float *Wr, const float *bias, const uint16_t *Wgu_packed,
+                          const uint16_t *Wd_packed, const uint16_t *Sgu_packed, const uint16_t *Sd_packed, int n_shared,
+                          int F_shared, int T, int H, int F, int N, int k, float alpha, int beta, int enable, float *logits,
+                          int32_t *topk_idx, float *topk_gate, float *topk_psum, int32_t *new_idx, float *new_gate,
+                          int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist, int32_t *num_active,
+                          int32_t *expert_offsets, int32_t *perm, int32_t *active_experts, int32_t *num_active_perm,
+                          float *y, void *workspace, void *stream, void *const *stage_events, const FfnScales *q8)
 {
-    using namespace lynx;
     int rc;
     bool fused = false;
     if (T <= 0 || !workspace) {
@@ -83,8 +82,11 @@ extern "C" int lynx_moe_layer(const uint16_t *x_bf16, const float *Wr, const flo
         if (F <= 0 || n_shared < 0 || !Wgu_packed || !Wd_packed || !y ||
             (n_shared > 0 && (F_shared <= 0 || !Sgu_packed || !Sd_packed)))
             return fail(LYNX_ERR_INVALID_ARG, "lynx_moe_layer: bad FFN size or null weight / output pointer");
-        if ((F % 32) != 0 || (n_shared > 0 && (F_shared % 32) != 0))
-            return fail(LYNX_ERR_UNSUPPORTED, "lynx_moe_layer: F and F_shared must be multiples of 32");
+        const int mult = q8 ? 64 : 32;
+        if ((H % mult) != 0 || (F % mult) != 0 || (n_shared > 0 && (F_shared % mult) != 0))
+            return fail(LYNX_ERR_UNSUPPORTED, "lynx_moe_layer: H, F and F_shared must be multiples of %d", mult);
+        if (q8 && (!q8->gu || !q8->d || (n_shared > 0 && (!q8->shared_gu || !q8->shared_d))))
+            return fail(LYNX_ERR_INVALID_ARG, "lynx_moe_layer_fp8: null scale pointer");
         rc = routing_fused(x_bf16, Wr, bias, T, H, N, k, alpha, beta, enable, logits, topk_idx, topk_gate, topk_psum,
                            new_idx, new_gate, cnt_before, cnt_after, bin_hist, num_active, expert_offsets, perm,
                            active_experts, num_active_perm, workspace, (hipStream_t)stream);
@@ -93,5 +95,40 @@ extern "C" int lynx_moe_layer(const uint16_t *x_bf16, const float *Wr, const flo
     }
     return moe_ffn_impl(x_bf16, Wgu_packed, Wd_packed, Sgu_packed, Sd_packed, n_shared, F_shared, new_idx, new_gate,
                         expert_offsets, perm, active_experts, num_active_perm, T, H, F, N, k, y, workspace, stream,
-                        stage_events, fused);
+                        stage_events, fused, q8);
+}
+}  // namespace lynx
+
+extern "C" int lynx_moe_layer(const uint16_t *x_bf16, const float *Wr, const float *bias, const uint16_t *Wgu_packed,
+                              const uint16_t *Wd_packed, const uint16_t *Sgu_packed, const uint16_t *Sd_packed,
+                              int n_shared, int F_shared, int T, int H, int F, int N, int k, float alpha, int beta,
+                              int enable, float *logits, int32_t *topk_idx, float *topk_gate, float *topk_psum,
+                              int32_t *new_idx, float *new_gate, int32_t *cnt_before, int32_t *cnt_after,
+                              int32_t *bin_hist, int32_t *num_active, int32_t *expert_offsets, int32_t *perm,
+                              int32_t *active_experts, int32_t *num_active_perm, float *y, void *workspace,
+                              void *stream, void *const *stage_events)
+{
+    return lynx::moe_layer_impl(x_bf16, Wr, bias, Wgu_packed, Wd_packed, Sgu_packed, Sd_packed, n_shared, F_shared, T, H, F,
+                                N, k, alpha, beta, enable, logits, topk_idx, topk_gate, topk_psum, new_idx, new_gate,
+                                cnt_before, cnt_after, bin_hist, num_active, expert_offsets, perm, active_experts,
+                                num_active_perm, y, workspace, stream, stage_events, nullptr);
+}
+
+extern "C" int lynx_moe_layer_fp8(const uint16_t *x_bf16, const float *Wr, const float *bias, const uint8_t *Wgu_q,
+                                  const uint8_t *Wd_q, const float *scales_gu, const float *scales_d, const uint8_t *Sgu_q,
+                                  const uint8_t *Sd_q, const float *shared_scales_gu, const float *shared_scales_d,
+                                  int n_shared, int F_shared, int T, int H, int F, int N, int k, float alpha, int beta,
+                                  int enable, float *logits, int32_t *topk_idx, float *topk_gate, float *topk_psum,
+                                  int32_t *new_idx, float *new_gate, int32_t *cnt_before, int32_t *cnt_after,
+                                  int32_t *bin_hist, int32_t *num_active, int32_t *expert_offsets, int32_t *perm,
+                                  int32_t *active_experts, int32_t *num_active_perm, float *y, void *workspace,
+                                  void *stream, void *const *stage_events)
+{
+    const lynx::FfnScales q = {scales_gu, scales_d, shared_scales_gu, shared_scales_d};
+    return lynx::moe_layer_impl(x_bf16, Wr, bias, reinterpret_cast<const uint16_t *>(Wgu_q),
+                                reinterpret_cast<const uint16_t *>(Wd_q), reinterpret_cast<const uint16_t *>(Sgu_q),
+                                reinterpret_cast<const uint16_t *>(Sd_q), n_shared, F_shared, T, H, F, N, k, alpha, beta,
+                                enable, logits, topk_idx, topk_gate, topk_psum, new_idx, new_gate, cnt_before, cnt_after,
+                                bin_hist, num_active, expert_offsets, perm, active_experts, num_active_perm, y, workspace,
+                                stream, stage_events, &q);
 }

@@ -118,6 +118,12 @@ __device__ __forceinline__ uint4 load_coherent(const uint4 *p)   // two 8-byte d
 // All memory operations this wave has issued are complete (vmcnt, expcnt, lgkmcnt = 0).
 __device__ __forceinline__ void wait_memory_complete() { __builtin_amdgcn_s_waitcnt(0); }
 
+// Row scales of FP8 expert weights (all DEVICE): gate/up [N][2][F] and down [N][H] of the routed experts, the same
+// of the shared experts.  A null pointer to this struct means bf16 weights.
+struct FfnScales {
+    const float *gu, *d, *shared_gu, *shared_d;
+};
+
 // ---- workspace layout (one caller-provided buffer serves every call) -----------------------------------
 // [ routing scratch | h: bf16 intermediate vectors | o: fp32 per-pair outputs ]
 // Routing scratch (int32 words): tickets of the "last workgroup finishes the batch-level step" pattern,

@@ -39,6 +39,8 @@ constexpr int kStageBytesBig = 2 * 128 * (4 * 64 + 16);   // the same in the lar
 struct GemmParams {
     const uint16_t *W_routed;   // packed routed weights (gate/up interleaved, or down)
     const uint16_t *W_shared;   // packed shared-expert weights or NULL
+    const float *sc_routed;     // FP8 weights: row scales, gate/up [N][2][F] or down [N][H]; else unused
+    const float *sc_shared;     // the same for the shared experts
     const uint16_t *B;          // gate/up: x [T,H]; down: h scratch
     void *out;                  // gate/up: h scratch (bf16); down: o scratch (fp32)
     const int32_t *offsets, *perm, *active, *num_active;
@@ -60,20 +62,30 @@ struct WorkItem {
     const uint4 *W;      // packed weights of the expert
     const uint16_t *B;   // B-operand rows
     void *out;
+    const float *sc;     // FP8 weights: this expert's row scales ([2][R] for gate/up, [R] for down)
     int R, K, tile, Te, off, shared_s, e;
     int ldb, ldo;        // elements between B rows / output rows
     int tok0;            // shared experts: first token of this work item's token block
-    int kbeg, ksteps;    // slice of the contraction dimension this work item covers, in k-steps of 32 columns
+    int kbeg, ksteps;    // slice of the contraction dimension this work item covers, in weight tiles (32 or 64 columns)
     int out_base;        // shared experts: first output row of this work item
     bool valid;
 };
 
 // First half: which expert, from blockIdx and the invoked-expert list (one round trip to memory).  Everything
 // the weight stream needs is known after it, so the weight prefetch can start before the token tables are read.
-template <bool DUAL>
+// Weight formats: bf16 (a 1 KiB tile is 16 rows x 32 columns) or FP8 E4M3 (W8: 16 rows x 64 columns, converted to
+// bf16 in registers; one fp32 scale per row applied to the accumulated sums).
+template <bool W8>
+struct TileCols {
+    static constexpr int value = W8 ? 64 : 32;
+};
+
+template <bool DUAL, bool W8>
 __device__ __forceinline__ WorkItem resolve_expert(const GemmParams &p, int b)
 {
+    constexpr int KC = TileCols<W8>::value;
     WorkItem w;
+    w.sc = nullptr;
     w.valid = false;
     w.off = 0;
     w.Te = 0;
@@ -96,9 +108,10 @@ __device__ __forceinline__ WorkItem resolve_expert(const GemmParams &p, int b)
         w.ldb = p.ldb_r;
         w.ldo = p.ldo_r;
         w.kbeg = 0;
-        w.ksteps = w.K / 32;
+        w.ksteps = w.K / KC;
         w.out_base = 0;
-        Wbase = p.W_routed + (size_t)e * ((size_t)w.R * w.K * (DUAL ? 2 : 1));
+        Wbase = p.W_routed + (size_t)e * ((size_t)w.R * w.K * (DUAL ? 2 : 1) / (W8 ? 2 : 1));
+        if (W8) w.sc = p.sc_routed + (size_t)e * w.R * (DUAL ? 2 : 1);
     } else {
         // b = ((shared expert, K slice) * token blocks + token block) * stride + row tile.  Workgroups go to the
         // XCDs round-robin and the stride is a multiple of 8, so the token blocks of one row tile read their
@@ -114,12 +127,13 @@ __device__ __forceinline__ WorkItem resolve_expert(const GemmParams &p, int b)
         w.K = p.Ks;
         w.ldb = p.ldb_s;
         w.ldo = p.ldo_s;
-        const int per = (w.K / 32 + p.shared_splits - 1) / p.shared_splits;
+        const int per = (w.K / KC + p.shared_splits - 1) / p.shared_splits;
         w.kbeg = (v % p.shared_splits) * per;
-        w.ksteps = min(w.K / 32, w.kbeg + per) - w.kbeg;
+        w.ksteps = min(w.K / KC, w.kbeg + per) - w.kbeg;
         if (w.ksteps <= 0) return w;
         w.out_base = p.T * p.k + v * p.T;
-        Wbase = p.W_shared + (size_t)w.shared_s * ((size_t)w.R * w.K * (DUAL ? 2 : 1));
+        Wbase = p.W_shared + (size_t)w.shared_s * ((size_t)w.R * w.K * (DUAL ? 2 : 1) / (W8 ? 2 : 1));
+        if (W8) w.sc = p.sc_shared + (size_t)w.shared_s * w.R * (DUAL ? 2 : 1);
         // shared experts keep their h rows in their own region of the scratch
         const size_t hbase = (size_t)p.shared_h_base + (size_t)w.shared_s * p.T * (DUAL ? w.ldo : w.ldb);
         if (DUAL)
@@ -192,25 +206,37 @@ __device__ __forceinline__ void clear_acc(f32x4 (&accg)[NT], f32x4 (&accu)[NT])
 
 // D fragment of v_mfma_f32_16x16x32: lane holds token column (lane & 15) and output rows
 // 4*(lane >> 4) .. +3 of the wave's 16.  gate/up: h = silu(g) * u rounded to bf16; down: fp32.
-template <bool DUAL, int NT>
-__device__ __forceinline__ void epilogue(const f32x4 (&accg)[NT], const f32x4 (&accu)[NT], void *out, int ld, int row0,
-                                         const int (&orow)[NT])
+// W8: the sums are scaled by the row scales first (sc: gate rows [R] then up rows [R], or the down rows).
+template <bool DUAL, int NT, bool W8>
+__device__ __forceinline__ void epilogue(const f32x4 (&accg_in)[NT], const f32x4 (&accu_in)[NT], void *out, int ld, int row0,
+                                         const int (&orow)[NT], const float *sc, int R)
 {
     const int r = row0 + 4 * (lane_id() >> 4);
+    f32x4 sg = {1.f, 1.f, 1.f, 1.f}, su = {1.f, 1.f, 1.f, 1.f};
+    if (W8) {
+        const float4 a = *reinterpret_cast<const float4 *>(sc + r);
+        sg = f32x4{a.x, a.y, a.z, a.w};
+        if (DUAL) {
+            const float4 b = *reinterpret_cast<const float4 *>(sc + R + r);
+            su = f32x4{b.x, b.y, b.z, b.w};
+        }
+    }
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
         if (orow[nt] < 0) continue;
+        const f32x4 accg = W8 ? accg_in[nt] * sg : accg_in[nt];
+        const f32x4 accu = (W8 && DUAL) ? accu_in[nt] * su : accu_in[nt];
         if (DUAL) {
             uint2 pk;
-            pk.x = (uint32_t)f32_to_bf16_rne(silu_mul(accg[nt][0], accu[nt][0])) |
-                   ((uint32_t)f32_to_bf16_rne(silu_mul(accg[nt][1], accu[nt][1])) << 16);
-            pk.y = (uint32_t)f32_to_bf16_rne(silu_mul(accg[nt][2], accu[nt][2])) |
-                   ((uint32_t)f32_to_bf16_rne(silu_mul(accg[nt][3], accu[nt][3])) << 16);
+            pk.x = (uint32_t)f32_to_bf16_rne(silu_mul(accg[0], accu[0])) |
+                   ((uint32_t)f32_to_bf16_rne(silu_mul(accg[1], accu[1])) << 16);
+            pk.y = (uint32_t)f32_to_bf16_rne(silu_mul(accg[2], accu[2])) |
+                   ((uint32_t)f32_to_bf16_rne(silu_mul(accg[3], accu[3])) << 16);
             // read by the down-projection workgroups of the same launch, possibly on another XCD
             store_coherent(reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(out) + (size_t)orow[nt] * ld + r), pk);
         } else {
             *reinterpret_cast<float4 *>(reinterpret_cast<float *>(out) + (size_t)orow[nt] * ld + r) =
-                make_float4(accg[nt][0], accg[nt][1], accg[nt][2], accg[nt][3]);
+                make_float4(accg[0], accg[1], accg[2], accg[3]);
         }
     }
 }
@@ -258,6 +284,25 @@ __device__ __forceinline__ uint4 ring_load_weights(const uint4 *__restrict__ bas
 
 // Two weight streams share every B fragment: gate and up tiles (interleaved: second = 64, step = 128) or,
 // for the down projection, two consecutive row tiles (second = one row tile further, step = 64).
+// 16 E4M3 codes (one lane's piece of a 64-column tile) -> two MFMA operands of 8 bf16 (columns 0-7 and 8-15 of
+// the lane's group).  The hardware conversion gives fp32; an E4M3 value has 3 mantissa bits, so the upper half
+// of the fp32 IS the bf16, exactly.
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t e4m3x2_to_bf16x2(uint32_t codes, bool upper)
+{
+    const f32x2 f = upper ? __builtin_amdgcn_cvt_pk_f32_fp8((int)codes, true) : __builtin_amdgcn_cvt_pk_f32_fp8((int)codes, false);
+    return __builtin_amdgcn_perm(__float_as_uint(f.y), __float_as_uint(f.x), 0x07060302u);
+}
+__device__ __forceinline__ void e4m3x16_to_bf16(uint4 c, bf16x8 &lo, bf16x8 &hi)
+{
+    const uint4 l = make_uint4(e4m3x2_to_bf16x2(c.x, false), e4m3x2_to_bf16x2(c.x, true), e4m3x2_to_bf16x2(c.y, false),
+                               e4m3x2_to_bf16x2(c.y, true));
+    const uint4 h = make_uint4(e4m3x2_to_bf16x2(c.z, false), e4m3x2_to_bf16x2(c.z, true), e4m3x2_to_bf16x2(c.w, false),
+                               e4m3x2_to_bf16x2(c.w, true));
+    lo = __builtin_bit_cast(bf16x8, l);
+    hi = __builtin_bit_cast(bf16x8, h);
+}
+
 struct WeightRing {
     uint4 w0[kPFD], w1[kPFD];
 };
@@ -271,13 +316,13 @@ struct DirectPlan {
     bool rows_ok;
 };
 
-template <bool DUAL, int KW>
+template <bool DUAL, int KW, bool W8>
 __device__ __forceinline__ DirectPlan plan_direct(const WorkItem &w)
 {
     constexpr int RW = kFfnWaves / KW;
     const int wv = wave_id();
     const int rw = wv / KW, kw = wv % KW;
-    const int KT = w.K / 32;
+    const int KT = w.K / TileCols<W8>::value;
     DirectPlan d;
     const int grp = w.tile * RW + rw;                  // row group of this wave
     d.rt = DUAL ? grp : 2 * grp;
@@ -305,20 +350,24 @@ __device__ __forceinline__ void prefetch_weights(const DirectPlan &d, WeightRing
 }
 
 // The ring arrives with its first turn of weight tiles already requested (prefetch_weights).
-template <int NT, bool COH>
+template <int NT, bool COH, bool W8>
 __device__ __forceinline__ void stream_direct(const DirectPlan &d, WeightRing &r, const uint4 *const (&brow)[NT],
                                               f32x4 (&acc0)[NT], f32x4 (&acc1)[NT])
 {
+    constexpr int BP = W8 ? 2 : 1;           // 16-byte pieces of a token row per lane and weight tile
+    constexpr int BS = TileCols<W8>::value / 8;   // uint4 units between the pieces of consecutive tiles
     const uint4 *Wl = d.Wl;
     const int step = d.step, second = d.second;
     const int n = d.rows_ok ? d.n : 0;     // k-steps whose products count
     const int last = max(d.n, 1) - 1;
-    uint4 bb[kPFD][NT];
+    uint4 bb[kPFD][NT][BP];
 #pragma unroll
     for (int j = 0; j < kPFD; ++j) {
         const int s = min(j, last);
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) bb[j][nt] = ring_load_b<COH>(brow[nt], s * 4);
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int h = 0; h < BP; ++h) bb[j][nt][h] = ring_load_b<COH>(brow[nt], s * BS + h);
     }
     for (int s0 = 0; s0 < n; s0 += kPFD) {
 #pragma unroll
@@ -326,13 +375,28 @@ __device__ __forceinline__ void stream_direct(const DirectPlan &d, WeightRing &r
             const int s = s0 + u;
             const bool live = s < n;
             // consume slot u ...
-            const bf16x8 a0 = __builtin_bit_cast(bf16x8, sel4(live, r.w0[u]));
-            const bf16x8 a1 = __builtin_bit_cast(bf16x8, sel4(live, r.w1[u]));
+            if (W8) {
+                bf16x8 a0l, a0h, a1l, a1h;
+                e4m3x16_to_bf16(sel4(live, r.w0[u]), a0l, a0h);
+                e4m3x16_to_bf16(sel4(live, r.w1[u]), a1l, a1h);
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
-                const bf16x8 b = __builtin_bit_cast(bf16x8, bb[u][nt]);
-                acc0[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, b, acc0[nt], 0, 0, 0);
-                acc1[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, b, acc1[nt], 0, 0, 0);
+                for (int nt = 0; nt < NT; ++nt) {
+                    const bf16x8 bl = __builtin_bit_cast(bf16x8, bb[u][nt][0]);
+                    const bf16x8 bh = __builtin_bit_cast(bf16x8, bb[u][nt][BP - 1]);
+                    acc0[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0l, bl, acc0[nt], 0, 0, 0);
+                    acc1[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1l, bl, acc1[nt], 0, 0, 0);
+                    acc0[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0h, bh, acc0[nt], 0, 0, 0);
+                    acc1[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1h, bh, acc1[nt], 0, 0, 0);
+                }
+            } else {
+                const bf16x8 a0 = __builtin_bit_cast(bf16x8, sel4(live, r.w0[u]));
+                const bf16x8 a1 = __builtin_bit_cast(bf16x8, sel4(live, r.w1[u]));
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) {
+                    const bf16x8 b = __builtin_bit_cast(bf16x8, bb[u][nt][0]);
+                    acc0[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, b, acc0[nt], 0, 0, 0);
+                    acc1[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, b, acc1[nt], 0, 0, 0);
+                }
             }
             // ... then refill it (the scheduling fences keep the refill behind the last read of the slot,
             // so that it can land in the same registers and the ring needs no copies)
@@ -341,7 +405,9 @@ __device__ __forceinline__ void stream_direct(const DirectPlan &d, WeightRing &r
             r.w0[u] = ring_load_weights(Wl, sn * step);
             r.w1[u] = ring_load_weights(Wl, sn * step + second);
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) bb[u][nt] = ring_load_b<COH>(brow[nt], sn * 4);
+            for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                for (int h = 0; h < BP; ++h) bb[u][nt][h] = ring_load_b<COH>(brow[nt], sn * BS + h);
             __builtin_amdgcn_sched_barrier(0);
         }
     }
@@ -350,10 +416,11 @@ __device__ __forceinline__ void stream_direct(const DirectPlan &d, WeightRing &r
 // One expert with <= 16*NT tokens: the four waves are RW row groups x KW slices of K; the slices are
 // summed through LDS at the end.  A row group is one 16-row tile of gate and up (gate/up) or two
 // consecutive 16-row tiles (down), so that every token fragment loaded feeds two MFMAs.
-template <bool DUAL, int NT, int KW>
+template <bool DUAL, int NT, int KW, bool W8>
 __device__ __forceinline__ void expert_direct(const GemmParams &p, const WorkItem &w, const DirectPlan &d, WeightRing &ring,
                                               float *red)
 {
+    constexpr int KC = TileCols<W8>::value;
     constexpr int NACC = NT * 2;
     const int lane = lane_id(), wv = wave_id();
     const int rw = wv / KW, kw = wv % KW;
@@ -372,11 +439,11 @@ __device__ __forceinline__ void expert_direct(const GemmParams &p, const WorkIte
             token_rows<DUAL>(p, w, 0, ro, none);
             ro = max(ro, 0);
         }
-        brow[nt] = reinterpret_cast<const uint4 *>(w.B + (size_t)ro + (size_t)kbc * 32 + (lane >> 4) * 8);
+        brow[nt] = reinterpret_cast<const uint4 *>(w.B + (size_t)ro + (size_t)kbc * KC + (lane >> 4) * (KC / 4));
     }
     f32x4 acc0[NT], acc1[NT];
     clear_acc<NT>(acc0, acc1);
-    stream_direct<NT, false>(d, ring, brow, acc0, acc1);
+    stream_direct<NT, false, W8>(d, ring, brow, acc0, acc1);
     if (KW > 1) {
         f32x4 *r4 = reinterpret_cast<f32x4 *>(red);   // [rw][kw-1][NACC][lane]
         if (kw > 0) {
@@ -402,33 +469,34 @@ __device__ __forceinline__ void expert_direct(const GemmParams &p, const WorkIte
     }
     if (kw == 0 && rows_ok) {
         if (DUAL) {
-            epilogue<true, NT>(acc0, acc1, w.out, w.ldo, rt * 16, orow);
+            epilogue<true, NT, W8>(acc0, acc1, w.out, w.ldo, rt * 16, orow, w.sc, w.R);
         } else {
-            epilogue<false, NT>(acc0, acc0, w.out, w.ldo, rt * 16, orow);
-            epilogue<false, NT>(acc1, acc1, w.out, w.ldo, rt * 16 + 16, orow);
+            epilogue<false, NT, W8>(acc0, acc0, w.out, w.ldo, rt * 16, orow, w.sc, w.R);
+            epilogue<false, NT, W8>(acc1, acc1, w.out, w.ldo, rt * 16 + 16, orow, w.sc, w.R);
         }
     }
 }
 
 // Staged: the token tile is staged through LDS in chunks of KS k-steps, double buffered and shared by
 // the four waves, which own four consecutive 16-row tiles and walk all of K.
-template <bool DUAL, int NT, int KS>
+template <bool DUAL, int NT, int KS, bool W8>
 __device__ __forceinline__ void stream_staged(const uint4 *__restrict__ Wt, bool wave_active, int KT, int K,
                                               const uint16_t *__restrict__ B, const int *rowoff, char *stage,
-                                              f32x4 (&accg)[NT], f32x4 (&accu)[NT])   // KT steps from Wt; B columns [0, K)
+                                              f32x4 (&accg)[NT], f32x4 (&accu)[NT])   // KT weight tiles from Wt; B columns [0, K)
 {
+    constexpr int TS = W8 ? 2 : 1;               // 32-column steps of the staged token tile per weight tile
     constexpr int ROWB = KS * 64 + 16;           // LDS bytes per token row (+16: conflict-free 16-byte reads)
     constexpr int BUFB = NT * 16 * ROWB;
     static_assert(2 * BUFB <= (NT > 4 ? kStageBytesBig : kStageBytes), "token tile does not fit the LDS stage");
     constexpr int PIECES = NT * 16 * KS * 4;     // 16-byte pieces per chunk
     static_assert(PIECES % kFfnThreads == 0, "pieces must divide evenly over the workgroup");
     constexpr int PPT = PIECES / kFfnThreads;
-    static_assert(kPF % KS == 0, "a ring turn must hold whole chunks");
+    static_assert((kPF * TS) % KS == 0, "a ring turn must hold whole chunks");
     constexpr int WSTEP = DUAL ? 2 * kWave : kWave;
 
     const int tid = threadIdx.x, lane = lane_id();
     const int last = KT - 1;
-    const int lastc = (KT + KS - 1) / KS - 1;
+    const int lastc = (KT * TS + KS - 1) / KS - 1;
 
     // this thread's staging pieces: (token row, 16-byte piece inside the chunk)
     int xoff[PPT];    // element offset of the piece in chunk 0
@@ -472,32 +540,48 @@ __device__ __forceinline__ void stream_staged(const uint4 *__restrict__ Wt, bool
     store_x(0);
     __syncthreads();
 
-    const int brow = (lane & 15) * ROWB + (lane >> 4) * 16;   // this lane's B-fragment offset inside a token tile
+    // this lane's B-fragment offset inside a token tile (its column group: 8 columns, or 16 for 64-column tiles)
+    const int brow = (lane & 15) * ROWB + (lane >> 4) * (W8 ? 32 : 16);
     for (int s0 = 0; s0 < KT; s0 += kPF) {
 #pragma unroll
         for (int u = 0; u < kPF; ++u) {
             const int s = s0 + u;
-            const int c = s / KS;
-            if (u % KS == 0) {
+            const int c = (s * TS) / KS;
+            if ((u * TS) % KS == 0) {
                 load_x(min(c + 1, lastc));
                 __builtin_amdgcn_sched_barrier(0);
             }
             const bool live = wave_active && s < KT;
-            const bf16x8 ag = __builtin_bit_cast(bf16x8, sel4(live, wg[u]));
-            const bf16x8 au = __builtin_bit_cast(bf16x8, sel4(live, wu[u]));
-            const char *buf = stage + (c & 1) * BUFB + brow + (u % KS) * 64;
+            const char *buf = stage + (c & 1) * BUFB + brow + ((u * TS) % KS) * 64;
+            if (W8) {
+                bf16x8 agl, agh, aul, auh;
+                e4m3x16_to_bf16(sel4(live, wg[u]), agl, agh);
+                e4m3x16_to_bf16(sel4(live, wu[u]), aul, auh);
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
-                const bf16x8 b = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(buf + nt * 16 * ROWB));
-                accg[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ag, b, accg[nt], 0, 0, 0);
-                if (DUAL) accu[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(au, b, accu[nt], 0, 0, 0);
+                for (int nt = 0; nt < NT; ++nt) {
+                    const bf16x8 bl = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(buf + nt * 16 * ROWB));
+                    const bf16x8 bh = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(buf + nt * 16 * ROWB + 16));
+                    accg[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(agl, bl, accg[nt], 0, 0, 0);
+                    if (DUAL) accu[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aul, bl, accu[nt], 0, 0, 0);
+                    accg[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(agh, bh, accg[nt], 0, 0, 0);
+                    if (DUAL) accu[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(auh, bh, accu[nt], 0, 0, 0);
+                }
+            } else {
+                const bf16x8 ag = __builtin_bit_cast(bf16x8, sel4(live, wg[u]));
+                const bf16x8 au = __builtin_bit_cast(bf16x8, sel4(live, wu[u]));
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) {
+                    const bf16x8 b = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(buf + nt * 16 * ROWB));
+                    accg[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ag, b, accg[nt], 0, 0, 0);
+                    if (DUAL) accu[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(au, b, accu[nt], 0, 0, 0);
+                }
             }
             __builtin_amdgcn_sched_barrier(0);
             const int sn = min(s + kPF, last);
             wg[u] = ring_load_weights(Wl, sn * WSTEP);
             if (DUAL) wu[u] = ring_load_weights(Wl, sn * WSTEP + kWave);
             __builtin_amdgcn_sched_barrier(0);
-            if (u % KS == KS - 1) {
+            if ((u * TS + TS - 1) % KS == KS - 1) {
                 store_x(c + 1);
                 __syncthreads();
             }
@@ -505,23 +589,24 @@ __device__ __forceinline__ void stream_staged(const uint4 *__restrict__ Wt, bool
     }
 }
 
-template <bool DUAL, int NT, int KS>
+template <bool DUAL, int NT, int KS, bool W8>
 __device__ __forceinline__ void expert_staged(const WorkItem &w, const int *rowoff, const int *outrow, char *stage)
 {
     constexpr int WSTEP = DUAL ? 2 * kWave : kWave;
-    const int KT = w.K / 32;
+    constexpr int KC = TileCols<W8>::value;
+    const int KT = w.K / KC;
     const int rt = w.tile * kFfnWaves + wave_id();
     const bool wave_active = rt * 16 < w.R;
     const int rtc = wave_active ? rt : 0;   // idle waves read tile 0 (in bounds) and contribute nothing
     f32x4 accg[NT], accu[NT];
     clear_acc<NT>(accg, accu);
-    stream_staged<DUAL, NT, KS>(w.W + ((size_t)rtc * KT + w.kbeg) * WSTEP, wave_active, w.ksteps, w.ksteps * 32,
-                                w.B + (size_t)w.kbeg * 32, rowoff, stage, accg, accu);
+    stream_staged<DUAL, NT, KS, W8>(w.W + ((size_t)rtc * KT + w.kbeg) * WSTEP, wave_active, w.ksteps, w.ksteps * KC,
+                                    w.B + (size_t)w.kbeg * KC, rowoff, stage, accg, accu);
     if (!wave_active) return;
     int orow[NT];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) orow[nt] = outrow[nt * 16 + (lane_id() & 15)];
-    epilogue<DUAL, NT>(accg, accu, w.out, w.ldo, rt * 16, orow);
+    epilogue<DUAL, NT, W8>(accg, accu, w.out, w.ldo, rt * 16, orow, w.sc, w.R);
 }
 
 // Both projections of every invoked and shared expert in ONE launch.  Grid: all gate/up workgroups, then
@@ -553,17 +638,17 @@ __device__ __forceinline__ int done_slot(const GemmParams &p, const WorkItem &w)
     return w.shared_s < 0 ? w.e : LYNX_MAX_N + w.shared_s * p.shared_tblocks + w.tok0 / p.tok_block;
 }
 
-template <bool DUAL, int KW, bool BIG>
+template <bool DUAL, int KW, bool BIG, bool W8>
 __device__ __forceinline__ void expert_work(const GemmParams &p, int b, const FfnParams &fp, char *stage, int *rowoff,
                                             int *outrow)
 {
     constexpr int TB = BIG ? kTokBlockBig : kTokBlock;   // tokens per pass
-    WorkItem w = resolve_expert<DUAL>(p, b);
+    WorkItem w = resolve_expert<DUAL, W8>(p, b);
     if (!w.valid) return;
     // The weight stream of the direct path starts before the token tables are read (their loads depend on
     // each other: offsets, then the permutation, then the token rows).
     // (Not in the large-batch kernels: their staged path needs the registers, and few of their experts are direct.)
-    const DirectPlan plan = plan_direct<DUAL, KW>(w);
+    const DirectPlan plan = plan_direct<DUAL, KW, W8>(w);
     WeightRing ring;
     if (!BIG) prefetch_weights(plan, ring);
     resolve_tokens(p, w);
@@ -585,7 +670,7 @@ __device__ __forceinline__ void expert_work(const GemmParams &p, int b, const Ff
     }
     if (w.Te <= kDirectMaxTokens) {
         if (BIG) prefetch_weights(plan, ring);
-        expert_direct<DUAL, 1, KW>(p, w, plan, ring, reinterpret_cast<float *>(stage));
+        expert_direct<DUAL, 1, KW, W8>(p, w, plan, ring, reinterpret_cast<float *>(stage));
     } else {
         // staged path: units of 64 rows.  A direct workgroup covers 16*RW rows (gate/up) or 32*RW rows (down).
         constexpr int kRowsPerWG = 16 * (kFfnWaves / KW) * (DUAL ? 1 : 2);
@@ -613,11 +698,11 @@ __device__ __forceinline__ void expert_work(const GemmParams &p, int b, const Ff
                 }
                 __syncthreads();
                 if (nb <= 32)
-                    expert_staged<DUAL, 2, 8>(w, rowoff, outrow, stage);
+                    expert_staged<DUAL, 2, 8, W8>(w, rowoff, outrow, stage);
                 else if (!BIG || nb <= 64)
-                    expert_staged<DUAL, 4, 4>(w, rowoff, outrow, stage);
+                    expert_staged<DUAL, 4, 4, W8>(w, rowoff, outrow, stage);
                 else
-                    expert_staged<DUAL, 8, 4>(w, rowoff, outrow, stage);
+                    expert_staged<DUAL, 8, 4, W8>(w, rowoff, outrow, stage);
             }
         }
     }
@@ -628,7 +713,7 @@ __device__ __forceinline__ void expert_work(const GemmParams &p, int b, const Ff
     }
 }
 
-template <int KWD, bool BIG>
+template <int KWD, bool BIG, bool W8>
 __global__ __launch_bounds__(kFfnThreads, 2) void ffn_kernel(FfnParams fp)
 {
     // staged token tile, or the K-slice partial sums
@@ -637,9 +722,9 @@ __global__ __launch_bounds__(kFfnThreads, 2) void ffn_kernel(FfnParams fp)
     __shared__ int outrow[BIG ? kTokBlockBig : kTokBlock];   // staged path: output row of each token, -1 = none
     const int b = blockIdx.x + fp.block0;
     if (b < fp.gu_blocks)
-        expert_work<true, 1, BIG>(fp.gu, b, fp, stage, rowoff, outrow);
+        expert_work<true, 1, BIG, W8>(fp.gu, b, fp, stage, rowoff, outrow);
     else
-        expert_work<false, KWD, BIG>(fp.dn, b - fp.gu_blocks, fp, stage, rowoff, outrow);
+        expert_work<false, KWD, BIG, W8>(fp.dn, b - fp.gu_blocks, fp, stage, rowoff, outrow);
 }
 
 __global__ __launch_bounds__(256) void clear_kernel(int32_t *p, int n)
@@ -697,10 +782,82 @@ __global__ __launch_bounds__(256) void pack_kernel(const uint16_t *__restrict__ 
     *reinterpret_cast<uint4 *>(out + q * 8) = *reinterpret_cast<const uint4 *>(src);
 }
 
+// Nearest E4M3 code of v (ties to the even code, 448 and above to +-448, NaN to NaN), in integer and exact
+// floating-point steps so that it does not depend on a conversion mode of the hardware.
+__device__ __forceinline__ uint32_t e4m3_encode(float v)
+{
+    const uint32_t sgn = (__float_as_uint(v) >> 24) & 0x80u;
+    if (v != v) return sgn | 0x7fu;
+    const float a = fabsf(v);
+    if (a >= 448.0f) return sgn | 0x7eu;
+    uint32_t code;
+    if (a < 0.015625f) {                       // below 2^-6: multiples of 2^-9
+        code = (uint32_t)rintf(a * 512.0f);
+    } else {
+        const uint32_t bits = __float_as_uint(a);
+        const int ex = (int)(bits >> 23) - 127;                              // a = m * 2^ex, m in [1, 2)
+        const float m = __uint_as_float((bits & 0x007fffffu) | 0x3f800000u);
+        const uint32_t q = (uint32_t)rintf((m - 1.0f) * 8.0f);               // exact product; 8 carries into the exponent
+        code = ((uint32_t)(ex + 7) << 3) + q;
+    }
+    return sgn | min(code, 0x7eu);
+}
+
+// Row-wise FP8 quantisation straight into the streaming layout: one wave per (expert, matrix, row).  scale =
+// amax / 448 (1 for an all-zero row), code = encode(w / scale), both divisions correctly rounded fp32.  A 1 KiB
+// tile is 16 rows x 64 columns: lane l = row l%16, column group l/16 (16 consecutive columns = 16 bytes).
+__global__ __launch_bounds__(256) void quantize_kernel(const uint16_t *__restrict__ Wa, const uint16_t *__restrict__ Wb,
+                                                       int nmat, int E, int R, int K, uint8_t *__restrict__ out,
+                                                       float *__restrict__ scales)
+{
+    const long row_id = (long)blockIdx.x * 4 + wave_id();   // (e, m, r)
+    if (row_id >= (long)E * nmat * R) return;
+    const int lane = lane_id();
+    const int r = (int)(row_id % R);
+    const int m = (int)((row_id / R) % nmat);
+    const int e = (int)(row_id / ((long)R * nmat));
+    const uint16_t *src = (m == 0 ? Wa : Wb) + ((size_t)e * R + r) * K;
+    float amax = 0.f;
+    for (int c = lane * 8; c < K; c += kWave * 8) {
+        const uint4 v = *reinterpret_cast<const uint4 *>(src + c);
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            amax = fmaxf(amax, fabsf(__uint_as_float(w[i] << 16)));
+            amax = fmaxf(amax, fabsf(__uint_as_float(w[i] & 0xffff0000u)));
+        }
+    }
+    amax = wave_max(amax);
+    const float sc = amax == 0.f ? 1.0f : __fdiv_rn(amax, 448.0f);
+    if (lane == 0) scales[((size_t)e * nmat + m) * R + r] = sc;
+    const int KT = K / 64;
+    for (int c = lane * 16; c < K; c += kWave * 16) {   // 16 consecutive columns = one lane's piece of a tile
+        uint32_t packed[4];
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            const uint4 v = *reinterpret_cast<const uint4 *>(src + c + half * 8);
+            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const uint32_t lo = e4m3_encode(__fdiv_rn(__uint_as_float(w[i] << 16), sc));
+                const uint32_t hi = e4m3_encode(__fdiv_rn(__uint_as_float(w[i] & 0xffff0000u), sc));
+                const uint32_t two = lo | (hi << 8);
+                if (i % 2 == 0)
+                    packed[half * 2 + i / 2] = two;
+                else
+                    packed[half * 2 + i / 2] |= two << 16;
+            }
+        }
+        const int kt = c / 64, g = (c % 64) / 16;
+        const size_t piece = ((((size_t)e * (R / 16) + r / 16) * KT + kt) * nmat + m) * kWave + g * 16 + (r % 16);
+        *reinterpret_cast<uint4 *>(out + piece * 16) = make_uint4(packed[0], packed[1], packed[2], packed[3]);
+    }
+}
+
 // How many of a workgroup's four waves split the contraction dimension (the rest split rows).  Long
 // per-wave streams amortise the fill and drain of the prefetch ring, so K is only split when the
 // batch cannot invoke enough experts to give every CU several waves otherwise.
-static int pick_k_waves(int K, bool dual, int T, int max_experts)
+static int pick_k_waves(int K, bool dual, int T, int max_experts, int bytes_per_weight)
 {
     // Gate/up: a wave streams a whole row tile of both matrices (2 * K * 32 bytes, contiguous); measured best
     // at every expert count.  It also makes a workgroup exactly one 64-row unit of the staged path.
@@ -712,7 +869,7 @@ static int pick_k_waves(int K, bool dual, int T, int max_experts)
     // Down, direct path only.  Measured: splitting K pays when the batch can invoke so few experts that
     // whole row groups would leave the chip with too few, too long workgroups (Mixtral-like shapes); with
     // many small experts the short streams cost more than the finer granularity gains.
-    const long group_bytes = (long)16 * K * 2 * 2;                        // weight bytes behind one row group
+    const long group_bytes = (long)16 * K * 2 * bytes_per_weight;         // weight bytes behind one row group
     int kw = max_experts <= 8 ? 4 : max_experts <= 16 ? 2 : 1;
     while (kw > 1 && group_bytes / kw < 32 * 1024) kw >>= 1;              // keep at least 32 KiB per wave
     return kw;
@@ -742,18 +899,18 @@ constexpr int kWgPerCu = 2;
 constexpr int kLdsPerCu = 160 * 1024;
 constexpr int kLdsTargetPerWg = 56 * 1024;
 
-template <int KWD, bool BIG>
+template <int KWD, bool BIG, bool W8>
 static int launch_padded(const FfnParams &fp, unsigned blocks, hipStream_t st)
 {
     static_assert(kLdsTargetPerWg * (kWgPerCu + 1) > kLdsPerCu && kLdsTargetPerWg * kWgPerCu <= kLdsPerCu, "LDS pad");
     static int pad = -1;   // per instantiation
     if (pad < 0) {
         hipFuncAttributes attr;
-        if (hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(&ffn_kernel<KWD, BIG>)) != hipSuccess)
+        if (hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(&ffn_kernel<KWD, BIG, W8>)) != hipSuccess)
             return fail(LYNX_ERR_HIP, "lynx_moe_ffn: hipFuncGetAttributes failed");
         pad = max(0, kLdsTargetPerWg - (int)attr.sharedSizeBytes);
     }
-    hipLaunchKernelGGL((ffn_kernel<KWD, BIG>), dim3(blocks), dim3(kFfnThreads), pad, st, fp);
+    hipLaunchKernelGGL((ffn_kernel<KWD, BIG, W8>), dim3(blocks), dim3(kFfnThreads), pad, st, fp);
     return LYNX_OK;
 }
 
@@ -766,11 +923,12 @@ static bool single_launch(int T, int F) { return T > kDirectMaxTokens && (F + 63
 
 // Gate/up and down over all invoked and shared experts.  Batches of more than 64 tokens take the
 // kernels whose staged path makes passes of up to 128 tokens.
+template <bool W8>
 static int launch_ffn(FfnParams fp, hipStream_t st)
 {
     const GemmParams &d = fp.dn;
     const int max_experts = (int)min((long)d.N, (long)d.T * d.k) + d.n_shared;
-    const int kwd = pick_k_waves(d.K, false, d.T, max_experts);
+    const int kwd = pick_k_waves(d.K, false, d.T, max_experts, W8 ? 1 : 2);
     set_tiles(fp.gu, 16 * kFfnWaves);                    // gate/up: four row tiles per workgroup
     set_tiles(fp.dn, 16 * (kFfnWaves / kwd) * 2);
     fp.gu_blocks = (int)grid_blocks(fp.gu);
@@ -783,13 +941,13 @@ static int launch_ffn(FfnParams fp, hipStream_t st)
         fp.block0 = part == 0 ? 0 : fp.gu_blocks;
         const unsigned blocks = single ? (unsigned)fp.gu_blocks + dn_blocks : part == 0 ? (unsigned)fp.gu_blocks : dn_blocks;
         if (big)
-            rc = launch_padded<2, true>(fp, blocks, st);
+            rc = launch_padded<2, true, W8>(fp, blocks, st);
         else if (kwd == 4)
-            rc = launch_padded<4, false>(fp, blocks, st);
+            rc = launch_padded<4, false, W8>(fp, blocks, st);
         else if (kwd == 2)
-            rc = launch_padded<2, false>(fp, blocks, st);
+            rc = launch_padded<2, false, W8>(fp, blocks, st);
         else
-            rc = launch_padded<1, false>(fp, blocks, st);
+            rc = launch_padded<1, false, W8>(fp, blocks, st);
         if (rc == LYNX_OK) rc = check_launch("lynx_moe_ffn(gate/up, down)");
     }
     return rc;
@@ -835,7 +993,7 @@ int moe_ffn_impl(const uint16_t *x_bf16, const uint16_t *Wgu_packed, const uint1
                  const uint16_t *Sd_packed, int n_shared, int F_shared, const int32_t *idx, const float *gate,
                  const int32_t *expert_offsets, const int32_t *perm, const int32_t *active_experts,
                  const int32_t *num_active, int T, int H, int F, int N, int k, float *y, void *workspace, void *stream,
-                 void *const *stage_events, bool counters_cleared)
+                 void *const *stage_events, bool counters_cleared, const FfnScales *q8)
 {
     auto mark = [&](int i) -> int {
         if (!stage_events || !stage_events[i]) return LYNX_OK;
@@ -846,10 +1004,13 @@ int moe_ffn_impl(const uint16_t *x_bf16, const uint16_t *Wgu_packed, const uint1
         return fail(LYNX_ERR_INVALID_ARG, "lynx_moe_ffn: bad size");
     if (n_shared > 0 && (F_shared <= 0 || !Sgu_packed || !Sd_packed))
         return fail(LYNX_ERR_INVALID_ARG, "lynx_moe_ffn: shared experts need F_shared > 0 and their weights");
-    if ((H % 32) != 0 || (F % 32) != 0 || (n_shared > 0 && (F_shared % 32) != 0) || N > LYNX_MAX_N || k > LYNX_MAX_K ||
-        T > LYNX_MAX_T || k > N)
-        return fail(LYNX_ERR_UNSUPPORTED, "lynx_moe_ffn: need H,F,F_shared multiples of 32, k<=N<=%d, k<=%d, T<=%d",
+    const int mult = q8 ? 64 : 32;   // columns of a weight tile
+    if ((H % mult) != 0 || (F % mult) != 0 || (n_shared > 0 && (F_shared % mult) != 0) || N > LYNX_MAX_N ||
+        k > LYNX_MAX_K || T > LYNX_MAX_T || k > N)
+        return fail(LYNX_ERR_UNSUPPORTED, "lynx_moe_ffn: need H,F,F_shared multiples of %d, k<=N<=%d, k<=%d, T<=%d", mult,
                     LYNX_MAX_N, LYNX_MAX_K, LYNX_MAX_T);
+    if (q8 && (!q8->gu || !q8->d || (n_shared > 0 && (!q8->shared_gu || !q8->shared_d))))
+        return fail(LYNX_ERR_INVALID_ARG, "lynx_moe_ffn_fp8: null scale pointer");
     if (T == 0) return LYNX_OK;
     if (!x_bf16 || !Wgu_packed || !Wd_packed || !idx || !gate || !expert_offsets || !perm || !active_experts ||
         !num_active || !y || !workspace)
@@ -899,6 +1060,8 @@ int moe_ffn_impl(const uint16_t *x_bf16, const uint16_t *Wgu_packed, const uint1
     p.K = H;
     p.Rs = F_shared;
     p.Ks = H;
+    p.sc_routed = q8 ? q8->gu : nullptr;
+    p.sc_shared = q8 ? q8->shared_gu : nullptr;
     p.ldb_r = p.ldb_s = H;
     p.ldo_r = h_stride(F);
     p.ldo_s = h_stride(F_shared);
@@ -912,6 +1075,8 @@ int moe_ffn_impl(const uint16_t *x_bf16, const uint16_t *Wgu_packed, const uint1
     p.K = F;
     p.Rs = H;
     p.Ks = F_shared;
+    p.sc_routed = q8 ? q8->d : nullptr;
+    p.sc_shared = q8 ? q8->shared_d : nullptr;
     p.ldb_r = h_stride(F);
     p.ldb_s = h_stride(F_shared);
     p.ldo_r = p.ldo_s = H;
@@ -919,7 +1084,7 @@ int moe_ffn_impl(const uint16_t *x_bf16, const uint16_t *Wgu_packed, const uint1
     fp.dn = p;
     rc = mark(0);
     if (rc != LYNX_OK) return rc;
-    rc = launch_ffn(fp, st);
+    rc = q8 ? launch_ffn<true>(fp, st) : launch_ffn<false>(fp, st);
     if (rc != LYNX_OK) return rc;
     rc = mark(1);
     if (rc != LYNX_OK) return rc;
@@ -944,7 +1109,43 @@ extern "C" int lynx_moe_ffn_timed(const uint16_t *x_bf16, const uint16_t *Wgu_pa
 {
     return lynx::moe_ffn_impl(x_bf16, Wgu_packed, Wd_packed, Sgu_packed, Sd_packed, n_shared, F_shared, idx, gate,
                               expert_offsets, perm, active_experts, num_active, T, H, F, N, k, y, workspace, stream,
-                              stage_events, false);
+                              stage_events, false, nullptr);
+}
+
+extern "C" int lynx_moe_ffn_fp8(const uint16_t *x_bf16, const uint8_t *Wgu_q, const uint8_t *Wd_q, const float *scales_gu,
+                                const float *scales_d, const uint8_t *Sgu_q, const uint8_t *Sd_q,
+                                const float *shared_scales_gu, const float *shared_scales_d, int n_shared, int F_shared,
+                                const int32_t *idx, const float *gate, const int32_t *expert_offsets, const int32_t *perm,
+                                const int32_t *active_experts, const int32_t *num_active, int T, int H, int F, int N,
+                                int k, float *y, void *workspace, void *stream, void *const *stage_events)
+{
+    const lynx::FfnScales q = {scales_gu, scales_d, shared_scales_gu, shared_scales_d};
+    return lynx::moe_ffn_impl(x_bf16, reinterpret_cast<const uint16_t *>(Wgu_q), reinterpret_cast<const uint16_t *>(Wd_q),
+                              reinterpret_cast<const uint16_t *>(Sgu_q), reinterpret_cast<const uint16_t *>(Sd_q), n_shared,
+                              F_shared, idx, gate, expert_offsets, perm, active_experts, num_active, T, H, F, N, k, y,
+                              workspace, stream, stage_events, false, &q);
+}
+
+extern "C" int lynx_quantize_weights_fp8(const uint16_t *Wg, const uint16_t *Wu, const uint16_t *Wd, int E, int H, int F,
+                                         uint8_t *Wgu_q, uint8_t *Wd_q, float *scales_gu, float *scales_d, void *stream)
+{
+    using namespace lynx;
+    if (E < 0 || H <= 0 || F <= 0) return fail(LYNX_ERR_INVALID_ARG, "lynx_quantize_weights_fp8: bad size");
+    if ((H % 64) != 0 || (F % 64) != 0)
+        return fail(LYNX_ERR_UNSUPPORTED, "lynx_quantize_weights_fp8: H and F must be multiples of 64 (H=%d F=%d)", H, F);
+    if (E == 0) return LYNX_OK;
+    if (!Wg || !Wu || !Wd || !Wgu_q || !Wd_q || !scales_gu || !scales_d)
+        return fail(LYNX_ERR_INVALID_ARG, "lynx_quantize_weights_fp8: null pointer");
+    const size_t rows_gu = (size_t)E * 2 * F, rows_d = (size_t)E * H;
+    if ((rows_gu + 3) / 4 > 0x7fffffffull || (rows_d + 3) / 4 > 0x7fffffffull)
+        return fail(LYNX_ERR_UNSUPPORTED, "lynx_quantize_weights_fp8: too large for one call");
+    hipLaunchKernelGGL(quantize_kernel, dim3((unsigned)((rows_gu + 3) / 4)), dim3(256), 0, (hipStream_t)stream, Wg, Wu, 2, E,
+                       F, H, Wgu_q, scales_gu);
+    int rc = check_launch("lynx_quantize_weights_fp8(gate/up)");
+    if (rc != LYNX_OK) return rc;
+    hipLaunchKernelGGL(quantize_kernel, dim3((unsigned)((rows_d + 3) / 4)), dim3(256), 0, (hipStream_t)stream, Wd, Wd, 1, E,
+                       H, F, Wd_q, scales_d);
+    return check_launch("lynx_quantize_weights_fp8(down)");
 }
 
 extern "C" int lynx_moe_ffn(const uint16_t *x_bf16, const uint16_t *Wgu_packed, const uint16_t *Wd_packed,

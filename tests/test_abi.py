@@ -14,13 +14,13 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def _declared():
     text = open(os.path.join(ROOT, "include", "lynx.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(lynx_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(lynx_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_library_exports_every_declared_symbol():
     lib = L.lib()
     names = _declared()
-    assert set(names) == set(L.SYMBOLS) and len(names) == 13
+    assert set(names) == set(L.SYMBOLS) and len(names) == 16
     for n in names:
         assert getattr(lib, n) is not None
 
@@ -73,6 +73,8 @@ def test_argument_errors_are_reported_before_any_launch():
     assert lib.lynx_residual_add(one, one, 3, one, None) == -1       # odd length
     assert lib.lynx_residual_add(one, None, 4, one, None) == -1
     assert lib.lynx_moe_ffn_launches(8, 14336) == 2 and lib.lynx_moe_ffn_launches(64, 768) == 1
+    assert lib.lynx_quantize_weights_fp8(one, one, one, 2, 96, 64, one, one, one, one, None) == -2    # H % 64
+    assert lib.lynx_quantize_weights_fp8(one, one, None, 2, 64, 64, one, one, one, one, None) == -1
     assert lib.lynx_read_probe(None, 32, 1, one, None) == -1
     assert lib.lynx_read_probe(one, 24, 1, one, None) == -1          # size not a multiple of 16
     assert lib.lynx_read_probe(one, 0, 1, one, None) == 0            # nothing to read
