@@ -426,14 +426,17 @@ def main():
         rm = {k_: bits(v) for k_, v in layer.row_major.items()}
         xh = bits(layer.tokens(T))
         Wr, bias = layer.Wr.cpu().numpy(), layer.bias.cpu().numpy()
-        t0 = time.perf_counter()
-        o = oracle.moe_layer(xh, Wr, bias, rm["Wg"], rm["Wu"], rm["Wd"], cfg.k, alpha, beta, enable, rm["Sg"], rm["Su"],
-                             rm["Sd"])
-        cpu_s = time.perf_counter() - t0
+        times = []
+        for _ in range(5):
+            t0 = time.perf_counter()
+            o = oracle.moe_layer(xh, Wr, bias, rm["Wg"], rm["Wu"], rm["Wd"], cfg.k, alpha, beta, enable, rm["Sg"], rm["Su"],
+                                 rm["Sd"])
+            times.append(time.perf_counter() - t0)
+        cpu_s = sorted(times)[len(times) // 2]
         out["cpu_baseline"] = {"value": round(cpu_s * 1e6, 1), "unit": "us/batch", "cores": oracle.num_threads(),
                                "kind": "oracle",
                                "sample": f"one full layer pass of the same workload ({T} tokens, all invoked experts), "
-                                         "1 repetition, plain C fp64 oracle with an OpenMP split over weight rows",
+                                         "median of 5 repetitions, plain C fp64 oracle with an OpenMP split over weight rows",
                                "experts_invoked": [int(v) for v in o["bin"]["num_active"]]}
     print(json.dumps(out))
 

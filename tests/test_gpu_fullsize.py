@@ -128,6 +128,38 @@ def test_full_size_layer(L, name, T, preset):
     print(f"  invoked {na.tolist()}, max sampled row err {err:.3e}", flush=True)
 
 
+@pytest.mark.parametrize("name,T", [("dsv2lite", 128), ("qwen3", 256), ("qwen15moe", 64)])
+def test_single_launch_reads_no_stale_intermediates(L, name, T):
+    """With more than 16 tokens both projections run in one launch and the down workgroups read the intermediate
+    vectors that gate/up workgroups of the same launch wrote.  Alternating two batches on ONE workspace (which
+    then always holds the other batch's intermediates) must give, bit for bit, what each batch gives on a
+    freshly zeroed workspace: a read of anything but this launch's values would differ between the two."""
+    print(f"stale-read check {name} T={T}", flush=True)
+    lay = _layer(L, name)
+    cfg, d = lay.cfg, lay.d
+    assert L.lynx_moe_ffn_launches(T, cfg.F) == 1
+    xa = to_bf16_dev(lay.tokens(T))
+    xb = to_bf16_dev(wl.make_tokens(cfg, T, host(d["Wr"]), host(d["bias"]), seed=1234))
+    (alpha, beta) = wl.PRESETS["moderate"]
+
+    def run(x, buffers):
+        b = L.lynx_moe_layer(x, d["Wr"], d["bias"], lay.Wgu, lay.Wdp, cfg.F, cfg.k, alpha, beta, 1, lay.Sgu, lay.Sdp,
+                             cfg.n_shared, cfg.F_shared, buffers=buffers)
+        torch.cuda.synchronize()
+        return host(b.y).copy()
+
+    fresh = []
+    for x in (xa, xb):
+        buf = L.LayerBuffers(T, cfg.H, cfg.F, cfg.N, cfg.k, beta, cfg.n_shared, cfg.F_shared)
+        buf.workspace.zero_()
+        fresh.append(run(x, buf))
+    assert not np.array_equal(fresh[0], fresh[1])
+    shared_buf = L.LayerBuffers(T, cfg.H, cfg.F, cfg.N, cfg.k, beta, cfg.n_shared, cfg.F_shared)
+    for rep in range(6):
+        y = run((xa, xb)[rep % 2], shared_buf)
+        assert np.array_equal(y, fresh[rep % 2]), f"repetition {rep}"
+
+
 def test_release_large_layers():
     _layers.clear()
     torch.cuda.empty_cache()
