@@ -19,7 +19,9 @@
  *  - Inputs are assumed finite.  Indices outside [0,N) in caller-provided index arrays never cause an
  *    out-of-bounds access: such pairs are skipped.
  *  - Limits: T <= LYNX_MAX_T, N <= LYNX_MAX_N, k <= LYNX_MAX_K, beta <= LYNX_MAX_BETA,
- *    H % 32 == 0, F % 32 == 0, F_shared % 32 == 0.
+ *    H % 32 == 0, F % 32 == 0, F_shared % 32 == 0 (multiples of 64 for the FP8-weight calls).
+ *  - Beyond the paper's bf16 method the header also declares a variant of the expert scorer
+ *    (lynx_affinity_bin_biased), FP8 expert weights (lynx_*_fp8) and measurement aids; each says so.
  */
 #ifndef LYNX_H
 #define LYNX_H

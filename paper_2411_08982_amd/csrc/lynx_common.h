@@ -108,13 +108,6 @@ __device__ __forceinline__ void store_coherent(uint2 *p, uint2 v)
     __hip_atomic_store(reinterpret_cast<unsigned long long *>(p), ((unsigned long long)v.y << 32) | v.x, __ATOMIC_RELAXED,
                        __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ __forceinline__ uint4 load_coherent(const uint4 *p)   // two 8-byte device-coherent loads
-{
-    const unsigned long long *q = reinterpret_cast<const unsigned long long *>(p);
-    const unsigned long long lo = __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    const unsigned long long hi = __hip_atomic_load(q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    return make_uint4((unsigned)lo, (unsigned)(lo >> 32), (unsigned)hi, (unsigned)(hi >> 32));
-}
 // All memory operations this wave has issued are complete (vmcnt, expcnt, lgkmcnt = 0).
 __device__ __forceinline__ void wait_memory_complete() { __builtin_amdgcn_s_waitcnt(0); }
 

@@ -13,8 +13,12 @@
 //     by four row tiles ("staged" path);
 //   * the grid is fixed (most experts the batch can invoke + shared experts, times row tiles); a
 //     workgroup whose rank is past the device-side num_active leaves at once, so nothing is read back
-//     to the host.
-// Launches: gate/up (with the SiLU-multiply epilogue), down, and a small combine.
+//     to the host;
+//   * gate/up (with the SiLU-multiply epilogue) and down are ONE kernel whose grid holds the workgroups of
+//     both; it is launched once (down workgroups wait for their expert's gate/up workgroups through
+//     completion counters) or once per projection, whichever measured faster for the shape;
+//   * weights are bf16 or FP8 E4M3 with one scale per row (converted to bf16 in registers).
+// Launches: the expert kernel (once or twice) and a small combine.
 
 #include "lynx_common.h"
 
@@ -26,10 +30,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 constexpr int kFfnThreads = 256;
 constexpr int kFfnWaves = kFfnThreads / kWave;
 constexpr int kPF = 8;                       // staged path: weight tiles in flight per wave and matrix
-#ifndef LYNX_PFD
-#define LYNX_PFD 8
-#endif
-constexpr int kPFD = LYNX_PFD;               // direct path: the same
+constexpr int kPFD = 8;                      // direct path: the same
 constexpr int kDirectMaxTokens = 16;         // experts with more tokens go to the staged kernel
 constexpr int kTokBlock = 64;                // tokens per pass of the staged path (batches of up to 64 tokens)
 constexpr int kTokBlockBig = 128;            // the same in the kernels launched for larger batches
@@ -264,13 +265,7 @@ __device__ __forceinline__ uint4 ring_load(const uint4 *__restrict__ base, int i
 // are invalidated when a kernel starts, a row is first touched after its expert's counter says it is complete,
 // and rows start on 128-byte lines, so no cache on the reading side can hold an older copy of a line.  (Device-
 // coherent loads instead would send every workgroup's re-reads of the same few rows to memory.)
-template <bool COH>
-__device__ __forceinline__ uint4 ring_load_b(const uint4 *__restrict__ base, int index)
-{
-    asm volatile("" : "+v"(index));
-    if (COH) return load_coherent(base + index);
-    return base[index];
-}
+__device__ __forceinline__ uint4 ring_load_b(const uint4 *__restrict__ base, int index) { return ring_load(base, index); }
 
 // The same for expert weights, as a non-temporal load: a weight byte is read once per launch, and a stream
 // that does not allocate in the caches on its way runs measurably closer to the HBM rate.
@@ -350,7 +345,7 @@ __device__ __forceinline__ void prefetch_weights(const DirectPlan &d, WeightRing
 }
 
 // The ring arrives with its first turn of weight tiles already requested (prefetch_weights).
-template <int NT, bool COH, bool W8>
+template <int NT, bool W8>
 __device__ __forceinline__ void stream_direct(const DirectPlan &d, WeightRing &r, const uint4 *const (&brow)[NT],
                                               f32x4 (&acc0)[NT], f32x4 (&acc1)[NT])
 {
@@ -367,7 +362,7 @@ __device__ __forceinline__ void stream_direct(const DirectPlan &d, WeightRing &r
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-            for (int h = 0; h < BP; ++h) bb[j][nt][h] = ring_load_b<COH>(brow[nt], s * BS + h);
+            for (int h = 0; h < BP; ++h) bb[j][nt][h] = ring_load_b(brow[nt], s * BS + h);
     }
     for (int s0 = 0; s0 < n; s0 += kPFD) {
 #pragma unroll
@@ -407,7 +402,7 @@ __device__ __forceinline__ void stream_direct(const DirectPlan &d, WeightRing &r
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-                for (int h = 0; h < BP; ++h) bb[u][nt][h] = ring_load_b<COH>(brow[nt], sn * BS + h);
+                for (int h = 0; h < BP; ++h) bb[u][nt][h] = ring_load_b(brow[nt], sn * BS + h);
             __builtin_amdgcn_sched_barrier(0);
         }
     }
@@ -443,7 +438,7 @@ __device__ __forceinline__ void expert_direct(const GemmParams &p, const WorkIte
     }
     f32x4 acc0[NT], acc1[NT];
     clear_acc<NT>(acc0, acc1);
-    stream_direct<NT, false, W8>(d, ring, brow, acc0, acc1);
+    stream_direct<NT, W8>(d, ring, brow, acc0, acc1);
     if (KW > 1) {
         f32x4 *r4 = reinterpret_cast<f32x4 *>(red);   // [rw][kw-1][NACC][lane]
         if (kw > 0) {

@@ -8,15 +8,18 @@
 // minimises dependent launches and dependent memory round trips inside them:
 //   logits_kernel         (token tile x expert group)  fp32 dot products: the router row is prefetched
 //                         into registers while the 4 tokens are staged in LDS; lanes split H; transposing
-//                         butterfly reduction.  Always its own launch (it needs the whole chip).
+//                         butterfly reduction.  Always its own launch (it needs the whole chip).  Above
+//                         128 tokens logits_mfma_kernel does the same on the fp32 matrix cores.
 //   T <= 16:  routing_small_kernel  ONE workgroup does everything else with all state in LDS: top-k,
 //                         bins + histogram, scores + score order, nominations, fill, remap, gates, counts
 //                         and (fused path) the token assignment.  Two launches for the whole routing side.
 //   T  > 16:  token_kernel -> nominate_kernel -> remap_kernel, one wave per token over many workgroups, one
 //                         launch per batch-level dependency (finished histogram; finished active set).
 //                         Scores/order and the fill are recomputed by every workgroup in its prologue
-//                         instead of costing a launch; the last workgroup of remap_kernel (atomic ticket
-//                         after a fence: nobody waits, nothing can hang) assigns the tokens.
+//                         instead of costing a launch; the last workgroup of remap_kernel (atomic ticket,
+//                         device-coherent stores and loads instead of a fence: nobody waits, nothing can
+//                         hang) assigns the tokens.
+//   lynx_affinity_bin_biased: token_kernel -> biased_remap_kernel (the score-biased selection variant).
 // Nomination: with the experts laid out across the lanes in score order, "the best-scoring expert that
 // qualifies" is a ballot followed by find-first-set.  All decisions are integer (bins from one fp32
 // subtract and one fp32 multiply, scores as base-T integers, ties to the lower expert index), so results
