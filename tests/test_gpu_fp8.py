@@ -99,6 +99,8 @@ FFN_CASES = [
     (24, 6, 3, 192, 256, 1, 128),       # staged path, single launch
     (70, 5, 2, 128, 128, 2, 64),        # more than 64 tokens: 128-token passes
     (200, 16, 4, 64, 64, 0, 0),
+    (8, 8, 2, 128, 64, 1, 256),         # shared expert wider than the routed ones: its down projection is split over K
+    (20, 8, 2, 128, 64, 1, 192),        # the same on the staged path (3 slices of one 64-column tile each)
 ]
 
 

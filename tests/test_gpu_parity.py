@@ -71,7 +71,7 @@ def test_route_ties_go_to_lower_index(L):
 BIN_CASES = [(16, 8, 2, 1.1, 0.0), (8, 8, 2, 1.1, 0.0), (32, 60, 4, 1.0, 0.0), (64, 64, 6, 0.9, 0.05),
              (128, 128, 8, 1.0, 0.0), (512, 128, 8, 1.0, 0.0), (256, 64, 6, 0.9, 0.05), (5, 6, 3, 1.0, 0.2),
              (2, 4, 2, 1.0, 0.0), (1, 8, 2, 1.0, 0.0), (33, 17, 5, 1.0, 0.1), (1024, 256, 16, 1.0, 0.0),
-             (7, 200, 16, 1.0, 0.0), (40, 10, 10, 1.0, 0.0)]
+             (7, 200, 16, 1.0, 0.0), (40, 10, 10, 1.0, 0.0), (9, 12, 1, 1.0, 0.0), (70, 12, 1, 1.0, 0.0)]
 
 
 def _check_bin(L, z, k, alpha, beta, enable):
