@@ -364,7 +364,8 @@ __device__ __forceinline__ void stream_direct(const DirectPlan &d, WeightRing &r
 #pragma unroll
             for (int h = 0; h < BP; ++h) bb[j][nt][h] = ring_load_b(brow[nt], s * BS + h);
     }
-    for (int s0 = 0; s0 < n; s0 += kPFD) {
+    // One turn of the ring: consume the kPFD slots in order, refilling each right after its last read.
+    auto turn = [&](int s0) {
 #pragma unroll
         for (int u = 0; u < kPFD; ++u) {
             const int s = s0 + u;
@@ -405,6 +406,15 @@ __device__ __forceinline__ void stream_direct(const DirectPlan &d, WeightRing &r
                 for (int h = 0; h < BP; ++h) bb[u][nt][h] = ring_load_b(brow[nt], sn * BS + h);
             __builtin_amdgcn_sched_barrier(0);
         }
+    };
+    // The first turn is peeled off the loop.  On entry the ring holds the weight loads of prefetch_weights
+    // followed by the token loads above; from the first turn on, the loads of a slot are interleaved
+    // (weights, weights, tokens).  The compiler inserts the waits for the oldest load from what may be
+    // outstanding on ANY path into a block: with the first turn inside the loop it would have to assume the
+    // entry order in every turn, and would wait until a third of the ring is left before the first slot.
+    if (n > 0) {
+        turn(0);
+        for (int s0 = kPFD; s0 < n; s0 += kPFD) turn(s0);
     }
 }
 
@@ -506,20 +516,22 @@ __device__ __forceinline__ void stream_staged(const uint4 *__restrict__ Wt, bool
     }
     const int pc0 = (tid % (KS * 4)) * 8;   // column of every piece of this thread inside a chunk (256 % (KS*4) == 0)
     uint4 xr[PPT];
-    auto load_x = [&](int c) {   // chunk c; columns past K read as zero
+    // chunk c: request it ... (nothing here reads what was loaded: a read would have to wait for the load, and
+    // with it for every weight tile requested before it)
+    auto load_x = [&](int c) {
         const int col = c * KS * 32;
-        const bool inside = col + pc0 < K;
-        const int ccol = inside ? col : 0;
+        const int ccol = col + pc0 < K ? col : 0;
 #pragma unroll
-        for (int i = 0; i < PPT; ++i)
-            xr[i] = sel4(inside && xok[i], *reinterpret_cast<const uint4 *>(B + (size_t)xoff[i] + ccol));
+        for (int i = 0; i < PPT; ++i) xr[i] = ring_load(reinterpret_cast<const uint4 *>(B + (size_t)xoff[i] + ccol), 0);
     };
+    // ... and, a chunk of weight tiles later, put it into the stage; rows without a token and columns past K as zero
     auto store_x = [&](int c) {
         char *buf = stage + (c & 1) * BUFB;
+        const bool inside = c * KS * 32 + pc0 < K;
 #pragma unroll
         for (int i = 0; i < PPT; ++i) {
             const int q = tid + kFfnThreads * i;
-            *reinterpret_cast<uint4 *>(buf + (q / (KS * 4)) * ROWB + (q % (KS * 4)) * 16) = xr[i];
+            *reinterpret_cast<uint4 *>(buf + (q / (KS * 4)) * ROWB + (q % (KS * 4)) * 16) = sel4(inside && xok[i], xr[i]);
         }
     };
 
