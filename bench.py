@@ -45,6 +45,9 @@ def parse():
                     help="resident copies of the expert weights that successive steps cycle over (0 = enough for 4 GiB)")
     ap.add_argument("--biased-gamma", type=float, default=4.0,
                     help="bias strength of the score-biased selection variant in the sweep (0 = leave it out)")
+    ap.add_argument("--layer-policy", default="",
+                    help="with --stack: a layer-adaptive remapping table such as '0-3:off,4-43:aggressive,44-47:moderate' "
+                         "(layers not named keep --preset); timed beside the uniform settings")
     ap.add_argument("--stack", type=int, default=0,
                     help="time a chained stack of this many layers (own router and weights each, x <- bf16(x + y) between "
                          "them) as a whole, eagerly and as one HIP graph, instead of the single-layer benchmark")
@@ -121,6 +124,22 @@ def preset_args(wl, preset):
     return a, b, 1
 
 
+def layer_policy(spec, n_layers, default_preset):
+    """'0-3:off,4-43:aggressive,44:moderate' -> one preset name per layer (paper Sec. 3.2.1: sensitivity to the
+    remap differs between layers, so the policy may; the paper gives no rule, the table is the caller's)."""
+    names = [default_preset] * n_layers
+    for part in filter(None, (q.strip() for q in spec.split(","))):
+        rng, _, preset = part.partition(":")
+        if preset not in ("off", "moderate", "aggressive"):
+            raise ValueError(f"--layer-policy: unknown preset in '{part}'")
+        lo, _, hi = rng.partition("-")
+        lo, hi = int(lo), int(hi) if hi else int(lo)
+        if not 0 <= lo <= hi < n_layers:
+            raise ValueError(f"--layer-policy: layers '{rng}' outside 0..{n_layers - 1}")
+        names[lo:hi + 1] = [preset] * (hi - lo + 1)
+    return names
+
+
 def run_stack(args, cfg, wl, torch):
     """A stack of layers on one stream with a true dependency from each layer to the next, timed as a whole."""
     import numpy as np
@@ -128,6 +147,8 @@ def run_stack(args, cfg, wl, torch):
     import paper_2411_08982_amd as L
     T, n_layers = args.tokens, args.stack
     alpha, beta, enable = preset_args(wl, args.preset)
+    table = layer_policy(args.layer_policy, n_layers, args.preset) if args.layer_policy else None
+    betas = sorted({beta} | {preset_args(wl, n)[1] for n in (table or []) if n != "off"})
     layers, bufs = [], []
     x0 = None
     for l in range(n_layers):
@@ -138,16 +159,23 @@ def run_stack(args, cfg, wl, torch):
             Sgu, Sdp = L.lynx_pack_weights(d["Sg"], d["Su"], d["Sd"])
         torch.cuda.synchronize()
         layers.append((d["Wr"], d["bias"], Wgu, Wdp, Sgu, Sdp))
-        bufs.append(L.LayerBuffers(T, cfg.H, cfg.F, cfg.N, cfg.k, beta, cfg.n_shared, cfg.F_shared))
+        bufs.append({bt: L.LayerBuffers(T, cfg.H, cfg.F, cfg.N, cfg.k, bt, cfg.n_shared, cfg.F_shared) for bt in betas})
         if l == 0:
             x0 = d["x"]
         del d
     xs = [x0] + [torch.empty_like(x0) for _ in range(n_layers)]
 
+    used = [None] * n_layers   # the buffers the last chain wrote, per layer
+
     def chain(en):
+        """en: 0 / 1 = remap off / the preset in every layer; "table" = the per-layer table."""
         for l, (Wr, bias, Wgu, Wdp, Sgu, Sdp) in enumerate(layers):
-            b = L.lynx_moe_layer(xs[l], Wr, bias, Wgu, Wdp, cfg.F, cfg.k, alpha, beta, en, Sgu, Sdp, cfg.n_shared,
-                                 cfg.F_shared, buffers=bufs[l])
+            a_l, b_l, e_l = (alpha, beta, en)
+            if en == "table":   # a layer that is switched off keeps the default preset's bins (they are not used)
+                a_l, b_l, e_l = preset_args(wl, table[l]) if table[l] != "off" else (alpha, beta, 0)
+            b = L.lynx_moe_layer(xs[l], Wr, bias, Wgu, Wdp, cfg.F, cfg.k, a_l, b_l, e_l, Sgu, Sdp, cfg.n_shared,
+                                 cfg.F_shared, buffers=bufs[l][b_l])
+            used[l] = b
             L.lynx_residual_add(xs[l], b.y, out=xs[l + 1])
 
     def timed(fn, reps):
@@ -161,7 +189,7 @@ def run_stack(args, cfg, wl, torch):
         return us[len(us) // 2], us[0]
 
     res = {}
-    for name, en in (("off", 0), (args.preset, enable)):
+    for name, en in (("off", 0), (args.preset, enable)) + ((("layer_policy", "table"),) if table else ()):
         if name in res:
             continue
         for _ in range(max(1, args.warmup)):
@@ -173,7 +201,7 @@ def run_stack(args, cfg, wl, torch):
         torch.cuda.synchronize()
         wall_us = (time.perf_counter() - t0) * 1e6 / args.steps
         eager_med, eager_min = timed(lambda: chain(en), args.steps)
-        na = np.array([b.num_active.cpu().numpy() for b in bufs])
+        na = np.array([b.num_active.cpu().numpy() for b in used])
         routed = float(na[:, 1].sum()) * 3 * cfg.H * cfg.F * 2 + n_layers * cfg.n_shared * 3 * cfg.H * cfg.F_shared * 2
         # the same chain as one HIP graph (the library enqueues kernels only: no allocation, memset or host read)
         g = torch.cuda.CUDAGraph()
@@ -203,7 +231,7 @@ def run_stack(args, cfg, wl, torch):
                       "tokens": T, "alpha": alpha, "beta": beta, "layers": n_layers},
            "us_per_layer": round(best["us_graph_median"] / n_layers, 2),
            "tokens_per_s": round(T / (best["us_graph_median"] * 1e-6), 1),
-           "stack": res,
+           "stack": res, "layer_policy": args.layer_policy or None,
            "roofline": {"bound": "hbm", "kernel": "whole stack (all kernels of all layers)", "achieved": best["expert_weight_GBps_graph"],
                         "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(best["expert_weight_GBps_graph"] / HBM_PEAK_GBPS, 4),
                         "traffic": None}}

@@ -25,3 +25,17 @@ def test_expert_bytes_match_the_shapes():
     gu, dn = bench.expert_bytes(cfg, 10)
     per_expert = 3 * cfg.H * cfg.F * 2
     assert gu + dn == 10 * per_expert + cfg.n_shared * 3 * cfg.H * cfg.F_shared * 2
+
+
+def test_layer_policy_table():
+    sys.path.insert(0, ROOT)
+    import pytest
+
+    import bench
+    names = bench.layer_policy("0-3:off,4-43:aggressive,44-47:moderate", 48, "aggressive")
+    assert names[:4] == ["off"] * 4 and names[4:44] == ["aggressive"] * 40 and names[44:] == ["moderate"] * 4
+    assert bench.layer_policy("", 3, "moderate") == ["moderate"] * 3          # layers not named keep the preset
+    assert bench.layer_policy("2:off", 4, "moderate") == ["moderate", "moderate", "off", "moderate"]
+    for bad in ("0-9:off", "1:sometimes", "3-1:off"):
+        with pytest.raises(ValueError):
+            bench.layer_policy(bad, 4, "off")

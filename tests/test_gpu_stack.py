@@ -31,8 +31,11 @@ def L():
 class Stack:
     """`n_layers` small layers with their own routers and expert weights, resident on the GPU."""
 
-    def __init__(self, L, cfg, T, n_layers, alpha, beta):
-        self.L, self.cfg, self.T, self.alpha, self.beta = L, cfg, T, alpha, beta
+    def __init__(self, L, cfg, T, n_layers, alpha, beta, policy=None):
+        self.L, self.cfg, self.T = L, cfg, T
+        # per-layer (alpha, beta, enable): the remapping policy may differ from layer to layer (paper Sec. 3.2.1,
+        # layer sensitivity); one setting for all layers by default
+        self.policy = list(policy) if policy else [(alpha, beta, 1)] * n_layers
         self.host_layers = [wl.make_layer(cfg, T, layer=l) for l in range(n_layers)]
         self.dev_layers = []
         for d in self.host_layers:
@@ -43,7 +46,8 @@ class Stack:
             self.dev_layers.append((dev(d["Wr"]), dev(d["bias"]), Wgu, Wdp, Sgu, Sdp))
         self.x0 = to_bf16_dev(self.host_layers[0]["x"])
         # every layer has its own outputs (kept for the checks) and its own input buffer
-        self.buf = [L.LayerBuffers(T, cfg.H, cfg.F, cfg.N, cfg.k, beta, cfg.n_shared, cfg.F_shared) for _ in range(n_layers)]
+        self.buf = [L.LayerBuffers(T, cfg.H, cfg.F, cfg.N, cfg.k, self.policy[l][1], cfg.n_shared, cfg.F_shared)
+                    for l in range(n_layers)]
         self.x = [self.x0] + [torch.empty_like(self.x0) for _ in range(n_layers)]
         torch.cuda.synchronize()
 
@@ -51,7 +55,8 @@ class Stack:
         """Enqueues the whole chain on the current stream; allocates nothing."""
         c = self.cfg
         for l, (Wr, bias, Wgu, Wdp, Sgu, Sdp) in enumerate(self.dev_layers):
-            b = self.L.lynx_moe_layer(self.x[l], Wr, bias, Wgu, Wdp, c.F, c.k, self.alpha, self.beta, 1, Sgu, Sdp,
+            alpha, beta, enable = self.policy[l]
+            b = self.L.lynx_moe_layer(self.x[l], Wr, bias, Wgu, Wdp, c.F, c.k, alpha, beta, enable, Sgu, Sdp,
                                       c.n_shared, c.F_shared, buffers=self.buf[l])
             self.L.lynx_residual_add(self.x[l], b.y, out=self.x[l + 1])
 
@@ -78,26 +83,33 @@ def test_residual_add_is_one_rounded_fp32_addition(L):
         assert np.array_equal(bf16_bits(x), want)
 
 
+# one setting for every layer, and a layer-adaptive table: off, moderate, aggressive, and a wide three-bin setting
+POLICIES = {"uniform": None, "per-layer": [(2.0, 2, 0), (2.0, 2, 1), (4.0, 1, 1), (1.0, 3, 1)]}
+
+
+@pytest.mark.parametrize("policy", list(POLICIES))
 @pytest.mark.parametrize("T,shared", [(8, 0), (24, 1)])
-def test_stack_parity_layer_by_layer(L, T, shared):
-    print(f"stack of 4 layers, T={T}, shared={shared}", flush=True)
+def test_stack_parity_layer_by_layer(L, T, shared, policy):
+    print(f"stack of 4 layers, T={T}, shared={shared}, policy={policy}", flush=True)
     cfg = dataclasses.replace(wl.CONFIGS["tiny"], name="stack", H=256, F=384, N=24, k=3, n_shared=shared,
                               F_shared=128 if shared else 0, seed=11)
-    alpha, beta = 2.0, 2
-    st = Stack(L, cfg, T, 4, alpha, beta)
+    st = Stack(L, cfg, T, 4, 2.0, 2, POLICIES[policy])
     st.run()
     torch.cuda.synchronize()
     remapped = 0
     for l, d in enumerate(st.host_layers):
+        alpha, beta, enable = st.policy[l]
         xb = bf16_bits(st.x[l])                     # the GPU's own input of this layer
         b = st.buf[l]
         z = host(b.logits)
         r = oracle.route(xb, d["Wr"], d["bias"], cfg.k)
         assert np.all(np.abs(z - r["logits"]) <= 1e-5 * np.maximum(1.0, np.abs(r["logits"])))
         tk = oracle.topk(z, cfg.k)
-        a = oracle.affinity_bin(z, tk["idx"], alpha, beta, 1)
+        a = oracle.affinity_bin(z, tk["idx"], alpha, beta, enable)
         assert np.array_equal(host(b.new_idx), a["new_idx"])
         assert np.array_equal(host(b.num_active), a["num_active"])
+        if not enable:
+            assert np.array_equal(a["new_idx"], tk["idx"])
         p = oracle.permute(a["new_idx"], cfg.N)
         assert np.array_equal(host(b.perm), p["perm"]) and np.array_equal(host(b.offsets), p["offsets"])
         y_ref = oracle.moe_ffn(xb, d["Wg"], d["Wu"], d["Wd"], a["new_idx"], a["new_gate"], d.get("Sg"), d.get("Su"),
