@@ -873,11 +873,12 @@ static int pick_k_waves(int K, bool dual, int T, int max_experts, int bytes_per_
     // of 32 rows per workgroup cover exactly one (workgroups that only exist to be told they have nothing to
     // do are expensive).
     if (T > kDirectMaxTokens) return 2;
-    // Down, direct path only.  Measured: splitting K pays when the batch can invoke so few experts that
-    // whole row groups would leave the chip with too few, too long workgroups (Mixtral-like shapes); with
-    // many small experts the short streams cost more than the finer granularity gains.
+    // Down, direct path only.  Measured: splitting K four ways pays when the batch can invoke so few experts
+    // that whole row groups would leave the chip with too few, too long workgroups (Mixtral-like shapes); with
+    // more experts two ways (64-row workgroups: 4-5 % faster than 128-row ones for DeepSeek-V2-Lite and
+    // Qwen1.5-MoE shapes), unless the streams would get too short.
     const long group_bytes = (long)16 * K * 2 * bytes_per_weight;         // weight bytes behind one row group
-    int kw = max_experts <= 8 ? 4 : max_experts <= 16 ? 2 : 1;
+    int kw = max_experts <= 8 ? 4 : 2;
     while (kw > 1 && group_bytes / kw < 32 * 1024) kw >>= 1;              // keep at least 32 KiB per wave
     return kw;
 }
