@@ -57,6 +57,12 @@ def _load():
         lib.orc_e4m3_encode.argtypes = [c_float]
         lib.orc_e4m3_encode.restype = ctypes.c_uint8
         lib.orc_quantize_rows_e4m3.argtypes = [u16p, ctypes.c_long, c_int, u8p, f32p]
+        lib.orc_e2m1_decode.argtypes = [ctypes.c_uint8]
+        lib.orc_e2m1_decode.restype = c_double
+        lib.orc_e2m1_encode.argtypes = [c_float]
+        lib.orc_e2m1_encode.restype = ctypes.c_uint8
+        lib.orc_quantize_mxfp4.argtypes = [u16p, ctypes.c_long, c_int, u8p, u8p]
+        lib.orc_dequantize_mxfp4.argtypes = [u8p, u8p, ctypes.c_long, c_int, u16p]
         lib.orc_quantize_rows_e4m3.restype = c_int
         lib.orc_moe_ffn_q8.argtypes = [u16p, u8p, u8p, u8p, f32p, f32p, f32p, u8p, u8p, u8p, f32p, f32p, f32p, c_int, c_int,
                                        i32p, f64p, c_int, c_int, c_int, c_int, c_int, f64p]
@@ -281,3 +287,54 @@ def moe_ffn_q8(x_bf16, Qg, Qu, Qd, sg, su, sd, idx, gate, SQg=None, SQu=None, SQ
     if rc != OK:
         raise OracleError(rc, "orc_moe_ffn_q8")
     return y
+
+
+def e2m1_decode(codes):
+    """4-bit E2M1 codes (uint8, low nibble; any shape) -> float64 values."""
+    c = np.ascontiguousarray(codes, dtype=np.uint8)
+    lib = _load()
+    return np.array([lib.orc_e2m1_decode(int(v)) for v in c.ravel()], np.float64).reshape(c.shape)
+
+
+def e2m1_encode(values):
+    """float32 values (any shape) -> nearest E2M1 codes (ties to the even code, saturating at +-6)."""
+    v = np.ascontiguousarray(values, dtype=np.float32)
+    lib = _load()
+    return np.array([lib.orc_e2m1_encode(float(x)) for x in v.ravel()], np.uint8).reshape(v.shape)
+
+
+def quantize_mxfp4(W_bf16):
+    """bf16 bits [..., K] (K a multiple of 32) -> (codes uint8 [..., K], one E2M1 code per byte; scale exponents
+    uint8 [..., K/32], E8M0): per block of 32, E - 127 = floor(log2(amax)) - 2."""
+    W = _arr(W_bf16, np.uint16)
+    K = W.shape[-1]
+    rows = W.size // K
+    codes = np.zeros(W.shape, np.uint8)
+    scales = np.zeros(W.shape[:-1] + (K // 32,), np.uint8)
+    u8p = lambda a: a.ctypes.data_as(POINTER(ctypes.c_uint8))
+    rc = _load().orc_quantize_mxfp4(_p(W, c_uint16), rows, K, u8p(codes), u8p(scales))
+    if rc != OK:
+        raise OracleError(rc, "orc_quantize_mxfp4")
+    return codes, scales
+
+
+def dequantize_mxfp4(codes, scales):
+    """(codes [..., K], scale exponents [..., K/32]) -> the bf16 bits of decode(code) * 2^(E - 127), exactly."""
+    c = np.ascontiguousarray(codes, dtype=np.uint8)
+    s = np.ascontiguousarray(scales, dtype=np.uint8)
+    K = c.shape[-1]
+    rows = c.size // K
+    W = np.zeros(c.shape, np.uint16)
+    u8p = lambda a: a.ctypes.data_as(POINTER(ctypes.c_uint8))
+    rc = _load().orc_dequantize_mxfp4(u8p(c), u8p(s), rows, K, _p(W, c_uint16))
+    if rc != OK:
+        raise OracleError(rc, "orc_dequantize_mxfp4")
+    return W
+
+
+def moe_ffn_q4(x_bf16, Qg, Qu, Qd, eg, eu, ed, idx, gate, SQg=None, SQu=None, SQd=None, seg=None, seu=None, sed=None):
+    """moe_ffn with MXFP4 weights (codes Q*, scale exponents e*; shared experts SQ*, se*): the dequantised weights
+    are bf16 numbers, so this is moe_ffn over them."""
+    dq = dequantize_mxfp4
+    shared = (None, None, None) if SQg is None else (dq(SQg, seg), dq(SQu, seu), dq(SQd, sed))
+    return moe_ffn(x_bf16, dq(Qg, eg), dq(Qu, eu), dq(Qd, ed), idx, gate, *shared)

@@ -667,3 +667,89 @@ int orc_moe_ffn_q8(const uint16_t *x_bf16, const uint8_t *Qg, const uint8_t *Qu,
     free(xs);
     return ORC_OK;
 }
+
+/* ------------------------------------------------------------------------------------------------------------
+ * Expert weights in 4-bit floating point with shared block scales, weight-only: the OCP Microscaling format
+ * MXFP4.  Elements are FP4 E2M1 (1 sign, 2 exponent bits with bias 1, 1 mantissa bit: magnitudes 0, 0.5, 1, 1.5,
+ * 2, 3, 4, 6; no infinities, no NaN); every block of 32 consecutive elements of a weight-matrix row shares one
+ * scale X = 2^(E - 127), stored as the 8-bit exponent E (E8M0; 255 = NaN, not produced here).  The weight a
+ * code stands for is decode(code) * X: a power of two times a two-bit significand, hence exactly a bf16 number,
+ * so the FFN over MXFP4 weights IS the bf16 FFN (orc_moe_ffn) over the dequantised weights.
+ * ------------------------------------------------------------------------------------------------------------ */
+
+static const double kE2M1[8] = {0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0};
+
+/* Value of an E2M1 code (low four bits of c). */
+double orc_e2m1_decode(uint8_t c)
+{
+    const double v = kE2M1[c & 7];
+    return (c & 8) ? -v : v;
+}
+
+/* Nearest E2M1 code of v: ties to the even code, magnitudes above 6 to +-6 (NaN to +-6 as well: the format has
+ * no NaN). */
+uint8_t orc_e2m1_encode(float v)
+{
+    const uint8_t sgn = signbit(v) ? 8 : 0;
+    if (isnan(v)) return (uint8_t)(sgn | 7);
+    const double a = fabs((double)v);
+    if (a >= 6.0) return (uint8_t)(sgn | 7); /* saturation (also keeps the distances below exact for huge a) */
+    int best = 0;
+    for (int c = 1; c < 8; ++c) {
+        const double d = fabs(a - kE2M1[c]), db = fabs(a - kE2M1[best]);
+        if (d < db || (d == db && (c & 1) == 0)) best = c;
+    }
+    return (uint8_t)(sgn | best);
+}
+
+/*
+ * Block quantisation of bf16 weights W [rows, K], K a multiple of 32, as the MX specification's conversion: per
+ * block of 32, E - 127 = floor(log2(max |w|)) - 2 (2 = exponent of the largest E2M1 magnitude, 6 = 1.5 * 2^2),
+ * clamped to the E8M0 range; an all-zero block gets X = 1; code = encode(w / X), which saturates the part of the
+ * block above 6 X.  codes: one code per byte [rows, K]; scales: E [rows, K/32].
+ */
+int orc_quantize_mxfp4(const uint16_t *W_bf16, long rows, int K, uint8_t *codes, uint8_t *scales)
+{
+    if (rows < 0 || K <= 0 || (K % 32) != 0) return ORC_ERR_INVALID_ARG;
+    const int nb = K / 32;
+    for (long r = 0; r < rows; ++r)
+        for (int b = 0; b < nb; ++b) {
+            const uint16_t *w = W_bf16 + (size_t)r * K + (size_t)b * 32;
+            double amax = 0.0;
+            for (int i = 0; i < 32; ++i) {
+                const double a = fabs(bf16_to_f64(w[i]));
+                if (a > amax) amax = a;
+            }
+            int E = 127;
+            if (amax > 0.0) {
+                int ex;
+                (void)frexp(amax, &ex); /* amax = fr * 2^ex with fr in [0.5, 1): floor(log2 amax) = ex - 1 */
+                E = (ex - 1) - 2 + 127;
+                if (E < 0) E = 0;
+                if (E > 254) E = 254;
+            }
+            scales[(size_t)r * nb + b] = (uint8_t)E;
+            for (int i = 0; i < 32; ++i)
+                codes[(size_t)r * K + (size_t)b * 32 + i] = orc_e2m1_encode((float)ldexp(bf16_to_f64(w[i]), 127 - E));
+        }
+    return ORC_OK;
+}
+
+/* The bf16 weights that codes and scales stand for (exact; fails if a product is not a bf16 number). */
+int orc_dequantize_mxfp4(const uint8_t *codes, const uint8_t *scales, long rows, int K, uint16_t *W_bf16)
+{
+    if (rows < 0 || K <= 0 || (K % 32) != 0) return ORC_ERR_INVALID_ARG;
+    const int nb = K / 32;
+    for (long r = 0; r < rows; ++r)
+        for (int i = 0; i < K; ++i) {
+            const int E = scales[(size_t)r * nb + i / 32];
+            if (E == 255) return ORC_ERR_INVALID_ARG;
+            const double v = ldexp(orc_e2m1_decode(codes[(size_t)r * K + i]), E - 127);
+            const float f = (float)v;
+            uint32_t u;
+            memcpy(&u, &f, 4);
+            if ((double)f != v || (u & 0xffffu) != 0 || isinf(f)) return ORC_ERR_INVALID_ARG;
+            W_bf16[(size_t)r * K + i] = (uint16_t)(u >> 16);
+        }
+    return ORC_OK;
+}
