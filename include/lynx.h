@@ -19,9 +19,9 @@
  *  - Inputs are assumed finite.  Indices outside [0,N) in caller-provided index arrays never cause an
  *    out-of-bounds access: such pairs are skipped.
  *  - Limits: T <= LYNX_MAX_T, N <= LYNX_MAX_N, k <= LYNX_MAX_K, beta <= LYNX_MAX_BETA,
- *    H % 32 == 0, F % 32 == 0, F_shared % 32 == 0 (multiples of 64 for the FP8-weight calls).
+ *    H % 32 == 0, F % 32 == 0, F_shared % 32 == 0 (multiples of 64 for the FP8-weight calls, of 128 for MXFP4).
  *  - Beyond the paper's bf16 method the header also declares a variant of the expert scorer
- *    (lynx_affinity_bin_biased), FP8 expert weights (lynx_*_fp8) and measurement aids; each says so.
+ *    (lynx_affinity_bin_biased), FP8 and MXFP4 expert weights (lynx_*_fp8, lynx_*_fp4) and measurement aids; each says so.
  */
 #ifndef LYNX_H
 #define LYNX_H
@@ -207,6 +207,49 @@ int lynx_moe_layer_fp8(const uint16_t *x_bf16, const float *Wr, const float *bia
                        int F_shared, int T, int H, int F, int N, int k, float alpha, int beta, int enable, float *logits,
                        int32_t *topk_idx, float *topk_gate, float *topk_psum, int32_t *new_idx, float *new_gate,
                        int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist, int32_t *num_active,
+                       int32_t *expert_offsets, int32_t *perm, int32_t *active_experts, int32_t *num_active_perm,
+                       float *y, void *workspace, void *stream, void *const *stage_events);
+
+/*
+ * Expert weights in 4-bit floating point with shared block scales, weight-only (the same widening, a quarter of the
+ * bf16 bytes plus 1/32 for the scales): the OCP Microscaling format MXFP4.  Elements are FP4 E2M1 (magnitudes 0,
+ * 0.5, 1, 1.5, 2, 3, 4, 6); each block of 32 consecutive columns of a weight-matrix row shares the scale
+ * 2^(E - 127), E an 8-bit exponent.  Conversion as in the MX specification: E - 127 = floor(log2(amax(block))) - 2,
+ * clamped to [0, 254] (E = 127 for an all-zero block); code = nearest E2M1 value of w / 2^(E - 127), ties to the even
+ * code, magnitudes above 6 to 6.  A code times its scale is exactly a bf16 number, so the FFN is the bf16 FFN over
+ * the dequantised weights.  (Blocks whose largest magnitude is below 2^-124 are outside the tested range.)
+ * lynx_quantize_weights_fp4 quantises row-major bf16 weights (as for lynx_pack_weights; H and F multiples of 128)
+ * straight into the streaming layout:
+ *   Wgu_q [E][F/16][H/128][2][64][16] bytes, Wd_q [E][H/16][F/128][64][16] bytes (a 1 KiB tile = 16 rows x 128
+ *   columns: lane l = row l%16, columns (l/16)*32 .. +31, byte j = columns 2j (low nibble) and 2j+1);
+ *   scales_gu [E][F/16][ceil(H/128 / 4)][64][2] dwords (lane, then gate|up; byte i of a dword = k-tile 4j+i),
+ *   scales_d [E][H/32][ceil(F/128 / 4)][64][2] dwords (lane, then the first|second row tile of the row pair).
+ * lynx_fp4_scale_words(E, rows, K, gate_up) gives the dword count of such a scale array (rows = F, K = H, gate_up
+ * = 1 for scales_gu; rows = H, K = F, gate_up = 0 for scales_d).  All DEVICE.
+ */
+size_t lynx_fp4_scale_words(int E, int rows, int K, int gate_up);
+int lynx_quantize_weights_fp4(const uint16_t *Wg, const uint16_t *Wu, const uint16_t *Wd, int E, int H, int F,
+                              uint8_t *Wgu_q, uint8_t *Wd_q, uint32_t *scales_gu, uint32_t *scales_d, void *stream);
+
+/*
+ * lynx_moe_ffn_timed with MXFP4 weights: the codes are converted to bf16, times their block scale, in registers
+ * (exact) and multiplied on the same bf16 MFMA path.  Shared experts: Sgu_q, Sd_q and their scale arrays in the
+ * same layouts with E = n_shared, F = F_shared (NULL if n_shared == 0).  H, F, F_shared multiples of 128.
+ */
+int lynx_moe_ffn_fp4(const uint16_t *x_bf16, const uint8_t *Wgu_q, const uint8_t *Wd_q, const uint32_t *scales_gu,
+                     const uint32_t *scales_d, const uint8_t *Sgu_q, const uint8_t *Sd_q,
+                     const uint32_t *shared_scales_gu, const uint32_t *shared_scales_d, int n_shared, int F_shared,
+                     const int32_t *idx, const float *gate, const int32_t *expert_offsets, const int32_t *perm,
+                     const int32_t *active_experts, const int32_t *num_active, int T, int H, int F, int N, int k,
+                     float *y, void *workspace, void *stream, void *const *stage_events);
+
+/* lynx_moe_layer with MXFP4 expert weights (routing unchanged). */
+int lynx_moe_layer_fp4(const uint16_t *x_bf16, const float *Wr, const float *bias, const uint8_t *Wgu_q,
+                       const uint8_t *Wd_q, const uint32_t *scales_gu, const uint32_t *scales_d, const uint8_t *Sgu_q,
+                       const uint8_t *Sd_q, const uint32_t *shared_scales_gu, const uint32_t *shared_scales_d,
+                       int n_shared, int F_shared, int T, int H, int F, int N, int k, float alpha, int beta, int enable,
+                       float *logits, int32_t *topk_idx, float *topk_gate, float *topk_psum, int32_t *new_idx,
+                       float *new_gate, int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist, int32_t *num_active,
                        int32_t *expert_offsets, int32_t *perm, int32_t *active_experts, int32_t *num_active_perm,
                        float *y, void *workspace, void *stream, void *const *stage_events);
 

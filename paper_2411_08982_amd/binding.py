@@ -21,7 +21,8 @@ MAX_T, MAX_N, MAX_K, MAX_BETA = 1024, 256, 16, 6
 
 SYMBOLS = ["lynx_last_error", "lynx_workspace_bytes", "lynx_route", "lynx_affinity_bin", "lynx_affinity_bin_biased", "lynx_permute",
            "lynx_pack_weights", "lynx_moe_ffn", "lynx_moe_ffn_timed", "lynx_moe_layer", "lynx_moe_ffn_launches", "lynx_residual_add", "lynx_read_probe",
-           "lynx_quantize_weights_fp8", "lynx_moe_ffn_fp8", "lynx_moe_layer_fp8"]
+           "lynx_quantize_weights_fp8", "lynx_moe_ffn_fp8", "lynx_moe_layer_fp8",
+           "lynx_fp4_scale_words", "lynx_quantize_weights_fp4", "lynx_moe_ffn_fp4", "lynx_moe_layer_fp4"]
 
 
 class LynxError(RuntimeError):
@@ -58,10 +59,15 @@ def lib():
         L.lynx_quantize_weights_fp8.argtypes = [P, P, P, I, I, I, P, P, P, P, P]
         L.lynx_moe_ffn_fp8.argtypes = [P] * 9 + [I, I] + [P] * 6 + [I] * 5 + [P, P, P, ctypes.POINTER(c_void_p)]
         L.lynx_moe_layer_fp8.argtypes = [P] * 11 + [I] * 7 + [F, I, I] + [P] * 17 + [ctypes.POINTER(c_void_p)]
+        L.lynx_fp4_scale_words.argtypes = [I, I, I, I]
+        L.lynx_quantize_weights_fp4.argtypes = L.lynx_quantize_weights_fp8.argtypes
+        L.lynx_moe_ffn_fp4.argtypes = L.lynx_moe_ffn_fp8.argtypes
+        L.lynx_moe_layer_fp4.argtypes = L.lynx_moe_layer_fp8.argtypes
         L.lynx_moe_ffn_launches.argtypes = [I, I]
         L.lynx_residual_add.argtypes = [P, P, c_size_t, P, P]
         for name in SYMBOLS[2:]:
             getattr(L, name).restype = c_int
+        L.lynx_fp4_scale_words.restype = c_size_t
         _lib = L
     return _lib
 
@@ -323,6 +329,78 @@ def lynx_moe_layer_fp8(x, Wr, bias, q, F, k, alpha, beta, enable=1, shared=None,
     a_, b_, c_, d_ = _fp8_ptrs(q)
     sa, sb, sc, sd = _fp8_ptrs(shared)
     _check(lib().lynx_moe_layer_fp8(
+        _ptr(x, BF16, "x"), _ptr(Wr, F32, "Wr"), _ptr(bias, F32, "bias"), a_, b_, c_, d_, sa, sb, sc, sd, n_shared, F_shared,
+        T, H, F, N, k, float(alpha), int(beta), int(enable), b.logits.data_ptr(), b.topk_idx.data_ptr(),
+        b.topk_gate.data_ptr(), b.topk_psum.data_ptr(), b.new_idx.data_ptr(), b.new_gate.data_ptr(),
+        b.cnt_before.data_ptr(), b.cnt_after.data_ptr(), b.bin_hist.data_ptr(), b.num_active.data_ptr(),
+        b.offsets.data_ptr(), b.perm.data_ptr(), b.active.data_ptr(), b.num_active_perm.data_ptr(), b.y.data_ptr(),
+        b.workspace.data_ptr(), _stream(),
+        None if stage_events is None else (c_void_p * 4)(*[e.cuda_event for e in stage_events])))
+    return b
+
+
+class Fp4Weights:
+    """MXFP4 expert weights of one set of experts in the streaming layout: packed E2M1 codes (uint8) and the
+    block-scale exponents (int32 words of four E8M0 bytes)."""
+
+    def __init__(self, Wgu_q, Wd_q, scales_gu, scales_d):
+        self.Wgu_q, self.Wd_q, self.scales_gu, self.scales_d = Wgu_q, Wd_q, scales_gu, scales_d
+
+
+def lynx_quantize_weights_fp4(Wg, Wu, Wd) -> Fp4Weights:
+    """Wg, Wu [E,F,H], Wd [E,H,F] bf16 row-major (H, F multiples of 128) -> Fp4Weights."""
+    E, Fdim, H = Wg.shape
+    dev = Wg.device
+    kt4 = lambda K: (K // 128 + 3) // 4
+    Wgu_q = torch.empty((E, Fdim // 16, H // 128, 2, 64, 16), dtype=U8, device=dev)
+    Wd_q = torch.empty((E, H // 16, Fdim // 128, 64, 16), dtype=U8, device=dev)
+    sgu = torch.zeros((E, Fdim // 16, kt4(H), 64, 2), dtype=I32, device=dev)
+    sd = torch.zeros((E, H // 32, kt4(Fdim), 64, 2), dtype=I32, device=dev)
+    if E and (H % 128 == 0) and (Fdim % 128 == 0):
+        assert lib().lynx_fp4_scale_words(E, Fdim, H, 1) == sgu.numel() and lib().lynx_fp4_scale_words(E, H, Fdim, 0) == sd.numel()
+    _check(lib().lynx_quantize_weights_fp4(_ptr(Wg, BF16, "Wg"), _ptr(Wu, BF16, "Wu"), _ptr(Wd, BF16, "Wd"), E, H, Fdim,
+                                           Wgu_q.data_ptr(), Wd_q.data_ptr(), sgu.data_ptr(), sd.data_ptr(), _stream()))
+    return Fp4Weights(Wgu_q, Wd_q, sgu, sd)
+
+
+def _fp4_ptrs(q):
+    if q is None:
+        return (None, None, None, None)
+    return (_ptr(q.Wgu_q, U8, "Wgu_q"), _ptr(q.Wd_q, U8, "Wd_q"), _ptr(q.scales_gu, I32, "scales_gu"),
+            _ptr(q.scales_d, I32, "scales_d"))
+
+
+def lynx_moe_ffn_fp4(x, q, idx, gate, perm_out, N, F, shared=None, n_shared=0, F_shared=0, workspace=None, y=None,
+                     stage_events=None):
+    """lynx_moe_ffn with MXFP4 weights: q, shared = Fp4Weights of the routed / shared experts."""
+    T, H = x.shape
+    k = idx.shape[1]
+    if workspace is None:
+        workspace = new_workspace(T, H, F, N, k, n_shared, F_shared, x.device)
+    if y is None:
+        y = torch.empty((T, H), dtype=F32, device=x.device)
+    a, b, c, d = _fp4_ptrs(q)
+    sa, sb, sc, sd = _fp4_ptrs(shared)
+    ev = None if stage_events is None else (c_void_p * 4)(*[e.cuda_event for e in stage_events])
+    _check(lib().lynx_moe_ffn_fp4(_ptr(x, BF16, "x"), a, b, c, d, sa, sb, sc, sd, n_shared, F_shared, _ptr(idx, I32, "idx"),
+                                  _ptr(gate, F32, "gate"), _ptr(perm_out["offsets"], I32, "offsets"),
+                                  _ptr(perm_out["perm"], I32, "perm"), _ptr(perm_out["active"], I32, "active"),
+                                  _ptr(perm_out["num_active"], I32, "num_active"), T, H, F, N, k, _ptr(y, F32, "y"),
+                                  workspace.data_ptr(), _stream(), ev))
+    return y
+
+
+def lynx_moe_layer_fp4(x, Wr, bias, q, F, k, alpha, beta, enable=1, shared=None, n_shared=0, F_shared=0,
+                       buffers: LayerBuffers | None = None, stage_events=None):
+    """lynx_moe_layer with MXFP4 expert weights.  Returns the LayerBuffers."""
+    T, H = x.shape
+    N = Wr.shape[0]
+    b = buffers or LayerBuffers(T, H, F, N, k, beta, n_shared, F_shared, x.device)
+    if b.sizes != (T, H, F, N, k, n_shared, F_shared) or b.beta != beta:
+        raise ValueError("buffers were allocated for other sizes")
+    a_, b_, c_, d_ = _fp4_ptrs(q)
+    sa, sb, sc, sd = _fp4_ptrs(shared)
+    _check(lib().lynx_moe_layer_fp4(
         _ptr(x, BF16, "x"), _ptr(Wr, F32, "Wr"), _ptr(bias, F32, "bias"), a_, b_, c_, d_, sa, sb, sc, sd, n_shared, F_shared,
         T, H, F, N, k, float(alpha), int(beta), int(enable), b.logits.data_ptr(), b.topk_idx.data_ptr(),
         b.topk_gate.data_ptr(), b.topk_psum.data_ptr(), b.new_idx.data_ptr(), b.new_gate.data_ptr(),

@@ -82,7 +82,7 @@ static int moe_layer_impl(const uint16_t *x_bf16, const float *Wr, const float *
         if (F <= 0 || n_shared < 0 || !Wgu_packed || !Wd_packed || !y ||
             (n_shared > 0 && (F_shared <= 0 || !Sgu_packed || !Sd_packed)))
             return fail(LYNX_ERR_INVALID_ARG, "lynx_moe_layer: bad FFN size or null weight / output pointer");
-        const int mult = q8 ? 64 : 32;
+        const int mult = q8 ? 32 << q8->format : 32;
         if ((H % mult) != 0 || (F % mult) != 0 || (n_shared > 0 && (F_shared % mult) != 0))
             return fail(LYNX_ERR_UNSUPPORTED, "lynx_moe_layer: H, F and F_shared must be multiples of %d", mult);
         if (q8 && (!q8->gu || !q8->d || (n_shared > 0 && (!q8->shared_gu || !q8->shared_d))))
@@ -124,7 +124,29 @@ extern "C" int lynx_moe_layer_fp8(const uint16_t *x_bf16, const float *Wr, const
                                   int32_t *active_experts, int32_t *num_active_perm, float *y, void *workspace,
                                   void *stream, void *const *stage_events)
 {
-    const lynx::FfnScales q = {scales_gu, scales_d, shared_scales_gu, shared_scales_d};
+    const lynx::FfnScales q = {scales_gu, scales_d, shared_scales_gu, shared_scales_d, 1};
+    return lynx::moe_layer_impl(x_bf16, Wr, bias, reinterpret_cast<const uint16_t *>(Wgu_q),
+                                reinterpret_cast<const uint16_t *>(Wd_q), reinterpret_cast<const uint16_t *>(Sgu_q),
+                                reinterpret_cast<const uint16_t *>(Sd_q), n_shared, F_shared, T, H, F, N, k, alpha, beta,
+                                enable, logits, topk_idx, topk_gate, topk_psum, new_idx, new_gate, cnt_before, cnt_after,
+                                bin_hist, num_active, expert_offsets, perm, active_experts, num_active_perm, y, workspace,
+                                stream, stage_events, &q);
+}
+
+extern "C" int lynx_moe_layer_fp4(const uint16_t *x_bf16, const float *Wr, const float *bias, const uint8_t *Wgu_q,
+                                  const uint8_t *Wd_q, const uint32_t *scales_gu, const uint32_t *scales_d,
+                                  const uint8_t *Sgu_q, const uint8_t *Sd_q, const uint32_t *shared_scales_gu,
+                                  const uint32_t *shared_scales_d, int n_shared, int F_shared, int T, int H, int F, int N,
+                                  int k, float alpha, int beta, int enable, float *logits, int32_t *topk_idx,
+                                  float *topk_gate, float *topk_psum, int32_t *new_idx, float *new_gate,
+                                  int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist, int32_t *num_active,
+                                  int32_t *expert_offsets, int32_t *perm, int32_t *active_experts,
+                                  int32_t *num_active_perm, float *y, void *workspace, void *stream,
+                                  void *const *stage_events)
+{
+    const lynx::FfnScales q = {reinterpret_cast<const float *>(scales_gu), reinterpret_cast<const float *>(scales_d),
+                               reinterpret_cast<const float *>(shared_scales_gu),
+                               reinterpret_cast<const float *>(shared_scales_d), 2};
     return lynx::moe_layer_impl(x_bf16, Wr, bias, reinterpret_cast<const uint16_t *>(Wgu_q),
                                 reinterpret_cast<const uint16_t *>(Wd_q), reinterpret_cast<const uint16_t *>(Sgu_q),
                                 reinterpret_cast<const uint16_t *>(Sd_q), n_shared, F_shared, T, H, F, N, k, alpha, beta,

@@ -111,10 +111,12 @@ __device__ __forceinline__ void store_coherent(uint2 *p, uint2 v)
 // All memory operations this wave has issued are complete (vmcnt, expcnt, lgkmcnt = 0).
 __device__ __forceinline__ void wait_memory_complete() { __builtin_amdgcn_s_waitcnt(0); }
 
-// Row scales of FP8 expert weights (all DEVICE): gate/up [N][2][F] and down [N][H] of the routed experts, the same
-// of the shared experts.  A null pointer to this struct means bf16 weights.
+// Scales of quantised expert weights (all DEVICE), for the routed and the shared experts.  format 1 = FP8 E4M3: fp32
+// row scales, gate/up [N][2][F] and down [N][H].  format 2 = MXFP4: the block-scale exponents in the streaming layout
+// (dwords, passed through these pointers).  A null pointer to this struct means bf16 weights.
 struct FfnScales {
     const float *gu, *d, *shared_gu, *shared_d;
+    int format;
 };
 
 // ---- workspace layout (one caller-provided buffer serves every call) -----------------------------------

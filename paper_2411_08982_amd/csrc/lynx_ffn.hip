@@ -74,17 +74,30 @@ struct WorkItem {
 
 // First half: which expert, from blockIdx and the invoked-expert list (one round trip to memory).  Everything
 // the weight stream needs is known after it, so the weight prefetch can start before the token tables are read.
-// Weight formats: bf16 (a 1 KiB tile is 16 rows x 32 columns) or FP8 E4M3 (W8: 16 rows x 64 columns, converted to
-// bf16 in registers; one fp32 scale per row applied to the accumulated sums).
-template <bool W8>
+// Weight formats WF: 0 = bf16 (a 1 KiB tile is 16 rows x 32 columns), 1 = FP8 E4M3 (16 rows x 64 columns, converted to
+// bf16 in registers; one fp32 scale per row applied to the accumulated sums), 2 = MXFP4 (16 rows x 128 columns:
+// lane l holds row l%16, columns 32*(l/16) .. +31, which is exactly one scale block; converted to bf16 times the
+// block's power-of-two scale in registers).  MXFP4 scale exponents: one dword per lane and four consecutive
+// k-tiles (byte i = tile 4j+i), stored [row group][k-tile/4][lane][2], the 2 being gate|up, or the two row tiles of
+// a down-projection row pair: a lane fetches both of its streams' scales with one 8-byte load.
+template <int WF>
 struct TileCols {
-    static constexpr int value = W8 ? 64 : 32;
+    static constexpr int value = 32 << WF;
 };
 
-template <bool DUAL, bool W8>
+// Dwords of MXFP4 scale exponents behind the weights of one expert's projection: row groups (gate/up: R/16 row
+// tiles, both matrices; down: R/32 row pairs) x groups of four k-tiles x 64 lanes x 2.
+__host__ __device__ __forceinline__ size_t mx_kt4(int K) { return (size_t)((K / 128 + 3) / 4); }
+template <bool DUAL>
+__host__ __device__ __forceinline__ size_t mx_scale_dwords(int R, int K)
+{
+    return (size_t)(DUAL ? R / 16 : R / 32) * mx_kt4(K) * 128;
+}
+
+template <bool DUAL, int WF>
 __device__ __forceinline__ WorkItem resolve_expert(const GemmParams &p, int b)
 {
-    constexpr int KC = TileCols<W8>::value;
+    constexpr int KC = TileCols<WF>::value;
     WorkItem w;
     w.sc = nullptr;
     w.valid = false;
@@ -111,8 +124,9 @@ __device__ __forceinline__ WorkItem resolve_expert(const GemmParams &p, int b)
         w.kbeg = 0;
         w.ksteps = w.K / KC;
         w.out_base = 0;
-        Wbase = p.W_routed + (size_t)e * ((size_t)w.R * w.K * (DUAL ? 2 : 1) / (W8 ? 2 : 1));
-        if (W8) w.sc = p.sc_routed + (size_t)e * w.R * (DUAL ? 2 : 1);
+        Wbase = p.W_routed + (size_t)e * (((size_t)w.R * w.K * (DUAL ? 2 : 1)) >> WF);
+        if (WF == 1) w.sc = p.sc_routed + (size_t)e * w.R * (DUAL ? 2 : 1);
+        if (WF == 2) w.sc = p.sc_routed + (size_t)e * mx_scale_dwords<DUAL>(w.R, w.K);
     } else {
         // b = ((shared expert, K slice) * token blocks + token block) * stride + row tile.  Workgroups go to the
         // XCDs round-robin and the stride is a multiple of 8, so the token blocks of one row tile read their
@@ -133,8 +147,9 @@ __device__ __forceinline__ WorkItem resolve_expert(const GemmParams &p, int b)
         w.ksteps = min(w.K / KC, w.kbeg + per) - w.kbeg;
         if (w.ksteps <= 0) return w;
         w.out_base = p.T * p.k + v * p.T;
-        Wbase = p.W_shared + (size_t)w.shared_s * ((size_t)w.R * w.K * (DUAL ? 2 : 1) / (W8 ? 2 : 1));
-        if (W8) w.sc = p.sc_shared + (size_t)w.shared_s * w.R * (DUAL ? 2 : 1);
+        Wbase = p.W_shared + (size_t)w.shared_s * (((size_t)w.R * w.K * (DUAL ? 2 : 1)) >> WF);
+        if (WF == 1) w.sc = p.sc_shared + (size_t)w.shared_s * w.R * (DUAL ? 2 : 1);
+        if (WF == 2) w.sc = p.sc_shared + (size_t)w.shared_s * mx_scale_dwords<DUAL>(w.R, w.K);
         // shared experts keep their h rows in their own region of the scratch
         const size_t hbase = (size_t)p.shared_h_base + (size_t)w.shared_s * p.T * (DUAL ? w.ldo : w.ldb);
         if (DUAL)
@@ -207,14 +222,14 @@ __device__ __forceinline__ void clear_acc(f32x4 (&accg)[NT], f32x4 (&accu)[NT])
 
 // D fragment of v_mfma_f32_16x16x32: lane holds token column (lane & 15) and output rows
 // 4*(lane >> 4) .. +3 of the wave's 16.  gate/up: h = silu(g) * u rounded to bf16; down: fp32.
-// W8: the sums are scaled by the row scales first (sc: gate rows [R] then up rows [R], or the down rows).
-template <bool DUAL, int NT, bool W8>
+// FP8 weights: the sums are scaled by the row scales first (sc: gate rows [R] then up rows [R], or the down rows).
+template <bool DUAL, int NT, int WF>
 __device__ __forceinline__ void epilogue(const f32x4 (&accg_in)[NT], const f32x4 (&accu_in)[NT], void *out, int ld, int row0,
                                          const int (&orow)[NT], const float *sc, int R)
 {
     const int r = row0 + 4 * (lane_id() >> 4);
     f32x4 sg = {1.f, 1.f, 1.f, 1.f}, su = {1.f, 1.f, 1.f, 1.f};
-    if (W8) {
+    if (WF == 1) {
         const float4 a = *reinterpret_cast<const float4 *>(sc + r);
         sg = f32x4{a.x, a.y, a.z, a.w};
         if (DUAL) {
@@ -225,8 +240,8 @@ __device__ __forceinline__ void epilogue(const f32x4 (&accg_in)[NT], const f32x4
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
         if (orow[nt] < 0) continue;
-        const f32x4 accg = W8 ? accg_in[nt] * sg : accg_in[nt];
-        const f32x4 accu = (W8 && DUAL) ? accu_in[nt] * su : accu_in[nt];
+        const f32x4 accg = WF == 1 ? accg_in[nt] * sg : accg_in[nt];
+        const f32x4 accu = (WF == 1 && DUAL) ? accu_in[nt] * su : accu_in[nt];
         if (DUAL) {
             uint2 pk;
             pk.x = (uint32_t)f32_to_bf16_rne(silu_mul(accg[0], accu[0])) |
@@ -298,26 +313,76 @@ __device__ __forceinline__ void e4m3x16_to_bf16(uint4 c, bf16x8 &lo, bf16x8 &hi)
     hi = __builtin_bit_cast(bf16x8, h);
 }
 
+// 32 E2M1 codes (one lane's piece of a 128-column MXFP4 tile: one scale block) -> four MFMA operands of 8 bf16
+// (columns 8j .. 8j+7 of the block), each value already multiplied by the block scale.  The conversion
+// instruction takes one byte (two codes, low nibble first) and the scale as a float; value * 2^k is exact in bf16.
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t e2m1x2_to_bf16x2(uint32_t codes, float scale, int byte)
+{
+    bf16x2 r;
+    switch (byte) {   // the byte select is an immediate
+    case 0: r = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(codes, scale, 0); break;
+    case 1: r = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(codes, scale, 1); break;
+    case 2: r = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(codes, scale, 2); break;
+    default: r = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(codes, scale, 3); break;
+    }
+    return __builtin_bit_cast(uint32_t, r);
+}
+__device__ __forceinline__ bf16x8 e2m1x8_to_bf16(uint32_t codes, float scale)
+{
+    const uint4 v = make_uint4(e2m1x2_to_bf16x2(codes, scale, 0), e2m1x2_to_bf16x2(codes, scale, 1),
+                               e2m1x2_to_bf16x2(codes, scale, 2), e2m1x2_to_bf16x2(codes, scale, 3));
+    return __builtin_bit_cast(bf16x8, v);
+}
+// The scale of k-tile kt from the lane's dword of four exponents: 2^(E - 127) is the float with exponent field E.
+__device__ __forceinline__ float mx_scale(uint32_t four, int kt) { return __uint_as_float(((four >> (8 * (kt & 3))) & 0xffu) << 23); }
+
+// One weight tile of one stream -> its MFMA A operands (1, 2 or 4 k-steps of 32 columns).
+template <int WF>
+__device__ __forceinline__ void decode_tile(uint4 w, float scale, bf16x8 (&a)[1 << WF])
+{
+    if constexpr (WF == 0) {
+        a[0] = __builtin_bit_cast(bf16x8, w);
+    } else if constexpr (WF == 1) {
+        e4m3x16_to_bf16(w, a[0], a[1]);
+    } else {
+        a[0] = e2m1x8_to_bf16(w.x, scale);
+        a[1] = e2m1x8_to_bf16(w.y, scale);
+        a[2] = e2m1x8_to_bf16(w.z, scale);
+        a[3] = e2m1x8_to_bf16(w.w, scale);
+    }
+}
+
+// Tiles in flight per wave and stream on the direct path.  MXFP4 tiles carry four k-steps, so the token
+// fragments that travel with a slot are 64 bytes per lane: six slots keep the ring inside the register file.
+template <int WF>
+struct DirectDepth {
+    static constexpr int value = WF == 2 ? 6 : kPFD;
+};
+
 struct WeightRing {
     uint4 w0[kPFD], w1[kPFD];
+    uint2 sq[kPFD];      // MXFP4: the scale exponents of both streams (see the layout above)
 };
 
 // Where a wave of the direct path streams from: needs the expert, not its tokens.
 struct DirectPlan {
     const uint4 *Wl;     // this lane's piece of the wave's first weight tile
+    const uint2 *Sl;     // MXFP4: this lane's scale dwords of the wave's row group, k-tile group 0
     int step, second;    // uint4 strides: next k-step, second stream
     int kb, n;           // first k-step and k-steps of this wave
+    int kt0;             // first k-tile actually read (kb, or 0 for a wave without work)
     int rt;              // first 16-row tile
     bool rows_ok;
 };
 
-template <bool DUAL, int KW, bool W8>
+template <bool DUAL, int KW, int WF>
 __device__ __forceinline__ DirectPlan plan_direct(const WorkItem &w)
 {
     constexpr int RW = kFfnWaves / KW;
     const int wv = wave_id();
     const int rw = wv / KW, kw = wv % KW;
-    const int KT = w.K / TileCols<W8>::value;
+    const int KT = w.K / TileCols<WF>::value;
     DirectPlan d;
     const int grp = w.tile * RW + rw;                  // row group of this wave
     d.rt = DUAL ? grp : 2 * grp;
@@ -327,79 +392,83 @@ __device__ __forceinline__ DirectPlan plan_direct(const WorkItem &w)
     d.n = min(w.kbeg + w.ksteps, d.kb + per) - d.kb;
     const int rtc = d.rows_ok ? d.rt : 0;              // waves past the last row read tile 0 and store nothing
     const int kbc = d.n > 0 ? d.kb : 0;
+    d.kt0 = kbc;
     d.step = DUAL ? 2 * kWave : kWave;
     d.second = DUAL ? kWave : KT * kWave;
     d.Wl = w.W + ((size_t)rtc * KT + kbc) * d.step + lane_id();
+    d.Sl = nullptr;
+    if (WF == 2)
+        d.Sl = reinterpret_cast<const uint2 *>(w.sc) + (size_t)(d.rows_ok ? grp : 0) * mx_kt4(w.K) * kWave + lane_id();
     return d;
 }
 
+__device__ __forceinline__ uint2 ring_load_scales(const uint2 *__restrict__ base, int index)
+{
+    asm volatile("" : "+v"(index));
+    return base[index];
+}
+
+template <int WF>
 __device__ __forceinline__ void prefetch_weights(const DirectPlan &d, WeightRing &r)
 {
+    constexpr int D = DirectDepth<WF>::value;
     const int last = max(d.n, 1) - 1;
 #pragma unroll
-    for (int j = 0; j < kPFD; ++j) {
+    for (int j = 0; j < D; ++j) {
         const int s = min(j, last);
         r.w0[j] = ring_load_weights(d.Wl, s * d.step);
         r.w1[j] = ring_load_weights(d.Wl, s * d.step + d.second);
+        if (WF == 2) r.sq[j] = ring_load_scales(d.Sl, ((d.kt0 + s) >> 2) * kWave);
     }
 }
 
 // The ring arrives with its first turn of weight tiles already requested (prefetch_weights).
-template <int NT, bool W8>
+template <int NT, int WF>
 __device__ __forceinline__ void stream_direct(const DirectPlan &d, WeightRing &r, const uint4 *const (&brow)[NT],
                                               f32x4 (&acc0)[NT], f32x4 (&acc1)[NT])
 {
-    constexpr int BP = W8 ? 2 : 1;           // 16-byte pieces of a token row per lane and weight tile
-    constexpr int BS = TileCols<W8>::value / 8;   // uint4 units between the pieces of consecutive tiles
+    constexpr int D = DirectDepth<WF>::value;
+    constexpr int BP = 1 << WF;              // 16-byte pieces of a token row per lane and weight tile = its k-steps
+    constexpr int BS = TileCols<WF>::value / 8;   // uint4 units between the pieces of consecutive tiles
     const uint4 *Wl = d.Wl;
     const int step = d.step, second = d.second;
     const int n = d.rows_ok ? d.n : 0;     // k-steps whose products count
     const int last = max(d.n, 1) - 1;
-    uint4 bb[kPFD][NT][BP];
+    uint4 bb[D][NT][BP];
 #pragma unroll
-    for (int j = 0; j < kPFD; ++j) {
+    for (int j = 0; j < D; ++j) {
         const int s = min(j, last);
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
             for (int h = 0; h < BP; ++h) bb[j][nt][h] = ring_load_b(brow[nt], s * BS + h);
     }
-    // One turn of the ring: consume the kPFD slots in order, refilling each right after its last read.
+    // One turn of the ring: consume the D slots in order, refilling each right after its last read.
     auto turn = [&](int s0) {
 #pragma unroll
-        for (int u = 0; u < kPFD; ++u) {
+        for (int u = 0; u < D; ++u) {
             const int s = s0 + u;
             const bool live = s < n;
             // consume slot u ...
-            if (W8) {
-                bf16x8 a0l, a0h, a1l, a1h;
-                e4m3x16_to_bf16(sel4(live, r.w0[u]), a0l, a0h);
-                e4m3x16_to_bf16(sel4(live, r.w1[u]), a1l, a1h);
+            bf16x8 a0[BP], a1[BP];
+            const int kt = d.kt0 + min(s, last);
+            decode_tile<WF>(sel4(live, r.w0[u]), WF == 2 ? mx_scale(r.sq[u].x, kt) : 1.0f, a0);
+            decode_tile<WF>(sel4(live, r.w1[u]), WF == 2 ? mx_scale(r.sq[u].y, kt) : 1.0f, a1);
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt) {
-                    const bf16x8 bl = __builtin_bit_cast(bf16x8, bb[u][nt][0]);
-                    const bf16x8 bh = __builtin_bit_cast(bf16x8, bb[u][nt][BP - 1]);
-                    acc0[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0l, bl, acc0[nt], 0, 0, 0);
-                    acc1[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1l, bl, acc1[nt], 0, 0, 0);
-                    acc0[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0h, bh, acc0[nt], 0, 0, 0);
-                    acc1[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1h, bh, acc1[nt], 0, 0, 0);
-                }
-            } else {
-                const bf16x8 a0 = __builtin_bit_cast(bf16x8, sel4(live, r.w0[u]));
-                const bf16x8 a1 = __builtin_bit_cast(bf16x8, sel4(live, r.w1[u]));
+            for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt) {
-                    const bf16x8 b = __builtin_bit_cast(bf16x8, bb[u][nt][0]);
-                    acc0[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, b, acc0[nt], 0, 0, 0);
-                    acc1[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, b, acc1[nt], 0, 0, 0);
+                for (int h = 0; h < BP; ++h) {
+                    const bf16x8 b = __builtin_bit_cast(bf16x8, bb[u][nt][h]);
+                    acc0[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0[h], b, acc0[nt], 0, 0, 0);
+                    acc1[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1[h], b, acc1[nt], 0, 0, 0);
                 }
-            }
             // ... then refill it (the scheduling fences keep the refill behind the last read of the slot,
             // so that it can land in the same registers and the ring needs no copies)
             __builtin_amdgcn_sched_barrier(0);
-            const int sn = min(s + kPFD, last);
+            const int sn = min(s + D, last);
             r.w0[u] = ring_load_weights(Wl, sn * step);
             r.w1[u] = ring_load_weights(Wl, sn * step + second);
+            if (WF == 2) r.sq[u] = ring_load_scales(d.Sl, ((d.kt0 + sn) >> 2) * kWave);
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
@@ -414,18 +483,18 @@ __device__ __forceinline__ void stream_direct(const DirectPlan &d, WeightRing &r
     // entry order in every turn, and would wait until a third of the ring is left before the first slot.
     if (n > 0) {
         turn(0);
-        for (int s0 = kPFD; s0 < n; s0 += kPFD) turn(s0);
+        for (int s0 = D; s0 < n; s0 += D) turn(s0);
     }
 }
 
 // One expert with <= 16*NT tokens: the four waves are RW row groups x KW slices of K; the slices are
 // summed through LDS at the end.  A row group is one 16-row tile of gate and up (gate/up) or two
 // consecutive 16-row tiles (down), so that every token fragment loaded feeds two MFMAs.
-template <bool DUAL, int NT, int KW, bool W8>
+template <bool DUAL, int NT, int KW, int WF>
 __device__ __forceinline__ void expert_direct(const GemmParams &p, const WorkItem &w, const DirectPlan &d, WeightRing &ring,
                                               float *red)
 {
-    constexpr int KC = TileCols<W8>::value;
+    constexpr int KC = TileCols<WF>::value;
     constexpr int NACC = NT * 2;
     const int lane = lane_id(), wv = wave_id();
     const int rw = wv / KW, kw = wv % KW;
@@ -448,7 +517,7 @@ __device__ __forceinline__ void expert_direct(const GemmParams &p, const WorkIte
     }
     f32x4 acc0[NT], acc1[NT];
     clear_acc<NT>(acc0, acc1);
-    stream_direct<NT, W8>(d, ring, brow, acc0, acc1);
+    stream_direct<NT, WF>(d, ring, brow, acc0, acc1);
     if (KW > 1) {
         f32x4 *r4 = reinterpret_cast<f32x4 *>(red);   // [rw][kw-1][NACC][lane]
         if (kw > 0) {
@@ -474,22 +543,24 @@ __device__ __forceinline__ void expert_direct(const GemmParams &p, const WorkIte
     }
     if (kw == 0 && rows_ok) {
         if (DUAL) {
-            epilogue<true, NT, W8>(acc0, acc1, w.out, w.ldo, rt * 16, orow, w.sc, w.R);
+            epilogue<true, NT, WF>(acc0, acc1, w.out, w.ldo, rt * 16, orow, w.sc, w.R);
         } else {
-            epilogue<false, NT, W8>(acc0, acc0, w.out, w.ldo, rt * 16, orow, w.sc, w.R);
-            epilogue<false, NT, W8>(acc1, acc1, w.out, w.ldo, rt * 16 + 16, orow, w.sc, w.R);
+            epilogue<false, NT, WF>(acc0, acc0, w.out, w.ldo, rt * 16, orow, w.sc, w.R);
+            epilogue<false, NT, WF>(acc1, acc1, w.out, w.ldo, rt * 16 + 16, orow, w.sc, w.R);
         }
     }
 }
 
 // Staged: the token tile is staged through LDS in chunks of KS k-steps, double buffered and shared by
 // the four waves, which own four consecutive 16-row tiles and walk all of K.
-template <bool DUAL, int NT, int KS, bool W8>
+template <bool DUAL, int NT, int KS, int WF>
 __device__ __forceinline__ void stream_staged(const uint4 *__restrict__ Wt, bool wave_active, int KT, int K,
                                               const uint16_t *__restrict__ B, const int *rowoff, char *stage,
+                                              const uint2 *__restrict__ Sl, int kt0, bool sc_second,
                                               f32x4 (&accg)[NT], f32x4 (&accu)[NT])   // KT weight tiles from Wt; B columns [0, K)
-{
-    constexpr int TS = W8 ? 2 : 1;               // 32-column steps of the staged token tile per weight tile
+{   // (MXFP4: Sl = this lane's scale dwords of the wave's row group, kt0 = the first k-tile's index, sc_second = a
+    // down-projection wave on the second row tile of its pair)
+    constexpr int TS = 1 << WF;                  // 32-column steps of the staged token tile per weight tile
     constexpr int ROWB = KS * 64 + 16;           // LDS bytes per token row (+16: conflict-free 16-byte reads)
     constexpr int BUFB = NT * 16 * ROWB;
     static_assert(2 * BUFB <= (NT > 4 ? kStageBytesBig : kStageBytes), "token tile does not fit the LDS stage");
@@ -537,18 +608,20 @@ __device__ __forceinline__ void stream_staged(const uint4 *__restrict__ Wt, bool
 
     const uint4 *Wl = Wt + lane;
     uint4 wg[kPF], wu[kPF];
+    uint2 sq[kPF];
 #pragma unroll
     for (int j = 0; j < kPF; ++j) {
         const int s = min(j, last);
         wg[j] = ring_load_weights(Wl, s * WSTEP);
         wu[j] = DUAL ? ring_load_weights(Wl, s * WSTEP + kWave) : zero4();
+        if (WF == 2) sq[j] = ring_load_scales(Sl, ((kt0 + s) >> 2) * kWave);
     }
     load_x(0);
     store_x(0);
     __syncthreads();
 
     // this lane's B-fragment offset inside a token tile (its column group: 8 columns, or 16 for 64-column tiles)
-    const int brow = (lane & 15) * ROWB + (lane >> 4) * (W8 ? 32 : 16);
+    const int brow = (lane & 15) * ROWB + (lane >> 4) * (16 << WF);
     for (int s0 = 0; s0 < KT; s0 += kPF) {
 #pragma unroll
         for (int u = 0; u < kPF; ++u) {
@@ -560,33 +633,23 @@ __device__ __forceinline__ void stream_staged(const uint4 *__restrict__ Wt, bool
             }
             const bool live = wave_active && s < KT;
             const char *buf = stage + (c & 1) * BUFB + brow + ((u * TS) % KS) * 64;
-            if (W8) {
-                bf16x8 agl, agh, aul, auh;
-                e4m3x16_to_bf16(sel4(live, wg[u]), agl, agh);
-                e4m3x16_to_bf16(sel4(live, wu[u]), aul, auh);
+            bf16x8 ag[TS], au[TS];
+            const int kt = kt0 + min(s, last);
+            decode_tile<WF>(sel4(live, wg[u]), WF == 2 ? mx_scale(sc_second ? sq[u].y : sq[u].x, kt) : 1.0f, ag);
+            if (DUAL) decode_tile<WF>(sel4(live, wu[u]), WF == 2 ? mx_scale(sq[u].y, kt) : 1.0f, au);
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt) {
-                    const bf16x8 bl = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(buf + nt * 16 * ROWB));
-                    const bf16x8 bh = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(buf + nt * 16 * ROWB + 16));
-                    accg[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(agl, bl, accg[nt], 0, 0, 0);
-                    if (DUAL) accu[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aul, bl, accu[nt], 0, 0, 0);
-                    accg[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(agh, bh, accg[nt], 0, 0, 0);
-                    if (DUAL) accu[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(auh, bh, accu[nt], 0, 0, 0);
-                }
-            } else {
-                const bf16x8 ag = __builtin_bit_cast(bf16x8, sel4(live, wg[u]));
-                const bf16x8 au = __builtin_bit_cast(bf16x8, sel4(live, wu[u]));
+            for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt) {
-                    const bf16x8 b = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(buf + nt * 16 * ROWB));
-                    accg[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ag, b, accg[nt], 0, 0, 0);
-                    if (DUAL) accu[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(au, b, accu[nt], 0, 0, 0);
+                for (int h = 0; h < TS; ++h) {
+                    const bf16x8 b = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(buf + nt * 16 * ROWB + 16 * h));
+                    accg[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ag[h], b, accg[nt], 0, 0, 0);
+                    if (DUAL) accu[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(au[h], b, accu[nt], 0, 0, 0);
                 }
-            }
             __builtin_amdgcn_sched_barrier(0);
             const int sn = min(s + kPF, last);
             wg[u] = ring_load_weights(Wl, sn * WSTEP);
             if (DUAL) wu[u] = ring_load_weights(Wl, sn * WSTEP + kWave);
+            if (WF == 2) sq[u] = ring_load_scales(Sl, ((kt0 + sn) >> 2) * kWave);
             __builtin_amdgcn_sched_barrier(0);
             if ((u * TS + TS - 1) % KS == KS - 1) {
                 store_x(c + 1);
@@ -596,24 +659,27 @@ __device__ __forceinline__ void stream_staged(const uint4 *__restrict__ Wt, bool
     }
 }
 
-template <bool DUAL, int NT, int KS, bool W8>
+template <bool DUAL, int NT, int KS, int WF>
 __device__ __forceinline__ void expert_staged(const WorkItem &w, const int *rowoff, const int *outrow, char *stage)
 {
     constexpr int WSTEP = DUAL ? 2 * kWave : kWave;
-    constexpr int KC = TileCols<W8>::value;
+    constexpr int KC = TileCols<WF>::value;
     const int KT = w.K / KC;
     const int rt = w.tile * kFfnWaves + wave_id();
     const bool wave_active = rt * 16 < w.R;
     const int rtc = wave_active ? rt : 0;   // idle waves read tile 0 (in bounds) and contribute nothing
     f32x4 accg[NT], accu[NT];
     clear_acc<NT>(accg, accu);
-    stream_staged<DUAL, NT, KS, W8>(w.W + ((size_t)rtc * KT + w.kbeg) * WSTEP, wave_active, w.ksteps, w.ksteps * KC,
-                                    w.B + (size_t)w.kbeg * KC, rowoff, stage, accg, accu);
+    const uint2 *Sl = nullptr;
+    if (WF == 2)
+        Sl = reinterpret_cast<const uint2 *>(w.sc) + (size_t)(DUAL ? rtc : rtc >> 1) * mx_kt4(w.K) * kWave + lane_id();
+    stream_staged<DUAL, NT, KS, WF>(w.W + ((size_t)rtc * KT + w.kbeg) * WSTEP, wave_active, w.ksteps, w.ksteps * KC,
+                                    w.B + (size_t)w.kbeg * KC, rowoff, stage, Sl, w.kbeg, !DUAL && (rtc & 1), accg, accu);
     if (!wave_active) return;
     int orow[NT];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) orow[nt] = outrow[nt * 16 + (lane_id() & 15)];
-    epilogue<DUAL, NT, W8>(accg, accu, w.out, w.ldo, rt * 16, orow, w.sc, w.R);
+    epilogue<DUAL, NT, WF>(accg, accu, w.out, w.ldo, rt * 16, orow, w.sc, w.R);
 }
 
 // Both projections of every invoked and shared expert in ONE launch.  Grid: all gate/up workgroups, then
@@ -645,19 +711,19 @@ __device__ __forceinline__ int done_slot(const GemmParams &p, const WorkItem &w)
     return w.shared_s < 0 ? w.e : LYNX_MAX_N + w.shared_s * p.shared_tblocks + w.tok0 / p.tok_block;
 }
 
-template <bool DUAL, int KW, bool BIG, bool W8>
+template <bool DUAL, int KW, bool BIG, int WF>
 __device__ __forceinline__ void expert_work(const GemmParams &p, int b, const FfnParams &fp, char *stage, int *rowoff,
                                             int *outrow)
 {
     constexpr int TB = BIG ? kTokBlockBig : kTokBlock;   // tokens per pass
-    WorkItem w = resolve_expert<DUAL, W8>(p, b);
+    WorkItem w = resolve_expert<DUAL, WF>(p, b);
     if (!w.valid) return;
     // The weight stream of the direct path starts before the token tables are read (their loads depend on
     // each other: offsets, then the permutation, then the token rows).
     // (Not in the large-batch kernels: their staged path needs the registers, and few of their experts are direct.)
-    const DirectPlan plan = plan_direct<DUAL, KW, W8>(w);
+    const DirectPlan plan = plan_direct<DUAL, KW, WF>(w);
     WeightRing ring;
-    if (!BIG) prefetch_weights(plan, ring);
+    if (!BIG) prefetch_weights<WF>(plan, ring);
     resolve_tokens(p, w);
     if (!w.valid) return;
     int32_t *counter = fp.done + done_slot(p, w);
@@ -676,8 +742,8 @@ __device__ __forceinline__ void expert_work(const GemmParams &p, int b, const Ff
         __syncthreads();
     }
     if (w.Te <= kDirectMaxTokens) {
-        if (BIG) prefetch_weights(plan, ring);
-        expert_direct<DUAL, 1, KW, W8>(p, w, plan, ring, reinterpret_cast<float *>(stage));
+        if (BIG) prefetch_weights<WF>(plan, ring);
+        expert_direct<DUAL, 1, KW, WF>(p, w, plan, ring, reinterpret_cast<float *>(stage));
     } else {
         // staged path: units of 64 rows.  A direct workgroup covers 16*RW rows (gate/up) or 32*RW rows (down).
         constexpr int kRowsPerWG = 16 * (kFfnWaves / KW) * (DUAL ? 1 : 2);
@@ -705,11 +771,11 @@ __device__ __forceinline__ void expert_work(const GemmParams &p, int b, const Ff
                 }
                 __syncthreads();
                 if (nb <= 32)
-                    expert_staged<DUAL, 2, 8, W8>(w, rowoff, outrow, stage);
+                    expert_staged<DUAL, 2, 8, WF>(w, rowoff, outrow, stage);
                 else if (!BIG || nb <= 64)
-                    expert_staged<DUAL, 4, 4, W8>(w, rowoff, outrow, stage);
+                    expert_staged<DUAL, 4, 4, WF>(w, rowoff, outrow, stage);
                 else
-                    expert_staged<DUAL, 8, 4, W8>(w, rowoff, outrow, stage);
+                    expert_staged<DUAL, 8, 4, WF>(w, rowoff, outrow, stage);
             }
         }
     }
@@ -720,7 +786,7 @@ __device__ __forceinline__ void expert_work(const GemmParams &p, int b, const Ff
     }
 }
 
-template <int KWD, bool BIG, bool W8>
+template <int KWD, bool BIG, int WF>
 __global__ __launch_bounds__(kFfnThreads, 2) void ffn_kernel(FfnParams fp)
 {
     // staged token tile, or the K-slice partial sums
@@ -729,9 +795,9 @@ __global__ __launch_bounds__(kFfnThreads, 2) void ffn_kernel(FfnParams fp)
     __shared__ int outrow[BIG ? kTokBlockBig : kTokBlock];   // staged path: output row of each token, -1 = none
     const int b = blockIdx.x + fp.block0;
     if (b < fp.gu_blocks)
-        expert_work<true, 1, BIG, W8>(fp.gu, b, fp, stage, rowoff, outrow);
+        expert_work<true, 1, BIG, WF>(fp.gu, b, fp, stage, rowoff, outrow);
     else
-        expert_work<false, KWD, BIG, W8>(fp.dn, b - fp.gu_blocks, fp, stage, rowoff, outrow);
+        expert_work<false, KWD, BIG, WF>(fp.dn, b - fp.gu_blocks, fp, stage, rowoff, outrow);
 }
 
 __global__ __launch_bounds__(256) void clear_kernel(int32_t *p, int n)
@@ -861,10 +927,85 @@ __global__ __launch_bounds__(256) void quantize_kernel(const uint16_t *__restric
     }
 }
 
+// Nearest E2M1 code of q (already divided by the block scale): ties to the even code, magnitudes above 6 to 6.
+// The thresholds are the midpoints of 0, 0.5, 1, 1.5, 2, 3, 4, 6; "<=" where the lower neighbour is the even code.
+__device__ __forceinline__ uint32_t e2m1_encode(float q)
+{
+    const uint32_t sgn = (__float_as_uint(q) >> 31) << 3;
+    const float a = fabsf(q);
+    const uint32_t code = a <= 0.25f ? 0u : a < 0.75f ? 1u : a <= 1.25f ? 2u : a < 1.75f ? 3u : a <= 2.5f ? 4u : a < 3.5f ? 5u : a <= 5.0f ? 6u : 7u;
+    return sgn | code;
+}
+
+// MXFP4 quantisation straight into the streaming layout: one wave per (expert, matrix, row), a lane per block of
+// 32 columns.  Per block: E - 127 = floor(log2(amax)) - 2, clamped to [0, 254] (E = 127 for an all-zero block);
+// code = encode(w * 2^(127 - E)), an exact scaling.  Weights: a 1 KiB tile is 16 rows x 128 columns, lane l = row
+// l%16, block l/16, 16 bytes, byte j = columns 2j (low nibble) and 2j+1.  Scale exponents: byte kt%4 of dword
+// [row group][kt/4][lane][which], (row group, which) = (row tile, matrix) for gate/up or (row pair, tile of the
+// pair) for down.
+__global__ __launch_bounds__(256) void quantize_fp4_kernel(const uint16_t *__restrict__ Wa, const uint16_t *__restrict__ Wb,
+                                                           int nmat, int E, int R, int K, uint8_t *__restrict__ out,
+                                                           uint8_t *__restrict__ scales)
+{
+    const long row_id = (long)blockIdx.x * 4 + wave_id();   // (e, m, r)
+    if (row_id >= (long)E * nmat * R) return;
+    const int lane = lane_id();
+    const int r = (int)(row_id % R);
+    const int m = (int)((row_id / R) % nmat);
+    const int e = (int)(row_id / ((long)R * nmat));
+    const uint16_t *src = (m == 0 ? Wa : Wb) + ((size_t)e * R + r) * K;
+    const int KT = K / 128;
+    const size_t KT4 = mx_kt4(K);
+    const int groups = nmat == 2 ? R / 16 : R / 32;
+    const int grp = nmat == 2 ? r / 16 : r / 32;
+    const int which = nmat == 2 ? m : (r / 16) & 1;
+    for (int c = lane * 32; c < K; c += kWave * 32) {
+        uint32_t w[16];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const uint4 v = *reinterpret_cast<const uint4 *>(src + c + q * 8);
+            w[4 * q] = v.x;
+            w[4 * q + 1] = v.y;
+            w[4 * q + 2] = v.z;
+            w[4 * q + 3] = v.w;
+        }
+        float amax = 0.f;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            amax = fmaxf(amax, fabsf(__uint_as_float(w[i] << 16)));
+            amax = fmaxf(amax, fabsf(__uint_as_float(w[i] & 0xffff0000u)));
+        }
+        int Eb = 127;
+        if (amax > 0.f) {
+            const uint32_t bits = __float_as_uint(amax);
+            const int ef = (int)(bits >> 23);
+            const int fl = ef != 0 ? ef - 127 : (31 - __clz((int)(bits & 0x007fffffu))) - 149;   // floor(log2(amax))
+            Eb = min(max(fl - 2 + 127, 0), 254);
+        }
+        uint32_t packed[4];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const uint32_t lo = e2m1_encode(ldexpf(__uint_as_float(w[i] << 16), 127 - Eb));
+            const uint32_t hi = e2m1_encode(ldexpf(__uint_as_float(w[i] & 0xffff0000u), 127 - Eb));
+            const uint32_t byte = lo | (hi << 4);
+            if (i % 4 == 0)
+                packed[i / 4] = byte;
+            else
+                packed[i / 4] |= byte << (8 * (i % 4));
+        }
+        const int kt = c / 128, g = (c % 128) / 32;
+        const int l = g * 16 + (r % 16);
+        const size_t piece = ((((size_t)e * (R / 16) + r / 16) * KT + kt) * nmat + m) * kWave + l;
+        *reinterpret_cast<uint4 *>(out + piece * 16) = make_uint4(packed[0], packed[1], packed[2], packed[3]);
+        const size_t dword = (((size_t)e * groups + grp) * KT4 + kt / 4) * 128 + (size_t)l * 2 + which;
+        scales[dword * 4 + (kt % 4)] = (uint8_t)Eb;
+    }
+}
+
 // How many of a workgroup's four waves split the contraction dimension (the rest split rows).  Long
 // per-wave streams amortise the fill and drain of the prefetch ring, so K is only split when the
 // batch cannot invoke enough experts to give every CU several waves otherwise.
-static int pick_k_waves(int K, bool dual, int T, int max_experts, int bytes_per_weight)
+static int pick_k_waves(int K, bool dual, int T, int max_experts, int bits_per_weight)
 {
     // Gate/up: a wave streams a whole row tile of both matrices (2 * K * 32 bytes, contiguous); measured best
     // at every expert count.  It also makes a workgroup exactly one 64-row unit of the staged path.
@@ -877,7 +1018,7 @@ static int pick_k_waves(int K, bool dual, int T, int max_experts, int bytes_per_
     // that whole row groups would leave the chip with too few, too long workgroups (Mixtral-like shapes); with
     // more experts two ways (64-row workgroups: 4-5 % faster than 128-row ones for DeepSeek-V2-Lite and
     // Qwen1.5-MoE shapes), unless the streams would get too short.
-    const long group_bytes = (long)16 * K * 2 * bytes_per_weight;         // weight bytes behind one row group
+    const long group_bytes = (long)16 * K * 2 * bits_per_weight / 8;      // weight bytes behind one row group
     int kw = max_experts <= 8 ? 4 : 2;
     while (kw > 1 && group_bytes / kw < 32 * 1024) kw >>= 1;              // keep at least 32 KiB per wave
     return kw;
@@ -907,18 +1048,18 @@ constexpr int kWgPerCu = 2;
 constexpr int kLdsPerCu = 160 * 1024;
 constexpr int kLdsTargetPerWg = 56 * 1024;
 
-template <int KWD, bool BIG, bool W8>
+template <int KWD, bool BIG, int WF>
 static int launch_padded(const FfnParams &fp, unsigned blocks, hipStream_t st)
 {
     static_assert(kLdsTargetPerWg * (kWgPerCu + 1) > kLdsPerCu && kLdsTargetPerWg * kWgPerCu <= kLdsPerCu, "LDS pad");
     static int pad = -1;   // per instantiation
     if (pad < 0) {
         hipFuncAttributes attr;
-        if (hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(&ffn_kernel<KWD, BIG, W8>)) != hipSuccess)
+        if (hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(&ffn_kernel<KWD, BIG, WF>)) != hipSuccess)
             return fail(LYNX_ERR_HIP, "lynx_moe_ffn: hipFuncGetAttributes failed");
         pad = max(0, kLdsTargetPerWg - (int)attr.sharedSizeBytes);
     }
-    hipLaunchKernelGGL((ffn_kernel<KWD, BIG, W8>), dim3(blocks), dim3(kFfnThreads), pad, st, fp);
+    hipLaunchKernelGGL((ffn_kernel<KWD, BIG, WF>), dim3(blocks), dim3(kFfnThreads), pad, st, fp);
     return LYNX_OK;
 }
 
@@ -931,12 +1072,12 @@ static bool single_launch(int T, int F) { return T > kDirectMaxTokens && (F + 63
 
 // Gate/up and down over all invoked and shared experts.  Batches of more than 64 tokens take the
 // kernels whose staged path makes passes of up to 128 tokens.
-template <bool W8>
+template <int WF>
 static int launch_ffn(FfnParams fp, hipStream_t st)
 {
     const GemmParams &d = fp.dn;
     const int max_experts = (int)min((long)d.N, (long)d.T * d.k) + d.n_shared;
-    const int kwd = pick_k_waves(d.K, false, d.T, max_experts, W8 ? 1 : 2);
+    const int kwd = pick_k_waves(d.K, false, d.T, max_experts, 16 >> WF);
     set_tiles(fp.gu, 16 * kFfnWaves);                    // gate/up: four row tiles per workgroup
     set_tiles(fp.dn, 16 * (kFfnWaves / kwd) * 2);
     fp.gu_blocks = (int)grid_blocks(fp.gu);
@@ -949,13 +1090,13 @@ static int launch_ffn(FfnParams fp, hipStream_t st)
         fp.block0 = part == 0 ? 0 : fp.gu_blocks;
         const unsigned blocks = single ? (unsigned)fp.gu_blocks + dn_blocks : part == 0 ? (unsigned)fp.gu_blocks : dn_blocks;
         if (big)
-            rc = launch_padded<2, true, W8>(fp, blocks, st);
+            rc = launch_padded<2, true, WF>(fp, blocks, st);
         else if (kwd == 4)
-            rc = launch_padded<4, false, W8>(fp, blocks, st);
+            rc = launch_padded<4, false, WF>(fp, blocks, st);
         else if (kwd == 2)
-            rc = launch_padded<2, false, W8>(fp, blocks, st);
+            rc = launch_padded<2, false, WF>(fp, blocks, st);
         else
-            rc = launch_padded<1, false, W8>(fp, blocks, st);
+            rc = launch_padded<1, false, WF>(fp, blocks, st);
         if (rc == LYNX_OK) rc = check_launch("lynx_moe_ffn(gate/up, down)");
     }
     return rc;
@@ -1012,7 +1153,7 @@ int moe_ffn_impl(const uint16_t *x_bf16, const uint16_t *Wgu_packed, const uint1
         return fail(LYNX_ERR_INVALID_ARG, "lynx_moe_ffn: bad size");
     if (n_shared > 0 && (F_shared <= 0 || !Sgu_packed || !Sd_packed))
         return fail(LYNX_ERR_INVALID_ARG, "lynx_moe_ffn: shared experts need F_shared > 0 and their weights");
-    const int mult = q8 ? 64 : 32;   // columns of a weight tile
+    const int mult = q8 ? 32 << q8->format : 32;   // columns of a weight tile
     if ((H % mult) != 0 || (F % mult) != 0 || (n_shared > 0 && (F_shared % mult) != 0) || N > LYNX_MAX_N ||
         k > LYNX_MAX_K || T > LYNX_MAX_T || k > N)
         return fail(LYNX_ERR_UNSUPPORTED, "lynx_moe_ffn: need H,F,F_shared multiples of %d, k<=N<=%d, k<=%d, T<=%d", mult,
@@ -1092,7 +1233,7 @@ int moe_ffn_impl(const uint16_t *x_bf16, const uint16_t *Wgu_packed, const uint1
     fp.dn = p;
     rc = mark(0);
     if (rc != LYNX_OK) return rc;
-    rc = q8 ? launch_ffn<true>(fp, st) : launch_ffn<false>(fp, st);
+    rc = !q8 ? launch_ffn<0>(fp, st) : q8->format == 2 ? launch_ffn<2>(fp, st) : launch_ffn<1>(fp, st);
     if (rc != LYNX_OK) return rc;
     rc = mark(1);
     if (rc != LYNX_OK) return rc;
@@ -1127,7 +1268,7 @@ extern "C" int lynx_moe_ffn_fp8(const uint16_t *x_bf16, const uint8_t *Wgu_q, co
                                 const int32_t *active_experts, const int32_t *num_active, int T, int H, int F, int N,
                                 int k, float *y, void *workspace, void *stream, void *const *stage_events)
 {
-    const lynx::FfnScales q = {scales_gu, scales_d, shared_scales_gu, shared_scales_d};
+    const lynx::FfnScales q = {scales_gu, scales_d, shared_scales_gu, shared_scales_d, 1};
     return lynx::moe_ffn_impl(x_bf16, reinterpret_cast<const uint16_t *>(Wgu_q), reinterpret_cast<const uint16_t *>(Wd_q),
                               reinterpret_cast<const uint16_t *>(Sgu_q), reinterpret_cast<const uint16_t *>(Sd_q), n_shared,
                               F_shared, idx, gate, expert_offsets, perm, active_experts, num_active, T, H, F, N, k, y,
@@ -1154,6 +1295,51 @@ extern "C" int lynx_quantize_weights_fp8(const uint16_t *Wg, const uint16_t *Wu,
     hipLaunchKernelGGL(quantize_kernel, dim3((unsigned)((rows_d + 3) / 4)), dim3(256), 0, (hipStream_t)stream, Wd, Wd, 1, E,
                        H, F, Wd_q, scales_d);
     return check_launch("lynx_quantize_weights_fp8(down)");
+}
+
+extern "C" size_t lynx_fp4_scale_words(int E, int rows, int K, int gate_up)
+{
+    if (E < 0 || rows <= 0 || K <= 0) return 0;
+    return (size_t)E * (gate_up ? lynx::mx_scale_dwords<true>(rows, K) : lynx::mx_scale_dwords<false>(rows, K));
+}
+
+extern "C" int lynx_quantize_weights_fp4(const uint16_t *Wg, const uint16_t *Wu, const uint16_t *Wd, int E, int H, int F,
+                                         uint8_t *Wgu_q, uint8_t *Wd_q, uint32_t *scales_gu, uint32_t *scales_d,
+                                         void *stream)
+{
+    using namespace lynx;
+    if (E < 0 || H <= 0 || F <= 0) return fail(LYNX_ERR_INVALID_ARG, "lynx_quantize_weights_fp4: bad size");
+    if ((H % 128) != 0 || (F % 128) != 0)
+        return fail(LYNX_ERR_UNSUPPORTED, "lynx_quantize_weights_fp4: H and F must be multiples of 128 (H=%d F=%d)", H, F);
+    if (E == 0) return LYNX_OK;
+    if (!Wg || !Wu || !Wd || !Wgu_q || !Wd_q || !scales_gu || !scales_d)
+        return fail(LYNX_ERR_INVALID_ARG, "lynx_quantize_weights_fp4: null pointer");
+    const size_t rows_gu = (size_t)E * 2 * F, rows_d = (size_t)E * H;
+    if ((rows_gu + 3) / 4 > 0x7fffffffull || (rows_d + 3) / 4 > 0x7fffffffull)
+        return fail(LYNX_ERR_UNSUPPORTED, "lynx_quantize_weights_fp4: too large for one call");
+    hipLaunchKernelGGL(quantize_fp4_kernel, dim3((unsigned)((rows_gu + 3) / 4)), dim3(256), 0, (hipStream_t)stream, Wg, Wu, 2,
+                       E, F, H, Wgu_q, reinterpret_cast<uint8_t *>(scales_gu));
+    int rc = check_launch("lynx_quantize_weights_fp4(gate/up)");
+    if (rc != LYNX_OK) return rc;
+    hipLaunchKernelGGL(quantize_fp4_kernel, dim3((unsigned)((rows_d + 3) / 4)), dim3(256), 0, (hipStream_t)stream, Wd, Wd, 1,
+                       E, H, F, Wd_q, reinterpret_cast<uint8_t *>(scales_d));
+    return check_launch("lynx_quantize_weights_fp4(down)");
+}
+
+extern "C" int lynx_moe_ffn_fp4(const uint16_t *x_bf16, const uint8_t *Wgu_q, const uint8_t *Wd_q, const uint32_t *scales_gu,
+                                const uint32_t *scales_d, const uint8_t *Sgu_q, const uint8_t *Sd_q,
+                                const uint32_t *shared_scales_gu, const uint32_t *shared_scales_d, int n_shared, int F_shared,
+                                const int32_t *idx, const float *gate, const int32_t *expert_offsets, const int32_t *perm,
+                                const int32_t *active_experts, const int32_t *num_active, int T, int H, int F, int N,
+                                int k, float *y, void *workspace, void *stream, void *const *stage_events)
+{
+    const lynx::FfnScales q = {reinterpret_cast<const float *>(scales_gu), reinterpret_cast<const float *>(scales_d),
+                               reinterpret_cast<const float *>(shared_scales_gu),
+                               reinterpret_cast<const float *>(shared_scales_d), 2};
+    return lynx::moe_ffn_impl(x_bf16, reinterpret_cast<const uint16_t *>(Wgu_q), reinterpret_cast<const uint16_t *>(Wd_q),
+                              reinterpret_cast<const uint16_t *>(Sgu_q), reinterpret_cast<const uint16_t *>(Sd_q), n_shared,
+                              F_shared, idx, gate, expert_offsets, perm, active_experts, num_active, T, H, F, N, k, y,
+                              workspace, stream, stage_events, false, &q);
 }
 
 extern "C" int lynx_moe_ffn(const uint16_t *x_bf16, const uint16_t *Wgu_packed, const uint16_t *Wd_packed,
