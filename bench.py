@@ -409,42 +409,51 @@ def main():
             out["sweep_score_biased_variant"] = var
 
     if not args.no_fp8:
-        # The same workload with the expert weights in FP8 E4M3 (weight-only, row scales): a widening beyond the
-        # bf16 metric above, reported beside it and never as `value`.
+        # The same workload with the expert weights in FP8 E4M3 (row scales) and in MXFP4 (block scales), both
+        # weight-only: widenings beyond the bf16 metric above, reported beside it and never as `value`.
         L = layer.L
         import workloads as wl2
-        q8 = []
-        for l in range(n_layers):
-            d = wl2.make_layer_device(cfg, 1, "cuda", layer=l)
-            q = L.lynx_quantize_weights_fp8(d["Wg"], d["Wu"], d["Wd"])
-            sh = L.lynx_quantize_weights_fp8(d["Sg"], d["Su"], d["Sd"]) if cfg.n_shared else None
-            torch.cuda.synchronize()
-            q8.append((q, sh))
-            del d
-        buf = layer.buffers(T, beta)
 
-        def step8(i, events=None):
-            q, sh = q8[i % n_layers]
-            return L.lynx_moe_layer_fp8(layer.tokens(T), layer.Wr, layer.bias, q, cfg.F, cfg.k, alpha, beta, enable, sh,
-                                        cfg.n_shared, cfg.F_shared, buffers=buf, stage_events=events)
-        for i in range(W):
-            step8(i)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for i in range(K):
-            step8(i)
-        torch.cuda.synchronize()
-        us8 = (time.perf_counter() - t0) * 1e6 / K
-        for i in range(K):
-            step8(i, events[i][:4])
-        torch.cuda.synchronize()
-        ffn8_ms = sum(e[0].elapsed_time(e[1]) for e in events) / K
-        out["fp8_weights"] = {"us_per_batch": round(us8, 2), "expert_ffn_us": round(ffn8_ms * 1e3, 2),
-                              "weight_bytes": ffn_bytes // 2, "expert_weight_GBps": round(ffn_bytes / 2 / (ffn8_ms * 1e-3) / 1e9, 1),
-                              "hbm_frac": round(ffn_bytes / 2 / (ffn8_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
-                              "speedup_vs_bf16": round(ms_per_step * 1e3 / us8, 3),
-                              "format": "OCP FP8 E4M3 codes + one fp32 scale per weight row; activations bf16"}
-        del q8
+        def quantised_variant(quantize, run_layer, bytes_num, bytes_den):
+            qs = []
+            for l in range(n_layers):
+                d = wl2.make_layer_device(cfg, 1, "cuda", layer=l)
+                q = quantize(d["Wg"], d["Wu"], d["Wd"])
+                sh = quantize(d["Sg"], d["Su"], d["Sd"]) if cfg.n_shared else None
+                torch.cuda.synchronize()
+                qs.append((q, sh))
+                del d
+            buf = layer.buffers(T, beta)
+
+            def step_q(i, ev=None):
+                q, sh = qs[i % n_layers]
+                return run_layer(layer.tokens(T), layer.Wr, layer.bias, q, cfg.F, cfg.k, alpha, beta, enable, sh,
+                                 cfg.n_shared, cfg.F_shared, buffers=buf, stage_events=ev)
+            for i in range(W):
+                step_q(i)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for i in range(K):
+                step_q(i)
+            torch.cuda.synchronize()
+            us = (time.perf_counter() - t0) * 1e6 / K
+            for i in range(K):
+                step_q(i, events[i][:4])
+            torch.cuda.synchronize()
+            ffn_ms = sum(e[0].elapsed_time(e[1]) for e in events) / K
+            nbytes = ffn_bytes * bytes_num // bytes_den
+            return {"us_per_batch": round(us, 2), "expert_ffn_us": round(ffn_ms * 1e3, 2), "weight_bytes": nbytes,
+                    "expert_weight_GBps": round(nbytes / (ffn_ms * 1e-3) / 1e9, 1),
+                    "hbm_frac": round(nbytes / (ffn_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                    "speedup_vs_bf16": round(ms_per_step * 1e3 / us, 3)}
+
+        out["fp8_weights"] = quantised_variant(L.lynx_quantize_weights_fp8, L.lynx_moe_layer_fp8, 1, 2)
+        out["fp8_weights"]["format"] = "OCP FP8 E4M3 codes + one fp32 scale per weight row; activations bf16"
+        if cfg.H % 128 == 0 and cfg.F % 128 == 0 and (cfg.n_shared == 0 or cfg.F_shared % 128 == 0):
+            # 4 bits per weight + 8 bits per block of 32 = 17/64 of the bf16 bytes
+            out["mxfp4_weights"] = quantised_variant(L.lynx_quantize_weights_fp4, L.lynx_moe_layer_fp4, 17, 64)
+            out["mxfp4_weights"]["format"] = ("OCP MXFP4: FP4 E2M1 codes + one E8M0 scale per block of 32 columns; "
+                                              "activations bf16")
 
     if not args.no_cpu_baseline:
         import numpy as np

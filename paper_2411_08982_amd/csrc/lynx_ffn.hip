@@ -354,10 +354,12 @@ __device__ __forceinline__ void decode_tile(uint4 w, float scale, bf16x8 (&a)[1 
 }
 
 // Tiles in flight per wave and stream on the direct path.  MXFP4 tiles carry four k-steps, so the token
-// fragments that travel with a slot are 64 bytes per lane: six slots keep the ring inside the register file.
+// fragments that travel with a slot are 64 bytes per lane, twice the slot's weights: four slots keep the ring
+// inside the register file (measured: 3 and 4 equal, 5 and more spill and are slower; an MXFP4 launch at these
+// sizes is short enough that the fixed part of a launch weighs more than the depth of the ring).
 template <int WF>
 struct DirectDepth {
-    static constexpr int value = WF == 2 ? 6 : kPFD;
+    static constexpr int value = WF == 2 ? 4 : kPFD;
 };
 
 struct WeightRing {
