@@ -17,7 +17,8 @@
 //   * gate/up (with the SiLU-multiply epilogue) and down are ONE kernel whose grid holds the workgroups of
 //     both; it is launched once (down workgroups wait for their expert's gate/up workgroups through
 //     completion counters) or once per projection, whichever measured faster for the shape;
-//   * weights are bf16 or FP8 E4M3 with one scale per row (converted to bf16 in registers).
+//   * weights are bf16, FP8 E4M3 with one scale per row, or MXFP4 with one scale per block of 32 columns (both
+//     converted to bf16 in registers).
 // Launches: the expert kernel (once or twice) and a small combine.
 
 #include "lynx_common.h"
@@ -30,7 +31,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 constexpr int kFfnThreads = 256;
 constexpr int kFfnWaves = kFfnThreads / kWave;
 constexpr int kPF = 8;                       // staged path: weight tiles in flight per wave and matrix
-constexpr int kPFD = 8;                      // direct path: the same
+constexpr int kPFD = 8;                      // direct path: the same (most; see DirectDepth for the depth per format)
 constexpr int kDirectMaxTokens = 16;         // experts with more tokens go to the staged kernel
 constexpr int kTokBlock = 64;                // tokens per pass of the staged path (batches of up to 64 tokens)
 constexpr int kTokBlockBig = 128;            // the same in the kernels launched for larger batches
@@ -40,7 +41,7 @@ constexpr int kStageBytesBig = 2 * 128 * (4 * 64 + 16);   // the same in the lar
 struct GemmParams {
     const uint16_t *W_routed;   // packed routed weights (gate/up interleaved, or down)
     const uint16_t *W_shared;   // packed shared-expert weights or NULL
-    const float *sc_routed;     // FP8 weights: row scales, gate/up [N][2][F] or down [N][H]; else unused
+    const float *sc_routed;     // FP8 weights: row scales, gate/up [N][2][F] or down [N][H]; MXFP4: the scale dwords; else unused
     const float *sc_shared;     // the same for the shared experts
     const uint16_t *B;          // gate/up: x [T,H]; down: h scratch
     void *out;                  // gate/up: h scratch (bf16); down: o scratch (fp32)
@@ -63,7 +64,7 @@ struct WorkItem {
     const uint4 *W;      // packed weights of the expert
     const uint16_t *B;   // B-operand rows
     void *out;
-    const float *sc;     // FP8 weights: this expert's row scales ([2][R] for gate/up, [R] for down)
+    const float *sc;     // FP8 weights: this expert's row scales ([2][R] for gate/up, [R] for down); MXFP4: its scale dwords
     int R, K, tile, Te, off, shared_s, e;
     int ldb, ldo;        // elements between B rows / output rows
     int tok0;            // shared experts: first token of this work item's token block
