@@ -207,3 +207,51 @@ def test_edge_sizes(L, T, N, k, H, F, S, Fs):
         y_ref = oracle.moe_ffn(d["x"], d["Wg"], d["Wu"], d["Wd"], a["new_idx"], a["new_gate"], d["Sg"], d["Su"], d["Sd"])
         err = row_rel_err(host(b.y), y_ref)
         assert err.max() <= Y_TOL, f"max row error {err.max():.3e}"
+
+
+QUANTISED = [("dsv2lite", 16, "fp8"), ("dsv2lite", 16, "fp4"), ("qwen3", 128, "fp8"), ("qwen3", 128, "fp4"),
+             ("qwen15moe", 64, "fp4"), ("mixtral", 8, "fp4")]
+
+
+@pytest.mark.parametrize("name,T,fmt", QUANTISED)
+def test_full_size_layer_quantised_weights(L, name, T, fmt):
+    """The FP8 and MXFP4 weight paths at benchmark sizes: routing as above; the layer output on sampled tokens
+    against the oracle, which quantises the weights of just the experts those tokens use by itself."""
+    print(f"full-size layer {name} T={T} weights={fmt}", flush=True)
+    lay = _layer(L, name)
+    cfg, d = lay.cfg, lay.d
+    (alpha, beta), enable = wl.PRESETS["aggressive"], 1
+    quant = L.lynx_quantize_weights_fp8 if fmt == "fp8" else L.lynx_quantize_weights_fp4
+    run = L.lynx_moe_layer_fp8 if fmt == "fp8" else L.lynx_moe_layer_fp4
+    q = quant(d["Wg"], d["Wu"], d["Wd"])
+    sh = quant(d["Sg"], d["Su"], d["Sd"]) if cfg.n_shared else None
+    xb = lay.tokens(T)
+    b = run(to_bf16_dev(xb), d["Wr"], d["bias"], q, cfg.F, cfg.k, alpha, beta, enable, sh, cfg.n_shared, cfg.F_shared)
+    torch.cuda.synchronize()
+    from paper_2411_08982_amd.binding import WAIT_FLAG_WORD
+    assert int(b.workspace.view(torch.int32)[WAIT_FLAG_WORD]) == 0
+    z = host(b.logits)
+    a = oracle.affinity_bin(z, oracle.topk(z, cfg.k)["idx"], alpha, beta, enable)
+    assert np.array_equal(host(b.new_idx), a["new_idx"])
+    y = host(b.y)
+    assert np.all(np.isfinite(y))
+    toks = sorted({0, T - 1, T // 2})                     # few tokens: the oracle quantises every expert they use
+    sel = a["new_idx"][toks]
+    used = np.unique(sel)
+    remap = {int(e): i for i, e in enumerate(used)}
+    sel_c = np.vectorize(remap.get)(sel).astype(np.int32)
+    ue = torch.from_numpy(used.astype(np.int64)).cuda()
+    W = [bf16_bits(d[k_].index_select(0, ue)) for k_ in ("Wg", "Wu", "Wd")]
+    S = [bf16_bits(d[k_]) for k_ in ("Sg", "Su", "Sd")] if cfg.n_shared else []
+    oq = oracle.quantize_rows_e4m3 if fmt == "fp8" else oracle.quantize_mxfp4
+    ffn = oracle.moe_ffn_q8 if fmt == "fp8" else oracle.moe_ffn_q4
+    (Qg, sg), (Qu, su), (Qd, sd) = (oq(w) for w in W)
+    shared = ()
+    if S:
+        (SQg, ssg), (SQu, ssu), (SQd, ssd) = (oq(w) for w in S)
+        shared = (SQg, SQu, SQd, ssg, ssu, ssd)
+    y_ref = ffn(xb[toks], Qg, Qu, Qd, sg, su, sd, sel_c, a["new_gate"][toks], *shared)
+    err = row_rel_err(y[toks], y_ref)
+    print(f"  invoked {a['num_active'].tolist()}, experts quantised by the oracle {len(used)}, max sampled row err {err.max():.3e}",
+          flush=True)
+    assert err.max() <= Y_TOL
