@@ -232,6 +232,8 @@ FFN_CASES = [
     (300, 128, 96, 4, 2, 2, 64, 2),      # 300 tokens per expert: more than one 128-token block; two shared experts
     (7, 64, 32, 3, 3, 0, 0, None),       # k = N, smallest allowed F
     (64, 2048, 768, 16, 8, 0, 0, None),  # Qwen3-like row / column sizes
+    (96, 512, 128, 256, 8, 0, 0, None),  # very small experts, nearly all 256 invoked: thousands of short workgroups
+    (72, 1024, 256, 200, 4, 1, 128, None),  # the same with a shared expert
 ]
 
 
@@ -240,6 +242,27 @@ def test_moe_ffn(L, T, H, F, N, k, S, Fs, hot):
     _say(f"moe_ffn T={T} H={H} F={F} N={N} k={k} shared={S}x{Fs} hot={hot}")
     e = _ffn_case(L, T, H, F, N, k, S, Fs, seed=T + F, hot=hot)
     _say(f"  max row rel err {e:.3e}")
+
+
+def test_moe_ffn_many_small_experts_and_one_crowded(L):
+    """Nearly all of 256 very small experts invoked (direct path, thousands of short workgroups in one launch) while
+    one expert holds every token and takes the staged path."""
+    rng = np.random.default_rng(21)
+    T, H, F, N, k = 64, 512, 128, 256, 8
+    _say(f"moe_ffn T={T} H={H} F={F} N={N} k={k}: expert 0 has all tokens")
+    x = wl.f32_to_bf16_bits(rng.standard_normal((T, H)).astype(np.float32))
+    Wg, Wu, Wd = wl.bf16_normal(rng, (N, F, H), 0.05), wl.bf16_normal(rng, (N, F, H), 0.05), wl.bf16_normal(rng, (N, H, F), 0.05)
+    idx = np.stack([np.concatenate([[0], 1 + rng.permutation(N - 1)[:k - 1]]) for _ in range(T)]).astype(np.int32)
+    gate = rng.random((T, k)).astype(np.float32) + 0.1
+    gate /= gate.sum(1, keepdims=True)
+    assert len(np.unique(idx)) > 200
+    y_ref = oracle.moe_ffn(x, Wg, Wu, Wd, idx, gate.astype(np.float64))
+    Wgu, Wdp = L.lynx_pack_weights(to_bf16_dev(Wg), to_bf16_dev(Wu), to_bf16_dev(Wd))
+    p = L.lynx_permute(dev(idx), N)
+    y = host(L.lynx_moe_ffn(to_bf16_dev(x), Wgu, Wdp, dev(idx), dev(gate), p, N, F))
+    torch.cuda.synchronize()
+    err = row_rel_err(y, y_ref)
+    assert np.all(np.isfinite(y)) and err.max() <= Y_TOL, f"max row error {err.max():.3e}"
 
 
 def test_moe_ffn_skips_invalid_pairs_without_fault(L):
