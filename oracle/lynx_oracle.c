@@ -18,8 +18,13 @@
  * Pins (tests/test_oracle_*.py): library fp64 matmul / softmax / stable argsort for the plain
  * steps; hand-worked 4x4 example; invariants the paper states (k distinct experts per token,
  * remap onto already-active experts, top-1 of a confident token kept, invoked count never rises);
- * closed-form special cases; exhaustive subset search on tiny batches.
- * Parity unpinned against the paper: the values of alpha and beta (the paper prints none).
+ * closed-form special cases; exhaustive subset search on tiny batches.  The widenings at the end of
+ * the file (score-biased selection; FP8 E4M3 and MXFP4 expert weights) have pins of their own: exact
+ * rational arithmetic and exhaustive search for the bias, the published element tables, an
+ * independent library cast (FP8), brute-force rounding on exact rationals, block exponents and error
+ * bounds (MXFP4), and a numpy fp64 contraction of the dequantised weights for the quantised FFNs.
+ * Parity unpinned against the paper: the values of alpha and beta, the bias scale gamma and the
+ * weight formats (the paper prints none of them).
  */
 #include <math.h>
 #include <stdint.h>
