@@ -31,14 +31,20 @@ def L():
 class Stack:
     """`n_layers` small layers with their own routers and expert weights, resident on the GPU."""
 
-    def __init__(self, L, cfg, T, n_layers, alpha, beta, policy=None):
-        self.L, self.cfg, self.T = L, cfg, T
+    def __init__(self, L, cfg, T, n_layers, alpha, beta, policy=None, weights="bf16"):
+        self.L, self.cfg, self.T, self.weights = L, cfg, T, weights
         # per-layer (alpha, beta, enable): the remapping policy may differ from layer to layer (paper Sec. 3.2.1,
         # layer sensitivity); one setting for all layers by default
         self.policy = list(policy) if policy else [(alpha, beta, 1)] * n_layers
         self.host_layers = [wl.make_layer(cfg, T, layer=l) for l in range(n_layers)]
         self.dev_layers = []
+        quant = {"fp8": L.lynx_quantize_weights_fp8, "fp4": L.lynx_quantize_weights_fp4}.get(weights)
         for d in self.host_layers:
+            if quant:      # quantised experts: (routed, shared) weight objects in the slots of the packed tensors
+                q = quant(to_bf16_dev(d["Wg"]), to_bf16_dev(d["Wu"]), to_bf16_dev(d["Wd"]))
+                sh = quant(to_bf16_dev(d["Sg"]), to_bf16_dev(d["Su"]), to_bf16_dev(d["Sd"])) if cfg.n_shared else None
+                self.dev_layers.append((dev(d["Wr"]), dev(d["bias"]), q, None, sh, None))
+                continue
             Wgu, Wdp = L.lynx_pack_weights(to_bf16_dev(d["Wg"]), to_bf16_dev(d["Wu"]), to_bf16_dev(d["Wd"]))
             Sgu = Sdp = None
             if cfg.n_shared:
@@ -56,8 +62,13 @@ class Stack:
         c = self.cfg
         for l, (Wr, bias, Wgu, Wdp, Sgu, Sdp) in enumerate(self.dev_layers):
             alpha, beta, enable = self.policy[l]
-            b = self.L.lynx_moe_layer(self.x[l], Wr, bias, Wgu, Wdp, c.F, c.k, alpha, beta, enable, Sgu, Sdp,
-                                      c.n_shared, c.F_shared, buffers=self.buf[l])
+            if self.weights != "bf16":
+                layer = self.L.lynx_moe_layer_fp8 if self.weights == "fp8" else self.L.lynx_moe_layer_fp4
+                b = layer(self.x[l], Wr, bias, Wgu, c.F, c.k, alpha, beta, enable, Sgu, c.n_shared, c.F_shared,
+                          buffers=self.buf[l])
+            else:
+                b = self.L.lynx_moe_layer(self.x[l], Wr, bias, Wgu, Wdp, c.F, c.k, alpha, beta, enable, Sgu, Sdp,
+                                          c.n_shared, c.F_shared, buffers=self.buf[l])
             self.L.lynx_residual_add(self.x[l], b.y, out=self.x[l + 1])
 
     def snapshot(self):
@@ -121,11 +132,12 @@ def test_stack_parity_layer_by_layer(L, T, shared, policy):
     print(f"  experts saved over the stack: {remapped}", flush=True)
 
 
+@pytest.mark.parametrize("weights", ["bf16", "fp8", "fp4"])
 @pytest.mark.parametrize("T", [8, 40])
-def test_graph_replays_reproduce_the_eager_stack(L, T):
-    print(f"graph capture of a 3-layer stack, T={T}", flush=True)
+def test_graph_replays_reproduce_the_eager_stack(L, T, weights):
+    print(f"graph capture of a 3-layer stack, T={T}, expert weights {weights}", flush=True)
     cfg = dataclasses.replace(wl.CONFIGS["tiny"], name="graph", H=256, F=384, N=24, k=3, n_shared=1, F_shared=128, seed=12)
-    st = Stack(L, cfg, T, 3, 4.0, 1)
+    st = Stack(L, cfg, T, 3, 4.0, 1, weights=weights)
     st.run()
     eager = st.snapshot()
     other = to_bf16_dev(wl.make_tokens(cfg, T, st.host_layers[0]["Wr"], st.host_layers[0]["bias"], seed=99))
