@@ -1172,8 +1172,20 @@ int moe_ffn_impl(const uint16_t *x_bf16, const uint16_t *Wgu_packed, const uint1
     if (LYNX_MAX_N + (long)n_shared * ((T + tok_block - 1) / tok_block) > kWsDoneWords)
         return fail(LYNX_ERR_UNSUPPORTED, "lynx_moe_ffn: too many shared experts for this batch size (n_shared=%d T=%d)",
                     n_shared, T);
-    const int splits = shared_down_splits(F, n_shared, F_shared);
+    // K slices of a shared expert's down projection.  The workspace is sized for the most there can be; a slice holds
+    // whole weight tiles, ceil(tiles / slices) of them, so fewer slices may already cover all tiles: an empty slice
+    // would leave its output rows unwritten, and the combine adds every slice's rows.
+    int splits = shared_down_splits(F, n_shared, F_shared);
     const Workspace ws = workspace_layout(T, H, F, k, n_shared, F_shared, splits);
+    if (n_shared > 0) {
+        const int kt = F_shared / mult;
+        for (;;) {
+            const int per = (kt + splits - 1) / splits;
+            const int need = (kt + per - 1) / per;
+            if (need == splits) break;
+            splits = need;
+        }
+    }
     if (ws.h_elems >= 0x7fffffffull || ws.o_elems >= 0x7fffffffull * 4)
         return fail(LYNX_ERR_UNSUPPORTED, "lynx_moe_ffn: scratch index would overflow 32 bits");
     uint16_t *hbuf = reinterpret_cast<uint16_t *>(reinterpret_cast<char *>(workspace) + ws.h_off);

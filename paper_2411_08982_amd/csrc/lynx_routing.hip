@@ -335,7 +335,10 @@ __device__ __forceinline__ void token_nominate(const TokenLogits<NS> &tl, int N,
     for (int i = 0; i < NS; ++i) {
         const int r = lane + kWave * i;
         er[i] = (r < N) ? order[r] : 0;
-        qr[i] = (r < N) ? bin_of(zmax, logit_of(tl, er[i]), alpha, beta) : INT_MAX;
+        // every lane takes part in the lane exchange, also those past the last rank: a lane that sits out cannot
+        // be read by the others, and the expert at this lane's rank may live in any lane
+        const float zr = logit_of(tl, er[i]);
+        qr[i] = (r < N) ? bin_of(zmax, zr, alpha, beta) : INT_MAX;
         if (r < N && inU[er[i]]) avail |= 1u << i;
     }
     // bins of the token's own picks, one per lane

@@ -71,7 +71,11 @@ def test_route_ties_go_to_lower_index(L):
 BIN_CASES = [(16, 8, 2, 1.1, 0.0), (8, 8, 2, 1.1, 0.0), (32, 60, 4, 1.0, 0.0), (64, 64, 6, 0.9, 0.05),
              (128, 128, 8, 1.0, 0.0), (512, 128, 8, 1.0, 0.0), (256, 64, 6, 0.9, 0.05), (5, 6, 3, 1.0, 0.2),
              (2, 4, 2, 1.0, 0.0), (1, 8, 2, 1.0, 0.0), (33, 17, 5, 1.0, 0.1), (1024, 256, 16, 1.0, 0.0),
-             (7, 200, 16, 1.0, 0.0), (40, 10, 10, 1.0, 0.0), (9, 12, 1, 1.0, 0.0), (70, 12, 1, 1.0, 0.0)]
+             (7, 200, 16, 1.0, 0.0), (40, 10, 10, 1.0, 0.0), (9, 12, 1, 1.0, 0.0), (70, 12, 1, 1.0, 0.0),
+             # expert counts above 64 that leave the last group of 64 score ranks partly empty, no popularity prior, many
+             # picks per token: experts of the last ranks get nominated (a lane past the last rank must still take part
+             # in the lane exchanges that fetch a ranked expert's logit)
+             (65, 200, 14, 0.0, 0.0), (16, 100, 12, 0.0, 0.0), (48, 130, 16, 0.0, 0.0), (300, 250, 10, 0.3, 0.1)]
 
 
 def _check_bin(L, z, k, alpha, beta, enable):
@@ -215,7 +219,11 @@ def _ffn_case(L, T, H, F, N, k, S, Fs, seed, hot=None, std=0.05):
         Sgu, Sdp = L.lynx_pack_weights(to_bf16_dev(Sg), to_bf16_dev(Su), to_bf16_dev(Sd))
     idx_d = dev(idx)
     p = L.lynx_permute(idx_d, N)
-    y = L.lynx_moe_ffn(to_bf16_dev(x), Wgu, Wdp, idx_d, dev(gate), p, N, F, Sgu, Sdp, S, Fs)
+    # workspace and output start as NaN / -1 patterns: nothing may depend on what a fresh allocation happens to hold
+    ws = L.new_workspace(T, H, F, N, k, S, Fs, "cuda")
+    ws.view(torch.uint8).fill_(0xFF)
+    y0 = torch.full((T, H), float("nan"), dtype=torch.float32, device="cuda")
+    y = L.lynx_moe_ffn(to_bf16_dev(x), Wgu, Wdp, idx_d, dev(gate), p, N, F, Sgu, Sdp, S, Fs, workspace=ws, y=y0)
     torch.cuda.synchronize()
     err = row_rel_err(host(y), y_ref)
     assert np.all(np.isfinite(host(y)))
@@ -234,6 +242,11 @@ FFN_CASES = [
     (64, 2048, 768, 16, 8, 0, 0, None),  # Qwen3-like row / column sizes
     (96, 512, 128, 256, 8, 0, 0, None),  # very small experts, nearly all 256 invoked: thousands of short workgroups
     (72, 1024, 256, 200, 4, 1, 128, None),  # the same with a shared expert
+    # shared experts 18-20 times wider than the routed ones: their down projection is cut into K slices of whole weight
+    # tiles, and 8 slices of ceil(19 / 8) = 3 tiles would leave the last one empty (its output rows must not be summed)
+    (31, 64, 32, 8, 2, 2, 608, None),
+    (8, 64, 32, 8, 2, 1, 576, None),
+    (70, 128, 64, 8, 2, 1, 1216, None),
 ]
 
 

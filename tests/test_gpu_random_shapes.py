@@ -1,0 +1,132 @@
+"""GPU parity of the whole MoE decode layer on seeded random shapes, bf16 / FP8 / MXFP4 expert weights.
+
+The hand-picked cases elsewhere aim at known boundaries (tile edges, the 16-, 64- and 128-token limits).  This
+sweep draws shapes nobody chose: token counts, hidden and FFN widths that are odd multiples of the tile sizes,
+expert counts from 2 to 256, k up to 16, zero to two shared experts narrower or wider than the routed ones, and
+binning parameters over their whole range.  Every case goes through the fused entry point and is compared
+with the oracle step by step: logits within 1e-5 (relative to max(1, |z|)), every integer of routing, binning and
+permutation bit-exact given the GPU's logits, gates within 1e-5, and the layer output per token row within
+max |y - y_ref| / max |y_ref| <= 1e-2.
+"""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads as wl
+from gpu_util import dev, host, row_rel_err, to_bf16_dev
+
+pytestmark = pytest.mark.gpu
+
+Y_TOL = 1e-2
+LOGIT_TOL = 1e-5
+GATE_TOL = 1e-5
+N_CASES = 30
+
+
+@pytest.fixture(scope="module")
+def L():
+    import paper_2411_08982_amd as lib
+    lib.lib()
+    assert torch.cuda.is_available()
+    return lib
+
+
+def draw_case(i):
+    """Case i of the sweep: (weight format, config, T, alpha, beta, enable).  The formats rotate; the column
+    multiple of a weight tile is 32 (bf16), 64 (FP8) or 128 (MXFP4)."""
+    rng = np.random.default_rng([2411, 8982, i])
+    fmt = ("bf16", "fp8", "fp4")[i % 3]
+    mult = {"bf16": 32, "fp8": 64, "fp4": 128}[fmt]
+    T = int(rng.choice([1, 2, 3, 5, 9, 15, 16, 17, 23, 31, 33, 47, 64, 65, 90, 129, 150, 200]))
+    N = int(rng.choice([2, 3, 5, 8, 13, 31, 60, 64, 65, 100, 128, 129, 200, 256]))
+    k = int(rng.integers(1, min(N, 16) + 1))
+    wide = N < 100    # many experts: narrower ones, so that the oracle's quantisers stay in seconds
+    H = mult * int(rng.integers(1, (512 if wide else 256) // mult + 1))
+    F = mult * int(rng.integers(1, (384 if wide else 128) // mult + 1))
+    S = int(rng.choice([0, 0, 1, 2]))
+    Fs = mult * int(rng.integers(1, 640 // mult + 1)) if S else 0
+    alpha = float(rng.choice([0.5, 1.0, 2.0, 4.0, 8.0]))
+    beta = int(rng.integers(1, 7))
+    enable = int(rng.random() < 0.85)
+    cfg = dataclasses.replace(wl.CONFIGS["tiny"], name=f"random{i}", H=H, F=F, N=N, k=k, n_shared=S, F_shared=Fs,
+                              zipf_s=float(rng.choice([0.0, 0.9, 1.3])), bias_scale=float(rng.choice([0.0, 0.5, 2.0])),
+                              tail_frac=float(rng.choice([0.0, 0.1])), seed=1000 + i)
+    return fmt, cfg, T, alpha, beta, enable
+
+
+def poisoned_buffers(L, cfg, T, beta):
+    """Outputs and workspace of a layer call filled with NaN / -1 patterns: the library must not rely on anything a
+    fresh allocation happens to hold (in a new process that is usually zeros, which hides a missing clear or an
+    output row nobody writes)."""
+    b = L.LayerBuffers(T, cfg.H, cfg.F, cfg.N, cfg.k, beta, cfg.n_shared, cfg.F_shared)
+    for t in vars(b).values():
+        if torch.is_tensor(t):
+            t.view(torch.uint8).fill_(0xFF)
+    return b
+
+
+def run_layer(L, fmt, cfg, d, alpha, beta, enable):
+    """The fused layer call for the given weight format, and the oracle's FFN over the same (quantised) weights."""
+    x, Wr, bias = to_bf16_dev(d["x"]), dev(d["Wr"]), dev(d["bias"])
+    buf = poisoned_buffers(L, cfg, x.shape[0], beta)
+    routed = [to_bf16_dev(d[n]) for n in ("Wg", "Wu", "Wd")]
+    shared = [to_bf16_dev(d[n]) for n in ("Sg", "Su", "Sd")] if cfg.n_shared else None
+    tail = (cfg.n_shared, cfg.F_shared)
+    if fmt == "bf16":
+        Wgu, Wdp = L.lynx_pack_weights(*routed)
+        Sgu, Sdp = L.lynx_pack_weights(*shared) if shared else (None, None)
+        b = L.lynx_moe_layer(x, Wr, bias, Wgu, Wdp, cfg.F, cfg.k, alpha, beta, enable, Sgu, Sdp, *tail, buffers=buf)
+
+        def ffn(idx, gate):
+            return oracle.moe_ffn(d["x"], d["Wg"], d["Wu"], d["Wd"], idx, gate, d["Sg"], d["Su"], d["Sd"])
+        return b, ffn
+    quantize, layer, oq, offn = {
+        "fp8": (L.lynx_quantize_weights_fp8, L.lynx_moe_layer_fp8, oracle.quantize_rows_e4m3, oracle.moe_ffn_q8),
+        "fp4": (L.lynx_quantize_weights_fp4, L.lynx_moe_layer_fp4, oracle.quantize_mxfp4, oracle.moe_ffn_q4),
+    }[fmt]
+    q = quantize(*routed)
+    sh = quantize(*shared) if shared else None
+    b = layer(x, Wr, bias, q, cfg.F, cfg.k, alpha, beta, enable, sh, *tail, buffers=buf)
+    (Qg, sg), (Qu, su), (Qd, sd) = (oq(d[n]) for n in ("Wg", "Wu", "Wd"))
+    extra = ()
+    if shared:
+        (SQg, ssg), (SQu, ssu), (SQd, ssd) = (oq(d[n]) for n in ("Sg", "Su", "Sd"))
+        extra = (SQg, SQu, SQd, ssg, ssu, ssd)
+
+    def ffn(idx, gate):
+        return offn(d["x"], Qg, Qu, Qd, sg, su, sd, idx, gate, *extra)
+    return b, ffn
+
+
+@pytest.mark.parametrize("i", range(N_CASES))
+def test_layer_random_shape(L, i):
+    fmt, cfg, T, alpha, beta, enable = draw_case(i)
+    print(f"random layer {i}: {fmt} T={T} H={cfg.H} F={cfg.F} N={cfg.N} k={cfg.k} shared={cfg.n_shared}x{cfg.F_shared} "
+          f"alpha={alpha} beta={beta} enable={enable}", flush=True)
+    d = wl.make_layer(cfg, T)
+    b, ffn = run_layer(L, fmt, cfg, d, alpha, beta, enable)
+    torch.cuda.synchronize()
+    from paper_2411_08982_amd.binding import WAIT_FLAG_WORD
+    assert int(b.workspace.view(torch.int32)[WAIT_FLAG_WORD]) == 0, "a bounded wait inside the launch ran out"
+    r = oracle.route(d["x"], d["Wr"], d["bias"], cfg.k)
+    z = host(b.logits)
+    assert np.all(np.abs(z - r["logits"]) <= LOGIT_TOL * np.maximum(1.0, np.abs(r["logits"])))
+    tk = oracle.topk(z, cfg.k)
+    assert np.array_equal(host(b.topk_idx), tk["idx"])
+    np.testing.assert_allclose(host(b.topk_gate), tk["gate"], rtol=GATE_TOL, atol=1e-7)
+    a = oracle.affinity_bin(z, tk["idx"], alpha, beta, enable)
+    for key, got in (("new_idx", b.new_idx), ("cnt_before", b.cnt_before), ("cnt_after", b.cnt_after),
+                     ("bin_hist", b.bin_hist), ("num_active", b.num_active)):
+        assert np.array_equal(host(got), a[key]), key
+    np.testing.assert_allclose(host(b.new_gate), a["new_gate"], rtol=GATE_TOL, atol=1e-7)
+    p = oracle.permute(a["new_idx"], cfg.N)
+    for key, got in (("offsets", b.offsets), ("perm", b.perm), ("active", b.active), ("num_active", b.num_active_perm)):
+        assert np.array_equal(host(got), p[key]), key
+    y = host(b.y)
+    assert np.all(np.isfinite(y))
+    err = row_rel_err(y, ffn(a["new_idx"], a["new_gate"]))
+    assert err.max() <= Y_TOL, f"max row error {err.max():.3e}"
+    print(f"  invoked {a['num_active'].tolist()}, max row err {err.max():.3e}", flush=True)
