@@ -78,7 +78,8 @@ int lynx_route(const uint16_t *x_bf16, const float *Wr, const float *bias, int T
  *   logit within the active set; gates are the softmax over the k selected original logits.
  *   enable = 0 (batch not memory-bound, Sec. 3.1.1) or T = 1 keeps topk_idx as it is.
  *
- *   logits [T,N] fp32, topk_idx [T,k] int32 (k distinct experts per row, descending logit).
+ *   logits [T,N] fp32, topk_idx [T,k] int32 (k distinct experts per row, descending logit; a row in another
+ *   order is accepted, and a slot that then finds no expert to nominate nominates nothing).
  *   new_idx [T,k] int32 out, new_gate [T,k] fp32 out, cnt_before [N], cnt_after [N] int32 out (pairs
  *   per expert before / after), bin_hist [N,beta] int32 out, num_active [2] int32 out (experts invoked
  *   before, after).  workspace: lynx_workspace_bytes() bytes (the first 64 KiB are used).

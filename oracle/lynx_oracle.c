@@ -247,7 +247,10 @@ int orc_affinity_bin(const float *logits, const int32_t *topk_idx, int T, int N,
                     if (!inU[e] || used[e] || qt[e] > qi) continue;
                     if (best < 0 || score[e] > score[best]) best = e;
                 }
-                /* never empty: the slot's own pick and the picks before it all qualify */
+                /* With the picks in rank order (descending logit, as top-k gives them) this is never empty: the
+                 * slot's own pick and the picks before it all qualify, and fewer than that are used.  Picks handed
+                 * over in another order can leave a slot without a candidate: it nominates nothing. */
+                if (best < 0) continue;
                 used[best] = 1;
                 inA[best] = 1;
             }

@@ -578,23 +578,25 @@ __device__ __forceinline__ void stream_staged(const uint4 *__restrict__ Wt, bool
     const int lastc = (KT * TS + KS - 1) / KS - 1;
 
     // this thread's staging pieces: (token row, 16-byte piece inside the chunk)
-    int xoff[PPT];    // element offset of the piece in chunk 0
+    int xoff[PPT];    // element offset of the piece's token row
     bool xok[PPT];
 #pragma unroll
     for (int i = 0; i < PPT; ++i) {
         const int q = tid + kFfnThreads * i;
-        const int row = q / (KS * 4), pc = q % (KS * 4);
+        const int row = q / (KS * 4);
         const int ro = rowoff[row];
         xok[i] = ro >= 0;
-        xoff[i] = (ro >= 0 ? ro : max(rowoff[0], 0)) + pc * 8;   // rows without a token: the pass's first row, zeroed below
+        xoff[i] = ro >= 0 ? ro : max(rowoff[0], 0);   // rows without a token: the pass's first row, zeroed below
     }
     const int pc0 = (tid % (KS * 4)) * 8;   // column of every piece of this thread inside a chunk (256 % (KS*4) == 0)
     uint4 xr[PPT];
     // chunk c: request it ... (nothing here reads what was loaded: a read would have to wait for the load, and
-    // with it for every weight tile requested before it)
+    // with it for every weight tile requested before it).  A piece past the row's last column (the last chunk of a
+    // ragged K, or a row shorter than one chunk) reads the row's first piece instead, so that no load leaves the
+    // row; it is stored as zero.
     auto load_x = [&](int c) {
-        const int col = c * KS * 32;
-        const int ccol = col + pc0 < K ? col : 0;
+        const int col = c * KS * 32 + pc0;
+        const int ccol = col < K ? col : 0;
 #pragma unroll
         for (int i = 0; i < PPT; ++i) xr[i] = ring_load(reinterpret_cast<const uint4 *>(B + (size_t)xoff[i] + ccol), 0);
     };

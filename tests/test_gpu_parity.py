@@ -104,6 +104,26 @@ def test_affinity_bin(L, T, N, k, s, tail):
     _check_bin(L, z, k, 2.0, 2, 0)                                   # bypass
 
 
+def test_affinity_bin_picks_in_any_order(L):
+    """Picks that are k distinct experts but neither the top-k nor in rank order: same result as the oracle, which
+    lets a slot without a candidate nominate nothing."""
+    for seed in range(12):
+        rng = np.random.default_rng(seed)
+        T = int(rng.choice([3, 16, 17, 70, 300]))
+        N = int(rng.choice([5, 60, 100, 130, 256]))
+        k = int(rng.integers(1, min(N, 16) + 1))
+        alpha, beta = float(rng.choice([0.5, 2.0, 4.0])), int(rng.integers(1, 5))
+        _say(f"affinity_bin, arbitrary picks: T={T} N={N} k={k} alpha={alpha} beta={beta}")
+        z = wl.make_logits(T, N, seed=seed, quantum=[None, 0.25][seed % 2])
+        idx = np.stack([rng.permutation(N)[:k] for _ in range(T)]).astype(np.int32)
+        ref = oracle.affinity_bin(z, idx, alpha, beta, 1)
+        out = L.lynx_affinity_bin(dev(z), dev(idx), alpha, beta, 1)
+        torch.cuda.synchronize()
+        for key in ("new_idx", "cnt_before", "cnt_after", "bin_hist", "num_active"):
+            assert np.array_equal(host(out[key]), ref[key]), key
+        np.testing.assert_allclose(host(out["new_gate"]), ref["new_gate"], rtol=GATE_TOL, atol=1e-7)
+
+
 def test_affinity_bin_worked_example(L, golden_w1):
     z = np.array(golden_w1["logits"], np.float32)
     idx = np.array(golden_w1["topk_idx"], np.int32)
@@ -247,6 +267,10 @@ FFN_CASES = [
     (31, 64, 32, 8, 2, 2, 608, None),
     (8, 64, 32, 8, 2, 1, 576, None),
     (70, 128, 64, 8, 2, 1, 1216, None),
+    # token rows shorter than one staged chunk (H = 32 and 64 against chunks of 128 and 256 columns), experts with
+    # more than 128 tokens (a second pass with few tokens): every load of a token row must stay inside the row
+    (189, 32, 512, 13, 2, 0, 0, 3),
+    (150, 64, 96, 5, 2, 1, 32, 2),
 ]
 
 

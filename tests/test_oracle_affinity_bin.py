@@ -219,6 +219,29 @@ def test_fill_when_nominations_leave_fewer_than_k():
     assert r["new_idx"].tolist() == [[0, 1], [0, 1], [0, 1]]
 
 
+def test_picks_in_any_order_are_accepted():
+    """The picks normally arrive in rank order (descending logit).  Rows in another order must not break anything: a
+    slot whose candidates are all used nominates nothing, the active set stays inside the invoked experts and holds at
+    least min(k, |U|) of them, and the new selection stays inside the active set."""
+    # hand case: token 0 lists its worse pick first; slot 0 (pick 1, bin 1) nominates the best-scoring expert with
+    # bin <= 1, which is expert 0; slot 1 (pick 0, bin 0) finds expert 0 used and no other expert in bin 0
+    z = np.array([[4.0, 3.0, 0.0], [4.0, 3.0, 0.0]], np.float32)
+    idx = np.array([[1, 0], [1, 0]], np.int32)
+    r = oracle.affinity_bin(z, idx, 1.0, 2)
+    assert r["active"].tolist() == [1, 1, 0] and r["new_idx"].tolist() == [[0, 1], [0, 1]]
+    for seed in range(60):
+        rng = np.random.default_rng(seed)
+        T, N = int(rng.integers(2, 200)), int(rng.integers(2, 130))
+        k = int(rng.integers(1, min(N, 16) + 1))
+        z = wl.make_logits(T, N, seed=seed, quantum=[None, 0.25][seed % 2])
+        idx = np.stack([rng.permutation(N)[:k] for _ in range(T)]).astype(np.int32)
+        r = oracle.affinity_bin(z, idx, float(rng.choice([0.5, 2.0, 4.0])), int(rng.integers(1, 5)))
+        U, A = set(idx.ravel().tolist()), set(np.nonzero(r["active"])[0].tolist())
+        assert A <= U and len(A) >= min(k, len(U))
+        assert set(r["new_idx"].ravel().tolist()) <= A
+        assert r["num_active"][1] <= r["num_active"][0] == len(U)
+
+
 def test_errors():
     z = wl.make_logits(4, 4, seed=0)
     idx = _topk(z, 2)
