@@ -17,6 +17,16 @@ def dev(a: np.ndarray):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
+def with_poisoned_tail(t, slack: int = 65536):
+    """The device tensor t re-allocated as the front of a larger buffer whose tail holds 0xFF bytes (NaN as bf16 /
+    fp32, -1 as int32): a kernel that reads a little past the end of t stays inside the allocation, and if the value
+    read takes part in a result the result turns NaN or fails its comparison."""
+    flat = t.contiguous().view(torch.uint8).reshape(-1)
+    big = torch.full((flat.numel() + slack,), 0xFF, dtype=torch.uint8, device=t.device)
+    big[:flat.numel()] = flat
+    return big[:flat.numel()].view(t.dtype).reshape(t.shape)
+
+
 def host(t) -> np.ndarray:
     return t.detach().cpu().numpy()
 

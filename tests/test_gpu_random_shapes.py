@@ -3,7 +3,9 @@
 The hand-picked cases elsewhere aim at known boundaries (tile edges, the 16-, 64- and 128-token limits).  This
 sweep draws shapes nobody chose: token counts, hidden and FFN widths that are odd multiples of the tile sizes,
 expert counts from 2 to 256, k up to 16, zero to two shared experts narrower or wider than the routed ones, and
-binning parameters over their whole range.  Every case goes through the fused entry point and is compared
+binning parameters over their whole range.  Inputs sit in front of a poisoned tail and outputs and workspace start
+poisoned, so that a read past an input's end or of memory nobody wrote shows in the result.  Every case goes through
+the fused entry point and is compared
 with the oracle step by step: logits within 1e-5 (relative to max(1, |z|)), every integer of routing, binning and
 permutation bit-exact given the GPU's logits, gates within 1e-5, and the layer output per token row within
 max |y - y_ref| / max |y_ref| <= 1e-2.
@@ -16,7 +18,8 @@ import torch
 
 import oracle
 import workloads as wl
-from gpu_util import dev, host, row_rel_err, to_bf16_dev
+from gpu_util import host, row_rel_err, with_poisoned_tail
+from gpu_util import dev as plain_dev, to_bf16_dev as plain_to_bf16_dev
 
 pytestmark = pytest.mark.gpu
 
@@ -24,6 +27,14 @@ Y_TOL = 1e-2
 LOGIT_TOL = 1e-5
 GATE_TOL = 1e-5
 N_CASES = 30
+
+
+def dev(a):
+    return with_poisoned_tail(plain_dev(a))
+
+
+def to_bf16_dev(bits):
+    return with_poisoned_tail(plain_to_bf16_dev(bits))
 
 
 @pytest.fixture(scope="module")
