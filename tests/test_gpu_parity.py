@@ -328,6 +328,35 @@ def test_moe_ffn_skips_invalid_pairs_without_fault(L):
 
 # ------------------------------------------------------------------------------------------------ whole layer
 
+def test_moe_ffn_over_expert_shards_sums_to_the_whole(L):
+    """How the path shards by expert: every shard runs the permutation and the FFN over its own experts only, with
+    the pairs of the other shards' experts marked invalid (documented as skipped), and the partial outputs add up to
+    the layer output.  Here the shards run one after the other on the one GPU; the sum stands in for the all-reduce."""
+    rng = np.random.default_rng(11)
+    T, H, F, N, k, shards = 40, 256, 128, 16, 4, 4
+    x = wl.f32_to_bf16_bits(rng.standard_normal((T, H)).astype(np.float32))
+    Wg, Wu, Wd = wl.bf16_normal(rng, (N, F, H), 0.05), wl.bf16_normal(rng, (N, F, H), 0.05), wl.bf16_normal(rng, (N, H, F), 0.05)
+    idx = np.stack([rng.permutation(N)[:k] for _ in range(T)]).astype(np.int32)
+    gate = rng.random((T, k)).astype(np.float32) + 0.1
+    gate /= gate.sum(1, keepdims=True)
+    y_ref = oracle.moe_ffn(x, Wg, Wu, Wd, idx, gate.astype(np.float64))
+    xd, gd = to_bf16_dev(x), dev(gate)
+    per = N // shards
+    total = np.zeros((T, H), np.float64)
+    for s in range(shards):
+        lo = s * per
+        local = np.where((idx >= lo) & (idx < lo + per), idx - lo, -1).astype(np.int32)
+        Wgu, Wdp = L.lynx_pack_weights(to_bf16_dev(Wg[lo:lo + per]), to_bf16_dev(Wu[lo:lo + per]), to_bf16_dev(Wd[lo:lo + per]))
+        ld = dev(local)
+        p = L.lynx_permute(ld, per)
+        y = host(L.lynx_moe_ffn(xd, Wgu, Wdp, ld, gd, p, per, F))
+        torch.cuda.synchronize()
+        assert np.all(np.isfinite(y))
+        assert int(host(p["offsets"])[per]) == int((local >= 0).sum())      # the shard took exactly its own pairs
+        total += y
+    assert row_rel_err(total, y_ref).max() <= Y_TOL
+
+
 def _layer_case(L, cfg, T, alpha, beta, enable, data=None):
     d = data or wl.make_layer(cfg, T)
     x, Wr, bias = to_bf16_dev(d["x"]), dev(d["Wr"]), dev(d["bias"])
