@@ -1,4 +1,5 @@
-"""GPU parity of the whole MoE decode layer on seeded random shapes, bf16 / FP8 / MXFP4 expert weights.
+"""GPU parity on seeded random shapes: the whole MoE decode layer (bf16 / FP8 / MXFP4 expert weights), the FFN alone
+with token distributions no router produces, and the binning entry points alone.
 
 The hand-picked cases elsewhere aim at known boundaries (tile edges, the 16-, 64- and 128-token limits).  This
 sweep draws shapes nobody chose: token counts, hidden and FFN widths that are odd multiples of the tile sizes,
@@ -141,3 +142,118 @@ def test_layer_random_shape(L, i):
     err = row_rel_err(y, ffn(a["new_idx"], a["new_gate"]))
     assert err.max() <= Y_TOL, f"max row error {err.max():.3e}"
     print(f"  invoked {a['num_active'].tolist()}, max row err {err.max():.3e}", flush=True)
+
+
+# ---- the FFN alone: token distributions a router would not produce -------------------------------------------------
+
+N_FFN_CASES = 24
+
+
+def draw_ffn_case(i):
+    """Weight format, shapes, and picks concentrated on `hot` experts (up to hundreds of tokens on one expert, most
+    experts idle), some pairs invalid (an index outside [0, N): documented as skipped)."""
+    rng = np.random.default_rng([8982, 2411, i])
+    fmt = ("bf16", "fp8", "fp4")[i % 3]
+    mult = {"bf16": 32, "fp8": 64, "fp4": 128}[fmt]
+    T = int(rng.integers(130, 600)) if i % 4 == 0 else int(rng.integers(1, 150))
+    N = int(rng.integers(1, 65))
+    k = int(rng.integers(1, min(N, 8) + 1))
+    hot = int(rng.integers(k, N + 1)) if rng.random() < 0.6 else N
+    H = mult * int(rng.integers(1, 256 // mult + 1))
+    F = mult * int(rng.integers(1, 256 // mult + 1))
+    S = int(rng.choice([0, 0, 1, 2]))
+    Fs = mult * int(rng.integers(1, 1280 // mult)) if S else 0
+    idx = np.stack([rng.permutation(hot)[:k] for _ in range(T)]).astype(np.int32)
+    gate = rng.random((T, k)).astype(np.float32) + 0.1
+    gate /= gate.sum(1, keepdims=True)
+    invalid = np.zeros((T, k), bool)
+    if rng.random() < 0.4:
+        invalid = rng.random((T, k)) < 0.1
+        invalid[0, 0] = False
+    bad = np.where(invalid, np.where(rng.random((T, k)) < 0.5, -1, N + 5), idx).astype(np.int32)
+    return fmt, (T, H, F, N, k, S, Fs, hot), rng, idx, bad, gate, invalid
+
+
+@pytest.mark.parametrize("i", range(N_FFN_CASES))
+def test_ffn_random_tokens(L, i):
+    fmt, (T, H, F, N, k, S, Fs, hot), rng, idx, bad, gate, invalid = draw_ffn_case(i)
+    print(f"random ffn {i}: {fmt} T={T} H={H} F={F} N={N} k={k} hot={hot} shared={S}x{Fs} invalid={int(invalid.sum())}",
+          flush=True)
+    x = wl.f32_to_bf16_bits(rng.standard_normal((T, H)).astype(np.float32))
+    Wg, Wu, Wd = (wl.bf16_normal(rng, shape, 0.05) for shape in ((N, F, H), (N, F, H), (N, H, F)))
+    Sg = Su = Sd = None
+    if S:
+        Sg, Su, Sd = (wl.bf16_normal(rng, shape, 0.05) for shape in ((S, Fs, H), (S, Fs, H), (S, H, Fs)))
+    g_ref = np.where(invalid, 0.0, gate.astype(np.float64))      # a skipped pair = its gate at zero
+    idx_d = dev(bad)
+    p = L.lynx_permute(idx_d, N)
+    ws = L.new_workspace(T, H, F, N, k, S, Fs, "cuda")
+    ws.fill_(0xFF)
+    y0 = torch.full((T, H), float("nan"), dtype=torch.float32, device="cuda")
+    routed = [to_bf16_dev(W) for W in (Wg, Wu, Wd)]
+    shared = [to_bf16_dev(W) for W in (Sg, Su, Sd)] if S else None
+    if fmt == "bf16":
+        y_ref = oracle.moe_ffn(x, Wg, Wu, Wd, idx, g_ref, Sg, Su, Sd)
+        Wgu, Wdp = L.lynx_pack_weights(*routed)
+        Sgu, Sdp = L.lynx_pack_weights(*shared) if S else (None, None)
+        y = L.lynx_moe_ffn(to_bf16_dev(x), Wgu, Wdp, idx_d, dev(gate), p, N, F, Sgu, Sdp, S, Fs, workspace=ws, y=y0)
+    else:
+        quantize, ffn, oq, offn = {
+            "fp8": (L.lynx_quantize_weights_fp8, L.lynx_moe_ffn_fp8, oracle.quantize_rows_e4m3, oracle.moe_ffn_q8),
+            "fp4": (L.lynx_quantize_weights_fp4, L.lynx_moe_ffn_fp4, oracle.quantize_mxfp4, oracle.moe_ffn_q4),
+        }[fmt]
+        (Qg, sg), (Qu, su), (Qd, sd) = (oq(W) for W in (Wg, Wu, Wd))
+        extra = ()
+        if S:
+            (SQg, ssg), (SQu, ssu), (SQd, ssd) = (oq(W) for W in (Sg, Su, Sd))
+            extra = (SQg, SQu, SQd, ssg, ssu, ssd)
+        y_ref = offn(x, Qg, Qu, Qd, sg, su, sd, idx, g_ref, *extra)
+        y = ffn(to_bf16_dev(x), quantize(*routed), idx_d, dev(gate), p, N, F, quantize(*shared) if S else None, S, Fs,
+                workspace=ws, y=y0)
+    torch.cuda.synchronize()
+    y = host(y)
+    assert np.all(np.isfinite(y))
+    err = row_rel_err(y, y_ref)
+    assert err.max() <= Y_TOL, f"max row error {err.max():.3e}"
+
+
+# ---- binning alone: top-k picks, picks in arbitrary order, the score-biased variant -------------------------------
+
+@pytest.mark.parametrize("block", range(4))
+def test_affinity_bin_random(L, block):
+    for i in range(block * 40, block * 40 + 40):
+        rng = np.random.default_rng([89, 82, i])
+        T = int(rng.integers(1, 1025)) if rng.random() < 0.25 else int(rng.integers(1, 100))
+        N = int(rng.integers(2, 257))
+        k = int(rng.integers(1, min(N, 16) + 1))
+        alpha = float(rng.choice([0.0, 0.25, 0.5, 1.0, 2.0, 3.0, 4.0, 8.0, 64.0, 1e6]))
+        beta = int(rng.integers(1, 7))
+        while float(T) ** beta >= 2.0 ** 62:
+            beta -= 1
+        gamma = float(rng.choice([0.0, 0.5, 1.0, 4.0, 1e6]))
+        quantum = [None, 0.25, 1.0][int(rng.integers(0, 3))]
+        mode = int(rng.integers(0, 3))    # 0: top-k picks, 1: k distinct experts in any order, 2: score-biased variant
+        enable = int(rng.random() < 0.9)
+        print(f"random bin {i}: T={T} N={N} k={k} alpha={alpha} beta={beta} gamma={gamma} quantum={quantum} mode={mode} "
+              f"enable={enable}", flush=True)
+        z = wl.make_logits(T, N, seed=7000 + i, zipf_s=float(rng.choice([0.0, 1.0, 1.5])),
+                           tail_frac=float(rng.choice([0.0, 0.1])), quantum=quantum)
+        if mode == 1:
+            idx = np.stack([rng.permutation(N)[:k] for _ in range(T)]).astype(np.int32)
+        else:
+            idx = oracle.topk(z, k)["idx"]
+        if mode == 2:
+            ref = oracle.affinity_bin_biased(z, idx, alpha, beta, gamma, enable)
+            out = L.lynx_affinity_bin_biased(dev(z), dev(idx), alpha, beta, gamma, enable)
+        else:
+            ref = oracle.affinity_bin(z, idx, alpha, beta, enable)
+            out = L.lynx_affinity_bin(dev(z), dev(idx), alpha, beta, enable)
+        torch.cuda.synchronize()
+        for key in ("new_idx", "cnt_before", "cnt_after", "bin_hist", "num_active"):
+            assert np.array_equal(host(out[key]), ref[key]), key
+        np.testing.assert_allclose(host(out["new_gate"]), ref["new_gate"], rtol=GATE_TOL, atol=1e-7)
+        p = L.lynx_permute(out["new_idx"], N)
+        torch.cuda.synchronize()
+        pr = oracle.permute(ref["new_idx"], N)
+        for key in ("offsets", "perm", "active", "num_active"):
+            assert np.array_equal(host(p[key]), pr[key]), key
