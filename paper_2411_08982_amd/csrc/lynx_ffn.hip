@@ -266,10 +266,11 @@ __device__ __forceinline__ void epilogue(const f32x4 (&accg_in)[NT], const f32x4
 // ---------------------------------------------------------------------------------------------------
 
 // Direct: Wt = first weight tile of this wave (uint4 units); n = k-steps of this wave (>= 1);
-// brow[nt] = this lane's B pointer at the wave's first column (4 uint4 = 32 columns per step).
+// boff[nt] = byte offset of this lane's B piece at the wave's first column (4 x 16 bytes = 32 columns per step).
 // The address passes through an empty asm so that the compiler treats every ring load as a distinct,
 // unmovable-by-value-numbering load: otherwise it merges the prefetch for the next turn of the ring
 // with the loads of that turn and issues them only when they are needed.
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ uint4 ring_load(const uint4 *__restrict__ base, int index)
 {
     asm volatile("" : "+v"(index));
@@ -281,11 +282,27 @@ __device__ __forceinline__ uint4 ring_load(const uint4 *__restrict__ base, int i
 // are invalidated when a kernel starts, a row is first touched after its expert's counter says it is complete,
 // and rows start on 128-byte lines, so no cache on the reading side can hold an older copy of a line.  (Device-
 // coherent loads instead would send every workgroup's re-reads of the same few rows to memory.)
-__device__ __forceinline__ uint4 ring_load_b(const uint4 *__restrict__ base, int index) { return ring_load(base, index); }
+//
+// They are read through a buffer resource over the B array with a byte offset per lane.  A lane whose token column
+// is empty (an expert with 3 tokens fills 3 of the 16 columns of a fragment) carries an offset past the resource's
+// range: the hardware returns zero for it and fetches nothing.  The load path's time goes with the lanes that are in
+// range (measured on a cache-resident region: 16 bytes per lane with 2 of 16 token columns in range cost 0.38 of
+// the full load), and with 4-bit weights the token fragments are four times the bytes of the weights they meet.
+constexpr unsigned kNoToken = 0x80000000u;   // past any resource (the B arrays stay below 2 GiB, checked on the host)
+typedef __amdgpu_buffer_rsrc_t BufferRsrc;
+__device__ __forceinline__ BufferRsrc token_rows_resource(const uint16_t *B)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(B), 0, 0x7fffffff, 0x00020000);
+}
+__device__ __forceinline__ uint4 ring_load_b(BufferRsrc rs, unsigned off, int index)
+{
+    asm volatile("" : "+v"(index));
+    const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, off + (unsigned)index * 16u, 0, 0);
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
 
 // The same for expert weights, as a non-temporal load: a weight byte is read once per launch, and a stream
 // that does not allocate in the caches on its way runs measurably closer to the HBM rate.
-typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ uint4 ring_load_weights(const uint4 *__restrict__ base, int index)
 {
     asm volatile("" : "+v"(index));
@@ -427,7 +444,7 @@ __device__ __forceinline__ void prefetch_weights(const DirectPlan &d, WeightRing
 
 // The ring arrives with its first turn of weight tiles already requested (prefetch_weights).
 template <int NT, int WF>
-__device__ __forceinline__ void stream_direct(const DirectPlan &d, WeightRing &r, const uint4 *const (&brow)[NT],
+__device__ __forceinline__ void stream_direct(const DirectPlan &d, WeightRing &r, BufferRsrc rs, const unsigned (&boff)[NT],
                                               f32x4 (&acc0)[NT], f32x4 (&acc1)[NT])
 {
     constexpr int D = DirectDepth<WF>::value;
@@ -444,7 +461,7 @@ __device__ __forceinline__ void stream_direct(const DirectPlan &d, WeightRing &r
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-            for (int h = 0; h < BP; ++h) bb[j][nt][h] = ring_load_b(brow[nt], s * BS + h);
+            for (int h = 0; h < BP; ++h) bb[j][nt][h] = ring_load_b(rs, boff[nt], s * BS + h);
     }
     // One turn of the ring: consume the D slots in order, refilling each right after its last read.
     auto turn = [&](int s0) {
@@ -475,7 +492,7 @@ __device__ __forceinline__ void stream_direct(const DirectPlan &d, WeightRing &r
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-                for (int h = 0; h < BP; ++h) bb[u][nt][h] = ring_load_b(brow[nt], sn * BS + h);
+                for (int h = 0; h < BP; ++h) bb[u][nt][h] = ring_load_b(rs, boff[nt], sn * BS + h);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -506,21 +523,17 @@ __device__ __forceinline__ void expert_direct(const GemmParams &p, const WorkIte
     const int kbc = d.n > 0 ? d.kb : 0;
 
     int orow[NT];
-    const uint4 *brow[NT];
+    unsigned boff[NT];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
         int ro;
         token_rows<DUAL>(p, w, nt * 16 + (lane & 15), ro, orow[nt]);
-        if (ro < 0) {   // columns without a token read the work item's first row (a row that is complete, which an
-            int none;   // arbitrary row of the intermediate vectors need not be); their results are never stored
-            token_rows<DUAL>(p, w, 0, ro, none);
-            ro = max(ro, 0);
-        }
-        brow[nt] = reinterpret_cast<const uint4 *>(w.B + (size_t)ro + (size_t)kbc * KC + (lane >> 4) * (KC / 4));
+        // columns without a token fetch nothing and read as zero; their results are never stored
+        boff[nt] = ro < 0 ? kNoToken : 2u * ((unsigned)ro + (unsigned)kbc * KC + (unsigned)(lane >> 4) * (KC / 4));
     }
     f32x4 acc0[NT], acc1[NT];
     clear_acc<NT>(acc0, acc1);
-    stream_direct<NT, WF>(d, ring, brow, acc0, acc1);
+    stream_direct<NT, WF>(d, ring, token_rows_resource(w.B), boff, acc0, acc1);
     if (KW > 1) {
         f32x4 *r4 = reinterpret_cast<f32x4 *>(red);   // [rw][kw-1][NACC][lane]
         if (kw > 0) {
@@ -1188,7 +1201,8 @@ int moe_ffn_impl(const uint16_t *x_bf16, const uint16_t *Wgu_packed, const uint1
             splits = need;
         }
     }
-    if (ws.h_elems >= 0x7fffffffull || ws.o_elems >= 0x7fffffffull * 4)
+    // (token rows are addressed with 32-bit byte offsets below 2 GiB)
+    if (ws.h_elems >= 0x3fffffffull || (unsigned long long)T * H >= 0x3fffffffull || ws.o_elems >= 0x7fffffffull * 4)
         return fail(LYNX_ERR_UNSUPPORTED, "lynx_moe_ffn: scratch index would overflow 32 bits");
     uint16_t *hbuf = reinterpret_cast<uint16_t *>(reinterpret_cast<char *>(workspace) + ws.h_off);
     float *obuf = reinterpret_cast<float *>(reinterpret_cast<char *>(workspace) + ws.o_off);
