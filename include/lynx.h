@@ -3,7 +3,7 @@
  * Lynx (arXiv 2411.08982): router logits, softmax and top-k (Sec. 2.1); AffinityBinning, batch-wide
  * expert scoring and remapping (Secs. 3.2.1, 3.3.1, 3.4); token assignment and weight
  * renormalisation (Sec. 4); grouped SwiGLU expert FFN over the experts still invoked, and the
- * gate-weighted combine (the "expert computation kernel" the remapper dispatches, Sec. 3.4).
+ * gate-weighted combine (the expert computation that the remapper dispatches, Sec. 3.4).
  *
  * Conventions
  *  - Every pointer is a DEVICE pointer owned by the caller unless it says "host".  The library
@@ -89,8 +89,8 @@ int lynx_affinity_bin(const float *logits, const int32_t *topk_idx, int T, int N
                       int32_t *bin_hist, int32_t *num_active, void *workspace, void *stream);
 
 /*
- * Score-biased selection: the variant of the adaptive expert scorer that takes Sec. 3.3.1's sentence "a
- * weighted score is added to its router logit" literally.  Bins, histogram and base-T scores exactly as in
+ * Score-biased selection: the variant of the adaptive expert scorer that takes literally what Sec. 3.3.1 says
+ * of it, namely that a weighted batch-level score is added to an expert's router logit.  Bins, histogram and base-T scores exactly as in
  * lynx_affinity_bin; then bias[e] = gamma * score[e] / T^beta (score / T^beta in [0,1]: one fp64 division
  * rounded to fp32, one fp32 multiply), and every token keeps its top-ranked expert (Sec. 3.3.1) and fills
  * its other k-1 slots with the experts of largest logit + bias (one fp32 addition) among those the batch

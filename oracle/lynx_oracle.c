@@ -77,7 +77,7 @@ static int topk_select(const float *z, const uint8_t *allowed, int N, int k, int
     return found;
 }
 
-/* Gates of a selection: softmax over the k selected logits only (Sec. 4, "renormalizes weights"). */
+/* Gates of a selection: softmax over the k selected logits only (Sec. 4: the weights are renormalised over the new selection). */
 static void gates_of_selection(const float *z, const int32_t *sel, int k, double *gate)
 {
     double zmax = (double)z[sel[0]];
@@ -295,8 +295,9 @@ int orc_affinity_bin(const float *logits, const int32_t *topk_idx, int T, int N,
 }
 
 /*
- * Score-biased selection, the literal reading of Sec. 3.3.1 ("a weighted score is added to its router logit
- * based on how frequently other tokens in the batch preferred it"), as a variant of orc_affinity_bin:
+ * Score-biased selection, the literal reading of the passage of Sec. 3.3.1 that describes the scorer as adding
+ * to an expert's router logit a weighted score that grows with how often the batch's other tokens prefer that
+ * expert, as a variant of orc_affinity_bin:
  * bins, histogram and base-T scores exactly as there; then, instead of nominations and an active set,
  *   s_e    = score_e / T^beta                 in [0, 1] (fp64 division, rounded once to fp32),
  *   z'[t,e] = z[t,e] + gamma * s_e            (one fp32 multiply, one fp32 add),

@@ -1,4 +1,4 @@
-// lynx_permute: token assignment for the grouped expert FFN (paper Sec. 4, "assigns tokens") as a
+// lynx_permute: token assignment for the grouped expert FFN (paper Sec. 4: the remapper hands every expert its tokens) as a
 // stand-alone call: one workgroup builds the per-expert token bit sets in LDS with atomic ORs
 // (order-free) and derives offsets, the stable permutation and the invoked-expert list from them.
 #include "lynx_permute_core.h"

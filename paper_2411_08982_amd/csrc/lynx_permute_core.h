@@ -1,4 +1,4 @@
-// Token assignment from per-expert token bit sets (paper Sec. 4, "assigns tokens"), shared by the
+// Token assignment from per-expert token bit sets (paper Sec. 4: the remapper hands every expert its tokens), shared by the
 // stand-alone lynx_permute kernel and by the last workgroup of the fused remap kernel.
 //
 // A token holds k distinct experts, so an expert sees a token at most once: the membership of the batch

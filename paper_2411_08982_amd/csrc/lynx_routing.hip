@@ -251,7 +251,7 @@ __device__ __forceinline__ float token_max(const TokenLogits<NS> &t)
 }
 
 // Gates of a selection held one per lane (lane j < k: expert mye, logit myz): softmax over the selected
-// logits (paper Sec. 4, "renormalizes weights").  Returns this lane's gate; num = sum of the numerators.
+// logits (paper Sec. 4: the weights are renormalised over the new selection).  Returns this lane's gate; num = sum of the numerators.
 __device__ __forceinline__ float selection_gate(int k, int mye, float myz, float &num, float &zref)
 {
     zref = wave_max(myz);
