@@ -328,6 +328,56 @@ def test_moe_ffn_skips_invalid_pairs_without_fault(L):
 
 # ------------------------------------------------------------------------------------------------ whole layer
 
+def _check_indices_in_range(new_idx, perm, offs, T, N, k):
+    assert new_idx.min() >= -1 and new_idx.max() < N
+    assert np.all(np.diff(offs) >= 0) and offs[0] >= 0 and offs[N] <= T * k
+    assert offs[N] == int((new_idx >= 0).sum())
+    valid = perm[:offs[N]]
+    assert len(set(valid.tolist())) == len(valid)
+    assert valid.size == 0 or (valid.min() >= 0 and valid.max() < T * k)
+
+
+@pytest.mark.parametrize("T,N,k", [(8, 12, 3), (40, 70, 6)])
+def test_non_finite_inputs_stay_in_bounds(L, T, N, k):
+    """Inputs are assumed finite; a token whose logits are not gets an undefined selection, but every index the
+    calls produce stays in range (or is -1 = no expert), the permutation stays a permutation of the valid pairs, and
+    the tokens with finite inputs still get finite outputs."""
+    rng = np.random.default_rng(T)
+    H, F = 64, 64
+    _say(f"non-finite inputs T={T} N={N} k={k}")
+    Wg, Wu, Wd = wl.bf16_normal(rng, (N, F, H), 0.05), wl.bf16_normal(rng, (N, F, H), 0.05), wl.bf16_normal(rng, (N, H, F), 0.05)
+    Wgu, Wdp = L.lynx_pack_weights(to_bf16_dev(Wg), to_bf16_dev(Wu), to_bf16_dev(Wd))
+    bad_tokens = [1, 2, 3, 4, 5]
+    good = [t for t in range(T) if t not in bad_tokens]
+    # (a) the binning call alone, valid picks, logits with NaN and infinities
+    z = wl.make_logits(T, N, seed=T)
+    z[1, :] = np.nan
+    z[2, 3] = np.inf
+    z[3, 0] = -np.inf
+    z[4, ::2] = np.nan
+    z[5, :] = np.inf
+    idx = np.stack([rng.permutation(N)[:k] for _ in range(T)]).astype(np.int32)
+    a = L.lynx_affinity_bin(dev(z), dev(idx), 2.0, 2, 1)
+    p = L.lynx_permute(a["new_idx"], N)
+    torch.cuda.synchronize()
+    _check_indices_in_range(host(a["new_idx"]), host(p["perm"]), host(p["offsets"]), T, N, k)
+    # (b) the whole layer with hidden states that are not finite for some tokens: their logits, picks and gates are
+    # whatever they are; the rest of the batch is served
+    x = rng.standard_normal((T, H)).astype(np.float32)
+    x[1, :] = np.nan
+    x[2, 7] = np.inf
+    x[3, :] = -np.inf
+    x[4, ::3] = np.nan
+    x[5, 0] = np.inf
+    x[5, 1] = -np.inf
+    Wr = (rng.standard_normal((N, H)) / np.sqrt(H)).astype(np.float32)
+    b = L.lynx_moe_layer(to_bf16_dev(wl.f32_to_bf16_bits(x)), dev(Wr), None, Wgu, Wdp, F, k, 2.0, 2, 1)
+    torch.cuda.synchronize()
+    _check_indices_in_range(host(b.new_idx), host(b.perm), host(b.offsets), T, N, k)
+    assert np.all(np.isfinite(host(b.y)[good]))
+    assert np.all(np.isfinite(host(b.logits)[good]))
+
+
 def test_moe_ffn_over_expert_shards_sums_to_the_whole(L):
     """How the path shards by expert: every shard runs the permutation and the FFN over its own experts only, with
     the pairs of the other shards' experts marked invalid (documented as skipped), and the partial outputs add up to
