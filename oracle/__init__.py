@@ -44,6 +44,8 @@ def _load():
         lib.orc_num_threads.restype = c_int
         lib.orc_route.argtypes = [u16p, f32p, f32p, c_int, c_int, c_int, c_int, f32p, i32p, f64p, f64p]
         lib.orc_topk.argtypes = [f32p, c_int, c_int, c_int, i32p, f64p, f64p]
+        lib.orc_topk_sigmoid.argtypes = [f32p, c_int, c_int, c_int, i32p, f64p, f64p]
+        lib.orc_sigmoid_gates.argtypes = [f32p, i32p, c_int, c_int, c_int, f64p, f64p]
         lib.orc_affinity_bin.argtypes = [f32p, i32p, c_int, c_int, c_int, c_float, c_int, c_int, i32p, f64p, i32p,
                                          i32p, i32p, i32p, i32p, u64p, i32p]
         lib.orc_affinity_bin_biased.argtypes = [f32p, i32p, c_int, c_int, c_int, c_float, c_int, c_float, c_int, i32p,
@@ -67,8 +69,8 @@ def _load():
         lib.orc_moe_ffn_q8.argtypes = [u16p, u8p, u8p, u8p, f32p, f32p, f32p, u8p, u8p, u8p, f32p, f32p, f32p, c_int, c_int,
                                        i32p, f64p, c_int, c_int, c_int, c_int, c_int, f64p]
         lib.orc_moe_ffn_q8.restype = c_int
-        for f in (lib.orc_route, lib.orc_topk, lib.orc_affinity_bin, lib.orc_affinity_bin_biased, lib.orc_permute,
-                  lib.orc_moe_ffn):
+        for f in (lib.orc_route, lib.orc_topk, lib.orc_topk_sigmoid, lib.orc_sigmoid_gates, lib.orc_affinity_bin,
+                  lib.orc_affinity_bin_biased, lib.orc_permute, lib.orc_moe_ffn):
             f.restype = c_int
         _lib = lib
     return _lib
@@ -126,6 +128,42 @@ def topk(logits, k):
     if rc != OK:
         raise OracleError(rc, "orc_topk")
     return dict(idx=idx, gate=gate, psum=psum)
+
+
+def topk_sigmoid(logits, k):
+    """Sigmoid-gated router: top-k by logit, gates = selected sigmoid scores / their sum.
+    Returns dict(idx, gate f64, ssum f64 = sum of the selected scores)."""
+    z = _arr(logits, np.float32)
+    T, N = z.shape
+    idx = np.zeros((T, k), np.int32)
+    gate = np.zeros((T, k), np.float64)
+    ssum = np.zeros((T,), np.float64)
+    rc = _load().orc_topk_sigmoid(_p(z, c_float), T, N, k, _p(idx, c_int32), _p(gate, c_double), _p(ssum, c_double))
+    if rc != OK:
+        raise OracleError(rc, "orc_topk_sigmoid")
+    return dict(idx=idx, gate=gate, ssum=ssum)
+
+
+def sigmoid_gates(logits, idx):
+    """Gates of a given selection idx [T,k] under a sigmoid-gated router.  Returns (gate f64 [T,k], ssum f64 [T])."""
+    z = _arr(logits, np.float32)
+    idx = _arr(idx, np.int32)
+    T, N = z.shape
+    k = idx.shape[1]
+    gate = np.zeros((T, k), np.float64)
+    ssum = np.zeros((T,), np.float64)
+    rc = _load().orc_sigmoid_gates(_p(z, c_float), _p(idx, c_int32), T, N, k, _p(gate, c_double), _p(ssum, c_double))
+    if rc != OK:
+        raise OracleError(rc, "orc_sigmoid_gates")
+    return gate, ssum
+
+
+def affinity_bin_sigmoid(logits, topk_idx, alpha, beta, enable=1):
+    """AffinityBinning under a sigmoid-gated router: bins, scores, nominations and remap exactly as affinity_bin (they
+    use logit differences only); the gates of the new selection are the sigmoid scores over their sum."""
+    a = affinity_bin(logits, topk_idx, alpha, beta, enable)
+    a["new_gate"], _ = sigmoid_gates(logits, a["new_idx"])
+    return a
 
 
 def affinity_bin(logits, topk_idx, alpha, beta, enable=1):

@@ -22,9 +22,10 @@
  * the file (score-biased selection; FP8 E4M3 and MXFP4 expert weights) have pins of their own: exact
  * rational arithmetic and exhaustive search for the bias, the published element tables, an
  * independent library cast (FP8), brute-force rounding on exact rationals, block exponents and error
- * bounds (MXFP4), and a numpy fp64 contraction of the dequantised weights for the quantised FFNs.
- * Parity unpinned against the paper: the values of alpha and beta, the bias scale gamma and the
- * weight formats (the paper prints none of them).
+ * bounds (MXFP4), and a numpy fp64 contraction of the dequantised weights for the quantised FFNs; the
+ * gates of sigmoid-gated routers: closed forms, a library logistic function, and what tells them from softmax.
+ * Parity unpinned against the paper: the values of alpha and beta, the bias scale gamma, the
+ * weight formats and the gate formula of sigmoid-gated routers (the paper prints none of them).
  */
 #include <math.h>
 #include <stdint.h>
@@ -108,6 +109,46 @@ int orc_topk(const float *logits, int T, int N, int k, int32_t *topk_idx, double
         select_and_weigh(logits + (size_t)t * N, N, k, topk_idx + (size_t)t * k, topk_gate + (size_t)t * k,
                          topk_psum + t);
     return ORC_OK;
+}
+
+/*
+ * Sigmoid-gated routers (Sec. 3.2.1 closes with the case of routers that do not use softmax: the bins are then
+ * taken from differences of the scores before the sigmoid, i.e. of the logits, exactly as above; so binning, scoring,
+ * nominations and the remap are orc_affinity_bin unchanged).  What differs is the weight of a selected expert.  The
+ * paper prints no formula for it; the reading here is the usual one for such routers: score s = 1 / (1 + exp(-z)),
+ * the k experts of largest score per token, and gates = the selected scores divided by their sum.  The sigmoid is
+ * strictly increasing, so the selection is taken on the fp32 logits themselves (descending, ties to the lower index):
+ * in floating point distinct logits can share a score, and both sides of a parity test must break such ties alike.
+ *
+ * orc_sigmoid_gates: gates [T,k] (fp64) and the sum of the selected scores ssum [T] for a given selection idx [T,k].
+ * orc_topk_sigmoid: selection by logit, then the same.
+ */
+static double sigmoid64(double z) { return z >= 0.0 ? 1.0 / (1.0 + exp(-z)) : exp(z) / (1.0 + exp(z)); }
+
+int orc_sigmoid_gates(const float *logits, const int32_t *idx, int T, int N, int k, double *gate, double *ssum)
+{
+    if (T < 0 || N <= 0 || k <= 0) return ORC_ERR_INVALID_ARG;
+    if (k > N) return ORC_ERR_UNSUPPORTED;
+    for (int t = 0; t < T; ++t) {
+        double sum = 0.0;
+        for (int j = 0; j < k; ++j) {
+            const int32_t e = idx[(size_t)t * k + j];
+            if (e < 0 || e >= N) return ORC_ERR_INVALID_ARG;
+            sum += sigmoid64((double)logits[(size_t)t * N + e]);
+        }
+        for (int j = 0; j < k; ++j)
+            gate[(size_t)t * k + j] = sigmoid64((double)logits[(size_t)t * N + idx[(size_t)t * k + j]]) / sum;
+        if (ssum) ssum[t] = sum;
+    }
+    return ORC_OK;
+}
+
+int orc_topk_sigmoid(const float *logits, int T, int N, int k, int32_t *topk_idx, double *topk_gate, double *topk_ssum)
+{
+    if (T < 0 || N <= 0 || k <= 0) return ORC_ERR_INVALID_ARG;
+    if (k > N) return ORC_ERR_UNSUPPORTED;
+    for (int t = 0; t < T; ++t) topk_select(logits + (size_t)t * N, NULL, N, k, topk_idx + (size_t)t * k);
+    return orc_sigmoid_gates(logits, topk_idx, T, N, k, topk_gate, topk_ssum);
 }
 
 /*
