@@ -255,6 +255,31 @@ int lynx_moe_layer_fp4(const uint16_t *x_bf16, const float *Wr, const float *bia
                        float *y, void *workspace, void *stream, void *const *stage_events);
 
 /*
+ * Sigmoid-gated routers.  Sec. 3.2.1 closes with routers that do not use softmax: their bins are taken from
+ * differences of the scores before the sigmoid, that is of the logits, which is what lynx_affinity_bin computes
+ * already; bins, histogram, scores, nominations and the remapped selection are therefore identical.  What
+ * differs is the weight of a selected expert, for which the paper prints no formula.  The reading here is the usual
+ * one for such routers: score = 1 / (1 + exp(-logit)) in fp32, the k experts of largest logit (the sigmoid is
+ * increasing; equal logits to the lower index, decided on the fp32 logits), gate = score / sum of the k selected
+ * scores.  The three calls below are lynx_route, lynx_affinity_bin and lynx_moe_layer (bf16 expert weights) with
+ * these gates: same arguments, same layouts, same errors.  topk_ssum [T] fp32 out = the sum of the selected
+ * scores (where the softmax calls give the selected probability mass).  They compose with lynx_permute,
+ * lynx_moe_ffn and the quantised FFN calls, which take any gates.
+ */
+int lynx_route_sigmoid(const uint16_t *x_bf16, const float *Wr, const float *bias, int T, int H, int N, int k,
+                       float *logits, int32_t *topk_idx, float *topk_gate, float *topk_ssum, void *stream);
+int lynx_affinity_bin_sigmoid(const float *logits, const int32_t *topk_idx, int T, int N, int k, float alpha, int beta,
+                              int enable, int32_t *new_idx, float *new_gate, int32_t *cnt_before, int32_t *cnt_after,
+                              int32_t *bin_hist, int32_t *num_active, void *workspace, void *stream);
+int lynx_moe_layer_sigmoid(const uint16_t *x_bf16, const float *Wr, const float *bias, const uint16_t *Wgu_packed,
+                           const uint16_t *Wd_packed, const uint16_t *Sgu_packed, const uint16_t *Sd_packed, int n_shared,
+                           int F_shared, int T, int H, int F, int N, int k, float alpha, int beta, int enable,
+                           float *logits, int32_t *topk_idx, float *topk_gate, float *topk_ssum, int32_t *new_idx,
+                           float *new_gate, int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist,
+                           int32_t *num_active, int32_t *expert_offsets, int32_t *perm, int32_t *active_experts,
+                           int32_t *num_active_perm, float *y, void *workspace, void *stream, void *const *stage_events);
+
+/*
  * Measurement aid, not a step of the method: the residual update that chains MoE layers into a stack (the
  * benchmark times a stack of layers as a whole, each layer's input depending on the layer before):
  * x_next[i] = bf16(float(x[i]) + y[i]) for i < n, one fp32 addition rounded to nearest even.  x_bf16 [n] and

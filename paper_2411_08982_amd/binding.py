@@ -22,7 +22,8 @@ MAX_T, MAX_N, MAX_K, MAX_BETA = 1024, 256, 16, 6
 SYMBOLS = ["lynx_last_error", "lynx_workspace_bytes", "lynx_route", "lynx_affinity_bin", "lynx_affinity_bin_biased", "lynx_permute",
            "lynx_pack_weights", "lynx_moe_ffn", "lynx_moe_ffn_timed", "lynx_moe_layer", "lynx_moe_ffn_launches", "lynx_residual_add", "lynx_read_probe",
            "lynx_quantize_weights_fp8", "lynx_moe_ffn_fp8", "lynx_moe_layer_fp8",
-           "lynx_fp4_scale_words", "lynx_quantize_weights_fp4", "lynx_moe_ffn_fp4", "lynx_moe_layer_fp4"]
+           "lynx_fp4_scale_words", "lynx_quantize_weights_fp4", "lynx_moe_ffn_fp4", "lynx_moe_layer_fp4",
+           "lynx_route_sigmoid", "lynx_affinity_bin_sigmoid", "lynx_moe_layer_sigmoid"]
 
 
 class LynxError(RuntimeError):
@@ -65,6 +66,13 @@ def lib():
         L.lynx_moe_layer_fp4.argtypes = L.lynx_moe_layer_fp8.argtypes
         L.lynx_moe_ffn_launches.argtypes = [I, I]
         L.lynx_residual_add.argtypes = [P, P, c_size_t, P, P]
+        L.lynx_route_sigmoid.argtypes = L.lynx_route.argtypes
+        L.lynx_affinity_bin_sigmoid.argtypes = L.lynx_affinity_bin.argtypes
+        L.lynx_moe_layer_sigmoid.argtypes = L.lynx_moe_layer.argtypes
+        for name in SYMBOLS:
+            # without declared argument types ctypes passes Python ints as 32-bit C ints: a device pointer would be cut
+            if getattr(L, name).argtypes is None:
+                raise RuntimeError(f"binding: no argument types declared for {name}")
         for name in SYMBOLS[2:]:
             getattr(L, name).restype = c_int
         L.lynx_fp4_scale_words.restype = c_size_t
@@ -107,20 +115,25 @@ def new_workspace(T, H, F, N, k, n_shared=0, F_shared=0, device="cuda"):
     return torch.empty(max(workspace_bytes(T, H, F, N, k, n_shared, F_shared), 256), dtype=torch.uint8, device=device)
 
 
-def lynx_route(x, Wr, bias, k, out=None):
+def lynx_route(x, Wr, bias, k, out=None, _entry="lynx_route"):
     """x [T,H] bf16, Wr [N,H] f32, bias [N] f32 or None -> dict(logits, idx, gate, psum)."""
     T, H = x.shape
     N = Wr.shape[0]
     dev = x.device
     o = out or dict(logits=torch.empty((T, N), dtype=F32, device=dev), idx=torch.empty((T, k), dtype=I32, device=dev),
                     gate=torch.empty((T, k), dtype=F32, device=dev), psum=torch.empty((T,), dtype=F32, device=dev))
-    _check(lib().lynx_route(_ptr(x, BF16, "x"), _ptr(Wr, F32, "Wr"), _ptr(bias, F32, "bias"), T, H, N, k,
-                            _ptr(o["logits"], F32, "logits"), _ptr(o["idx"], I32, "idx"), _ptr(o["gate"], F32, "gate"),
-                            _ptr(o["psum"], F32, "psum"), _stream()))
+    _check(getattr(lib(), _entry)(_ptr(x, BF16, "x"), _ptr(Wr, F32, "Wr"), _ptr(bias, F32, "bias"), T, H, N, k,
+                                  _ptr(o["logits"], F32, "logits"), _ptr(o["idx"], I32, "idx"),
+                                  _ptr(o["gate"], F32, "gate"), _ptr(o["psum"], F32, "psum"), _stream()))
     return o
 
 
-def lynx_affinity_bin(logits, topk_idx, alpha, beta, enable=1, workspace=None, out=None):
+def lynx_route_sigmoid(x, Wr, bias, k, out=None):
+    """lynx_route for a sigmoid-gated router; the entry "psum" holds the sum of the selected scores."""
+    return lynx_route(x, Wr, bias, k, out, _entry="lynx_route_sigmoid")
+
+
+def lynx_affinity_bin(logits, topk_idx, alpha, beta, enable=1, workspace=None, out=None, _entry="lynx_affinity_bin"):
     """logits [T,N] f32, topk_idx [T,k] i32 -> dict(new_idx, new_gate, cnt_before, cnt_after, bin_hist, num_active)."""
     T, N = logits.shape
     k = topk_idx.shape[1]
@@ -132,12 +145,17 @@ def lynx_affinity_bin(logits, topk_idx, alpha, beta, enable=1, workspace=None, o
     if workspace is None:
         workspace = torch.empty(65536, dtype=torch.uint8, device=dev)
     ws = workspace.data_ptr()
-    _check(lib().lynx_affinity_bin(_ptr(logits, F32, "logits"), _ptr(topk_idx, I32, "topk_idx"), T, N, k, float(alpha),
-                                   int(beta), int(enable), _ptr(o["new_idx"], I32, "new_idx"),
-                                   _ptr(o["new_gate"], F32, "new_gate"), _ptr(o["cnt_before"], I32, "cnt_before"),
-                                   _ptr(o["cnt_after"], I32, "cnt_after"), _ptr(o["bin_hist"], I32, "bin_hist"),
-                                   _ptr(o["num_active"], I32, "num_active"), ws, _stream()))
+    _check(getattr(lib(), _entry)(_ptr(logits, F32, "logits"), _ptr(topk_idx, I32, "topk_idx"), T, N, k, float(alpha),
+                                  int(beta), int(enable), _ptr(o["new_idx"], I32, "new_idx"),
+                                  _ptr(o["new_gate"], F32, "new_gate"), _ptr(o["cnt_before"], I32, "cnt_before"),
+                                  _ptr(o["cnt_after"], I32, "cnt_after"), _ptr(o["bin_hist"], I32, "bin_hist"),
+                                  _ptr(o["num_active"], I32, "num_active"), ws, _stream()))
     return o
+
+
+def lynx_affinity_bin_sigmoid(logits, topk_idx, alpha, beta, enable=1, workspace=None, out=None):
+    """lynx_affinity_bin with the gates of a sigmoid-gated router."""
+    return lynx_affinity_bin(logits, topk_idx, alpha, beta, enable, workspace, out, _entry="lynx_affinity_bin_sigmoid")
 
 
 def lynx_affinity_bin_biased(logits, topk_idx, alpha, beta, gamma, enable=1, workspace=None, out=None):
@@ -227,14 +245,14 @@ class LayerBuffers:
 
 
 def lynx_moe_layer(x, Wr, bias, Wgu, Wdp, F, k, alpha, beta, enable=1, Sgu=None, Sdp=None, n_shared=0, F_shared=0,
-                   buffers: LayerBuffers | None = None, stage_events=None):
+                   buffers: LayerBuffers | None = None, stage_events=None, _entry="lynx_moe_layer"):
     """route -> affinity_bin -> permute -> FFN + combine on the current stream.  Returns the LayerBuffers."""
     T, H = x.shape
     N = Wr.shape[0]
     b = buffers or LayerBuffers(T, H, F, N, k, beta, n_shared, F_shared, x.device)
     if b.sizes != (T, H, F, N, k, n_shared, F_shared) or b.beta != beta:
         raise ValueError("buffers were allocated for other sizes")
-    _check(lib().lynx_moe_layer(
+    _check(getattr(lib(), _entry)(
         _ptr(x, BF16, "x"), _ptr(Wr, F32, "Wr"), _ptr(bias, F32, "bias"), _ptr(Wgu, BF16, "Wgu"), _ptr(Wdp, BF16, "Wdp"),
         _ptr(Sgu, BF16, "Sgu"), _ptr(Sdp, BF16, "Sdp"), n_shared, F_shared, T, H, F, N, k, float(alpha), int(beta),
         int(enable), b.logits.data_ptr(), b.topk_idx.data_ptr(), b.topk_gate.data_ptr(), b.topk_psum.data_ptr(),
@@ -243,6 +261,13 @@ def lynx_moe_layer(x, Wr, bias, Wgu, Wdp, F, k, alpha, beta, enable=1, Sgu=None,
         b.num_active_perm.data_ptr(), b.y.data_ptr(), b.workspace.data_ptr(), _stream(),
         None if stage_events is None else (c_void_p * 4)(*[e.cuda_event for e in stage_events])))
     return b
+
+
+def lynx_moe_layer_sigmoid(x, Wr, bias, Wgu, Wdp, F, k, alpha, beta, enable=1, Sgu=None, Sdp=None, n_shared=0, F_shared=0,
+                           buffers: LayerBuffers | None = None, stage_events=None):
+    """lynx_moe_layer for a sigmoid-gated router (topk_psum holds the sum of the selected scores)."""
+    return lynx_moe_layer(x, Wr, bias, Wgu, Wdp, F, k, alpha, beta, enable, Sgu, Sdp, n_shared, F_shared, buffers,
+                          stage_events, _entry="lynx_moe_layer_sigmoid")
 
 
 def lynx_read_probe(buf, sink, non_temporal=True):

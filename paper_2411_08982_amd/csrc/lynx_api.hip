@@ -30,7 +30,7 @@ extern "C" const char *lynx_last_error(void) { return lynx::g_last_error; }
 
 namespace lynx {
 int routing_fused(const uint16_t *x, const float *Wr, const float *bias, int T, int H, int N, int k, float alpha,
-                  int beta, int enable, float *logits, int32_t *topk_idx, float *topk_gate, float *topk_psum,
+                  int beta, int enable, int gate_fn, float *logits, int32_t *topk_idx, float *topk_gate, float *topk_psum,
                   int32_t *new_idx, float *new_gate, int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist,
                   int32_t *num_active, int32_t *expert_offsets, int32_t *perm, int32_t *active_experts,
                   int32_t *num_active_perm, void *workspace, hipStream_t st);
@@ -51,16 +51,19 @@ static int moe_layer_impl(const uint16_t *x_bf16, const float *Wr, const float *
                           int32_t *topk_idx, float *topk_gate, float *topk_psum, int32_t *new_idx, float *new_gate,
                           int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist, int32_t *num_active,
                           int32_t *expert_offsets, int32_t *perm, int32_t *active_experts, int32_t *num_active_perm,
-                          float *y, void *workspace, void *stream, void *const *stage_events, const FfnScales *q8)
+                          float *y, void *workspace, void *stream, void *const *stage_events, const FfnScales *q8,
+                          int gate_fn = 0)   // 1: sigmoid-gated router
 {
     int rc;
     bool fused = false;
     if (T <= 0 || !workspace) {
         // no tokens (or a missing workspace, which the separate calls report): take the separate calls
-        rc = lynx_route(x_bf16, Wr, bias, T, H, N, k, logits, topk_idx, topk_gate, topk_psum, stream);
+        rc = (gate_fn ? lynx_route_sigmoid : lynx_route)(x_bf16, Wr, bias, T, H, N, k, logits, topk_idx, topk_gate, topk_psum,
+                                                         stream);
         if (rc != LYNX_OK) return rc;
-        rc = lynx_affinity_bin(logits, topk_idx, T, N, k, alpha, beta, enable, new_idx, new_gate, cnt_before, cnt_after,
-                               bin_hist, num_active, workspace, stream);
+        rc = (gate_fn ? lynx_affinity_bin_sigmoid : lynx_affinity_bin)(logits, topk_idx, T, N, k, alpha, beta, enable, new_idx,
+                                                                       new_gate, cnt_before, cnt_after, bin_hist, num_active,
+                                                                       workspace, stream);
         if (rc != LYNX_OK) return rc;
         rc = lynx_permute(new_idx, T, N, k, expert_offsets, perm, active_experts, num_active_perm, stream);
         if (rc != LYNX_OK) return rc;
@@ -87,7 +90,7 @@ static int moe_layer_impl(const uint16_t *x_bf16, const float *Wr, const float *
             return fail(LYNX_ERR_UNSUPPORTED, "lynx_moe_layer: H, F and F_shared must be multiples of %d", mult);
         if (q8 && (!q8->gu || !q8->d || (n_shared > 0 && (!q8->shared_gu || !q8->shared_d))))
             return fail(LYNX_ERR_INVALID_ARG, "lynx_moe_layer_fp8: null scale pointer");
-        rc = routing_fused(x_bf16, Wr, bias, T, H, N, k, alpha, beta, enable, logits, topk_idx, topk_gate, topk_psum,
+        rc = routing_fused(x_bf16, Wr, bias, T, H, N, k, alpha, beta, enable, gate_fn, logits, topk_idx, topk_gate, topk_psum,
                            new_idx, new_gate, cnt_before, cnt_after, bin_hist, num_active, expert_offsets, perm,
                            active_experts, num_active_perm, workspace, (hipStream_t)stream);
         if (rc != LYNX_OK) return rc;
@@ -112,6 +115,21 @@ extern "C" int lynx_moe_layer(const uint16_t *x_bf16, const float *Wr, const flo
                                 N, k, alpha, beta, enable, logits, topk_idx, topk_gate, topk_psum, new_idx, new_gate,
                                 cnt_before, cnt_after, bin_hist, num_active, expert_offsets, perm, active_experts,
                                 num_active_perm, y, workspace, stream, stage_events, nullptr);
+}
+
+extern "C" int lynx_moe_layer_sigmoid(const uint16_t *x_bf16, const float *Wr, const float *bias, const uint16_t *Wgu_packed,
+                                      const uint16_t *Wd_packed, const uint16_t *Sgu_packed, const uint16_t *Sd_packed,
+                                      int n_shared, int F_shared, int T, int H, int F, int N, int k, float alpha, int beta,
+                                      int enable, float *logits, int32_t *topk_idx, float *topk_gate, float *topk_ssum,
+                                      int32_t *new_idx, float *new_gate, int32_t *cnt_before, int32_t *cnt_after,
+                                      int32_t *bin_hist, int32_t *num_active, int32_t *expert_offsets, int32_t *perm,
+                                      int32_t *active_experts, int32_t *num_active_perm, float *y, void *workspace,
+                                      void *stream, void *const *stage_events)
+{
+    return lynx::moe_layer_impl(x_bf16, Wr, bias, Wgu_packed, Wd_packed, Sgu_packed, Sd_packed, n_shared, F_shared, T, H, F,
+                                N, k, alpha, beta, enable, logits, topk_idx, topk_gate, topk_ssum, new_idx, new_gate,
+                                cnt_before, cnt_after, bin_hist, num_active, expert_offsets, perm, active_experts,
+                                num_active_perm, y, workspace, stream, stage_events, nullptr, 1);
 }
 
 extern "C" int lynx_moe_layer_fp8(const uint16_t *x_bf16, const float *Wr, const float *bias, const uint8_t *Wgu_q,

@@ -251,21 +251,27 @@ __device__ __forceinline__ float token_max(const TokenLogits<NS> &t)
 }
 
 // Gates of a selection held one per lane (lane j < k: expert mye, logit myz): softmax over the selected
-// logits (paper Sec. 4: the weights are renormalised over the new selection).  Returns this lane's gate; num = sum of the numerators.
-__device__ __forceinline__ float selection_gate(int k, int mye, float myz, float &num, float &zref)
+// logits (paper Sec. 4: the weights are renormalised over the new selection), or, for a sigmoid-gated router
+// (gate_fn = 1; Sec. 3.2.1 names such routers), the selected sigmoid scores over their sum.  Returns this lane's
+// gate; num = sum of the numerators.
+constexpr int kGateSoftmax = 0, kGateSigmoid = 1;
+__device__ __forceinline__ float selection_gate(int k, int mye, float myz, int gate_fn, float &num, float &zref)
 {
     zref = wave_max(myz);
-    const float mynum = (lane_id() < k && mye >= 0) ? expf(myz - zref) : 0.f;
+    float mynum = 0.f;
+    if (lane_id() < k && mye >= 0) mynum = gate_fn == kGateSigmoid ? 1.0f / (1.0f + expf(-myz)) : expf(myz - zref);
     num = wave_sum(mynum);
     return mynum / num;
 }
 
 // ---- per-token steps (one wave per token), shared by the single-workgroup and the multi-workgroup paths ----
 
-// Softmax + top-k (Sec. 2.1): lane j < k returns the j-th pick in mye; writes idx / gate / psum.
+// Softmax + top-k (Sec. 2.1): lane j < k returns the j-th pick in mye; writes idx / gate / psum (softmax: the
+// selected probability mass; sigmoid-gated: the sum of the selected scores).
 template <int NS>
-__device__ __forceinline__ int token_topk(const TokenLogits<NS> &tl, int t, int k, int32_t *__restrict__ topk_idx,
-                                          float *__restrict__ topk_gate, float *__restrict__ topk_psum)
+__device__ __forceinline__ int token_topk(const TokenLogits<NS> &tl, int t, int k, int gate_fn,
+                                          int32_t *__restrict__ topk_idx, float *__restrict__ topk_gate,
+                                          float *__restrict__ topk_psum)
 {
     const int lane = lane_id();
     int mye = -1;
@@ -277,7 +283,7 @@ __device__ __forceinline__ int token_topk(const TokenLogits<NS> &tl, int t, int 
         }
     });
     float num, zref;
-    const float g = selection_gate(k, mye, myz, num, zref);
+    const float g = selection_gate(k, mye, myz, gate_fn, num, zref);
     float part = 0.f;
 #pragma unroll
     for (int i = 0; i < NS; ++i)
@@ -287,7 +293,7 @@ __device__ __forceinline__ int token_topk(const TokenLogits<NS> &tl, int t, int 
         topk_idx[(size_t)t * k + lane] = mye;
         topk_gate[(size_t)t * k + lane] = g;
     }
-    if (lane == 0) topk_psum[t] = num / den;
+    if (lane == 0) topk_psum[t] = gate_fn == kGateSigmoid ? num : num / den;
     return mye;
 }
 
@@ -395,7 +401,7 @@ __device__ __forceinline__ int wave_fill_active(int N, int k, const int *order, 
 // Selection of one token inside the active set (or its unchanged selection when bypassed) and its gates
 // (Secs. 3.4, 4).  Lane j < k returns the j-th expert; writes new_idx / new_gate.
 template <int NS>
-__device__ __forceinline__ int token_remap(const TokenLogits<NS> &tl, int t, int N, int k, bool bypass, const int *inA,
+__device__ __forceinline__ int token_remap(const TokenLogits<NS> &tl, int t, int N, int k, bool bypass, int gate_fn, const int *inA,
                                            const int32_t *sel, int32_t *__restrict__ new_idx,
                                            float *__restrict__ new_gate)
 {
@@ -423,7 +429,7 @@ __device__ __forceinline__ int token_remap(const TokenLogits<NS> &tl, int t, int
         });
     }
     float num, zref;
-    const float g = selection_gate(k, mye, myz, num, zref);
+    const float g = selection_gate(k, mye, myz, gate_fn, num, zref);
     if (lane < k) {
         store_coherent(&new_idx[(size_t)t * k + lane], mye);   // read by the workgroup that assigns the tokens
         new_gate[(size_t)t * k + lane] = g;
@@ -485,7 +491,7 @@ static_assert(kSmallT <= kSmallWaves && kSmallT <= 32, "one wave per token, one 
 // One workgroup, wave t owns token t and keeps its logits in registers from the first step to the last.
 template <int NS, bool DO_TOPK, bool DO_PERMUTE>
 __global__ __launch_bounds__(kSmallThreads) void routing_small_kernel(
-    const float *__restrict__ logits, int T, int N, int k, float alpha, int beta, int bypass,
+    const float *__restrict__ logits, int T, int N, int k, float alpha, int beta, int bypass, int gate_fn,
     int32_t *__restrict__ topk_idx, float *__restrict__ topk_gate, float *__restrict__ topk_psum,
     int32_t *__restrict__ new_idx, float *__restrict__ new_gate, int32_t *__restrict__ cnt_before,
     int32_t *__restrict__ cnt_after, int32_t *__restrict__ bin_hist, int32_t *__restrict__ num_active,
@@ -514,7 +520,7 @@ __global__ __launch_bounds__(kSmallThreads) void routing_small_kernel(
     if (has_token) {
         int mye = -1;
         if (DO_TOPK) {
-            mye = token_topk(tl, t, k, topk_idx, topk_gate, topk_psum);
+            mye = token_topk(tl, t, k, gate_fn, topk_idx, topk_gate, topk_psum);
         } else if (lane < k) {
             mye = (given < 0 || given >= N) ? -1 : given;
         }
@@ -537,7 +543,7 @@ __global__ __launch_bounds__(kSmallThreads) void routing_small_kernel(
     }
     __syncthreads();
     if (has_token) {
-        const int mye = token_remap(tl, t, N, k, bypass != 0, sh.inA, sh.sel + t * k, new_idx, new_gate);
+        const int mye = token_remap(tl, t, N, k, bypass != 0, gate_fn, sh.inA, sh.sel + t * k, new_idx, new_gate);
         if (lane < k) {
             sh.newsel[t * k + lane] = mye;
             if (mye >= 0) {
@@ -569,7 +575,8 @@ __global__ __launch_bounds__(kSmallThreads) void routing_small_kernel(
 // into the zeroed outputs).
 template <int NS, bool DO_TOPK, bool DO_BINS>
 __global__ __launch_bounds__(kTokThreads) void token_kernel(const float *__restrict__ logits, int T, int N, int k,
-                                                            float alpha, int beta, int32_t *__restrict__ topk_idx,
+                                                            float alpha, int beta, int gate_fn,
+                                                            int32_t *__restrict__ topk_idx,
                                                             float *__restrict__ topk_gate,
                                                             float *__restrict__ topk_psum,
                                                             int32_t *__restrict__ bin_hist,
@@ -588,7 +595,7 @@ __global__ __launch_bounds__(kTokThreads) void token_kernel(const float *__restr
         const TokenLogits<NS> tl = load_token<NS>(logits + (size_t)t * N, N);
         int mye = -1;
         if (DO_TOPK) {
-            mye = token_topk(tl, t, k, topk_idx, topk_gate, topk_psum);
+            mye = token_topk(tl, t, k, gate_fn, topk_idx, topk_gate, topk_psum);
         } else if (lane < k) {
             mye = topk_idx[(size_t)t * k + lane];
             if (mye < 0 || mye >= N) mye = -1;
@@ -653,7 +660,7 @@ template <int NS, bool DO_PERMUTE>
 __global__ __launch_bounds__(kTokThreads) void remap_kernel(const float *__restrict__ logits,
                                                             const int32_t *__restrict__ topk_idx,
                                                             const int32_t *__restrict__ cnt_before, int T, int N, int k,
-                                                            int bypass, int32_t *__restrict__ ws,
+                                                            int bypass, int gate_fn, int32_t *__restrict__ ws,
                                                             int32_t *__restrict__ new_idx, float *__restrict__ new_gate,
                                                             int32_t *__restrict__ cnt_after,
                                                             int32_t *__restrict__ num_active,
@@ -688,7 +695,7 @@ __global__ __launch_bounds__(kTokThreads) void remap_kernel(const float *__restr
     }
     __syncthreads();
     if (t < T) {
-        const int mye = token_remap(tl, t, N, k, bypass != 0, sh.inA, sel + wave * k, new_idx, new_gate);
+        const int mye = token_remap(tl, t, N, k, bypass != 0, gate_fn, sh.inA, sel + wave * k, new_idx, new_gate);
         if (lane < k && mye >= 0) {
             atomicAdd(&sh.cnta[mye], 1);
             if (DO_PERMUTE) atomicOr(reinterpret_cast<unsigned *>(ws + kWsMember) + mye * W + (t >> 5), 1u << (t & 31));
@@ -790,7 +797,7 @@ __global__ __launch_bounds__(kTokThreads) void biased_remap_kernel(const float *
             if (lane > 0 && mye >= 0) myz = zo;
         }
         float num, zref;
-        const float g = selection_gate(k, mye, myz, num, zref);
+        const float g = selection_gate(k, mye, myz, kGateSoftmax, num, zref);
         if (lane < k) {
             new_idx[(size_t)t * k + lane] = mye;
             new_gate[(size_t)t * k + lane] = g;
@@ -853,7 +860,7 @@ static void launch_logits(const uint16_t *x, const float *Wr, const float *bias,
 // with a launch of their own, false = the caller already had them cleared (by the logits kernel).
 template <int NS, bool DO_TOPK, bool DO_PERMUTE>
 static int launch_after_logits_ns(const char *who, const float *logits, int T, int N, int k, float alpha, int beta,
-                               int enable, int32_t *topk_idx, float *topk_gate, float *topk_psum, int32_t *new_idx,
+                               int enable, int gate_fn, int32_t *topk_idx, float *topk_gate, float *topk_psum, int32_t *new_idx,
                                float *new_gate, int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist,
                                int32_t *num_active, int32_t *expert_offsets, int32_t *perm, int32_t *active_experts,
                                int32_t *num_active_perm, int32_t *ws, bool clear_first, hipStream_t st)
@@ -861,7 +868,7 @@ static int launch_after_logits_ns(const char *who, const float *logits, int T, i
     const int bypass = (!enable || T <= 1) ? 1 : 0;
     if (T <= kSmallT) {
         hipLaunchKernelGGL((routing_small_kernel<NS, DO_TOPK, DO_PERMUTE>), dim3(1), dim3(kSmallThreads), 0, st, logits, T, N, k,
-                           alpha, beta, bypass, topk_idx, topk_gate, topk_psum, new_idx, new_gate, cnt_before, cnt_after,
+                           alpha, beta, bypass, gate_fn, topk_idx, topk_gate, topk_psum, new_idx, new_gate, cnt_before, cnt_after,
                            bin_hist, num_active, expert_offsets, perm, active_experts, num_active_perm);
         return check_launch(who);
     }
@@ -880,7 +887,7 @@ static int launch_after_logits_ns(const char *who, const float *logits, int T, i
         if (rc != LYNX_OK) return rc;
     }
     const dim3 tgrid((T + kTokWaves - 1) / kTokWaves), tblock(kTokThreads);
-    hipLaunchKernelGGL((token_kernel<NS, DO_TOPK, true>), tgrid, tblock, 0, st, logits, T, N, k, alpha, beta, topk_idx,
+    hipLaunchKernelGGL((token_kernel<NS, DO_TOPK, true>), tgrid, tblock, 0, st, logits, T, N, k, alpha, beta, gate_fn, topk_idx,
                        topk_gate, topk_psum, bin_hist, cnt_before);
     rc = check_launch(who);
     if (rc != LYNX_OK) return rc;
@@ -890,20 +897,20 @@ static int launch_after_logits_ns(const char *who, const float *logits, int T, i
         rc = check_launch(who);
         if (rc != LYNX_OK) return rc;
     }
-    hipLaunchKernelGGL((remap_kernel<NS, DO_PERMUTE>), tgrid, tblock, 0, st, logits, topk_idx, cnt_before, T, N, k, bypass, ws,
+    hipLaunchKernelGGL((remap_kernel<NS, DO_PERMUTE>), tgrid, tblock, 0, st, logits, topk_idx, cnt_before, T, N, k, bypass, gate_fn, ws,
                        new_idx, new_gate, cnt_after, num_active, expert_offsets, perm, active_experts, num_active_perm);
     return check_launch(who);
 }
 
 template <bool DO_TOPK, bool DO_PERMUTE>
 static int launch_after_logits(const char *who, const float *logits, int T, int N, int k, float alpha, int beta,
-                               int enable, int32_t *topk_idx, float *topk_gate, float *topk_psum, int32_t *new_idx,
+                               int enable, int gate_fn, int32_t *topk_idx, float *topk_gate, float *topk_psum, int32_t *new_idx,
                                float *new_gate, int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist,
                                int32_t *num_active, int32_t *expert_offsets, int32_t *perm, int32_t *active_experts,
                                int32_t *num_active_perm, int32_t *ws, bool clear_first, hipStream_t st)
 {
 #define LYNX_ROUTING_ARGS                                                                                             \
-    who, logits, T, N, k, alpha, beta, enable, topk_idx, topk_gate, topk_psum, new_idx, new_gate, cnt_before, cnt_after, \
+    who, logits, T, N, k, alpha, beta, enable, gate_fn, topk_idx, topk_gate, topk_psum, new_idx, new_gate, cnt_before, cnt_after, \
         bin_hist, num_active, expert_offsets, perm, active_experts, num_active_perm, ws, clear_first, st
     if (N <= kWave) return launch_after_logits_ns<1, DO_TOPK, DO_PERMUTE>(LYNX_ROUTING_ARGS);
     if (N <= 2 * kWave) return launch_after_logits_ns<2, DO_TOPK, DO_PERMUTE>(LYNX_ROUTING_ARGS);
@@ -913,7 +920,7 @@ static int launch_after_logits(const char *who, const float *logits, int T, int 
 
 // The whole routing side of lynx_moe_layer: two launches for T <= kSmallT, four otherwise.  T >= 1, arguments checked.
 int routing_fused(const uint16_t *x, const float *Wr, const float *bias, int T, int H, int N, int k, float alpha,
-                  int beta, int enable, float *logits, int32_t *topk_idx, float *topk_gate, float *topk_psum,
+                  int beta, int enable, int gate_fn, float *logits, int32_t *topk_idx, float *topk_gate, float *topk_psum,
                   int32_t *new_idx, float *new_gate, int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist,
                   int32_t *num_active, int32_t *expert_offsets, int32_t *perm, int32_t *active_experts,
                   int32_t *num_active_perm, void *workspace, hipStream_t st)
@@ -933,7 +940,7 @@ int routing_fused(const uint16_t *x, const float *Wr, const float *bias, int T, 
     launch_logits(x, Wr, bias, T, H, N, logits, z, st);
     int rc = check_launch("lynx_moe_layer(logits)");
     if (rc != LYNX_OK) return rc;
-    return launch_after_logits<true, true>("lynx_moe_layer(routing)", logits, T, N, k, alpha, beta, enable, topk_idx,
+    return launch_after_logits<true, true>("lynx_moe_layer(routing)", logits, T, N, k, alpha, beta, enable, gate_fn, topk_idx,
                                            topk_gate, topk_psum, new_idx, new_gate, cnt_before, cnt_after, bin_hist,
                                            num_active, expert_offsets, perm, active_experts, num_active_perm, ws, false, st);
 }
@@ -975,7 +982,7 @@ extern "C" int lynx_affinity_bin_biased(const float *logits, const int32_t *topk
 #define LYNX_BIASED(NS)                                                                                                 \
     do {                                                                                                                \
         hipLaunchKernelGGL((token_kernel<NS, false, true>), tgrid, tblock, 0, st, logits, T, N, k, alpha, beta,         \
-                           const_cast<int32_t *>(topk_idx), nullptr, nullptr, bin_hist, cnt_before);                    \
+                           kGateSoftmax, const_cast<int32_t *>(topk_idx), nullptr, nullptr, bin_hist, cnt_before);      \
         rc = check_launch("lynx_affinity_bin_biased(bins)");                                                            \
         if (rc != LYNX_OK) return rc;                                                                                   \
         hipLaunchKernelGGL((biased_remap_kernel<NS>), tgrid, tblock, 0, st, logits, topk_idx, cnt_before, bin_hist, T,  \
@@ -991,8 +998,8 @@ extern "C" int lynx_affinity_bin_biased(const float *logits, const int32_t *topk
     return check_launch("lynx_affinity_bin_biased(select)");
 }
 
-extern "C" int lynx_route(const uint16_t *x_bf16, const float *Wr, const float *bias, int T, int H, int N, int k,
-                          float *logits, int32_t *topk_idx, float *topk_gate, float *topk_psum, void *stream)
+static int route_impl(const uint16_t *x_bf16, const float *Wr, const float *bias, int T, int H, int N, int k, int gate_fn,
+                      float *logits, int32_t *topk_idx, float *topk_gate, float *topk_psum, void *stream)
 {
     using namespace lynx;
     int rc = check_routing_sizes("lynx_route", T, N, k);
@@ -1010,21 +1017,32 @@ extern "C" int lynx_route(const uint16_t *x_bf16, const float *Wr, const float *
     if (rc != LYNX_OK) return rc;
     const dim3 tgrid((T + kTokWaves - 1) / kTokWaves), tblock(kTokThreads);
     if (N <= kWave)
-        hipLaunchKernelGGL((token_kernel<1, true, false>), tgrid, tblock, 0, st, logits, T, N, k, 0.f, 1, topk_idx,
+        hipLaunchKernelGGL((token_kernel<1, true, false>), tgrid, tblock, 0, st, logits, T, N, k, 0.f, 1, gate_fn, topk_idx,
                            topk_gate, topk_psum, nullptr, nullptr);
     else if (N <= 2 * kWave)
-        hipLaunchKernelGGL((token_kernel<2, true, false>), tgrid, tblock, 0, st, logits, T, N, k, 0.f, 1, topk_idx,
+        hipLaunchKernelGGL((token_kernel<2, true, false>), tgrid, tblock, 0, st, logits, T, N, k, 0.f, 1, gate_fn, topk_idx,
                            topk_gate, topk_psum, nullptr, nullptr);
     else
-        hipLaunchKernelGGL((token_kernel<4, true, false>), tgrid, tblock, 0, st, logits, T, N, k, 0.f, 1, topk_idx,
+        hipLaunchKernelGGL((token_kernel<4, true, false>), tgrid, tblock, 0, st, logits, T, N, k, 0.f, 1, gate_fn, topk_idx,
                            topk_gate, topk_psum, nullptr, nullptr);
     return check_launch("lynx_route(top-k)");
 }
 
-extern "C" int lynx_affinity_bin(const float *logits, const int32_t *topk_idx, int T, int N, int k, float alpha,
-                                 int beta, int enable, int32_t *new_idx, float *new_gate, int32_t *cnt_before,
-                                 int32_t *cnt_after, int32_t *bin_hist, int32_t *num_active, void *workspace,
-                                 void *stream)
+extern "C" int lynx_route(const uint16_t *x_bf16, const float *Wr, const float *bias, int T, int H, int N, int k,
+                          float *logits, int32_t *topk_idx, float *topk_gate, float *topk_psum, void *stream)
+{
+    return route_impl(x_bf16, Wr, bias, T, H, N, k, lynx::kGateSoftmax, logits, topk_idx, topk_gate, topk_psum, stream);
+}
+
+extern "C" int lynx_route_sigmoid(const uint16_t *x_bf16, const float *Wr, const float *bias, int T, int H, int N, int k,
+                                  float *logits, int32_t *topk_idx, float *topk_gate, float *topk_ssum, void *stream)
+{
+    return route_impl(x_bf16, Wr, bias, T, H, N, k, lynx::kGateSigmoid, logits, topk_idx, topk_gate, topk_ssum, stream);
+}
+
+static int affinity_bin_impl(const float *logits, const int32_t *topk_idx, int T, int N, int k, float alpha, int beta,
+                             int enable, int gate_fn, int32_t *new_idx, float *new_gate, int32_t *cnt_before,
+                             int32_t *cnt_after, int32_t *bin_hist, int32_t *num_active, void *workspace, void *stream)
 {
     using namespace lynx;
     int rc = check_routing_sizes("lynx_affinity_bin", T, N, k);
@@ -1047,8 +1065,26 @@ extern "C" int lynx_affinity_bin(const float *logits, const int32_t *topk_idx, i
         hipLaunchKernelGGL(zero_kernel, dim3(1), dim3(256), 0, st, z);
         return check_launch("lynx_affinity_bin(clear)");
     }
-    return launch_after_logits<false, false>("lynx_affinity_bin", logits, T, N, k, alpha, beta, enable,
+    return launch_after_logits<false, false>("lynx_affinity_bin", logits, T, N, k, alpha, beta, enable, gate_fn,
                                              const_cast<int32_t *>(topk_idx), nullptr, nullptr, new_idx, new_gate,
                                              cnt_before, cnt_after, bin_hist, num_active, nullptr, nullptr, nullptr,
                                              nullptr, ws, true, st);
+}
+
+extern "C" int lynx_affinity_bin(const float *logits, const int32_t *topk_idx, int T, int N, int k, float alpha,
+                                 int beta, int enable, int32_t *new_idx, float *new_gate, int32_t *cnt_before,
+                                 int32_t *cnt_after, int32_t *bin_hist, int32_t *num_active, void *workspace,
+                                 void *stream)
+{
+    return affinity_bin_impl(logits, topk_idx, T, N, k, alpha, beta, enable, lynx::kGateSoftmax, new_idx, new_gate,
+                             cnt_before, cnt_after, bin_hist, num_active, workspace, stream);
+}
+
+extern "C" int lynx_affinity_bin_sigmoid(const float *logits, const int32_t *topk_idx, int T, int N, int k, float alpha,
+                                         int beta, int enable, int32_t *new_idx, float *new_gate, int32_t *cnt_before,
+                                         int32_t *cnt_after, int32_t *bin_hist, int32_t *num_active, void *workspace,
+                                         void *stream)
+{
+    return affinity_bin_impl(logits, topk_idx, T, N, k, alpha, beta, enable, lynx::kGateSigmoid, new_idx, new_gate,
+                             cnt_before, cnt_after, bin_hist, num_active, workspace, stream);
 }
