@@ -104,7 +104,7 @@ class Layer:
             self.buf[key] = self.L.LayerBuffers(T, c.H, c.F, c.N, c.k, beta, c.n_shared, c.F_shared)
         return self.buf[key]
 
-    def step(self, T, alpha, beta, enable, events=None, layer=None):
+    def step(self, T, alpha, beta, enable, events=None, layer=None, sigmoid=False):
         """One decode step (the whole hot path) through the fused C-ABI entry point, on the current stream.
         Successive calls take the resident layers' expert weights in turn."""
         c = self.cfg
@@ -112,9 +112,9 @@ class Layer:
             layer = self.calls % len(self.weights)
             self.calls += 1
         Wgu, Wdp, Sgu, Sdp = self.weights[layer]
-        return self.L.lynx_moe_layer(self.tokens(T), self.Wr, self.bias, Wgu, Wdp, c.F, c.k, alpha, beta, enable,
-                                     Sgu, Sdp, c.n_shared, c.F_shared, buffers=self.buffers(T, beta),
-                                     stage_events=events)
+        entry = self.L.lynx_moe_layer_sigmoid if sigmoid else self.L.lynx_moe_layer
+        return entry(self.tokens(T), self.Wr, self.bias, Wgu, Wdp, c.F, c.k, alpha, beta, enable, Sgu, Sdp, c.n_shared,
+                     c.F_shared, buffers=self.buffers(T, beta), stage_events=events)
 
 
 def preset_args(wl, preset):
@@ -407,6 +407,22 @@ def main():
                 var.append({"tokens": Ts, "gamma": args.biased_gamma, "alpha": a_, "beta": b_, "us": round(us, 1),
                             "invoked_before": nb, "invoked_after": na})
             out["sweep_score_biased_variant"] = var
+
+    if not args.no_sweep:
+        # The same workload behind a sigmoid-gated router (gates = selected sigmoid scores over their sum; bins,
+        # scores and the remap are the softmax path's): a widening, reported beside the metric above.
+        for _ in range(3):
+            layer.step(T, alpha, beta, enable, sigmoid=True)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(args.sweep_iters):
+            bb = layer.step(T, alpha, beta, enable, sigmoid=True)
+        e1.record()
+        torch.cuda.synchronize()
+        nb, na = (int(v) for v in bb.num_active.cpu().tolist())
+        out["sigmoid_router"] = {"us_per_batch": round(e0.elapsed_time(e1) * 1e3 / args.sweep_iters, 2),
+                                 "invoked_before": nb, "invoked_after": na}
 
     if not args.no_fp8:
         # The same workload with the expert weights in FP8 E4M3 (row scales) and in MXFP4 (block scales), both
