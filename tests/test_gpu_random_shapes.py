@@ -80,7 +80,7 @@ def poisoned_buffers(L, cfg, T, beta):
     return b
 
 
-def run_layer(L, fmt, cfg, d, alpha, beta, enable):
+def run_layer(L, fmt, cfg, d, alpha, beta, enable, sigmoid=False):
     """The fused layer call for the given weight format, and the oracle's FFN over the same (quantised) weights."""
     x, Wr, bias = to_bf16_dev(d["x"]), dev(d["Wr"]), dev(d["bias"])
     buf = poisoned_buffers(L, cfg, x.shape[0], beta)
@@ -90,7 +90,8 @@ def run_layer(L, fmt, cfg, d, alpha, beta, enable):
     if fmt == "bf16":
         Wgu, Wdp = L.lynx_pack_weights(*routed)
         Sgu, Sdp = L.lynx_pack_weights(*shared) if shared else (None, None)
-        b = L.lynx_moe_layer(x, Wr, bias, Wgu, Wdp, cfg.F, cfg.k, alpha, beta, enable, Sgu, Sdp, *tail, buffers=buf)
+        entry = L.lynx_moe_layer_sigmoid if sigmoid else L.lynx_moe_layer
+        b = entry(x, Wr, bias, Wgu, Wdp, cfg.F, cfg.k, alpha, beta, enable, Sgu, Sdp, *tail, buffers=buf)
 
         def ffn(idx, gate):
             return oracle.moe_ffn(d["x"], d["Wg"], d["Wu"], d["Wd"], idx, gate, d["Sg"], d["Su"], d["Sd"])
@@ -116,20 +117,21 @@ def run_layer(L, fmt, cfg, d, alpha, beta, enable):
 @pytest.mark.parametrize("i", range(N_CASES))
 def test_layer_random_shape(L, i):
     fmt, cfg, T, alpha, beta, enable = draw_case(i)
+    sigmoid = fmt == "bf16" and i % 2 == 0           # every other bf16 case sits behind a sigmoid-gated router
     print(f"random layer {i}: {fmt} T={T} H={cfg.H} F={cfg.F} N={cfg.N} k={cfg.k} shared={cfg.n_shared}x{cfg.F_shared} "
-          f"alpha={alpha} beta={beta} enable={enable}", flush=True)
+          f"alpha={alpha} beta={beta} enable={enable} router={'sigmoid' if sigmoid else 'softmax'}", flush=True)
     d = wl.make_layer(cfg, T)
-    b, ffn = run_layer(L, fmt, cfg, d, alpha, beta, enable)
+    b, ffn = run_layer(L, fmt, cfg, d, alpha, beta, enable, sigmoid)
     torch.cuda.synchronize()
     from paper_2411_08982_amd.binding import WAIT_FLAG_WORD
     assert int(b.workspace.view(torch.int32)[WAIT_FLAG_WORD]) == 0, "a bounded wait inside the launch ran out"
     r = oracle.route(d["x"], d["Wr"], d["bias"], cfg.k)
     z = host(b.logits)
     assert np.all(np.abs(z - r["logits"]) <= LOGIT_TOL * np.maximum(1.0, np.abs(r["logits"])))
-    tk = oracle.topk(z, cfg.k)
+    tk = (oracle.topk_sigmoid if sigmoid else oracle.topk)(z, cfg.k)
     assert np.array_equal(host(b.topk_idx), tk["idx"])
     np.testing.assert_allclose(host(b.topk_gate), tk["gate"], rtol=GATE_TOL, atol=1e-7)
-    a = oracle.affinity_bin(z, tk["idx"], alpha, beta, enable)
+    a = (oracle.affinity_bin_sigmoid if sigmoid else oracle.affinity_bin)(z, tk["idx"], alpha, beta, enable)
     for key, got in (("new_idx", b.new_idx), ("cnt_before", b.cnt_before), ("cnt_after", b.cnt_after),
                      ("bin_hist", b.bin_hist), ("num_active", b.num_active)):
         assert np.array_equal(host(got), a[key]), key
