@@ -34,7 +34,11 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", default="mixtral", choices=["tiny", "mixtral", "qwen15moe", "dsv2lite", "qwen3"])
+    ap.add_argument("--config", default="mixtral", choices=["tiny", "mixtral", "qwen15moe", "dsv2lite", "qwen3", "dsv3"])
+    ap.add_argument("--router", default="softmax", choices=["softmax", "sigmoid"],
+                    help="gate function of the router; sigmoid: the layer runs through lynx_moe_layer_sigmoid (the "
+                         "quantised-weight variants, the score-biased variant and the CPU baseline, which are "
+                         "softmax-gated, are then left out)")
     ap.add_argument("--tokens", type=int, default=8)
     ap.add_argument("--preset", default="aggressive", choices=["moderate", "aggressive", "off"])
     ap.add_argument("--no-sweep", action="store_true")
@@ -75,6 +79,7 @@ class Layer:
         self.L, self.cfg, self.torch, self.wl = L, cfg, torch, wl
         self.weights = []          # per resident layer: packed routed gate/up, down, shared gate/up, down
         self.calls = 0
+        self.sigmoid_router = False
         for l in range(n_layers):
             d = wl.make_layer_device(cfg, T_gen if l == 0 else 1, "cuda", layer=l)
             Wgu, Wdp = L.lynx_pack_weights(d["Wg"], d["Wu"], d["Wd"])
@@ -104,7 +109,7 @@ class Layer:
             self.buf[key] = self.L.LayerBuffers(T, c.H, c.F, c.N, c.k, beta, c.n_shared, c.F_shared)
         return self.buf[key]
 
-    def step(self, T, alpha, beta, enable, events=None, layer=None, sigmoid=False):
+    def step(self, T, alpha, beta, enable, events=None, layer=None, sigmoid=None):
         """One decode step (the whole hot path) through the fused C-ABI entry point, on the current stream.
         Successive calls take the resident layers' expert weights in turn."""
         c = self.cfg
@@ -112,6 +117,8 @@ class Layer:
             layer = self.calls % len(self.weights)
             self.calls += 1
         Wgu, Wdp, Sgu, Sdp = self.weights[layer]
+        if sigmoid is None:
+            sigmoid = self.sigmoid_router
         entry = self.L.lynx_moe_layer_sigmoid if sigmoid else self.L.lynx_moe_layer
         return entry(self.tokens(T), self.Wr, self.bias, Wgu, Wdp, c.F, c.k, alpha, beta, enable, Sgu, Sdp, c.n_shared,
                      c.F_shared, buffers=self.buffers(T, beta), stage_events=events)
@@ -254,10 +261,13 @@ def main():
         run_stack(args, cfg, wl, torch)
         return
     T = args.tokens
+    if args.router == "sigmoid":
+        args.no_fp8, args.no_cpu_baseline, args.biased_gamma = True, True, 0.0
     alpha, beta, enable = preset_args(wl, args.preset)
     routed_bytes = 3 * cfg.N * cfg.H * cfg.F * 2
     n_layers = args.layers if args.layers > 0 else max(1, min(8, -(-(4 << 30) // routed_bytes)))
     layer = Layer(cfg, T, keep_row_major=not args.no_cpu_baseline, n_layers=n_layers)
+    layer.sigmoid_router = args.router == "sigmoid"
 
     if args.pmc_calibration:
         a = torch.ones(1 << 28, dtype=torch.float32, device="cuda")   # 1 GiB
@@ -335,7 +345,8 @@ def main():
         "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": f"{cfg.name}-shaped MoE layer: hidden {cfg.H}, FFN {cfg.F}, {cfg.N} experts top-{cfg.k}, "
-                               f"{cfg.n_shared} shared, bf16 weights, {T} decode tokens, remap {args.preset}",
+                               f"{cfg.n_shared} shared, bf16 weights, {T} decode tokens, remap {args.preset}"
+                               + (", sigmoid-gated router" if args.router == "sigmoid" else ""),
                    "tokens": T, "alpha": alpha, "beta": beta, "remap": bool(enable), "resident_layers": n_layers},
         "tokens_per_s": round(T / (ms_per_step * 1e-3), 1),
         "experts_invoked": {"before": n_before, "after": n_after},

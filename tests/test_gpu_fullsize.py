@@ -60,23 +60,24 @@ def _layer(L, name):
     return _layers[name]
 
 
-def _check_layer(L, lay, T, alpha, beta, enable, n_sample=5, seed=0):
+def _check_layer(L, lay, T, alpha, beta, enable, n_sample=5, seed=0, sigmoid=False):
     cfg, d = lay.cfg, lay.d
     xb = lay.tokens(T)
     x = to_bf16_dev(xb)
-    b = L.lynx_moe_layer(x, d["Wr"], d["bias"], lay.Wgu, lay.Wdp, cfg.F, cfg.k, alpha, beta, enable, lay.Sgu, lay.Sdp,
-                         cfg.n_shared, cfg.F_shared)
+    entry = L.lynx_moe_layer_sigmoid if sigmoid else L.lynx_moe_layer
+    b = entry(x, d["Wr"], d["bias"], lay.Wgu, lay.Wdp, cfg.F, cfg.k, alpha, beta, enable, lay.Sgu, lay.Sdp,
+              cfg.n_shared, cfg.F_shared)
     torch.cuda.synchronize()
     Wr, bias = host(d["Wr"]), host(d["bias"])
     # routing, whole batch
     r = oracle.route(xb, Wr, bias, cfg.k)
     z = host(b.logits)
     assert np.all(np.abs(z - r["logits"]) <= LOGIT_TOL * np.maximum(1.0, np.abs(r["logits"])))
-    tk = oracle.topk(z, cfg.k)
+    tk = (oracle.topk_sigmoid if sigmoid else oracle.topk)(z, cfg.k)
     assert np.array_equal(host(b.topk_idx), tk["idx"])
     np.testing.assert_allclose(host(b.topk_gate), tk["gate"], rtol=GATE_TOL, atol=1e-7)
-    np.testing.assert_allclose(host(b.topk_psum), tk["psum"], rtol=GATE_TOL, atol=1e-7)
-    a = oracle.affinity_bin(z, tk["idx"], alpha, beta, enable)
+    np.testing.assert_allclose(host(b.topk_psum), tk["ssum" if sigmoid else "psum"], rtol=GATE_TOL, atol=1e-7)
+    a = (oracle.affinity_bin_sigmoid if sigmoid else oracle.affinity_bin)(z, tk["idx"], alpha, beta, enable)
     for key, got in (("new_idx", b.new_idx), ("cnt_before", b.cnt_before), ("cnt_after", b.cnt_after),
                      ("bin_hist", b.bin_hist), ("num_active", b.num_active)):
         assert np.array_equal(host(got), a[key]), key
@@ -126,6 +127,19 @@ def test_full_size_layer(L, name, T, preset):
         (alpha, beta), enable = wl.PRESETS[preset], 1
     na, err = _check_layer(L, lay, T, alpha, beta, enable)
     print(f"  invoked {na.tolist()}, max sampled row err {err:.3e}", flush=True)
+
+
+@pytest.mark.parametrize("T,preset", [(8, "aggressive"), (64, "moderate")])
+def test_full_size_layer_sigmoid_router(L, T, preset):
+    """A DeepSeek-V3-shaped layer (256 experts of 88 MB, top-8, one shared expert) behind the sigmoid-gated router:
+    routing of the whole batch against the oracle, sampled tokens' outputs against the oracle's FFN."""
+    print(f"full-size layer dsv3 T={T} remap={preset}, sigmoid-gated router", flush=True)
+    lay = _layer(L, "dsv3")
+    alpha, beta = wl.PRESETS[preset]
+    na, err = _check_layer(L, lay, T, alpha, beta, 1, n_sample=2, sigmoid=True)
+    print(f"  invoked {na.tolist()}, max sampled row err {err:.3e}", flush=True)
+    _layers.clear()              # 45 GB of row-major and packed weights: release them before the next test
+    torch.cuda.empty_cache()
 
 
 @pytest.mark.parametrize("name,T", [("dsv2lite", 128), ("qwen3", 256), ("qwen15moe", 64)])

@@ -40,6 +40,9 @@ CONFIGS = {
     "qwen15moe": MoEConfig("qwen15moe", 2048, 1408, 60, 4, 1, 5632, 1.0, 0.5, 0.0, (8, 32, 64, 128, 256), 2),
     "dsv2lite": MoEConfig("dsv2lite", 2048, 1408, 64, 6, 2, 1408, 0.9, 0.5, 0.05, (16, 64, 128, 256), 3),
     "qwen3": MoEConfig("qwen3", 2048, 768, 128, 8, 0, 0, 1.0, 0.5, 0.0, (32, 128, 256, 512), 4, layers=48),
+    # not one of the benchmark's configurations: a DeepSeek-V3-shaped layer (256 routed experts, top-8, one shared
+    # expert, sigmoid-gated router) for the sigmoid-router widening; 22.5 GB of routed expert weights per layer
+    "dsv3": MoEConfig("dsv3", 7168, 2048, 256, 8, 1, 2048, 1.0, 0.5, 0.0, (8, 32, 64, 128), 5),
 }
 
 # (alpha, beta) presets of the binning resolution; the paper prints no values (Sec. 3.2.1).
