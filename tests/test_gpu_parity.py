@@ -104,6 +104,20 @@ def test_affinity_bin(L, T, N, k, s, tail):
     _check_bin(L, z, k, 2.0, 2, 0)                                   # bypass
 
 
+@pytest.mark.parametrize("T,N,beta", [(256, 255, 3), (256, 256, 3), (1024, 64, 2), (1024, 256, 2), (40, 100, 6), (16, 255, 3)])
+def test_affinity_bin_score_order_at_the_key_width_boundary(L, T, N, beta):
+    """The kernels order the experts by one 32-bit key, score * N + (N - 1 - index), whenever its largest possible value
+    fits (a score reaches T^beta when every token puts an expert into bin 0), and by the 64-bit score otherwise.  Both
+    sides of that switch, with every token agreeing on its top expert so that the largest score occurs, and with
+    many equal scores so that the index decides."""
+    k = 4
+    _say(f"score order at the key boundary: T={T} N={N} beta={beta} (T^beta*N+N = {T ** beta * N + N}, 2^32 = {2 ** 32})")
+    z = wl.make_logits(T, N, seed=T + N, quantum=0.5)
+    z[:, 7] = z.max() + 1.0                       # everybody's top-1: the score T^beta occurs
+    for alpha in (1.0, 0.25):
+        _check_bin(L, z, k, alpha, beta, 1)
+
+
 def test_affinity_bin_picks_in_any_order(L):
     """Picks that are k distinct experts but neither the top-k nor in rank order: same result as the oracle, which
     lets a slot without a candidate nominate nothing."""
