@@ -51,6 +51,29 @@ __device__ __forceinline__ float wave_sum(float v)
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 
+// The same on integers.  With the identity of the maximum as the value of the lanes a step does not write, a step
+// is one instruction (a float step is four: the float maximum has to quieten NaNs first).
+#define LYNX_DPP_STEP_IMAX(ctrl, rmask) v = max(v, __builtin_amdgcn_update_dpp(INT_MIN, v, ctrl, rmask, 0xf, false))
+__device__ __forceinline__ int wave_max_i32(int v)
+{
+    LYNX_DPP_STEP_IMAX(0x111, 0xf);
+    LYNX_DPP_STEP_IMAX(0x112, 0xf);
+    LYNX_DPP_STEP_IMAX(0x114, 0xf);
+    LYNX_DPP_STEP_IMAX(0x118, 0xf);
+    LYNX_DPP_STEP_IMAX(0x142, 0xa);
+    LYNX_DPP_STEP_IMAX(0x143, 0xc);
+    return __builtin_amdgcn_readlane(v, 63);
+}
+
+// Floats as integers that compare the same way (finite values and infinities; -0 is first made +0, so that the two
+// stay equal), and back.
+__device__ __forceinline__ int order_key(float f)
+{
+    const int b = __float_as_int(f + 0.0f);
+    return b ^ ((b >> 31) & 0x7fffffff);
+}
+__device__ __forceinline__ float key_value(int key) { return __int_as_float(key ^ ((key >> 31) & 0x7fffffff)); }
+
 // Bin magnitude of one (token, expert) pair: min(floor(alpha * (zmax - z)), beta), with exactly one
 // rounded fp32 subtract and one rounded fp32 multiply (paper Sec. 3.2.1; bin value = -q).
 __device__ __forceinline__ int bin_of(float zmax, float z, float alpha, int beta)
@@ -69,20 +92,25 @@ template <int NS, typename Emit>
 __device__ __forceinline__ void wave_topk(const float (&v)[NS], unsigned cand, int k, Emit &&emit)
 {
     const int lane = lane_id();
+    // the k wave-wide maxima are taken on order-preserving integer keys: see wave_max_i32
+    int key[NS];
+#pragma unroll
+    for (int i = 0; i < NS; ++i) key[i] = order_key(v[i]);
+    const int none = order_key(-INFINITY);
     for (int j = 0; j < k; ++j) {
-        float m = -INFINITY;
+        int m = none;
 #pragma unroll
         for (int i = 0; i < NS; ++i)
-            if ((cand >> i) & 1u) m = fmaxf(m, v[i]);
-        const float best = wave_max(m);
+            if ((cand >> i) & 1u) m = max(m, key[i]);
+        const int best = wave_max_i32(m);
         int e = INT_MAX;
 #pragma unroll
         for (int i = 0; i < NS; ++i) {
-            const unsigned long long b = __ballot(((cand >> i) & 1u) && v[i] == best);
+            const unsigned long long b = __ballot(((cand >> i) & 1u) && key[i] == best);
             if (e == INT_MAX && b != 0ull) e = __ffsll((long long)b) - 1 + kWave * i;
         }
         if (e != INT_MAX && (e & (kWave - 1)) == lane) cand &= ~(1u << (e >> 6));
-        emit(j, e, best);
+        emit(j, e, key_value(best));
     }
 }
 
