@@ -118,6 +118,21 @@ def test_affinity_bin_score_order_at_the_key_width_boundary(L, T, N, beta):
         _check_bin(L, z, k, alpha, beta, 1)
 
 
+def test_affinity_bin_signed_zero_logits_stay_tied(L):
+    """-0.0 and +0.0 are equal logits: the lower expert index wins, whichever sign it carries (the kernels pick on
+    integer keys of the floats, which would tell the two zeros apart if -0 were not made +0 first)."""
+    for T, N, k in [(3, 6, 2), (20, 70, 5)]:
+        rng = np.random.default_rng(N)
+        z = np.where(rng.random((T, N)) < 0.5, np.float32(-0.0), np.float32(0.0)).astype(np.float32)
+        z[:, N - 2:] = -5.0
+        assert np.signbit(z).any() and (~np.signbit(z)).any()
+        idx = oracle.topk(z, k)["idx"]
+        assert np.array_equal(idx, np.tile(np.arange(k, dtype=np.int32), (T, 1)))      # all zeros tie: indices 0..k-1
+        _say(f"signed zeros T={T} N={N} k={k}")
+        for alpha, beta in [(1.0, 1), (2.0, 3)]:
+            _check_bin(L, z, k, alpha, beta, 1)
+
+
 def test_affinity_bin_picks_in_any_order(L):
     """Picks that are k distinct experts but neither the top-k nor in rank order: same result as the oracle, which
     lets a slot without a candidate nominate nothing."""
