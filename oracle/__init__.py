@@ -41,11 +41,16 @@ def _load():
         lib = ctypes.CDLL(build())
         u16p, f32p, f64p, i32p, u64p = (POINTER(c_uint16), POINTER(c_float), POINTER(c_double), POINTER(c_int32),
                                         POINTER(c_uint64))
+        u8p = POINTER(ctypes.c_uint8)
         lib.orc_num_threads.restype = c_int
         lib.orc_route.argtypes = [u16p, f32p, f32p, c_int, c_int, c_int, c_int, f32p, i32p, f64p, f64p]
         lib.orc_topk.argtypes = [f32p, c_int, c_int, c_int, i32p, f64p, f64p]
         lib.orc_topk_sigmoid.argtypes = [f32p, c_int, c_int, c_int, i32p, f64p, f64p]
         lib.orc_sigmoid_gates.argtypes = [f32p, i32p, c_int, c_int, c_int, f64p, f64p]
+        lib.orc_group_allowed.argtypes = [f32p, c_int, c_int, c_int, c_int, u8p]
+        lib.orc_topk_grouped.argtypes = [f32p, c_int, c_int, c_int, c_int, c_int, c_int, i32p, f64p, f64p]
+        lib.orc_affinity_bin_grouped.argtypes = [f32p, i32p, c_int, c_int, c_int, c_int, c_int, c_float, c_int, c_int, i32p,
+                                                 f64p, i32p, i32p, i32p, i32p, i32p]
         lib.orc_affinity_bin.argtypes = [f32p, i32p, c_int, c_int, c_int, c_float, c_int, c_int, i32p, f64p, i32p,
                                          i32p, i32p, i32p, i32p, u64p, i32p]
         lib.orc_affinity_bin_biased.argtypes = [f32p, i32p, c_int, c_int, c_int, c_float, c_int, c_float, c_int, i32p,
@@ -53,7 +58,6 @@ def _load():
         lib.orc_permute.argtypes = [i32p, c_int, c_int, c_int, i32p, i32p, i32p, i32p]
         lib.orc_moe_ffn.argtypes = [u16p, u16p, u16p, u16p, u16p, u16p, u16p, c_int, c_int, i32p, f64p, c_int, c_int,
                                     c_int, c_int, c_int, f64p]
-        u8p = POINTER(ctypes.c_uint8)
         lib.orc_e4m3_decode.argtypes = [ctypes.c_uint8]
         lib.orc_e4m3_decode.restype = c_double
         lib.orc_e4m3_encode.argtypes = [c_float]
@@ -164,6 +168,60 @@ def affinity_bin_sigmoid(logits, topk_idx, alpha, beta, enable=1):
     a = affinity_bin(logits, topk_idx, alpha, beta, enable)
     a["new_gate"], _ = sigmoid_gates(logits, a["new_idx"])
     return a
+
+
+def group_allowed(logits, n_group, topk_group):
+    """Group-limited routers: allow [T,N] (0/1), the experts of each token's topk_group best groups (group score =
+    largest logit in the group, ties to the lower group)."""
+    z = _arr(logits, np.float32)
+    T, N = z.shape
+    allow = np.zeros((T, N), np.uint8)
+    rc = _load().orc_group_allowed(_p(z, c_float), T, N, int(n_group), int(topk_group), _p(allow, ctypes.c_uint8))
+    if rc != OK:
+        raise OracleError(rc, "orc_group_allowed")
+    return allow
+
+
+def topk_grouped(logits, k, n_group, topk_group, gate_fn=0):
+    """Group-limited top-k.  gate_fn 0: softmax gates, third = selected share of the softmax over all experts;
+    1: sigmoid gates, third = sum of the selected scores.  Returns dict(idx, gate f64, third f64)."""
+    z = _arr(logits, np.float32)
+    T, N = z.shape
+    idx = np.zeros((T, k), np.int32)
+    gate = np.zeros((T, k), np.float64)
+    third = np.zeros((T,), np.float64)
+    rc = _load().orc_topk_grouped(_p(z, c_float), T, N, k, int(n_group), int(topk_group), int(gate_fn), _p(idx, c_int32),
+                                  _p(gate, c_double), _p(third, c_double))
+    if rc != OK:
+        raise OracleError(rc, "orc_topk_grouped")
+    return dict(idx=idx, gate=gate, third=third)
+
+
+def affinity_bin_grouped(logits, topk_idx, n_group, topk_group, alpha, beta, enable=1, gate_fn=0):
+    """AffinityBinning for a group-limited router: every token stays inside its own groups.  topk_idx is the selection
+    of topk_grouped.  Returns dict with new_idx, new_gate (f64), cnt_before, cnt_after, bin_hist, num_active, active."""
+    z = _arr(logits, np.float32)
+    idx = _arr(topk_idx, np.int32)
+    T, N = z.shape
+    k = idx.shape[1]
+    nb = max(int(beta), 1)
+    new_idx = np.zeros((T, k), np.int32)
+    new_gate = np.zeros((T, k), np.float64)
+    cnt_before = np.zeros((N,), np.int32)
+    cnt_after = np.zeros((N,), np.int32)
+    bin_hist = np.zeros((N, nb), np.int32)
+    num_active = np.zeros((2,), np.int32)
+    active = np.zeros((N,), np.int32)
+    rc = _load().orc_affinity_bin_grouped(_p(z, c_float), _p(idx, c_int32), T, N, k, int(n_group), int(topk_group),
+                                          float(alpha), int(beta), int(enable), _p(new_idx, c_int32),
+                                          _p(new_gate, c_double), _p(cnt_before, c_int32), _p(cnt_after, c_int32),
+                                          _p(bin_hist, c_int32), _p(num_active, c_int32), _p(active, c_int32))
+    if rc != OK:
+        raise OracleError(rc, "orc_affinity_bin_grouped")
+    if gate_fn:
+        new_gate, _ = sigmoid_gates(z, new_idx)
+    return dict(new_idx=new_idx, new_gate=new_gate, cnt_before=cnt_before, cnt_after=cnt_after, bin_hist=bin_hist,
+                num_active=num_active, active=active)
 
 
 def affinity_bin(logits, topk_idx, alpha, beta, enable=1):

@@ -23,9 +23,12 @@
  * rational arithmetic and exhaustive search for the bias, the published element tables, an
  * independent library cast (FP8), brute-force rounding on exact rationals, block exponents and error
  * bounds (MXFP4), and a numpy fp64 contraction of the dequantised weights for the quantised FFNs; the
- * gates of sigmoid-gated routers: closed forms, a library logistic function, and what tells them from softmax.
+ * gates of sigmoid-gated routers: closed forms, a library logistic function, and what tells them from softmax;
+ * group-limited routers: hand-worked cases, a numpy statement of the mask, and the reduction of the grouped
+ * remap to the ungrouped one on logits whose forbidden entries are pushed far down.
  * Parity unpinned against the paper: the values of alpha and beta, the bias scale gamma, the
- * weight formats and the gate formula of sigmoid-gated routers (the paper prints none of them).
+ * weight formats, the gate formula of sigmoid-gated routers and the rule for expert groups (the paper prints
+ * none of them).
  */
 #include <math.h>
 #include <stdint.h>
@@ -201,11 +204,17 @@ int orc_route(const uint16_t *x_bf16, const float *Wr, const float *bias, int T,
  * enable = 0 (batch not memory-bound, Sec. 3.1.1 / 3.5) or T = 1 leaves the selection as it is.
  *
  * q_out [T,N], score_out [N], active_out [N] (0/1) are optional diagnostics (may be NULL).
+ *
+ * allow [T,N] (0/1) or NULL restricts, per token, the experts the token may be sent to (group-limited routers, see
+ * orc_group_allowed below); NULL = every expert, which is the method as the paper states it.  With a mask, a
+ * (token, expert) pair that is not allowed has no bin (it does not vote), is never nominated by that token and is
+ * never selected for it; the token's own picks must be allowed.  A token whose allowed experts hold fewer than k
+ * members of the active set keeps, for the slots that stay empty, its own picks in rank order (those not chosen yet).
  */
-int orc_affinity_bin(const float *logits, const int32_t *topk_idx, int T, int N, int k, float alpha, int beta,
-                     int enable, int32_t *new_idx, double *new_gate, int32_t *cnt_before, int32_t *cnt_after,
-                     int32_t *bin_hist, int32_t *num_active, int32_t *q_out, uint64_t *score_out,
-                     int32_t *active_out)
+static int affinity_bin_core(const float *logits, const int32_t *topk_idx, const uint8_t *allow, int T, int N, int k,
+                             float alpha, int beta, int enable, int32_t *new_idx, double *new_gate, int32_t *cnt_before,
+                             int32_t *cnt_after, int32_t *bin_hist, int32_t *num_active, int32_t *q_out,
+                             uint64_t *score_out, int32_t *active_out)
 {
     if (T < 0 || N <= 0 || k <= 0 || beta < 1 || !(alpha >= 0.0f) || isinf(alpha)) return ORC_ERR_INVALID_ARG;
     if (k > N || beta > ORC_MAX_BETA) return ORC_ERR_UNSUPPORTED;
@@ -218,11 +227,13 @@ int orc_affinity_bin(const float *logits, const int32_t *topk_idx, int T, int N,
         for (int j = 0; j < k; ++j) {
             int32_t e = topk_idx[(size_t)t * k + j];
             if (e < 0 || e >= N) return ORC_ERR_INVALID_ARG;
+            if (allow && !allow[(size_t)t * N + e]) return ORC_ERR_INVALID_ARG;
             for (int i = 0; i < j; ++i)
                 if (topk_idx[(size_t)t * k + i] == e) return ORC_ERR_INVALID_ARG;
         }
 
     int32_t *q = (int32_t *)malloc(sizeof(int32_t) * (size_t)(T > 0 ? T : 1) * N);
+    uint8_t *mask = (uint8_t *)calloc((size_t)N, 1);
     uint64_t *score = (uint64_t *)calloc((size_t)N, sizeof(uint64_t));
     uint8_t *inU = (uint8_t *)calloc((size_t)N, 1);
     uint8_t *inA = (uint8_t *)calloc((size_t)N, 1);
@@ -248,6 +259,7 @@ int orc_affinity_bin(const float *logits, const int32_t *topk_idx, int T, int N,
     for (int t = 0; t < T; ++t)
         for (int e = 0; e < N; ++e) {
             int32_t b = q[(size_t)t * N + e];
+            if (allow && !allow[(size_t)t * N + e]) continue;
             if (b < beta) bin_hist[(size_t)e * beta + b] += 1;
         }
     for (int t = 0; t < T; ++t)
@@ -286,6 +298,7 @@ int orc_affinity_bin(const float *logits, const int32_t *topk_idx, int T, int N,
                 int best = -1;
                 for (int e = 0; e < N; ++e) {
                     if (!inU[e] || used[e] || qt[e] > qi) continue;
+                    if (allow && !allow[(size_t)t * N + e]) continue;
                     if (best < 0 || score[e] > score[best]) best = e;
                 }
                 /* With the picks in rank order (descending logit, as top-k gives them) this is never empty: the
@@ -313,7 +326,14 @@ int orc_affinity_bin(const float *logits, const int32_t *topk_idx, int T, int N,
         for (int t = 0; t < T; ++t) {
             const float *z = logits + (size_t)t * N;
             int32_t *sel = new_idx + (size_t)t * k;
-            topk_select(z, inA, N, k, sel);
+            for (int e = 0; e < N; ++e) mask[e] = inA[e] && (!allow || allow[(size_t)t * N + e]);
+            int found = topk_select(z, mask, N, k, sel);
+            for (int j = 0; j < k && found < k; ++j) { /* only with an allow mask: see the header */
+                const int32_t own = topk_idx[(size_t)t * k + j];
+                int chosen = 0;
+                for (int i = 0; i < found; ++i) chosen |= sel[i] == own;
+                if (!chosen) sel[found++] = own;
+            }
             gates_of_selection(z, sel, k, new_gate + (size_t)t * k);
             for (int j = 0; j < k; ++j) cnt_after[sel[j]] += 1;
         }
@@ -332,7 +352,100 @@ int orc_affinity_bin(const float *logits, const int32_t *topk_idx, int T, int N,
     free(inU);
     free(inA);
     free(used);
+    free(mask);
     return ORC_OK;
+}
+
+int orc_affinity_bin(const float *logits, const int32_t *topk_idx, int T, int N, int k, float alpha, int beta,
+                     int enable, int32_t *new_idx, double *new_gate, int32_t *cnt_before, int32_t *cnt_after,
+                     int32_t *bin_hist, int32_t *num_active, int32_t *q_out, uint64_t *score_out,
+                     int32_t *active_out)
+{
+    return affinity_bin_core(logits, topk_idx, NULL, T, N, k, alpha, beta, enable, new_idx, new_gate, cnt_before,
+                             cnt_after, bin_hist, num_active, q_out, score_out, active_out);
+}
+
+/*
+ * Group-limited routers.  Sec. 1 lists expert grouping among the architectures the method has to cover and says no
+ * more about it.  The reading here: the N experts form n_group groups of N / n_group consecutive experts; a token
+ * may only be sent to experts of its topk_group best groups, the score of a group being the largest logit in it
+ * (softmax and sigmoid are increasing, so this is also the largest probability or score), equal group scores to the
+ * lower group; the router's selection is the top-k among those experts; and the remap keeps every token inside its
+ * own groups, so whatever the limit buys (a bound on the devices a token's activations travel to) survives it.
+ * Everything else is orc_affinity_bin with that mask (see there for what the mask does).
+ *
+ * orc_group_allowed: allow [T,N] (0/1).
+ * orc_topk_grouped: the group-limited selection, its gates (gate_fn 0: softmax over the selected logits, 1: the
+ *   selected sigmoid scores over their sum) and the third output (0: the selected share of the softmax over ALL
+ *   N experts, 1: the sum of the selected scores).
+ * orc_affinity_bin_grouped: the remap under the mask; topk_idx is the selection of orc_topk_grouped.  Gates as in
+ *   orc_affinity_bin (softmax); for sigmoid gates apply orc_sigmoid_gates to new_idx.
+ */
+int orc_group_allowed(const float *logits, int T, int N, int n_group, int topk_group, uint8_t *allow)
+{
+    if (T < 0 || N <= 0 || n_group <= 0 || topk_group <= 0 || topk_group > n_group || (N % n_group) != 0)
+        return ORC_ERR_INVALID_ARG;
+    const int gs = N / n_group;
+    float *gscore = (float *)malloc(sizeof(float) * (size_t)n_group);
+    int32_t *best = (int32_t *)malloc(sizeof(int32_t) * (size_t)topk_group);
+    for (int t = 0; t < T; ++t) {
+        const float *z = logits + (size_t)t * N;
+        for (int g = 0; g < n_group; ++g) {
+            gscore[g] = z[(size_t)g * gs];
+            for (int i = 1; i < gs; ++i)
+                if (z[(size_t)g * gs + i] > gscore[g]) gscore[g] = z[(size_t)g * gs + i];
+        }
+        const int found = topk_select(gscore, NULL, n_group, topk_group, best);
+        memset(allow + (size_t)t * N, 0, (size_t)N);
+        for (int j = 0; j < found; ++j) memset(allow + (size_t)t * N + (size_t)best[j] * gs, 1, (size_t)gs);
+    }
+    free(gscore);
+    free(best);
+    return ORC_OK;
+}
+
+int orc_topk_grouped(const float *logits, int T, int N, int k, int n_group, int topk_group, int gate_fn,
+                     int32_t *topk_idx, double *topk_gate, double *topk_third)
+{
+    if (T < 0 || N <= 0 || k <= 0 || (gate_fn != 0 && gate_fn != 1)) return ORC_ERR_INVALID_ARG;
+    if (k > N) return ORC_ERR_UNSUPPORTED;
+    if (n_group <= 0 || topk_group <= 0 || topk_group > n_group || (N % n_group) != 0 ||
+        (long)topk_group * (N / n_group) < k)
+        return ORC_ERR_INVALID_ARG;
+    uint8_t *allow = (uint8_t *)malloc((size_t)(T > 0 ? T : 1) * N);
+    int rc = orc_group_allowed(logits, T, N, n_group, topk_group, allow);
+    for (int t = 0; t < T && rc == ORC_OK; ++t) {
+        const float *z = logits + (size_t)t * N;
+        int32_t *sel = topk_idx + (size_t)t * k;
+        topk_select(z, allow + (size_t)t * N, N, k, sel);
+        if (gate_fn == 0) {
+            double zmax = (double)z[0], den = 0.0, num = 0.0;
+            for (int e = 1; e < N; ++e)
+                if ((double)z[e] > zmax) zmax = (double)z[e];
+            for (int e = 0; e < N; ++e) den += exp((double)z[e] - zmax);
+            for (int j = 0; j < k; ++j) num += exp((double)z[sel[j]] - zmax);
+            topk_third[t] = num / den;
+            gates_of_selection(z, sel, k, topk_gate + (size_t)t * k);
+        }
+    }
+    if (rc == ORC_OK && gate_fn == 1) rc = orc_sigmoid_gates(logits, topk_idx, T, N, k, topk_gate, topk_third);
+    free(allow);
+    return rc;
+}
+
+int orc_affinity_bin_grouped(const float *logits, const int32_t *topk_idx, int T, int N, int k, int n_group,
+                             int topk_group, float alpha, int beta, int enable, int32_t *new_idx, double *new_gate,
+                             int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist, int32_t *num_active,
+                             int32_t *active_out)
+{
+    if (T < 0 || N <= 0) return ORC_ERR_INVALID_ARG;
+    uint8_t *allow = (uint8_t *)malloc((size_t)(T > 0 ? T : 1) * N);
+    int rc = orc_group_allowed(logits, T, N, n_group, topk_group, allow);
+    if (rc == ORC_OK)
+        rc = affinity_bin_core(logits, topk_idx, allow, T, N, k, alpha, beta, enable, new_idx, new_gate, cnt_before,
+                               cnt_after, bin_hist, num_active, NULL, NULL, active_out);
+    free(allow);
+    return rc;
 }
 
 /*
