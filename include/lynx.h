@@ -280,6 +280,44 @@ int lynx_moe_layer_sigmoid(const uint16_t *x_bf16, const float *Wr, const float 
                            int32_t *num_active_perm, float *y, void *workspace, void *stream, void *const *stage_events);
 
 /*
+ * Group-limited routers.  Sec. 1 lists expert grouping among the architectures the method has to cover and gives no
+ * rule for it.  The reading here: the N experts form n_group groups of N / n_group consecutive experts; the score of a
+ * group for a token is the largest logit in it; the token may only be sent to experts of its topk_group best groups
+ * (equal group scores to the lower group); the router's selection is the top-k among those; and the remap keeps the
+ * token inside the same groups: a forbidden (token, expert) pair has no bin and casts no vote, is never nominated and
+ * never selected.  A token whose groups hold fewer than k members of the active set takes them all and keeps, for the
+ * slots left, its own picks that are not in the active set, in rank order (so new_idx always holds k distinct experts
+ * the batch already invoked).  Batch scores, score order, active-set fill, gates, counts and permutation are as in
+ * the calls above.  gate_fn: 0 = softmax gates, topk_third [T] = selected share of the softmax over ALL N experts;
+ * 1 = sigmoid gates (see above), topk_third = sum of the selected scores.
+ *
+ * n_group >= 1 must divide N, 1 <= topk_group <= n_group, topk_group * N / n_group >= k, gate_fn in {0, 1}, else
+ * LYNX_ERR_INVALID_ARG; n_group <= 64, else LYNX_ERR_UNSUPPORTED.  n_group = 1 (or topk_group = n_group) is the
+ * router without groups.
+ *
+ * lynx_route_grouped: lynx_route with the group limit.
+ * lynx_affinity_bin_grouped: top-k and remap from given logits in one call (the remap needs the group-limited
+ *   selection, so it is computed here, not handed in): topk_idx / topk_gate [T,k] and topk_third [T] are OUTPUTS,
+ *   the rest as lynx_affinity_bin.
+ * lynx_moe_layer_grouped: lynx_moe_layer (bf16 expert weights) with the group limit.
+ */
+int lynx_route_grouped(const uint16_t *x_bf16, const float *Wr, const float *bias, int T, int H, int N, int k, int n_group,
+                       int topk_group, int gate_fn, float *logits, int32_t *topk_idx, float *topk_gate, float *topk_third,
+                       void *stream);
+int lynx_affinity_bin_grouped(const float *logits, int T, int N, int k, int n_group, int topk_group, int gate_fn, float alpha,
+                              int beta, int enable, int32_t *topk_idx, float *topk_gate, float *topk_third,
+                              int32_t *new_idx, float *new_gate, int32_t *cnt_before, int32_t *cnt_after,
+                              int32_t *bin_hist, int32_t *num_active, void *workspace, void *stream);
+int lynx_moe_layer_grouped(const uint16_t *x_bf16, const float *Wr, const float *bias, const uint16_t *Wgu_packed,
+                           const uint16_t *Wd_packed, const uint16_t *Sgu_packed, const uint16_t *Sd_packed, int n_shared,
+                           int F_shared, int T, int H, int F, int N, int k, int n_group, int topk_group, int gate_fn,
+                           float alpha, int beta, int enable, float *logits, int32_t *topk_idx, float *topk_gate,
+                           float *topk_third, int32_t *new_idx, float *new_gate, int32_t *cnt_before, int32_t *cnt_after,
+                           int32_t *bin_hist, int32_t *num_active, int32_t *expert_offsets, int32_t *perm,
+                           int32_t *active_experts, int32_t *num_active_perm, float *y, void *workspace, void *stream,
+                           void *const *stage_events);
+
+/*
  * Measurement aid, not a step of the method: the residual update that chains MoE layers into a stack (the
  * benchmark times a stack of layers as a whole, each layer's input depending on the layer before):
  * x_next[i] = bf16(float(x[i]) + y[i]) for i < n, one fp32 addition rounded to nearest even.  x_bf16 [n] and

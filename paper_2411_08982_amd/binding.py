@@ -23,7 +23,8 @@ SYMBOLS = ["lynx_last_error", "lynx_workspace_bytes", "lynx_route", "lynx_affini
            "lynx_pack_weights", "lynx_moe_ffn", "lynx_moe_ffn_timed", "lynx_moe_layer", "lynx_moe_ffn_launches", "lynx_residual_add", "lynx_read_probe",
            "lynx_quantize_weights_fp8", "lynx_moe_ffn_fp8", "lynx_moe_layer_fp8",
            "lynx_fp4_scale_words", "lynx_quantize_weights_fp4", "lynx_moe_ffn_fp4", "lynx_moe_layer_fp4",
-           "lynx_route_sigmoid", "lynx_affinity_bin_sigmoid", "lynx_moe_layer_sigmoid"]
+           "lynx_route_sigmoid", "lynx_affinity_bin_sigmoid", "lynx_moe_layer_sigmoid",
+           "lynx_route_grouped", "lynx_affinity_bin_grouped", "lynx_moe_layer_grouped"]
 
 
 class LynxError(RuntimeError):
@@ -69,6 +70,10 @@ def lib():
         L.lynx_route_sigmoid.argtypes = L.lynx_route.argtypes
         L.lynx_affinity_bin_sigmoid.argtypes = L.lynx_affinity_bin.argtypes
         L.lynx_moe_layer_sigmoid.argtypes = L.lynx_moe_layer.argtypes
+        L.lynx_route_grouped.argtypes = [P, P, P, I, I, I, I, I, I, I, P, P, P, P, P]
+        L.lynx_affinity_bin_grouped.argtypes = [P, I, I, I, I, I, I, F, I, I] + [P] * 11
+        L.lynx_moe_layer_grouped.argtypes = ([P, P, P, P, P, P, P, I, I, I, I, I, I, I, I, I, I, F, I, I] + [P] * 17 +
+                                             [ctypes.POINTER(c_void_p)])
         for name in SYMBOLS:
             # without declared argument types ctypes passes Python ints as 32-bit C ints: a device pointer would be cut
             if getattr(L, name).argtypes is None:
@@ -131,6 +136,43 @@ def lynx_route(x, Wr, bias, k, out=None, _entry="lynx_route"):
 def lynx_route_sigmoid(x, Wr, bias, k, out=None):
     """lynx_route for a sigmoid-gated router; the entry "psum" holds the sum of the selected scores."""
     return lynx_route(x, Wr, bias, k, out, _entry="lynx_route_sigmoid")
+
+
+def lynx_route_grouped(x, Wr, bias, k, n_group, topk_group, gate_fn=0, out=None):
+    """lynx_route for a group-limited router (gate_fn 0 softmax, 1 sigmoid); "psum" holds the third output."""
+    T, H = x.shape
+    N = Wr.shape[0]
+    dev = x.device
+    o = out or dict(logits=torch.empty((T, N), dtype=F32, device=dev), idx=torch.empty((T, k), dtype=I32, device=dev),
+                    gate=torch.empty((T, k), dtype=F32, device=dev), psum=torch.empty((T,), dtype=F32, device=dev))
+    _check(lib().lynx_route_grouped(_ptr(x, BF16, "x"), _ptr(Wr, F32, "Wr"), _ptr(bias, F32, "bias"), T, H, N, k,
+                                    int(n_group), int(topk_group), int(gate_fn), _ptr(o["logits"], F32, "logits"),
+                                    _ptr(o["idx"], I32, "idx"), _ptr(o["gate"], F32, "gate"), _ptr(o["psum"], F32, "psum"),
+                                    _stream()))
+    return o
+
+
+def lynx_affinity_bin_grouped(logits, k, n_group, topk_group, alpha, beta, gate_fn=0, enable=1, workspace=None, out=None):
+    """Group-limited top-k and remap from logits [T,N] f32 -> dict(idx, gate, psum, new_idx, new_gate, cnt_before,
+    cnt_after, bin_hist, num_active)."""
+    T, N = logits.shape
+    dev = logits.device
+    nb = max(int(beta), 1)
+    o = out or dict(idx=torch.empty((T, k), dtype=I32, device=dev), gate=torch.empty((T, k), dtype=F32, device=dev),
+                    psum=torch.empty((T,), dtype=F32, device=dev),
+                    new_idx=torch.empty((T, k), dtype=I32, device=dev), new_gate=torch.empty((T, k), dtype=F32, device=dev),
+                    cnt_before=torch.empty((N,), dtype=I32, device=dev), cnt_after=torch.empty((N,), dtype=I32, device=dev),
+                    bin_hist=torch.empty((N, nb), dtype=I32, device=dev), num_active=torch.empty((2,), dtype=I32, device=dev))
+    if workspace is None:
+        workspace = torch.empty(65536, dtype=torch.uint8, device=dev)
+    _check(lib().lynx_affinity_bin_grouped(_ptr(logits, F32, "logits"), T, N, int(k), int(n_group), int(topk_group),
+                                           int(gate_fn), float(alpha), int(beta), int(enable), _ptr(o["idx"], I32, "idx"),
+                                           _ptr(o["gate"], F32, "gate"), _ptr(o["psum"], F32, "psum"),
+                                           _ptr(o["new_idx"], I32, "new_idx"), _ptr(o["new_gate"], F32, "new_gate"),
+                                           _ptr(o["cnt_before"], I32, "cnt_before"), _ptr(o["cnt_after"], I32, "cnt_after"),
+                                           _ptr(o["bin_hist"], I32, "bin_hist"), _ptr(o["num_active"], I32, "num_active"),
+                                           workspace.data_ptr(), _stream()))
+    return o
 
 
 def lynx_affinity_bin(logits, topk_idx, alpha, beta, enable=1, workspace=None, out=None, _entry="lynx_affinity_bin"):
@@ -268,6 +310,26 @@ def lynx_moe_layer_sigmoid(x, Wr, bias, Wgu, Wdp, F, k, alpha, beta, enable=1, S
     """lynx_moe_layer for a sigmoid-gated router (topk_psum holds the sum of the selected scores)."""
     return lynx_moe_layer(x, Wr, bias, Wgu, Wdp, F, k, alpha, beta, enable, Sgu, Sdp, n_shared, F_shared, buffers,
                           stage_events, _entry="lynx_moe_layer_sigmoid")
+
+
+def lynx_moe_layer_grouped(x, Wr, bias, Wgu, Wdp, F, k, n_group, topk_group, alpha, beta, gate_fn=0, enable=1, Sgu=None,
+                           Sdp=None, n_shared=0, F_shared=0, buffers: LayerBuffers | None = None, stage_events=None):
+    """lynx_moe_layer for a group-limited router (gate_fn 0 softmax, 1 sigmoid)."""
+    T, H = x.shape
+    N = Wr.shape[0]
+    b = buffers or LayerBuffers(T, H, F, N, k, beta, n_shared, F_shared, x.device)
+    if b.sizes != (T, H, F, N, k, n_shared, F_shared) or b.beta != beta:
+        raise ValueError("buffers were allocated for other sizes")
+    _check(lib().lynx_moe_layer_grouped(
+        _ptr(x, BF16, "x"), _ptr(Wr, F32, "Wr"), _ptr(bias, F32, "bias"), _ptr(Wgu, BF16, "Wgu"), _ptr(Wdp, BF16, "Wdp"),
+        _ptr(Sgu, BF16, "Sgu"), _ptr(Sdp, BF16, "Sdp"), n_shared, F_shared, T, H, F, N, k, int(n_group), int(topk_group),
+        int(gate_fn), float(alpha), int(beta), int(enable), b.logits.data_ptr(), b.topk_idx.data_ptr(),
+        b.topk_gate.data_ptr(), b.topk_psum.data_ptr(), b.new_idx.data_ptr(), b.new_gate.data_ptr(),
+        b.cnt_before.data_ptr(), b.cnt_after.data_ptr(), b.bin_hist.data_ptr(), b.num_active.data_ptr(),
+        b.offsets.data_ptr(), b.perm.data_ptr(), b.active.data_ptr(), b.num_active_perm.data_ptr(), b.y.data_ptr(),
+        b.workspace.data_ptr(), _stream(),
+        None if stage_events is None else (c_void_p * 4)(*[e.cuda_event for e in stage_events])))
+    return b
 
 
 def lynx_read_probe(buf, sink, non_temporal=True):

@@ -30,10 +30,11 @@ extern "C" const char *lynx_last_error(void) { return lynx::g_last_error; }
 
 namespace lynx {
 int routing_fused(const uint16_t *x, const float *Wr, const float *bias, int T, int H, int N, int k, float alpha,
-                  int beta, int enable, int gate_fn, float *logits, int32_t *topk_idx, float *topk_gate, float *topk_psum,
+                  int beta, int enable, RouterKind rk, float *logits, int32_t *topk_idx, float *topk_gate, float *topk_psum,
                   int32_t *new_idx, float *new_gate, int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist,
                   int32_t *num_active, int32_t *expert_offsets, int32_t *perm, int32_t *active_experts,
                   int32_t *num_active_perm, void *workspace, hipStream_t st);
+int check_router_kind(const char *who, int N, int k, const RouterKind &rk);
 int moe_ffn_impl(const uint16_t *x_bf16, const uint16_t *Wgu_packed, const uint16_t *Wd_packed, const uint16_t *Sgu_packed,
                  const uint16_t *Sd_packed, int n_shared, int F_shared, const int32_t *idx, const float *gate,
                  const int32_t *expert_offsets, const int32_t *perm, const int32_t *active_experts,
@@ -52,11 +53,23 @@ static int moe_layer_impl(const uint16_t *x_bf16, const float *Wr, const float *
                           int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist, int32_t *num_active,
                           int32_t *expert_offsets, int32_t *perm, int32_t *active_experts, int32_t *num_active_perm,
                           float *y, void *workspace, void *stream, void *const *stage_events, const FfnScales *q8,
-                          int gate_fn = 0)   // 1: sigmoid-gated router
+                          RouterKind rk = {0, 1, 1})
 {
     int rc;
     bool fused = false;
-    if (T <= 0 || !workspace) {
+    const int gate_fn = rk.gate_fn;
+    if (rk.n_group > 1 && (T <= 0 || !workspace)) {
+        // group-limited router: route + remap in one call, which also reports a missing workspace
+        rc = lynx_route_grouped(x_bf16, Wr, bias, T, H, N, k, rk.n_group, rk.topk_group, gate_fn, logits, topk_idx, topk_gate,
+                                topk_psum, stream);
+        if (rc != LYNX_OK) return rc;
+        rc = lynx_affinity_bin_grouped(logits, T, N, k, rk.n_group, rk.topk_group, gate_fn, alpha, beta, enable, topk_idx,
+                                       topk_gate, topk_psum, new_idx, new_gate, cnt_before, cnt_after, bin_hist, num_active,
+                                       workspace, stream);
+        if (rc != LYNX_OK) return rc;
+        rc = lynx_permute(new_idx, T, N, k, expert_offsets, perm, active_experts, num_active_perm, stream);
+        if (rc != LYNX_OK) return rc;
+    } else if (T <= 0 || !workspace) {
         // no tokens (or a missing workspace, which the separate calls report): take the separate calls
         rc = (gate_fn ? lynx_route_sigmoid : lynx_route)(x_bf16, Wr, bias, T, H, N, k, logits, topk_idx, topk_gate, topk_psum,
                                                          stream);
@@ -70,6 +83,8 @@ static int moe_layer_impl(const uint16_t *x_bf16, const float *Wr, const float *
     } else {
         // same argument checks as the separate calls, before anything is enqueued
         if (H <= 0 || N <= 0 || k <= 0) return fail(LYNX_ERR_INVALID_ARG, "lynx_moe_layer: negative or zero size");
+        rc = check_router_kind("lynx_moe_layer", N, k, rk);
+        if (rc != LYNX_OK) return rc;
         if (k > N || N > LYNX_MAX_N || k > LYNX_MAX_K || T > LYNX_MAX_T || (H % 32) != 0 || beta > LYNX_MAX_BETA)
             return fail(LYNX_ERR_UNSUPPORTED, "lynx_moe_layer: need k<=N<=%d, k<=%d, T<=%d, beta<=%d, H%%32==0", LYNX_MAX_N,
                         LYNX_MAX_K, LYNX_MAX_T, LYNX_MAX_BETA);
@@ -90,7 +105,7 @@ static int moe_layer_impl(const uint16_t *x_bf16, const float *Wr, const float *
             return fail(LYNX_ERR_UNSUPPORTED, "lynx_moe_layer: H, F and F_shared must be multiples of %d", mult);
         if (q8 && (!q8->gu || !q8->d || (n_shared > 0 && (!q8->shared_gu || !q8->shared_d))))
             return fail(LYNX_ERR_INVALID_ARG, "lynx_moe_layer_fp8: null scale pointer");
-        rc = routing_fused(x_bf16, Wr, bias, T, H, N, k, alpha, beta, enable, gate_fn, logits, topk_idx, topk_gate, topk_psum,
+        rc = routing_fused(x_bf16, Wr, bias, T, H, N, k, alpha, beta, enable, rk, logits, topk_idx, topk_gate, topk_psum,
                            new_idx, new_gate, cnt_before, cnt_after, bin_hist, num_active, expert_offsets, perm,
                            active_experts, num_active_perm, workspace, (hipStream_t)stream);
         if (rc != LYNX_OK) return rc;
@@ -129,7 +144,24 @@ extern "C" int lynx_moe_layer_sigmoid(const uint16_t *x_bf16, const float *Wr, c
     return lynx::moe_layer_impl(x_bf16, Wr, bias, Wgu_packed, Wd_packed, Sgu_packed, Sd_packed, n_shared, F_shared, T, H, F,
                                 N, k, alpha, beta, enable, logits, topk_idx, topk_gate, topk_ssum, new_idx, new_gate,
                                 cnt_before, cnt_after, bin_hist, num_active, expert_offsets, perm, active_experts,
-                                num_active_perm, y, workspace, stream, stage_events, nullptr, 1);
+                                num_active_perm, y, workspace, stream, stage_events, nullptr, lynx::RouterKind{1, 1, 1});
+}
+
+extern "C" int lynx_moe_layer_grouped(const uint16_t *x_bf16, const float *Wr, const float *bias, const uint16_t *Wgu_packed,
+                                      const uint16_t *Wd_packed, const uint16_t *Sgu_packed, const uint16_t *Sd_packed,
+                                      int n_shared, int F_shared, int T, int H, int F, int N, int k, int n_group,
+                                      int topk_group, int gate_fn, float alpha, int beta, int enable, float *logits,
+                                      int32_t *topk_idx, float *topk_gate, float *topk_third, int32_t *new_idx,
+                                      float *new_gate, int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist,
+                                      int32_t *num_active, int32_t *expert_offsets, int32_t *perm, int32_t *active_experts,
+                                      int32_t *num_active_perm, float *y, void *workspace, void *stream,
+                                      void *const *stage_events)
+{
+    return lynx::moe_layer_impl(x_bf16, Wr, bias, Wgu_packed, Wd_packed, Sgu_packed, Sd_packed, n_shared, F_shared, T, H, F,
+                                N, k, alpha, beta, enable, logits, topk_idx, topk_gate, topk_third, new_idx, new_gate,
+                                cnt_before, cnt_after, bin_hist, num_active, expert_offsets, perm, active_experts,
+                                num_active_perm, y, workspace, stream, stage_events, nullptr,
+                                lynx::RouterKind{gate_fn, n_group, topk_group});
 }
 
 extern "C" int lynx_moe_layer_fp8(const uint16_t *x_bf16, const float *Wr, const float *bias, const uint8_t *Wgu_q,

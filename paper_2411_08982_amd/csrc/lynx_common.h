@@ -142,6 +142,12 @@ __device__ __forceinline__ void wait_memory_complete() { __builtin_amdgcn_s_wait
 // Scales of quantised expert weights (all DEVICE), for the routed and the shared experts.  format 1 = FP8 E4M3: fp32
 // row scales, gate/up [N][2][F] and down [N][H].  format 2 = MXFP4: the block-scale exponents in the streaming layout
 // (dwords, passed through these pointers).  A null pointer to this struct means bf16 weights.
+// What kind of router the layer has.  gate_fn: 0 = softmax over the selected logits, 1 = selected sigmoid scores over
+// their sum.  n_group > 1: group-limited, a token may only use the experts of its topk_group best groups.
+struct RouterKind {
+    int gate_fn, n_group, topk_group;
+};
+
 struct FfnScales {
     const float *gu, *d, *shared_gu, *shared_d;
     int format;

@@ -250,6 +250,48 @@ __device__ __forceinline__ float token_max(const TokenLogits<NS> &t)
     return wave_max(m);
 }
 
+// Group-limited routers (the paper's Sec. 1 names expert grouping and gives no rule; the reading: groups of
+// N / n_group consecutive experts, group score = its largest logit, a token may only use the experts of its topk_group
+// best groups, equal group scores to the lower group).  Returns the token's logits with the other experts taken out:
+// value -inf (logits are finite, so -inf marks "not allowed" wherever a value travels between lanes) and no
+// candidate bit.  Wave-uniform control flow; every lane of the wave must call it.
+template <int NS>
+__device__ __forceinline__ TokenLogits<NS> limit_groups(const TokenLogits<NS> &raw, int N, const RouterKind &rk)
+{
+    if (rk.n_group <= 1 || rk.topk_group >= rk.n_group) return raw;
+    const int lane = lane_id();
+    const int gs = N / rk.n_group;
+    int grp[NS], key[NS];
+#pragma unroll
+    for (int i = 0; i < NS; ++i) {
+        const int e = lane + kWave * i;
+        grp[i] = ((raw.have >> i) & 1u) ? e / gs : -1;
+        key[i] = order_key(raw.v[i]);
+    }
+    const int none = order_key(-INFINITY);
+    float gscore[1] = {-INFINITY};   // lane g: score of group g
+    for (int g = 0; g < rk.n_group; ++g) {
+        int m = none;
+#pragma unroll
+        for (int i = 0; i < NS; ++i) m = (grp[i] == g) ? max(m, key[i]) : m;
+        const int best = wave_max_i32(m);
+        if (lane == g) gscore[0] = key_value(best);
+    }
+    unsigned long long chosen = 0ull;   // bit g: group g is one of the token's groups
+    wave_topk(gscore, lane < rk.n_group ? 1u : 0u, rk.topk_group, [&](int, int g, float) {
+        if (g != INT_MAX) chosen |= 1ull << g;
+    });
+    TokenLogits<NS> t;
+    t.have = 0;
+#pragma unroll
+    for (int i = 0; i < NS; ++i) {
+        const bool ok = grp[i] >= 0 && ((chosen >> grp[i]) & 1ull);
+        t.v[i] = ok ? raw.v[i] : -INFINITY;
+        t.have |= ok ? (1u << i) : 0u;
+    }
+    return t;
+}
+
 // Gates of a selection held one per lane (lane j < k: expert mye, logit myz): softmax over the selected
 // logits (paper Sec. 4: the weights are renormalised over the new selection), or, for a sigmoid-gated router
 // (gate_fn = 1; Sec. 3.2.1 names such routers), the selected sigmoid scores over their sum.  Returns this lane's
@@ -268,8 +310,10 @@ __device__ __forceinline__ float selection_gate(int k, int mye, float myz, int g
 
 // Softmax + top-k (Sec. 2.1): lane j < k returns the j-th pick in mye; writes idx / gate / psum (softmax: the
 // selected probability mass; sigmoid-gated: the sum of the selected scores).
+// tl = the experts the token may use, raw = all of them (the same unless the router is group-limited): the softmax
+// denominator runs over all.
 template <int NS>
-__device__ __forceinline__ int token_topk(const TokenLogits<NS> &tl, int t, int k, int gate_fn,
+__device__ __forceinline__ int token_topk(const TokenLogits<NS> &tl, const TokenLogits<NS> &raw, int t, int k, int gate_fn,
                                           int32_t *__restrict__ topk_idx, float *__restrict__ topk_gate,
                                           float *__restrict__ topk_psum)
 {
@@ -287,7 +331,7 @@ __device__ __forceinline__ int token_topk(const TokenLogits<NS> &tl, int t, int 
     float part = 0.f;
 #pragma unroll
     for (int i = 0; i < NS; ++i)
-        if ((tl.have >> i) & 1u) part += expf(tl.v[i] - zref);
+        if ((raw.have >> i) & 1u) part += expf(raw.v[i] - zref);
     const float den = wave_sum(part);
     if (lane < k) {
         topk_idx[(size_t)t * k + lane] = mye;
@@ -344,7 +388,7 @@ __device__ __forceinline__ void token_nominate(const TokenLogits<NS> &tl, int N,
         // every lane takes part in the lane exchange, also those past the last rank: a lane that sits out cannot
         // be read by the others, and the expert at this lane's rank may live in any lane
         const float zr = logit_of(tl, er[i]);
-        qr[i] = (r < N) ? bin_of(zmax, zr, alpha, beta) : INT_MAX;
+        qr[i] = (r < N && zr != -INFINITY) ? bin_of(zmax, zr, alpha, beta) : INT_MAX;   // -inf: not one of the token's groups
         if (r < N && inU[er[i]]) avail |= 1u << i;
     }
     // bins of the token's own picks, one per lane
@@ -427,6 +471,27 @@ __device__ __forceinline__ int token_remap(const TokenLogits<NS> &tl, int t, int
                 myz = zz;
             }
         });
+        // A group-limited token can find fewer than k members of the active set among its experts (without groups
+        // the active set holds at least k for everybody).  Then all of them were taken, and the slots left keep the
+        // token's own picks that are not in the active set, in rank order.
+        int slot = __popcll(__ballot(lane < k && mye >= 0));
+        if (slot < k) {
+            const int es = (lane < k) ? sel[lane] : -1;
+            const bool ok = es >= 0 && es < N;
+            const float zs = logit_of(tl, ok ? es : 0);
+            unsigned long long rest = __ballot(ok && !inA[ok ? es : 0]);
+            while (rest != 0ull && slot < k) {
+                const int src = __ffsll((long long)rest) - 1;
+                rest &= rest - 1ull;
+                const int e = __shfl(es, src, kWave);
+                const float zz = __shfl(zs, src, kWave);
+                if (lane == slot) {
+                    mye = e;
+                    myz = zz;
+                }
+                ++slot;
+            }
+        }
     }
     float num, zref;
     const float g = selection_gate(k, mye, myz, gate_fn, num, zref);
@@ -512,7 +577,7 @@ static_assert(kSmallT <= kSmallWaves && kSmallT <= 32, "one wave per token, one 
 // One workgroup, wave t owns token t and keeps its logits in registers from the first step to the last.
 template <int NS, bool DO_TOPK, bool DO_PERMUTE>
 __global__ __launch_bounds__(kSmallThreads) void routing_small_kernel(
-    const float *__restrict__ logits, int T, int N, int k, float alpha, int beta, int bypass, int gate_fn,
+    const float *__restrict__ logits, int T, int N, int k, float alpha, int beta, int bypass, RouterKind rk,
     int32_t *__restrict__ topk_idx, float *__restrict__ topk_gate, float *__restrict__ topk_psum,
     int32_t *__restrict__ new_idx, float *__restrict__ new_gate, int32_t *__restrict__ cnt_before,
     int32_t *__restrict__ cnt_after, int32_t *__restrict__ bin_hist, int32_t *__restrict__ num_active,
@@ -523,7 +588,7 @@ __global__ __launch_bounds__(kSmallThreads) void routing_small_kernel(
     const int tid = threadIdx.x, lane = lane_id(), t = wave_id();
     const bool has_token = t < T;
     // the token's logits (and, if given, its picks) are requested first; everything below overlaps the loads
-    TokenLogits<NS> tl = load_token<NS>(logits + (size_t)(has_token ? t : 0) * N, N);
+    const TokenLogits<NS> raw = load_token<NS>(logits + (size_t)(has_token ? t : 0) * N, N);
     int given = -1;
     if (!DO_TOPK && has_token && lane < k) given = topk_idx[(size_t)t * k + lane];
     for (int i = tid; i < N * beta; i += kSmallThreads) sh.hist[i] = 0;
@@ -536,12 +601,13 @@ __global__ __launch_bounds__(kSmallThreads) void routing_small_kernel(
     if (DO_PERMUTE)
         for (int p = tid; p < T * k; p += kSmallThreads) perm[p] = -1;
     if (tid == 0) sh.n_after = 0;
+    const TokenLogits<NS> tl = limit_groups(raw, N, rk);
     __syncthreads();
     // top-k (or the given picks), bins, histogram
     if (has_token) {
         int mye = -1;
         if (DO_TOPK) {
-            mye = token_topk(tl, t, k, gate_fn, topk_idx, topk_gate, topk_psum);
+            mye = token_topk(tl, raw, t, k, rk.gate_fn, topk_idx, topk_gate, topk_psum);
         } else if (lane < k) {
             mye = (given < 0 || given >= N) ? -1 : given;
         }
@@ -564,7 +630,7 @@ __global__ __launch_bounds__(kSmallThreads) void routing_small_kernel(
     }
     __syncthreads();
     if (has_token) {
-        const int mye = token_remap(tl, t, N, k, bypass != 0, gate_fn, sh.inA, sh.sel + t * k, new_idx, new_gate);
+        const int mye = token_remap(tl, t, N, k, bypass != 0, rk.gate_fn, sh.inA, sh.sel + t * k, new_idx, new_gate);
         if (lane < k) {
             sh.newsel[t * k + lane] = mye;
             if (mye >= 0) {
@@ -596,7 +662,7 @@ __global__ __launch_bounds__(kSmallThreads) void routing_small_kernel(
 // into the zeroed outputs).
 template <int NS, bool DO_TOPK, bool DO_BINS>
 __global__ __launch_bounds__(kTokThreads) void token_kernel(const float *__restrict__ logits, int T, int N, int k,
-                                                            float alpha, int beta, int gate_fn,
+                                                            float alpha, int beta, RouterKind rk,
                                                             int32_t *__restrict__ topk_idx,
                                                             float *__restrict__ topk_gate,
                                                             float *__restrict__ topk_psum,
@@ -613,10 +679,11 @@ __global__ __launch_bounds__(kTokThreads) void token_kernel(const float *__restr
     }
     const int t = blockIdx.x * kTokWaves + wave;
     if (t < T) {
-        const TokenLogits<NS> tl = load_token<NS>(logits + (size_t)t * N, N);
+        const TokenLogits<NS> raw = load_token<NS>(logits + (size_t)t * N, N);
+        const TokenLogits<NS> tl = limit_groups(raw, N, rk);
         int mye = -1;
         if (DO_TOPK) {
-            mye = token_topk(tl, t, k, gate_fn, topk_idx, topk_gate, topk_psum);
+            mye = token_topk(tl, raw, t, k, rk.gate_fn, topk_idx, topk_gate, topk_psum);
         } else if (lane < k) {
             mye = topk_idx[(size_t)t * k + lane];
             if (mye < 0 || mye >= N) mye = -1;
@@ -638,7 +705,8 @@ __global__ __launch_bounds__(kTokThreads) void nominate_kernel(const float *__re
                                                                const int32_t *__restrict__ topk_idx,
                                                                const int32_t *__restrict__ bin_hist,
                                                                const int32_t *__restrict__ cnt_before, int T, int N,
-                                                               int k, float alpha, int beta, int32_t *__restrict__ ws)
+                                                               int k, float alpha, int beta, RouterKind rk,
+                                                               int32_t *__restrict__ ws)
 {
     __shared__ unsigned long long score[LYNX_MAX_N];
     __shared__ int order[LYNX_MAX_N], inU[LYNX_MAX_N], inA[LYNX_MAX_N];
@@ -647,13 +715,14 @@ __global__ __launch_bounds__(kTokThreads) void nominate_kernel(const float *__re
     const int tid = threadIdx.x, lane = lane_id(), wave = wave_id();
     const int t = blockIdx.x * kTokWaves + wave;
     // the token's logits and picks are requested first; the score prologue overlaps the loads
-    const TokenLogits<NS> tl = load_token<NS>(logits + (size_t)(t < T ? t : 0) * N, N);
+    const TokenLogits<NS> raw = load_token<NS>(logits + (size_t)(t < T ? t : 0) * N, N);
     if (lane < k) sel[wave * k + lane] = (t < T) ? topk_idx[(size_t)t * k + lane] : -1;
     score_of(tid, N, T, beta, bin_hist, score);
     if (tid < N) {
         inU[tid] = cnt_before[tid] > 0;
         inA[tid] = 0;
     }
+    const TokenLogits<NS> tl = limit_groups(raw, N, rk);
     __syncthreads();
     rank_of(tid, N, T, beta, score, key, order);
     __syncthreads();
@@ -682,7 +751,7 @@ template <int NS, bool DO_PERMUTE>
 __global__ __launch_bounds__(kTokThreads) void remap_kernel(const float *__restrict__ logits,
                                                             const int32_t *__restrict__ topk_idx,
                                                             const int32_t *__restrict__ cnt_before, int T, int N, int k,
-                                                            int bypass, int gate_fn, int32_t *__restrict__ ws,
+                                                            int bypass, RouterKind rk, int32_t *__restrict__ ws,
                                                             int32_t *__restrict__ new_idx, float *__restrict__ new_gate,
                                                             int32_t *__restrict__ cnt_after,
                                                             int32_t *__restrict__ num_active,
@@ -697,7 +766,7 @@ __global__ __launch_bounds__(kTokThreads) void remap_kernel(const float *__restr
     const int W = (T + 31) / 32;
     const int t = blockIdx.x * kTokWaves + wave;
     // the token's logits and picks are requested first; the prologue overlaps the loads
-    const TokenLogits<NS> tl = load_token<NS>(logits + (size_t)(t < T ? t : 0) * N, N);
+    const TokenLogits<NS> raw = load_token<NS>(logits + (size_t)(t < T ? t : 0) * N, N);
     if (lane < k) sel[wave * k + lane] = (t < T) ? topk_idx[(size_t)t * k + lane] : -1;
     if (tid < N) {
         sh.inA[tid] = bypass ? 0 : ws[kWsActive + tid];
@@ -706,6 +775,7 @@ __global__ __launch_bounds__(kTokThreads) void remap_kernel(const float *__restr
         sh.cnta[tid] = 0;
     }
     if (tid == 0) sh.n_after = 0;
+    const TokenLogits<NS> tl = limit_groups(raw, N, rk);
     if (DO_PERMUTE) {   // pairs whose expert is invalid stay unassigned
         const int p0 = blockIdx.x * kTokWaves * k, p1 = min(T * k, p0 + kTokWaves * k);
         for (int p = p0 + tid; p < p1; p += kTokThreads) store_coherent(&perm[p], -1);   // overwritten by the last workgroup
@@ -717,7 +787,7 @@ __global__ __launch_bounds__(kTokThreads) void remap_kernel(const float *__restr
     }
     __syncthreads();
     if (t < T) {
-        const int mye = token_remap(tl, t, N, k, bypass != 0, gate_fn, sh.inA, sel + wave * k, new_idx, new_gate);
+        const int mye = token_remap(tl, t, N, k, bypass != 0, rk.gate_fn, sh.inA, sel + wave * k, new_idx, new_gate);
         if (lane < k && mye >= 0) {
             atomicAdd(&sh.cnta[mye], 1);
             if (DO_PERMUTE) atomicOr(reinterpret_cast<unsigned *>(ws + kWsMember) + mye * W + (t >> 5), 1u << (t & 31));
@@ -859,6 +929,19 @@ static int check_bin_params(const char *who, int T, float alpha, int beta)
     return LYNX_OK;
 }
 
+int check_router_kind(const char *who, int N, int k, const RouterKind &rk)
+{
+    if (rk.gate_fn != kGateSoftmax && rk.gate_fn != kGateSigmoid)
+        return fail(LYNX_ERR_INVALID_ARG, "%s: gate_fn must be 0 (softmax) or 1 (sigmoid), got %d", who, rk.gate_fn);
+    if (rk.n_group < 1 || rk.topk_group < 1 || rk.topk_group > rk.n_group || (N % rk.n_group) != 0)
+        return fail(LYNX_ERR_INVALID_ARG, "%s: need 1 <= topk_group <= n_group and n_group dividing N (N=%d n_group=%d topk_group=%d)",
+                    who, N, rk.n_group, rk.topk_group);
+    if ((long long)rk.topk_group * (N / rk.n_group) < k)
+        return fail(LYNX_ERR_INVALID_ARG, "%s: topk_group groups of %d experts hold fewer than k=%d", who, N / rk.n_group, k);
+    if (rk.n_group > kWave) return fail(LYNX_ERR_UNSUPPORTED, "%s: n_group <= %d (n_group=%d)", who, kWave, rk.n_group);
+    return LYNX_OK;
+}
+
 static void add_zero(ZeroList &z, int32_t *p, int count)
 {
     z.ptr[z.n] = p;
@@ -882,7 +965,7 @@ static void launch_logits(const uint16_t *x, const float *Wr, const float *bias,
 // with a launch of their own, false = the caller already had them cleared (by the logits kernel).
 template <int NS, bool DO_TOPK, bool DO_PERMUTE>
 static int launch_after_logits_ns(const char *who, const float *logits, int T, int N, int k, float alpha, int beta,
-                               int enable, int gate_fn, int32_t *topk_idx, float *topk_gate, float *topk_psum, int32_t *new_idx,
+                               int enable, RouterKind rk, int32_t *topk_idx, float *topk_gate, float *topk_psum, int32_t *new_idx,
                                float *new_gate, int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist,
                                int32_t *num_active, int32_t *expert_offsets, int32_t *perm, int32_t *active_experts,
                                int32_t *num_active_perm, int32_t *ws, bool clear_first, hipStream_t st)
@@ -890,7 +973,7 @@ static int launch_after_logits_ns(const char *who, const float *logits, int T, i
     const int bypass = (!enable || T <= 1) ? 1 : 0;
     if (T <= kSmallT) {
         hipLaunchKernelGGL((routing_small_kernel<NS, DO_TOPK, DO_PERMUTE>), dim3(1), dim3(kSmallThreads), 0, st, logits, T, N, k,
-                           alpha, beta, bypass, gate_fn, topk_idx, topk_gate, topk_psum, new_idx, new_gate, cnt_before, cnt_after,
+                           alpha, beta, bypass, rk, topk_idx, topk_gate, topk_psum, new_idx, new_gate, cnt_before, cnt_after,
                            bin_hist, num_active, expert_offsets, perm, active_experts, num_active_perm);
         return check_launch(who);
     }
@@ -909,30 +992,30 @@ static int launch_after_logits_ns(const char *who, const float *logits, int T, i
         if (rc != LYNX_OK) return rc;
     }
     const dim3 tgrid((T + kTokWaves - 1) / kTokWaves), tblock(kTokThreads);
-    hipLaunchKernelGGL((token_kernel<NS, DO_TOPK, true>), tgrid, tblock, 0, st, logits, T, N, k, alpha, beta, gate_fn, topk_idx,
+    hipLaunchKernelGGL((token_kernel<NS, DO_TOPK, true>), tgrid, tblock, 0, st, logits, T, N, k, alpha, beta, rk, topk_idx,
                        topk_gate, topk_psum, bin_hist, cnt_before);
     rc = check_launch(who);
     if (rc != LYNX_OK) return rc;
     if (!bypass) {
         hipLaunchKernelGGL((nominate_kernel<NS>), tgrid, tblock, 0, st, logits, topk_idx, bin_hist, cnt_before, T, N, k, alpha,
-                           beta, ws);
+                           beta, rk, ws);
         rc = check_launch(who);
         if (rc != LYNX_OK) return rc;
     }
-    hipLaunchKernelGGL((remap_kernel<NS, DO_PERMUTE>), tgrid, tblock, 0, st, logits, topk_idx, cnt_before, T, N, k, bypass, gate_fn, ws,
+    hipLaunchKernelGGL((remap_kernel<NS, DO_PERMUTE>), tgrid, tblock, 0, st, logits, topk_idx, cnt_before, T, N, k, bypass, rk, ws,
                        new_idx, new_gate, cnt_after, num_active, expert_offsets, perm, active_experts, num_active_perm);
     return check_launch(who);
 }
 
 template <bool DO_TOPK, bool DO_PERMUTE>
 static int launch_after_logits(const char *who, const float *logits, int T, int N, int k, float alpha, int beta,
-                               int enable, int gate_fn, int32_t *topk_idx, float *topk_gate, float *topk_psum, int32_t *new_idx,
+                               int enable, RouterKind rk, int32_t *topk_idx, float *topk_gate, float *topk_psum, int32_t *new_idx,
                                float *new_gate, int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist,
                                int32_t *num_active, int32_t *expert_offsets, int32_t *perm, int32_t *active_experts,
                                int32_t *num_active_perm, int32_t *ws, bool clear_first, hipStream_t st)
 {
 #define LYNX_ROUTING_ARGS                                                                                             \
-    who, logits, T, N, k, alpha, beta, enable, gate_fn, topk_idx, topk_gate, topk_psum, new_idx, new_gate, cnt_before, cnt_after, \
+    who, logits, T, N, k, alpha, beta, enable, rk, topk_idx, topk_gate, topk_psum, new_idx, new_gate, cnt_before, cnt_after, \
         bin_hist, num_active, expert_offsets, perm, active_experts, num_active_perm, ws, clear_first, st
     if (N <= kWave) return launch_after_logits_ns<1, DO_TOPK, DO_PERMUTE>(LYNX_ROUTING_ARGS);
     if (N <= 2 * kWave) return launch_after_logits_ns<2, DO_TOPK, DO_PERMUTE>(LYNX_ROUTING_ARGS);
@@ -942,7 +1025,7 @@ static int launch_after_logits(const char *who, const float *logits, int T, int 
 
 // The whole routing side of lynx_moe_layer: two launches for T <= kSmallT, four otherwise.  T >= 1, arguments checked.
 int routing_fused(const uint16_t *x, const float *Wr, const float *bias, int T, int H, int N, int k, float alpha,
-                  int beta, int enable, int gate_fn, float *logits, int32_t *topk_idx, float *topk_gate, float *topk_psum,
+                  int beta, int enable, RouterKind rk, float *logits, int32_t *topk_idx, float *topk_gate, float *topk_psum,
                   int32_t *new_idx, float *new_gate, int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist,
                   int32_t *num_active, int32_t *expert_offsets, int32_t *perm, int32_t *active_experts,
                   int32_t *num_active_perm, void *workspace, hipStream_t st)
@@ -962,7 +1045,7 @@ int routing_fused(const uint16_t *x, const float *Wr, const float *bias, int T, 
     launch_logits(x, Wr, bias, T, H, N, logits, z, st);
     int rc = check_launch("lynx_moe_layer(logits)");
     if (rc != LYNX_OK) return rc;
-    return launch_after_logits<true, true>("lynx_moe_layer(routing)", logits, T, N, k, alpha, beta, enable, gate_fn, topk_idx,
+    return launch_after_logits<true, true>("lynx_moe_layer(routing)", logits, T, N, k, alpha, beta, enable, rk, topk_idx,
                                            topk_gate, topk_psum, new_idx, new_gate, cnt_before, cnt_after, bin_hist,
                                            num_active, expert_offsets, perm, active_experts, num_active_perm, ws, false, st);
 }
@@ -1004,7 +1087,8 @@ extern "C" int lynx_affinity_bin_biased(const float *logits, const int32_t *topk
 #define LYNX_BIASED(NS)                                                                                                 \
     do {                                                                                                                \
         hipLaunchKernelGGL((token_kernel<NS, false, true>), tgrid, tblock, 0, st, logits, T, N, k, alpha, beta,         \
-                           kGateSoftmax, const_cast<int32_t *>(topk_idx), nullptr, nullptr, bin_hist, cnt_before);      \
+                           RouterKind{kGateSoftmax, 1, 1}, const_cast<int32_t *>(topk_idx), nullptr, nullptr, bin_hist, \
+                           cnt_before);                                                                                 \
         rc = check_launch("lynx_affinity_bin_biased(bins)");                                                            \
         if (rc != LYNX_OK) return rc;                                                                                   \
         hipLaunchKernelGGL((biased_remap_kernel<NS>), tgrid, tblock, 0, st, logits, topk_idx, cnt_before, bin_hist, T,  \
@@ -1020,11 +1104,13 @@ extern "C" int lynx_affinity_bin_biased(const float *logits, const int32_t *topk
     return check_launch("lynx_affinity_bin_biased(select)");
 }
 
-static int route_impl(const uint16_t *x_bf16, const float *Wr, const float *bias, int T, int H, int N, int k, int gate_fn,
-                      float *logits, int32_t *topk_idx, float *topk_gate, float *topk_psum, void *stream)
+static int route_impl(const uint16_t *x_bf16, const float *Wr, const float *bias, int T, int H, int N, int k,
+                      lynx::RouterKind rk, float *logits, int32_t *topk_idx, float *topk_gate, float *topk_psum, void *stream)
 {
     using namespace lynx;
     int rc = check_routing_sizes("lynx_route", T, N, k);
+    if (rc != LYNX_OK) return rc;
+    rc = check_router_kind("lynx_route", N, k, rk);
     if (rc != LYNX_OK) return rc;
     if (H <= 0) return fail(LYNX_ERR_INVALID_ARG, "lynx_route: H must be positive");
     if ((H % 32) != 0) return fail(LYNX_ERR_UNSUPPORTED, "lynx_route: H must be a multiple of 32 (H=%d)", H);
@@ -1039,13 +1125,13 @@ static int route_impl(const uint16_t *x_bf16, const float *Wr, const float *bias
     if (rc != LYNX_OK) return rc;
     const dim3 tgrid((T + kTokWaves - 1) / kTokWaves), tblock(kTokThreads);
     if (N <= kWave)
-        hipLaunchKernelGGL((token_kernel<1, true, false>), tgrid, tblock, 0, st, logits, T, N, k, 0.f, 1, gate_fn, topk_idx,
+        hipLaunchKernelGGL((token_kernel<1, true, false>), tgrid, tblock, 0, st, logits, T, N, k, 0.f, 1, rk, topk_idx,
                            topk_gate, topk_psum, nullptr, nullptr);
     else if (N <= 2 * kWave)
-        hipLaunchKernelGGL((token_kernel<2, true, false>), tgrid, tblock, 0, st, logits, T, N, k, 0.f, 1, gate_fn, topk_idx,
+        hipLaunchKernelGGL((token_kernel<2, true, false>), tgrid, tblock, 0, st, logits, T, N, k, 0.f, 1, rk, topk_idx,
                            topk_gate, topk_psum, nullptr, nullptr);
     else
-        hipLaunchKernelGGL((token_kernel<4, true, false>), tgrid, tblock, 0, st, logits, T, N, k, 0.f, 1, gate_fn, topk_idx,
+        hipLaunchKernelGGL((token_kernel<4, true, false>), tgrid, tblock, 0, st, logits, T, N, k, 0.f, 1, rk, topk_idx,
                            topk_gate, topk_psum, nullptr, nullptr);
     return check_launch("lynx_route(top-k)");
 }
@@ -1053,13 +1139,23 @@ static int route_impl(const uint16_t *x_bf16, const float *Wr, const float *bias
 extern "C" int lynx_route(const uint16_t *x_bf16, const float *Wr, const float *bias, int T, int H, int N, int k,
                           float *logits, int32_t *topk_idx, float *topk_gate, float *topk_psum, void *stream)
 {
-    return route_impl(x_bf16, Wr, bias, T, H, N, k, lynx::kGateSoftmax, logits, topk_idx, topk_gate, topk_psum, stream);
+    return route_impl(x_bf16, Wr, bias, T, H, N, k, lynx::RouterKind{lynx::kGateSoftmax, 1, 1}, logits, topk_idx, topk_gate,
+                      topk_psum, stream);
 }
 
 extern "C" int lynx_route_sigmoid(const uint16_t *x_bf16, const float *Wr, const float *bias, int T, int H, int N, int k,
                                   float *logits, int32_t *topk_idx, float *topk_gate, float *topk_ssum, void *stream)
 {
-    return route_impl(x_bf16, Wr, bias, T, H, N, k, lynx::kGateSigmoid, logits, topk_idx, topk_gate, topk_ssum, stream);
+    return route_impl(x_bf16, Wr, bias, T, H, N, k, lynx::RouterKind{lynx::kGateSigmoid, 1, 1}, logits, topk_idx, topk_gate,
+                      topk_ssum, stream);
+}
+
+extern "C" int lynx_route_grouped(const uint16_t *x_bf16, const float *Wr, const float *bias, int T, int H, int N, int k,
+                                  int n_group, int topk_group, int gate_fn, float *logits, int32_t *topk_idx,
+                                  float *topk_gate, float *topk_third, void *stream)
+{
+    return route_impl(x_bf16, Wr, bias, T, H, N, k, lynx::RouterKind{gate_fn, n_group, topk_group}, logits, topk_idx,
+                      topk_gate, topk_third, stream);
 }
 
 static int affinity_bin_impl(const float *logits, const int32_t *topk_idx, int T, int N, int k, float alpha, int beta,
@@ -1087,7 +1183,8 @@ static int affinity_bin_impl(const float *logits, const int32_t *topk_idx, int T
         hipLaunchKernelGGL(zero_kernel, dim3(1), dim3(256), 0, st, z);
         return check_launch("lynx_affinity_bin(clear)");
     }
-    return launch_after_logits<false, false>("lynx_affinity_bin", logits, T, N, k, alpha, beta, enable, gate_fn,
+    return launch_after_logits<false, false>("lynx_affinity_bin", logits, T, N, k, alpha, beta, enable,
+                                             RouterKind{gate_fn, 1, 1},
                                              const_cast<int32_t *>(topk_idx), nullptr, nullptr, new_idx, new_gate,
                                              cnt_before, cnt_after, bin_hist, num_active, nullptr, nullptr, nullptr,
                                              nullptr, ws, true, st);
@@ -1109,4 +1206,39 @@ extern "C" int lynx_affinity_bin_sigmoid(const float *logits, const int32_t *top
 {
     return affinity_bin_impl(logits, topk_idx, T, N, k, alpha, beta, enable, lynx::kGateSigmoid, new_idx, new_gate,
                              cnt_before, cnt_after, bin_hist, num_active, workspace, stream);
+}
+
+extern "C" int lynx_affinity_bin_grouped(const float *logits, int T, int N, int k, int n_group, int topk_group, int gate_fn,
+                                         float alpha, int beta, int enable, int32_t *topk_idx, float *topk_gate,
+                                         float *topk_third, int32_t *new_idx, float *new_gate, int32_t *cnt_before,
+                                         int32_t *cnt_after, int32_t *bin_hist, int32_t *num_active, void *workspace,
+                                         void *stream)
+{
+    using namespace lynx;
+    const RouterKind rk = {gate_fn, n_group, topk_group};
+    int rc = check_routing_sizes("lynx_affinity_bin_grouped", T, N, k);
+    if (rc != LYNX_OK) return rc;
+    rc = check_router_kind("lynx_affinity_bin_grouped", N, k, rk);
+    if (rc != LYNX_OK) return rc;
+    rc = check_bin_params("lynx_affinity_bin_grouped", T, alpha, beta);
+    if (rc != LYNX_OK) return rc;
+    if (!cnt_before || !cnt_after || !bin_hist || !num_active || !workspace)
+        return fail(LYNX_ERR_INVALID_ARG, "lynx_affinity_bin_grouped: null output or workspace pointer");
+    if (T > 0 && (!logits || !topk_idx || !topk_gate || !topk_third || !new_idx || !new_gate))
+        return fail(LYNX_ERR_INVALID_ARG, "lynx_affinity_bin_grouped: null pointer");
+    hipStream_t st = (hipStream_t)stream;
+    if (T == 0) {
+        ZeroList z;
+        z.n = 0;
+        add_zero(z, bin_hist, N * beta);
+        add_zero(z, cnt_before, N);
+        add_zero(z, cnt_after, N);
+        add_zero(z, num_active, 2);
+        hipLaunchKernelGGL(zero_kernel, dim3(1), dim3(256), 0, st, z);
+        return check_launch("lynx_affinity_bin_grouped(clear)");
+    }
+    return launch_after_logits<true, false>("lynx_affinity_bin_grouped", logits, T, N, k, alpha, beta, enable, rk, topk_idx,
+                                            topk_gate, topk_third, new_idx, new_gate, cnt_before, cnt_after, bin_hist,
+                                            num_active, nullptr, nullptr, nullptr, nullptr,
+                                            reinterpret_cast<int32_t *>(workspace), true, st);
 }

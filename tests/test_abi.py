@@ -20,7 +20,7 @@ def _declared():
 def test_library_exports_every_declared_symbol():
     lib = L.lib()
     names = _declared()
-    assert set(names) == set(L.SYMBOLS) and len(names) == 23
+    assert set(names) == set(L.SYMBOLS) and len(names) == 26
     for n in names:
         assert getattr(lib, n) is not None
 
