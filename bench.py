@@ -39,6 +39,10 @@ def parse():
                     help="gate function of the router; sigmoid: the layer runs through lynx_moe_layer_sigmoid (the "
                          "quantised-weight variants, the score-biased variant and the CPU baseline, which are "
                          "softmax-gated, are then left out)")
+    ap.add_argument("--groups", default="", metavar="G,TG",
+                    help="group-limited router: G groups of consecutive experts, a token uses the experts of its TG "
+                         "best groups; the layer runs through lynx_moe_layer_grouped (with --router's gate function; "
+                         "the same variants are left out as for --router sigmoid)")
     ap.add_argument("--tokens", type=int, default=8)
     ap.add_argument("--preset", default="aggressive", choices=["moderate", "aggressive", "off"])
     ap.add_argument("--no-sweep", action="store_true")
@@ -80,6 +84,7 @@ class Layer:
         self.weights = []          # per resident layer: packed routed gate/up, down, shared gate/up, down
         self.calls = 0
         self.sigmoid_router = False
+        self.groups = None   # (n_group, topk_group) for a group-limited router
         for l in range(n_layers):
             d = wl.make_layer_device(cfg, T_gen if l == 0 else 1, "cuda", layer=l)
             Wgu, Wdp = L.lynx_pack_weights(d["Wg"], d["Wu"], d["Wd"])
@@ -119,6 +124,10 @@ class Layer:
         Wgu, Wdp, Sgu, Sdp = self.weights[layer]
         if sigmoid is None:
             sigmoid = self.sigmoid_router
+        if self.groups is not None:
+            return self.L.lynx_moe_layer_grouped(self.tokens(T), self.Wr, self.bias, Wgu, Wdp, c.F, c.k, self.groups[0],
+                                                 self.groups[1], alpha, beta, int(bool(sigmoid)), enable, Sgu, Sdp, c.n_shared,
+                                                 c.F_shared, buffers=self.buffers(T, beta), stage_events=events)
         entry = self.L.lynx_moe_layer_sigmoid if sigmoid else self.L.lynx_moe_layer
         return entry(self.tokens(T), self.Wr, self.bias, Wgu, Wdp, c.F, c.k, alpha, beta, enable, Sgu, Sdp, c.n_shared,
                      c.F_shared, buffers=self.buffers(T, beta), stage_events=events)
@@ -261,13 +270,15 @@ def main():
         run_stack(args, cfg, wl, torch)
         return
     T = args.tokens
-    if args.router == "sigmoid":
+    if args.router == "sigmoid" or args.groups:
         args.no_fp8, args.no_cpu_baseline, args.biased_gamma = True, True, 0.0
     alpha, beta, enable = preset_args(wl, args.preset)
     routed_bytes = 3 * cfg.N * cfg.H * cfg.F * 2
     n_layers = args.layers if args.layers > 0 else max(1, min(8, -(-(4 << 30) // routed_bytes)))
     layer = Layer(cfg, T, keep_row_major=not args.no_cpu_baseline, n_layers=n_layers)
     layer.sigmoid_router = args.router == "sigmoid"
+    if args.groups:
+        layer.groups = tuple(int(v) for v in args.groups.split(","))
 
     if args.pmc_calibration:
         a = torch.ones(1 << 28, dtype=torch.float32, device="cuda")   # 1 GiB
@@ -346,7 +357,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{cfg.name}-shaped MoE layer: hidden {cfg.H}, FFN {cfg.F}, {cfg.N} experts top-{cfg.k}, "
                                f"{cfg.n_shared} shared, bf16 weights, {T} decode tokens, remap {args.preset}"
-                               + (", sigmoid-gated router" if args.router == "sigmoid" else ""),
+                               + (", sigmoid-gated router" if args.router == "sigmoid" else "")
+                               + (f", group-limited router ({layer.groups[1]} of {layer.groups[0]} groups)" if layer.groups else ""),
                    "tokens": T, "alpha": alpha, "beta": beta, "remap": bool(enable), "resident_layers": n_layers},
         "tokens_per_s": round(T / (ms_per_step * 1e-3), 1),
         "experts_invoked": {"before": n_before, "after": n_after},
@@ -419,7 +431,7 @@ def main():
                             "invoked_before": nb, "invoked_after": na})
             out["sweep_score_biased_variant"] = var
 
-    if not args.no_sweep:
+    if not args.no_sweep and not args.groups:
         # The same workload behind a sigmoid-gated router (gates = selected sigmoid scores over their sum; bins,
         # scores and the remap are the softmax path's): a widening, reported beside the metric above.
         for _ in range(3):

@@ -259,3 +259,51 @@ def test_affinity_bin_random(L, block):
         pr = oracle.permute(ref["new_idx"], N)
         for key in ("offsets", "perm", "active", "num_active"):
             assert np.array_equal(host(p[key]), pr[key]), key
+
+
+def grouped_case(L, i):
+    """One random group-limited case: sizes, groups, gate function, bin parameters and logit structure all drawn."""
+    rng = np.random.default_rng([71, 82, i])
+    G = int(rng.choice([1, 2, 3, 4, 8, 16, 64])) if rng.random() < 0.7 else int(rng.integers(1, 65))
+    gs = int(rng.integers(1, 256 // G + 1))
+    N = G * gs
+    tg = int(rng.integers(1, G + 1))
+    k = int(rng.integers(1, min(tg * gs, 16) + 1))
+    T = int(rng.integers(1, 1025)) if rng.random() < 0.2 else int(rng.integers(1, 100))
+    alpha = float(rng.choice([0.0, 0.25, 0.5, 1.0, 2.0, 4.0, 8.0, 1e6]))
+    beta = int(rng.integers(1, 7))
+    while float(T) ** beta >= 2.0 ** 62:
+        beta -= 1
+    quantum = [None, 0.25, 1.0][int(rng.integers(0, 3))]
+    gate_fn = int(rng.integers(0, 2))
+    enable = int(rng.random() < 0.9)
+    print(f"random grouped {i}: T={T} N={N} k={k} G={G} tg={tg} alpha={alpha} beta={beta} quantum={quantum} "
+          f"gate_fn={gate_fn} enable={enable}", flush=True)
+    z = wl.make_logits(T, N, seed=9000 + i, zipf_s=float(rng.choice([0.0, 1.0, 1.5])),
+                       tail_frac=float(rng.choice([0.0, 0.1])), quantum=quantum)
+    I, F = torch.int32, torch.float32
+
+    def poisoned(shape, dtype):
+        t = torch.empty(shape, dtype=dtype, device="cuda")
+        t.view(torch.uint8).fill_(0xFF)
+        return t
+    o = dict(idx=poisoned((T, k), I), gate=poisoned((T, k), F), psum=poisoned((T,), F), new_idx=poisoned((T, k), I),
+             new_gate=poisoned((T, k), F), cnt_before=poisoned((N,), I), cnt_after=poisoned((N,), I),
+             bin_hist=poisoned((N, beta), I), num_active=poisoned((2,), I))
+    ws = torch.full((65536,), 0xFF, dtype=torch.uint8, device="cuda")
+    out = L.lynx_affinity_bin_grouped(dev(z), k, G, tg, alpha, beta, gate_fn, enable, ws, o)
+    torch.cuda.synchronize()
+    tk = oracle.topk_grouped(z, k, G, tg, gate_fn)
+    assert np.array_equal(host(out["idx"]), tk["idx"])
+    np.testing.assert_allclose(host(out["gate"]), tk["gate"], rtol=GATE_TOL, atol=1e-7)
+    np.testing.assert_allclose(host(out["psum"]), tk["third"], rtol=GATE_TOL, atol=1e-7)
+    ref = oracle.affinity_bin_grouped(z, tk["idx"], G, tg, alpha, beta, enable, gate_fn)
+    for key in ("new_idx", "cnt_before", "cnt_after", "bin_hist", "num_active"):
+        assert np.array_equal(host(out[key]), ref[key]), key
+    np.testing.assert_allclose(host(out["new_gate"]), ref["new_gate"], rtol=GATE_TOL, atol=1e-7)
+
+
+@pytest.mark.parametrize("block", range(3))
+def test_affinity_bin_grouped_random(L, block):
+    for i in range(block * 40, block * 40 + 40):
+        grouped_case(L, i)
