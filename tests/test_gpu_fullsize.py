@@ -60,24 +60,37 @@ def _layer(L, name):
     return _layers[name]
 
 
-def _check_layer(L, lay, T, alpha, beta, enable, n_sample=5, seed=0, sigmoid=False):
+def _check_layer(L, lay, T, alpha, beta, enable, n_sample=5, seed=0, sigmoid=False, groups=None):
     cfg, d = lay.cfg, lay.d
     xb = lay.tokens(T)
     x = to_bf16_dev(xb)
-    entry = L.lynx_moe_layer_sigmoid if sigmoid else L.lynx_moe_layer
-    b = entry(x, d["Wr"], d["bias"], lay.Wgu, lay.Wdp, cfg.F, cfg.k, alpha, beta, enable, lay.Sgu, lay.Sdp,
-              cfg.n_shared, cfg.F_shared)
+    if groups:
+        b = L.lynx_moe_layer_grouped(x, d["Wr"], d["bias"], lay.Wgu, lay.Wdp, cfg.F, cfg.k, groups[0], groups[1], alpha, beta,
+                                     int(sigmoid), enable, lay.Sgu, lay.Sdp, cfg.n_shared, cfg.F_shared)
+    else:
+        entry = L.lynx_moe_layer_sigmoid if sigmoid else L.lynx_moe_layer
+        b = entry(x, d["Wr"], d["bias"], lay.Wgu, lay.Wdp, cfg.F, cfg.k, alpha, beta, enable, lay.Sgu, lay.Sdp,
+                  cfg.n_shared, cfg.F_shared)
     torch.cuda.synchronize()
     Wr, bias = host(d["Wr"]), host(d["bias"])
     # routing, whole batch
     r = oracle.route(xb, Wr, bias, cfg.k)
     z = host(b.logits)
     assert np.all(np.abs(z - r["logits"]) <= LOGIT_TOL * np.maximum(1.0, np.abs(r["logits"])))
-    tk = (oracle.topk_sigmoid if sigmoid else oracle.topk)(z, cfg.k)
+    if groups:
+        tk = oracle.topk_grouped(z, cfg.k, groups[0], groups[1], int(sigmoid))
+        third = tk["third"]
+    else:
+        tk = (oracle.topk_sigmoid if sigmoid else oracle.topk)(z, cfg.k)
+        third = tk["ssum" if sigmoid else "psum"]
     assert np.array_equal(host(b.topk_idx), tk["idx"])
     np.testing.assert_allclose(host(b.topk_gate), tk["gate"], rtol=GATE_TOL, atol=1e-7)
-    np.testing.assert_allclose(host(b.topk_psum), tk["ssum" if sigmoid else "psum"], rtol=GATE_TOL, atol=1e-7)
-    a = (oracle.affinity_bin_sigmoid if sigmoid else oracle.affinity_bin)(z, tk["idx"], alpha, beta, enable)
+    np.testing.assert_allclose(host(b.topk_psum), third, rtol=GATE_TOL, atol=1e-7)
+    if groups:
+        a = oracle.affinity_bin_grouped(z, tk["idx"], groups[0], groups[1], alpha, beta, enable, int(sigmoid))
+        assert np.take_along_axis(oracle.group_allowed(z, groups[0], groups[1]), a["new_idx"], 1).all()
+    else:
+        a = (oracle.affinity_bin_sigmoid if sigmoid else oracle.affinity_bin)(z, tk["idx"], alpha, beta, enable)
     for key, got in (("new_idx", b.new_idx), ("cnt_before", b.cnt_before), ("cnt_after", b.cnt_after),
                      ("bin_hist", b.bin_hist), ("num_active", b.num_active)):
         assert np.array_equal(host(got), a[key]), key
@@ -129,14 +142,15 @@ def test_full_size_layer(L, name, T, preset):
     print(f"  invoked {na.tolist()}, max sampled row err {err:.3e}", flush=True)
 
 
-@pytest.mark.parametrize("T,preset", [(8, "aggressive"), (64, "moderate")])
-def test_full_size_layer_sigmoid_router(L, T, preset):
-    """A DeepSeek-V3-shaped layer (256 experts of 88 MB, top-8, one shared expert) behind the sigmoid-gated router:
-    routing of the whole batch against the oracle, sampled tokens' outputs against the oracle's FFN."""
-    print(f"full-size layer dsv3 T={T} remap={preset}, sigmoid-gated router", flush=True)
+@pytest.mark.parametrize("T,preset,groups", [(8, "aggressive", None), (64, "moderate", None), (32, "moderate", (8, 4))])
+def test_full_size_layer_sigmoid_router(L, T, preset, groups):
+    """A DeepSeek-V3-shaped layer (256 experts of 88 MB, top-8, one shared expert) behind the sigmoid-gated router,
+    without and with the group limit (4 of 8 groups): routing of the whole batch against the oracle, sampled tokens'
+    outputs against the oracle's FFN."""
+    print(f"full-size layer dsv3 T={T} remap={preset}, sigmoid-gated router, groups={groups}", flush=True)
     lay = _layer(L, "dsv3")
     alpha, beta = wl.PRESETS[preset]
-    na, err = _check_layer(L, lay, T, alpha, beta, 1, n_sample=2, sigmoid=True)
+    na, err = _check_layer(L, lay, T, alpha, beta, 1, n_sample=2, sigmoid=True, groups=groups)
     print(f"  invoked {na.tolist()}, max sampled row err {err:.3e}", flush=True)
     _layers.clear()              # 45 GB of row-major and packed weights: release them before the next test
     torch.cuda.empty_cache()
