@@ -83,33 +83,40 @@ __device__ __forceinline__ int bin_of(float zmax, float z, float alpha, int beta
     return (qf >= (float)beta) ? beta : (int)qf;
 }
 
+// Writes a value into one lane of a per-lane variable, as a select (no branch).
+__device__ __forceinline__ void put_lane(int &var, int lane, int value) { var = (lane_id() == lane) ? value : var; }
+__device__ __forceinline__ void put_lane(float &var, int lane, float value) { var = (lane_id() == lane) ? value : var; }
+
 // The wave holds one token's logits: lane l, slot i <-> expert l + 64*i.  Picks the k largest among
 // the candidate slots (bit i of `cand`), descending, equal values to the lower expert index, and calls
-// emit(j, expert, value) on every lane with the j-th winner (expert = INT_MAX when none is left).
+// emit(j, expert, value) on every lane with the j-th winner, both wave-uniform (expert = INT_MAX when none is left).
 // Per pick: one DPP max reduction, then the lowest-indexed holder of that maximum by ballot + find-first
-// (slot 0 holds the lower experts, so the first slot with a match wins).  Values are finite.
+// (slot 0 holds the lower experts, so the first slot with a match wins).  Values are finite: the key of -inf marks
+// the entries that are no candidates or already taken.  A pick is a chain of dependent instructions that a lone
+// wave issues at one per 8-12 cycles (measured), so the loop body is kept short: 34 instructions for two slots.
 template <int NS, typename Emit>
 __device__ __forceinline__ void wave_topk(const float (&v)[NS], unsigned cand, int k, Emit &&emit)
 {
     const int lane = lane_id();
     // the k wave-wide maxima are taken on order-preserving integer keys: see wave_max_i32
+    const int none = order_key(-INFINITY);
     int key[NS];
 #pragma unroll
-    for (int i = 0; i < NS; ++i) key[i] = order_key(v[i]);
-    const int none = order_key(-INFINITY);
+    for (int i = 0; i < NS; ++i) key[i] = ((cand >> i) & 1u) ? order_key(v[i]) : none;
     for (int j = 0; j < k; ++j) {
-        int m = none;
+        int m = key[0];
 #pragma unroll
-        for (int i = 0; i < NS; ++i)
-            if ((cand >> i) & 1u) m = max(m, key[i]);
+        for (int i = 1; i < NS; ++i) m = max(m, key[i]);
         const int best = wave_max_i32(m);
         int e = INT_MAX;
 #pragma unroll
-        for (int i = 0; i < NS; ++i) {
-            const unsigned long long b = __ballot(((cand >> i) & 1u) && key[i] == best);
-            if (e == INT_MAX && b != 0ull) e = __ffsll((long long)b) - 1 + kWave * i;
+        for (int i = NS - 1; i >= 0; --i) {   // descending: the last slot to report is the lowest
+            const unsigned long long b = __ballot(key[i] == best);
+            if (b != 0ull) e = __ffsll((long long)b) - 1 + kWave * i;
         }
-        if (e != INT_MAX && (e & (kWave - 1)) == lane) cand &= ~(1u << (e >> 6));
+        if (best == none) e = INT_MAX;
+#pragma unroll
+        for (int i = 0; i < NS; ++i) key[i] = (e == lane + kWave * i) ? none : key[i];
         emit(j, e, key_value(best));
     }
 }

@@ -321,10 +321,8 @@ __device__ __forceinline__ int token_topk(const TokenLogits<NS> &tl, const Token
     int mye = -1;
     float myz = -INFINITY;
     wave_topk(tl.v, tl.have, k, [&](int j, int e, float z) {
-        if (lane == j) {
-            mye = (e == INT_MAX) ? -1 : e;
-            myz = z;
-        }
+        put_lane(mye, j, (e == INT_MAX) ? -1 : e);
+        put_lane(myz, j, z);
     });
     float num, zref;
     const float g = selection_gate(k, mye, myz, gate_fn, num, zref);
@@ -466,10 +464,8 @@ __device__ __forceinline__ int token_remap(const TokenLogits<NS> &tl, int t, int
         for (int i = 0; i < NS; ++i)
             if (((tl.have >> i) & 1u) && inA[lane + kWave * i]) cand |= 1u << i;
         wave_topk(tl.v, cand, k, [&](int j, int e, float zz) {
-            if (lane == j) {
-                mye = (e == INT_MAX) ? -1 : e;
-                myz = zz;
-            }
+            put_lane(mye, j, (e == INT_MAX) ? -1 : e);
+            put_lane(myz, j, zz);
         });
         // A group-limited token can find fewer than k members of the active set among its experts (without groups
         // the active set holds at least k for everybody).  Then all of them were taken, and the slots left keep the
@@ -882,9 +878,7 @@ __global__ __launch_bounds__(kTokThreads) void biased_remap_kernel(const float *
                 zb[i] = have ? __fadd_rn(tl.v[i], bias[e]) : -INFINITY;
                 if (have && inU[e] && e != top) cand |= 1u << i;
             }
-            wave_topk(zb, cand, k - 1, [&](int j, int e, float) {
-                if (lane == j + 1) mye = (e == INT_MAX) ? -1 : e;
-            });
+            wave_topk(zb, cand, k - 1, [&](int j, int e, float) { put_lane(mye, j + 1, (e == INT_MAX) ? -1 : e); });
             const float zo = logit_of(tl, mye >= 0 ? mye : 0);   // gates come from the original logits
             if (lane > 0 && mye >= 0) myz = zo;
         }
