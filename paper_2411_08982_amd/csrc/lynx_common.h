@@ -65,6 +65,21 @@ __device__ __forceinline__ int wave_max_i32(int v)
     return __builtin_amdgcn_readlane(v, 63);
 }
 
+// Inclusive prefix sums over the lanes of the wave, same data path: the four row shifts leave every lane with the
+// sum of its row up to itself, the two broadcasts add the totals of the rows before.  Every lane gets its prefix.
+__device__ __forceinline__ int wave_prefix_sum_i32(int v)
+{
+#define LYNX_DPP_STEP_IADD(ctrl, rmask) v += __builtin_amdgcn_update_dpp(0, v, ctrl, rmask, 0xf, false)
+    LYNX_DPP_STEP_IADD(0x111, 0xf);
+    LYNX_DPP_STEP_IADD(0x112, 0xf);
+    LYNX_DPP_STEP_IADD(0x114, 0xf);
+    LYNX_DPP_STEP_IADD(0x118, 0xf);
+    LYNX_DPP_STEP_IADD(0x142, 0xa);
+    LYNX_DPP_STEP_IADD(0x143, 0xc);
+#undef LYNX_DPP_STEP_IADD
+    return v;
+}
+
 // Floats as integers that compare the same way (finite values and infinities; -0 is first made +0, so that the two
 // stay equal), and back.
 __device__ __forceinline__ int order_key(float f)

@@ -40,28 +40,23 @@ __device__ __forceinline__ void permute_from_bitsets(Shared &sh, const int32_t *
         sh.count[tid] = c;
     }
     __syncthreads();
-    // exclusive prefixes over experts: pair offsets and rank among the invoked experts
+    // exclusive prefixes over experts: pair offsets and rank among the invoked experts, both in one scan (the pair
+    // count of the whole batch is at most LYNX_MAX_T * LYNX_MAX_K < 2^16: it leaves the upper half to the ranks)
+    static_assert(LYNX_MAX_T * LYNX_MAX_K < 65536 && LYNX_MAX_N < 32768, "packed prefix sums");
     if (tid < kWave) {
         int carry_o = 0, carry_a = 0;
         for (int base = 0; base < N; base += kWave) {
             const int e = base + tid;
             const int c = (e < N) ? sh.count[e] : 0;
             const int a = c > 0 ? 1 : 0;
-            int so = c, sa = a;
-#pragma unroll
-            for (int d = 1; d < kWave; d <<= 1) {
-                const int uo = __shfl_up(so, d, kWave), ua = __shfl_up(sa, d, kWave);
-                if (tid >= d) {
-                    so += uo;
-                    sa += ua;
-                }
-            }
+            const int s = wave_prefix_sum_i32(c | (a << 16));
             if (e < N) {
-                sh.offs[e] = carry_o + so - c;
-                sh.arank[e] = carry_a + sa - a;
+                sh.offs[e] = carry_o + (s & 0xffff) - c;
+                sh.arank[e] = carry_a + (s >> 16) - a;
             }
-            carry_o += __shfl(so, kWave - 1, kWave);
-            carry_a += __shfl(sa, kWave - 1, kWave);
+            const int total = __builtin_amdgcn_readlane(s, kWave - 1);
+            carry_o += total & 0xffff;
+            carry_a += total >> 16;
         }
         if (tid == 0) {
             sh.offs[N] = carry_o;
