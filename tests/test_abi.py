@@ -63,6 +63,18 @@ def test_argument_errors_are_reported_before_any_launch():
     abb = lambda gamma: lib.lynx_affinity_bin_biased(one, one, 4, 8, 2, ctypes.c_float(2.0), 2, ctypes.c_float(gamma), 1,
                                                      one, one, one, one, one, one, None, None)
     assert abb(-1.0) == -1 and abb(float("nan")) == -1 and abb(float("inf")) == -1
+    # group-limited router: n_group divides N, 1 <= topk_group <= n_group, enough experts in the groups, gate_fn 0 / 1
+    rg = lambda N, k, G, tg, gf: lib.lynx_route_grouped(one, one, None, 4, 64, N, k, G, tg, gf, one, one, one, one, None)
+    assert rg(12, 2, 5, 2, 0) == -1 and b"n_group" in lib.lynx_last_error()
+    assert rg(12, 2, 4, 5, 0) == -1 and rg(12, 2, 0, 1, 0) == -1 and rg(12, 2, 4, 0, 0) == -1
+    assert rg(12, 4, 4, 1, 0) == -1 and b"fewer than k" in lib.lynx_last_error()
+    assert rg(12, 2, 4, 2, 2) == -1 and b"gate_fn" in lib.lynx_last_error()
+    assert rg(256, 2, 128, 2, 0) == -2
+    abg = lambda N, k, G, tg, beta: lib.lynx_affinity_bin_grouped(one, 4, N, k, G, tg, 0, ctypes.c_float(1.0), beta, 1, one,
+                                                                  one, one, one, one, one, one, one, one, one, None)
+    assert abg(12, 2, 5, 2, 2) == -1 and abg(12, 4, 4, 1, 2) == -1 and abg(12, 2, 4, 2, 0) == -1 and abg(12, 2, 4, 2, 7) == -2
+    assert lib.lynx_affinity_bin_grouped(one, 4, 12, 2, 4, 2, 0, ctypes.c_float(1.0), 2, 1, one, one, one, one, one, one, one,
+                                         one, one, None, None) == -1      # no workspace
     assert lib.lynx_permute(one, 4, 8, 9, one, one, one, one, None) == -2
     assert lib.lynx_permute(one, 4, 0, 1, one, one, one, one, None) == -1
     assert lib.lynx_pack_weights(one, one, one, 2, 48, 64, one, one, None) == -2
