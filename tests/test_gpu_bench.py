@@ -48,3 +48,12 @@ def test_bench_stack_mode():
     for v in d["stack"].values():
         assert v["us_graph_median"] > 0 and v["us_eager_median"] > 0
     assert d["stack"]["layer_policy"]["invoked_after_mean"] <= d["stack"]["off"]["invoked_after_mean"]
+
+
+def test_bench_router_options():
+    print("bench.py --config tiny --router sigmoid --groups 4,2", flush=True)
+    d = _run("--config", "tiny", "--tokens", "16", "--steps", "3", "--warmup", "1", "--sweep-iters", "2", "--router", "sigmoid",
+             "--groups", "4,2")
+    assert "sigmoid-gated router" in d["config"]["workload"] and "group-limited router (2 of 4 groups)" in d["config"]["workload"]
+    assert d["value"] > 0 and "cpu_baseline" not in d and "fp8_weights" not in d
+    assert d["experts_invoked"]["after"] <= d["experts_invoked"]["before"]
