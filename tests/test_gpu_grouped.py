@@ -171,3 +171,24 @@ def test_bad_arguments(L):
     with pytest.raises(L.LynxError) as e:
         L.lynx_affinity_bin_grouped(z, 2, 128, 2, 1.0, 2)
     assert e.value.code == L.binding.ERR_UNSUPPORTED
+
+
+def test_zero_tokens_and_single_token(L):
+    cfg = wl.CONFIGS["tiny"]                                        # 8 experts, top-2
+    d = wl.make_layer(cfg, 0)
+    Wgu, Wdp = L.lynx_pack_weights(to_bf16_dev(d["Wg"]), to_bf16_dev(d["Wu"]), to_bf16_dev(d["Wd"]))
+    x = torch.empty((0, cfg.H), dtype=torch.bfloat16, device="cuda")
+    b = L.lynx_moe_layer_grouped(x, dev(d["Wr"]), dev(d["bias"]), Wgu, Wdp, cfg.F, cfg.k, 4, 2, 2.0, 2, 1)
+    torch.cuda.synchronize()
+    assert host(b.num_active).tolist() == [0, 0] and host(b.num_active_perm).tolist() == [0]
+    assert np.all(host(b.offsets) == 0) and np.all(host(b.active) == -1) and np.all(host(b.cnt_before) == 0)
+    # one token: nothing to share, the group-limited selection stays
+    d = wl.make_layer(cfg, 1)
+    b = L.lynx_moe_layer_grouped(to_bf16_dev(d["x"]), dev(d["Wr"]), dev(d["bias"]), Wgu, Wdp, cfg.F, cfg.k, 4, 1, 2.0, 2, 0)
+    torch.cuda.synchronize()
+    z = host(b.logits)
+    tk = oracle.topk_grouped(z, cfg.k, 4, 1, 0)
+    assert np.array_equal(host(b.topk_idx), tk["idx"]) and np.array_equal(host(b.new_idx), tk["idx"])
+    assert host(b.topk_idx)[0, 0] // 2 == host(b.topk_idx)[0, 1] // 2      # both picks in the one allowed group of two
+    y_ref = oracle.moe_ffn(d["x"], d["Wg"], d["Wu"], d["Wd"], tk["idx"], tk["gate"])
+    assert row_rel_err(host(b.y), y_ref).max() <= Y_TOL
