@@ -705,11 +705,13 @@ __device__ __forceinline__ void expert_staged(const WorkItem &w, const int *rowo
 // (routed expert rank, tile of 16*RW rows), RW = 4 / KW.  An expert with at most kDirectMaxTokens tokens
 // takes the direct path with the workgroup's four waves as RW row tiles x KW slices of K.  A larger expert
 // takes the staged path, in which a workgroup covers 64 rows: of every KW consecutive workgroups one does the
-// work, in passes of up to 64 (128) tokens, and the others leave.
+// work, in passes of up to 64 (128) tokens, and the others leave.  The gate/up part of the grid ends with spare
+// workgroups: when the last round of live gate/up workgroups is small, each of its workgroups is replaced by four
+// of one row tile (see ffn_kernel).
 //
-// A down workgroup needs the intermediate vectors h of its expert complete.  Every gate/up workgroup adds one
-// to its expert's counter once its h stores have completed; a down workgroup requests its first weight tiles
-// and then waits for the counter.  Workgroups are dispatched in index order, so when a down workgroup runs,
+// A down workgroup needs the intermediate vectors h of its expert complete.  Every gate/up workgroup adds its
+// row tiles (four, or one) to its expert's counter once its h stores have completed; a down workgroup requests its
+// first weight tiles and then waits for the counter to reach the expert's row tiles.  Workgroups are dispatched in index order, so when a down workgroup runs,
 // every gate/up workgroup has been dispatched, and those wait for nothing: the wait always ends.  It is bounded
 // all the same (on running out it sets a flag in the workspace and goes on), so no wave can hang.  The gain:
 // the down projection's start-up overlaps the tail of gate/up instead of following a launch boundary.
@@ -717,11 +719,14 @@ struct FfnParams {
     GemmParams gu, dn;
     int gu_blocks;
     int block0;       // index of this launch's first workgroup in the (gate/up, down) order
+    int gu_split;     // 1: the last, partial round of gate/up workgroups is cut into single row tiles (see ffn_kernel)
     int wait;         // 0: the down workgroups of this launch follow a finished gate/up launch and do not wait
     int32_t *done;    // [LYNX_MAX_N] routed experts, then [n_shared * token blocks]; zero before the launch
     int32_t *flags;
 };
 
+constexpr int kSplitRound = 256;     // CUs: workgroups per round of the dispatcher
+constexpr int kSplitMaxRem = 128;    // largest partial round that is cut into single row tiles
 constexpr int kSpinLimit = 1 << 17;   // polls of a counter (about a microsecond each) before giving up
 
 __device__ __forceinline__ int done_slot(const GemmParams &p, const WorkItem &w)
@@ -729,13 +734,15 @@ __device__ __forceinline__ int done_slot(const GemmParams &p, const WorkItem &w)
     return w.shared_s < 0 ? w.e : LYNX_MAX_N + w.shared_s * p.shared_tblocks + w.tok0 / p.tok_block;
 }
 
+// sub >= 0 (gate/up, KW = 4 only): the workgroup takes row tile `sub` of the four that workgroup b stands for.
 template <bool DUAL, int KW, bool BIG, int WF>
 __device__ __forceinline__ void expert_work(const GemmParams &p, int b, const FfnParams &fp, char *stage, int *rowoff,
-                                            int *outrow)
+                                            int *outrow, int sub = -1)
 {
     constexpr int TB = BIG ? kTokBlockBig : kTokBlock;   // tokens per pass
     WorkItem w = resolve_expert<DUAL, WF>(p, b);
     if (!w.valid) return;
+    if (sub >= 0) w.tile = w.tile * kFfnWaves + sub;
     // The weight stream of the direct path starts before the token tables are read (their loads depend on
     // each other: offsets, then the permutation, then the token rows).
     // (Not in the large-batch kernels: their staged path needs the registers, and few of their experts are direct.)
@@ -746,7 +753,8 @@ __device__ __forceinline__ void expert_work(const GemmParams &p, int b, const Ff
     if (!w.valid) return;
     int32_t *counter = fp.done + done_slot(p, w);
     if (!DUAL && fp.wait) {   // wait for this expert's (this token block's) intermediate vectors
-        const int target = w.shared_s < 0 ? fp.gu.tiles_r : fp.gu.tiles_s;
+        // (gate/up workgroups report row tiles: four each, or one for a workgroup of a single tile)
+        const int target = kFfnWaves * (w.shared_s < 0 ? fp.gu.tiles_r : fp.gu.tiles_s);
         if (threadIdx.x == 0) {
             int polls = 0;
             while (load_coherent(counter) < target) {
@@ -767,13 +775,15 @@ __device__ __forceinline__ void expert_work(const GemmParams &p, int b, const Ff
         constexpr int kRowsPerWG = 16 * (kFfnWaves / KW) * (DUAL ? 1 : 2);
         constexpr int kUnits = kRowsPerWG >= 64 ? kRowsPerWG / 64 : 1;      // staged units this workgroup does
         constexpr int kShare = kRowsPerWG >= 64 ? 1 : 64 / kRowsPerWG;      // workgroups that share one unit
-        static_assert(!DUAL || (kUnits == 1 && kShare == 1), "every gate/up workgroup must do work and report it");
+        // (a gate/up workgroup that shares its unit with others and leaves the work to one of them still reports
+        // below: a down workgroup waits for the row tiles of all gate/up workgroups of its expert)
         // (shared experts see every token, so the host knows that they are staged and gives them one workgroup
         // per unit)
         const bool shared = w.shared_s >= 0;
-        if (!shared && (w.tile % kShare) != 0) return;
+        const bool leaves = !shared && (w.tile % kShare) != 0;
+        if (leaves && !(DUAL && fp.wait)) return;
         const int unit0 = shared ? w.tile : (w.tile / kShare) * kUnits;
-        const int units = shared ? 1 : kUnits;
+        const int units = leaves ? 0 : shared ? 1 : kUnits;
         const int tid = threadIdx.x;
         for (int un = 0; un < units; ++un) {
             w.tile = unit0 + un;
@@ -800,7 +810,7 @@ __device__ __forceinline__ void expert_work(const GemmParams &p, int b, const Ff
     if (DUAL && fp.wait) {   // report: this workgroup's part of h is complete in memory
         wait_memory_complete();
         __syncthreads();
-        if (threadIdx.x == 0) atomicAdd(counter, 1);
+        if (threadIdx.x == 0) atomicAdd(counter, KW == 1 ? kFfnWaves : 1);
     }
 }
 
@@ -812,10 +822,33 @@ __global__ __launch_bounds__(kFfnThreads, 2) void ffn_kernel(FfnParams fp)
     __shared__ int rowoff[BIG ? kTokBlockBig : kTokBlock];   // staged path: element offset of each token's B row, -1 = none
     __shared__ int outrow[BIG ? kTokBlockBig : kTokBlock];   // staged path: output row of each token, -1 = none
     const int b = blockIdx.x + fp.block0;
-    if (b < fp.gu_blocks)
-        expert_work<true, 1, BIG, WF>(fp.gu, b, fp, stage, rowoff, outrow);
-    else
+    if (b < fp.gu_blocks) {
+        // Gate/up workgroups take four row tiles, one per wave, and the dispatcher hands workgroups to the CUs
+        // breadth first: L live workgroups put two on L mod 256 CUs and one on the rest, and while the stream is
+        // HBM-bound the CUs share it evenly, so the CUs with two take twice as long (measured: Qwen3 shape, 312
+        // workgroups: 21-24 us against 40-48 us), at the end on a fraction of the chip's waves.  When that last,
+        // partial round is small, each of its workgroups is replaced by four workgroups of one row tile (the
+        // four waves split K), which the dispatcher spreads over all CUs: at most one or two tiles more per CU.
+        // The count of live workgroups is a device-side value, so the mapping is made here.
+        // (bf16 weights only: in the kernels of the quantised formats the second code path costs spilled registers)
+        int bb = b, sub = -1;
+        if (WF == 0 && fp.gu_split) {
+            const int live = fp.gu.shared_blocks + min(*fp.gu.num_active, fp.gu.N) * fp.gu.tiles_r;
+            const int full = live / kSplitRound * kSplitRound, rem = live - full;
+            if (rem > 0 && rem <= kSplitMaxRem && full >= fp.gu.shared_blocks && b >= full) {
+                bb = full + (b - full) / kFfnWaves;
+                sub = (b - full) % kFfnWaves;
+                if (bb >= live) return;
+            }
+        }
+        if (sub < 0 && bb >= fp.gu.shared_blocks + fp.gu.routed_blocks) return;   // the workgroups the split may need
+        if (WF != 0 || sub < 0)
+            expert_work<true, 1, BIG, WF>(fp.gu, bb, fp, stage, rowoff, outrow);
+        else if constexpr (WF == 0)
+            expert_work<true, kFfnWaves, BIG, WF>(fp.gu, bb, fp, stage, rowoff, outrow, sub);
+    } else {
         expert_work<false, KWD, BIG, WF>(fp.dn, b - fp.gu_blocks, fp, stage, rowoff, outrow);
+    }
 }
 
 __global__ __launch_bounds__(256) void clear_kernel(int32_t *p, int n)
@@ -1098,7 +1131,9 @@ static int launch_ffn(FfnParams fp, hipStream_t st)
     const int kwd = pick_k_waves(d.K, false, d.T, max_experts, 16 >> WF);
     set_tiles(fp.gu, 16 * kFfnWaves);                    // gate/up: four row tiles per workgroup
     set_tiles(fp.dn, 16 * (kFfnWaves / kwd) * 2);
-    fp.gu_blocks = (int)grid_blocks(fp.gu);
+    // the split of the last round needs up to three more workgroups per workgroup it replaces
+    fp.gu_split = (WF == 0 && max_experts > 8 && fp.gu.shared_blocks < kSplitRound) ? 1 : 0;
+    fp.gu_blocks = (int)grid_blocks(fp.gu) + (fp.gu_split ? kSplitMaxRem * (kFfnWaves - 1) : 0);
     const unsigned dn_blocks = grid_blocks(fp.dn);
     const bool big = d.T > kTokBlock;
     const bool single = single_launch(d.T, d.K);
