@@ -300,6 +300,16 @@ FFN_CASES = [
     # more than 128 tokens (a second pass with few tokens): every load of a token row must stay inside the row
     (189, 32, 512, 13, 2, 0, 0, 3),
     (150, 64, 96, 5, 2, 1, 32, 2),
+    # the last, partial round of gate/up workgroups is cut into workgroups of one row tile: all of them (48 live
+    # workgroups), the 64 past a full round of 256 (40 experts x 8), with F / 16 no multiple of 4 (row tiles past the
+    # last row), with crowded experts on the staged path among them, with a shared expert in front, and at most 16
+    # tokens (gate/up and down as two launches)
+    (40, 128, 128, 24, 4, 0, 0, None),
+    (64, 64, 512, 40, 8, 0, 0, None),
+    (33, 64, 96, 30, 5, 0, 0, None),
+    (120, 64, 160, 20, 4, 0, 0, 12),
+    (48, 128, 192, 28, 6, 1, 128, None),
+    (12, 256, 224, 18, 3, 0, 0, None),
 ]
 
 
