@@ -1132,7 +1132,7 @@ static int launch_ffn(FfnParams fp, hipStream_t st)
     set_tiles(fp.gu, 16 * kFfnWaves);                    // gate/up: four row tiles per workgroup
     set_tiles(fp.dn, 16 * (kFfnWaves / kwd) * 2);
     // the split of the last round needs up to three more workgroups per workgroup it replaces
-    fp.gu_split = (WF == 0 && max_experts > 8 && fp.gu.shared_blocks < kSplitRound) ? 1 : 0;
+    fp.gu_split = (WF == 0 && fp.gu.shared_blocks < kSplitRound) ? 1 : 0;
     fp.gu_blocks = (int)grid_blocks(fp.gu) + (fp.gu_split ? kSplitMaxRem * (kFfnWaves - 1) : 0);
     const unsigned dn_blocks = grid_blocks(fp.dn);
     const bool big = d.T > kTokBlock;
