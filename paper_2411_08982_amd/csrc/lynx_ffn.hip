@@ -727,6 +727,7 @@ struct FfnParams {
 
 constexpr int kSplitRound = 256;     // CUs: workgroups per round of the dispatcher
 constexpr int kSplitMaxRem = 128;    // largest partial round that is cut into single row tiles
+constexpr int kSplitMaxTokens = 32;  // largest batch for which it is done
 constexpr int kSpinLimit = 1 << 17;   // polls of a counter (about a microsecond each) before giving up
 
 __device__ __forceinline__ int done_slot(const GemmParams &p, const WorkItem &w)
@@ -1132,7 +1133,10 @@ static int launch_ffn(FfnParams fp, hipStream_t st)
     set_tiles(fp.gu, 16 * kFfnWaves);                    // gate/up: four row tiles per workgroup
     set_tiles(fp.dn, 16 * (kFfnWaves / kwd) * 2);
     // the split of the last round needs up to three more workgroups per workgroup it replaces
-    fp.gu_split = (WF == 0 && fp.gu.shared_blocks < kSplitRound) ? 1 : 0;
+    // (not for batches of more than 32 tokens: more and more experts are then on the staged path, whose unit is the
+    // whole workgroup of four row tiles, and three of the four small workgroups only find out that they leave;
+    // measured equal or 3 us slower at 64 tokens, 3-8 us slower at 128 and 256)
+    fp.gu_split = (WF == 0 && d.T <= kSplitMaxTokens && fp.gu.shared_blocks < kSplitRound) ? 1 : 0;
     fp.gu_blocks = (int)grid_blocks(fp.gu) + (fp.gu_split ? kSplitMaxRem * (kFfnWaves - 1) : 0);
     const unsigned dn_blocks = grid_blocks(fp.dn);
     const bool big = d.T > kTokBlock;

@@ -303,13 +303,14 @@ FFN_CASES = [
     # the last, partial round of gate/up workgroups is cut into workgroups of one row tile: all of them (48 live
     # workgroups), the 64 past a full round of 256 (40 experts x 8), with F / 16 no multiple of 4 (row tiles past the
     # last row), with crowded experts on the staged path among them, with a shared expert in front, and at most 16
-    # tokens (gate/up and down as two launches)
-    (40, 128, 128, 24, 4, 0, 0, None),
-    (64, 64, 512, 40, 8, 0, 0, None),
-    (33, 64, 96, 30, 5, 0, 0, None),
-    (120, 64, 160, 20, 4, 0, 0, 12),
-    (48, 128, 192, 28, 6, 1, 128, None),
+    # tokens (gate/up and down as two launches); batches of at most 32 tokens, beyond which it is not done
+    (32, 128, 128, 24, 4, 0, 0, None),
+    (32, 64, 512, 40, 8, 0, 0, None),
+    (31, 64, 96, 30, 5, 0, 0, None),
+    (32, 64, 160, 20, 8, 0, 0, 10),
+    (24, 128, 192, 28, 6, 1, 128, None),
     (12, 256, 224, 18, 3, 0, 0, None),
+    (64, 64, 512, 40, 8, 0, 0, None),
 ]
 
 
