@@ -47,6 +47,8 @@ def _load():
         lib.orc_topk.argtypes = [f32p, c_int, c_int, c_int, i32p, f64p, f64p]
         lib.orc_topk_sigmoid.argtypes = [f32p, c_int, c_int, c_int, i32p, f64p, f64p]
         lib.orc_sigmoid_gates.argtypes = [f32p, i32p, c_int, c_int, c_int, f64p, f64p]
+        lib.orc_selection_mass.argtypes = [f32p, i32p, c_int, c_int, c_int, f64p]
+        lib.orc_selection_mass.restype = c_int
         lib.orc_group_allowed.argtypes = [f32p, c_int, c_int, c_int, c_int, u8p]
         lib.orc_topk_grouped.argtypes = [f32p, c_int, c_int, c_int, c_int, c_int, c_int, i32p, f64p, f64p]
         lib.orc_affinity_bin_grouped.argtypes = [f32p, i32p, c_int, c_int, c_int, c_int, c_int, c_float, c_int, c_int, i32p,
@@ -134,6 +136,18 @@ def topk(logits, k):
     return dict(idx=idx, gate=gate, psum=psum)
 
 
+def selection_mass(logits, idx):
+    """Share of the softmax over all experts held by the selection idx [T,k] (entries outside [0,N) skipped): f64 [T]."""
+    z = _arr(logits, np.float32)
+    idx = _arr(idx, np.int32)
+    T, N = z.shape
+    psum = np.zeros((T,), np.float64)
+    rc = _load().orc_selection_mass(_p(z, c_float), _p(idx, c_int32), T, N, idx.shape[1], _p(psum, c_double))
+    if rc != OK:
+        raise OracleError(rc, "orc_selection_mass")
+    return psum
+
+
 def topk_sigmoid(logits, k):
     """Sigmoid-gated router: top-k by logit, gates = selected sigmoid scores / their sum.
     Returns dict(idx, gate f64, ssum f64 = sum of the selected scores)."""
@@ -166,7 +180,7 @@ def affinity_bin_sigmoid(logits, topk_idx, alpha, beta, enable=1):
     """AffinityBinning under a sigmoid-gated router: bins, scores, nominations and remap exactly as affinity_bin (they
     use logit differences only); the gates of the new selection are the sigmoid scores over their sum."""
     a = affinity_bin(logits, topk_idx, alpha, beta, enable)
-    a["new_gate"], _ = sigmoid_gates(logits, a["new_idx"])
+    a["new_gate"], a["new_psum"] = sigmoid_gates(logits, a["new_idx"])   # the sum of the new selection's scores
     return a
 
 
@@ -218,9 +232,10 @@ def affinity_bin_grouped(logits, topk_idx, n_group, topk_group, alpha, beta, ena
                                           _p(bin_hist, c_int32), _p(num_active, c_int32), _p(active, c_int32))
     if rc != OK:
         raise OracleError(rc, "orc_affinity_bin_grouped")
+    new_third = selection_mass(z, new_idx)
     if gate_fn:
-        new_gate, _ = sigmoid_gates(z, new_idx)
-    return dict(new_idx=new_idx, new_gate=new_gate, cnt_before=cnt_before, cnt_after=cnt_after, bin_hist=bin_hist,
+        new_gate, new_third = sigmoid_gates(z, new_idx)
+    return dict(new_idx=new_idx, new_gate=new_gate, new_psum=new_third, cnt_before=cnt_before, cnt_after=cnt_after, bin_hist=bin_hist,
                 num_active=num_active, active=active)
 
 
@@ -249,8 +264,8 @@ def affinity_bin(logits, topk_idx, alpha, beta, enable=1):
                                   _p(q, c_int32), _p(score, c_uint64), _p(active, c_int32))
     if rc != OK:
         raise OracleError(rc, "orc_affinity_bin")
-    return dict(new_idx=new_idx, new_gate=new_gate, cnt_before=cnt_before, cnt_after=cnt_after, bin_hist=bin_hist,
-                num_active=num_active, q=q, score=score, active=active)
+    return dict(new_idx=new_idx, new_gate=new_gate, new_psum=selection_mass(z, new_idx), cnt_before=cnt_before,
+                cnt_after=cnt_after, bin_hist=bin_hist, num_active=num_active, q=q, score=score, active=active)
 
 
 def affinity_bin_biased(logits, topk_idx, alpha, beta, gamma, enable=1):
@@ -275,8 +290,8 @@ def affinity_bin_biased(logits, topk_idx, alpha, beta, gamma, enable=1):
                                          _p(num_active, c_int32), _p(bias, c_float))
     if rc != OK:
         raise OracleError(rc, "orc_affinity_bin_biased")
-    return dict(new_idx=new_idx, new_gate=new_gate, cnt_before=cnt_before, cnt_after=cnt_after, bin_hist=bin_hist,
-                num_active=num_active, bias=bias)
+    return dict(new_idx=new_idx, new_gate=new_gate, new_psum=selection_mass(z, new_idx), cnt_before=cnt_before,
+                cnt_after=cnt_after, bin_hist=bin_hist, num_active=num_active, bias=bias)
 
 
 def permute(idx, N):

@@ -114,6 +114,28 @@ int orc_topk(const float *logits, int T, int N, int k, int32_t *topk_idx, double
     return ORC_OK;
 }
 
+/* The "top-k weight sum" of any selection idx [T,k] (Sec. 4 lists these sums among the kernels' outputs): the share of
+ * the softmax over all N experts that the selected experts hold, psum[t] = sum_j p[t, idx[t,j]].  For the router's own
+ * top-k it is orc_topk's psum; for a remapped selection it says how much probability mass the remap kept.  Entries
+ * outside [0,N) are skipped. */
+int orc_selection_mass(const float *logits, const int32_t *idx, int T, int N, int k, double *psum)
+{
+    if (T < 0 || N <= 0 || k <= 0) return ORC_ERR_INVALID_ARG;
+    for (int t = 0; t < T; ++t) {
+        const float *z = logits + (size_t)t * N;
+        double zmax = (double)z[0], den = 0.0, num = 0.0;
+        for (int e = 1; e < N; ++e)
+            if ((double)z[e] > zmax) zmax = (double)z[e];
+        for (int e = 0; e < N; ++e) den += exp((double)z[e] - zmax);
+        for (int j = 0; j < k; ++j) {
+            const int32_t e = idx[(size_t)t * k + j];
+            if (e >= 0 && e < N) num += exp((double)z[e] - zmax);
+        }
+        psum[t] = num / den;
+    }
+    return ORC_OK;
+}
+
 /*
  * Sigmoid-gated routers (Sec. 3.2.1 closes with the case of routers that do not use softmax: the bins are then
  * taken from differences of the scores before the sigmoid, i.e. of the logits, exactly as above; so binning, scoring,

@@ -295,3 +295,66 @@ def test_active_set_is_feasible_and_near_minimal_on_tiny_batches(T, N, k):
             gaps.append(len(A) - best)
     # the slot-by-slot rule is greedy: it may exceed the minimum, but not by much on batches this small
     assert np.mean(gaps) < 0.5 and max(gaps) <= 2
+
+
+# ---- the probability mass of a selection (the "top-k weight sums" of Sec. 4) ------------------------------------------
+
+def test_selection_mass_is_the_share_of_the_full_softmax():
+    """orc_selection_mass against a library softmax: sum of the selected probabilities; the router's own top-k gives
+    orc_topk's psum; entries outside [0, N) are skipped; all experts selected gives 1."""
+    from scipy.special import softmax
+    rng = np.random.default_rng(5)
+    for T, N, k in [(1, 4, 2), (9, 60, 4), (33, 128, 8)]:
+        z = (rng.standard_normal((T, N)) * 3).astype(np.float32)
+        p = softmax(z.astype(np.float64), axis=1)
+        sel = np.stack([rng.choice(N, size=k, replace=False) for _ in range(T)]).astype(np.int32)
+        np.testing.assert_allclose(oracle.selection_mass(z, sel), np.take_along_axis(p, sel, 1).sum(1), rtol=1e-12)
+        tk = oracle.topk(z, k)
+        np.testing.assert_allclose(oracle.selection_mass(z, tk["idx"]), tk["psum"], rtol=1e-12)
+        bad = sel.copy()
+        bad[:, 0] = -1
+        np.testing.assert_allclose(oracle.selection_mass(z, bad), np.take_along_axis(p, sel[:, 1:], 1).sum(1), rtol=1e-12)
+        every = np.tile(np.arange(N, dtype=np.int32), (T, 1))
+        np.testing.assert_allclose(oracle.selection_mass(z, every), 1.0, rtol=1e-12)
+    # a closed form: logits ln 1, ln 2, ln 3, ln 4 are probabilities 0.1 .. 0.4
+    z = np.log(np.array([[1.0, 2.0, 3.0, 4.0]])).astype(np.float32)
+    np.testing.assert_allclose(oracle.selection_mass(z, np.array([[3, 1]], np.int32)), [0.6], rtol=1e-6)
+
+
+@pytest.mark.parametrize("preset", ["moderate", "aggressive"])
+def test_remap_never_gains_probability_mass_and_keeps_it_where_nothing_moves(preset):
+    """new_psum <= the mass of the router's own top-k (the top-k is the selection of largest mass), with equality
+    exactly where the selection is unchanged; bypassed calls keep everything."""
+    alpha, beta = wl.PRESETS[preset]
+    for T, N, k, seed in [(8, 8, 2, 0), (32, 128, 8, 1), (64, 60, 4, 2), (256, 64, 6, 3)]:
+        z = wl.make_logits(T, N, seed=seed, tail_frac=0.05)
+        tk = oracle.topk(z, k)
+        a = oracle.affinity_bin(z, tk["idx"], alpha, beta, 1)
+        assert np.all(a["new_psum"] <= tk["psum"] * (1 + 1e-12))
+        same = np.all(np.sort(a["new_idx"], 1) == np.sort(tk["idx"], 1), axis=1)
+        np.testing.assert_allclose(a["new_psum"][same], tk["psum"][same], rtol=1e-12)
+        assert np.all(a["new_psum"][~same] < tk["psum"][~same])
+        off = oracle.affinity_bin(z, tk["idx"], alpha, beta, 0)
+        np.testing.assert_allclose(off["new_psum"], tk["psum"], rtol=1e-12)
+
+
+def test_rank0_retention_under_the_reading():
+    """Sec. 3.3.1: high-confidence tokens always keep their top-ranked expert.  Under the reading implemented here a
+    token keeps its top-1 whenever that expert is alone in the token's bin 0 (no other expert within 1/alpha of it); a
+    token whose top-1 has company in bin 0 may be moved to the batch-preferred member of that bin, which is at most one
+    bin width below.  Both halves, on router-like logits."""
+    for preset in ("moderate", "aggressive"):
+        alpha, beta = wl.PRESETS[preset]
+        for T, N, k, seed in [(32, 128, 8, 0), (128, 64, 6, 1), (16, 8, 2, 2)]:
+            z = wl.make_logits(T, N, seed=seed)
+            tk = oracle.topk(z, k)
+            a = oracle.affinity_bin(z, tk["idx"], alpha, beta, 1)
+            top = tk["idx"][:, 0]
+            alone = (a["q"] == 0).sum(1) == 1
+            kept = (a["new_idx"] == top[:, None]).any(1)
+            assert kept[alone].all()
+            # a token that lost its top-1 got, as its best expert, one of the same bin: less than 1/alpha below
+            lost = ~kept
+            zt = np.take_along_axis(z, top[:, None], 1)[:, 0]
+            zn = np.take_along_axis(z, a["new_idx"][:, :1], 1)[:, 0]
+            assert np.all(zt[lost] - zn[lost] < 1.0 / alpha)
