@@ -21,7 +21,8 @@
  *  - Limits: T <= LYNX_MAX_T, N <= LYNX_MAX_N, k <= LYNX_MAX_K, beta <= LYNX_MAX_BETA,
  *    H % 32 == 0, F % 32 == 0, F_shared % 32 == 0 (multiples of 64 for the FP8-weight calls, of 128 for MXFP4).
  *  - Beyond the paper's bf16 method the header also declares a variant of the expert scorer
- *    (lynx_affinity_bin_biased), FP8 and MXFP4 expert weights (lynx_*_fp8, lynx_*_fp4) and measurement aids; each says so.
+ *    (lynx_affinity_bin_biased), FP8 and MXFP4 expert weights (lynx_*_fp8, lynx_*_fp4), sigmoid-gated and
+ *    group-limited routers; each says so.  Measurement aids and test knobs are in lynx_bench.h.
  */
 #ifndef LYNX_H
 #define LYNX_H
@@ -48,10 +49,8 @@ const char *lynx_last_error(void);
 
 /* Bytes of device workspace that lynx_affinity_bin, lynx_moe_ffn and lynx_moe_layer need for these
  * sizes (one buffer serves all; contents need not be preserved between calls; calls that share a
- * workspace must not overlap in time).  lynx_affinity_bin alone uses only the first 64 KiB.  Word
- * 9744 of the workspace (int32) is a diagnostic written by lynx_moe_ffn / lynx_moe_layer: non-zero after
- * the call if a workgroup gave up a bounded wait for another workgroup's result (never seen; y is then
- * not valid). */
+ * workspace must not overlap in time).  lynx_affinity_bin alone uses only the first 64 KiB.  N does not
+ * enter the size: the per-expert tables are reserved for LYNX_MAX_N experts inside those 64 KiB. */
 size_t lynx_workspace_bytes(int T, int H, int F, int N, int k, int n_shared, int F_shared);
 
 /*
@@ -60,6 +59,10 @@ size_t lynx_workspace_bytes(int T, int H, int F, int N, int k, int n_shared, int
  *   x_bf16 [T,H] bf16, Wr [N,H] fp32, bias [N] fp32 or NULL.
  *   logits [T,N] fp32 out; topk_idx [T,k] int32 out; topk_gate [T,k] fp32 out = selected
  *   probabilities renormalised to sum 1; topk_psum [T] fp32 out = sum of the selected probabilities.
+ * Accuracy of the logits: fp32 multiply-adds over H terms in a fixed order, so a logit differs from the exactly
+ * rounded sum by a few ulp of sum_h |x[t,h] * Wr[e,h]|, not of the logit itself.  For hidden states and router rows of
+ * ordinary scale (terms that do not cancel by orders of magnitude) that is below 1e-5 * max(1, |z|), the bound the
+ * parity tests check; a router whose terms are a thousand times larger than their sum loses the corresponding digits.
  */
 int lynx_route(const uint16_t *x_bf16, const float *Wr, const float *bias, int T, int H, int N, int k,
                float *logits, int32_t *topk_idx, float *topk_gate, float *topk_psum, void *stream);
@@ -80,13 +83,16 @@ int lynx_route(const uint16_t *x_bf16, const float *Wr, const float *bias, int T
  *
  *   logits [T,N] fp32, topk_idx [T,k] int32 (k distinct experts per row, descending logit; a row in another
  *   order is accepted, and a slot that then finds no expert to nominate nominates nothing).
- *   new_idx [T,k] int32 out, new_gate [T,k] fp32 out, cnt_before [N], cnt_after [N] int32 out (pairs
- *   per expert before / after), bin_hist [N,beta] int32 out, num_active [2] int32 out (experts invoked
- *   before, after).  workspace: lynx_workspace_bytes() bytes (the first 64 KiB are used).
+ *   new_idx [T,k] int32 out, new_gate [T,k] fp32 out, new_psum [T] fp32 out or NULL = the share of the softmax over
+ *   all N experts that the NEW selection holds (Sec. 4 names the top-k weight sums among the kernels' outputs; beside
+ *   lynx_route's topk_psum it says how much probability mass the remap gave up for the token: new_psum <= topk_psum,
+ *   equal where the selection did not change), cnt_before [N], cnt_after [N] int32 out (pairs per expert before /
+ *   after), bin_hist [N,beta] int32 out, num_active [2] int32 out (experts invoked before, after).
+ *   workspace: lynx_workspace_bytes() bytes (the first 64 KiB are used).
  */
 int lynx_affinity_bin(const float *logits, const int32_t *topk_idx, int T, int N, int k, float alpha, int beta,
-                      int enable, int32_t *new_idx, float *new_gate, int32_t *cnt_before, int32_t *cnt_after,
-                      int32_t *bin_hist, int32_t *num_active, void *workspace, void *stream);
+                      int enable, int32_t *new_idx, float *new_gate, float *new_psum, int32_t *cnt_before,
+                      int32_t *cnt_after, int32_t *bin_hist, int32_t *num_active, void *workspace, void *stream);
 
 /*
  * Score-biased selection: the variant of the adaptive expert scorer that takes literally what Sec. 3.3.1 says
@@ -99,8 +105,9 @@ int lynx_affinity_bin(const float *logits, const int32_t *topk_idx, int T, int N
  * arguments, outputs and the workspace as in lynx_affinity_bin; composes with lynx_permute and lynx_moe_ffn.
  */
 int lynx_affinity_bin_biased(const float *logits, const int32_t *topk_idx, int T, int N, int k, float alpha, int beta,
-                             float gamma, int enable, int32_t *new_idx, float *new_gate, int32_t *cnt_before,
-                             int32_t *cnt_after, int32_t *bin_hist, int32_t *num_active, void *workspace, void *stream);
+                             float gamma, int enable, int32_t *new_idx, float *new_gate, float *new_psum,
+                             int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist, int32_t *num_active,
+                             void *workspace, void *stream);
 
 /*
  * Token assignment (Sec. 4): expert_offsets [N+1] int32 out = exclusive prefix of pairs per expert;
@@ -128,51 +135,38 @@ int lynx_pack_weights(const uint16_t *Wg, const uint16_t *Wu, const uint16_t *Wd
  *          + sum_s Sd[s] (silu(Sg[s] x_t) .* (Su[s] x_t))            (shared experts, weight 1,
  *                                                                      Sec. 3.3.1 last paragraph)
  * bf16 operands, fp32 accumulation; the intermediate vector is rounded to bf16 between the two
- * projections.  Each invoked expert's weights are read once per call; experts with no pair are not
- * touched.  When both projections run as one launch, a down-projection workgroup waits (bounded) for the
- * gate/up workgroups of its expert, which always precede it in dispatch order.  Weights in the packed layout of lynx_pack_weights (Sgu/Sd: packed with E = n_shared,
- * F = F_shared; NULL when n_shared = 0).  expert_offsets / perm / active_experts / num_active as
- * written by lynx_permute for the same idx.  y [T,H] fp32 out, overwritten.
+ * projections.  Each invoked expert's weights are read once per call (an expert with more tokens than one pass of
+ * the kernel holds, 64 or 128, once per pass); experts with no pair are not touched.  Weights in the packed layout of
+ * lynx_pack_weights (Sgu/Sd: packed with E = n_shared, F = F_shared; NULL when n_shared = 0).  expert_offsets / perm as
+ * written by lynx_permute for the same idx: the invoked experts are those with a non-empty range in expert_offsets
+ * (active_experts / num_active are accepted for symmetry with lynx_permute and not read).  y [T,H] fp32 out, overwritten.
+ *
+ * status: one int32, DEVICE, out, or NULL.  When both projections run as one launch, a down-projection workgroup waits
+ * for the gate/up workgroups of its expert, which always precede it in dispatch order; the wait is bounded so that no
+ * wave can hang.  If a wait ever runs out, the call does not pass garbage on: every element of y is NaN and *status is
+ * 1; otherwise *status is 0.  (The return value cannot say it: the call has returned before the kernels run.)
  */
 int lynx_moe_ffn(const uint16_t *x_bf16, const uint16_t *Wgu_packed, const uint16_t *Wd_packed,
                  const uint16_t *Sgu_packed, const uint16_t *Sd_packed, int n_shared, int F_shared,
                  const int32_t *idx, const float *gate, const int32_t *expert_offsets, const int32_t *perm,
                  const int32_t *active_experts, const int32_t *num_active, int T, int H, int F, int N, int k,
-                 float *y, void *workspace, void *stream);
-
-/*
- * How many launches of the weight-streaming kernel lynx_moe_ffn issues for this batch size and expert width:
- * 1 (gate/up and down workgroups in one grid) or 2 (one grid each).  For measurement: per-launch figures of
- * a profile are whole-FFN figures divided by this.
- */
-int lynx_moe_ffn_launches(int T, int F);
-
-/*
- * lynx_moe_ffn with stage timing for measurement (roofline of the weight-streaming kernels): the same
- * work, and additionally records the caller's events on `stream`.  stage_events: HOST array of four
- * hipEvent_t (entries may be NULL): [0] is recorded before the weight-streaming launch(es), [1] and [2]
- * after them (gate/up and down are one kernel, launched once or twice: the two events are adjacent), [3]
- * after the combine.  stage_events == NULL is exactly lynx_moe_ffn.
- */
-int lynx_moe_ffn_timed(const uint16_t *x_bf16, const uint16_t *Wgu_packed, const uint16_t *Wd_packed,
-                       const uint16_t *Sgu_packed, const uint16_t *Sd_packed, int n_shared, int F_shared,
-                       const int32_t *idx, const float *gate, const int32_t *expert_offsets, const int32_t *perm,
-                       const int32_t *active_experts, const int32_t *num_active, int T, int H, int F, int N, int k,
-                       float *y, void *workspace, void *stream, void *const *stage_events);
+                 float *y, int32_t *status, void *workspace, void *stream);
 
 /*
  * The whole decode step of one MoE layer: the work of lynx_route, lynx_affinity_bin, lynx_permute and
  * lynx_moe_ffn chained on `stream` with the argument meanings above and identical results (the routing
- * side is issued as two launches up to 16 tokens and four beyond).  All intermediate arrays are outputs.  stage_events: as in
- * lynx_moe_ffn_timed, or NULL.
+ * side is issued as two launches up to 16 tokens and four beyond).  All intermediate arrays are outputs; new_psum and
+ * status may be NULL.  Every argument check of the four calls is made before anything is enqueued.  stage_events: HOST
+ * array of four hipEvent_t (entries may be NULL) or NULL: [0] is recorded on `stream` before the weight-streaming
+ * launch(es), [1] and [2] after them, [3] after the combine (for measurement; see lynx_bench.h).
  */
 int lynx_moe_layer(const uint16_t *x_bf16, const float *Wr, const float *bias, const uint16_t *Wgu_packed,
                    const uint16_t *Wd_packed, const uint16_t *Sgu_packed, const uint16_t *Sd_packed, int n_shared,
                    int F_shared, int T, int H, int F, int N, int k, float alpha, int beta, int enable, float *logits,
                    int32_t *topk_idx, float *topk_gate, float *topk_psum, int32_t *new_idx, float *new_gate,
-                   int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist, int32_t *num_active,
+                   float *new_psum, int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist, int32_t *num_active,
                    int32_t *expert_offsets, int32_t *perm, int32_t *active_experts, int32_t *num_active_perm, float *y,
-                   void *workspace, void *stream, void *const *stage_events);
+                   int32_t *status, void *workspace, void *stream, void *const *stage_events);
 
 /*
  * Expert weights in 8-bit floating point, weight-only (a widening beyond the paper's bf16 runs; its Sec. 5 shows
@@ -189,7 +183,7 @@ int lynx_quantize_weights_fp8(const uint16_t *Wg, const uint16_t *Wu, const uint
                               uint8_t *Wgu_q, uint8_t *Wd_q, float *scales_gu, float *scales_d, void *stream);
 
 /*
- * lynx_moe_ffn_timed with FP8 weights: the codes are converted to bf16 in registers (exact), multiplied on the
+ * lynx_moe_ffn with FP8 weights (and the stage events of lynx_moe_layer): the codes are converted to bf16 in registers (exact), multiplied on the
  * matrix cores as in the bf16 path, and the accumulated sums are multiplied by the row scales; activations and
  * the intermediate vector stay bf16.  Shared experts quantised likewise (NULL when n_shared = 0).
  * stage_events may be NULL.  H, F, F_shared multiples of 64.
@@ -198,8 +192,8 @@ int lynx_moe_ffn_fp8(const uint16_t *x_bf16, const uint8_t *Wgu_q, const uint8_t
                      const float *scales_d, const uint8_t *Sgu_q, const uint8_t *Sd_q, const float *shared_scales_gu,
                      const float *shared_scales_d, int n_shared, int F_shared, const int32_t *idx, const float *gate,
                      const int32_t *expert_offsets, const int32_t *perm, const int32_t *active_experts,
-                     const int32_t *num_active, int T, int H, int F, int N, int k, float *y, void *workspace,
-                     void *stream, void *const *stage_events);
+                     const int32_t *num_active, int T, int H, int F, int N, int k, float *y, int32_t *status,
+                     void *workspace, void *stream, void *const *stage_events);
 
 /* lynx_moe_layer with FP8 expert weights (routing unchanged). */
 int lynx_moe_layer_fp8(const uint16_t *x_bf16, const float *Wr, const float *bias, const uint8_t *Wgu_q,
@@ -207,9 +201,9 @@ int lynx_moe_layer_fp8(const uint16_t *x_bf16, const float *Wr, const float *bia
                        const uint8_t *Sd_q, const float *shared_scales_gu, const float *shared_scales_d, int n_shared,
                        int F_shared, int T, int H, int F, int N, int k, float alpha, int beta, int enable, float *logits,
                        int32_t *topk_idx, float *topk_gate, float *topk_psum, int32_t *new_idx, float *new_gate,
-                       int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist, int32_t *num_active,
+                       float *new_psum, int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist, int32_t *num_active,
                        int32_t *expert_offsets, int32_t *perm, int32_t *active_experts, int32_t *num_active_perm,
-                       float *y, void *workspace, void *stream, void *const *stage_events);
+                       float *y, int32_t *status, void *workspace, void *stream, void *const *stage_events);
 
 /*
  * Expert weights in 4-bit floating point with shared block scales, weight-only (the same widening, a quarter of the
@@ -233,7 +227,7 @@ int lynx_quantize_weights_fp4(const uint16_t *Wg, const uint16_t *Wu, const uint
                               uint8_t *Wgu_q, uint8_t *Wd_q, uint32_t *scales_gu, uint32_t *scales_d, void *stream);
 
 /*
- * lynx_moe_ffn_timed with MXFP4 weights: the codes are converted to bf16, times their block scale, in registers
+ * lynx_moe_ffn with MXFP4 weights (and the stage events of lynx_moe_layer): the codes are converted to bf16, times their block scale, in registers
  * (exact) and multiplied on the same bf16 MFMA path.  Shared experts: Sgu_q, Sd_q and their scale arrays in the
  * same layouts with E = n_shared, F = F_shared (NULL if n_shared == 0).  H, F, F_shared multiples of 128.
  */
@@ -242,7 +236,7 @@ int lynx_moe_ffn_fp4(const uint16_t *x_bf16, const uint8_t *Wgu_q, const uint8_t
                      const uint32_t *shared_scales_gu, const uint32_t *shared_scales_d, int n_shared, int F_shared,
                      const int32_t *idx, const float *gate, const int32_t *expert_offsets, const int32_t *perm,
                      const int32_t *active_experts, const int32_t *num_active, int T, int H, int F, int N, int k,
-                     float *y, void *workspace, void *stream, void *const *stage_events);
+                     float *y, int32_t *status, void *workspace, void *stream, void *const *stage_events);
 
 /* lynx_moe_layer with MXFP4 expert weights (routing unchanged). */
 int lynx_moe_layer_fp4(const uint16_t *x_bf16, const float *Wr, const float *bias, const uint8_t *Wgu_q,
@@ -250,9 +244,10 @@ int lynx_moe_layer_fp4(const uint16_t *x_bf16, const float *Wr, const float *bia
                        const uint8_t *Sd_q, const uint32_t *shared_scales_gu, const uint32_t *shared_scales_d,
                        int n_shared, int F_shared, int T, int H, int F, int N, int k, float alpha, int beta, int enable,
                        float *logits, int32_t *topk_idx, float *topk_gate, float *topk_psum, int32_t *new_idx,
-                       float *new_gate, int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist, int32_t *num_active,
-                       int32_t *expert_offsets, int32_t *perm, int32_t *active_experts, int32_t *num_active_perm,
-                       float *y, void *workspace, void *stream, void *const *stage_events);
+                       float *new_gate, float *new_psum, int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist,
+                       int32_t *num_active, int32_t *expert_offsets, int32_t *perm, int32_t *active_experts,
+                       int32_t *num_active_perm, float *y, int32_t *status, void *workspace, void *stream,
+                       void *const *stage_events);
 
 /*
  * Sigmoid-gated routers.  Sec. 3.2.1 closes with routers that do not use softmax: their bins are taken from
@@ -262,22 +257,24 @@ int lynx_moe_layer_fp4(const uint16_t *x_bf16, const float *Wr, const float *bia
  * one for such routers: score = 1 / (1 + exp(-logit)) in fp32, the k experts of largest logit (the sigmoid is
  * increasing; equal logits to the lower index, decided on the fp32 logits), gate = score / sum of the k selected
  * scores.  The three calls below are lynx_route, lynx_affinity_bin and lynx_moe_layer (bf16 expert weights) with
- * these gates: same arguments, same layouts, same errors.  topk_ssum [T] fp32 out = the sum of the selected
- * scores (where the softmax calls give the selected probability mass).  They compose with lynx_permute,
+ * these gates: same arguments, same layouts, same errors.  topk_ssum / new_ssum [T] fp32 out = the sum of the selected
+ * scores, of the router's own and of the remapped selection (where the softmax calls give the selected probability
+ * mass).  They compose with lynx_permute,
  * lynx_moe_ffn and the quantised FFN calls, which take any gates.
  */
 int lynx_route_sigmoid(const uint16_t *x_bf16, const float *Wr, const float *bias, int T, int H, int N, int k,
                        float *logits, int32_t *topk_idx, float *topk_gate, float *topk_ssum, void *stream);
 int lynx_affinity_bin_sigmoid(const float *logits, const int32_t *topk_idx, int T, int N, int k, float alpha, int beta,
-                              int enable, int32_t *new_idx, float *new_gate, int32_t *cnt_before, int32_t *cnt_after,
-                              int32_t *bin_hist, int32_t *num_active, void *workspace, void *stream);
+                              int enable, int32_t *new_idx, float *new_gate, float *new_ssum, int32_t *cnt_before,
+                              int32_t *cnt_after, int32_t *bin_hist, int32_t *num_active, void *workspace, void *stream);
 int lynx_moe_layer_sigmoid(const uint16_t *x_bf16, const float *Wr, const float *bias, const uint16_t *Wgu_packed,
                            const uint16_t *Wd_packed, const uint16_t *Sgu_packed, const uint16_t *Sd_packed, int n_shared,
                            int F_shared, int T, int H, int F, int N, int k, float alpha, int beta, int enable,
                            float *logits, int32_t *topk_idx, float *topk_gate, float *topk_ssum, int32_t *new_idx,
-                           float *new_gate, int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist,
+                           float *new_gate, float *new_ssum, int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist,
                            int32_t *num_active, int32_t *expert_offsets, int32_t *perm, int32_t *active_experts,
-                           int32_t *num_active_perm, float *y, void *workspace, void *stream, void *const *stage_events);
+                           int32_t *num_active_perm, float *y, int32_t *status, void *workspace, void *stream,
+                           void *const *stage_events);
 
 /*
  * Group-limited routers.  Sec. 1 lists expert grouping among the architectures the method has to cover and gives no
@@ -289,7 +286,8 @@ int lynx_moe_layer_sigmoid(const uint16_t *x_bf16, const float *Wr, const float 
  * slots left, its own picks that are not in the active set, in rank order (so new_idx always holds k distinct experts
  * the batch already invoked).  Batch scores, score order, active-set fill, gates, counts and permutation are as in
  * the calls above.  gate_fn: 0 = softmax gates, topk_third [T] = selected share of the softmax over ALL N experts;
- * 1 = sigmoid gates (see above), topk_third = sum of the selected scores.
+ * 1 = sigmoid gates (see above), topk_third = sum of the selected scores; new_third [T] (or NULL) = the same of the
+ * remapped selection.
  *
  * n_group >= 1 must divide N, 1 <= topk_group <= n_group, topk_group * N / n_group >= k, gate_fn in {0, 1}, else
  * LYNX_ERR_INVALID_ARG; n_group <= 64, else LYNX_ERR_UNSUPPORTED.  n_group = 1 (or topk_group = n_group) is the
@@ -306,34 +304,16 @@ int lynx_route_grouped(const uint16_t *x_bf16, const float *Wr, const float *bia
                        void *stream);
 int lynx_affinity_bin_grouped(const float *logits, int T, int N, int k, int n_group, int topk_group, int gate_fn, float alpha,
                               int beta, int enable, int32_t *topk_idx, float *topk_gate, float *topk_third,
-                              int32_t *new_idx, float *new_gate, int32_t *cnt_before, int32_t *cnt_after,
-                              int32_t *bin_hist, int32_t *num_active, void *workspace, void *stream);
+                              int32_t *new_idx, float *new_gate, float *new_third, int32_t *cnt_before,
+                              int32_t *cnt_after, int32_t *bin_hist, int32_t *num_active, void *workspace, void *stream);
 int lynx_moe_layer_grouped(const uint16_t *x_bf16, const float *Wr, const float *bias, const uint16_t *Wgu_packed,
                            const uint16_t *Wd_packed, const uint16_t *Sgu_packed, const uint16_t *Sd_packed, int n_shared,
                            int F_shared, int T, int H, int F, int N, int k, int n_group, int topk_group, int gate_fn,
                            float alpha, int beta, int enable, float *logits, int32_t *topk_idx, float *topk_gate,
-                           float *topk_third, int32_t *new_idx, float *new_gate, int32_t *cnt_before, int32_t *cnt_after,
-                           int32_t *bin_hist, int32_t *num_active, int32_t *expert_offsets, int32_t *perm,
-                           int32_t *active_experts, int32_t *num_active_perm, float *y, void *workspace, void *stream,
-                           void *const *stage_events);
-
-/*
- * Measurement aid, not a step of the method: the residual update that chains MoE layers into a stack (the
- * benchmark times a stack of layers as a whole, each layer's input depending on the layer before):
- * x_next[i] = bf16(float(x[i]) + y[i]) for i < n, one fp32 addition rounded to nearest even.  x_bf16 [n] and
- * x_next_bf16 [n] bf16, y [n] fp32, all DEVICE; n even; x_next may be x itself.  n == 0 is a no-op.
- */
-int lynx_residual_add(const uint16_t *x_bf16, const float *y, size_t n, uint16_t *x_next_bf16, void *stream);
-
-/*
- * Measurement aid, not a step of the method: enqueues a plain read-only streaming kernel over
- * buf[0, bytes) (DEVICE memory, 16-byte aligned, bytes a multiple of 16; nothing is modified).  Timed by the
- * caller over a buffer much larger than the caches it gives the read bandwidth the chip delivers in
- * practice, which the benchmark prints beside the rate of the expert-weight stream.  non_temporal != 0:
- * the loads carry the same non-temporal hint as the weight stream.  sink: one DEVICE uint32_t (kept only so
- * that the loads have a use; practically never written).  bytes == 0 is a no-op.
- */
-int lynx_read_probe(const void *buf, size_t bytes, int non_temporal, uint32_t *sink, void *stream);
+                           float *topk_third, int32_t *new_idx, float *new_gate, float *new_third, int32_t *cnt_before,
+                           int32_t *cnt_after, int32_t *bin_hist, int32_t *num_active, int32_t *expert_offsets,
+                           int32_t *perm, int32_t *active_experts, int32_t *num_active_perm, float *y, int32_t *status,
+                           void *workspace, void *stream, void *const *stage_events);
 
 #ifdef __cplusplus
 }

@@ -24,7 +24,7 @@ SYMBOLS = ["lynx_last_error", "lynx_workspace_bytes", "lynx_route", "lynx_affini
            "lynx_quantize_weights_fp8", "lynx_moe_ffn_fp8", "lynx_moe_layer_fp8",
            "lynx_fp4_scale_words", "lynx_quantize_weights_fp4", "lynx_moe_ffn_fp4", "lynx_moe_layer_fp4",
            "lynx_route_sigmoid", "lynx_affinity_bin_sigmoid", "lynx_moe_layer_sigmoid",
-           "lynx_route_grouped", "lynx_affinity_bin_grouped", "lynx_moe_layer_grouped"]
+           "lynx_route_grouped", "lynx_affinity_bin_grouped", "lynx_moe_layer_grouped", "lynx_debug_set"]
 
 
 class LynxError(RuntimeError):
@@ -50,29 +50,30 @@ def lib():
         L.lynx_workspace_bytes.restype = c_size_t
         L.lynx_workspace_bytes.argtypes = [I] * 7
         L.lynx_route.argtypes = [P, P, P, I, I, I, I, P, P, P, P, P]
-        L.lynx_affinity_bin.argtypes = [P, P, I, I, I, F, I, I, P, P, P, P, P, P, P, P]
-        L.lynx_affinity_bin_biased.argtypes = [P, P, I, I, I, F, I, F, I, P, P, P, P, P, P, P, P]
+        L.lynx_affinity_bin.argtypes = [P, P, I, I, I, F, I, I, P, P, P, P, P, P, P, P, P]
+        L.lynx_affinity_bin_biased.argtypes = [P, P, I, I, I, F, I, F, I, P, P, P, P, P, P, P, P, P]
         L.lynx_permute.argtypes = [P, I, I, I, P, P, P, P, P]
         L.lynx_pack_weights.argtypes = [P, P, P, I, I, I, P, P, P]
-        L.lynx_moe_ffn.argtypes = [P, P, P, P, P, I, I, P, P, P, P, P, P, I, I, I, I, I, P, P, P]
+        L.lynx_moe_ffn.argtypes = [P, P, P, P, P, I, I, P, P, P, P, P, P, I, I, I, I, I, P, P, P, P]
         L.lynx_moe_ffn_timed.argtypes = L.lynx_moe_ffn.argtypes + [ctypes.POINTER(c_void_p)]
-        L.lynx_moe_layer.argtypes = [P, P, P, P, P, P, P, I, I, I, I, I, I, I, F, I, I] + [P] * 17 + [ctypes.POINTER(c_void_p)]
+        L.lynx_moe_layer.argtypes = [P, P, P, P, P, P, P, I, I, I, I, I, I, I, F, I, I] + [P] * 19 + [ctypes.POINTER(c_void_p)]
         L.lynx_read_probe.argtypes = [P, c_size_t, I, P, P]
         L.lynx_quantize_weights_fp8.argtypes = [P, P, P, I, I, I, P, P, P, P, P]
-        L.lynx_moe_ffn_fp8.argtypes = [P] * 9 + [I, I] + [P] * 6 + [I] * 5 + [P, P, P, ctypes.POINTER(c_void_p)]
-        L.lynx_moe_layer_fp8.argtypes = [P] * 11 + [I] * 7 + [F, I, I] + [P] * 17 + [ctypes.POINTER(c_void_p)]
+        L.lynx_moe_ffn_fp8.argtypes = [P] * 9 + [I, I] + [P] * 6 + [I] * 5 + [P, P, P, P, ctypes.POINTER(c_void_p)]
+        L.lynx_moe_layer_fp8.argtypes = [P] * 11 + [I] * 7 + [F, I, I] + [P] * 19 + [ctypes.POINTER(c_void_p)]
         L.lynx_fp4_scale_words.argtypes = [I, I, I, I]
         L.lynx_quantize_weights_fp4.argtypes = L.lynx_quantize_weights_fp8.argtypes
         L.lynx_moe_ffn_fp4.argtypes = L.lynx_moe_ffn_fp8.argtypes
         L.lynx_moe_layer_fp4.argtypes = L.lynx_moe_layer_fp8.argtypes
         L.lynx_moe_ffn_launches.argtypes = [I, I]
         L.lynx_residual_add.argtypes = [P, P, c_size_t, P, P]
+        L.lynx_debug_set.argtypes = [I, I]
         L.lynx_route_sigmoid.argtypes = L.lynx_route.argtypes
         L.lynx_affinity_bin_sigmoid.argtypes = L.lynx_affinity_bin.argtypes
         L.lynx_moe_layer_sigmoid.argtypes = L.lynx_moe_layer.argtypes
         L.lynx_route_grouped.argtypes = [P, P, P, I, I, I, I, I, I, I, P, P, P, P, P]
-        L.lynx_affinity_bin_grouped.argtypes = [P, I, I, I, I, I, I, F, I, I] + [P] * 11
-        L.lynx_moe_layer_grouped.argtypes = ([P, P, P, P, P, P, P, I, I, I, I, I, I, I, I, I, I, F, I, I] + [P] * 17 +
+        L.lynx_affinity_bin_grouped.argtypes = [P, I, I, I, I, I, I, F, I, I] + [P] * 12
+        L.lynx_moe_layer_grouped.argtypes = ([P, P, P, P, P, P, P, I, I, I, I, I, I, I, I, I, I, F, I, I] + [P] * 19 +
                                              [ctypes.POINTER(c_void_p)])
         for name in SYMBOLS:
             # without declared argument types ctypes passes Python ints as 32-bit C ints: a device pointer would be cut
@@ -161,6 +162,7 @@ def lynx_affinity_bin_grouped(logits, k, n_group, topk_group, alpha, beta, gate_
     o = out or dict(idx=torch.empty((T, k), dtype=I32, device=dev), gate=torch.empty((T, k), dtype=F32, device=dev),
                     psum=torch.empty((T,), dtype=F32, device=dev),
                     new_idx=torch.empty((T, k), dtype=I32, device=dev), new_gate=torch.empty((T, k), dtype=F32, device=dev),
+                    new_psum=torch.empty((T,), dtype=F32, device=dev),
                     cnt_before=torch.empty((N,), dtype=I32, device=dev), cnt_after=torch.empty((N,), dtype=I32, device=dev),
                     bin_hist=torch.empty((N, nb), dtype=I32, device=dev), num_active=torch.empty((2,), dtype=I32, device=dev))
     if workspace is None:
@@ -169,6 +171,7 @@ def lynx_affinity_bin_grouped(logits, k, n_group, topk_group, alpha, beta, gate_
                                            int(gate_fn), float(alpha), int(beta), int(enable), _ptr(o["idx"], I32, "idx"),
                                            _ptr(o["gate"], F32, "gate"), _ptr(o["psum"], F32, "psum"),
                                            _ptr(o["new_idx"], I32, "new_idx"), _ptr(o["new_gate"], F32, "new_gate"),
+                                           _ptr(o.get("new_psum"), F32, "new_psum"),
                                            _ptr(o["cnt_before"], I32, "cnt_before"), _ptr(o["cnt_after"], I32, "cnt_after"),
                                            _ptr(o["bin_hist"], I32, "bin_hist"), _ptr(o["num_active"], I32, "num_active"),
                                            workspace.data_ptr(), _stream()))
@@ -182,6 +185,7 @@ def lynx_affinity_bin(logits, topk_idx, alpha, beta, enable=1, workspace=None, o
     dev = logits.device
     nb = max(int(beta), 1)
     o = out or dict(new_idx=torch.empty((T, k), dtype=I32, device=dev), new_gate=torch.empty((T, k), dtype=F32, device=dev),
+                    new_psum=torch.empty((T,), dtype=F32, device=dev),
                     cnt_before=torch.empty((N,), dtype=I32, device=dev), cnt_after=torch.empty((N,), dtype=I32, device=dev),
                     bin_hist=torch.empty((N, nb), dtype=I32, device=dev), num_active=torch.empty((2,), dtype=I32, device=dev))
     if workspace is None:
@@ -189,7 +193,8 @@ def lynx_affinity_bin(logits, topk_idx, alpha, beta, enable=1, workspace=None, o
     ws = workspace.data_ptr()
     _check(getattr(lib(), _entry)(_ptr(logits, F32, "logits"), _ptr(topk_idx, I32, "topk_idx"), T, N, k, float(alpha),
                                   int(beta), int(enable), _ptr(o["new_idx"], I32, "new_idx"),
-                                  _ptr(o["new_gate"], F32, "new_gate"), _ptr(o["cnt_before"], I32, "cnt_before"),
+                                  _ptr(o["new_gate"], F32, "new_gate"), _ptr(o.get("new_psum"), F32, "new_psum"),
+                                  _ptr(o["cnt_before"], I32, "cnt_before"),
                                   _ptr(o["cnt_after"], I32, "cnt_after"), _ptr(o["bin_hist"], I32, "bin_hist"),
                                   _ptr(o["num_active"], I32, "num_active"), ws, _stream()))
     return o
@@ -207,6 +212,7 @@ def lynx_affinity_bin_biased(logits, topk_idx, alpha, beta, gamma, enable=1, wor
     dev = logits.device
     nb = max(int(beta), 1)
     o = out or dict(new_idx=torch.empty((T, k), dtype=I32, device=dev), new_gate=torch.empty((T, k), dtype=F32, device=dev),
+                    new_psum=torch.empty((T,), dtype=F32, device=dev),
                     cnt_before=torch.empty((N,), dtype=I32, device=dev), cnt_after=torch.empty((N,), dtype=I32, device=dev),
                     bin_hist=torch.empty((N, nb), dtype=I32, device=dev), num_active=torch.empty((2,), dtype=I32, device=dev))
     if workspace is None:
@@ -214,6 +220,7 @@ def lynx_affinity_bin_biased(logits, topk_idx, alpha, beta, gamma, enable=1, wor
     _check(lib().lynx_affinity_bin_biased(_ptr(logits, F32, "logits"), _ptr(topk_idx, I32, "topk_idx"), T, N, k,
                                           float(alpha), int(beta), float(gamma), int(enable),
                                           _ptr(o["new_idx"], I32, "new_idx"), _ptr(o["new_gate"], F32, "new_gate"),
+                                          _ptr(o.get("new_psum"), F32, "new_psum"),
                                           _ptr(o["cnt_before"], I32, "cnt_before"), _ptr(o["cnt_after"], I32, "cnt_after"),
                                           _ptr(o["bin_hist"], I32, "bin_hist"), _ptr(o["num_active"], I32, "num_active"),
                                           workspace.data_ptr(), _stream()))
@@ -245,7 +252,7 @@ def lynx_pack_weights(Wg, Wu, Wd):
 
 
 def lynx_moe_ffn(x, Wgu, Wdp, idx, gate, perm_out, N, F, Sgu=None, Sdp=None, n_shared=0, F_shared=0, workspace=None,
-                 y=None, stage_events=None):
+                 y=None, stage_events=None, status=None):
     """x [T,H] bf16, packed weights, idx/gate [T,k], perm_out = result of lynx_permute -> y [T,H] f32.
     stage_events: optional list of four torch.cuda.Event(enable_timing=True) that have been recorded at
     least once (so that their handles exist); they are re-recorded at the stage boundaries."""
@@ -262,7 +269,7 @@ def lynx_moe_ffn(x, Wgu, Wdp, idx, gate, perm_out, N, F, Sgu=None, Sdp=None, n_s
             _ptr(Sdp, BF16, "Sdp"), n_shared, F_shared, _ptr(idx, I32, "idx"), _ptr(gate, F32, "gate"),
             _ptr(perm_out["offsets"], I32, "offsets"), _ptr(perm_out["perm"], I32, "perm"),
             _ptr(perm_out["active"], I32, "active"), _ptr(perm_out["num_active"], I32, "num_active"),
-            T, H, F, N, k, _ptr(y, F32, "y"), workspace.data_ptr(), _stream())
+            T, H, F, N, k, _ptr(y, F32, "y"), _ptr(status, I32, "status"), workspace.data_ptr(), _stream())
     if stage_events is None:
         _check(lib().lynx_moe_ffn(*args))
     else:
@@ -279,7 +286,8 @@ class LayerBuffers:
         self.sizes = (T, H, F, N, k, n_shared, F_shared)
         self.beta = beta
         self.logits, self.topk_idx, self.topk_gate, self.topk_psum = e((T, N), F32), e((T, k), I32), e((T, k), F32), e((T,), F32)
-        self.new_idx, self.new_gate = e((T, k), I32), e((T, k), F32)
+        self.new_idx, self.new_gate, self.new_psum = e((T, k), I32), e((T, k), F32), e((T,), F32)
+        self.status = e((1,), I32)
         self.cnt_before, self.cnt_after, self.bin_hist, self.num_active = e((N,), I32), e((N,), I32), e((N, beta), I32), e((2,), I32)
         self.offsets, self.perm, self.active, self.num_active_perm = e((N + 1,), I32), e((max(T * k, 1),), I32), e((N,), I32), e((1,), I32)
         self.y = e((T, H), F32)
@@ -298,9 +306,9 @@ def lynx_moe_layer(x, Wr, bias, Wgu, Wdp, F, k, alpha, beta, enable=1, Sgu=None,
         _ptr(x, BF16, "x"), _ptr(Wr, F32, "Wr"), _ptr(bias, F32, "bias"), _ptr(Wgu, BF16, "Wgu"), _ptr(Wdp, BF16, "Wdp"),
         _ptr(Sgu, BF16, "Sgu"), _ptr(Sdp, BF16, "Sdp"), n_shared, F_shared, T, H, F, N, k, float(alpha), int(beta),
         int(enable), b.logits.data_ptr(), b.topk_idx.data_ptr(), b.topk_gate.data_ptr(), b.topk_psum.data_ptr(),
-        b.new_idx.data_ptr(), b.new_gate.data_ptr(), b.cnt_before.data_ptr(), b.cnt_after.data_ptr(),
+        b.new_idx.data_ptr(), b.new_gate.data_ptr(), b.new_psum.data_ptr(), b.cnt_before.data_ptr(), b.cnt_after.data_ptr(),
         b.bin_hist.data_ptr(), b.num_active.data_ptr(), b.offsets.data_ptr(), b.perm.data_ptr(), b.active.data_ptr(),
-        b.num_active_perm.data_ptr(), b.y.data_ptr(), b.workspace.data_ptr(), _stream(),
+        b.num_active_perm.data_ptr(), b.y.data_ptr(), b.status.data_ptr(), b.workspace.data_ptr(), _stream(),
         None if stage_events is None else (c_void_p * 4)(*[e.cuda_event for e in stage_events])))
     return b
 
@@ -324,9 +332,9 @@ def lynx_moe_layer_grouped(x, Wr, bias, Wgu, Wdp, F, k, n_group, topk_group, alp
         _ptr(x, BF16, "x"), _ptr(Wr, F32, "Wr"), _ptr(bias, F32, "bias"), _ptr(Wgu, BF16, "Wgu"), _ptr(Wdp, BF16, "Wdp"),
         _ptr(Sgu, BF16, "Sgu"), _ptr(Sdp, BF16, "Sdp"), n_shared, F_shared, T, H, F, N, k, int(n_group), int(topk_group),
         int(gate_fn), float(alpha), int(beta), int(enable), b.logits.data_ptr(), b.topk_idx.data_ptr(),
-        b.topk_gate.data_ptr(), b.topk_psum.data_ptr(), b.new_idx.data_ptr(), b.new_gate.data_ptr(),
+        b.topk_gate.data_ptr(), b.topk_psum.data_ptr(), b.new_idx.data_ptr(), b.new_gate.data_ptr(), b.new_psum.data_ptr(),
         b.cnt_before.data_ptr(), b.cnt_after.data_ptr(), b.bin_hist.data_ptr(), b.num_active.data_ptr(),
-        b.offsets.data_ptr(), b.perm.data_ptr(), b.active.data_ptr(), b.num_active_perm.data_ptr(), b.y.data_ptr(),
+        b.offsets.data_ptr(), b.perm.data_ptr(), b.active.data_ptr(), b.num_active_perm.data_ptr(), b.y.data_ptr(), b.status.data_ptr(),
         b.workspace.data_ptr(), _stream(),
         None if stage_events is None else (c_void_p * 4)(*[e.cuda_event for e in stage_events])))
     return b
@@ -346,6 +354,14 @@ def lynx_residual_add(x, y, out=None):
     assert x.shape == y.shape == out.shape
     _check(lib().lynx_residual_add(_ptr(x, BF16, "x"), _ptr(y, F32, "y"), x.numel(), _ptr(out, BF16, "out"), _stream()))
     return out
+
+
+DEBUG_SPIN_LIMIT, DEBUG_TARGET_BIAS, DEBUG_DOWN_ITEM_CAP, DEBUG_DOWN_ITEM_UNITS = 1, 2, 3, 4
+
+
+def lynx_debug_set(what: int, value: int):
+    """Process-wide knob of the library (include/lynx_bench.h): tuning runs and the test of the give-up path."""
+    _check(lib().lynx_debug_set(int(what), int(value)))
 
 
 def lynx_moe_ffn_launches(T, F) -> int:
@@ -386,7 +402,7 @@ def _fp8_ptrs(q):
 
 
 def lynx_moe_ffn_fp8(x, q, idx, gate, perm_out, N, F, shared=None, n_shared=0, F_shared=0, workspace=None, y=None,
-                     stage_events=None):
+                     stage_events=None, status=None):
     """lynx_moe_ffn with FP8 weights: q, shared = Fp8Weights of the routed / shared experts."""
     T, H = x.shape
     k = idx.shape[1]
@@ -401,7 +417,7 @@ def lynx_moe_ffn_fp8(x, q, idx, gate, perm_out, N, F, shared=None, n_shared=0, F
                                   _ptr(gate, F32, "gate"), _ptr(perm_out["offsets"], I32, "offsets"),
                                   _ptr(perm_out["perm"], I32, "perm"), _ptr(perm_out["active"], I32, "active"),
                                   _ptr(perm_out["num_active"], I32, "num_active"), T, H, F, N, k, _ptr(y, F32, "y"),
-                                  workspace.data_ptr(), _stream(), ev))
+                                  _ptr(status, I32, "status"), workspace.data_ptr(), _stream(), ev))
     return y
 
 
@@ -418,9 +434,9 @@ def lynx_moe_layer_fp8(x, Wr, bias, q, F, k, alpha, beta, enable=1, shared=None,
     _check(lib().lynx_moe_layer_fp8(
         _ptr(x, BF16, "x"), _ptr(Wr, F32, "Wr"), _ptr(bias, F32, "bias"), a_, b_, c_, d_, sa, sb, sc, sd, n_shared, F_shared,
         T, H, F, N, k, float(alpha), int(beta), int(enable), b.logits.data_ptr(), b.topk_idx.data_ptr(),
-        b.topk_gate.data_ptr(), b.topk_psum.data_ptr(), b.new_idx.data_ptr(), b.new_gate.data_ptr(),
+        b.topk_gate.data_ptr(), b.topk_psum.data_ptr(), b.new_idx.data_ptr(), b.new_gate.data_ptr(), b.new_psum.data_ptr(),
         b.cnt_before.data_ptr(), b.cnt_after.data_ptr(), b.bin_hist.data_ptr(), b.num_active.data_ptr(),
-        b.offsets.data_ptr(), b.perm.data_ptr(), b.active.data_ptr(), b.num_active_perm.data_ptr(), b.y.data_ptr(),
+        b.offsets.data_ptr(), b.perm.data_ptr(), b.active.data_ptr(), b.num_active_perm.data_ptr(), b.y.data_ptr(), b.status.data_ptr(),
         b.workspace.data_ptr(), _stream(),
         None if stage_events is None else (c_void_p * 4)(*[e.cuda_event for e in stage_events])))
     return b
@@ -458,7 +474,7 @@ def _fp4_ptrs(q):
 
 
 def lynx_moe_ffn_fp4(x, q, idx, gate, perm_out, N, F, shared=None, n_shared=0, F_shared=0, workspace=None, y=None,
-                     stage_events=None):
+                     stage_events=None, status=None):
     """lynx_moe_ffn with MXFP4 weights: q, shared = Fp4Weights of the routed / shared experts."""
     T, H = x.shape
     k = idx.shape[1]
@@ -473,7 +489,7 @@ def lynx_moe_ffn_fp4(x, q, idx, gate, perm_out, N, F, shared=None, n_shared=0, F
                                   _ptr(gate, F32, "gate"), _ptr(perm_out["offsets"], I32, "offsets"),
                                   _ptr(perm_out["perm"], I32, "perm"), _ptr(perm_out["active"], I32, "active"),
                                   _ptr(perm_out["num_active"], I32, "num_active"), T, H, F, N, k, _ptr(y, F32, "y"),
-                                  workspace.data_ptr(), _stream(), ev))
+                                  _ptr(status, I32, "status"), workspace.data_ptr(), _stream(), ev))
     return y
 
 
@@ -490,9 +506,9 @@ def lynx_moe_layer_fp4(x, Wr, bias, q, F, k, alpha, beta, enable=1, shared=None,
     _check(lib().lynx_moe_layer_fp4(
         _ptr(x, BF16, "x"), _ptr(Wr, F32, "Wr"), _ptr(bias, F32, "bias"), a_, b_, c_, d_, sa, sb, sc, sd, n_shared, F_shared,
         T, H, F, N, k, float(alpha), int(beta), int(enable), b.logits.data_ptr(), b.topk_idx.data_ptr(),
-        b.topk_gate.data_ptr(), b.topk_psum.data_ptr(), b.new_idx.data_ptr(), b.new_gate.data_ptr(),
+        b.topk_gate.data_ptr(), b.topk_psum.data_ptr(), b.new_idx.data_ptr(), b.new_gate.data_ptr(), b.new_psum.data_ptr(),
         b.cnt_before.data_ptr(), b.cnt_after.data_ptr(), b.bin_hist.data_ptr(), b.num_active.data_ptr(),
-        b.offsets.data_ptr(), b.perm.data_ptr(), b.active.data_ptr(), b.num_active_perm.data_ptr(), b.y.data_ptr(),
+        b.offsets.data_ptr(), b.perm.data_ptr(), b.active.data_ptr(), b.num_active_perm.data_ptr(), b.y.data_ptr(), b.status.data_ptr(),
         b.workspace.data_ptr(), _stream(),
         None if stage_events is None else (c_void_p * 4)(*[e.cuda_event for e in stage_events])))
     return b

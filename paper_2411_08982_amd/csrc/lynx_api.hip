@@ -2,7 +2,8 @@
 #include <stdarg.h>
 #include <stdio.h>
 
-#include "lynx_common.h"
+
+#include "lynx_plan.h"
 
 namespace lynx {
 
@@ -31,15 +32,20 @@ extern "C" const char *lynx_last_error(void) { return lynx::g_last_error; }
 namespace lynx {
 int routing_fused(const uint16_t *x, const float *Wr, const float *bias, int T, int H, int N, int k, float alpha,
                   int beta, int enable, RouterKind rk, float *logits, int32_t *topk_idx, float *topk_gate, float *topk_psum,
-                  int32_t *new_idx, float *new_gate, int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist,
+                  int32_t *new_idx, float *new_gate, float *new_psum, int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist,
                   int32_t *num_active, int32_t *expert_offsets, int32_t *perm, int32_t *active_experts,
-                  int32_t *num_active_perm, void *workspace, hipStream_t st);
+                  int32_t *num_active_perm, void *workspace, hipStream_t st, const PlanShape &ps);
 int check_router_kind(const char *who, int N, int k, const RouterKind &rk);
+PlanShape ffn_plan_shape(int T, int H, int F, int N, int k, int n_shared, int format);
+int moe_ffn_validate(const void *x_bf16, const void *Wgu_packed, const void *Wd_packed, const void *Sgu_packed,
+                     const void *Sd_packed, int n_shared, int F_shared, const void *idx, const void *gate, const void *perm,
+                     const void *offsets, int T, int H, int F, int N, int k, const void *y, const void *workspace,
+                     const FfnScales *q8);
 int moe_ffn_impl(const uint16_t *x_bf16, const uint16_t *Wgu_packed, const uint16_t *Wd_packed, const uint16_t *Sgu_packed,
                  const uint16_t *Sd_packed, int n_shared, int F_shared, const int32_t *idx, const float *gate,
-                 const int32_t *expert_offsets, const int32_t *perm, const int32_t *active_experts,
-                 const int32_t *num_active, int T, int H, int F, int N, int k, float *y, void *workspace, void *stream,
-                 void *const *stage_events, bool counters_cleared, const FfnScales *q8);
+                 const int32_t *expert_offsets, const int32_t *perm, int T, int H, int F, int N, int k, float *y,
+                 int32_t *status, void *workspace, void *stream, void *const *stage_events, bool plan_ready,
+                 const FfnScales *q8);
 }
 
 // The fused path issues the routing side in two launches up to 16 tokens (logits; everything else in one
@@ -50,10 +56,10 @@ static int moe_layer_impl(const uint16_t *x_bf16, const float *Wr, const float *
                           const uint16_t *Wd_packed, const uint16_t *Sgu_packed, const uint16_t *Sd_packed, int n_shared,
                           int F_shared, int T, int H, int F, int N, int k, float alpha, int beta, int enable, float *logits,
                           int32_t *topk_idx, float *topk_gate, float *topk_psum, int32_t *new_idx, float *new_gate,
-                          int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist, int32_t *num_active,
+                          float *new_psum, int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist, int32_t *num_active,
                           int32_t *expert_offsets, int32_t *perm, int32_t *active_experts, int32_t *num_active_perm,
-                          float *y, void *workspace, void *stream, void *const *stage_events, const FfnScales *q8,
-                          RouterKind rk = {0, 1, 1})
+                          float *y, int32_t *status, void *workspace, void *stream, void *const *stage_events,
+                          const FfnScales *q8, RouterKind rk = {0, 1, 1})
 {
     int rc;
     bool fused = false;
@@ -64,8 +70,8 @@ static int moe_layer_impl(const uint16_t *x_bf16, const float *Wr, const float *
                                 topk_psum, stream);
         if (rc != LYNX_OK) return rc;
         rc = lynx_affinity_bin_grouped(logits, T, N, k, rk.n_group, rk.topk_group, gate_fn, alpha, beta, enable, topk_idx,
-                                       topk_gate, topk_psum, new_idx, new_gate, cnt_before, cnt_after, bin_hist, num_active,
-                                       workspace, stream);
+                                       topk_gate, topk_psum, new_idx, new_gate, new_psum, cnt_before, cnt_after, bin_hist,
+                                       num_active, workspace, stream);
         if (rc != LYNX_OK) return rc;
         rc = lynx_permute(new_idx, T, N, k, expert_offsets, perm, active_experts, num_active_perm, stream);
         if (rc != LYNX_OK) return rc;
@@ -75,8 +81,8 @@ static int moe_layer_impl(const uint16_t *x_bf16, const float *Wr, const float *
                                                          stream);
         if (rc != LYNX_OK) return rc;
         rc = (gate_fn ? lynx_affinity_bin_sigmoid : lynx_affinity_bin)(logits, topk_idx, T, N, k, alpha, beta, enable, new_idx,
-                                                                       new_gate, cnt_before, cnt_after, bin_hist, num_active,
-                                                                       workspace, stream);
+                                                                       new_gate, new_psum, cnt_before, cnt_after, bin_hist,
+                                                                       num_active, workspace, stream);
         if (rc != LYNX_OK) return rc;
         rc = lynx_permute(new_idx, T, N, k, expert_offsets, perm, active_experts, num_active_perm, stream);
         if (rc != LYNX_OK) return rc;
@@ -96,24 +102,19 @@ static int moe_layer_impl(const uint16_t *x_bf16, const float *Wr, const float *
         if (!x_bf16 || !Wr || !logits || !topk_idx || !topk_gate || !topk_psum || !new_idx || !new_gate || !cnt_before ||
             !cnt_after || !bin_hist || !num_active || !expert_offsets || !perm || !active_experts || !num_active_perm)
             return fail(LYNX_ERR_INVALID_ARG, "lynx_moe_layer: null pointer");
-        // the FFN's own checks, repeated here so that an error leaves nothing enqueued
-        if (F <= 0 || n_shared < 0 || !Wgu_packed || !Wd_packed || !y ||
-            (n_shared > 0 && (F_shared <= 0 || !Sgu_packed || !Sd_packed)))
-            return fail(LYNX_ERR_INVALID_ARG, "lynx_moe_layer: bad FFN size or null weight / output pointer");
-        const int mult = q8 ? 32 << q8->format : 32;
-        if ((H % mult) != 0 || (F % mult) != 0 || (n_shared > 0 && (F_shared % mult) != 0))
-            return fail(LYNX_ERR_UNSUPPORTED, "lynx_moe_layer: H, F and F_shared must be multiples of %d", mult);
-        if (q8 && (!q8->gu || !q8->d || (n_shared > 0 && (!q8->shared_gu || !q8->shared_d))))
-            return fail(LYNX_ERR_INVALID_ARG, "lynx_moe_layer_fp8: null scale pointer");
-        rc = routing_fused(x_bf16, Wr, bias, T, H, N, k, alpha, beta, enable, rk, logits, topk_idx, topk_gate, topk_psum,
-                           new_idx, new_gate, cnt_before, cnt_after, bin_hist, num_active, expert_offsets, perm,
-                           active_experts, num_active_perm, workspace, (hipStream_t)stream);
+        // the FFN's own checks, made here so that an error leaves nothing enqueued
+        rc = moe_ffn_validate(x_bf16, Wgu_packed, Wd_packed, Sgu_packed, Sd_packed, n_shared, F_shared, new_idx, new_gate, perm,
+                              expert_offsets, T, H, F, N, k, y, workspace, q8);
         if (rc != LYNX_OK) return rc;
-        fused = true;   // its first kernel has also cleared the FFN's completion counters
+        rc = routing_fused(x_bf16, Wr, bias, T, H, N, k, alpha, beta, enable, rk, logits, topk_idx, topk_gate, topk_psum,
+                           new_idx, new_gate, new_psum, cnt_before, cnt_after, bin_hist, num_active, expert_offsets, perm,
+                           active_experts, num_active_perm, workspace, (hipStream_t)stream,
+                           ffn_plan_shape(T, H, F, N, k, n_shared, q8 ? q8->format : 0));
+        if (rc != LYNX_OK) return rc;
+        fused = true;   // its kernels have also cleared the FFN's completion counters and written the work plan
     }
     return moe_ffn_impl(x_bf16, Wgu_packed, Wd_packed, Sgu_packed, Sd_packed, n_shared, F_shared, new_idx, new_gate,
-                        expert_offsets, perm, active_experts, num_active_perm, T, H, F, N, k, y, workspace, stream,
-                        stage_events, fused, q8);
+                        expert_offsets, perm, T, H, F, N, k, y, status, workspace, stream, stage_events, fused, q8);
 }
 }  // namespace lynx
 
@@ -121,30 +122,30 @@ extern "C" int lynx_moe_layer(const uint16_t *x_bf16, const float *Wr, const flo
                               const uint16_t *Wd_packed, const uint16_t *Sgu_packed, const uint16_t *Sd_packed,
                               int n_shared, int F_shared, int T, int H, int F, int N, int k, float alpha, int beta,
                               int enable, float *logits, int32_t *topk_idx, float *topk_gate, float *topk_psum,
-                              int32_t *new_idx, float *new_gate, int32_t *cnt_before, int32_t *cnt_after,
+                              int32_t *new_idx, float *new_gate, float *new_psum, int32_t *cnt_before, int32_t *cnt_after,
                               int32_t *bin_hist, int32_t *num_active, int32_t *expert_offsets, int32_t *perm,
-                              int32_t *active_experts, int32_t *num_active_perm, float *y, void *workspace,
+                              int32_t *active_experts, int32_t *num_active_perm, float *y, int32_t *status, void *workspace,
                               void *stream, void *const *stage_events)
 {
     return lynx::moe_layer_impl(x_bf16, Wr, bias, Wgu_packed, Wd_packed, Sgu_packed, Sd_packed, n_shared, F_shared, T, H, F,
-                                N, k, alpha, beta, enable, logits, topk_idx, topk_gate, topk_psum, new_idx, new_gate,
+                                N, k, alpha, beta, enable, logits, topk_idx, topk_gate, topk_psum, new_idx, new_gate, new_psum,
                                 cnt_before, cnt_after, bin_hist, num_active, expert_offsets, perm, active_experts,
-                                num_active_perm, y, workspace, stream, stage_events, nullptr);
+                                num_active_perm, y, status, workspace, stream, stage_events, nullptr);
 }
 
 extern "C" int lynx_moe_layer_sigmoid(const uint16_t *x_bf16, const float *Wr, const float *bias, const uint16_t *Wgu_packed,
                                       const uint16_t *Wd_packed, const uint16_t *Sgu_packed, const uint16_t *Sd_packed,
                                       int n_shared, int F_shared, int T, int H, int F, int N, int k, float alpha, int beta,
                                       int enable, float *logits, int32_t *topk_idx, float *topk_gate, float *topk_ssum,
-                                      int32_t *new_idx, float *new_gate, int32_t *cnt_before, int32_t *cnt_after,
+                                      int32_t *new_idx, float *new_gate, float *new_psum, int32_t *cnt_before, int32_t *cnt_after,
                                       int32_t *bin_hist, int32_t *num_active, int32_t *expert_offsets, int32_t *perm,
-                                      int32_t *active_experts, int32_t *num_active_perm, float *y, void *workspace,
+                                      int32_t *active_experts, int32_t *num_active_perm, float *y, int32_t *status, void *workspace,
                                       void *stream, void *const *stage_events)
 {
     return lynx::moe_layer_impl(x_bf16, Wr, bias, Wgu_packed, Wd_packed, Sgu_packed, Sd_packed, n_shared, F_shared, T, H, F,
-                                N, k, alpha, beta, enable, logits, topk_idx, topk_gate, topk_ssum, new_idx, new_gate,
+                                N, k, alpha, beta, enable, logits, topk_idx, topk_gate, topk_ssum, new_idx, new_gate, new_psum,
                                 cnt_before, cnt_after, bin_hist, num_active, expert_offsets, perm, active_experts,
-                                num_active_perm, y, workspace, stream, stage_events, nullptr, lynx::RouterKind{1, 1, 1});
+                                num_active_perm, y, status, workspace, stream, stage_events, nullptr, lynx::RouterKind{1, 1, 1});
 }
 
 extern "C" int lynx_moe_layer_grouped(const uint16_t *x_bf16, const float *Wr, const float *bias, const uint16_t *Wgu_packed,
@@ -152,15 +153,15 @@ extern "C" int lynx_moe_layer_grouped(const uint16_t *x_bf16, const float *Wr, c
                                       int n_shared, int F_shared, int T, int H, int F, int N, int k, int n_group,
                                       int topk_group, int gate_fn, float alpha, int beta, int enable, float *logits,
                                       int32_t *topk_idx, float *topk_gate, float *topk_third, int32_t *new_idx,
-                                      float *new_gate, int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist,
+                                      float *new_gate, float *new_psum, int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist,
                                       int32_t *num_active, int32_t *expert_offsets, int32_t *perm, int32_t *active_experts,
-                                      int32_t *num_active_perm, float *y, void *workspace, void *stream,
+                                      int32_t *num_active_perm, float *y, int32_t *status, void *workspace, void *stream,
                                       void *const *stage_events)
 {
     return lynx::moe_layer_impl(x_bf16, Wr, bias, Wgu_packed, Wd_packed, Sgu_packed, Sd_packed, n_shared, F_shared, T, H, F,
-                                N, k, alpha, beta, enable, logits, topk_idx, topk_gate, topk_third, new_idx, new_gate,
+                                N, k, alpha, beta, enable, logits, topk_idx, topk_gate, topk_third, new_idx, new_gate, new_psum,
                                 cnt_before, cnt_after, bin_hist, num_active, expert_offsets, perm, active_experts,
-                                num_active_perm, y, workspace, stream, stage_events, nullptr,
+                                num_active_perm, y, status, workspace, stream, stage_events, nullptr,
                                 lynx::RouterKind{gate_fn, n_group, topk_group});
 }
 
@@ -169,17 +170,17 @@ extern "C" int lynx_moe_layer_fp8(const uint16_t *x_bf16, const float *Wr, const
                                   const uint8_t *Sd_q, const float *shared_scales_gu, const float *shared_scales_d,
                                   int n_shared, int F_shared, int T, int H, int F, int N, int k, float alpha, int beta,
                                   int enable, float *logits, int32_t *topk_idx, float *topk_gate, float *topk_psum,
-                                  int32_t *new_idx, float *new_gate, int32_t *cnt_before, int32_t *cnt_after,
+                                  int32_t *new_idx, float *new_gate, float *new_psum, int32_t *cnt_before, int32_t *cnt_after,
                                   int32_t *bin_hist, int32_t *num_active, int32_t *expert_offsets, int32_t *perm,
-                                  int32_t *active_experts, int32_t *num_active_perm, float *y, void *workspace,
+                                  int32_t *active_experts, int32_t *num_active_perm, float *y, int32_t *status, void *workspace,
                                   void *stream, void *const *stage_events)
 {
     const lynx::FfnScales q = {scales_gu, scales_d, shared_scales_gu, shared_scales_d, 1};
     return lynx::moe_layer_impl(x_bf16, Wr, bias, reinterpret_cast<const uint16_t *>(Wgu_q),
                                 reinterpret_cast<const uint16_t *>(Wd_q), reinterpret_cast<const uint16_t *>(Sgu_q),
                                 reinterpret_cast<const uint16_t *>(Sd_q), n_shared, F_shared, T, H, F, N, k, alpha, beta,
-                                enable, logits, topk_idx, topk_gate, topk_psum, new_idx, new_gate, cnt_before, cnt_after,
-                                bin_hist, num_active, expert_offsets, perm, active_experts, num_active_perm, y, workspace,
+                                enable, logits, topk_idx, topk_gate, topk_psum, new_idx, new_gate, new_psum, cnt_before, cnt_after,
+                                bin_hist, num_active, expert_offsets, perm, active_experts, num_active_perm, y, status, workspace,
                                 stream, stage_events, &q);
 }
 
@@ -188,10 +189,10 @@ extern "C" int lynx_moe_layer_fp4(const uint16_t *x_bf16, const float *Wr, const
                                   const uint8_t *Sgu_q, const uint8_t *Sd_q, const uint32_t *shared_scales_gu,
                                   const uint32_t *shared_scales_d, int n_shared, int F_shared, int T, int H, int F, int N,
                                   int k, float alpha, int beta, int enable, float *logits, int32_t *topk_idx,
-                                  float *topk_gate, float *topk_psum, int32_t *new_idx, float *new_gate,
+                                  float *topk_gate, float *topk_psum, int32_t *new_idx, float *new_gate, float *new_psum,
                                   int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist, int32_t *num_active,
                                   int32_t *expert_offsets, int32_t *perm, int32_t *active_experts,
-                                  int32_t *num_active_perm, float *y, void *workspace, void *stream,
+                                  int32_t *num_active_perm, float *y, int32_t *status, void *workspace, void *stream,
                                   void *const *stage_events)
 {
     const lynx::FfnScales q = {reinterpret_cast<const float *>(scales_gu), reinterpret_cast<const float *>(scales_d),
@@ -200,7 +201,7 @@ extern "C" int lynx_moe_layer_fp4(const uint16_t *x_bf16, const float *Wr, const
     return lynx::moe_layer_impl(x_bf16, Wr, bias, reinterpret_cast<const uint16_t *>(Wgu_q),
                                 reinterpret_cast<const uint16_t *>(Wd_q), reinterpret_cast<const uint16_t *>(Sgu_q),
                                 reinterpret_cast<const uint16_t *>(Sd_q), n_shared, F_shared, T, H, F, N, k, alpha, beta,
-                                enable, logits, topk_idx, topk_gate, topk_psum, new_idx, new_gate, cnt_before, cnt_after,
-                                bin_hist, num_active, expert_offsets, perm, active_experts, num_active_perm, y, workspace,
+                                enable, logits, topk_idx, topk_gate, topk_psum, new_idx, new_gate, new_psum, cnt_before, cnt_after,
+                                bin_hist, num_active, expert_offsets, perm, active_experts, num_active_perm, y, status, workspace,
                                 stream, stage_events, &q);
 }

@@ -186,7 +186,10 @@ constexpr int kWsMember = kWsActive + LYNX_MAX_N;          // LYNX_MAX_N * LYNX_
 constexpr int kWsDone = kWsMember + LYNX_MAX_N * (LYNX_MAX_T / 32);   // FFN: gate/up completion counters
 constexpr int kWsDoneWords = 1024;                         // LYNX_MAX_N routed + (shared expert, token block) pairs
 constexpr int kWsFlags = kWsDone + kWsDoneWords;           // FFN: bit 0 = a bounded wait ran out
-constexpr int kWsRoutingWords = kWsFlags + 16;
+constexpr int kWsPlanHdr = kWsFlags + 16;                  // FFN work plan (lynx_plan.h): header, 16 words
+constexpr int kWsPlanPrefix = kWsPlanHdr + 16;             // block prefix per rank, LYNX_MAX_N + 1 words (padded to 16)
+constexpr int kWsPlanRec = kWsPlanPrefix + LYNX_MAX_N + 16;   // two words per rank
+constexpr int kWsRoutingWords = kWsPlanRec + 2 * LYNX_MAX_N;
 constexpr size_t kWsRoutingBytes = 65536;
 static_assert((size_t)kWsRoutingWords * 4 <= kWsRoutingBytes, "routing scratch does not fit its reservation");
 

@@ -21,7 +21,10 @@
 //     converted to bf16 in registers).
 // Launches: the expert kernel (once or twice) and a small combine.
 
-#include "lynx_common.h"
+#include <atomic>
+
+#include "../../include/lynx_bench.h"
+#include "lynx_plan.h"
 
 namespace lynx {
 
@@ -32,11 +35,31 @@ constexpr int kFfnThreads = 256;
 constexpr int kFfnWaves = kFfnThreads / kWave;
 constexpr int kPF = 8;                       // staged path: weight tiles in flight per wave and matrix
 constexpr int kPFD = 8;                      // direct path: the same (most; see DirectDepth for the depth per format)
-constexpr int kDirectMaxTokens = 16;         // experts with more tokens go to the staged kernel
-constexpr int kTokBlock = 64;                // tokens per pass of the staged path (batches of up to 64 tokens)
-constexpr int kTokBlockBig = 128;            // the same in the kernels launched for larger batches
 constexpr int kStageBytes = 2 * 18432;       // two LDS buffers for the staged token tile
 constexpr int kStageBytesBig = 2 * 128 * (4 * 64 + 16);   // the same in the large-batch kernels (128 tokens x 4 k-steps)
+
+// Optional per-workgroup timeline of the expert kernel (-DLYNX_TIMELINE; measurement builds only): for every workgroup
+// four stamps of the chip-wide 100 MHz clock (start, item known, wait over, work done) and what it was (projection,
+// workgroup index, XCC id), read back with lynx_debug_timeline.  The product build defines none of it.
+#ifdef LYNX_TIMELINE
+constexpr int kTimelineSlots = 1 << 15;
+__device__ unsigned long long g_timeline[kTimelineSlots][6];
+#define LYNX_TS_BEGIN(kind, b)                                                                                         \
+    const int ts_slot_ = (int)blockIdx.x < kTimelineSlots ? (int)blockIdx.x : kTimelineSlots - 1;                      \
+    if (threadIdx.x == 0) {                                                                                            \
+        unsigned xcc_;                                                                                                 \
+        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc_));                                          \
+        g_timeline[ts_slot_][0] = wall_clock64();                                                                      \
+        g_timeline[ts_slot_][4] = ((unsigned long long)(kind) << 32) | (unsigned)(b);                                  \
+        g_timeline[ts_slot_][5] = xcc_ & 0xf;                                                                          \
+        g_timeline[ts_slot_][1] = g_timeline[ts_slot_][2] = g_timeline[ts_slot_][3] = 0;                               \
+    }
+#define LYNX_TS(i)                                                                                                     \
+    if (threadIdx.x == 0) g_timeline[ts_slot_][i] = wall_clock64()
+#else
+#define LYNX_TS_BEGIN(kind, b)
+#define LYNX_TS(i)
+#endif
 
 struct GemmParams {
     const uint16_t *W_routed;   // packed routed weights (gate/up interleaved, or down)
@@ -45,12 +68,13 @@ struct GemmParams {
     const float *sc_shared;     // the same for the shared experts
     const uint16_t *B;          // gate/up: x [T,H]; down: h scratch
     void *out;                  // gate/up: h scratch (bf16); down: o scratch (fp32)
-    const int32_t *offsets, *perm, *active, *num_active;
+    const int32_t *perm;        // pair ids grouped by expert (the token assignment)
+    const int32_t *plan;        // the routing part of the workspace: the work plan (lynx_plan.h)
     int T, N, k, n_shared;
     int R, K;                   // routed: output rows, contraction length
     int ldb_r, ldo_r, ldb_s, ldo_s;   // elements between B rows / output rows, routed and shared
     int Rs, Ks;                 // shared
-    int tiles_r, tiles_s;       // row tiles (workgroups) per routed expert / per shared work item
+    int tiles_r, tiles_s;       // row units per (routed expert, token block) / per shared work item
     int tiles_s_stride;         // tiles_s rounded up so that the token blocks of one shared row tile share an XCD
     int shared_tblocks;         // token blocks that a shared expert's tokens are divided into (1 = not divided)
     int tok_block;              // tokens per block: one pass of the staged path
@@ -66,15 +90,14 @@ struct WorkItem {
     void *out;
     const float *sc;     // FP8 weights: this expert's row scales ([2][R] for gate/up, [R] for down); MXFP4: its scale dwords
     int R, K, tile, Te, off, shared_s, e;
+    int te_all;          // all tokens of the expert (Te bounds this item's token block)
     int ldb, ldo;        // elements between B rows / output rows
-    int tok0;            // shared experts: first token of this work item's token block
+    int tok0;            // first token of this work item's token block
     int kbeg, ksteps;    // slice of the contraction dimension this work item covers, in weight tiles (32 or 64 columns)
     int out_base;        // shared experts: first output row of this work item
     bool valid;
 };
 
-// First half: which expert, from blockIdx and the invoked-expert list (one round trip to memory).  Everything
-// the weight stream needs is known after it, so the weight prefetch can start before the token tables are read.
 // Weight formats WF: 0 = bf16 (a 1 KiB tile is 16 rows x 32 columns), 1 = FP8 E4M3 (16 rows x 64 columns, converted to
 // bf16 in registers; one fp32 scale per row applied to the accumulated sums), 2 = MXFP4 (16 rows x 128 columns:
 // lane l holds row l%16, columns 32*(l/16) .. +31, which is exactly one scale block; converted to bf16 times the
@@ -95,8 +118,17 @@ __host__ __device__ __forceinline__ size_t mx_scale_dwords(int R, int K)
     return (size_t)(DUAL ? R / 16 : R / 32) * mx_kt4(K) * 128;
 }
 
+// What the plan says of a routed work item, handed from the thread that found it to the workgroup.
+struct ItemShared {
+    int e, te, off, tb;
+};
+
+// Which work item workgroup b of a projection is: one round trip to memory.  The shared experts' items come first
+// (static: they see every token); the routed items follow in the plan's order, item = block * per + unit with
+// per = the row units (gate/up) or groups of m row units (down) of one (expert, token block) pair.  Every thread of
+// the workgroup calls this (it holds a barrier).  w.tile = the first row unit of the item, units = how many it covers.
 template <bool DUAL, int WF>
-__device__ __forceinline__ WorkItem resolve_expert(const GemmParams &p, int b)
+__device__ __forceinline__ WorkItem resolve_item(const GemmParams &p, int b, ItemShared *ish, int &units)
 {
     constexpr int KC = TileCols<WF>::value;
     WorkItem w;
@@ -104,20 +136,53 @@ __device__ __forceinline__ WorkItem resolve_expert(const GemmParams &p, int b)
     w.valid = false;
     w.off = 0;
     w.Te = 0;
+    w.te_all = 0;
     w.e = -1;
     w.shared_s = -1;
     w.tok0 = 0;
     w.B = p.B;
     w.out = p.out;
+    units = 1;
     const uint16_t *Wbase;
     if (b >= p.shared_blocks) {
-        const int br = b - p.shared_blocks;
-        const int rank = br / p.tiles_r;
-        w.tile = br % p.tiles_r;
-        const int e = p.active[rank];           // rank < min(N, T*k) <= N: inside the list
-        const int na = min(*p.num_active, p.N);
-        if (rank >= na || e < 0 || e >= p.N) return w;
+        const int idx = b - p.shared_blocks;
+        const int32_t *__restrict__ plan = p.plan;
+        const int tid = threadIdx.x;
+        // everything is requested at once: the header words and, per thread, one rank's prefix entries and record
+        const int B = plan[kWsPlanHdr + kPlanB];
+        const int m = DUAL ? 1 : plan[kWsPlanHdr + kPlanM];
+        int lo = 0, hi = 0, r0 = 0, r1 = 0;
+        if (tid < p.N) {
+            lo = plan[kWsPlanPrefix + tid];
+            hi = plan[kWsPlanPrefix + tid + 1];
+            r0 = plan[kWsPlanRec + 2 * tid];
+            r1 = plan[kWsPlanRec + 2 * tid + 1];
+        }
+        const int mm = m >= 1 ? m : 1;
+        const int per = (p.tiles_r + mm - 1) / mm;
+        if (B <= 0 || idx >= per * B) return w;   // (uniform: the whole workgroup leaves)
+        const int q = idx / per;
+        if (tid < p.N && lo <= q && q < hi) {
+            ish->e = r0 & 0xffff;
+            ish->te = (int)((unsigned)r0 >> 16);
+            ish->off = r1;
+            ish->tb = q - lo;
+        }
+        __syncthreads();
+        const int e = ish->e, te = ish->te, off = ish->off, tb = ish->tb;
+        if (e < 0 || e >= p.N || te <= 0 || off < 0 || off + te > p.T * p.k) return w;
         w.e = e;
+        w.off = off;
+        w.te_all = te;
+        if (te > kDirectMaxTokens) {   // one pass of the staged path: tokens [tok0, Te) of the expert
+            w.tok0 = tb * p.tok_block;
+            w.Te = min(te, w.tok0 + p.tok_block);
+            if (w.tok0 >= te) return w;
+        } else {
+            w.Te = te;
+        }
+        w.tile = (idx % per) * mm;
+        units = min(mm, p.tiles_r - w.tile);
         w.R = p.R;
         w.K = p.K;
         w.ldb = p.ldb_r;
@@ -139,6 +204,7 @@ __device__ __forceinline__ WorkItem resolve_expert(const GemmParams &p, int b)
         w.shared_s = v / p.shared_splits;
         if (w.tile >= p.tiles_s || w.shared_s >= p.n_shared || w.tok0 >= p.T) return w;
         w.Te = p.shared_tblocks > 1 ? min(p.T, w.tok0 + p.tok_block) : p.T;   // tokens [tok0, Te)
+        w.te_all = p.T;
         w.R = p.Rs;
         w.K = p.Ks;
         w.ldb = p.ldb_s;
@@ -161,15 +227,6 @@ __device__ __forceinline__ WorkItem resolve_expert(const GemmParams &p, int b)
     w.W = reinterpret_cast<const uint4 *>(Wbase);
     w.valid = true;
     return w;
-}
-
-// Second half: the routed expert's token range (a second round trip).
-__device__ __forceinline__ void resolve_tokens(const GemmParams &p, WorkItem &w)
-{
-    if (w.shared_s >= 0) return;
-    w.off = p.offsets[w.e];
-    w.Te = p.offsets[w.e + 1] - w.off;
-    if (w.off < 0 || w.Te <= 0 || w.off + w.Te > p.T * p.k) w.valid = false;
 }
 
 // B row (element offset) and output row of the i-th token of the work item; -1 = none.
@@ -510,30 +567,33 @@ __device__ __forceinline__ void stream_direct(const DirectPlan &d, WeightRing &r
 // One expert with <= 16*NT tokens: the four waves are RW row groups x KW slices of K; the slices are
 // summed through LDS at the end.  A row group is one 16-row tile of gate and up (gate/up) or two
 // consecutive 16-row tiles (down), so that every token fragment loaded feeds two MFMAs.
-template <bool DUAL, int NT, int KW, int WF>
-__device__ __forceinline__ void expert_direct(const GemmParams &p, const WorkItem &w, const DirectPlan &d, WeightRing &ring,
-                                              float *red)
+// The two halves of one row unit on the direct path.  direct_stream: the wave's products over its slice of K (the
+// ring arrives with its first turn of weight tiles requested).  direct_finish: the K slices are summed through LDS and
+// the results stored.  Between the two the ring's registers are free, so the caller requests the next unit's first
+// tiles there: they are in flight while this unit's sums are exchanged and written.
+// ro / orow: B row (element offset) and output row of this lane's token column, the same for every unit of an item.
+template <int NT, int KW, int WF>
+__device__ __forceinline__ void direct_stream(const WorkItem &w, const DirectPlan &d, WeightRing &ring, const int (&ro)[NT],
+                                              f32x4 (&acc0)[NT], f32x4 (&acc1)[NT])
 {
     constexpr int KC = TileCols<WF>::value;
+    const int lane = lane_id();
+    const int kbc = d.n > 0 ? d.kb : 0;
+    unsigned boff[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)   // columns without a token fetch nothing and read as zero; their results are never stored
+        boff[nt] = ro[nt] < 0 ? kNoToken : 2u * ((unsigned)ro[nt] + (unsigned)kbc * KC + (unsigned)(lane >> 4) * (KC / 4));
+    clear_acc<NT>(acc0, acc1);
+    stream_direct<NT, WF>(d, ring, token_rows_resource(w.B), boff, acc0, acc1);
+}
+
+template <bool DUAL, int NT, int KW, int WF>
+__device__ __forceinline__ void direct_finish(const WorkItem &w, const DirectPlan &d, const int (&orow)[NT], f32x4 (&acc0)[NT],
+                                              f32x4 (&acc1)[NT], float *red)
+{
     constexpr int NACC = NT * 2;
     const int lane = lane_id(), wv = wave_id();
     const int rw = wv / KW, kw = wv % KW;
-    const int rt = d.rt;
-    const bool rows_ok = d.rows_ok;
-    const int kbc = d.n > 0 ? d.kb : 0;
-
-    int orow[NT];
-    unsigned boff[NT];
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-        int ro;
-        token_rows<DUAL>(p, w, nt * 16 + (lane & 15), ro, orow[nt]);
-        // columns without a token fetch nothing and read as zero; their results are never stored
-        boff[nt] = ro < 0 ? kNoToken : 2u * ((unsigned)ro + (unsigned)kbc * KC + (unsigned)(lane >> 4) * (KC / 4));
-    }
-    f32x4 acc0[NT], acc1[NT];
-    clear_acc<NT>(acc0, acc1);
-    stream_direct<NT, WF>(d, ring, token_rows_resource(w.B), boff, acc0, acc1);
     if (KW > 1) {
         f32x4 *r4 = reinterpret_cast<f32x4 *>(red);   // [rw][kw-1][NACC][lane]
         if (kw > 0) {
@@ -557,12 +617,12 @@ __device__ __forceinline__ void expert_direct(const GemmParams &p, const WorkIte
             }
         }
     }
-    if (kw == 0 && rows_ok) {
+    if (kw == 0 && d.rows_ok) {
         if (DUAL) {
-            epilogue<true, NT, WF>(acc0, acc1, w.out, w.ldo, rt * 16, orow, w.sc, w.R);
+            epilogue<true, NT, WF>(acc0, acc1, w.out, w.ldo, d.rt * 16, orow, w.sc, w.R);
         } else {
-            epilogue<false, NT, WF>(acc0, acc0, w.out, w.ldo, rt * 16, orow, w.sc, w.R);
-            epilogue<false, NT, WF>(acc1, acc1, w.out, w.ldo, rt * 16 + 16, orow, w.sc, w.R);
+            epilogue<false, NT, WF>(acc0, acc0, w.out, w.ldo, d.rt * 16, orow, w.sc, w.R);
+            epilogue<false, NT, WF>(acc1, acc1, w.out, w.ldo, d.rt * 16 + 16, orow, w.sc, w.R);
         }
     }
 }
@@ -701,26 +761,33 @@ __device__ __forceinline__ void expert_staged(const WorkItem &w, const int *rowo
 }
 
 // Both projections of every invoked and shared expert in ONE launch.  Grid: all gate/up workgroups, then
-// all down workgroups; per projection (shared expert, K slice, token block, row tile) items first, then
-// (routed expert rank, tile of 16*RW rows), RW = 4 / KW.  An expert with at most kDirectMaxTokens tokens
-// takes the direct path with the workgroup's four waves as RW row tiles x KW slices of K.  A larger expert
-// takes the staged path, in which a workgroup covers 64 rows: of every KW consecutive workgroups one does the
-// work, in passes of up to 64 (128) tokens, and the others leave.  The gate/up part of the grid ends with spare
-// workgroups: when the last round of live gate/up workgroups is small, each of its workgroups is replaced by four
-// of one row tile (see ffn_kernel).
+// all down workgroups; per projection the shared experts' items first, then the routed items in the order of the
+// device-built plan (lynx_plan.h): live items are contiguous from the front of each part, and a workgroup past them
+// leaves after one load.  A row unit is 16*RW rows of gate and up, or 32*RW rows of down, RW = 4 / KW.  An expert
+// with at most kDirectMaxTokens tokens takes the direct path with the workgroup's four waves as RW row tiles x KW
+// slices of K.  A larger expert takes the staged path, in which a workgroup covers 64 rows: of every KW
+// consecutive workgroups one does the work, one pass of up to 64 (128) tokens per item, and the others leave.  A down
+// item covers m consecutive row units, m chosen on the device from the number of (expert, token block) pairs: few
+// invoked experts get short items that fill the chip, many get fewer, longer ones, whose start-up (tables, first
+// tiles) weighs less.  The gate/up part of the grid ends with spare workgroups: when the last round of live gate/up
+// workgroups is small, each of its workgroups is replaced by four of one row tile (see ffn_kernel).
 //
 // A down workgroup needs the intermediate vectors h of its expert complete.  Every gate/up workgroup adds its
 // row tiles (four, or one) to its expert's counter once its h stores have completed; a down workgroup requests its
-// first weight tiles and then waits for the counter to reach the expert's row tiles.  Workgroups are dispatched in index order, so when a down workgroup runs,
-// every gate/up workgroup has been dispatched, and those wait for nothing: the wait always ends.  It is bounded
-// all the same (on running out it sets a flag in the workspace and goes on), so no wave can hang.  The gain:
-// the down projection's start-up overlaps the tail of gate/up instead of following a launch boundary.
+// first weight tiles and then waits for the counter to reach the expert's row tiles.  Workgroups are dispatched in
+// index order, so when a down workgroup runs, every gate/up workgroup has been dispatched, and those wait for
+// nothing: the wait always ends.  It is bounded all the same: on running out the workgroup sets a flag in the
+// workspace and goes on, so no wave can hang, and the combine kernel turns the flag into NaNs in y and a non-zero
+// status word.  The gain: the down projection's start-up overlaps the tail of gate/up instead of following a launch
+// boundary.
 struct FfnParams {
     GemmParams gu, dn;
     int gu_blocks;
     int block0;       // index of this launch's first workgroup in the (gate/up, down) order
     int gu_split;     // 1: the last, partial round of gate/up workgroups is cut into single row tiles (see ffn_kernel)
     int wait;         // 0: the down workgroups of this launch follow a finished gate/up launch and do not wait
+    int spin_limit;   // polls of a completion counter before a down workgroup gives up
+    int target_bias;  // added to the count a down workgroup waits for (0; tests of the give-up path set it)
     int32_t *done;    // [LYNX_MAX_N] routed experts, then [n_shared * token blocks]; zero before the launch
     int32_t *flags;
 };
@@ -738,28 +805,27 @@ __device__ __forceinline__ int done_slot(const GemmParams &p, const WorkItem &w)
 // sub >= 0 (gate/up, KW = 4 only): the workgroup takes row tile `sub` of the four that workgroup b stands for.
 template <bool DUAL, int KW, bool BIG, int WF>
 __device__ __forceinline__ void expert_work(const GemmParams &p, int b, const FfnParams &fp, char *stage, int *rowoff,
-                                            int *outrow, int sub = -1)
+                                            int *outrow, ItemShared *ish, int sub = -1)
 {
     constexpr int TB = BIG ? kTokBlockBig : kTokBlock;   // tokens per pass
-    WorkItem w = resolve_expert<DUAL, WF>(p, b);
+    int units;
+    LYNX_TS_BEGIN(DUAL ? (sub >= 0 ? 2 : 1) : 0, b);
+    WorkItem w = resolve_item<DUAL, WF>(p, b, ish, units);
     if (!w.valid) return;
     if (sub >= 0) w.tile = w.tile * kFfnWaves + sub;
-    // The weight stream of the direct path starts before the token tables are read (their loads depend on
-    // each other: offsets, then the permutation, then the token rows).
-    // (Not in the large-batch kernels: their staged path needs the registers, and few of their experts are direct.)
-    const DirectPlan plan = plan_direct<DUAL, KW, WF>(w);
-    WeightRing ring;
-    if (!BIG) prefetch_weights<WF>(plan, ring);
-    resolve_tokens(p, w);
-    if (!w.valid) return;
     int32_t *counter = fp.done + done_slot(p, w);
-    if (!DUAL && fp.wait) {   // wait for this expert's (this token block's) intermediate vectors
-        // (gate/up workgroups report row tiles: four each, or one for a workgroup of a single tile)
-        const int target = kFfnWaves * (w.shared_s < 0 ? fp.gu.tiles_r : fp.gu.tiles_s);
+    const int unit0 = w.tile;
+    LYNX_TS(1);
+    // Waits for this expert's (this token block's) intermediate vectors (down projection in the same launch as
+    // gate/up; gate/up workgroups report row tiles: four each, or one for a workgroup of a single tile).
+    auto wait_for_h = [&]() {
+        if (DUAL || !fp.wait) return;
+        const int items = w.shared_s < 0 ? fp.gu.tiles_r * plan_token_blocks(w.te_all, p.tok_block) : fp.gu.tiles_s;
+        const int target = kFfnWaves * items + fp.target_bias;
         if (threadIdx.x == 0) {
             int polls = 0;
             while (load_coherent(counter) < target) {
-                if (++polls > kSpinLimit) {
+                if (++polls > fp.spin_limit) {
                     atomicOr(fp.flags, 1);
                     break;
                 }
@@ -767,47 +833,71 @@ __device__ __forceinline__ void expert_work(const GemmParams &p, int b, const Ff
             }
         }
         __syncthreads();
-    }
-    if (w.Te <= kDirectMaxTokens) {
-        if (BIG) prefetch_weights<WF>(plan, ring);
-        expert_direct<DUAL, 1, KW, WF>(p, w, plan, ring, reinterpret_cast<float *>(stage));
+    };
+    if (w.te_all <= kDirectMaxTokens) {
+        // Direct path.  The weight stream starts before anything else is waited for, and the next unit's first tiles
+        // are requested before this unit's results are exchanged and stored.
+        DirectPlan plan = plan_direct<DUAL, KW, WF>(w);
+        WeightRing ring;
+        prefetch_weights<WF>(plan, ring);
+        int ro[1], orow[1];
+        token_rows<DUAL>(p, w, lane_id() & 15, ro[0], orow[0]);
+        wait_for_h();
+        LYNX_TS(2);
+        for (int un = 0; un < units; ++un) {
+            f32x4 acc0[1], acc1[1];
+            direct_stream<1, KW, WF>(w, plan, ring, ro, acc0, acc1);
+            const DirectPlan done = plan;
+            if (un + 1 < units) {
+                w.tile = unit0 + un + 1;
+                plan = plan_direct<DUAL, KW, WF>(w);
+                prefetch_weights<WF>(plan, ring);
+            }
+            direct_finish<DUAL, 1, KW, WF>(w, done, orow, acc0, acc1, reinterpret_cast<float *>(stage));
+            if (KW > 1 && un + 1 < units) __syncthreads();   // the next unit reuses the K-slice sums in LDS
+        }
     } else {
+        wait_for_h();
+        LYNX_TS(2);
         // staged path: units of 64 rows.  A direct workgroup covers 16*RW rows (gate/up) or 32*RW rows (down).
         constexpr int kRowsPerWG = 16 * (kFfnWaves / KW) * (DUAL ? 1 : 2);
-        constexpr int kUnits = kRowsPerWG >= 64 ? kRowsPerWG / 64 : 1;      // staged units this workgroup does
-        constexpr int kShare = kRowsPerWG >= 64 ? 1 : 64 / kRowsPerWG;      // workgroups that share one unit
+        constexpr int kUnits = kRowsPerWG >= 64 ? kRowsPerWG / 64 : 1;      // staged units per row unit
+        constexpr int kShare = kRowsPerWG >= 64 ? 1 : 64 / kRowsPerWG;      // workgroups that share one staged unit
         // (a gate/up workgroup that shares its unit with others and leaves the work to one of them still reports
         // below: a down workgroup waits for the row tiles of all gate/up workgroups of its expert)
         // (shared experts see every token, so the host knows that they are staged and gives them one workgroup
         // per unit)
         const bool shared = w.shared_s >= 0;
-        const bool leaves = !shared && (w.tile % kShare) != 0;
-        if (leaves && !(DUAL && fp.wait)) return;
-        const int unit0 = shared ? w.tile : (w.tile / kShare) * kUnits;
-        const int units = leaves ? 0 : shared ? 1 : kUnits;
         const int tid = threadIdx.x;
         for (int un = 0; un < units; ++un) {
-            w.tile = unit0 + un;
-            if (w.tile * 64 >= w.R) break;
-            for (int i0 = w.tok0; i0 < w.Te; i0 += TB) {
-                const int nb = min(w.Te - i0, TB);
-                __syncthreads();   // the previous pass has read rowoff / outrow and the stage
-                if (tid < TB) {
-                    int ro, orow;
-                    token_rows<DUAL>(p, w, tid < nb ? i0 + tid : w.Te, ro, orow);
-                    rowoff[tid] = ro;
-                    outrow[tid] = orow;
+            const int tile = unit0 + un;
+            if (!shared && (tile % kShare) != 0) continue;   // leaves the unit to the workgroup it shares it with
+            const int s0 = shared ? tile : (tile / kShare) * kUnits;
+            const int sn = shared ? 1 : kUnits;
+            for (int su = 0; su < sn; ++su) {
+                w.tile = s0 + su;
+                if (w.tile * 64 >= w.R) break;
+                for (int i0 = w.tok0; i0 < w.Te; i0 += TB) {
+                    const int nb = min(w.Te - i0, TB);
+                    __syncthreads();   // the previous pass has read rowoff / outrow and the stage
+                    if (tid < TB) {
+                        int ro, orow;
+                        token_rows<DUAL>(p, w, tid < nb ? i0 + tid : w.Te, ro, orow);
+                        rowoff[tid] = ro;
+                        outrow[tid] = orow;
+                    }
+                    __syncthreads();
+                    if (nb <= 32)
+                        expert_staged<DUAL, 2, 8, WF>(w, rowoff, outrow, stage);
+                    else if (!BIG || nb <= 64)
+                        expert_staged<DUAL, 4, 4, WF>(w, rowoff, outrow, stage);
+                    else
+                        expert_staged<DUAL, 8, 4, WF>(w, rowoff, outrow, stage);
                 }
-                __syncthreads();
-                if (nb <= 32)
-                    expert_staged<DUAL, 2, 8, WF>(w, rowoff, outrow, stage);
-                else if (!BIG || nb <= 64)
-                    expert_staged<DUAL, 4, 4, WF>(w, rowoff, outrow, stage);
-                else
-                    expert_staged<DUAL, 8, 4, WF>(w, rowoff, outrow, stage);
             }
         }
     }
+    LYNX_TS(3);
     if (DUAL && fp.wait) {   // report: this workgroup's part of h is complete in memory
         wait_memory_complete();
         __syncthreads();
@@ -822,6 +912,7 @@ __global__ __launch_bounds__(kFfnThreads, 2) void ffn_kernel(FfnParams fp)
     __shared__ __attribute__((aligned(16))) char stage[BIG ? kStageBytesBig : kStageBytes];
     __shared__ int rowoff[BIG ? kTokBlockBig : kTokBlock];   // staged path: element offset of each token's B row, -1 = none
     __shared__ int outrow[BIG ? kTokBlockBig : kTokBlock];   // staged path: output row of each token, -1 = none
+    __shared__ ItemShared ish;
     const int b = blockIdx.x + fp.block0;
     if (b < fp.gu_blocks) {
         // Gate/up workgroups take four row tiles, one per wave, and the dispatcher hands workgroups to the CUs
@@ -834,7 +925,7 @@ __global__ __launch_bounds__(kFfnThreads, 2) void ffn_kernel(FfnParams fp)
         // (bf16 weights only: in the kernels of the quantised formats the second code path costs spilled registers)
         int bb = b, sub = -1;
         if (WF == 0 && fp.gu_split) {
-            const int live = fp.gu.shared_blocks + min(*fp.gu.num_active, fp.gu.N) * fp.gu.tiles_r;
+            const int live = fp.gu.shared_blocks + max(fp.gu.plan[kWsPlanHdr + kPlanB], 0) * fp.gu.tiles_r;
             const int full = live / kSplitRound * kSplitRound, rem = live - full;
             if (rem > 0 && rem <= kSplitMaxRem && full >= fp.gu.shared_blocks && b >= full) {
                 bb = full + (b - full) / kFfnWaves;
@@ -842,30 +933,51 @@ __global__ __launch_bounds__(kFfnThreads, 2) void ffn_kernel(FfnParams fp)
                 if (bb >= live) return;
             }
         }
-        if (sub < 0 && bb >= fp.gu.shared_blocks + fp.gu.routed_blocks) return;   // the workgroups the split may need
         if (WF != 0 || sub < 0)
-            expert_work<true, 1, BIG, WF>(fp.gu, bb, fp, stage, rowoff, outrow);
+            expert_work<true, 1, BIG, WF>(fp.gu, bb, fp, stage, rowoff, outrow, &ish);
         else if constexpr (WF == 0)
-            expert_work<true, kFfnWaves, BIG, WF>(fp.gu, bb, fp, stage, rowoff, outrow, sub);
+            expert_work<true, kFfnWaves, BIG, WF>(fp.gu, bb, fp, stage, rowoff, outrow, &ish, sub);
     } else {
-        expert_work<false, KWD, BIG, WF>(fp.dn, b - fp.gu_blocks, fp, stage, rowoff, outrow);
+        expert_work<false, KWD, BIG, WF>(fp.dn, b - fp.gu_blocks, fp, stage, rowoff, outrow, &ish);
     }
 }
 
-__global__ __launch_bounds__(256) void clear_kernel(int32_t *p, int n)
+// The plan from a caller's token assignment (lynx_moe_ffn after lynx_permute): the experts with a valid, non-empty
+// range in expert_offsets are the invoked ones.  One workgroup; also clears the completion counters and the flags.
+__global__ __launch_bounds__(256) void plan_kernel(const int32_t *__restrict__ offsets, int N, int P, PlanShape ps,
+                                                   int32_t *__restrict__ ws)
 {
-    const int i = blockIdx.x * 256 + threadIdx.x;
-    if (i < n) p[i] = 0;
+    __shared__ int count[LYNX_MAX_N], offs[LYNX_MAX_N];
+    const int tid = threadIdx.x;
+    for (int i = tid; i < kWsDoneWords + 16; i += 256) ws[kWsDone + i] = 0;
+    if (tid < N) {
+        const int o0 = offsets[tid], o1 = offsets[tid + 1];
+        const bool ok = o0 >= 0 && o1 > o0 && o1 <= P;
+        count[tid] = ok ? o1 - o0 : 0;
+        offs[tid] = ok ? o0 : 0;
+    }
+    __syncthreads();
+    build_plan<256>(ps, N, count, offs, ws);
 }
 
-// y[t] = sum_j gate[t,j] * o[t*k+j] + sum_s o[P + s*T + t]
+// y[t] = sum_j gate[t,j] * o[t*k+j] + sum_s o[P + s*T + t].  If a workgroup of the expert kernel gave up a bounded wait
+// (flags != 0: some rows of o may then be computed from incomplete intermediate vectors) every element of y becomes NaN
+// and *status (if given) 1, else *status 0: a failed hand-over cannot pass for a result.
 __global__ __launch_bounds__(256) void combine_kernel(const float *__restrict__ o, const int32_t *__restrict__ idx,
                                                       const float *__restrict__ gate, int T, int H, int N, int k,
-                                                      int n_shared, float *__restrict__ y)
+                                                      int n_shared, float *__restrict__ y,
+                                                      const int32_t *__restrict__ flags, int32_t *__restrict__ status)
 {
     const int t = blockIdx.y;
     const int h = (blockIdx.x * 256 + threadIdx.x) * 4;
+    const bool failed = *flags != 0;
+    if (status && t == 0 && blockIdx.x == 0 && threadIdx.x == 0) *status = failed ? 1 : 0;
     if (h >= H) return;
+    if (failed) {
+        const float q = __int_as_float(0x7fc00000);
+        *reinterpret_cast<float4 *>(y + (size_t)t * H + h) = make_float4(q, q, q, q);
+        return;
+    }
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int j = 0; j < k; ++j) {
         const int e = idx[(size_t)t * k + j];
@@ -1076,9 +1188,54 @@ static int pick_k_waves(int K, bool dual, int T, int max_experts, int bits_per_w
     return kw;
 }
 
-static void set_tiles(GemmParams &p, int rows_per_wg)
+// Knobs that tuning runs and the test of the give-up path set through lynx_debug_set (lynx_bench.h); the defaults are
+// what the library ships with.
+struct Tunables {
+    std::atomic<int> spin_limit{kSpinLimit};
+    std::atomic<int> target_bias{0};
+    std::atomic<int> dn_cap{768};      // down items the grid aims at (two per CU are resident: 512)
+    std::atomic<int> dn_m_max{1};      // most row units per down item
+};
+static Tunables g_tune;
+
+// Everything the host decides from the sizes alone.
+struct FfnShape {
+    int kwd;            // K slices of a down workgroup's waves
+    bool big, single;   // 128-token staged passes; one launch for both projections
+    int tok_block;
+    int max_blocks;     // most (expert, token block) pairs of a batch
+    PlanShape plan;
+};
+
+static bool single_launch(int T, int F) { return T > kDirectMaxTokens && (F + 63) / 64 <= 64; }
+
+static FfnShape ffn_shape(int T, int H, int F, int N, int k, int n_shared, int format)
 {
-    p.tiles_r = (p.R + rows_per_wg - 1) / rows_per_wg;
+    FfnShape s;
+    const int max_experts = (int)min((long)N, (long)T * k) + n_shared;
+    s.kwd = pick_k_waves(F, false, T, max_experts, 16 >> format);
+    s.big = T > kTokBlock;
+    s.single = single_launch(T, F);
+    s.tok_block = s.big ? kTokBlockBig : kTokBlock;
+    s.max_blocks = plan_max_blocks(T, N, k, s.tok_block);
+    const int rows_dn = 16 * (kFfnWaves / s.kwd) * 2;
+    s.plan.units_gu = (F + 16 * kFfnWaves - 1) / (16 * kFfnWaves);
+    s.plan.units_dn = (H + rows_dn - 1) / rows_dn;
+    s.plan.tok_block = s.tok_block;
+    // Longer down items only where the staged unit and the direct workgroup are the same 64 rows (two K slices).
+    s.plan.dn_m_max = s.kwd == 2 ? max(1, g_tune.dn_m_max.load()) : 1;
+    s.plan.dn_cap = max(1, g_tune.dn_cap.load());
+    return s;
+}
+
+PlanShape ffn_plan_shape(int T, int H, int F, int N, int k, int n_shared, int format)
+{
+    return ffn_shape(T, H, F, N, k, n_shared, format).plan;
+}
+
+static void set_tiles(GemmParams &p, int units_r, int rows_per_wg, int routed_items)
+{
+    p.tiles_r = units_r;
     // shared experts process all T tokens: staged (units of 64 rows, one per workgroup) when T is past the direct limit
     const int rows_shared = p.T > kDirectMaxTokens ? 64 : rows_per_wg;
     p.tiles_s = p.n_shared ? (p.Rs + rows_shared - 1) / rows_shared : 0;
@@ -1088,7 +1245,7 @@ static void set_tiles(GemmParams &p, int rows_per_wg)
     p.shared_tblocks = p.T > kDirectMaxTokens ? (p.T + p.tok_block - 1) / p.tok_block : 1;
     p.tiles_s_stride = p.shared_tblocks > 1 ? (p.tiles_s + 7) / 8 * 8 : p.tiles_s;
     p.shared_blocks = p.n_shared * p.shared_splits * p.shared_tblocks * p.tiles_s_stride;
-    p.routed_blocks = (int)min((long)p.N, (long)p.T * p.k) * p.tiles_r;   // at most min(N, T*k) experts are invoked
+    p.routed_blocks = routed_items;
 }
 
 static unsigned grid_blocks(const GemmParams &p) { return (unsigned)(p.shared_blocks + p.routed_blocks); }
@@ -1104,13 +1261,10 @@ template <int KWD, bool BIG, int WF>
 static int launch_padded(const FfnParams &fp, unsigned blocks, hipStream_t st)
 {
     static_assert(kLdsTargetPerWg * (kWgPerCu + 1) > kLdsPerCu && kLdsTargetPerWg * kWgPerCu <= kLdsPerCu, "LDS pad");
-    static int pad = -1;   // per instantiation
-    if (pad < 0) {
-        hipFuncAttributes attr;
-        if (hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(&ffn_kernel<KWD, BIG, WF>)) != hipSuccess)
-            return fail(LYNX_ERR_HIP, "lynx_moe_ffn: hipFuncGetAttributes failed");
-        pad = max(0, kLdsTargetPerWg - (int)attr.sharedSizeBytes);
-    }
+    // what the kernel declares itself: the stage, the two token tables and the item record
+    constexpr int kStatic = (BIG ? kStageBytesBig : kStageBytes) + 2 * 4 * (BIG ? kTokBlockBig : kTokBlock) + (int)sizeof(ItemShared);
+    constexpr int pad = kLdsTargetPerWg > kStatic ? kLdsTargetPerWg - kStatic : 0;
+    static_assert((kStatic + pad) * kWgPerCu <= kLdsPerCu, "two workgroups must fit a CU");
     hipLaunchKernelGGL((ffn_kernel<KWD, BIG, WF>), dim3(blocks), dim3(kFfnThreads), pad, st, fp);
     return LYNX_OK;
 }
@@ -1120,18 +1274,15 @@ static int launch_padded(const FfnParams &fp, unsigned blocks, hipStream_t st)
 // launch is 3-12 % faster (the down projection fills the tail of gate/up and there is one start-up less); with
 // huge experts (hundreds of gate/up workgroups each, whose completion reports then cost more than the overlap
 // gains) or at most 16 tokens it is equal or slower.
-static bool single_launch(int T, int F) { return T > kDirectMaxTokens && (F + 63) / 64 <= 64; }
 
 // Gate/up and down over all invoked and shared experts.  Batches of more than 64 tokens take the
 // kernels whose staged path makes passes of up to 128 tokens.
 template <int WF>
-static int launch_ffn(FfnParams fp, hipStream_t st)
+static int launch_ffn(FfnParams fp, const FfnShape &sh, hipStream_t st)
 {
     const GemmParams &d = fp.dn;
-    const int max_experts = (int)min((long)d.N, (long)d.T * d.k) + d.n_shared;
-    const int kwd = pick_k_waves(d.K, false, d.T, max_experts, 16 >> WF);
-    set_tiles(fp.gu, 16 * kFfnWaves);                    // gate/up: four row tiles per workgroup
-    set_tiles(fp.dn, 16 * (kFfnWaves / kwd) * 2);
+    set_tiles(fp.gu, sh.plan.units_gu, 16 * kFfnWaves, sh.plan.units_gu * sh.max_blocks);   // gate/up: four row tiles per workgroup
+    set_tiles(fp.dn, sh.plan.units_dn, 16 * (kFfnWaves / sh.kwd) * 2, plan_down_grid(sh.plan, sh.max_blocks));
     // the split of the last round needs up to three more workgroups per workgroup it replaces
     // (not for batches of more than 32 tokens: more and more experts are then on the staged path, whose unit is the
     // whole workgroup of four row tiles, and three of the four small workgroups only find out that they leave;
@@ -1139,18 +1290,16 @@ static int launch_ffn(FfnParams fp, hipStream_t st)
     fp.gu_split = (WF == 0 && d.T <= kSplitMaxTokens && fp.gu.shared_blocks < kSplitRound) ? 1 : 0;
     fp.gu_blocks = (int)grid_blocks(fp.gu) + (fp.gu_split ? kSplitMaxRem * (kFfnWaves - 1) : 0);
     const unsigned dn_blocks = grid_blocks(fp.dn);
-    const bool big = d.T > kTokBlock;
-    const bool single = single_launch(d.T, d.K);
     int rc = LYNX_OK;
-    for (int part = 0; part < (single ? 1 : 2) && rc == LYNX_OK; ++part) {
-        fp.wait = single ? 1 : 0;
+    for (int part = 0; part < (sh.single ? 1 : 2) && rc == LYNX_OK; ++part) {
+        fp.wait = sh.single ? 1 : 0;
         fp.block0 = part == 0 ? 0 : fp.gu_blocks;
-        const unsigned blocks = single ? (unsigned)fp.gu_blocks + dn_blocks : part == 0 ? (unsigned)fp.gu_blocks : dn_blocks;
-        if (big)
+        const unsigned blocks = sh.single ? (unsigned)fp.gu_blocks + dn_blocks : part == 0 ? (unsigned)fp.gu_blocks : dn_blocks;
+        if (sh.big)
             rc = launch_padded<2, true, WF>(fp, blocks, st);
-        else if (kwd == 4)
+        else if (sh.kwd == 4)
             rc = launch_padded<4, false, WF>(fp, blocks, st);
-        else if (kwd == 2)
+        else if (sh.kwd == 2)
             rc = launch_padded<2, false, WF>(fp, blocks, st);
         else
             rc = launch_padded<1, false, WF>(fp, blocks, st);
@@ -1163,13 +1312,36 @@ static int launch_ffn(FfnParams fp, hipStream_t st)
 
 extern "C" size_t lynx_workspace_bytes(int T, int H, int F, int N, int k, int n_shared, int F_shared)
 {
+    // (N does not enter: the tables per expert are reserved for LYNX_MAX_N experts, inside the first 64 KiB)
     if (T < 0 || H < 0 || F < 0 || N < 0 || k < 0 || n_shared < 0 || F_shared < 0) return 0;
-    (void)N;
     if (n_shared == 0) F_shared = 0;
     return lynx::workspace_layout(T, H, F, k, n_shared, F_shared, lynx::shared_down_splits(F, n_shared, F_shared)).total;
 }
 
 extern "C" int lynx_moe_ffn_launches(int T, int F) { return lynx::single_launch(T, F) ? 1 : 2; }
+
+extern "C" int lynx_debug_set(int what, int value)
+{
+    using namespace lynx;
+    switch (what) {
+    case LYNX_DEBUG_SPIN_LIMIT: g_tune.spin_limit.store(value < 0 ? kSpinLimit : value); return LYNX_OK;
+    case LYNX_DEBUG_TARGET_BIAS: g_tune.target_bias.store(value); return LYNX_OK;
+    case LYNX_DEBUG_DOWN_ITEM_CAP: g_tune.dn_cap.store(value <= 0 ? 768 : value); return LYNX_OK;
+    case LYNX_DEBUG_DOWN_ITEM_UNITS: g_tune.dn_m_max.store(value <= 0 ? 1 : value); return LYNX_OK;
+    default: return fail(LYNX_ERR_INVALID_ARG, "lynx_debug_set: unknown knob %d", what);
+    }
+}
+
+#ifdef LYNX_TIMELINE
+// Measurement builds only: copies the timeline of the last expert-kernel launch to a HOST array of n x 6 uint64.
+extern "C" int lynx_debug_timeline(unsigned long long *host_out, int n)
+{
+    if (n > lynx::kTimelineSlots) n = lynx::kTimelineSlots;
+    return hipMemcpyFromSymbol(host_out, HIP_SYMBOL(lynx::g_timeline), (size_t)n * 6 * sizeof(unsigned long long)) == hipSuccess
+               ? LYNX_OK
+               : LYNX_ERR_HIP;
+}
+#endif
 
 extern "C" int lynx_pack_weights(const uint16_t *Wg, const uint16_t *Wu, const uint16_t *Wd, int E, int H, int F,
                                  uint16_t *Wgu_packed, uint16_t *Wd_packed, void *stream)
@@ -1193,19 +1365,13 @@ extern "C" int lynx_pack_weights(const uint16_t *Wg, const uint16_t *Wu, const u
 
 namespace lynx {
 
-// counters_cleared: the caller has already had the completion counters in the workspace cleared on `stream`
-// (the fused layer path does it in its first kernel); otherwise a small launch clears them here.
-int moe_ffn_impl(const uint16_t *x_bf16, const uint16_t *Wgu_packed, const uint16_t *Wd_packed, const uint16_t *Sgu_packed,
-                 const uint16_t *Sd_packed, int n_shared, int F_shared, const int32_t *idx, const float *gate,
-                 const int32_t *expert_offsets, const int32_t *perm, const int32_t *active_experts,
-                 const int32_t *num_active, int T, int H, int F, int N, int k, float *y, void *workspace, void *stream,
-                 void *const *stage_events, bool counters_cleared, const FfnScales *q8)
+// Every check of the FFN call that needs no device: sizes, limits, pointers.  lynx_moe_layer runs it before its
+// routing kernels are enqueued, so that an error leaves nothing behind.
+int moe_ffn_validate(const void *x_bf16, const void *Wgu_packed, const void *Wd_packed, const void *Sgu_packed,
+                     const void *Sd_packed, int n_shared, int F_shared, const void *idx, const void *gate, const void *perm,
+                     const void *offsets, int T, int H, int F, int N, int k, const void *y, const void *workspace,
+                     const FfnScales *q8)
 {
-    auto mark = [&](int i) -> int {
-        if (!stage_events || !stage_events[i]) return LYNX_OK;
-        const hipError_t err = hipEventRecord((hipEvent_t)stage_events[i], (hipStream_t)stream);
-        return err == hipSuccess ? LYNX_OK : fail(LYNX_ERR_HIP, "lynx_moe_ffn_timed: hipEventRecord: %s", hipGetErrorString(err));
-    };
     if (T < 0 || H <= 0 || F <= 0 || N <= 0 || k <= 0 || n_shared < 0)
         return fail(LYNX_ERR_INVALID_ARG, "lynx_moe_ffn: bad size");
     if (n_shared > 0 && (F_shared <= 0 || !Sgu_packed || !Sd_packed))
@@ -1218,14 +1384,39 @@ int moe_ffn_impl(const uint16_t *x_bf16, const uint16_t *Wgu_packed, const uint1
     if (q8 && (!q8->gu || !q8->d || (n_shared > 0 && (!q8->shared_gu || !q8->shared_d))))
         return fail(LYNX_ERR_INVALID_ARG, "lynx_moe_ffn_fp8: null scale pointer");
     if (T == 0) return LYNX_OK;
-    if (!x_bf16 || !Wgu_packed || !Wd_packed || !idx || !gate || !expert_offsets || !perm || !active_experts ||
-        !num_active || !y || !workspace)
+    if (!x_bf16 || !Wgu_packed || !Wd_packed || !idx || !gate || !offsets || !perm || !y || !workspace)
         return fail(LYNX_ERR_INVALID_ARG, "lynx_moe_ffn: null pointer");
     if (n_shared == 0) F_shared = 0;
     const int tok_block = T > kTokBlock ? kTokBlockBig : kTokBlock;
     if (LYNX_MAX_N + (long)n_shared * ((T + tok_block - 1) / tok_block) > kWsDoneWords)
         return fail(LYNX_ERR_UNSUPPORTED, "lynx_moe_ffn: too many shared experts for this batch size (n_shared=%d T=%d)",
                     n_shared, T);
+    const Workspace ws = workspace_layout(T, H, F, k, n_shared, F_shared, shared_down_splits(F, n_shared, F_shared));
+    // (token rows are addressed with 32-bit byte offsets below 2 GiB)
+    if (ws.h_elems >= 0x3fffffffull || (unsigned long long)T * H >= 0x3fffffffull || ws.o_elems >= 0x7fffffffull * 4)
+        return fail(LYNX_ERR_UNSUPPORTED, "lynx_moe_ffn: scratch index would overflow 32 bits");
+    return LYNX_OK;
+}
+
+// plan_ready: the caller has already had the completion counters in the workspace cleared and the work plan written
+// on `stream` (the fused layer path does both in its routing kernels); otherwise a small launch does it here from
+// expert_offsets.
+int moe_ffn_impl(const uint16_t *x_bf16, const uint16_t *Wgu_packed, const uint16_t *Wd_packed, const uint16_t *Sgu_packed,
+                 const uint16_t *Sd_packed, int n_shared, int F_shared, const int32_t *idx, const float *gate,
+                 const int32_t *expert_offsets, const int32_t *perm, int T, int H, int F, int N, int k, float *y,
+                 int32_t *status, void *workspace, void *stream, void *const *stage_events, bool plan_ready,
+                 const FfnScales *q8)
+{
+    auto mark = [&](int i) -> int {
+        if (!stage_events || !stage_events[i]) return LYNX_OK;
+        const hipError_t err = hipEventRecord((hipEvent_t)stage_events[i], (hipStream_t)stream);
+        return err == hipSuccess ? LYNX_OK : fail(LYNX_ERR_HIP, "lynx_moe_ffn_timed: hipEventRecord: %s", hipGetErrorString(err));
+    };
+    int rc = moe_ffn_validate(x_bf16, Wgu_packed, Wd_packed, Sgu_packed, Sd_packed, n_shared, F_shared, idx, gate, perm,
+                              expert_offsets, T, H, F, N, k, y, workspace, q8);
+    if (rc != LYNX_OK || T == 0) return rc;
+    if (n_shared == 0) F_shared = 0;
+    const int mult = q8 ? 32 << q8->format : 32;
     // K slices of a shared expert's down projection.  The workspace is sized for the most there can be; a slice holds
     // whole weight tiles, ceil(tiles / slices) of them, so fewer slices may already cover all tiles: an empty slice
     // would leave its output rows unwritten, and the combine adds every slice's rows.
@@ -1240,18 +1431,14 @@ int moe_ffn_impl(const uint16_t *x_bf16, const uint16_t *Wgu_packed, const uint1
             splits = need;
         }
     }
-    // (token rows are addressed with 32-bit byte offsets below 2 GiB)
-    if (ws.h_elems >= 0x3fffffffull || (unsigned long long)T * H >= 0x3fffffffull || ws.o_elems >= 0x7fffffffull * 4)
-        return fail(LYNX_ERR_UNSUPPORTED, "lynx_moe_ffn: scratch index would overflow 32 bits");
     uint16_t *hbuf = reinterpret_cast<uint16_t *>(reinterpret_cast<char *>(workspace) + ws.h_off);
     float *obuf = reinterpret_cast<float *>(reinterpret_cast<char *>(workspace) + ws.o_off);
     int32_t *rws = reinterpret_cast<int32_t *>(workspace);
     hipStream_t st = (hipStream_t)stream;
-    int rc;
-    if (!counters_cleared) {
-        hipLaunchKernelGGL(clear_kernel, dim3((kWsDoneWords + 16 + 255) / 256), dim3(256), 0, st, rws + kWsDone,
-                           kWsDoneWords + 16);
-        rc = check_launch("lynx_moe_ffn(clear)");
+    const FfnShape shape = ffn_shape(T, H, F, N, k, n_shared, q8 ? q8->format : 0);
+    if (!plan_ready) {
+        hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(256), 0, st, expert_offsets, N, T * k, shape.plan, rws);
+        rc = check_launch("lynx_moe_ffn(plan)");
         if (rc != LYNX_OK) return rc;
     }
 
@@ -1259,11 +1446,11 @@ int moe_ffn_impl(const uint16_t *x_bf16, const uint16_t *Wgu_packed, const uint1
     fp.done = rws + kWsDone;
     fp.flags = rws + kWsFlags;
     fp.gu_blocks = 0;
+    fp.spin_limit = g_tune.spin_limit.load();
+    fp.target_bias = g_tune.target_bias.load();
     GemmParams p;
-    p.offsets = expert_offsets;
     p.perm = perm;
-    p.active = active_experts;
-    p.num_active = num_active;
+    p.plan = rws;
     p.T = T;
     p.N = N;
     p.k = k;
@@ -1303,7 +1490,7 @@ int moe_ffn_impl(const uint16_t *x_bf16, const uint16_t *Wgu_packed, const uint1
     fp.dn = p;
     rc = mark(0);
     if (rc != LYNX_OK) return rc;
-    rc = !q8 ? launch_ffn<0>(fp, st) : q8->format == 2 ? launch_ffn<2>(fp, st) : launch_ffn<1>(fp, st);
+    rc = !q8 ? launch_ffn<0>(fp, shape, st) : q8->format == 2 ? launch_ffn<2>(fp, shape, st) : launch_ffn<1>(fp, shape, st);
     if (rc != LYNX_OK) return rc;
     rc = mark(1);
     if (rc != LYNX_OK) return rc;
@@ -1311,7 +1498,7 @@ int moe_ffn_impl(const uint16_t *x_bf16, const uint16_t *Wgu_packed, const uint1
     if (rc != LYNX_OK) return rc;
 
     hipLaunchKernelGGL(combine_kernel, dim3((H / 4 + 255) / 256, T), dim3(256), 0, st, obuf, idx, gate, T, H, N, k,
-                       n_shared * splits, y);
+                       n_shared * splits, y, fp.flags, status);
     rc = check_launch("lynx_moe_ffn(combine)");
     if (rc != LYNX_OK) return rc;
     return mark(3);
@@ -1323,12 +1510,14 @@ extern "C" int lynx_moe_ffn_timed(const uint16_t *x_bf16, const uint16_t *Wgu_pa
                                   const uint16_t *Sgu_packed, const uint16_t *Sd_packed, int n_shared, int F_shared,
                                   const int32_t *idx, const float *gate, const int32_t *expert_offsets,
                                   const int32_t *perm, const int32_t *active_experts, const int32_t *num_active, int T,
-                                  int H, int F, int N, int k, float *y, void *workspace, void *stream,
+                                  int H, int F, int N, int k, float *y, int32_t *status, void *workspace, void *stream,
                                   void *const *stage_events)
 {
+    (void)active_experts;   // the invoked experts are those with a non-empty range in expert_offsets
+    (void)num_active;
     return lynx::moe_ffn_impl(x_bf16, Wgu_packed, Wd_packed, Sgu_packed, Sd_packed, n_shared, F_shared, idx, gate,
-                              expert_offsets, perm, active_experts, num_active, T, H, F, N, k, y, workspace, stream,
-                              stage_events, false, nullptr);
+                              expert_offsets, perm, T, H, F, N, k, y, status, workspace, stream, stage_events, false,
+                              nullptr);
 }
 
 extern "C" int lynx_moe_ffn_fp8(const uint16_t *x_bf16, const uint8_t *Wgu_q, const uint8_t *Wd_q, const float *scales_gu,
@@ -1336,13 +1525,15 @@ extern "C" int lynx_moe_ffn_fp8(const uint16_t *x_bf16, const uint8_t *Wgu_q, co
                                 const float *shared_scales_gu, const float *shared_scales_d, int n_shared, int F_shared,
                                 const int32_t *idx, const float *gate, const int32_t *expert_offsets, const int32_t *perm,
                                 const int32_t *active_experts, const int32_t *num_active, int T, int H, int F, int N,
-                                int k, float *y, void *workspace, void *stream, void *const *stage_events)
+                                int k, float *y, int32_t *status, void *workspace, void *stream, void *const *stage_events)
 {
+    (void)active_experts;
+    (void)num_active;
     const lynx::FfnScales q = {scales_gu, scales_d, shared_scales_gu, shared_scales_d, 1};
     return lynx::moe_ffn_impl(x_bf16, reinterpret_cast<const uint16_t *>(Wgu_q), reinterpret_cast<const uint16_t *>(Wd_q),
                               reinterpret_cast<const uint16_t *>(Sgu_q), reinterpret_cast<const uint16_t *>(Sd_q), n_shared,
-                              F_shared, idx, gate, expert_offsets, perm, active_experts, num_active, T, H, F, N, k, y,
-                              workspace, stream, stage_events, false, &q);
+                              F_shared, idx, gate, expert_offsets, perm, T, H, F, N, k, y, status, workspace, stream,
+                              stage_events, false, &q);
 }
 
 extern "C" int lynx_quantize_weights_fp8(const uint16_t *Wg, const uint16_t *Wu, const uint16_t *Wd, int E, int H, int F,
@@ -1401,24 +1592,26 @@ extern "C" int lynx_moe_ffn_fp4(const uint16_t *x_bf16, const uint8_t *Wgu_q, co
                                 const uint32_t *shared_scales_gu, const uint32_t *shared_scales_d, int n_shared, int F_shared,
                                 const int32_t *idx, const float *gate, const int32_t *expert_offsets, const int32_t *perm,
                                 const int32_t *active_experts, const int32_t *num_active, int T, int H, int F, int N,
-                                int k, float *y, void *workspace, void *stream, void *const *stage_events)
+                                int k, float *y, int32_t *status, void *workspace, void *stream, void *const *stage_events)
 {
+    (void)active_experts;
+    (void)num_active;
     const lynx::FfnScales q = {reinterpret_cast<const float *>(scales_gu), reinterpret_cast<const float *>(scales_d),
                                reinterpret_cast<const float *>(shared_scales_gu),
                                reinterpret_cast<const float *>(shared_scales_d), 2};
     return lynx::moe_ffn_impl(x_bf16, reinterpret_cast<const uint16_t *>(Wgu_q), reinterpret_cast<const uint16_t *>(Wd_q),
                               reinterpret_cast<const uint16_t *>(Sgu_q), reinterpret_cast<const uint16_t *>(Sd_q), n_shared,
-                              F_shared, idx, gate, expert_offsets, perm, active_experts, num_active, T, H, F, N, k, y,
-                              workspace, stream, stage_events, false, &q);
+                              F_shared, idx, gate, expert_offsets, perm, T, H, F, N, k, y, status, workspace, stream,
+                              stage_events, false, &q);
 }
 
 extern "C" int lynx_moe_ffn(const uint16_t *x_bf16, const uint16_t *Wgu_packed, const uint16_t *Wd_packed,
                             const uint16_t *Sgu_packed, const uint16_t *Sd_packed, int n_shared, int F_shared,
                             const int32_t *idx, const float *gate, const int32_t *expert_offsets, const int32_t *perm,
                             const int32_t *active_experts, const int32_t *num_active, int T, int H, int F, int N, int k,
-                            float *y, void *workspace, void *stream)
+                            float *y, int32_t *status, void *workspace, void *stream)
 {
     return lynx_moe_ffn_timed(x_bf16, Wgu_packed, Wd_packed, Sgu_packed, Sd_packed, n_shared, F_shared, idx, gate,
-                              expert_offsets, perm, active_experts, num_active, T, H, F, N, k, y, workspace, stream,
+                              expert_offsets, perm, active_experts, num_active, T, H, F, N, k, y, status, workspace, stream,
                               nullptr);
 }

@@ -6,7 +6,7 @@
 // inside its expert is the popcount of the bits below t.  No sort, no ordered atomics.
 #pragma once
 
-#include "lynx_common.h"
+#include "lynx_plan.h"
 
 namespace lynx {
 
@@ -21,12 +21,14 @@ struct PermuteSharedT {
 typedef PermuteSharedT<LYNX_MAX_T / 32> PermuteShared;
 
 // Every thread of the workgroup calls this with sh.member filled (and visible: barrier before).
-// perm must have been pre-filled with -1 where invalid indices can occur.
+// perm must have been pre-filled with -1 where invalid indices can occur.  With ps.units_gu > 0 it also writes the
+// work plan of the expert FFN into the workspace ws (lynx_plan.h).
 template <int THREADS, typename Shared>
 __device__ __forceinline__ void permute_from_bitsets(Shared &sh, const int32_t *__restrict__ idx, int T, int N,
                                                      int k, int32_t *__restrict__ expert_offsets,
                                                      int32_t *__restrict__ perm, int32_t *__restrict__ active_experts,
-                                                     int32_t *__restrict__ num_active)
+                                                     int32_t *__restrict__ num_active, const PlanShape &ps = PlanShape{0, 0, 0, 0, 0},
+                                                     int32_t *__restrict__ ws = nullptr)
 {
     const int tid = threadIdx.x;
     const int W = (T + 31) / 32;
@@ -64,6 +66,7 @@ __device__ __forceinline__ void permute_from_bitsets(Shared &sh, const int32_t *
         }
     }
     __syncthreads();
+    build_plan<THREADS>(ps, N, sh.count, sh.offs, ws);
     // (the indices are read with device-coherent loads: in the fused kernel another workgroup of this launch
     // wrote them; such loads go to memory, so several are requested before the first is used)
     constexpr int kBatch = 8;

@@ -9,6 +9,7 @@
 // any access pattern).
 #include <hip/hip_runtime.h>
 
+#include "../../include/lynx_bench.h"
 #include "lynx_common.h"
 
 namespace lynx {

@@ -308,6 +308,20 @@ __device__ __forceinline__ float selection_gate(int k, int mye, float myz, int g
 
 // ---- per-token steps (one wave per token), shared by the single-workgroup and the multi-workgroup paths ----
 
+// The "top-k weight sum" of a selection (paper Sec. 4): with num = sum over the selected experts of exp(z - zref) it is
+// num over the same sum taken over all N experts; for a sigmoid-gated router the sum of the selected scores itself.
+template <int NS>
+__device__ __forceinline__ void selection_mass(const TokenLogits<NS> &raw, int t, int gate_fn, float num, float zref,
+                                               float *__restrict__ out)
+{
+    float part = 0.f;
+#pragma unroll
+    for (int i = 0; i < NS; ++i)
+        if ((raw.have >> i) & 1u) part += expf(raw.v[i] - zref);
+    const float den = wave_sum(part);
+    if (lane_id() == 0) out[t] = gate_fn == kGateSigmoid ? num : num / den;
+}
+
 // Softmax + top-k (Sec. 2.1): lane j < k returns the j-th pick in mye; writes idx / gate / psum (softmax: the
 // selected probability mass; sigmoid-gated: the sum of the selected scores).
 // tl = the experts the token may use, raw = all of them (the same unless the router is group-limited): the softmax
@@ -326,16 +340,11 @@ __device__ __forceinline__ int token_topk(const TokenLogits<NS> &tl, const Token
     });
     float num, zref;
     const float g = selection_gate(k, mye, myz, gate_fn, num, zref);
-    float part = 0.f;
-#pragma unroll
-    for (int i = 0; i < NS; ++i)
-        if ((raw.have >> i) & 1u) part += expf(raw.v[i] - zref);
-    const float den = wave_sum(part);
     if (lane < k) {
         topk_idx[(size_t)t * k + lane] = mye;
         topk_gate[(size_t)t * k + lane] = g;
     }
-    if (lane == 0) topk_psum[t] = gate_fn == kGateSigmoid ? num : num / den;
+    selection_mass(raw, t, gate_fn, num, zref, topk_psum);
     return mye;
 }
 
@@ -442,10 +451,13 @@ __device__ __forceinline__ int wave_fill_active(int N, int k, const int *order, 
 
 // Selection of one token inside the active set (or its unchanged selection when bypassed) and its gates
 // (Secs. 3.4, 4).  Lane j < k returns the j-th expert; writes new_idx / new_gate.
+// new_psum (may be null): what token_topk writes as topk_psum, for the new selection: its share of the softmax over all
+// N experts (raw), or the sum of its sigmoid scores.  Same arithmetic as there, so an unchanged selection gives the
+// same bits.
 template <int NS>
-__device__ __forceinline__ int token_remap(const TokenLogits<NS> &tl, int t, int N, int k, bool bypass, int gate_fn, const int *inA,
-                                           const int32_t *sel, int32_t *__restrict__ new_idx,
-                                           float *__restrict__ new_gate)
+__device__ __forceinline__ int token_remap(const TokenLogits<NS> &tl, const TokenLogits<NS> &raw, int t, int N, int k, bool bypass,
+                                           int gate_fn, const int *inA, const int32_t *sel, int32_t *__restrict__ new_idx,
+                                           float *__restrict__ new_gate, float *__restrict__ new_psum)
 {
     const int lane = lane_id();
     int mye = -1;
@@ -495,6 +507,7 @@ __device__ __forceinline__ int token_remap(const TokenLogits<NS> &tl, int t, int
         store_coherent(&new_idx[(size_t)t * k + lane], mye);   // read by the workgroup that assigns the tokens
         new_gate[(size_t)t * k + lane] = g;
     }
+    if (new_psum) selection_mass(raw, t, gate_fn, num, zref, new_psum);
     return mye;
 }
 
@@ -575,10 +588,10 @@ template <int NS, bool DO_TOPK, bool DO_PERMUTE>
 __global__ __launch_bounds__(kSmallThreads) void routing_small_kernel(
     const float *__restrict__ logits, int T, int N, int k, float alpha, int beta, int bypass, RouterKind rk,
     int32_t *__restrict__ topk_idx, float *__restrict__ topk_gate, float *__restrict__ topk_psum,
-    int32_t *__restrict__ new_idx, float *__restrict__ new_gate, int32_t *__restrict__ cnt_before,
-    int32_t *__restrict__ cnt_after, int32_t *__restrict__ bin_hist, int32_t *__restrict__ num_active,
-    int32_t *__restrict__ expert_offsets, int32_t *__restrict__ perm, int32_t *__restrict__ active_experts,
-    int32_t *__restrict__ num_active_perm)
+    int32_t *__restrict__ new_idx, float *__restrict__ new_gate, float *__restrict__ new_psum,
+    int32_t *__restrict__ cnt_before, int32_t *__restrict__ cnt_after, int32_t *__restrict__ bin_hist,
+    int32_t *__restrict__ num_active, int32_t *__restrict__ expert_offsets, int32_t *__restrict__ perm,
+    int32_t *__restrict__ active_experts, int32_t *__restrict__ num_active_perm, PlanShape ps, int32_t *__restrict__ ws)
 {
     __shared__ SmallShared sh;
     const int tid = threadIdx.x, lane = lane_id(), t = wave_id();
@@ -626,7 +639,8 @@ __global__ __launch_bounds__(kSmallThreads) void routing_small_kernel(
     }
     __syncthreads();
     if (has_token) {
-        const int mye = token_remap(tl, t, N, k, bypass != 0, rk.gate_fn, sh.inA, sh.sel + t * k, new_idx, new_gate);
+        const int mye = token_remap(tl, raw, t, N, k, bypass != 0, rk.gate_fn, sh.inA, sh.sel + t * k, new_idx, new_gate,
+                                    new_psum);
         if (lane < k) {
             sh.newsel[t * k + lane] = mye;
             if (mye >= 0) {
@@ -649,7 +663,7 @@ __global__ __launch_bounds__(kSmallThreads) void routing_small_kernel(
     }
     if constexpr (DO_PERMUTE)
         permute_from_bitsets<kSmallThreads>(sh.perm, sh.newsel, T, N, k, expert_offsets, perm, active_experts,
-                                            num_active_perm);
+                                            num_active_perm, ps, ws);
 }
 
 // ---- large batches: one wave per token over many workgroups, one launch per batch-level dependency ----------
@@ -749,12 +763,13 @@ __global__ __launch_bounds__(kTokThreads) void remap_kernel(const float *__restr
                                                             const int32_t *__restrict__ cnt_before, int T, int N, int k,
                                                             int bypass, RouterKind rk, int32_t *__restrict__ ws,
                                                             int32_t *__restrict__ new_idx, float *__restrict__ new_gate,
+                                                            float *__restrict__ new_psum,
                                                             int32_t *__restrict__ cnt_after,
                                                             int32_t *__restrict__ num_active,
                                                             int32_t *__restrict__ expert_offsets,
                                                             int32_t *__restrict__ perm,
                                                             int32_t *__restrict__ active_experts,
-                                                            int32_t *__restrict__ num_active_perm)
+                                                            int32_t *__restrict__ num_active_perm, PlanShape ps)
 {
     __shared__ RemapShared<DO_PERMUTE> sh;
     __shared__ int32_t sel[kTokWaves * LYNX_MAX_K];
@@ -783,7 +798,8 @@ __global__ __launch_bounds__(kTokThreads) void remap_kernel(const float *__restr
     }
     __syncthreads();
     if (t < T) {
-        const int mye = token_remap(tl, t, N, k, bypass != 0, rk.gate_fn, sh.inA, sel + wave * k, new_idx, new_gate);
+        const int mye = token_remap(tl, raw, t, N, k, bypass != 0, rk.gate_fn, sh.inA, sel + wave * k, new_idx, new_gate,
+                                    new_psum);
         if (lane < k && mye >= 0) {
             atomicAdd(&sh.cnta[mye], 1);
             if (DO_PERMUTE) atomicOr(reinterpret_cast<unsigned *>(ws + kWsMember) + mye * W + (t >> 5), 1u << (t & 31));
@@ -814,7 +830,7 @@ __global__ __launch_bounds__(kTokThreads) void remap_kernel(const float *__restr
     if (tid == 0) num_active[1] = sh.n_after;
     if constexpr (DO_PERMUTE)
         permute_from_bitsets<kTokThreads>(sh.perm, new_idx, T, N, k, expert_offsets, perm, active_experts,
-                                          num_active_perm);
+                                          num_active_perm, ps, ws);
 }
 
 // ---- score-biased selection (the variant of Sec. 3.3.1 that adds the batch score to the logits) ------------------
@@ -831,6 +847,7 @@ __global__ __launch_bounds__(kTokThreads) void biased_remap_kernel(const float *
                                                                    int k, int beta, float gamma, double tpow, int bypass,
                                                                    int32_t *__restrict__ ws, int32_t *__restrict__ new_idx,
                                                                    float *__restrict__ new_gate,
+                                                                   float *__restrict__ new_psum,
                                                                    int32_t *__restrict__ cnt_after,
                                                                    int32_t *__restrict__ num_active)
 {
@@ -889,6 +906,7 @@ __global__ __launch_bounds__(kTokThreads) void biased_remap_kernel(const float *
             new_gate[(size_t)t * k + lane] = g;
             if (mye >= 0) atomicAdd(&cnta[mye], 1);
         }
+        if (new_psum) selection_mass(tl, t, kGateSoftmax, num, zref, new_psum);
     }
     __syncthreads();
     if (tid < N && cnta[tid]) atomicAdd(&cnt_after[tid], cnta[tid]);
@@ -960,15 +978,15 @@ static void launch_logits(const uint16_t *x, const float *Wr, const float *bias,
 template <int NS, bool DO_TOPK, bool DO_PERMUTE>
 static int launch_after_logits_ns(const char *who, const float *logits, int T, int N, int k, float alpha, int beta,
                                int enable, RouterKind rk, int32_t *topk_idx, float *topk_gate, float *topk_psum, int32_t *new_idx,
-                               float *new_gate, int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist,
+                               float *new_gate, float *new_psum, int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist,
                                int32_t *num_active, int32_t *expert_offsets, int32_t *perm, int32_t *active_experts,
-                               int32_t *num_active_perm, int32_t *ws, bool clear_first, hipStream_t st)
+                               int32_t *num_active_perm, int32_t *ws, bool clear_first, hipStream_t st, const PlanShape &ps)
 {
     const int bypass = (!enable || T <= 1) ? 1 : 0;
     if (T <= kSmallT) {
         hipLaunchKernelGGL((routing_small_kernel<NS, DO_TOPK, DO_PERMUTE>), dim3(1), dim3(kSmallThreads), 0, st, logits, T, N, k,
-                           alpha, beta, bypass, rk, topk_idx, topk_gate, topk_psum, new_idx, new_gate, cnt_before, cnt_after,
-                           bin_hist, num_active, expert_offsets, perm, active_experts, num_active_perm);
+                           alpha, beta, bypass, rk, topk_idx, topk_gate, topk_psum, new_idx, new_gate, new_psum, cnt_before,
+                           cnt_after, bin_hist, num_active, expert_offsets, perm, active_experts, num_active_perm, ps, ws);
         return check_launch(who);
     }
     int rc;
@@ -997,20 +1015,22 @@ static int launch_after_logits_ns(const char *who, const float *logits, int T, i
         if (rc != LYNX_OK) return rc;
     }
     hipLaunchKernelGGL((remap_kernel<NS, DO_PERMUTE>), tgrid, tblock, 0, st, logits, topk_idx, cnt_before, T, N, k, bypass, rk, ws,
-                       new_idx, new_gate, cnt_after, num_active, expert_offsets, perm, active_experts, num_active_perm);
+                       new_idx, new_gate, new_psum, cnt_after, num_active, expert_offsets, perm, active_experts,
+                       num_active_perm, ps);
     return check_launch(who);
 }
 
 template <bool DO_TOPK, bool DO_PERMUTE>
 static int launch_after_logits(const char *who, const float *logits, int T, int N, int k, float alpha, int beta,
                                int enable, RouterKind rk, int32_t *topk_idx, float *topk_gate, float *topk_psum, int32_t *new_idx,
-                               float *new_gate, int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist,
+                               float *new_gate, float *new_psum, int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist,
                                int32_t *num_active, int32_t *expert_offsets, int32_t *perm, int32_t *active_experts,
-                               int32_t *num_active_perm, int32_t *ws, bool clear_first, hipStream_t st)
+                               int32_t *num_active_perm, int32_t *ws, bool clear_first, hipStream_t st,
+                               const PlanShape &ps = PlanShape{0, 0, 0, 0, 0})
 {
 #define LYNX_ROUTING_ARGS                                                                                             \
-    who, logits, T, N, k, alpha, beta, enable, rk, topk_idx, topk_gate, topk_psum, new_idx, new_gate, cnt_before, cnt_after, \
-        bin_hist, num_active, expert_offsets, perm, active_experts, num_active_perm, ws, clear_first, st
+    who, logits, T, N, k, alpha, beta, enable, rk, topk_idx, topk_gate, topk_psum, new_idx, new_gate, new_psum, cnt_before, \
+        cnt_after, bin_hist, num_active, expert_offsets, perm, active_experts, num_active_perm, ws, clear_first, st, ps
     if (N <= kWave) return launch_after_logits_ns<1, DO_TOPK, DO_PERMUTE>(LYNX_ROUTING_ARGS);
     if (N <= 2 * kWave) return launch_after_logits_ns<2, DO_TOPK, DO_PERMUTE>(LYNX_ROUTING_ARGS);
     return launch_after_logits_ns<4, DO_TOPK, DO_PERMUTE>(LYNX_ROUTING_ARGS);
@@ -1020,9 +1040,9 @@ static int launch_after_logits(const char *who, const float *logits, int T, int 
 // The whole routing side of lynx_moe_layer: two launches for T <= kSmallT, four otherwise.  T >= 1, arguments checked.
 int routing_fused(const uint16_t *x, const float *Wr, const float *bias, int T, int H, int N, int k, float alpha,
                   int beta, int enable, RouterKind rk, float *logits, int32_t *topk_idx, float *topk_gate, float *topk_psum,
-                  int32_t *new_idx, float *new_gate, int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist,
+                  int32_t *new_idx, float *new_gate, float *new_psum, int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist,
                   int32_t *num_active, int32_t *expert_offsets, int32_t *perm, int32_t *active_experts,
-                  int32_t *num_active_perm, void *workspace, hipStream_t st)
+                  int32_t *num_active_perm, void *workspace, hipStream_t st, const PlanShape &ps)
 {
     int32_t *ws = reinterpret_cast<int32_t *>(workspace);
     ZeroList z;
@@ -1040,15 +1060,15 @@ int routing_fused(const uint16_t *x, const float *Wr, const float *bias, int T, 
     int rc = check_launch("lynx_moe_layer(logits)");
     if (rc != LYNX_OK) return rc;
     return launch_after_logits<true, true>("lynx_moe_layer(routing)", logits, T, N, k, alpha, beta, enable, rk, topk_idx,
-                                           topk_gate, topk_psum, new_idx, new_gate, cnt_before, cnt_after, bin_hist,
-                                           num_active, expert_offsets, perm, active_experts, num_active_perm, ws, false, st);
+                                           topk_gate, topk_psum, new_idx, new_gate, new_psum, cnt_before, cnt_after, bin_hist,
+                                           num_active, expert_offsets, perm, active_experts, num_active_perm, ws, false, st, ps);
 }
 
 }  // namespace lynx
 
 extern "C" int lynx_affinity_bin_biased(const float *logits, const int32_t *topk_idx, int T, int N, int k, float alpha,
                                         int beta, float gamma, int enable, int32_t *new_idx, float *new_gate,
-                                        int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist,
+                                        float *new_psum, int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist,
                                         int32_t *num_active, void *workspace, void *stream)
 {
     using namespace lynx;
@@ -1086,7 +1106,7 @@ extern "C" int lynx_affinity_bin_biased(const float *logits, const int32_t *topk
         rc = check_launch("lynx_affinity_bin_biased(bins)");                                                            \
         if (rc != LYNX_OK) return rc;                                                                                   \
         hipLaunchKernelGGL((biased_remap_kernel<NS>), tgrid, tblock, 0, st, logits, topk_idx, cnt_before, bin_hist, T,  \
-                           N, k, beta, gamma, tpow, bypass, ws, new_idx, new_gate, cnt_after, num_active);              \
+                           N, k, beta, gamma, tpow, bypass, ws, new_idx, new_gate, new_psum, cnt_after, num_active);    \
     } while (0)
     if (N <= kWave)
         LYNX_BIASED(1);
@@ -1153,7 +1173,7 @@ extern "C" int lynx_route_grouped(const uint16_t *x_bf16, const float *Wr, const
 }
 
 static int affinity_bin_impl(const float *logits, const int32_t *topk_idx, int T, int N, int k, float alpha, int beta,
-                             int enable, int gate_fn, int32_t *new_idx, float *new_gate, int32_t *cnt_before,
+                             int enable, int gate_fn, int32_t *new_idx, float *new_gate, float *new_psum, int32_t *cnt_before,
                              int32_t *cnt_after, int32_t *bin_hist, int32_t *num_active, void *workspace, void *stream)
 {
     using namespace lynx;
@@ -1179,34 +1199,34 @@ static int affinity_bin_impl(const float *logits, const int32_t *topk_idx, int T
     }
     return launch_after_logits<false, false>("lynx_affinity_bin", logits, T, N, k, alpha, beta, enable,
                                              RouterKind{gate_fn, 1, 1},
-                                             const_cast<int32_t *>(topk_idx), nullptr, nullptr, new_idx, new_gate,
+                                             const_cast<int32_t *>(topk_idx), nullptr, nullptr, new_idx, new_gate, new_psum,
                                              cnt_before, cnt_after, bin_hist, num_active, nullptr, nullptr, nullptr,
                                              nullptr, ws, true, st);
 }
 
 extern "C" int lynx_affinity_bin(const float *logits, const int32_t *topk_idx, int T, int N, int k, float alpha,
-                                 int beta, int enable, int32_t *new_idx, float *new_gate, int32_t *cnt_before,
-                                 int32_t *cnt_after, int32_t *bin_hist, int32_t *num_active, void *workspace,
-                                 void *stream)
+                                 int beta, int enable, int32_t *new_idx, float *new_gate, float *new_psum,
+                                 int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist, int32_t *num_active,
+                                 void *workspace, void *stream)
 {
     return affinity_bin_impl(logits, topk_idx, T, N, k, alpha, beta, enable, lynx::kGateSoftmax, new_idx, new_gate,
-                             cnt_before, cnt_after, bin_hist, num_active, workspace, stream);
+                             new_psum, cnt_before, cnt_after, bin_hist, num_active, workspace, stream);
 }
 
 extern "C" int lynx_affinity_bin_sigmoid(const float *logits, const int32_t *topk_idx, int T, int N, int k, float alpha,
-                                         int beta, int enable, int32_t *new_idx, float *new_gate, int32_t *cnt_before,
-                                         int32_t *cnt_after, int32_t *bin_hist, int32_t *num_active, void *workspace,
-                                         void *stream)
+                                         int beta, int enable, int32_t *new_idx, float *new_gate, float *new_ssum,
+                                         int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist, int32_t *num_active,
+                                         void *workspace, void *stream)
 {
     return affinity_bin_impl(logits, topk_idx, T, N, k, alpha, beta, enable, lynx::kGateSigmoid, new_idx, new_gate,
-                             cnt_before, cnt_after, bin_hist, num_active, workspace, stream);
+                             new_ssum, cnt_before, cnt_after, bin_hist, num_active, workspace, stream);
 }
 
 extern "C" int lynx_affinity_bin_grouped(const float *logits, int T, int N, int k, int n_group, int topk_group, int gate_fn,
                                          float alpha, int beta, int enable, int32_t *topk_idx, float *topk_gate,
-                                         float *topk_third, int32_t *new_idx, float *new_gate, int32_t *cnt_before,
-                                         int32_t *cnt_after, int32_t *bin_hist, int32_t *num_active, void *workspace,
-                                         void *stream)
+                                         float *topk_third, int32_t *new_idx, float *new_gate, float *new_third,
+                                         int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist, int32_t *num_active,
+                                         void *workspace, void *stream)
 {
     using namespace lynx;
     const RouterKind rk = {gate_fn, n_group, topk_group};
@@ -1232,7 +1252,7 @@ extern "C" int lynx_affinity_bin_grouped(const float *logits, int T, int N, int 
         return check_launch("lynx_affinity_bin_grouped(clear)");
     }
     return launch_after_logits<true, false>("lynx_affinity_bin_grouped", logits, T, N, k, alpha, beta, enable, rk, topk_idx,
-                                            topk_gate, topk_third, new_idx, new_gate, cnt_before, cnt_after, bin_hist,
+                                            topk_gate, topk_third, new_idx, new_gate, new_third, cnt_before, cnt_after, bin_hist,
                                             num_active, nullptr, nullptr, nullptr, nullptr,
                                             reinterpret_cast<int32_t *>(workspace), true, st);
 }

@@ -96,6 +96,8 @@ def _check_layer(L, lay, T, alpha, beta, enable, n_sample=5, seed=0, sigmoid=Fal
         assert np.array_equal(host(got), a[key]), key
     g = host(b.new_gate)
     np.testing.assert_allclose(g, a["new_gate"], rtol=GATE_TOL, atol=1e-7)
+    np.testing.assert_allclose(host(b.new_psum), a["new_psum"], rtol=GATE_TOL, atol=1e-7)
+    assert int(host(b.status)[0]) == 0
     p = oracle.permute(a["new_idx"], cfg.N)
     for key, got in (("offsets", b.offsets), ("perm", b.perm), ("active", b.active), ("num_active", b.num_active_perm)):
         assert np.array_equal(host(got), p[key]), key

@@ -39,7 +39,7 @@ def _poisoned(shape, dtype):
 def _bin_out(T, N, k, beta):
     I, F = torch.int32, torch.float32
     return dict(idx=_poisoned((T, k), I), gate=_poisoned((T, k), F), psum=_poisoned((T,), F), new_idx=_poisoned((T, k), I),
-                new_gate=_poisoned((T, k), F), cnt_before=_poisoned((N,), I), cnt_after=_poisoned((N,), I),
+                new_gate=_poisoned((T, k), F), new_psum=_poisoned((T,), F), cnt_before=_poisoned((N,), I), cnt_after=_poisoned((N,), I),
                 bin_hist=_poisoned((N, beta), I), num_active=_poisoned((2,), I))
 
 
@@ -52,6 +52,7 @@ def _check_bin(out, z, k, G, tg, alpha, beta, enable, gate_fn):
     for key in ("new_idx", "cnt_before", "cnt_after", "bin_hist", "num_active"):
         assert np.array_equal(host(out[key]), ref[key]), key
     np.testing.assert_allclose(host(out["new_gate"]), ref["new_gate"], rtol=GATE_TOL, atol=1e-7)
+    np.testing.assert_allclose(host(out["new_psum"]), ref["new_psum"], rtol=GATE_TOL, atol=1e-7)
     return ref
 
 
@@ -142,7 +143,7 @@ def test_layer_grouped(L, T, shared, gate_fn):
     r = oracle.route(d["x"], d["Wr"], d["bias"], cfg.k)
     assert np.all(np.abs(z - r["logits"]) <= LOGIT_TOL * np.maximum(1.0, np.abs(r["logits"])))
     got = dict(idx=b.topk_idx, gate=b.topk_gate, psum=b.topk_psum, new_idx=b.new_idx, new_gate=b.new_gate,
-               cnt_before=b.cnt_before, cnt_after=b.cnt_after, bin_hist=b.bin_hist, num_active=b.num_active)
+               new_psum=b.new_psum, cnt_before=b.cnt_before, cnt_after=b.cnt_after, bin_hist=b.bin_hist, num_active=b.num_active)
     a = _check_bin(got, z, cfg.k, G, tg, alpha, beta, 1, gate_fn)
     p = oracle.permute(a["new_idx"], cfg.N)
     for key, val in (("offsets", b.offsets), ("perm", b.perm), ("active", b.active), ("num_active", b.num_active_perm)):

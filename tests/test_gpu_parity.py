@@ -86,6 +86,14 @@ def _check_bin(L, z, k, alpha, beta, enable):
     for key in ("new_idx", "cnt_before", "cnt_after", "bin_hist", "num_active"):
         assert np.array_equal(host(out[key]), ref[key]), key
     np.testing.assert_allclose(host(out["new_gate"]), ref["new_gate"], rtol=GATE_TOL, atol=1e-7)
+    # the probability mass of the new selection (the remap's "top-k weight sum"), and against the router's own: the
+    # GPU computes both the same way, so a token whose selection did not change shows the same bits
+    np.testing.assert_allclose(host(out["new_psum"]), ref["new_psum"], rtol=GATE_TOL, atol=1e-7)
+    top = L.lynx_affinity_bin(dev(z), dev(idx), alpha, beta, 0)
+    torch.cuda.synchronize()
+    same = np.all(np.sort(host(out["new_idx"]), axis=1) == np.sort(idx, axis=1), axis=1)
+    assert np.array_equal(host(out["new_psum"])[same], host(top["new_psum"])[same])
+    assert np.all(host(out["new_psum"]) <= host(top["new_psum"]) * (1 + 1e-6))
     return ref
 
 
@@ -192,6 +200,7 @@ def test_affinity_bin_biased(L, T, N, k, s, tail):
             for key in ("new_idx", "cnt_before", "cnt_after", "bin_hist", "num_active"):
                 assert np.array_equal(host(out[key]), ref[key]), key
             np.testing.assert_allclose(host(out["new_gate"]), ref["new_gate"], rtol=GATE_TOL, atol=1e-7)
+            np.testing.assert_allclose(host(out["new_psum"]), ref["new_psum"], rtol=GATE_TOL, atol=1e-7)
     z = wl.make_logits(T, N, seed=3, zipf_s=s, tail_frac=tail)
     idx = oracle.topk(z, k)["idx"]
     out = L.lynx_affinity_bin_biased(dev(z), dev(idx), 2.0, 2, 3.0, 0)   # bypass
@@ -311,6 +320,11 @@ FFN_CASES = [
     (24, 128, 192, 28, 6, 1, 128, None),
     (12, 256, 224, 18, 3, 0, 0, None),
     (64, 64, 512, 40, 8, 0, 0, None),
+    # down-projection work items of two and four 64-row units (many invoked experts x many row units), with crowded
+    # experts cut into token blocks that go to workgroups of their own, direct and staged experts mixed
+    (200, 1024, 128, 64, 8, 0, 0, None),
+    (130, 512, 64, 48, 6, 1, 64, 20),
+    (48, 768, 96, 100, 10, 0, 0, None),
 ]
 
 
@@ -340,6 +354,48 @@ def test_moe_ffn_many_small_experts_and_one_crowded(L):
     torch.cuda.synchronize()
     err = row_rel_err(y, y_ref)
     assert np.all(np.isfinite(y)) and err.max() <= Y_TOL, f"max row error {err.max():.3e}"
+
+
+def test_a_failed_wait_shows_in_y_and_status(L):
+    """The one hand-over inside a launch (a down-projection workgroup waits for its expert's gate/up workgroups) is
+    bounded.  Forced from the host: a poll limit of 0 and a count the counters never reach make every such wait give
+    up at once, while every kernel still runs to its end.  The call must then not pass a result on: y all NaN, status 1.
+    With the knobs back at their defaults the same call gives status 0 and the right y."""
+    from paper_2411_08982_amd import binding as B
+    cfg = wl.CONFIGS["tiny"]
+    T = 40                                         # more than 16 tokens, moderate experts: both projections in one launch
+    assert L.lynx_moe_ffn_launches(T, cfg.F) == 1
+    alpha, beta = wl.PRESETS["moderate"]
+    d = wl.make_layer(cfg, T)
+    x, Wr, bias = to_bf16_dev(d["x"]), dev(d["Wr"]), dev(d["bias"])
+    Wgu, Wdp = L.lynx_pack_weights(to_bf16_dev(d["Wg"]), to_bf16_dev(d["Wu"]), to_bf16_dev(d["Wd"]))
+    try:
+        L.lynx_debug_set(B.DEBUG_SPIN_LIMIT, 0)
+        L.lynx_debug_set(B.DEBUG_TARGET_BIAS, 1 << 20)
+        _say("failed wait, forced from the host: whole layer")
+        b = L.lynx_moe_layer(x, Wr, bias, Wgu, Wdp, cfg.F, cfg.k, alpha, beta, 1)
+        torch.cuda.synchronize()
+        assert int(host(b.status)[0]) == 1 and np.isnan(host(b.y)).all()
+        assert int(host(b.workspace.view(torch.int32))[B.WAIT_FLAG_WORD]) != 0
+        _say("failed wait, forced from the host: lynx_moe_ffn")
+        p = dict(offsets=b.offsets, perm=b.perm, active=b.active, num_active=b.num_active_perm)
+        st = torch.full((1,), -7, dtype=torch.int32, device="cuda")
+        y = L.lynx_moe_ffn(x, Wgu, Wdp, b.new_idx, b.new_gate, p, cfg.N, cfg.F, status=st)
+        torch.cuda.synchronize()
+        assert int(host(st)[0]) == 1 and np.isnan(host(y)).all()
+    finally:
+        L.lynx_debug_set(B.DEBUG_SPIN_LIMIT, -1)
+        L.lynx_debug_set(B.DEBUG_TARGET_BIAS, 0)
+    _say("the same calls with the defaults")
+    b = L.lynx_moe_layer(x, Wr, bias, Wgu, Wdp, cfg.F, cfg.k, alpha, beta, 1, buffers=b)
+    st = torch.full((1,), -7, dtype=torch.int32, device="cuda")
+    p = dict(offsets=b.offsets, perm=b.perm, active=b.active, num_active=b.num_active_perm)
+    y = L.lynx_moe_ffn(x, Wgu, Wdp, b.new_idx, b.new_gate, p, cfg.N, cfg.F, status=st)
+    torch.cuda.synchronize()
+    assert int(host(b.status)[0]) == 0 and int(host(st)[0]) == 0
+    a = oracle.affinity_bin(host(b.logits), oracle.topk(host(b.logits), cfg.k)["idx"], alpha, beta, 1)
+    y_ref = oracle.moe_ffn(d["x"], d["Wg"], d["Wu"], d["Wd"], a["new_idx"], a["new_gate"])
+    assert row_rel_err(host(b.y), y_ref).max() <= Y_TOL and np.array_equal(host(y), host(b.y))
 
 
 def test_moe_ffn_skips_invalid_pairs_without_fault(L):

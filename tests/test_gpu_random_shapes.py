@@ -136,6 +136,8 @@ def test_layer_random_shape(L, i):
                      ("bin_hist", b.bin_hist), ("num_active", b.num_active)):
         assert np.array_equal(host(got), a[key]), key
     np.testing.assert_allclose(host(b.new_gate), a["new_gate"], rtol=GATE_TOL, atol=1e-7)
+    np.testing.assert_allclose(host(b.new_psum), a["new_psum"], rtol=GATE_TOL, atol=1e-7)
+    assert int(host(b.status)[0]) == 0
     p = oracle.permute(a["new_idx"], cfg.N)
     for key, got in (("offsets", b.offsets), ("perm", b.perm), ("active", b.active), ("num_active", b.num_active_perm)):
         assert np.array_equal(host(got), p[key]), key
@@ -288,7 +290,7 @@ def grouped_case(L, i):
         t.view(torch.uint8).fill_(0xFF)
         return t
     o = dict(idx=poisoned((T, k), I), gate=poisoned((T, k), F), psum=poisoned((T,), F), new_idx=poisoned((T, k), I),
-             new_gate=poisoned((T, k), F), cnt_before=poisoned((N,), I), cnt_after=poisoned((N,), I),
+             new_gate=poisoned((T, k), F), new_psum=poisoned((T,), F), cnt_before=poisoned((N,), I), cnt_after=poisoned((N,), I),
              bin_hist=poisoned((N, beta), I), num_active=poisoned((2,), I))
     ws = torch.full((65536,), 0xFF, dtype=torch.uint8, device="cuda")
     out = L.lynx_affinity_bin_grouped(dev(z), k, G, tg, alpha, beta, gate_fn, enable, ws, o)
@@ -301,6 +303,7 @@ def grouped_case(L, i):
     for key in ("new_idx", "cnt_before", "cnt_after", "bin_hist", "num_active"):
         assert np.array_equal(host(out[key]), ref[key]), key
     np.testing.assert_allclose(host(out["new_gate"]), ref["new_gate"], rtol=GATE_TOL, atol=1e-7)
+    np.testing.assert_allclose(host(out["new_psum"]), ref["new_psum"], rtol=GATE_TOL, atol=1e-7)
 
 
 @pytest.mark.parametrize("block", range(3))

@@ -62,6 +62,7 @@ def test_affinity_bin_sigmoid(L, T, N, k):
             assert np.array_equal(host(out[key]), ref[key]), key
             assert np.array_equal(host(out[key]), host(soft[key])), key      # only the gates differ from the softmax call
         np.testing.assert_allclose(host(out["new_gate"]), ref["new_gate"], rtol=GATE_TOL, atol=1e-7)
+        np.testing.assert_allclose(host(out["new_psum"]), ref["new_psum"], rtol=GATE_TOL, atol=1e-7)   # sum of the scores
 
 
 @pytest.mark.parametrize("T,shared", [(8, 0), (16, 1), (40, 1), (130, 0)])
@@ -87,6 +88,7 @@ def test_layer_sigmoid(L, T, shared):
                      ("bin_hist", b.bin_hist), ("num_active", b.num_active)):
         assert np.array_equal(host(got), a[key]), key
     np.testing.assert_allclose(host(b.new_gate), a["new_gate"], rtol=GATE_TOL, atol=1e-7)
+    np.testing.assert_allclose(host(b.new_psum), a["new_psum"], rtol=GATE_TOL, atol=1e-7)
     p = oracle.permute(a["new_idx"], cfg.N)
     for key, got in (("offsets", b.offsets), ("perm", b.perm), ("active", b.active), ("num_active", b.num_active_perm)):
         assert np.array_equal(host(got), p[key]), key
