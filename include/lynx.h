@@ -7,7 +7,8 @@
  *
  * Conventions
  *  - Every pointer is a DEVICE pointer owned by the caller unless it says "host".  The library
- *    allocates nothing and keeps no state between calls.
+ *    allocates nothing and keeps no state between calls (one exception, stated there: lynx_moe_layer_static
+ *    remembers, per GPU, where its built-in scratch array lives).
  *  - Every call only enqueues kernels on `stream` (a hipStream_t passed as void*; NULL = the null
  *    stream).  No call synchronises with the host or reads device results on the host, so a sequence
  *    of calls can be captured into a hipGraph.
@@ -43,6 +44,7 @@ extern "C" {
 #define LYNX_MAX_N 256
 #define LYNX_MAX_K 16
 #define LYNX_MAX_BETA 6
+#define LYNX_STATIC_SCRATCH_BYTES (64u << 20) /* the built-in scratch array of lynx_moe_layer_static, per GPU */
 
 /* Host string describing the last error on this thread ("" if none). */
 const char *lynx_last_error(void);
@@ -167,6 +169,26 @@ int lynx_moe_layer(const uint16_t *x_bf16, const float *Wr, const float *bias, c
                    float *new_psum, int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist, int32_t *num_active,
                    int32_t *expert_offsets, int32_t *perm, int32_t *active_experts, int32_t *num_active_perm, float *y,
                    int32_t *status, void *workspace, void *stream, void *const *stage_events);
+
+/*
+ * lynx_moe_layer for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments (without workspace and
+ * stage_events), same kernels and bit-identical results; the scratch memory is a device array built into the library
+ * (LYNX_STATIC_SCRATCH_BYTES = 64 MiB; every GPU the library runs on holds its copy until the process ends).  The call
+ * allocates and frees nothing.  Sizes whose lynx_workspace_bytes() exceeds the array are refused with
+ * LYNX_ERR_UNSUPPORTED before anything is enqueued (all benchmark shapes up to T = 512 fit).  The first call on a device
+ * looks up that device's copy of the array (the device must be current, as for any launch on `stream`; make that first
+ * call outside a stream capture).  Every call on a GPU uses that GPU's one array, which keeps the last call's contents
+ * (what must start at zero is cleared by the first kernel of each call): calls that overlap in time on one GPU race,
+ * on any streams; calls on one stream, or ordered by events, are fine.
+ */
+int lynx_moe_layer_static(const uint16_t *x_bf16, const float *Wr, const float *bias, const uint16_t *Wgu_packed,
+                          const uint16_t *Wd_packed, const uint16_t *Sgu_packed, const uint16_t *Sd_packed, int n_shared,
+                          int F_shared, int T, int H, int F, int N, int k, float alpha, int beta, int enable, float *logits,
+                          int32_t *topk_idx, float *topk_gate, float *topk_psum, int32_t *new_idx, float *new_gate,
+                          float *new_psum, int32_t *cnt_before, int32_t *cnt_after, int32_t *bin_hist, int32_t *num_active,
+                          int32_t *expert_offsets, int32_t *perm, int32_t *active_experts, int32_t *num_active_perm, float *y,
+                          int32_t *status, void *stream);
 
 /*
  * Expert weights in 8-bit floating point, weight-only (a widening beyond the paper's bf16 runs; its Sec. 5 shows

@@ -20,7 +20,7 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_HIP = 0, -1, -2, -3
 MAX_T, MAX_N, MAX_K, MAX_BETA = 1024, 256, 16, 6
 
 SYMBOLS = ["lynx_last_error", "lynx_workspace_bytes", "lynx_route", "lynx_affinity_bin", "lynx_affinity_bin_biased", "lynx_permute",
-           "lynx_pack_weights", "lynx_moe_ffn", "lynx_moe_ffn_timed", "lynx_moe_layer", "lynx_moe_ffn_launches", "lynx_residual_add", "lynx_read_probe",
+           "lynx_pack_weights", "lynx_moe_ffn", "lynx_moe_ffn_timed", "lynx_moe_layer", "lynx_moe_layer_static", "lynx_moe_ffn_launches", "lynx_residual_add", "lynx_read_probe",
            "lynx_quantize_weights_fp8", "lynx_moe_ffn_fp8", "lynx_moe_layer_fp8",
            "lynx_fp4_scale_words", "lynx_quantize_weights_fp4", "lynx_moe_ffn_fp4", "lynx_moe_layer_fp4",
            "lynx_route_sigmoid", "lynx_affinity_bin_sigmoid", "lynx_moe_layer_sigmoid",
@@ -57,6 +57,7 @@ def lib():
         L.lynx_moe_ffn.argtypes = [P, P, P, P, P, I, I, P, P, P, P, P, P, I, I, I, I, I, P, P, P, P]
         L.lynx_moe_ffn_timed.argtypes = L.lynx_moe_ffn.argtypes + [ctypes.POINTER(c_void_p)]
         L.lynx_moe_layer.argtypes = [P, P, P, P, P, P, P, I, I, I, I, I, I, I, F, I, I] + [P] * 19 + [ctypes.POINTER(c_void_p)]
+        L.lynx_moe_layer_static.argtypes = [P, P, P, P, P, P, P, I, I, I, I, I, I, I, F, I, I] + [P] * 18
         L.lynx_read_probe.argtypes = [P, c_size_t, I, P, P]
         L.lynx_quantize_weights_fp8.argtypes = [P, P, P, I, I, I, P, P, P, P, P]
         L.lynx_moe_ffn_fp8.argtypes = [P] * 9 + [I, I] + [P] * 6 + [I] * 5 + [P, P, P, P, ctypes.POINTER(c_void_p)]
@@ -310,6 +311,27 @@ def lynx_moe_layer(x, Wr, bias, Wgu, Wdp, F, k, alpha, beta, enable=1, Sgu=None,
         b.bin_hist.data_ptr(), b.num_active.data_ptr(), b.offsets.data_ptr(), b.perm.data_ptr(), b.active.data_ptr(),
         b.num_active_perm.data_ptr(), b.y.data_ptr(), b.status.data_ptr(), b.workspace.data_ptr(), _stream(),
         None if stage_events is None else (c_void_p * 4)(*[e.cuda_event for e in stage_events])))
+    return b
+
+
+STATIC_SCRATCH_BYTES = 64 << 20   # LYNX_STATIC_SCRATCH_BYTES
+
+
+def lynx_moe_layer_static(x, Wr, bias, Wgu, Wdp, F, k, alpha, beta, enable=1, Sgu=None, Sdp=None, n_shared=0, F_shared=0,
+                          buffers: LayerBuffers | None = None):
+    """lynx_moe_layer on the library's built-in scratch array (the call allocates nothing; b.workspace is not used)."""
+    T, H = x.shape
+    N = Wr.shape[0]
+    b = buffers or LayerBuffers(T, H, F, N, k, beta, n_shared, F_shared, x.device)
+    if b.sizes != (T, H, F, N, k, n_shared, F_shared) or b.beta != beta:
+        raise ValueError("buffers were allocated for other sizes")
+    _check(lib().lynx_moe_layer_static(
+        _ptr(x, BF16, "x"), _ptr(Wr, F32, "Wr"), _ptr(bias, F32, "bias"), _ptr(Wgu, BF16, "Wgu"), _ptr(Wdp, BF16, "Wdp"),
+        _ptr(Sgu, BF16, "Sgu"), _ptr(Sdp, BF16, "Sdp"), n_shared, F_shared, T, H, F, N, k, float(alpha), int(beta),
+        int(enable), b.logits.data_ptr(), b.topk_idx.data_ptr(), b.topk_gate.data_ptr(), b.topk_psum.data_ptr(),
+        b.new_idx.data_ptr(), b.new_gate.data_ptr(), b.new_psum.data_ptr(), b.cnt_before.data_ptr(), b.cnt_after.data_ptr(),
+        b.bin_hist.data_ptr(), b.num_active.data_ptr(), b.offsets.data_ptr(), b.perm.data_ptr(), b.active.data_ptr(),
+        b.num_active_perm.data_ptr(), b.y.data_ptr(), b.status.data_ptr(), _stream()))
     return b
 
 

@@ -2,6 +2,7 @@
 #include <stdarg.h>
 #include <stdio.h>
 
+#include <mutex>
 
 #include "lynx_plan.h"
 
@@ -131,6 +132,70 @@ extern "C" int lynx_moe_layer(const uint16_t *x_bf16, const float *Wr, const flo
                                 N, k, alpha, beta, enable, logits, topk_idx, topk_gate, topk_psum, new_idx, new_gate, new_psum,
                                 cnt_before, cnt_after, bin_hist, num_active, expert_offsets, perm, active_experts,
                                 num_active_perm, y, status, workspace, stream, stage_events, nullptr);
+}
+
+// ---- the whole layer for callers that cannot allocate ---------------------------------------------------------
+// The workspace of lynx_moe_layer (routing tickets and bit sets, completion counters, the intermediate vectors h
+// and the per-pair outputs o) lives in a device array of the library instead of a caller's buffer.  The array's
+// name is a host-side stand-in for the symbol, not a device address: the address on each GPU comes from
+// hipGetSymbolAddress, asked once per device with that device current, and only that pointer is handed to kernels.
+namespace lynx {
+constexpr size_t kStaticScratchBytes = (size_t)LYNX_STATIC_SCRATCH_BYTES;
+constexpr int kMaxDevices = 64;
+}  // namespace lynx
+static __device__ __align__(256) unsigned char scratch[lynx::kStaticScratchBytes];
+
+namespace lynx {
+static std::mutex g_scratch_mutex;
+static void *g_scratch_ptr[kMaxDevices];   // per device: where that GPU holds its copy of `scratch`
+
+// The current device's copy of the scratch array (resolved on the first call on that device), or null with the error set.
+static void *static_scratch()
+{
+    int dev = -1;
+    hipError_t err = hipGetDevice(&dev);
+    if (err != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        fail(LYNX_ERR_HIP, "lynx_moe_layer_static: hipGetDevice: %s (device %d)", hipGetErrorString(err), dev);
+        return nullptr;
+    }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        err = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (err != hipSuccess || !ptr) {
+            fail(LYNX_ERR_HIP, "lynx_moe_layer_static: hipGetSymbolAddress: %s", hipGetErrorString(err));
+            return nullptr;
+        }
+        g_scratch_ptr[dev] = ptr;
+    }
+    return g_scratch_ptr[dev];
+}
+}  // namespace lynx
+
+extern "C" int lynx_moe_layer_static(const uint16_t *x_bf16, const float *Wr, const float *bias, const uint16_t *Wgu_packed,
+                                     const uint16_t *Wd_packed, const uint16_t *Sgu_packed, const uint16_t *Sd_packed,
+                                     int n_shared, int F_shared, int T, int H, int F, int N, int k, float alpha, int beta,
+                                     int enable, float *logits, int32_t *topk_idx, float *topk_gate, float *topk_psum,
+                                     int32_t *new_idx, float *new_gate, float *new_psum, int32_t *cnt_before, int32_t *cnt_after,
+                                     int32_t *bin_hist, int32_t *num_active, int32_t *expert_offsets, int32_t *perm,
+                                     int32_t *active_experts, int32_t *num_active_perm, float *y, int32_t *status, void *stream)
+{
+    using namespace lynx;
+    if (T < 0 || H <= 0 || F <= 0 || N <= 0 || k <= 0 || n_shared < 0 || (n_shared > 0 && F_shared <= 0))
+        return fail(LYNX_ERR_INVALID_ARG, "lynx_moe_layer_static: negative or zero size");
+    if (T > LYNX_MAX_T || N > LYNX_MAX_N || k > LYNX_MAX_K || k > N)
+        return fail(LYNX_ERR_UNSUPPORTED, "lynx_moe_layer_static: need k<=N<=%d, k<=%d, T<=%d", LYNX_MAX_N, LYNX_MAX_K, LYNX_MAX_T);
+    const size_t need = lynx_workspace_bytes(T, H, F, N, k, n_shared, F_shared);
+    if (need > kStaticScratchBytes)
+        return fail(LYNX_ERR_UNSUPPORTED,
+                    "lynx_moe_layer_static: these sizes need %zu bytes of scratch, the built-in array holds %zu "
+                    "(use lynx_moe_layer with a workspace of your own)", need, kStaticScratchBytes);
+    void *ws = static_scratch();
+    if (!ws) return LYNX_ERR_HIP;
+    return moe_layer_impl(x_bf16, Wr, bias, Wgu_packed, Wd_packed, Sgu_packed, Sd_packed, n_shared, F_shared, T, H, F, N, k,
+                          alpha, beta, enable, logits, topk_idx, topk_gate, topk_psum, new_idx, new_gate, new_psum, cnt_before,
+                          cnt_after, bin_hist, num_active, expert_offsets, perm, active_experts, num_active_perm, y, status, ws,
+                          stream, nullptr, nullptr);
 }
 
 extern "C" int lynx_moe_layer_sigmoid(const uint16_t *x_bf16, const float *Wr, const float *bias, const uint16_t *Wgu_packed,

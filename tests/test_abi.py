@@ -21,7 +21,7 @@ def _declared():
 def test_library_exports_every_declared_symbol():
     lib = L.lib()
     names = _declared()
-    assert set(names) == set(L.SYMBOLS) and len(names) == 27
+    assert set(names) == set(L.SYMBOLS) and len(names) == 28
     for n in names:
         assert getattr(lib, n) is not None
 
@@ -89,6 +89,12 @@ def test_argument_errors_are_reported_before_any_launch():
                                                 ctypes.c_float(2.0), 2, 1, *([one] * 16), None, one, None, None)
     assert ly(400, 1024) == -2 and b"shared experts" in lib.lynx_last_error()
     assert lib.lynx_debug_set(99, 1) == -1 and lib.lynx_debug_set(1, -1) == 0
+    # the entry point on the built-in scratch array refuses sizes that do not fit it, before anything is enqueued
+    st = lambda T, H, F, N, k: lib.lynx_moe_layer_static(one, one, None, one, one, None, None, 0, 0, T, H, F, N, k,
+                                                         ctypes.c_float(2.0), 2, 1, *([one] * 17), None)
+    assert st(1024, 4096, 14336, 8, 2) == -2 and b"scratch" in lib.lynx_last_error()
+    assert L.workspace_bytes(512, 2048, 768, 128, 8) <= 64 << 20 < L.workspace_bytes(1024, 4096, 14336, 8, 2)
+    assert st(4, 64, 64, 4, 8) == -2 and st(-1, 64, 64, 4, 2) == -1
     assert lib.lynx_residual_add(one, one, 3, one, None) == -1       # odd length
     assert lib.lynx_residual_add(one, None, 4, one, None) == -1
     assert lib.lynx_moe_ffn_launches(8, 14336) == 2 and lib.lynx_moe_ffn_launches(64, 768) == 1
