@@ -76,6 +76,7 @@ def parse():
                          "rocprofv3 --pmc its FETCH_SIZE / WRITE_SIZE readings give the counters' scale")
     ap.add_argument("--down-item-cap", type=int, default=0, help="tuning: down-projection work items the plan aims at")
     ap.add_argument("--down-item-units", type=int, default=0, help="tuning: most 64-row units per down work item")
+    ap.add_argument("--down-k-waves", type=int, default=0, help="tuning: K slices of a down workgroup's waves")
     return ap.parse_args()
 
 
@@ -706,11 +707,12 @@ def main():
     import workloads as wl
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
-    if args.down_item_cap or args.down_item_units:
+    if args.down_item_cap or args.down_item_units or args.down_k_waves:
         import paper_2411_08982_amd as L_
         from paper_2411_08982_amd import binding as B_
         L_.lynx_debug_set(B_.DEBUG_DOWN_ITEM_CAP, args.down_item_cap)
         L_.lynx_debug_set(B_.DEBUG_DOWN_ITEM_UNITS, args.down_item_units)
+        L_.lynx_debug_set(B_.DEBUG_DOWN_K_WAVES, args.down_k_waves)
     if not args.config:
         out = full_report(args, wl, torch)
     elif args.stack > 0:

@@ -58,12 +58,15 @@ int lynx_read_probe(const void *buf, size_t bytes, int non_temporal, uint32_t *s
  *                               bias the counters never reach, every wait gives up at once and every kernel still
  *                               runs to its end: how the test of lynx_moe_ffn's status output forces the condition.
  *   LYNX_DEBUG_DOWN_ITEM_CAP    down-projection work items the device-side plan aims at (default 768)
- *   LYNX_DEBUG_DOWN_ITEM_UNITS  most 64-row units per down-projection work item (a power of two; default 1)
+ *   LYNX_DEBUG_DOWN_ITEM_UNITS  most row units per down-projection work item (a power of two; default 1)
+ *   LYNX_DEBUG_DOWN_K_WAVES     K slices that the four waves of a down-projection workgroup form (1, 2, or 4 for batches
+ *                               of at most 16 tokens; default 0 = the library's rule)
  */
 #define LYNX_DEBUG_SPIN_LIMIT 1
 #define LYNX_DEBUG_TARGET_BIAS 2
 #define LYNX_DEBUG_DOWN_ITEM_CAP 3
 #define LYNX_DEBUG_DOWN_ITEM_UNITS 4
+#define LYNX_DEBUG_DOWN_K_WAVES 5
 int lynx_debug_set(int what, int value);
 
 #ifdef __cplusplus

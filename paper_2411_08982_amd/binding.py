@@ -378,7 +378,7 @@ def lynx_residual_add(x, y, out=None):
     return out
 
 
-DEBUG_SPIN_LIMIT, DEBUG_TARGET_BIAS, DEBUG_DOWN_ITEM_CAP, DEBUG_DOWN_ITEM_UNITS = 1, 2, 3, 4
+DEBUG_SPIN_LIMIT, DEBUG_TARGET_BIAS, DEBUG_DOWN_ITEM_CAP, DEBUG_DOWN_ITEM_UNITS, DEBUG_DOWN_K_WAVES = 1, 2, 3, 4, 5
 
 
 def lynx_debug_set(what: int, value: int):

@@ -34,7 +34,10 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 constexpr int kFfnThreads = 256;
 constexpr int kFfnWaves = kFfnThreads / kWave;
 constexpr int kPF = 8;                       // staged path: weight tiles in flight per wave and matrix
-constexpr int kPFD = 8;                      // direct path: the same (most; see DirectDepth for the depth per format)
+#ifndef LYNX_PFD
+#define LYNX_PFD 8
+#endif
+constexpr int kPFD = LYNX_PFD;               // direct path: the same (most; see DirectDepth for the depth per format)
 constexpr int kStageBytes = 2 * 18432;       // two LDS buffers for the staged token tile
 constexpr int kStageBytesBig = 2 * 128 * (4 * 64 + 16);   // the same in the large-batch kernels (128 tokens x 4 k-steps)
 
@@ -47,11 +50,12 @@ __device__ unsigned long long g_timeline[kTimelineSlots][6];
 #define LYNX_TS_BEGIN(kind, b)                                                                                         \
     const int ts_slot_ = (int)blockIdx.x < kTimelineSlots ? (int)blockIdx.x : kTimelineSlots - 1;                      \
     if (threadIdx.x == 0) {                                                                                            \
-        unsigned xcc_;                                                                                                 \
+        unsigned xcc_, hwid_;                                                                                          \
         asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc_));                                          \
+        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hwid_));                                          \
         g_timeline[ts_slot_][0] = wall_clock64();                                                                      \
         g_timeline[ts_slot_][4] = ((unsigned long long)(kind) << 32) | (unsigned)(b);                                  \
-        g_timeline[ts_slot_][5] = xcc_ & 0xf;                                                                          \
+        g_timeline[ts_slot_][5] = (xcc_ & 0xf) | ((unsigned long long)hwid_ << 8);                                     \
         g_timeline[ts_slot_][1] = g_timeline[ts_slot_][2] = g_timeline[ts_slot_][3] = 0;                               \
     }
 #define LYNX_TS(i)                                                                                                     \
@@ -358,12 +362,28 @@ __device__ __forceinline__ uint4 ring_load_b(BufferRsrc rs, unsigned off, int in
     return make_uint4(v.x, v.y, v.z, v.w);
 }
 
-// The same for expert weights, as a non-temporal load: a weight byte is read once per launch, and a stream
-// that does not allocate in the caches on its way runs measurably closer to the HBM rate.
-__device__ __forceinline__ uint4 ring_load_weights(const uint4 *__restrict__ base, int index)
+// Expert weights: a non-temporal load (a weight byte is read once per launch, and a stream that does not allocate in
+// the caches on its way runs measurably closer to the HBM rate) through a buffer resource over the wave's run of weight
+// tiles.  The ring is refilled without branches, so a wave nearing the end of its run still issues its refills; those
+// carry an offset past the resource's range, for which the hardware returns zero and fetches nothing.  (Clamping them
+// to the last tile instead re-read that tile once per ring slot: with the short runs of small experts, a down
+// projection of 12 k-steps behind a ring of 8, two thirds more loads than the weights need.  A streaming probe with
+// the same clamped ring reads 12 KiB runs at 5.9 TB/s and runs of 24 KiB and more at 7.0-7.2 TB/s.)
+__device__ __forceinline__ BufferRsrc weights_resource(const uint4 *wave_base)
 {
-    asm volatile("" : "+v"(index));
-    const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(base) + index);
+    // the run's first tile is the same for all lanes of a wave: hand the address over as scalars
+    const unsigned long long a = reinterpret_cast<unsigned long long>(wave_base);
+    const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)a), hi = __builtin_amdgcn_readfirstlane((unsigned)(a >> 32));
+    return __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void *>(((unsigned long long)hi << 32) | lo), 0, 0x7fffffff,
+                                             0x00020000);
+}
+constexpr int kAuxNonTemporal = 2;
+// index: in 16-byte units from this lane's piece of the run's first tile; live = false: nothing is fetched, zero returns
+__device__ __forceinline__ uint4 ring_load_weights(BufferRsrc rs, int index, bool live)
+{
+    unsigned off = live ? ((unsigned)index + (unsigned)lane_id()) * 16u : kNoToken;
+    asm volatile("" : "+v"(off));
+    const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, off, 0, kAuxNonTemporal);
     return make_uint4(v.x, v.y, v.z, v.w);
 }
 
@@ -444,7 +464,7 @@ struct WeightRing {
 
 // Where a wave of the direct path streams from: needs the expert, not its tokens.
 struct DirectPlan {
-    const uint4 *Wl;     // this lane's piece of the wave's first weight tile
+    const uint4 *Wb;     // the wave's first weight tile (the same for all lanes)
     const uint2 *Sl;     // MXFP4: this lane's scale dwords of the wave's row group, k-tile group 0
     int step, second;    // uint4 strides: next k-step, second stream
     int kb, n;           // first k-step and k-steps of this wave
@@ -472,7 +492,7 @@ __device__ __forceinline__ DirectPlan plan_direct(const WorkItem &w)
     d.kt0 = kbc;
     d.step = DUAL ? 2 * kWave : kWave;
     d.second = DUAL ? kWave : KT * kWave;
-    d.Wl = w.W + ((size_t)rtc * KT + kbc) * d.step + lane_id();
+    d.Wb = w.W + ((size_t)rtc * KT + kbc) * d.step;
     d.Sl = nullptr;
     if (WF == 2)
         d.Sl = reinterpret_cast<const uint2 *>(w.sc) + (size_t)(d.rows_ok ? grp : 0) * mx_kt4(w.K) * kWave + lane_id();
@@ -490,11 +510,12 @@ __device__ __forceinline__ void prefetch_weights(const DirectPlan &d, WeightRing
 {
     constexpr int D = DirectDepth<WF>::value;
     const int last = max(d.n, 1) - 1;
+    const BufferRsrc rw = weights_resource(d.Wb);
 #pragma unroll
     for (int j = 0; j < D; ++j) {
         const int s = min(j, last);
-        r.w0[j] = ring_load_weights(d.Wl, s * d.step);
-        r.w1[j] = ring_load_weights(d.Wl, s * d.step + d.second);
+        r.w0[j] = ring_load_weights(rw, j * d.step, j <= last);
+        r.w1[j] = ring_load_weights(rw, j * d.step + d.second, j <= last);
         if (WF == 2) r.sq[j] = ring_load_scales(d.Sl, ((d.kt0 + s) >> 2) * kWave);
     }
 }
@@ -507,18 +528,17 @@ __device__ __forceinline__ void stream_direct(const DirectPlan &d, WeightRing &r
     constexpr int D = DirectDepth<WF>::value;
     constexpr int BP = 1 << WF;              // 16-byte pieces of a token row per lane and weight tile = its k-steps
     constexpr int BS = TileCols<WF>::value / 8;   // uint4 units between the pieces of consecutive tiles
-    const uint4 *Wl = d.Wl;
+    const BufferRsrc rw = weights_resource(d.Wb);
     const int step = d.step, second = d.second;
     const int n = d.rows_ok ? d.n : 0;     // k-steps whose products count
     const int last = max(d.n, 1) - 1;
     uint4 bb[D][NT][BP];
 #pragma unroll
     for (int j = 0; j < D; ++j) {
-        const int s = min(j, last);
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-            for (int h = 0; h < BP; ++h) bb[j][nt][h] = ring_load_b(rs, boff[nt], s * BS + h);
+            for (int h = 0; h < BP; ++h) bb[j][nt][h] = ring_load_b(rs, j <= last ? boff[nt] : kNoToken, j * BS + h);
     }
     // One turn of the ring: consume the D slots in order, refilling each right after its last read.
     auto turn = [&](int s0) {
@@ -542,14 +562,15 @@ __device__ __forceinline__ void stream_direct(const DirectPlan &d, WeightRing &r
             // ... then refill it (the scheduling fences keep the refill behind the last read of the slot,
             // so that it can land in the same registers and the ring needs no copies)
             __builtin_amdgcn_sched_barrier(0);
-            const int sn = min(s + D, last);
-            r.w0[u] = ring_load_weights(Wl, sn * step);
-            r.w1[u] = ring_load_weights(Wl, sn * step + second);
-            if (WF == 2) r.sq[u] = ring_load_scales(d.Sl, ((d.kt0 + sn) >> 2) * kWave);
+            const int sn = s + D;          // refills past the end of the run fetch nothing
+            const bool more = sn <= last;
+            r.w0[u] = ring_load_weights(rw, sn * step, more);
+            r.w1[u] = ring_load_weights(rw, sn * step + second, more);
+            if (WF == 2) r.sq[u] = ring_load_scales(d.Sl, ((d.kt0 + min(sn, last)) >> 2) * kWave);
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-                for (int h = 0; h < BP; ++h) bb[u][nt][h] = ring_load_b(rs, boff[nt], sn * BS + h);
+                for (int h = 0; h < BP; ++h) bb[u][nt][h] = ring_load_b(rs, more ? boff[nt] : kNoToken, sn * BS + h);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -684,14 +705,14 @@ __device__ __forceinline__ void stream_staged(const uint4 *__restrict__ Wt, bool
         }
     };
 
-    const uint4 *Wl = Wt + lane;
+    const BufferRsrc rw = weights_resource(Wt);
     uint4 wg[kPF], wu[kPF];
     uint2 sq[kPF];
 #pragma unroll
     for (int j = 0; j < kPF; ++j) {
         const int s = min(j, last);
-        wg[j] = ring_load_weights(Wl, s * WSTEP);
-        wu[j] = DUAL ? ring_load_weights(Wl, s * WSTEP + kWave) : zero4();
+        wg[j] = ring_load_weights(rw, j * WSTEP, j <= last);
+        wu[j] = DUAL ? ring_load_weights(rw, j * WSTEP + kWave, j <= last) : zero4();
         if (WF == 2) sq[j] = ring_load_scales(Sl, ((kt0 + s) >> 2) * kWave);
     }
     load_x(0);
@@ -724,10 +745,10 @@ __device__ __forceinline__ void stream_staged(const uint4 *__restrict__ Wt, bool
                     if (DUAL) accu[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(au[h], b, accu[nt], 0, 0, 0);
                 }
             __builtin_amdgcn_sched_barrier(0);
-            const int sn = min(s + kPF, last);
-            wg[u] = ring_load_weights(Wl, sn * WSTEP);
-            if (DUAL) wu[u] = ring_load_weights(Wl, sn * WSTEP + kWave);
-            if (WF == 2) sq[u] = ring_load_scales(Sl, ((kt0 + sn) >> 2) * kWave);
+            const int sn = s + kPF;        // refills past the end of the run fetch nothing
+            wg[u] = ring_load_weights(rw, sn * WSTEP, sn <= last);
+            if (DUAL) wu[u] = ring_load_weights(rw, sn * WSTEP + kWave, sn <= last);
+            if (WF == 2) sq[u] = ring_load_scales(Sl, ((kt0 + min(sn, last)) >> 2) * kWave);
             __builtin_amdgcn_sched_barrier(0);
             if ((u * TS + TS - 1) % KS == KS - 1) {
                 store_x(c + 1);
@@ -905,8 +926,13 @@ __device__ __forceinline__ void expert_work(const GemmParams &p, int b, const Ff
     }
 }
 
+#ifndef LYNX_WGCU
+#define LYNX_WGCU 2
+#endif
+constexpr int kWgPerCuSmall = LYNX_WGCU;   // workgroups per CU of the kernels for batches of at most 64 tokens
+
 template <int KWD, bool BIG, int WF>
-__global__ __launch_bounds__(kFfnThreads, 2) void ffn_kernel(FfnParams fp)
+__global__ __launch_bounds__(kFfnThreads, (BIG || WF != 0) ? 2 : kWgPerCuSmall) void ffn_kernel(FfnParams fp)
 {
     // staged token tile, or the K-slice partial sums
     __shared__ __attribute__((aligned(16))) char stage[BIG ? kStageBytesBig : kStageBytes];
@@ -927,10 +953,27 @@ __global__ __launch_bounds__(kFfnThreads, 2) void ffn_kernel(FfnParams fp)
         if (WF == 0 && fp.gu_split) {
             const int live = fp.gu.shared_blocks + max(fp.gu.plan[kWsPlanHdr + kPlanB], 0) * fp.gu.tiles_r;
             const int full = live / kSplitRound * kSplitRound, rem = live - full;
-            if (rem > 0 && rem <= kSplitMaxRem && full >= fp.gu.shared_blocks && b >= full) {
-                bb = full + (b - full) / kFfnWaves;
-                sub = (b - full) % kFfnWaves;
-                if (bb >= live) return;
+            if (rem > 0 && rem <= kSplitMaxRem && full >= fp.gu.shared_blocks) {
+                // When everything is resident at once (at most two workgroups per CU), the small workgroups go
+                // first: of two workgroups on a CU the older gets most of the CU's share of the stream, and a small
+                // workgroup that is the younger one is left with most of its tiles when the large one ends, which it
+                // then streams alone at a single workgroup's rate (measured: the last of them ended at 43 us, the
+                // four-tile workgroups at 24-32 us).  With more rounds the small ones stay last: they fill the tail.
+                const bool small_first = live <= 2 * kSplitRound;
+                const int nsub = rem * kFfnWaves;
+                if (small_first) {
+                    if (b < nsub) {
+                        bb = full + b / kFfnWaves;
+                        sub = b % kFfnWaves;
+                    } else {
+                        bb = b - nsub;
+                        if (bb >= full) return;
+                    }
+                } else if (b >= full) {
+                    bb = full + (b - full) / kFfnWaves;
+                    sub = (b - full) % kFfnWaves;
+                    if (bb >= live) return;
+                }
             }
         }
         if (WF != 0 || sub < 0)
@@ -1195,6 +1238,7 @@ struct Tunables {
     std::atomic<int> target_bias{0};
     std::atomic<int> dn_cap{768};      // down items the grid aims at (two per CU are resident: 512)
     std::atomic<int> dn_m_max{1};      // most row units per down item
+    std::atomic<int> dn_kw{0};         // 0 = the rule of pick_k_waves, else the K slices of a down workgroup's waves
 };
 static Tunables g_tune;
 
@@ -1214,6 +1258,8 @@ static FfnShape ffn_shape(int T, int H, int F, int N, int k, int n_shared, int f
     FfnShape s;
     const int max_experts = (int)min((long)N, (long)T * k) + n_shared;
     s.kwd = pick_k_waves(F, false, T, max_experts, 16 >> format);
+    const int forced = g_tune.dn_kw.load();
+    if (forced == 1 || forced == 2 || (forced == 4 && T <= kDirectMaxTokens)) s.kwd = forced;
     s.big = T > kTokBlock;
     s.single = single_launch(T, F);
     s.tok_block = s.big ? kTokBlockBig : kTokBlock;
@@ -1223,7 +1269,7 @@ static FfnShape ffn_shape(int T, int H, int F, int N, int k, int n_shared, int f
     s.plan.units_dn = (H + rows_dn - 1) / rows_dn;
     s.plan.tok_block = s.tok_block;
     // Longer down items only where the staged unit and the direct workgroup are the same 64 rows (two K slices).
-    s.plan.dn_m_max = s.kwd == 2 ? max(1, g_tune.dn_m_max.load()) : 1;
+    s.plan.dn_m_max = s.kwd <= 2 ? max(1, g_tune.dn_m_max.load()) : 1;
     s.plan.dn_cap = max(1, g_tune.dn_cap.load());
     return s;
 }
@@ -1253,18 +1299,18 @@ static unsigned grid_blocks(const GemmParams &p) { return (unsigned)(p.shared_bl
 // Workgroups per CU.  The dispatcher fills a CU up to its occupancy limit before it moves on, so a grid
 // that is small compared with the chip (few invoked experts) would leave CUs idle while others hold three
 // workgroups.  A dynamic-LDS pad makes exactly kWgPerCu workgroups fit a CU, which spreads such grids.
-constexpr int kWgPerCu = 2;
 constexpr int kLdsPerCu = 160 * 1024;
-constexpr int kLdsTargetPerWg = 56 * 1024;
 
 template <int KWD, bool BIG, int WF>
 static int launch_padded(const FfnParams &fp, unsigned blocks, hipStream_t st)
 {
+    constexpr int kWgPerCu = (BIG || WF != 0) ? 2 : kWgPerCuSmall;
+    constexpr int kLdsTargetPerWg = kWgPerCu == 2 ? 56 * 1024 : kLdsPerCu / kWgPerCu / 1024 * 1024;   // (at most 64 KiB per workgroup)
     static_assert(kLdsTargetPerWg * (kWgPerCu + 1) > kLdsPerCu && kLdsTargetPerWg * kWgPerCu <= kLdsPerCu, "LDS pad");
     // what the kernel declares itself: the stage, the two token tables and the item record
     constexpr int kStatic = (BIG ? kStageBytesBig : kStageBytes) + 2 * 4 * (BIG ? kTokBlockBig : kTokBlock) + (int)sizeof(ItemShared);
     constexpr int pad = kLdsTargetPerWg > kStatic ? kLdsTargetPerWg - kStatic : 0;
-    static_assert((kStatic + pad) * kWgPerCu <= kLdsPerCu, "two workgroups must fit a CU");
+    static_assert((kStatic + pad) * kWgPerCu <= kLdsPerCu, "the workgroups must fit a CU");
     hipLaunchKernelGGL((ffn_kernel<KWD, BIG, WF>), dim3(blocks), dim3(kFfnThreads), pad, st, fp);
     return LYNX_OK;
 }
@@ -1295,7 +1341,9 @@ static int launch_ffn(FfnParams fp, const FfnShape &sh, hipStream_t st)
         fp.wait = sh.single ? 1 : 0;
         fp.block0 = part == 0 ? 0 : fp.gu_blocks;
         const unsigned blocks = sh.single ? (unsigned)fp.gu_blocks + dn_blocks : part == 0 ? (unsigned)fp.gu_blocks : dn_blocks;
-        if (sh.big)
+        if (sh.big && sh.kwd == 1)
+            rc = launch_padded<1, true, WF>(fp, blocks, st);
+        else if (sh.big)
             rc = launch_padded<2, true, WF>(fp, blocks, st);
         else if (sh.kwd == 4)
             rc = launch_padded<4, false, WF>(fp, blocks, st);
@@ -1328,6 +1376,7 @@ extern "C" int lynx_debug_set(int what, int value)
     case LYNX_DEBUG_TARGET_BIAS: g_tune.target_bias.store(value); return LYNX_OK;
     case LYNX_DEBUG_DOWN_ITEM_CAP: g_tune.dn_cap.store(value <= 0 ? 768 : value); return LYNX_OK;
     case LYNX_DEBUG_DOWN_ITEM_UNITS: g_tune.dn_m_max.store(value <= 0 ? 1 : value); return LYNX_OK;
+    case LYNX_DEBUG_DOWN_K_WAVES: g_tune.dn_kw.store(value <= 0 ? 0 : value); return LYNX_OK;
     default: return fail(LYNX_ERR_INVALID_ARG, "lynx_debug_set: unknown knob %d", what);
     }
 }
