@@ -173,7 +173,9 @@ __device__ __forceinline__ WorkItem resolve_item(const GemmParams &p, int b, Ite
             ish->tb = q - lo;
         }
         __syncthreads();
-        const int e = ish->e, te = ish->te, off = ish->off, tb = ish->tb;
+        // (the same for every lane: kept in scalar registers, and everything derived from them too)
+        const int e = __builtin_amdgcn_readfirstlane(ish->e), te = __builtin_amdgcn_readfirstlane(ish->te),
+                  off = __builtin_amdgcn_readfirstlane(ish->off), tb = __builtin_amdgcn_readfirstlane(ish->tb);
         if (e < 0 || e >= p.N || te <= 0 || off < 0 || off + te > p.T * p.k) return w;
         w.e = e;
         w.off = off;
@@ -671,37 +673,31 @@ __device__ __forceinline__ void stream_staged(const uint4 *__restrict__ Wt, bool
     const int last = KT - 1;
     const int lastc = (KT * TS + KS - 1) / KS - 1;
 
-    // this thread's staging pieces: (token row, 16-byte piece inside the chunk)
-    int xoff[PPT];    // element offset of the piece's token row
-    bool xok[PPT];
-#pragma unroll
-    for (int i = 0; i < PPT; ++i) {
-        const int q = tid + kFfnThreads * i;
-        const int row = q / (KS * 4);
-        const int ro = rowoff[row];
-        xok[i] = ro >= 0;
-        xoff[i] = ro >= 0 ? ro : max(rowoff[0], 0);   // rows without a token: the pass's first row, zeroed below
-    }
+    // This thread's staging pieces: (token row, 16-byte piece inside the chunk).  The rows' offsets stay in the LDS
+    // table and are looked up again for every chunk: registers are what this path is short of.  The pieces are read
+    // through a buffer resource over the B array; a piece of a row without a token, or past the row's last column
+    // (the last chunk of a ragged K, or a row shorter than one chunk), carries an offset out of range: nothing is
+    // fetched for it and it arrives as zero, which is what the stage has to hold there.
+    const BufferRsrc rb = token_rows_resource(B);
     const int pc0 = (tid % (KS * 4)) * 8;   // column of every piece of this thread inside a chunk (256 % (KS*4) == 0)
     uint4 xr[PPT];
     // chunk c: request it ... (nothing here reads what was loaded: a read would have to wait for the load, and
-    // with it for every weight tile requested before it).  A piece past the row's last column (the last chunk of a
-    // ragged K, or a row shorter than one chunk) reads the row's first piece instead, so that no load leaves the
-    // row; it is stored as zero.
+    // with it for every weight tile requested before it)
     auto load_x = [&](int c) {
         const int col = c * KS * 32 + pc0;
-        const int ccol = col < K ? col : 0;
 #pragma unroll
-        for (int i = 0; i < PPT; ++i) xr[i] = ring_load(reinterpret_cast<const uint4 *>(B + (size_t)xoff[i] + ccol), 0);
+        for (int i = 0; i < PPT; ++i) {
+            const int ro = rowoff[(tid + kFfnThreads * i) / (KS * 4)];
+            xr[i] = ring_load_b(rb, (ro >= 0 && col < K) ? 2u * (unsigned)(ro + col) : kNoToken, 0);
+        }
     };
-    // ... and, a chunk of weight tiles later, put it into the stage; rows without a token and columns past K as zero
+    // ... and, a chunk of weight tiles later, put it into the stage
     auto store_x = [&](int c) {
         char *buf = stage + (c & 1) * BUFB;
-        const bool inside = c * KS * 32 + pc0 < K;
 #pragma unroll
         for (int i = 0; i < PPT; ++i) {
             const int q = tid + kFfnThreads * i;
-            *reinterpret_cast<uint4 *>(buf + (q / (KS * 4)) * ROWB + (q % (KS * 4)) * 16) = sel4(inside && xok[i], xr[i]);
+            *reinterpret_cast<uint4 *>(buf + (q / (KS * 4)) * ROWB + (q % (KS * 4)) * 16) = xr[i];
         }
     };
 
@@ -892,7 +888,11 @@ __device__ __forceinline__ void expert_work(const GemmParams &p, int b, const Ff
         const int tid = threadIdx.x;
         for (int un = 0; un < units; ++un) {
             const int tile = unit0 + un;
-            if (!shared && (tile % kShare) != 0) continue;   // leaves the unit to the workgroup it shares it with
+            // Of the workgroups that share a unit one does the work and the others leave.  Which one rotates with the
+            // unit and the expert: the sharing workgroups have consecutive indices, so a fixed choice would put all the
+            // staged work of the launch on the XCDs that the first of every four workgroups goes to (measured: two of
+            // the eight XCDs ended their gate/up work at 44 us, the others at 31 us).
+            if (!shared && (tile % kShare) != ((tile / kShare + w.e) % kShare)) continue;
             const int s0 = shared ? tile : (tile / kShare) * kUnits;
             const int sn = shared ? 1 : kUnits;
             for (int su = 0; su < sn; ++su) {
