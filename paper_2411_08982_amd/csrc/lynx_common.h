@@ -187,10 +187,11 @@ constexpr int kWsDone = kWsMember + LYNX_MAX_N * (LYNX_MAX_T / 32);   // FFN: ga
 constexpr int kWsDoneWords = 1024;                         // LYNX_MAX_N routed + (shared expert, token block) pairs
 constexpr int kWsFlags = kWsDone + kWsDoneWords;           // FFN: bit 0 = a bounded wait ran out
 constexpr int kWsPlanHdr = kWsFlags + 16;                  // FFN work plan (lynx_plan.h): header, 16 words
-constexpr int kWsPlanPrefix = kWsPlanHdr + 16;             // block prefix per rank, LYNX_MAX_N + 1 words (padded to 16)
-constexpr int kWsPlanRec = kWsPlanPrefix + LYNX_MAX_N + 16;   // two words per rank
-constexpr int kWsRoutingWords = kWsPlanRec + 2 * LYNX_MAX_N;
-constexpr size_t kWsRoutingBytes = 65536;
+constexpr int kPlanMaxBlocks = 512;                        // most (expert, token block) pairs: LYNX_MAX_N + LYNX_MAX_T * LYNX_MAX_K / 128, rounded up
+constexpr int kWsPlanBlk = kWsPlanHdr + 16;                // one record of four words per (expert, token block) pair
+constexpr int kWsPlanPairs = kWsPlanBlk + 4 * kPlanMaxBlocks;   // 16 pair ids of 16 bits per block: 8 words each
+constexpr int kWsRoutingWords = kWsPlanPairs + 8 * kPlanMaxBlocks;
+constexpr size_t kWsRoutingBytes = 98304;
 static_assert((size_t)kWsRoutingWords * 4 <= kWsRoutingBytes, "routing scratch does not fit its reservation");
 
 inline int h_stride(int F) { return (F + 63) / 64 * 64; }   // elements between rows of the h scratch

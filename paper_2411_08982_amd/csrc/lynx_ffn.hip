@@ -84,6 +84,7 @@ struct GemmParams {
     int tok_block;              // tokens per block: one pass of the staged path
     int routed_blocks, shared_blocks;   // grid = shared blocks first (the longest workgroups), then routed
     int shared_splits;          // K slices per shared expert (down projection only; each slice has its own output rows)
+    int dn_m_max;               // most row units per down item that the plan may choose (1: always one)
     long long shared_h_base;    // element offset of the shared experts' h rows in the h scratch
 };
 
@@ -99,6 +100,7 @@ struct WorkItem {
     int tok0;            // first token of this work item's token block
     int kbeg, ksteps;    // slice of the contraction dimension this work item covers, in weight tiles (32 or 64 columns)
     int out_base;        // shared experts: first output row of this work item
+    int pair;            // direct path, routed experts: the pair id of this lane's token column (lane % 16), -1 = none
     bool valid;
 };
 
@@ -122,17 +124,13 @@ __host__ __device__ __forceinline__ size_t mx_scale_dwords(int R, int K)
     return (size_t)(DUAL ? R / 16 : R / 32) * mx_kt4(K) * 128;
 }
 
-// What the plan says of a routed work item, handed from the thread that found it to the workgroup.
-struct ItemShared {
-    int e, te, off, tb;
-};
-
 // Which work item workgroup b of a projection is: one round trip to memory.  The shared experts' items come first
 // (static: they see every token); the routed items follow in the plan's order, item = block * per + unit with
-// per = the row units (gate/up) or groups of m row units (down) of one (expert, token block) pair.  Every thread of
-// the workgroup calls this (it holds a barrier).  w.tile = the first row unit of the item, units = how many it covers.
+// per = the row units (gate/up) or groups of m row units (down) of one (expert, token block) pair.  The block's
+// record, the header and the lane's pair id are requested together; their addresses follow from b alone.
+// w.tile = the first row unit of the item, units = how many it covers.
 template <bool DUAL, int WF>
-__device__ __forceinline__ WorkItem resolve_item(const GemmParams &p, int b, ItemShared *ish, int &units)
+__device__ __forceinline__ WorkItem resolve_item(const GemmParams &p, int b, int &units)
 {
     constexpr int KC = TileCols<WF>::value;
     WorkItem w;
@@ -144,6 +142,7 @@ __device__ __forceinline__ WorkItem resolve_item(const GemmParams &p, int b, Ite
     w.e = -1;
     w.shared_s = -1;
     w.tok0 = 0;
+    w.pair = -1;
     w.B = p.B;
     w.out = p.out;
     units = 1;
@@ -151,31 +150,19 @@ __device__ __forceinline__ WorkItem resolve_item(const GemmParams &p, int b, Ite
     if (b >= p.shared_blocks) {
         const int idx = b - p.shared_blocks;
         const int32_t *__restrict__ plan = p.plan;
-        const int tid = threadIdx.x;
-        // everything is requested at once: the header words and, per thread, one rank's prefix entries and record
+        // (down items of more than one row unit: their number per block is a device-side value, and the block
+        // follows from it: a second round trip, only with that tuning knob set)
+        const int m = (DUAL || p.dn_m_max <= 1) ? 1 : max(plan[kWsPlanHdr + kPlanM], 1);
+        const int per = (p.tiles_r + m - 1) / m;
+        const int q = min(idx / per, kPlanMaxBlocks - 1);
         const int B = plan[kWsPlanHdr + kPlanB];
-        const int m = DUAL ? 1 : plan[kWsPlanHdr + kPlanM];
-        int lo = 0, hi = 0, r0 = 0, r1 = 0;
-        if (tid < p.N) {
-            lo = plan[kWsPlanPrefix + tid];
-            hi = plan[kWsPlanPrefix + tid + 1];
-            r0 = plan[kWsPlanRec + 2 * tid];
-            r1 = plan[kWsPlanRec + 2 * tid + 1];
-        }
-        const int mm = m >= 1 ? m : 1;
-        const int per = (p.tiles_r + mm - 1) / mm;
+        const int4 rec = *reinterpret_cast<const int4 *>(plan + kWsPlanBlk + 4 * q);
+        const unsigned pv = reinterpret_cast<const uint16_t *>(plan + kWsPlanPairs)[q * kDirectMaxTokens + (lane_id() & 15)];
         if (B <= 0 || idx >= per * B) return w;   // (uniform: the whole workgroup leaves)
-        const int q = idx / per;
-        if (tid < p.N && lo <= q && q < hi) {
-            ish->e = r0 & 0xffff;
-            ish->te = (int)((unsigned)r0 >> 16);
-            ish->off = r1;
-            ish->tb = q - lo;
-        }
-        __syncthreads();
         // (the same for every lane: kept in scalar registers, and everything derived from them too)
-        const int e = __builtin_amdgcn_readfirstlane(ish->e), te = __builtin_amdgcn_readfirstlane(ish->te),
-                  off = __builtin_amdgcn_readfirstlane(ish->off), tb = __builtin_amdgcn_readfirstlane(ish->tb);
+        const int r0 = __builtin_amdgcn_readfirstlane(rec.x);
+        const int e = r0 & 0xffff, te = (int)((unsigned)r0 >> 16);
+        const int off = __builtin_amdgcn_readfirstlane(rec.y), tb = __builtin_amdgcn_readfirstlane(rec.z);
         if (e < 0 || e >= p.N || te <= 0 || off < 0 || off + te > p.T * p.k) return w;
         w.e = e;
         w.off = off;
@@ -186,9 +173,10 @@ __device__ __forceinline__ WorkItem resolve_item(const GemmParams &p, int b, Ite
             if (w.tok0 >= te) return w;
         } else {
             w.Te = te;
+            w.pair = (int)pv;   // (checked where it is used)
         }
-        w.tile = (idx % per) * mm;
-        units = min(mm, p.tiles_r - w.tile);
+        w.tile = (idx % per) * m;
+        units = min(m, p.tiles_r - w.tile);
         w.R = p.R;
         w.K = p.K;
         w.ldb = p.ldb_r;
@@ -260,6 +248,30 @@ __device__ __forceinline__ void token_rows(const GemmParams &p, const WorkItem &
     } else {
         ro = i * w.ldb;
         orow = w.out_base + i;
+    }
+}
+
+// The same for this lane's token column on the direct path, from the pair id that came with the item: no load.
+template <bool DUAL>
+__device__ __forceinline__ void token_rows_direct(const GemmParams &p, const WorkItem &w, int &ro, int &orow)
+{
+    const int i = lane_id() & 15;
+    ro = -1;
+    orow = -1;
+    if (i >= w.Te) return;
+    if (w.shared_s < 0) {
+        const bool ok = w.pair >= 0 && w.pair < p.T * p.k;
+        if (DUAL) {
+            if (!ok) return;
+            ro = (w.pair / p.k) * w.ldb;
+            orow = w.off + i;
+        } else {
+            ro = (w.off + i) * w.ldb;
+            orow = ok ? w.pair : -1;
+        }
+    } else {
+        ro = i * w.ldb;
+        orow = DUAL ? i : w.out_base + i;
     }
 }
 
@@ -355,7 +367,12 @@ constexpr unsigned kNoToken = 0x80000000u;   // past any resource (the B arrays 
 typedef __amdgpu_buffer_rsrc_t BufferRsrc;
 __device__ __forceinline__ BufferRsrc token_rows_resource(const uint16_t *B)
 {
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(B), 0, 0x7fffffff, 0x00020000);
+    // the array is the same for all lanes of a wave: hand the address over as scalars (a resource that the compiler
+    // takes for a per-lane value costs a loop over its distinct values around every load)
+    const unsigned long long a = reinterpret_cast<unsigned long long>(B);
+    const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)a), hi = __builtin_amdgcn_readfirstlane((unsigned)(a >> 32));
+    return __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void *>(((unsigned long long)hi << 32) | lo), 0, 0x7fffffff,
+                                             0x00020000);
 }
 __device__ __forceinline__ uint4 ring_load_b(BufferRsrc rs, unsigned off, int index)
 {
@@ -822,12 +839,12 @@ __device__ __forceinline__ int done_slot(const GemmParams &p, const WorkItem &w)
 // sub >= 0 (gate/up, KW = 4 only): the workgroup takes row tile `sub` of the four that workgroup b stands for.
 template <bool DUAL, int KW, bool BIG, int WF>
 __device__ __forceinline__ void expert_work(const GemmParams &p, int b, const FfnParams &fp, char *stage, int *rowoff,
-                                            int *outrow, ItemShared *ish, int sub = -1)
+                                            int *outrow, int sub = -1)
 {
     constexpr int TB = BIG ? kTokBlockBig : kTokBlock;   // tokens per pass
     int units;
     LYNX_TS_BEGIN(DUAL ? (sub >= 0 ? 2 : 1) : 0, b);
-    WorkItem w = resolve_item<DUAL, WF>(p, b, ish, units);
+    WorkItem w = resolve_item<DUAL, WF>(p, b, units);
     if (!w.valid) return;
     if (sub >= 0) w.tile = w.tile * kFfnWaves + sub;
     int32_t *counter = fp.done + done_slot(p, w);
@@ -858,7 +875,7 @@ __device__ __forceinline__ void expert_work(const GemmParams &p, int b, const Ff
         WeightRing ring;
         prefetch_weights<WF>(plan, ring);
         int ro[1], orow[1];
-        token_rows<DUAL>(p, w, lane_id() & 15, ro[0], orow[0]);
+        token_rows_direct<DUAL>(p, w, ro[0], orow[0]);
         wait_for_h();
         LYNX_TS(2);
         for (int un = 0; un < units; ++un) {
@@ -938,7 +955,6 @@ __global__ __launch_bounds__(kFfnThreads, (BIG || WF != 0) ? 2 : kWgPerCuSmall) 
     __shared__ __attribute__((aligned(16))) char stage[BIG ? kStageBytesBig : kStageBytes];
     __shared__ int rowoff[BIG ? kTokBlockBig : kTokBlock];   // staged path: element offset of each token's B row, -1 = none
     __shared__ int outrow[BIG ? kTokBlockBig : kTokBlock];   // staged path: output row of each token, -1 = none
-    __shared__ ItemShared ish;
     const int b = blockIdx.x + fp.block0;
     if (b < fp.gu_blocks) {
         // Gate/up workgroups take four row tiles, one per wave, and the dispatcher hands workgroups to the CUs
@@ -977,20 +993,20 @@ __global__ __launch_bounds__(kFfnThreads, (BIG || WF != 0) ? 2 : kWgPerCuSmall) 
             }
         }
         if (WF != 0 || sub < 0)
-            expert_work<true, 1, BIG, WF>(fp.gu, bb, fp, stage, rowoff, outrow, &ish);
+            expert_work<true, 1, BIG, WF>(fp.gu, bb, fp, stage, rowoff, outrow);
         else if constexpr (WF == 0)
-            expert_work<true, kFfnWaves, BIG, WF>(fp.gu, bb, fp, stage, rowoff, outrow, &ish, sub);
+            expert_work<true, kFfnWaves, BIG, WF>(fp.gu, bb, fp, stage, rowoff, outrow, sub);
     } else {
-        expert_work<false, KWD, BIG, WF>(fp.dn, b - fp.gu_blocks, fp, stage, rowoff, outrow, &ish);
+        expert_work<false, KWD, BIG, WF>(fp.dn, b - fp.gu_blocks, fp, stage, rowoff, outrow);
     }
 }
 
 // The plan from a caller's token assignment (lynx_moe_ffn after lynx_permute): the experts with a valid, non-empty
 // range in expert_offsets are the invoked ones.  One workgroup; also clears the completion counters and the flags.
-__global__ __launch_bounds__(256) void plan_kernel(const int32_t *__restrict__ offsets, int N, int P, PlanShape ps,
-                                                   int32_t *__restrict__ ws)
+__global__ __launch_bounds__(256) void plan_kernel(const int32_t *__restrict__ offsets, const int32_t *__restrict__ perm, int N,
+                                                   int P, PlanShape ps, int32_t *__restrict__ ws)
 {
-    __shared__ int count[LYNX_MAX_N], offs[LYNX_MAX_N];
+    __shared__ int count[LYNX_MAX_N], offs[LYNX_MAX_N], blk0[LYNX_MAX_N];
     const int tid = threadIdx.x;
     for (int i = tid; i < kWsDoneWords + 16; i += 256) ws[kWsDone + i] = 0;
     if (tid < N) {
@@ -1000,7 +1016,13 @@ __global__ __launch_bounds__(256) void plan_kernel(const int32_t *__restrict__ o
         offs[tid] = ok ? o0 : 0;
     }
     __syncthreads();
-    build_plan<256>(ps, N, count, offs, ws);
+    build_plan<256>(ps, N, count, offs, blk0, ws);
+    __syncthreads();
+    // the pair ids of the experts on the direct path, 16 threads per expert
+    for (int e = tid / kDirectMaxTokens; e < N; e += 256 / kDirectMaxTokens) {
+        const int i = tid % kDirectMaxTokens;
+        if (i < count[e]) plan_file_pair(ps, blk0, e, count[e], i, perm[offs[e] + i] & 0xffff, ws);
+    }
 }
 
 // y[t] = sum_j gate[t,j] * o[t*k+j] + sum_s o[P + s*T + t].  If a workgroup of the expert kernel gave up a bounded wait
@@ -1307,8 +1329,8 @@ static int launch_padded(const FfnParams &fp, unsigned blocks, hipStream_t st)
     constexpr int kWgPerCu = (BIG || WF != 0) ? 2 : kWgPerCuSmall;
     constexpr int kLdsTargetPerWg = kWgPerCu == 2 ? 56 * 1024 : kLdsPerCu / kWgPerCu / 1024 * 1024;   // (at most 64 KiB per workgroup)
     static_assert(kLdsTargetPerWg * (kWgPerCu + 1) > kLdsPerCu && kLdsTargetPerWg * kWgPerCu <= kLdsPerCu, "LDS pad");
-    // what the kernel declares itself: the stage, the two token tables and the item record
-    constexpr int kStatic = (BIG ? kStageBytesBig : kStageBytes) + 2 * 4 * (BIG ? kTokBlockBig : kTokBlock) + (int)sizeof(ItemShared);
+    // what the kernel declares itself: the stage and the two token tables
+    constexpr int kStatic = (BIG ? kStageBytesBig : kStageBytes) + 2 * 4 * (BIG ? kTokBlockBig : kTokBlock) ;
     constexpr int pad = kLdsTargetPerWg > kStatic ? kLdsTargetPerWg - kStatic : 0;
     static_assert((kStatic + pad) * kWgPerCu <= kLdsPerCu, "the workgroups must fit a CU");
     hipLaunchKernelGGL((ffn_kernel<KWD, BIG, WF>), dim3(blocks), dim3(kFfnThreads), pad, st, fp);
@@ -1329,6 +1351,7 @@ static int launch_ffn(FfnParams fp, const FfnShape &sh, hipStream_t st)
     const GemmParams &d = fp.dn;
     set_tiles(fp.gu, sh.plan.units_gu, 16 * kFfnWaves, sh.plan.units_gu * sh.max_blocks);   // gate/up: four row tiles per workgroup
     set_tiles(fp.dn, sh.plan.units_dn, 16 * (kFfnWaves / sh.kwd) * 2, plan_down_grid(sh.plan, sh.max_blocks));
+    fp.gu.dn_m_max = fp.dn.dn_m_max = sh.plan.dn_m_max;
     // the split of the last round needs up to three more workgroups per workgroup it replaces
     // (not for batches of more than 32 tokens: more and more experts are then on the staged path, whose unit is the
     // whole workgroup of four row tiles, and three of the four small workgroups only find out that they leave;
@@ -1486,7 +1509,7 @@ int moe_ffn_impl(const uint16_t *x_bf16, const uint16_t *Wgu_packed, const uint1
     hipStream_t st = (hipStream_t)stream;
     const FfnShape shape = ffn_shape(T, H, F, N, k, n_shared, q8 ? q8->format : 0);
     if (!plan_ready) {
-        hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(256), 0, st, expert_offsets, N, T * k, shape.plan, rws);
+        hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(256), 0, st, expert_offsets, perm, N, T * k, shape.plan, rws);
         rc = check_launch("lynx_moe_ffn(plan)");
         if (rc != LYNX_OK) return rc;
     }

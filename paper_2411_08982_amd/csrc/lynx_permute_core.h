@@ -17,6 +17,7 @@ struct PermuteSharedT {
     int count[LYNX_MAX_N];
     int offs[LYNX_MAX_N + 1];
     int arank[LYNX_MAX_N + 1];
+    int blk0[LYNX_MAX_N];                 // first block of the expert in the FFN's work plan
 };
 typedef PermuteSharedT<LYNX_MAX_T / 32> PermuteShared;
 
@@ -66,7 +67,8 @@ __device__ __forceinline__ void permute_from_bitsets(Shared &sh, const int32_t *
         }
     }
     __syncthreads();
-    build_plan<THREADS>(ps, N, sh.count, sh.offs, ws);
+    build_plan<THREADS>(ps, N, sh.count, sh.offs, sh.blk0, ws);
+    __syncthreads();
     // (the indices are read with device-coherent loads: in the fused kernel another workgroup of this launch
     // wrote them; such loads go to memory, so several are requested before the first is used)
     constexpr int kBatch = 8;
@@ -85,6 +87,7 @@ __device__ __forceinline__ void permute_from_bitsets(Shared &sh, const int32_t *
             const int wt = t >> 5;
             const int pos = sh.offs[e] + sh.before[e * W + wt] + __popc(sh.member[e * W + wt] & ((1u << (t & 31)) - 1u));
             perm[pos] = p;   // pos < offs[N] <= P by construction
+            plan_file_pair(ps, sh.blk0, e, sh.count[e], pos - sh.offs[e], p, ws);
         }
     }
     for (int e = tid; e <= N; e += THREADS) expert_offsets[e] = sh.offs[e];

@@ -7,14 +7,15 @@
 // tables in the workspace that the token assignment writes as its last step:
 //   hdr     [0] = B, the number of (expert, token block) pairs of the batch, [1] = units per down-projection work
 //           item, [2] = invoked experts;
-//   prefix  [r] = (expert, token block) pairs of the experts before rank r, r = 0 .. N (entries past the invoked
-//           experts hold B), the invoked experts ranked by ascending id;
-//   rec     [r] = {expert id | tokens << 16, offset of the expert's pairs in the permutation}.
+//   blk     [q] = {expert id | tokens << 16, offset of the expert's pairs in the permutation, token block, 0} for
+//           block q < B, the invoked experts by ascending id, an expert's blocks in a row;
+//   pairs   [q][i], 16 bits each: the (token, slot) pair id of the i-th token of block q, for the blocks of experts
+//           with at most kDirectMaxTokens tokens (entries past the expert's tokens are not written).
 // An expert with at most kDirectMaxTokens tokens is one token block; a larger one is cut into blocks of tok_block tokens
 // (one pass of the staged path each), which go to workgroups of their own.  The work items of a projection are
-// numbered block-major, unit-minor: item = block * units + unit.  A workgroup finds its item with one round trip to
-// memory: every thread looks at one rank's prefix entries, and the one whose range holds the block publishes the
-// record through LDS.
+// numbered block-major, unit-minor: item = block * units + unit, so a workgroup knows from its index alone which
+// records to read, and one round trip to memory tells it its expert, its tokens and where their rows are: nothing
+// it needs for its first weight and token loads depends on a second load.
 #pragma once
 
 #include "lynx_common.h"
@@ -72,17 +73,19 @@ inline int plan_down_grid(const PlanShape &ps, int max_blocks)
     return (int)worst;
 }
 
-// Builds the three tables.  Every thread of the workgroup calls it (one wave does the work); count[e] / offs[e] (pairs
-// of expert e and where they start in the permutation) are in LDS and complete (barrier before).  ws = the routing
-// part of the workspace.  Ranks follow the expert ids.
+// Builds the header and the block records.  Every thread of the workgroup calls it (one wave does the work); count[e] /
+// offs[e] (pairs of expert e and where they start in the permutation) are in LDS and complete (barrier before).
+// blk0[e] (LDS) receives the first block of expert e, for the caller to file the pair ids under (barrier after).
+// ws = the routing part of the workspace.
 template <int THREADS>
-__device__ __forceinline__ void build_plan(const PlanShape &ps, int N, const int *count, const int *offs, int32_t *__restrict__ ws)
+__device__ __forceinline__ void build_plan(const PlanShape &ps, int N, const int *count, const int *offs, int *blk0,
+                                           int32_t *__restrict__ ws)
 {
     if (ps.units_gu <= 0) return;
     const int tid = threadIdx.x;
     if (tid >= kWave) return;
     // exclusive prefixes over the experts in one packed scan: rank among the invoked experts (low half) and token
-    // blocks before (high half; at most LYNX_MAX_N + LYNX_MAX_T * LYNX_MAX_K / 64 < 2^15)
+    // blocks before (high half; at most kPlanMaxBlocks < 2^15)
     int carry_r = 0, carry_b = 0;
     for (int base = 0; base < N; base += kWave) {
         const int e = base + tid;
@@ -90,22 +93,29 @@ __device__ __forceinline__ void build_plan(const PlanShape &ps, int N, const int
         const int a = c > 0 ? 1 : 0;
         const int nb = c > 0 ? plan_token_blocks(c, ps.tok_block) : 0;
         const int s = wave_prefix_sum_i32(a | (nb << 16));
+        if (e < N) blk0[e] = carry_b + (s >> 16) - nb;
         if (a) {
-            const int r = carry_r + (s & 0xffff) - 1;
-            ws[kWsPlanPrefix + r] = carry_b + (s >> 16) - nb;
-            ws[kWsPlanRec + 2 * r] = e | (c << 16);
-            ws[kWsPlanRec + 2 * r + 1] = offs[e];
+            const int q0 = carry_b + (s >> 16) - nb;
+            for (int j = 0; j < nb && q0 + j < kPlanMaxBlocks; ++j)
+                *reinterpret_cast<int4 *>(ws + kWsPlanBlk + 4 * (q0 + j)) = make_int4(e | (c << 16), offs[e], j, 0);
         }
         const int total = __builtin_amdgcn_readlane(s, kWave - 1);
         carry_r += total & 0xffff;
         carry_b += total >> 16;
     }
-    for (int r = carry_r + tid; r <= N; r += kWave) ws[kWsPlanPrefix + r] = carry_b;   // ranks past the invoked experts
     if (tid == 0) {
-        ws[kWsPlanHdr + kPlanB] = carry_b;
+        ws[kWsPlanHdr + kPlanB] = min(carry_b, kPlanMaxBlocks);
         ws[kWsPlanHdr + kPlanM] = plan_down_units_per_item(ps, carry_b);
         ws[kWsPlanHdr + kPlanNa] = carry_r;
     }
+}
+
+// Files pair id p, the i-th of expert e's te pairs, under the expert's block (experts on the direct path only).
+__device__ __forceinline__ void plan_file_pair(const PlanShape &ps, const int *blk0, int e, int te, int i, int p,
+                                               int32_t *__restrict__ ws)
+{
+    if (ps.units_gu <= 0 || te > kDirectMaxTokens) return;
+    reinterpret_cast<uint16_t *>(ws + kWsPlanPairs)[blk0[e] * kDirectMaxTokens + i] = (uint16_t)p;
 }
 
 }  // namespace lynx
