@@ -45,3 +45,21 @@ def pack_reference(W: np.ndarray) -> np.ndarray:
     E, R, K = W.shape
     t = W.reshape(E, R // 16, 16, K // 32, 4, 8)       # e, rt, r, kt, g, i
     return np.ascontiguousarray(t.transpose(0, 1, 3, 4, 2, 5)).reshape(E, R // 16, K // 32, 64, 8)   # lane = g*16 + r
+
+
+def tile_covering_tokens(offsets, perm, k):
+    """Tokens that between them sit in every 16-token column tile of three experts: the fullest one that streams
+    without the LDS stage (at most 16 tokens), the fullest one of 17 to 64 tokens (a 64-token pass) and the fullest
+    one beyond 64 (128-token passes), where the batch has such experts.  A fault tied to a position inside an expert's
+    token range, e.g. one column tile of a pass, cannot hide between random samples."""
+    te = np.diff(offsets)
+    picked = []
+    for lo, hi in ((1, 16), (17, 64), (65, 1 << 30)):
+        cand = np.flatnonzero((te >= lo) & (te <= hi))
+        if cand.size == 0:
+            continue
+        e = int(cand[np.argmax(te[cand])])
+        for tile in range((int(te[e]) + 15) // 16):
+            pos = offsets[e] + min(16 * tile + (5 * tile + 3) % 16, int(te[e]) - 1)   # a different lane in every tile
+            picked.append(int(perm[pos]) // k)
+    return picked

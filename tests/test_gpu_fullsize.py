@@ -16,7 +16,7 @@ import torch
 
 import oracle
 import workloads as wl
-from gpu_util import bf16_bits, dev, host, row_rel_err, to_bf16_dev
+from gpu_util import bf16_bits, dev, host, row_rel_err, tile_covering_tokens, to_bf16_dev
 
 pytestmark = pytest.mark.gpu
 
@@ -108,9 +108,11 @@ def _check_layer(L, lay, T, alpha, beta, enable, n_sample=5, seed=0, sigmoid=Fal
     assert np.all(np.isfinite(y))
     np.testing.assert_allclose(g.sum(1), 1.0, rtol=1e-5)
     assert a["num_active"][1] <= a["num_active"][0]
-    # sampled tokens against the oracle, with only the experts those tokens use copied to the host
+    # sampled tokens against the oracle, with only the experts those tokens use copied to the host: the first and the
+    # last token, some at random, and tokens chosen by where they sit in their expert's sorted range (see below)
     rng = np.random.default_rng(seed)
-    toks = sorted(set([0, T - 1] + rng.choice(T, size=min(T, n_sample), replace=False).tolist()))
+    toks = sorted(set([0, T - 1] + rng.choice(T, size=min(T, n_sample), replace=False).tolist()
+                      + tile_covering_tokens(p["offsets"], p["perm"], cfg.k)))
     sel = a["new_idx"][toks]
     used = np.unique(sel)
     remap = {int(e): i for i, e in enumerate(used)}

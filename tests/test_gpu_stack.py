@@ -13,7 +13,7 @@ import torch
 
 import oracle
 import workloads as wl
-from gpu_util import bf16_bits, dev, host, row_rel_err, to_bf16_dev
+from gpu_util import bf16_bits, dev, host, row_rel_err, tile_covering_tokens, to_bf16_dev
 
 pytestmark = pytest.mark.gpu
 
@@ -167,3 +167,72 @@ def test_graph_replays_reproduce_the_eager_stack(L, T, weights):
         got = st.snapshot()
         for i, (u, v) in enumerate(zip(got, want)):
             assert np.array_equal(u, v), f"replay {rep}: array {i} differs from the eager run"
+
+
+@pytest.mark.timeout(400)
+@pytest.mark.parametrize("T,preset", [(128, "aggressive")])
+def test_full_qwen3_stack_layers_0_24_47(L, T, preset):
+    """The 48-layer Qwen3-shaped stack that bench.py times (58 GB of packed expert weights resident), run once as a
+    chain; layers 0, 24 and 47 are checked like a single full-size layer: routing outputs in full, the layer output
+    on sampled tokens, each with the GPU's own input of that layer fed to the oracle."""
+    cfg = wl.CONFIGS["qwen3"]
+    check = (0, 24, 47)
+    alpha, beta = wl.PRESETS[preset]
+    n_layers = 48
+    print(f"qwen3-shaped stack, {n_layers} layers, T={T}, preset {preset}", flush=True)
+    layers, kept = [], {}
+    for l in range(n_layers):
+        d = wl.make_layer_device(cfg, 1, "cuda", layer=l)
+        Wgu, Wdp = L.lynx_pack_weights(d["Wg"], d["Wu"], d["Wd"])
+        torch.cuda.synchronize()
+        layers.append((d["Wr"], d["bias"], Wgu, Wdp))
+        if l in check:
+            kept[l] = d
+        del d
+        if l % 12 == 11:
+            print(f"  {l + 1} layers resident", flush=True)
+    Wr0, b0 = host(layers[0][0]), host(layers[0][1])
+    xs = [to_bf16_dev(wl.make_tokens(cfg, T, Wr0, b0))]
+    bufs = {}
+    for l, (Wr, bias, Wgu, Wdp) in enumerate(layers):
+        buf = L.LayerBuffers(T, cfg.H, cfg.F, cfg.N, cfg.k, beta, 0, 0) if l in check else bufs.setdefault("scratch", L.LayerBuffers(T, cfg.H, cfg.F, cfg.N, cfg.k, beta, 0, 0))
+        b = L.lynx_moe_layer(xs[l], Wr, bias, Wgu, Wdp, cfg.F, cfg.k, alpha, beta, 1, None, None, 0, 0, buffers=buf)
+        if l in check:
+            bufs[l] = b
+        xs.append(L.lynx_residual_add(xs[l], b.y))
+    torch.cuda.synchronize()
+    for l in check:
+        d, b = kept[l], bufs[l]
+        xb = bf16_bits(xs[l])
+        Wr, bias = host(d["Wr"]), host(d["bias"])
+        z = host(b.logits)
+        r = oracle.route(xb, Wr, bias, cfg.k)
+        # deeper layers see the un-normalised chain's larger token norms: the bound scales with the logit
+        assert np.all(np.abs(z - r["logits"]) <= 1e-5 * np.maximum(1.0, np.abs(r["logits"]))), f"layer {l}: logits"
+        tk = oracle.topk(z, cfg.k)
+        assert np.array_equal(host(b.topk_idx), tk["idx"]), f"layer {l}: top-k"
+        a = oracle.affinity_bin(z, tk["idx"], alpha, beta, 1)
+        for key, got in (("new_idx", b.new_idx), ("cnt_before", b.cnt_before), ("cnt_after", b.cnt_after),
+                         ("bin_hist", b.bin_hist), ("num_active", b.num_active)):
+            assert np.array_equal(host(got), a[key]), f"layer {l}: {key}"
+        np.testing.assert_allclose(host(b.new_gate), a["new_gate"], rtol=1e-5, atol=1e-7)
+        p = oracle.permute(a["new_idx"], cfg.N)
+        for key, got in (("offsets", b.offsets), ("perm", b.perm), ("active", b.active), ("num_active", b.num_active_perm)):
+            assert np.array_equal(host(got), p[key]), f"layer {l}: {key}"
+        assert int(host(b.status)[0]) == 0
+        y = host(b.y)
+        assert np.all(np.isfinite(y))
+        toks = sorted(set([0, T - 1] + tile_covering_tokens(p["offsets"], p["perm"], cfg.k)[:6]))
+        sel = a["new_idx"][toks]
+        used = np.unique(sel)
+        remap = {int(e): i for i, e in enumerate(used)}
+        sel_c = np.vectorize(remap.get)(sel).astype(np.int32)
+        ue = torch.from_numpy(used.astype(np.int64)).cuda()
+        Wg, Wu, Wd = (bf16_bits(d[k_].index_select(0, ue)) for k_ in ("Wg", "Wu", "Wd"))
+        y_ref = oracle.moe_ffn(xb[toks], Wg, Wu, Wd, sel_c, a["new_gate"][toks])
+        err = row_rel_err(y[toks], y_ref).max()
+        assert err <= Y_TOL, f"layer {l}: max row error {err:.3e} on tokens {toks}"
+        assert np.array_equal(bf16_bits(xs[l + 1]), wl.f32_to_bf16_bits(wl.bf16_bits_to_f32(xb) + y)), f"layer {l}: residual"
+        print(f"  layer {l}: experts {a['num_active'].tolist()}, max row error {err:.2e} on tokens {toks}", flush=True)
+    del layers, kept, bufs, xs
+    torch.cuda.empty_cache()
