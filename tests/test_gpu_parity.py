@@ -325,6 +325,12 @@ FFN_CASES = [
     (200, 1024, 128, 64, 8, 0, 0, None),
     (130, 512, 64, 48, 6, 1, 64, 20),
     (48, 768, 96, 100, 10, 0, 0, None),
+    # beyond 64 tokens a down workgroup covers 128 rows and its waves walk two row tiles each: hidden sizes that are
+    # no multiple of 128 (10 and 14 row tiles: the last workgroup of an expert has one and three waves with rows),
+    # direct and staged experts mixed, with and without a shared expert
+    (100, 160, 96, 6, 3, 0, 0, 3),
+    (90, 224, 64, 5, 2, 1, 96, 2),
+    (256, 96, 128, 12, 4, 0, 0, 5),
 ]
 
 
