@@ -1309,7 +1309,7 @@ struct FfnShape {
     PlanShape plan;
 };
 
-static bool single_launch(int T, int F) { return T > kDirectMaxTokens && (F + 63) / 64 <= 64; }
+static bool single_launch(int T, int F) { return T >= 1 && (F + 63) / 64 <= 64; }   // (any batch size: see below)
 
 static FfnShape ffn_shape(int T, int H, int F, int N, int k, int n_shared, int format)
 {
@@ -1374,10 +1374,11 @@ static int launch_padded(const FfnParams &fp, unsigned blocks, hipStream_t st)
 }
 
 // One launch for both projections, or one each (the same kernel over its gate/up and its down workgroups)?
-// Measured over the benchmark configurations: with more than 16 tokens and experts of moderate size the single
-// launch is 3-12 % faster (the down projection fills the tail of gate/up and there is one start-up less); with
-// huge experts (hundreds of gate/up workgroups each, whose completion reports then cost more than the overlap
-// gains) or at most 16 tokens it is equal or slower.
+// Measured over the benchmark configurations: with experts of moderate size the single launch is 3-12 % faster beyond
+// 16 tokens (the down projection fills the tail of gate/up and there is one start-up less) and 0-5 % faster up to 16
+// (DeepSeek-V2-Lite shapes, 16 tokens: 87.6 -> 84.7 us per layer, remap off 150.0 -> 146.5; Qwen1.5-MoE shapes, 8
+// tokens: 81.7 -> 81.7, remap off 92.3 -> 87.5); with huge experts (hundreds of gate/up workgroups each, whose
+// completion reports then cost more than the overlap gains) it is equal or slower at every batch size.
 
 // Gate/up and down over all invoked and shared experts.  Batches of more than 64 tokens take the
 // kernels whose staged path makes passes of up to 128 tokens.
