@@ -90,7 +90,9 @@ def make_router(cfg: MoEConfig, seed: int | None = None, layer: int = 0):
 def make_tokens(cfg: MoEConfig, T: int, Wr=None, bias=None, seed: int | None = None, layer: int = 0) -> np.ndarray:
     """Hidden states [T,H] as bf16 bits.  For configs with a low-affinity tail, a seeded fraction of the
     tokens is shifted inside the row space of the router so that their logits come out near-uniform
-    (N(0, 0.02^2) around 0)."""
+    (N(0, 0.02^2) around 0).  This shapes an input: it solves a linear system in Wr for a prescribed router response
+    (numpy's matmul and solve); no expected value of any test comes from it, and neither the oracle nor the kernels
+    use it."""
     rng = np.random.default_rng([cfg.seed if seed is None else seed, layer, 22, T])
     x = rng.standard_normal((T, cfg.H), dtype=np.float32)
     if cfg.tail_frac > 0 and T > 0 and Wr is not None:
